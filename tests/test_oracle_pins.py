@@ -1,0 +1,391 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Each test is chosen so that a plausible slip in oracle/ (a dropped term, a wrong
+index order, a transposed operand, a wrong sign in the bound) fails it.
+"""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import naive_c
+from oracle import rbgp_oracle as orc
+from paper_2006_13486_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return json.load(f)
+
+
+# ---------------------------------------------------------------- random source
+def test_splitmix64_published_vectors():
+    g = _gold("splitmix64_vectors.json")
+    s = orc.CoinStream.__new__(orc.CoinStream)
+    s.key, s.n = g["state"], 0
+    assert [s.draw() for _ in g["outputs"]] == g["outputs"]
+
+
+def test_coin_streams_differ_by_factor_and_attempt():
+    a = [orc.CoinStream(7, 0, 0).coin() for _ in range(1)]
+    seqs = {}
+    for f, t in itertools.product(range(3), range(3)):
+        cs = orc.CoinStream(7, f, t)
+        seqs[(f, t)] = tuple(cs.coin() for _ in range(64))
+    assert len(set(seqs.values())) == 9
+    allbits = np.array([b for s in seqs.values() for b in s])
+    assert 0.35 < allbits.mean() < 0.65
+
+
+# ---------------------------------------------------------------- 2-lift (Appendix)
+@pytest.mark.parametrize("a,c", [(1, 2), (2, 2), (3, 5), (4, 8)])
+def test_two_lift_invariants(a, c):
+    rng = np.random.default_rng(a * 100 + c)
+    B = (rng.random((a, c)) < 0.6).astype(np.uint8)
+    L = orc.two_lift(B, orc.CoinStream(5, 0, 0))
+    assert L.shape == (2 * a, 2 * c)                       # vertices double
+    assert L.sum() == 2 * B.sum()                          # edges double
+    # every vertex and its clone keep the degree of the original vertex
+    assert np.array_equal(L.sum(1), np.concatenate([B.sum(1), B.sum(1)]))
+    assert np.array_equal(L.sum(0), np.concatenate([B.sum(0), B.sum(0)]))
+    # each edge became the identity pair or the crossover pair, never both
+    assert np.array_equal(L[:a, :c] + L[:a, c:], B)
+    assert np.array_equal(L[:a, :c], L[a:, c:])
+    assert np.array_equal(L[:a, c:], L[a:, :c])
+
+
+def test_two_lift_coin_order_is_row_major():
+    """Edge (u,v) consumes coin number rank(u,v) in row-major order."""
+    B = np.array([[1, 0, 1], [0, 1, 1]], dtype=np.uint8)
+    cs = orc.CoinStream(9, 1, 0)
+    coins = [orc.CoinStream(9, 1, 0) for _ in range(1)][0]
+    bits = [coins.coin() for _ in range(4)]
+    L = orc.two_lift(B, cs)
+    edges = [(0, 0), (0, 2), (1, 1), (1, 2)]
+    for bit, (u, v) in zip(bits, edges):
+        assert L[u, v + 3] == bit and L[u, v] == 1 - bit
+
+
+@pytest.mark.parametrize("a,c,d", [(16, 16, 8), (4, 8, 2), (8, 8, 4), (4, 8, 4), (8, 8, 2), (4, 4, 2),
+                                    (32, 128, 16), (32, 32, 4)])
+def test_sample_biregular_degrees(a, c, d):
+    B = orc.sample_biregular(a, c, d, orc.CoinStream(3, 0, 0))
+    assert B.shape == (a, c)
+    assert np.all(B.sum(1) == d)
+    assert np.all(B.sum(0) == a * d // c)
+
+
+def test_num_lifts_rejects_non_power_of_two():
+    assert orc.num_lifts(8, 2) == 2
+    with pytest.raises(ValueError):
+        orc.num_lifts(9, 3)
+    with pytest.raises(ValueError):
+        orc.num_lifts(8, 3)
+
+
+# ---------------------------------------------------------------- spectrum (Section 3)
+def test_singular_values_closed_forms():
+    # complete a x c: one singular value sqrt(a c)
+    s = orc.singular_values(np.ones((4, 9), dtype=np.uint8))
+    assert np.allclose(s, [6, 0, 0, 0], atol=1e-12)
+    # 8-cycle as a 4x4 2-regular bipartite graph: 2, sqrt2, sqrt2, 0
+    C8 = np.array([[1, 1, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [1, 0, 0, 1]], dtype=np.uint8)
+    assert np.allclose(orc.singular_values(C8), [2, math.sqrt(2), math.sqrt(2), 0], atol=1e-12)
+    # two disjoint 4-cycles: 2, 2, 0, 0
+    CC = np.array([[1, 1, 0, 0], [1, 1, 0, 0], [0, 0, 1, 1], [0, 0, 1, 1]], dtype=np.uint8)
+    assert np.allclose(orc.singular_values(CC), [2, 2, 0, 0], atol=1e-12)
+    # forest of four stars K_{1,2} (4x8, degrees 2 and 1): sqrt2 four times
+    SF = np.kron(np.eye(4, dtype=np.uint8), np.ones((1, 2), dtype=np.uint8))
+    assert np.allclose(orc.singular_values(SF), [math.sqrt(2)] * 4, atol=1e-12)
+
+
+def test_ramanujan_bound_formula():
+    assert orc.ramanujan_bound(8, 8) == pytest.approx(2 * math.sqrt(7))
+    assert orc.ramanujan_bound(2, 1) == pytest.approx(1.0)
+    assert orc.ramanujan_bound(4, 2) == pytest.approx(math.sqrt(3) + 1)
+
+
+def test_petersen_like_known_ramanujan_and_known_failure():
+    """Heawood graph (incidence of the Fano plane) is (3,3)-biregular with
+    sigma_2 = sqrt2 <= 2 sqrt2: Ramanujan.  Two disjoint K_{3,3} are
+    3-regular with sigma_2 = 3 > 2 sqrt2: not Ramanujan."""
+    lines = [(0, 1, 2), (0, 3, 4), (0, 5, 6), (1, 3, 5), (1, 4, 6), (2, 3, 6), (2, 4, 5)]
+    H = np.zeros((7, 7), dtype=np.uint8)
+    for i, ln in enumerate(lines):
+        H[i, list(ln)] = 1
+    assert orc.second_singular(H) == pytest.approx(math.sqrt(2))
+    assert orc.second_singular(H) <= orc.ramanujan_bound(3, 3)
+    D = np.kron(np.eye(2, dtype=np.uint8), np.ones((3, 3), dtype=np.uint8))
+    assert orc.second_singular(D) == pytest.approx(3.0)
+    assert orc.second_singular(D) > orc.ramanujan_bound(3, 3)
+
+
+@pytest.mark.parametrize("w", wl.CONFIGS, ids=lambda w: w.name)
+def test_sampled_factors_meet_bound(w):
+    Bs, infos = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    for i, (B, info) in enumerate(zip(Bs, infos)):
+        a, c, d = w.rows[i], w.cols[i], w.row_deg[i]
+        e = a * d // c
+        assert np.all(B.sum(1) == d) and np.all(B.sum(0) == e)
+        if d == c:
+            assert info["status"] == orc.STATUS_COMPLETE and np.all(B == 1)
+        elif min(d, e) == 1:
+            # column degree 1 forces a star forest: sigma_2 = sigma_1 > bound
+            assert info["status"] == orc.STATUS_DEGENERATE
+            assert info["sigma2"] == pytest.approx(info["sigma1"])
+            assert info["sigma2"] > info["bound"]
+        else:
+            assert info["status"] == orc.STATUS_OK
+            assert info["sigma1"] == pytest.approx(math.sqrt(d * e))
+            assert info["sigma2"] <= info["bound"] * (1 + 1e-9)
+            assert info["sigma2"] == pytest.approx(np.linalg.svd(B.astype(float), compute_uv=False)[1])
+
+
+def test_rejection_loop_skips_non_ramanujan_samples():
+    """A 16x16 degree-8 factor is rejected sometimes; the accepted attempt is
+    the first whose sigma_2 meets the bound."""
+    seen_reject = False
+    for seed in range(40):
+        B, info = orc.sample_factor(32, 32, 4, seed, 0)
+        for t in range(info["tries"] - 1):
+            Bt = orc.sample_biregular(32, 32, 4, orc.CoinStream(seed, 0, t))
+            assert orc.second_singular(Bt) > info["bound"]
+            seen_reject = True
+        Bt = orc.sample_biregular(32, 32, 4, orc.CoinStream(seed, 0, info["tries"] - 1))
+        assert np.array_equal(Bt, B)
+    assert seen_reject
+
+
+# ---------------------------------------------------------------- mask (Sections 3-5)
+def _factors(w):
+    return orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)[0]
+
+
+@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV3_BF16, wl.WRN_G1], ids=lambda w: w.name)
+def test_kron_mask_equals_numpy_kron(w):
+    Bs = _factors(w)
+    ref = Bs[0]
+    for B in Bs[1:]:
+        ref = np.kron(ref, B)
+    mask = orc.kron_mask(Bs)
+    assert mask.shape == (w.M, w.K)
+    assert np.array_equal(mask, ref)
+
+
+def test_kron_mask_is_not_commutative_pin():
+    """Order of factors matters: last factor is the innermost block."""
+    A = np.array([[1, 0], [0, 1]], dtype=np.uint8)
+    B = np.array([[1, 1]], dtype=np.uint8)
+    m = orc.kron_mask([A, B])
+    assert np.array_equal(m, np.array([[1, 1, 0, 0], [0, 0, 1, 1]], dtype=np.uint8))
+
+
+@pytest.mark.parametrize("w", wl.CONFIGS, ids=lambda w: w.name)
+def test_mask_density_and_degrees_are_products(w):
+    if w.M * w.K > 4_000_000:
+        pytest.skip("dense mask too large for this pin")
+    mask = orc.kron_mask(_factors(w))
+    dens = np.prod([d / c for d, c in zip(w.row_deg, w.cols)])
+    assert mask.mean() == pytest.approx(dens)
+    assert np.all(mask.sum(1) == np.prod(w.row_deg))
+    coldeg = np.prod([a * d // c for a, d, c in zip(w.rows, w.row_deg, w.cols)])
+    assert np.all(mask.sum(0) == coldeg)
+
+
+def test_conv5_mask_density_and_degrees():
+    w = wl.VGG19_CONV5
+    mask = orc.kron_mask(_factors(w))
+    assert mask.mean() == pytest.approx(1 / 8)
+    assert np.all(mask.sum(1) == 576) and np.all(mask.sum(0) == 64)
+
+
+def _is_cubs(mask, bh, bw):
+    M, K = mask.shape
+    blocks = mask.reshape(M // bh, bh, K // bw, bw).transpose(0, 2, 1, 3)
+    nz = blocks.reshape(M // bh, K // bw, -1).any(-1)
+    if not (len(set(nz.sum(1))) == 1 and len(set(nz.sum(0))) == 1):
+        return False                                        # uniform
+    pats = blocks[nz]
+    return bool(np.all(pats == pats[0]))                    # cloned
+
+
+@pytest.mark.parametrize("w", [wl.TINY, wl.WRN_G1, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
+def test_mask_is_rcubs_at_every_block_level(w):
+    """Section 4: block sizes B_j = (prod_{i>j}|G_i.U|, prod_{i>j}|G_i.V|)."""
+    mask = orc.kron_mask(_factors(w))
+    for j in range(1, 4):
+        bh = int(np.prod(w.rows[j:]))
+        bw = int(np.prod(w.cols[j:]))
+        assert _is_cubs(mask, bh, bw)
+
+
+def test_paper_worked_examples():
+    g = _gold("paper_worked_examples.json")
+    # Section 4, memory efficiency: 8*2*8*4 = 512 edges stored as 8+2+8+4 = 22
+    rows, cols, deg = (4, 2, 4, 2), (4, 2, 4, 2), (2, 1, 2, 2)
+    Bs, _ = orc.sample_factors(rows, cols, deg, 5)
+    edges = [int(B.sum()) for B in Bs]
+    assert edges == g["memory_efficiency"]["factor_edges"]
+    mask = orc.kron_mask(Bs)
+    assert int(mask.sum()) == g["memory_efficiency"]["product_edges"]
+    assert sum(edges) == g["memory_efficiency"]["stored_edges"]
+    assert int(mask.sum()) // sum(edges) == g["memory_efficiency"]["ratio_floor"]
+    # the same example's block levels (16,16), (8,8), (2,2)
+    for bh, bw in g["block_levels_example"]["levels"]:
+        assert _is_cubs(mask, bh, bw)
+    # Section 6: two factorings give W_s of size (64,16)
+    for ex in g["size_examples"]:
+        r = [s[0] for s in ex["sizes"]]
+        c = [s[1] for s in ex["sizes"]]
+        Bs = [np.ones((a, b), dtype=np.uint8) for a, b in zip(r, c)]
+        assert list(orc.kron_mask(Bs).shape) == ex["W_shape"]
+    # Section 6: (0,75%) and (50%,50%) both give 75 % sparsity
+    for ex in g["sparsity_examples"]:
+        do, di = round(8 * (1 - ex["sp_o"])), round(8 * (1 - ex["sp_i"]))
+        Bs, _ = orc.sample_factors((8, 1, 8, 1), (8, 1, 8, 1), (do, 1, di, 1), 3)
+        assert 1 - orc.kron_mask(Bs).mean() == pytest.approx(ex["sp"])
+
+
+def test_row_repetition_groups():
+    """Section 5: rows sharing (u_o,u_i) have identical nonzero columns; group
+    size |G_r.U|*|G_b.U| (4 in Figure 1's configuration)."""
+    g = _gold("paper_worked_examples.json")["figure1"]
+    rows, cols = (4, g["G_r"][0], 4, g["G_b"][0]), (4, g["G_r"][1], 4, g["G_b"][1])
+    deg = (2, g["G_r"][1], 2, g["G_b"][1])
+    Bs, _ = orc.sample_factors(rows, cols, deg, 8)
+    mask = orc.kron_mask(Bs)
+    a1, a2, a3, a4 = rows
+    groups = {}
+    for m in range(mask.shape[0]):
+        u4 = m % a4
+        u3 = (m // a4) % a3
+        u1 = m // (a4 * a3 * a2)
+        groups.setdefault((u1, u3), []).append(mask[m].tobytes())
+    for pats in groups.values():
+        assert len(pats) == g["row_repetition"] and len(set(pats)) == 1
+    # tile (0, first nonzero tile): rows 0,1,4,5 of the 8-row... pattern shared by u_r in {0,1}, u_b in {0,1}
+    assert len({tuple(sorted(set(v))) for v in groups.values()}) > 1
+
+
+def test_product_spectrum_is_product_of_factor_spectra():
+    """Proof of Theorem 1: singular values of the product are the products."""
+    w = wl.TINY
+    Bs = _factors(w)
+    mask = orc.kron_mask(Bs)
+    prod = np.array([1.0])
+    for B in Bs:
+        prod = np.outer(prod, orc.singular_values(B)).ravel()
+    prod = np.sort(prod)[::-1]
+    assert np.allclose(orc.singular_values(mask), prod, atol=1e-9)
+    s1 = np.prod([math.sqrt(d * (a * d // c)) for a, c, d in zip(w.rows, w.cols, w.row_deg)])
+    assert orc.singular_values(mask)[0] == pytest.approx(s1)
+
+
+@pytest.mark.parametrize("w", [wl.TINY, wl.WRN_G1, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
+def test_canonical_order_is_algorithm1_indexing(w):
+    """Algorithm 1 addresses data[row][((outk*RK + rk)*d_i + ink)*BK + bk]; the
+    column it multiplies with is ((adj_o[outk]*RK + rk)*|G_i.V| + adj_i[ink])*BK + bk."""
+    Bs = _factors(w)
+    adj = [orc.adjacency_lists(B) for B in Bs]
+    cols = orc.canonical_columns(orc.kron_mask(Bs))
+    a, c, d = w.rows, w.cols, w.row_deg
+    rng = np.random.default_rng(0)
+    for m in rng.integers(0, w.M, size=12):
+        u4 = m % a[3]; u3 = (m // a[3]) % a[2]; u2 = (m // (a[3] * a[2])) % a[1]; u1 = m // (a[3] * a[2] * a[1])
+        t = 0
+        for j1 in range(d[0]):
+            for j2 in range(d[1]):
+                for j3 in range(d[2]):
+                    for j4 in range(d[3]):
+                        k = ((adj[0][u1][j1] * c[1] + adj[1][u2][j2]) * c[2] + adj[2][u3][j3]) * c[3] + adj[3][u4][j4]
+                        assert cols[m][t] == k
+                        t += 1
+
+
+# ---------------------------------------------------------------- O = W_s x I
+def _tiny_problem(seed=0, N=5):
+    rows, cols, deg = (2, 2, 2, 1), (2, 1, 4, 3), (1, 1, 2, 3)
+    Bs, _ = orc.sample_factors(rows, cols, deg, seed)
+    mask = orc.kron_mask(Bs)
+    rng = np.random.default_rng(seed)
+    vals = rng.standard_normal((mask.shape[0], int(mask[0].sum()))).astype(np.float32)
+    I = rng.standard_normal((mask.shape[1], N)).astype(np.float32)
+    return mask, vals, I
+
+
+def test_spmm_equals_dense_matmul_with_explicit_zeros():
+    mask, vals, I = _tiny_problem()
+    W = orc.scatter_values(mask, vals)
+    assert np.count_nonzero(W) == mask.sum() and np.all(W[mask == 0] == 0)
+    ref = W.astype(np.float64) @ I.astype(np.float64)
+    assert np.allclose(orc.spmm_definition(mask, W, I), ref, rtol=1e-13, atol=1e-13)
+    assert np.allclose(orc.spmm_bruteforce_scalar(mask, W, I), ref, rtol=1e-13, atol=1e-13)
+    # a value parked outside the mask must not contribute
+    W2 = W.copy()
+    W2[mask == 0] = 7.0
+    assert np.allclose(orc.spmm_definition(mask, W2, I), ref, rtol=1e-13, atol=1e-13)
+
+
+def test_scatter_values_row_order():
+    mask, vals, _ = _tiny_problem(3)
+    W = orc.scatter_values(mask, vals)
+    for m in range(mask.shape[0]):
+        assert np.array_equal(W[m][mask[m] == 1], vals[m])      # ascending columns
+
+
+def test_naive_c_matches_definition_and_matmul():
+    for seed in range(3):
+        mask, vals, I = _tiny_problem(seed, N=7)
+        W = orc.scatter_values(mask, vals)
+        ref = W.astype(np.float64) @ I.astype(np.float64)
+        assert np.allclose(naive_c.spmm(mask, W, I), ref, rtol=1e-13, atol=1e-13)
+        W2 = W.copy()
+        W2[mask == 0] = -3.0
+        assert np.allclose(naive_c.spmm(mask, W2, I), ref, rtol=1e-13, atol=1e-13)
+        assert np.allclose(naive_c.spmm_abs(mask, W, I), np.abs(W).astype(np.float64) @ np.abs(I), rtol=1e-13)
+    assert naive_c.threads() >= 1
+
+
+def test_all_complete_factors_reduce_to_dense_gemm():
+    Bs, infos = orc.sample_factors((2, 2, 2, 2), (1, 3, 2, 2), (1, 3, 2, 2), 1)
+    assert all(i["status"] == orc.STATUS_COMPLETE for i in infos)
+    mask = orc.kron_mask(Bs)
+    assert np.all(mask == 1)
+    rng = np.random.default_rng(1)
+    vals = rng.standard_normal(mask.shape).astype(np.float32)
+    I = rng.standard_normal((mask.shape[1], 9)).astype(np.float32)
+    W = orc.scatter_values(mask, vals)
+    assert np.array_equal(W, vals)
+    assert np.allclose(naive_c.spmm(mask, W, I), np.matmul(vals.astype(np.float64), I.astype(np.float64)))
+
+
+def test_tiny_config_naive_c_vs_definition():
+    w = wl.TINY
+    mask = orc.kron_mask(_factors(w))
+    W = orc.scatter_values(mask, wl.kept_weights(w))
+    I = wl.activations(w, 16)
+    assert np.allclose(naive_c.spmm(mask, W, I), orc.spmm_definition(mask, W, I), rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- bf16 rounding
+def test_bf16_rounding_matches_torch_and_ties_to_even():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(4096).astype(np.float32) * 0.02,
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, -1e-40, np.inf], np.float32)])
+    assert np.array_equal(orc.f32_to_bf16_bits(x), wl.to_bf16_bits(x))
+    # 1 + 2^-8 is a tie between 1.0 and 1+2^-7: goes to even (1.0); 1 + 3*2^-8 ties up to 1+2^-6
+    assert orc.bf16_bits_to_f32(orc.f32_to_bf16_bits(np.array([1.00390625], np.float32)))[0] == 1.0
+    assert orc.bf16_bits_to_f32(orc.f32_to_bf16_bits(np.array([1.01171875], np.float32)))[0] == 1.015625
+    assert np.array_equal(orc.bf16_bits_to_f32(wl.to_bf16_bits(x)), wl.bf16_bits_as_f32(wl.to_bf16_bits(x)))
+
+
+def test_normalised_error_metric():
+    ref = np.array([[1.0, 0.0]])
+    den = np.array([[2.0, 0.0]])
+    assert orc.normalised_error(np.array([[1.5, 0.0]]), ref, den) == pytest.approx(0.25)
+    assert orc.normalised_error(np.array([[1.0, 1e-30]]), ref, den) == math.inf
