@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the RBGP4 sparse x dense product on one MI355X.
+
+One "step" is one pass of the whole hot path (tile walk, W and I staging, inner
+walk, dense-block MACs, epilogue = one rbgp_spmm call) over one batch of
+synthetic input that is already resident in HBM.  Steps rotate over several
+distinct (I, O) buffer sets so that the working set exceeds the 256 MB
+Infinity Cache and the rate is not a cache-resident one (`--sets 1` gives the
+hot-cache rate).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2006_13486_amd import binding as rb      # noqa: E402
+from paper_2006_13486_amd import workloads as wl    # noqa: E402
+
+PEAK_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix (= packed vector) peak
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+WORKLOADS = {"conv5": wl.VGG19_CONV5, "conv3": wl.VGG19_CONV3_BF16, "wrn": wl.WRN_G1, "tiny": wl.TINY}
+# which roofline bounds each workload (arithmetic intensity vs the fp32 / bf16 ridge)
+BOUND = {"conv5": "mfma", "conv3": "hbm", "wrn": "hbm", "tiny": "hbm"}
+
+
+def cpu_baseline(w, vals_f32, I_f32, out_gpu):
+    """Time the oracle's naive masked triple loop on the host cores and use its
+    result to check the GPU output of the same inputs."""
+    from oracle import naive_c
+    from oracle import rbgp_oracle as orc
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = orc.kron_mask(Bs)
+    W = orc.scatter_values(mask, vals_f32)
+    # bounded sample: at most ~2^31 multiply-adds, taken as the leading columns of I
+    ncols = int(min(w.N, max(64, (1 << 31) // max(w.nnz, 1))))
+    Is = np.ascontiguousarray(I_f32[:, :ncols])
+    naive_c.spmm(mask, W, Is[:, :64])       # warm-up (threads, page faults)
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        ref = naive_c.spmm(mask, W, Is)
+        best = min(best, time.perf_counter() - t0)
+    den = naive_c.spmm_abs(mask, W, Is)
+    err = orc.normalised_error(out_gpu[:, :ncols], ref, den)
+    return {"value": 2.0 * w.nnz * ncols / best / 1e12, "unit": "TFLOP/s", "cores": naive_c.threads(),
+            "kind": "oracle", "sample": f"first {ncols} of {w.N} columns, best of 3, {best * 1e3:.1f} ms",
+            "parity_err": err}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="conv5", choices=sorted(WORKLOADS))
+    ap.add_argument("--sets", type=int, default=0, help="distinct (I,O) buffer sets to rotate over (0 = auto)")
+    ap.add_argument("--tune", default="", help="cols_per_lane,cols_per_workgroup,groups_per_workgroup")
+    ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (sharding along N is described in DESIGN.md); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    w = WORKLOADS[args.workload]
+    bf16 = w.dtype == wl.BF16
+
+    vals = wl.kept_weights(w)
+    I = wl.activations(w)
+    if bf16:
+        vals_lib, I_lib = wl.to_bf16_bits(vals), wl.to_bf16_bits(I)
+        vals_f32, I_f32 = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(I_lib)
+    else:
+        vals_lib, I_lib, vals_f32, I_f32 = vals, I, vals, I
+
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    if args.kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mask, args.kernel)
+    if args.tune:
+        rb.rbgp_mask_tune(mask, *[int(x) for x in args.tune.split(",")])
+    stream = torch.cuda.current_stream().cuda_stream
+    packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device=dev)
+    rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
+
+    set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
+    nsets = args.sets if args.sets > 0 else max(2, min(16, -(-512 * 2**20 // set_bytes)))
+    I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
+    Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
+    Os = [torch.empty((w.M, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+    def step(i):
+        j = i % nsets
+        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
+                     Os[j].data_ptr(), w.N, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                              # same stream as the launches (torch's current stream)
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+
+    value = w.flops / (ms_per_step * 1e-3) / 1e12
+    bound = BOUND[args.workload]
+    if bound == "mfma":
+        achieved = w.flops / (kern_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_F32_TFLOPS, "traffic": None}
+    else:
+        achieved = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roof["kernel_ms"] = kern_ms
+    roof["algorithmic_bytes"] = w.algorithmic_bytes
+    roof["algorithmic_flops"] = w.flops
+
+    out = {"metric": "effective TFLOP/s (2*nnz*N) RBGP4 SpMM", "value": value, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+           "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "density": w.density,
+                      "factors_rows": list(w.rows), "factors_cols": list(w.cols), "factors_row_deg": list(w.row_deg),
+                      "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "tune": args.tune or "default",
+                      "buffer_sets": nsets},
+           "roofline": roof}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, Os[0].cpu().numpy())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,156 @@
+/* rbgp.h -- C ABI of the MI355X (gfx950) RBGP4 sparse x dense product library.
+ *
+ * The library computes O = W_s x I, where the mask of W_s is the bipartite
+ * graph product G_o (x) G_r (x) G_i (x) G_b of four biregular bipartite graphs
+ * (Section 5, "RBGP4 sparsity pattern"): G_o and G_i sparse Ramanujan graphs,
+ * G_r and G_b complete.  By Section 3 the biadjacency matrix of the product is
+ * the Kronecker product of the factors' biadjacency matrices.  The mask is held
+ * as the factors' adjacency lists only (Section 4, "Memory efficiency").
+ *
+ * Notation.  Factor i (0..3 = G_o, G_r, G_i, G_b) has rows[i] left vertices,
+ * cols[i] right vertices and left degree row_deg[i]; its right degree is
+ * rows[i]*row_deg[i]/cols[i].  M = prod rows, K = prod cols, rowdeg = prod
+ * row_deg, nnz = M*rowdeg.  Row m = ((u0*rows[1]+u1)*rows[2]+u2)*rows[3]+u3
+ * and column k = ((v0*cols[1]+v1)*cols[2]+v2)*cols[3]+v3 (last factor fastest).
+ *
+ * Canonical value order (the `data[rows][(1-sp)*cols]` array of the Appendix,
+ * indexed as Algorithm 1 does): the kept values of row m are stored
+ * contiguously, position t = ((j0*row_deg[1]+j1)*row_deg[2]+j2)*row_deg[3]+j3
+ * holding column ((adj0[u0][j0]*cols[1]+adj1[u1][j1])*cols[2]+adj2[u2][j2])*cols[3]+adj3[u3][j3].
+ * Adjacency lists ascend, so this is ascending-column order.
+ *
+ * Conventions.  Every function returns RBGP_OK (0) or a negative error code and
+ * leaves its outputs untouched on error; no C++ exception crosses the boundary.
+ * "host" pointers are ordinary process memory, "device" pointers are HIP device
+ * memory of the current device.  The library never allocates or frees a buffer
+ * the caller passes; it keeps small device-side copies of its own index tables
+ * inside the mask object (created on first use on the current device, released
+ * by rbgp_mask_free).  `hip_stream` is a hipStream_t passed as void* (NULL = the
+ * default stream); device work is enqueued on it asynchronously unless stated.
+ * One GPU: a mask object is bound to the device that is current on first use.
+ * A mask object may be used from one host thread at a time.
+ */
+#ifndef RBGP_H_
+#define RBGP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rbgp_mask rbgp_mask_t; /* opaque, host memory */
+
+/* RBGP_F32: W, I fp32; RBGP_BF16_F32ACC: W, I bfloat16, fp32 accumulation.  O is fp32 in both. */
+typedef enum { RBGP_F32 = 0, RBGP_BF16_F32ACC = 1 } rbgp_dtype_t;
+
+enum {
+  RBGP_OK = 0,
+  RBGP_EINVAL = -1,        /* null pointer, non-positive size, density not 1/2^L, ... */
+  RBGP_ENOMEM = -2,
+  RBGP_ENOTRAMANUJAN = -3, /* no sample met the bound within max_tries */
+  RBGP_ESHAPE = -4,        /* M, K, ld* do not match the mask */
+  RBGP_EHIP = -5,          /* a HIP call failed (message via rbgp_last_hip_error) */
+  RBGP_EUNSUPPORTED = -6   /* requested kernel cannot run this mask / dtype */
+};
+
+/* per-factor result of the spectral test */
+enum { RBGP_SPEC_OK = 0, RBGP_SPEC_COMPLETE = 1, RBGP_SPEC_DEGENERATE = 2 };
+
+/* kernel families */
+enum { RBGP_KERNEL_AUTO = 0, RBGP_KERNEL_GENERIC = 1, RBGP_KERNEL_MFMA = 2 };
+
+/* Sample the four base graphs and build the mask (host only, no GPU call).
+ * Appendix "Ramanujan Bipartite Graph Generation": a factor with row_deg < cols
+ * is produced by L = log2(cols/row_deg) random 2-lifts of the complete bipartite
+ * graph on (rows/2^L, cols/2^L) vertices and resampled until its second largest
+ * singular value is <= sqrt(d_l-1)+sqrt(d_r-1) (Section 3), at most max_tries
+ * times (<= 0 means 1000).  row_deg == cols means a complete factor.  A sparse
+ * factor whose smaller degree is 1 cannot meet the bound; its first sample is
+ * kept and reported RBGP_SPEC_DEGENERATE.  The random source is the counter
+ * based SplitMix64 stream keyed by (seed, factor, attempt); equal arguments give
+ * byte-identical masks.  *out is owned by the caller (rbgp_mask_free).
+ * Errors: EINVAL (null, size <= 0, cols/row_deg not a power of two, rows not
+ * divisible by it, M or K above 2^24), ENOTRAMANUJAN, ENOMEM. */
+int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t row_deg[4],
+                   uint64_t seed, int32_t max_tries, rbgp_mask_t **out);
+
+/* Release the mask and its device tables.  NULL is allowed. */
+void rbgp_mask_free(rbgp_mask_t *mask);
+
+/* Sizes of the product (any output pointer may be NULL). */
+int rbgp_mask_shape(const rbgp_mask_t *mask, int64_t *M, int64_t *K, int64_t *rowdeg,
+                    int64_t *coldeg, int64_t *nnz);
+
+/* Factor i: sizes, left degree and a borrowed pointer to its adjacency list
+ * (host, rows*deg int32, row-major, ascending per row; valid until mask_free). */
+int rbgp_mask_factor(const rbgp_mask_t *mask, int i, int32_t *rows, int32_t *cols, int32_t *deg,
+                     const int32_t **adj);
+
+/* Spectral data of factor i: two largest singular values of its biadjacency
+ * matrix (= lambda_1, lambda_2 of the graph), the Ramanujan bound, the status
+ * (RBGP_SPEC_*) and the number of samples drawn (0 for a complete factor). */
+int rbgp_mask_spectrum(const rbgp_mask_t *mask, int i, double *sigma1, double *sigma2,
+                       double *bound, int *status, int *tries);
+
+/* Column of every kept value in canonical order: out is caller-owned host
+ * memory of M*rowdeg int32. */
+int rbgp_mask_columns(const rbgp_mask_t *mask, int32_t *out);
+
+/* Dense 0/1 mask, caller-owned host memory of M*K bytes (for tests). */
+int rbgp_mask_dense(const rbgp_mask_t *mask, uint8_t *out);
+
+/* Choose the kernel family used by rbgp_packed_bytes / rbgp_pack / rbgp_spmm for
+ * this mask: AUTO (default; MFMA when the mask's shape is covered, else GENERIC),
+ * GENERIC (plain FMA kernel, any mask) or MFMA (EUNSUPPORTED if not covered).
+ * Changing it invalidates buffers packed before the change. */
+int rbgp_mask_set_kernel(rbgp_mask_t *mask, int kernel);
+
+/* Kernel family (RBGP_KERNEL_GENERIC or RBGP_KERNEL_MFMA) that would run. */
+int rbgp_mask_kernel(const rbgp_mask_t *mask, rbgp_dtype_t dtype);
+
+/* Tuning knobs of the MFMA family for this mask (0 = library default): columns
+ * per lane (1 or 2), columns per workgroup (64*t*{1,2}), G_i vertices per
+ * workgroup (a divisor of |G_i.U|).  Does not change the packed layout.
+ * rbgp_spmm returns EUNSUPPORTED for a combination that is not built. */
+int rbgp_mask_tune(rbgp_mask_t *mask, int cols_per_lane, int cols_per_workgroup, int groups_per_workgroup);
+
+/* Bytes of the device buffer that rbgp_pack fills (kernel layout incl. padding); 0 on error. */
+size_t rbgp_packed_bytes(const rbgp_mask_t *mask, rbgp_dtype_t dtype);
+
+/* Reorder the kept values from canonical order into the layout the SpMM kernel
+ * reads, which stores the dense |G_r.U||G_b.U| x |G_b.V| blocks of one tile step
+ * contiguously (the compact W tile that Algorithm 1 stages per step).
+ * host_values: M*rowdeg elements of the dtype's input type (float or bf16 bits),
+ * host memory, read before the call returns.  dev_packed: caller-owned device
+ * buffer of rbgp_packed_bytes().  The permutation runs in a HIP kernel on
+ * `hip_stream`; the call synchronises that stream before returning. */
+int rbgp_pack(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *host_values,
+              void *dev_packed, void *hip_stream);
+
+/* Same with the canonical values already in device memory (M*rowdeg elements);
+ * asynchronous on `hip_stream`. */
+int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *dev_values,
+                     void *dev_packed, void *hip_stream);
+
+/* O = W_s x I (Section 5, "GPU Implementation"; Algorithm 1 with C overwritten).
+ * dev_I: K x N row-major with leading dimension ldI >= N elements (the lowered
+ * convolution input, N = batch*H*W contiguous); dev_O: M x N row-major fp32 with
+ * leading dimension ldO >= N, overwritten.  M and K must equal the mask's
+ * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  For the
+ * MFMA kernels dev_I, dev_O must be 16-byte aligned and ldI, ldO multiples of 4
+ * (fp32) or 8 (bf16) elements, otherwise the GENERIC kernel is used if the
+ * buffer was packed for it, else ESHAPE.  Asynchronous on `hip_stream`. */
+int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
+              const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,
+              void *hip_stream);
+
+/* Static description of an error code / of the last HIP failure in this thread. */
+const char *rbgp_strerror(int code);
+const char *rbgp_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RBGP_H_ */

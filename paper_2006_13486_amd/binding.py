@@ -1,0 +1,178 @@
+"""Thin ctypes binding over the C-ABI library (include/rbgp.h): argument
+marshalling only, same names as the C entry points.  Every step of the path
+runs inside librbgp.so; there is no Python or CPU fallback.  torch is used by
+callers for device memory and streams, this module only passes raw pointers."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+F32, BF16_F32ACC = 0, 1
+KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA = 0, 1, 2
+SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE = 0, 1, 2
+OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librbgp.so")
+_lib = None
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_intp = ctypes.POINTER(ctypes.c_int)
+_vp = ctypes.c_void_p
+
+SIGNATURES = {
+    "rbgp_make_mask": (ctypes.c_int, [_i32p, _i32p, _i32p, ctypes.c_uint64, ctypes.c_int32, ctypes.POINTER(_vp)]),
+    "rbgp_mask_free": (None, [_vp]),
+    "rbgp_mask_shape": (ctypes.c_int, [_vp, _i64p, _i64p, _i64p, _i64p, _i64p]),
+    "rbgp_mask_factor": (ctypes.c_int, [_vp, ctypes.c_int, _i32p, _i32p, _i32p, ctypes.POINTER(_i32p)]),
+    "rbgp_mask_spectrum": (ctypes.c_int, [_vp, ctypes.c_int, _f64p, _f64p, _f64p, _intp, _intp]),
+    "rbgp_mask_columns": (ctypes.c_int, [_vp, _vp]),
+    "rbgp_mask_dense": (ctypes.c_int, [_vp, _vp]),
+    "rbgp_mask_set_kernel": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "rbgp_mask_kernel": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "rbgp_mask_tune": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int]),
+    "rbgp_packed_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int]),
+    "rbgp_pack": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
+    "rbgp_pack_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
+    "rbgp_spmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                 _vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]),
+    "rbgp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "rbgp_last_hip_error": (ctypes.c_char_p, []),
+}
+
+
+class RbgpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        lib = load()
+        msg = lib.rbgp_strerror(code).decode()
+        if code == EHIP:
+            msg += ": " + lib.rbgp_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+def load():
+    """Load librbgp.so (built by paper_2006_13486_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise RbgpError(code, where)
+
+
+def _i32x4(v):
+    arr = (ctypes.c_int32 * 4)(*[int(x) for x in v])
+    return arr
+
+
+class Mask:
+    """Owner of one rbgp_mask_t*."""
+
+    def __init__(self, handle):
+        self.handle = handle
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.rbgp_mask_free(h)
+
+
+def rbgp_make_mask(rows, cols, row_deg, seed: int, max_tries: int = 0) -> Mask:
+    out = _vp()
+    _check(load().rbgp_make_mask(_i32x4(rows), _i32x4(cols), _i32x4(row_deg), int(seed), int(max_tries),
+                                 ctypes.byref(out)), "rbgp_make_mask")
+    return Mask(out)
+
+
+def rbgp_mask_free(mask: Mask):
+    h, mask.handle = mask.handle, None
+    if h:
+        load().rbgp_mask_free(h)
+
+
+def rbgp_mask_shape(mask: Mask) -> dict:
+    v = [ctypes.c_int64() for _ in range(5)]
+    _check(load().rbgp_mask_shape(mask.handle, *[ctypes.byref(x) for x in v]), "rbgp_mask_shape")
+    return dict(zip(("M", "K", "rowdeg", "coldeg", "nnz"), (int(x.value) for x in v)))
+
+
+def rbgp_mask_factor(mask: Mask, i: int):
+    r, c, d = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    adj = _i32p()
+    _check(load().rbgp_mask_factor(mask.handle, i, ctypes.byref(r), ctypes.byref(c), ctypes.byref(d),
+                                   ctypes.byref(adj)), "rbgp_mask_factor")
+    a = np.ctypeslib.as_array(adj, shape=(r.value, d.value)).copy()
+    return int(r.value), int(c.value), int(d.value), a
+
+
+def rbgp_mask_spectrum(mask: Mask, i: int) -> dict:
+    s1, s2, b = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    st, tr = ctypes.c_int(), ctypes.c_int()
+    _check(load().rbgp_mask_spectrum(mask.handle, i, ctypes.byref(s1), ctypes.byref(s2), ctypes.byref(b),
+                                     ctypes.byref(st), ctypes.byref(tr)), "rbgp_mask_spectrum")
+    return dict(sigma1=s1.value, sigma2=s2.value, bound=b.value, status=st.value, tries=tr.value)
+
+
+def rbgp_mask_columns(mask: Mask) -> np.ndarray:
+    sh = rbgp_mask_shape(mask)
+    out = np.empty((sh["M"], sh["rowdeg"]), dtype=np.int32)
+    _check(load().rbgp_mask_columns(mask.handle, out.ctypes.data), "rbgp_mask_columns")
+    return out
+
+
+def rbgp_mask_dense(mask: Mask) -> np.ndarray:
+    sh = rbgp_mask_shape(mask)
+    out = np.empty((sh["M"], sh["K"]), dtype=np.uint8)
+    _check(load().rbgp_mask_dense(mask.handle, out.ctypes.data), "rbgp_mask_dense")
+    return out
+
+
+def rbgp_mask_set_kernel(mask: Mask, kernel: int):
+    _check(load().rbgp_mask_set_kernel(mask.handle, kernel), "rbgp_mask_set_kernel")
+
+
+def rbgp_mask_kernel(mask: Mask, dtype: int) -> int:
+    return int(load().rbgp_mask_kernel(mask.handle, dtype))
+
+
+def rbgp_mask_tune(mask: Mask, cols_per_lane: int = 0, cols_per_workgroup: int = 0, groups_per_workgroup: int = 0):
+    _check(load().rbgp_mask_tune(mask.handle, cols_per_lane, cols_per_workgroup, groups_per_workgroup),
+           "rbgp_mask_tune")
+
+
+def rbgp_packed_bytes(mask: Mask, dtype: int) -> int:
+    return int(load().rbgp_packed_bytes(mask.handle, dtype))
+
+
+def rbgp_pack(mask: Mask, dtype: int, host_values: np.ndarray, dev_packed_ptr: int, stream: int = 0):
+    """host_values: contiguous numpy array, float32 (F32) or uint16 bf16 bits (BF16_F32ACC)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    if host_values.dtype != want or not host_values.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"host_values must be C-contiguous {want}")
+    if host_values.size != rbgp_mask_shape(mask)["nnz"]:
+        raise ValueError("host_values must hold M*rowdeg elements")
+    _check(load().rbgp_pack(mask.handle, dtype, host_values.ctypes.data, dev_packed_ptr, stream), "rbgp_pack")
+
+
+def rbgp_pack_device(mask: Mask, dtype: int, dev_values_ptr: int, dev_packed_ptr: int, stream: int = 0):
+    _check(load().rbgp_pack_device(mask.handle, dtype, dev_values_ptr, dev_packed_ptr, stream), "rbgp_pack_device")
+
+
+def rbgp_spmm(mask: Mask, dtype: int, M: int, K: int, N: int, dev_packed_ptr: int, dev_I_ptr: int, ldI: int,
+              dev_O_ptr: int, ldO: int, stream: int = 0):
+    _check(load().rbgp_spmm(mask.handle, dtype, M, K, N, dev_packed_ptr, dev_I_ptr, ldI, dev_O_ptr, ldO, stream),
+           "rbgp_spmm")

@@ -1,0 +1,350 @@
+// Host part of the library: base-graph sampler, spectral test, mask object and
+// the index expansions that need no GPU.
+//
+// Appendix "Ramanujan Bipartite Graph Generation": 2-lift, sparse biregular
+// generation by log2(1/(1-sp)) lifts of a complete graph, rejection sampling
+// until the graph meets the bound of Section 3.  Section 3: bipartite graph
+// product = Kronecker product of biadjacency matrices.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "rbgp_internal.h"
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+
+inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// Fair coins for (seed, factor, attempt): counter-based SplitMix64.
+struct Coins {
+  uint64_t key, n = 0;
+  Coins(uint64_t seed, uint64_t factor, uint64_t attempt)
+      : key(mix64(mix64(mix64(seed) + factor) + attempt)) {}
+  int next() {
+    ++n;
+    return int(mix64(key + n * kGolden) >> 63);
+  }
+};
+
+using Bits = std::vector<uint8_t>;  // dense 0/1 matrix, row-major
+
+// One random 2-lift: clone of u is u+a, clone of v is v+c; per edge (row-major
+// order) coin 0 keeps the identity pair, coin 1 takes the crossover pair.
+Bits lift2(const Bits &B, int a, int c, Coins &coins) {
+  Bits L(size_t(4) * a * c, 0);
+  const int c2 = 2 * c;
+  for (int u = 0; u < a; ++u)
+    for (int v = 0; v < c; ++v) {
+      if (!B[size_t(u) * c + v]) continue;
+      if (coins.next() == 0) {
+        L[size_t(u) * c2 + v] = 1;
+        L[size_t(u + a) * c2 + v + c] = 1;
+      } else {
+        L[size_t(u) * c2 + v + c] = 1;
+        L[size_t(u + a) * c2 + v] = 1;
+      }
+    }
+  return L;
+}
+
+Bits sample_biregular(int a, int c, int lifts, Coins &coins) {
+  int ba = a >> lifts, bc = c >> lifts;
+  Bits B(size_t(ba) * bc, 1);
+  for (int l = 0; l < lifts; ++l) {
+    B = lift2(B, ba, bc, coins);
+    ba *= 2;
+    bc *= 2;
+  }
+  return B;
+}
+
+// Eigenvalues of a symmetric n x n matrix by cyclic Jacobi rotations, descending.
+std::vector<double> sym_eigenvalues(std::vector<double> A, int n) {
+  auto at = [&](int i, int j) -> double & { return A[size_t(i) * n + j]; };
+  double norm = 0;
+  for (double x : A) norm += x * x;
+  norm = std::sqrt(norm);
+  for (int sweep = 0; sweep < 100; ++sweep) {
+    double off = 0;
+    for (int i = 0; i < n; ++i)
+      for (int j = i + 1; j < n; ++j) off += at(i, j) * at(i, j);
+    if (std::sqrt(2 * off) <= 1e-15 * norm || norm == 0) break;
+    for (int p = 0; p < n; ++p)
+      for (int q = p + 1; q < n; ++q) {
+        double apq = at(p, q);
+        if (std::fabs(apq) < 1e-300) continue;
+        double theta = (at(q, q) - at(p, p)) / (2 * apq);
+        double t = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1));
+        double cs = 1 / std::sqrt(t * t + 1), sn = t * cs;
+        for (int k = 0; k < n; ++k) {
+          double akp = at(k, p), akq = at(k, q);
+          at(k, p) = cs * akp - sn * akq;
+          at(k, q) = sn * akp + cs * akq;
+        }
+        for (int k = 0; k < n; ++k) {
+          double apk = at(p, k), aqk = at(q, k);
+          at(p, k) = cs * apk - sn * aqk;
+          at(q, k) = sn * apk + cs * aqk;
+        }
+      }
+  }
+  std::vector<double> ev(n);
+  for (int i = 0; i < n; ++i) ev[i] = at(i, i);
+  std::sort(ev.begin(), ev.end(), [](double x, double y) { return x > y; });
+  return ev;
+}
+
+// Two largest singular values of the a x c 0/1 matrix B (eigenvalues of the
+// smaller Gram matrix).  lambda_2 of the bipartite graph equals sigma_2.
+void top_singular(const Bits &B, int a, int c, double *s1, double *s2) {
+  const bool rows_small = a <= c;
+  const int n = rows_small ? a : c;
+  std::vector<double> G(size_t(n) * n, 0.0);
+  for (int i = 0; i < n; ++i)
+    for (int j = i; j < n; ++j) {
+      int dot = 0;
+      if (rows_small)
+        for (int k = 0; k < c; ++k) dot += B[size_t(i) * c + k] & B[size_t(j) * c + k];
+      else
+        for (int k = 0; k < a; ++k) dot += B[size_t(k) * c + i] & B[size_t(k) * c + j];
+      G[size_t(i) * n + j] = G[size_t(j) * n + i] = dot;
+    }
+  std::vector<double> ev = sym_eigenvalues(G, n);
+  *s1 = std::sqrt(std::max(0.0, ev[0]));
+  *s2 = n > 1 ? std::sqrt(std::max(0.0, ev[1])) : 0.0;
+}
+
+int ilog2_exact(int q) {  // log2(q) if q is a power of two, else -1
+  if (q <= 0 || (q & (q - 1))) return -1;
+  int l = 0;
+  while ((1 << l) < q) ++l;
+  return l;
+}
+
+thread_local char g_hip_error[256] = "";
+
+}  // namespace
+
+void rbgp_set_hip_error(const char *msg) {
+  std::strncpy(g_hip_error, msg ? msg : "", sizeof(g_hip_error) - 1);
+  g_hip_error[sizeof(g_hip_error) - 1] = 0;
+}
+
+// Decide whether the MFMA kernels cover this mask and derive their tile shape.
+// They need the RBGP4 roles: G_r and G_b complete (Section 5).
+void rbgp_plan_mfma(rbgp_mask *m) {
+  rbgp_mfma_plan p;
+  const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
+  p.R = m->a[1] * m->a[3];
+  p.RB = (p.R + 3) / 4;
+  p.KS = m->d[2] * m->c[3];
+  p.NCH = (p.KS + 15) / 16;
+  p.SR = m->c[2] * m->c[3];
+  p.packed_elems = int64_t(m->a[0]) * m->d[0] * m->c[1] * m->a[2] * p.RB * p.NCH * 64;
+  p.ok = roles;
+  m->plan = p;
+}
+
+// Packed layouts.
+//  GENERIC: canonical order, nnz elements.
+//  MFMA:    [u_o][j_o][v_r][u_i][rb][ch][b][i] with b the position inside a
+//           16-wide chunk of the group's (j_i, v_b) contraction list and i the
+//           row inside a 4-row block of the group's (u_r, u_b) rows; padding
+//           (kk >= KS or row >= R) is zero.  One (u_o, j_o, v_r) slice is the
+//           compact W tile of one step of Algorithm 1's outer loop.
+void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, std::vector<int32_t> &perm) {
+  if (kernel != RBGP_KERNEL_MFMA) {
+    perm.resize(size_t(m->nnz));
+    for (int64_t i = 0; i < m->nnz; ++i) perm[size_t(i)] = int32_t(i);
+    return;
+  }
+  const rbgp_mfma_plan &p = m->plan;
+  const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3];
+  const int d1 = m->d[0], d2 = m->d[1], d3 = m->d[2], d4 = m->d[3];
+  perm.assign(size_t(p.packed_elems), -1);
+  size_t pos = 0;
+  for (int u1 = 0; u1 < a1; ++u1)
+    for (int j1 = 0; j1 < d1; ++j1)
+      for (int v2 = 0; v2 < d2; ++v2)
+        for (int u3 = 0; u3 < a3; ++u3)
+          for (int rb = 0; rb < p.RB; ++rb)
+            for (int ch = 0; ch < p.NCH; ++ch)
+              for (int b = 0; b < 16; ++b)
+                for (int i = 0; i < 4; ++i, ++pos) {
+                  const int kk = ch * 16 + b, r = rb * 4 + i;
+                  if (kk >= p.KS || r >= p.R) continue;
+                  const int j3 = kk / d4, v4 = kk % d4;
+                  const int u2 = r / a4, u4 = r % a4;
+                  const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
+                  const int64_t t = ((int64_t(j1) * d2 + v2) * d3 + j3) * d4 + v4;
+                  perm[pos] = int32_t(row * m->rowdeg + t);
+                }
+}
+
+extern "C" {
+
+int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t row_deg[4],
+                   uint64_t seed, int32_t max_tries, rbgp_mask_t **out) {
+  if (!rows || !cols || !row_deg || !out) return RBGP_EINVAL;
+  if (max_tries <= 0) max_tries = 1000;
+  int lifts[4];
+  int64_t M = 1, K = 1, rowdeg = 1, coldeg = 1;
+  for (int i = 0; i < 4; ++i) {
+    if (rows[i] <= 0 || cols[i] <= 0 || row_deg[i] <= 0 || row_deg[i] > cols[i]) return RBGP_EINVAL;
+    if (cols[i] % row_deg[i]) return RBGP_EINVAL;
+    lifts[i] = ilog2_exact(cols[i] / row_deg[i]);
+    if (lifts[i] < 0 || rows[i] % (1 << lifts[i])) return RBGP_EINVAL;
+    M *= rows[i];
+    K *= cols[i];
+    rowdeg *= row_deg[i];
+    coldeg *= int64_t(rows[i]) * row_deg[i] / cols[i];
+    if (M > (1 << 24) || K > (1 << 24)) return RBGP_EINVAL;
+  }
+  if (M * rowdeg >= (int64_t(1) << 31)) return RBGP_EINVAL;
+  rbgp_mask *m = new (std::nothrow) rbgp_mask();
+  if (!m) return RBGP_ENOMEM;
+  try {
+    for (int i = 0; i < 4; ++i) {
+      const int a = rows[i], c = cols[i], d = row_deg[i], e = int(int64_t(a) * d / c);
+      m->a[i] = a; m->c[i] = c; m->d[i] = d; m->e[i] = e;
+      m->bound[i] = std::sqrt(double(d - 1)) + std::sqrt(double(e - 1));
+      Bits B;
+      if (d == c) {
+        B.assign(size_t(a) * c, 1);
+        m->sigma1[i] = std::sqrt(double(a) * c);
+        m->sigma2[i] = 0;
+        m->status[i] = RBGP_SPEC_COMPLETE;
+        m->tries[i] = 0;
+      } else {
+        bool accepted = false;
+        for (int t = 0; t < max_tries && !accepted; ++t) {
+          Coins coins(seed, uint64_t(i), uint64_t(t));
+          B = sample_biregular(a, c, lifts[i], coins);
+          top_singular(B, a, c, &m->sigma1[i], &m->sigma2[i]);
+          m->tries[i] = t + 1;
+          if (std::min(d, e) == 1) {
+            m->status[i] = RBGP_SPEC_DEGENERATE;
+            accepted = true;
+          } else if (m->sigma2[i] <= m->bound[i] * (1.0 + 1e-9)) {
+            m->status[i] = RBGP_SPEC_OK;
+            accepted = true;
+          }
+        }
+        if (!accepted) {
+          delete m;
+          return RBGP_ENOTRAMANUJAN;
+        }
+      }
+      m->adj[i].resize(size_t(a) * d);
+      for (int u = 0; u < a; ++u) {
+        int j = 0;
+        for (int v = 0; v < c; ++v)
+          if (B[size_t(u) * c + v]) m->adj[i][size_t(u) * d + j++] = v;
+      }
+    }
+  } catch (const std::bad_alloc &) {
+    delete m;
+    return RBGP_ENOMEM;
+  }
+  m->M = M; m->K = K; m->rowdeg = rowdeg; m->coldeg = coldeg; m->nnz = M * rowdeg;
+  m->kernel_choice = RBGP_KERNEL_AUTO;
+  m->dev = nullptr;
+  rbgp_plan_mfma(m);
+  *out = m;
+  return RBGP_OK;
+}
+
+void rbgp_mask_free(rbgp_mask_t *mask) {
+  if (!mask) return;
+  if (mask->dev) rbgp_device_release(mask->dev);
+  delete mask;
+}
+
+int rbgp_mask_shape(const rbgp_mask_t *m, int64_t *M, int64_t *K, int64_t *rowdeg, int64_t *coldeg,
+                    int64_t *nnz) {
+  if (!m) return RBGP_EINVAL;
+  if (M) *M = m->M;
+  if (K) *K = m->K;
+  if (rowdeg) *rowdeg = m->rowdeg;
+  if (coldeg) *coldeg = m->coldeg;
+  if (nnz) *nnz = m->nnz;
+  return RBGP_OK;
+}
+
+int rbgp_mask_factor(const rbgp_mask_t *m, int i, int32_t *rows, int32_t *cols, int32_t *deg,
+                     const int32_t **adj) {
+  if (!m || i < 0 || i > 3) return RBGP_EINVAL;
+  if (rows) *rows = m->a[i];
+  if (cols) *cols = m->c[i];
+  if (deg) *deg = m->d[i];
+  if (adj) *adj = m->adj[i].data();
+  return RBGP_OK;
+}
+
+int rbgp_mask_spectrum(const rbgp_mask_t *m, int i, double *sigma1, double *sigma2, double *bound,
+                       int *status, int *tries) {
+  if (!m || i < 0 || i > 3) return RBGP_EINVAL;
+  if (sigma1) *sigma1 = m->sigma1[i];
+  if (sigma2) *sigma2 = m->sigma2[i];
+  if (bound) *bound = m->bound[i];
+  if (status) *status = m->status[i];
+  if (tries) *tries = m->tries[i];
+  return RBGP_OK;
+}
+
+int rbgp_mask_columns(const rbgp_mask_t *m, int32_t *out) {
+  if (!m || !out) return RBGP_EINVAL;
+  const int32_t *A0 = m->adj[0].data(), *A1 = m->adj[1].data(), *A2 = m->adj[2].data(),
+                *A3 = m->adj[3].data();
+  int64_t pos = 0;
+  for (int u0 = 0; u0 < m->a[0]; ++u0)
+    for (int u1 = 0; u1 < m->a[1]; ++u1)
+      for (int u2 = 0; u2 < m->a[2]; ++u2)
+        for (int u3 = 0; u3 < m->a[3]; ++u3)
+          for (int j0 = 0; j0 < m->d[0]; ++j0)
+            for (int j1 = 0; j1 < m->d[1]; ++j1)
+              for (int j2 = 0; j2 < m->d[2]; ++j2)
+                for (int j3 = 0; j3 < m->d[3]; ++j3) {
+                  int64_t k = A0[u0 * m->d[0] + j0];
+                  k = k * m->c[1] + A1[u1 * m->d[1] + j1];
+                  k = k * m->c[2] + A2[u2 * m->d[2] + j2];
+                  k = k * m->c[3] + A3[u3 * m->d[3] + j3];
+                  out[pos++] = int32_t(k);
+                }
+  return RBGP_OK;
+}
+
+int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
+  if (!m || !out) return RBGP_EINVAL;
+  std::memset(out, 0, size_t(m->M) * size_t(m->K));
+  std::vector<int32_t> cols(size_t(m->nnz));
+  rbgp_mask_columns(m, cols.data());
+  for (int64_t row = 0; row < m->M; ++row)
+    for (int64_t t = 0; t < m->rowdeg; ++t)
+      out[size_t(row) * size_t(m->K) + size_t(cols[size_t(row * m->rowdeg + t)])] = 1;
+  return RBGP_OK;
+}
+
+const char *rbgp_strerror(int code) {
+  switch (code) {
+    case RBGP_OK: return "ok";
+    case RBGP_EINVAL: return "invalid argument";
+    case RBGP_ENOMEM: return "out of memory";
+    case RBGP_ENOTRAMANUJAN: return "no Ramanujan sample within max_tries";
+    case RBGP_ESHAPE: return "shape, leading dimension or alignment does not match the mask";
+    case RBGP_EHIP: return "HIP call failed";
+    case RBGP_EUNSUPPORTED: return "kernel does not cover this mask or dtype";
+    default: return "unknown error";
+  }
+}
+
+const char *rbgp_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs, element by element."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import rbgp_oracle as orc
+from paper_2006_13486_amd import binding as rb
+from paper_2006_13486_amd import workloads as wl
+from tests import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+GEN, MFMA = rb.KERNEL_GENERIC, rb.KERNEL_MFMA
+
+
+# ------------------------------------------------------------------ fixed configurations, full size
+@pytest.mark.parametrize("w", wl.CONFIGS, ids=lambda w: w.name)
+def test_config_full_size_default_launch(w):
+    """The launch configuration bench.py times (library defaults)."""
+    gh.check_parity(w, expect_kernel=MFMA)
+
+
+@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
+def test_config_generic_kernel(w):
+    gh.check_parity(w, N=min(w.N, 1024), kernel=GEN, expect_kernel=GEN)
+
+
+@pytest.mark.parametrize("tune", [(1, 64, 0), (2, 128, 0), (1, 64, 2), (2, 128, 1)])
+@pytest.mark.parametrize("w", [wl.VGG19_CONV5, wl.VGG19_CONV3_BF16, wl.WRN_G1], ids=lambda w: w.name)
+def test_config_tile_shapes(w, tune):
+    gh.check_parity(w, N=1536 if w.N > 4096 else w.N, kernel=MFMA, tune=tune)
+
+
+# ------------------------------------------------------------------ ragged and degenerate sizes
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("N,ld_pad", [(1, 7), (63, 1), (64, 0), (65, 3), (200, 8), (257, 15)])
+def test_ragged_columns(N, ld_pad, dtype):
+    """Column counts that leave a partial tile, with a padded leading dimension
+    (pad columns of O must stay untouched)."""
+    epc = 8 if dtype == wl.BF16 else 4
+    pad = (-N) % epc + ld_pad // epc * epc            # keeps ldI a multiple of the 16-byte chunk
+    w = replace(wl.VGG19_CONV5, rows=(4, 4, 4, 2), cols=(4, 4, 8, 9), row_deg=(2, 4, 2, 9), dtype=dtype,
+                name=f"ragged_{dtype}")
+    for tune in [(1, 64, 0), (2, 128, 0)]:
+        gh.check_parity(w, N=N, kernel=MFMA, tune=tune, ld_pad=pad)
+    gh.check_parity(w, N=N, kernel=GEN, ld_pad=ld_pad)
+
+
+def test_empty_input_is_a_noop():
+    import torch
+    w = wl.TINY
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    O = torch.full((w.M, 4), 5.0, device="cuda:0")
+    rb.rbgp_spmm(mask, w.dtype, w.M, w.K, 0, 0, 0, 0, O.data_ptr(), 0, 0)
+    torch.cuda.synchronize()
+    assert bool((O == 5.0).all())
+
+
+def test_misaligned_input_is_rejected_by_the_mfma_family():
+    import torch
+    w = wl.TINY
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device="cuda:0")
+    I = torch.zeros(w.K * 70 + 8, device="cuda:0")
+    O = torch.zeros(w.M * 70, device="cuda:0")
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, 66, packed.data_ptr(), I.data_ptr(), 66, O.data_ptr(), 66, 0)
+    assert ei.value.code == rb.ESHAPE
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, 64, packed.data_ptr(), I.data_ptr() + 4, 64, O.data_ptr(), 64, 0)
+    assert ei.value.code == rb.ESHAPE
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ exact cases
+@pytest.mark.parametrize("kernel", [GEN, MFMA])
+@pytest.mark.parametrize("w", [wl.TINY, replace(wl.WRN_G1, N=576)], ids=lambda w: w.name)
+def test_one_hot_input_returns_dense_weights_exactly(w, kernel):
+    """I = identity: every output is one kept weight times 1 plus zeros, exact
+    in fp32.  Pins the pack permutation and every index bit for bit."""
+    vals = wl.kept_weights(w)
+    I = np.eye(w.K, dtype=np.float32)
+    out, _ = gh.library_spmm(w, vals, I, kernel, tag="one-hot")
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    W = orc.scatter_values(orc.kron_mask(Bs), vals)
+    assert np.array_equal(out, W)
+
+
+def test_one_hot_bf16_exact():
+    w = replace(wl.TINY, dtype=wl.BF16, name="tiny_bf16")
+    vb = wl.to_bf16_bits(wl.kept_weights(w))
+    Ib = wl.to_bf16_bits(np.eye(w.K, dtype=np.float32))
+    for kernel in (GEN, MFMA):
+        out, _ = gh.library_spmm(w, vb, Ib, kernel, tag="one-hot bf16")
+        Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+        W = orc.scatter_values(orc.kron_mask(Bs), wl.bf16_bits_as_f32(vb))
+        assert np.array_equal(out, W)
+
+
+def test_all_complete_factors_is_a_dense_gemm():
+    w = wl.Workload("dense_32x72", (2, 4, 2, 2), (1, 2, 4, 9), (1, 2, 4, 9), 300, wl.F32, 1, 2, 3)
+    gh.check_parity(w, kernel=MFMA, ld_pad=0)
+    gh.check_parity(w, kernel=GEN)
+
+
+# ------------------------------------------------------------------ shapes across the kernel table
+FUZZ = [
+    # rows, cols, row_deg  (G_r, G_b complete)                     covers
+    ((2, 1, 2, 1), (4, 1, 4, 1), (2, 1, 2, 1)),                    # R=1, KS=2
+    ((4, 2, 8, 1), (4, 3, 8, 1), (2, 3, 4, 1)),                    # R=2, KS=4, |G_r.V|=3
+    ((2, 1, 16, 4), (2, 1, 16, 2), (2, 1, 8, 2)),                  # R=4, KS=16
+    ((4, 4, 16, 1), (8, 1, 32, 1), (4, 1, 8, 1)),                  # Table-2-like: R=4, KS=8, 16 groups
+    ((2, 2, 32, 2), (4, 1, 32, 1), (2, 1, 32, 1)),                 # KS=32, 32 groups
+    ((4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9)),                    # R=8, KS=36
+    ((2, 4, 4, 2), (2, 2, 8, 9), (1, 2, 8, 9)),                    # KS=72
+    ((4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9)),                    # R=3 (partial 4-row block)
+    ((2, 3, 4, 2), (2, 2, 4, 9), (1, 2, 2, 9)),                    # R=6 (one full, one partial block)
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("idx", range(len(FUZZ)))
+def test_shapes_across_the_kernel_table(idx, dtype):
+    rows, cols, deg = FUZZ[idx]
+    w = wl.Workload(f"fuzz{idx}_{dtype}", rows, cols, deg, 328, dtype, 100 + idx, 200 + idx, 300 + idx, 1.0)
+    e1 = gh.check_parity(w, kernel=MFMA, tune=(1, 64, 0))
+    e2 = gh.check_parity(w, kernel=MFMA, tune=(2, 128, 0))
+    gh.check_parity(w, kernel=GEN)
+
+
+def test_masks_outside_rbgp4_roles_use_the_generic_kernel():
+    """Sparse G_r / G_b (general four-factor RBGP) still multiply correctly."""
+    w = wl.Workload("general_rbgp", (4, 4, 4, 2), (4, 4, 8, 4), (2, 2, 4, 2), 130, wl.F32, 5, 6, 7, 1.0)
+    gh.check_parity(w, expect_kernel=GEN)
+
+
+def test_sdmm4096_paper_workload_sampled():
+    """Table 2's 4096^3 SDMM at 87.5 % sparsity, (50 %, 75 %) split: full shape
+    on the GPU, a sample of output columns checked against the oracle."""
+    w = wl.sdmm4096_table2(1, 2)
+    vl, Il, vf, If = gh.host_inputs(w)
+    out, used = gh.library_spmm(w, vl, Il, tag="table2")
+    assert used == MFMA
+    cols = np.r_[0:64, 2000:2064, 4032:4096]
+    ref, den = gh.oracle_spmm(w, vf, np.ascontiguousarray(If[:, cols]))
+    assert orc.normalised_error(out[:, cols], ref, den) <= gh.TOL[w.dtype]
