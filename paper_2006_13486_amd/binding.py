@@ -60,6 +60,10 @@ def load():
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch bundles its own HIP runtime (SONAME libamdhip64.so.7).  Import it first so
+        # that librbgp.so binds to that copy: two HIP runtimes in one process do not share
+        # the device and the second one reports "no ROCm-capable device".
+        import torch  # noqa: F401
         lib = ctypes.CDLL(_LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
