@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="conv5", choices=sorted(WORKLOADS))
     ap.add_argument("--sets", type=int, default=0, help="distinct (I,O) buffer sets to rotate over (0 = auto)")
-    ap.add_argument("--tune", default="", help="cols_per_lane,cols_per_workgroup,groups_per_workgroup")
+    ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -89,7 +89,8 @@ def main():
     if args.kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask, args.kernel)
     if args.tune:
-        rb.rbgp_mask_tune(mask, *[int(x) for x in args.tune.split(",")])
+        for knob, value in enumerate(int(x) for x in args.tune.split(",")):
+            rb.rbgp_mask_tune(mask, knob, value)
     stream = torch.cuda.current_stream().cuda_stream
     packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)

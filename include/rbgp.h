@@ -59,7 +59,21 @@ enum {
 enum { RBGP_SPEC_OK = 0, RBGP_SPEC_COMPLETE = 1, RBGP_SPEC_DEGENERATE = 2 };
 
 /* kernel families */
-enum { RBGP_KERNEL_AUTO = 0, RBGP_KERNEL_GENERIC = 1, RBGP_KERNEL_MFMA = 2 };
+enum {
+  RBGP_KERNEL_AUTO = 0,
+  RBGP_KERNEL_GENERIC = 1,  /* plain FMA, any four-factor mask, canonical layout */
+  RBGP_KERNEL_MFMA = 2,     /* RBGP4 masks: I tiles staged in LDS, MFMA on the dense blocks */
+  RBGP_KERNEL_MFMA_REG = 3  /* RBGP4 masks, fp32: I rows streamed into registers and reused
+                               across a cluster of tile rows, MFMA on the dense blocks */
+};
+
+/* tuning knobs (rbgp_mask_tune) */
+enum {
+  RBGP_TUNE_COLS_PER_LANE = 0,        /* MFMA: 1 or 2 */
+  RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128 */
+  RBGP_TUNE_GROUPS_PER_WORKGROUP = 2, /* MFMA: a divisor of |G_i.U| */
+  RBGP_TUNE_CLUSTER = 3               /* MFMA_REG: 16-row MFMA groups per wavefront, 1 or 2 */
+};
 
 /* Sample the four base graphs and build the mask (host only, no GPU call).
  * Appendix "Ramanujan Bipartite Graph Generation": a factor with row_deg < cols
@@ -102,19 +116,19 @@ int rbgp_mask_columns(const rbgp_mask_t *mask, int32_t *out);
 int rbgp_mask_dense(const rbgp_mask_t *mask, uint8_t *out);
 
 /* Choose the kernel family used by rbgp_packed_bytes / rbgp_pack / rbgp_spmm for
- * this mask: AUTO (default; MFMA when the mask's shape is covered, else GENERIC),
- * GENERIC (plain FMA kernel, any mask) or MFMA (EUNSUPPORTED if not covered).
- * Changing it invalidates buffers packed before the change. */
+ * this mask: AUTO (default: an MFMA family when the mask's shape is covered, else
+ * GENERIC) or one family (EUNSUPPORTED if it does not cover the mask's shape; a
+ * family that does not cover the dtype falls back to GENERIC).  Each family has
+ * its own packed layout: changing it invalidates buffers packed before. */
 int rbgp_mask_set_kernel(rbgp_mask_t *mask, int kernel);
 
-/* Kernel family (RBGP_KERNEL_GENERIC or RBGP_KERNEL_MFMA) that would run. */
+/* Kernel family (never AUTO) that rbgp_pack / rbgp_spmm use for this dtype. */
 int rbgp_mask_kernel(const rbgp_mask_t *mask, rbgp_dtype_t dtype);
 
-/* Tuning knobs of the MFMA family for this mask (0 = library default): columns
- * per lane (1 or 2), columns per workgroup (64*t*{1,2}), G_i vertices per
- * workgroup (a divisor of |G_i.U|).  Does not change the packed layout.
- * rbgp_spmm returns EUNSUPPORTED for a combination that is not built. */
-int rbgp_mask_tune(rbgp_mask_t *mask, int cols_per_lane, int cols_per_workgroup, int groups_per_workgroup);
+/* Set one launch-shape knob (RBGP_TUNE_*) of this mask; 0 = library default.
+ * Does not change the packed layout.  rbgp_spmm returns EUNSUPPORTED for a
+ * combination that is not built. */
+int rbgp_mask_tune(rbgp_mask_t *mask, int knob, int value);
 
 /* Bytes of the device buffer that rbgp_pack fills (kernel layout incl. padding); 0 on error. */
 size_t rbgp_packed_bytes(const rbgp_mask_t *mask, rbgp_dtype_t dtype);
@@ -138,10 +152,11 @@ int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *de
  * dev_I: K x N row-major with leading dimension ldI >= N elements (the lowered
  * convolution input, N = batch*H*W contiguous); dev_O: M x N row-major fp32 with
  * leading dimension ldO >= N, overwritten.  M and K must equal the mask's
- * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  For the
- * MFMA kernels dev_I, dev_O must be 16-byte aligned and ldI, ldO multiples of 4
- * (fp32) or 8 (bf16) elements, otherwise the GENERIC kernel is used if the
- * buffer was packed for it, else ESHAPE.  Asynchronous on `hip_stream`. */
+ * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  The
+ * RBGP_KERNEL_MFMA family needs dev_I 16-byte aligned and ldI a multiple of 4
+ * (fp32) or 8 (bf16) elements (ESHAPE otherwise); the other families take any
+ * alignment.  dev_packed must have been packed with the same kernel family and
+ * dtype.  Asynchronous on `hip_stream`. */
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
               const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,
               void *hip_stream);

@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 F32, BF16_F32ACC = 0, 1
-KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA = 0, 1, 2
+KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG = 0, 1, 2, 3
+TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_CLUSTER = 0, 1, 2, 3
 SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE = 0, 1, 2
 OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 
@@ -33,7 +34,7 @@ SIGNATURES = {
     "rbgp_mask_dense": (ctypes.c_int, [_vp, _vp]),
     "rbgp_mask_set_kernel": (ctypes.c_int, [_vp, ctypes.c_int]),
     "rbgp_mask_kernel": (ctypes.c_int, [_vp, ctypes.c_int]),
-    "rbgp_mask_tune": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int]),
+    "rbgp_mask_tune": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
     "rbgp_packed_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int]),
     "rbgp_pack": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_pack_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
@@ -153,9 +154,8 @@ def rbgp_mask_kernel(mask: Mask, dtype: int) -> int:
     return int(load().rbgp_mask_kernel(mask.handle, dtype))
 
 
-def rbgp_mask_tune(mask: Mask, cols_per_lane: int = 0, cols_per_workgroup: int = 0, groups_per_workgroup: int = 0):
-    _check(load().rbgp_mask_tune(mask.handle, cols_per_lane, cols_per_workgroup, groups_per_workgroup),
-           "rbgp_mask_tune")
+def rbgp_mask_tune(mask: Mask, knob: int, value: int):
+    _check(load().rbgp_mask_tune(mask.handle, knob, value), "rbgp_mask_tune")
 
 
 def rbgp_packed_bytes(mask: Mask, dtype: int) -> int:

@@ -32,8 +32,6 @@
 
 #include "rbgp_internal.h"
 
-void rbgp_set_hip_error(const char *msg);
-
 #define RBGP_HIP(call)                                                              \
   do {                                                                              \
     hipError_t e_ = (call);                                                         \
@@ -49,11 +47,12 @@ struct rbgp_device_state {
   int device = -1;
   int32_t *adj[4] = {nullptr, nullptr, nullptr, nullptr};
   int32_t *rowoff = nullptr;             // [a_i][KS]: stage-relative I row of each contraction step
-  int32_t *perm[3] = {nullptr, nullptr, nullptr};  // pack permutation per kernel family
-  size_t perm_elems[3] = {0, 0, 0};
+  int32_t *perm[RBGP_NUM_KERNELS] = {};  // pack permutation per kernel family
+  size_t perm_elems[RBGP_NUM_KERNELS] = {};
+  void *reg_state = nullptr;             // tables of the register-streaming family
   void *staging = nullptr;               // canonical values on their way through rbgp_pack
   size_t staging_bytes = 0;
-  int tune_t = 0, tune_tn = 0, tune_gw = 0;
+  int tune[4] = {0, 0, 0, 0};            // RBGP_TUNE_* values, 0 = default
 };
 
 void rbgp_device_release(rbgp_device_state *dev) {
@@ -61,8 +60,9 @@ void rbgp_device_release(rbgp_device_state *dev) {
   for (int i = 0; i < 4; ++i)
     if (dev->adj[i]) (void)hipFree(dev->adj[i]);
   if (dev->rowoff) (void)hipFree(dev->rowoff);
-  for (int i = 0; i < 3; ++i)
+  for (int i = 0; i < RBGP_NUM_KERNELS; ++i)
     if (dev->perm[i]) (void)hipFree(dev->perm[i]);
+  rbgp_reg_release(dev->reg_state);
   if (dev->staging) (void)hipFree(dev->staging);
   delete dev;
 }
@@ -340,9 +340,24 @@ bool mfma_covers(const rbgp_mask *m) {
   return find_mfma(p.KS, p.RB, 1, 64, 0) != nullptr;
 }
 
-int resolve_kernel(const rbgp_mask *m) {
-  if (m->kernel_choice == RBGP_KERNEL_GENERIC) return RBGP_KERNEL_GENERIC;
+// AUTO: the register-streaming family for fp32 masks whose I rows are shared by few
+// G_i vertices (little to gain from staging them in LDS), else the LDS family, else GENERIC.
+int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
+  const bool reg_ok = dtype == RBGP_F32 && rbgp_reg_covers(m);
+  switch (m->kernel_choice) {
+    case RBGP_KERNEL_GENERIC: return RBGP_KERNEL_GENERIC;
+    case RBGP_KERNEL_MFMA: return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
+    case RBGP_KERNEL_MFMA_REG: return reg_ok ? RBGP_KERNEL_MFMA_REG : RBGP_KERNEL_GENERIC;
+    default: break;
+  }
+  if (reg_ok && m->e[2] <= 2) return RBGP_KERNEL_MFMA_REG;
   return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
+}
+
+int64_t packed_elems(const rbgp_mask *m, int kernel) {
+  if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
+  if (kernel == RBGP_KERNEL_MFMA_REG) return m->reg.packed_elems;
+  return m->nnz;
 }
 
 template <typename T>
@@ -394,34 +409,31 @@ extern "C" {
 
 int rbgp_mask_set_kernel(rbgp_mask_t *m, int kernel) {
   if (!m) return RBGP_EINVAL;
-  if (kernel != RBGP_KERNEL_AUTO && kernel != RBGP_KERNEL_GENERIC && kernel != RBGP_KERNEL_MFMA)
-    return RBGP_EINVAL;
+  if (kernel < RBGP_KERNEL_AUTO || kernel >= RBGP_NUM_KERNELS) return RBGP_EINVAL;
   if (kernel == RBGP_KERNEL_MFMA && !mfma_covers(m)) return RBGP_EUNSUPPORTED;
+  if (kernel == RBGP_KERNEL_MFMA_REG && !rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
   m->kernel_choice = kernel;
   return RBGP_OK;
 }
 
 int rbgp_mask_kernel(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
   if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return RBGP_EINVAL;
-  return resolve_kernel(m);
+  return resolve_kernel(m, dtype);
 }
 
-int rbgp_mask_tune(rbgp_mask_t *m, int t, int tn, int gw) {
-  if (!m) return RBGP_EINVAL;
+int rbgp_mask_tune(rbgp_mask_t *m, int knob, int value) {
+  if (!m || knob < 0 || knob > 3 || value < 0) return RBGP_EINVAL;
   if (!m->dev) {
     m->dev = new (std::nothrow) rbgp_device_state();
     if (!m->dev) return RBGP_ENOMEM;
   }
-  m->dev->tune_t = t;
-  m->dev->tune_tn = tn;
-  m->dev->tune_gw = gw;
+  m->dev->tune[knob] = value;
   return RBGP_OK;
 }
 
 size_t rbgp_packed_bytes(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
   if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return 0;
-  const int64_t elems = resolve_kernel(m) == RBGP_KERNEL_MFMA ? m->plan.packed_elems : m->nnz;
-  return size_t(elems) * elem_bytes(dtype);
+  return size_t(packed_elems(m, resolve_kernel(m, dtype))) * elem_bytes(dtype);
 }
 
 int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
@@ -430,7 +442,7 @@ int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_v
   if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
-  const int kernel = resolve_kernel(m);
+  const int kernel = resolve_kernel(m, dtype);
   rc = ensure_perm(m, kernel);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -480,8 +492,12 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   if (rc) return rc;
   rbgp_device_state *dev = m->dev;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int kernel = resolve_kernel(m);
+  const int kernel = resolve_kernel(m, dtype);
   const bool bf16 = dtype == RBGP_BF16_F32ACC;
+
+  if (kernel == RBGP_KERNEL_MFMA_REG)
+    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_CLUSTER], N, dev_packed, dev_I, ldI,
+                           static_cast<float *>(dev_O), ldO, hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {
     GenericParams gp;
@@ -509,9 +525,10 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   const int epc = bf16 ? 8 : 4;
   if ((reinterpret_cast<uintptr_t>(dev_I) & 15) || (ldI % epc)) return RBGP_ESHAPE;
   // tile shape: T columns per lane, TN per workgroup, GW groups (waves) per workgroup
-  int T = dev->tune_t ? dev->tune_t : 2;
-  int TN = dev->tune_tn ? dev->tune_tn : 64 * T;
-  if (!dev->tune_t && !dev->tune_tn) {
+  const int tune_t = dev->tune[RBGP_TUNE_COLS_PER_LANE], tune_tn = dev->tune[RBGP_TUNE_COLS_PER_WORKGROUP];
+  int T = tune_t ? tune_t : 2;
+  int TN = tune_tn ? tune_tn : 64 * T;
+  if (!tune_t && !tune_tn) {
     // enough workgroups to fill 256 CUs, else narrower tiles
     const int64_t wg128 = ((N + 127) / 128) * m->a[0];
     if (wg128 < 512) { T = 1; TN = 64; }
@@ -519,7 +536,7 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   const MfmaEntry *e = find_mfma(pl.KS, pl.RB, T, TN, bf16 ? 1 : 0);
   if (!e) return RBGP_EUNSUPPORTED;
   const int nsub = TN / (64 * T);
-  int GW = dev->tune_gw ? dev->tune_gw : m->a[2];
+  int GW = dev->tune[RBGP_TUNE_GROUPS_PER_WORKGROUP] ? dev->tune[RBGP_TUNE_GROUPS_PER_WORKGROUP] : m->a[2];
   if (GW < 1) GW = 1;
   while (GW > 1 && (GW * nsub > 8 || m->a[2] % GW)) --GW;  // at most 8 waves per workgroup, GW | a_i
   if (GW * nsub > 8) return RBGP_EUNSUPPORTED;

@@ -152,6 +152,32 @@ void rbgp_plan_mfma(rbgp_mask *m) {
   m->plan = p;
 }
 
+// Register-streaming family: a stage is VC columns of G_r of one nonzero tile;
+// its contraction list (v_r, j_i, v_b) has KC <= 72 entries, consumed two at a time.
+void rbgp_plan_reg(rbgp_mask *m) {
+  rbgp_reg_plan p;
+  const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
+  p.R = m->a[1] * m->a[3];
+  p.RB = (p.R + 3) / 4;
+  p.KT = m->c[1] * m->d[2] * m->c[3];
+  const int per_v = m->d[2] * m->c[3];
+  p.VC = 0;
+  for (int vc = m->c[1]; vc >= 1; --vc)
+    if (m->c[1] % vc == 0 && vc * per_v <= 72) { p.VC = vc; break; }
+  p.ok = roles && p.VC > 0 && p.R <= 16;
+  if (p.ok) {
+    p.KC = p.VC * per_v;
+    p.NSTG = m->c[1] / p.VC;
+    p.RS = 1;
+    while (p.RS < p.R) p.RS *= 2;
+    p.MG = 16 / p.RS;
+    p.NO = (p.KC + 3) / 4;
+    p.NQ = (p.NO + 3) / 4;
+    p.packed_elems = int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] * p.NQ * 4 * p.RS * 4;
+  }
+  m->reg = p;
+}
+
 // Packed layouts.
 //  GENERIC: canonical order, nnz elements.
 //  MFMA:    [u_o][j_o][v_r][u_i][rb][ch][b][i] with b the position inside a
@@ -159,7 +185,35 @@ void rbgp_plan_mfma(rbgp_mask *m) {
 //           row inside a 4-row block of the group's (u_r, u_b) rows; padding
 //           (kk >= KS or row >= R) is zero.  One (u_o, j_o, v_r) slice is the
 //           compact W tile of one step of Algorithm 1's outer loop.
+//  MFMA_REG: [u_o][j_o][stage][u_i][q][g][i][w]: the stage's contraction list
+//           kk = ((v_r % VC) * d_i + j_i) * |G_b.V| + v_b is dealt to 4 lane
+//           groups g; element (q, g, i, w) is the weight of row i (< RS, the
+//           group's (u_r, u_b) rows padded to a power of two) at kk = 16q + 4w + g,
+//           so that one 16-byte load per lane fetches a row's weights for four
+//           consecutive load slots.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, std::vector<int32_t> &perm) {
+  if (kernel == RBGP_KERNEL_MFMA_REG) {
+    const rbgp_reg_plan &p = m->reg;
+    const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
+    perm.assign(size_t(p.packed_elems), -1);
+    size_t pos = 0;
+    for (int u1 = 0; u1 < a1; ++u1)
+      for (int j1 = 0; j1 < d1; ++j1)
+        for (int sg = 0; sg < p.NSTG; ++sg)
+          for (int u3 = 0; u3 < a3; ++u3)
+            for (int q = 0; q < p.NQ; ++q)
+              for (int g = 0; g < 4; ++g)
+                for (int r = 0; r < p.RS; ++r)
+                  for (int w = 0; w < 4; ++w, ++pos) {
+                    const int kk = 16 * q + 4 * w + g;
+                    if (kk >= p.KC || r >= p.R) continue;
+                    const int u2 = r / a4, u4 = r % a4;
+                    const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
+                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + kk;
+                    perm[pos] = int32_t(row * m->rowdeg + t);
+                  }
+    return;
+  }
   if (kernel != RBGP_KERNEL_MFMA) {
     perm.resize(size_t(m->nnz));
     for (int64_t i = 0; i < m->nnz; ++i) perm[size_t(i)] = int32_t(i);
@@ -257,6 +311,7 @@ int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t r
   m->kernel_choice = RBGP_KERNEL_AUTO;
   m->dev = nullptr;
   rbgp_plan_mfma(m);
+  rbgp_plan_reg(m);
   *out = m;
   return RBGP_OK;
 }

@@ -21,6 +21,22 @@ struct rbgp_mfma_plan {
   int64_t packed_elems = 0;
 };
 
+// Shape of the register-streaming MFMA kernels (see rbgp_mfma_reg.hip).
+struct rbgp_reg_plan {
+  bool ok = false;
+  int R = 0, RB = 0;
+  int KT = 0;    // contraction length of one group in one tile: |G_r.V| * d_i * |G_b.V|
+  int VC = 0;    // G_r columns per stage
+  int KC = 0;    // contraction length per stage: VC * d_i * |G_b.V|
+  int NSTG = 0;  // stages per tile: |G_r.V| / VC
+  int RS = 0;    // weight rows per tile row inside a 16-row MFMA group: R rounded up to 2^k
+  int MG = 0;    // tile rows per MFMA group: 16 / RS
+  int NO = 0;    // load slots per stage: ceil(KC / 4)
+  int NQ = 0;    // 16-byte weight loads per lane, group and stage: ceil(NO / 4)
+  int SRC = 0;   // rows of I spanned by one stage: VC * |G_i.V| * |G_b.V|
+  int64_t packed_elems = 0;
+};
+
 struct rbgp_mask {
   int32_t a[4], c[4], d[4], e[4];     // rows, cols, left degree, right degree of each factor
   std::vector<int32_t> adj[4];        // adjacency lists, a[i] x d[i], ascending
@@ -29,12 +45,23 @@ struct rbgp_mask {
   int64_t M, K, rowdeg, coldeg, nnz;
   int kernel_choice;                  // RBGP_KERNEL_*
   rbgp_mfma_plan plan;
+  rbgp_reg_plan reg;
   mutable rbgp_device_state *dev;     // lazily created device tables
 };
 
+enum { RBGP_NUM_KERNELS = 4 };
+#define RBGP_REG_G 8   // lane groups of the register-streaming family (part of its packed layout)  // one more than the largest RBGP_KERNEL_* value
+
 // device part
 void rbgp_device_release(rbgp_device_state *dev);
+void rbgp_set_hip_error(const char *msg);
+// register-streaming family (rbgp_mfma_reg.hip); `state` is its lazily built table cache
+bool rbgp_reg_covers(const rbgp_mask *m);
+int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_u, int64_t N, const void *packed, const void *I,
+                    int64_t ldI, float *O, int64_t ldO, void *stream);
+void rbgp_reg_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);
+void rbgp_plan_reg(rbgp_mask *m);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, std::vector<int32_t> &perm);

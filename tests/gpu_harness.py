@@ -28,8 +28,8 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
     if kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask, kernel)
-    if tune:
-        rb.rbgp_mask_tune(mask, *tune)
+    for knob, value in enumerate(tune or ()):
+        rb.rbgp_mask_tune(mask, knob, value)
     stream = torch.cuda.current_stream().cuda_stream
     packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, w.dtype), 16), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)

@@ -12,14 +12,14 @@ from tests import gpu_harness as gh
 
 pytestmark = pytest.mark.gpu
 
-GEN, MFMA = rb.KERNEL_GENERIC, rb.KERNEL_MFMA
+GEN, MFMA, REG = rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG
 
 
 # ------------------------------------------------------------------ fixed configurations, full size
 @pytest.mark.parametrize("w", wl.CONFIGS, ids=lambda w: w.name)
 def test_config_full_size_default_launch(w):
     """The launch configuration bench.py times (library defaults)."""
-    gh.check_parity(w, expect_kernel=MFMA)
+    gh.check_parity(w, expect_kernel=MFMA if w.dtype == wl.BF16 else REG)
 
 
 @pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
@@ -31,6 +31,17 @@ def test_config_generic_kernel(w):
 @pytest.mark.parametrize("w", [wl.VGG19_CONV5, wl.VGG19_CONV3_BF16, wl.WRN_G1], ids=lambda w: w.name)
 def test_config_tile_shapes(w, tune):
     gh.check_parity(w, N=1536 if w.N > 4096 else w.N, kernel=MFMA, tune=tune)
+
+
+@pytest.mark.parametrize("cluster", [1, 2])
+@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.WRN_G1], ids=lambda w: w.name)
+def test_config_register_family_cluster_sizes(w, cluster):
+    gh.check_parity(w, N=1000 if w.N > 4096 else w.N, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
+
+
+def test_fp32_lds_family_full_size():
+    for w in (wl.VGG19_CONV5, wl.WRN_G1):
+        gh.check_parity(w, kernel=MFMA, expect_kernel=MFMA)
 
 
 # ------------------------------------------------------------------ ragged and degenerate sizes
@@ -46,6 +57,9 @@ def test_ragged_columns(N, ld_pad, dtype):
     for tune in [(1, 64, 0), (2, 128, 0)]:
         gh.check_parity(w, N=N, kernel=MFMA, tune=tune, ld_pad=pad)
     gh.check_parity(w, N=N, kernel=GEN, ld_pad=ld_pad)
+    if dtype == wl.F32:
+        for cluster in (1, 2):
+            gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, cluster), ld_pad=ld_pad, expect_kernel=REG)
 
 
 def test_empty_input_is_a_noop():
@@ -62,6 +76,7 @@ def test_misaligned_input_is_rejected_by_the_mfma_family():
     import torch
     w = wl.TINY
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    rb.rbgp_mask_set_kernel(mask, MFMA)
     packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device="cuda:0")
     I = torch.zeros(w.K * 70 + 8, device="cuda:0")
     O = torch.zeros(w.M * 70, device="cuda:0")
@@ -75,7 +90,7 @@ def test_misaligned_input_is_rejected_by_the_mfma_family():
 
 
 # ------------------------------------------------------------------ exact cases
-@pytest.mark.parametrize("kernel", [GEN, MFMA])
+@pytest.mark.parametrize("kernel", [GEN, MFMA, REG])
 @pytest.mark.parametrize("w", [wl.TINY, replace(wl.WRN_G1, N=576)], ids=lambda w: w.name)
 def test_one_hot_input_returns_dense_weights_exactly(w, kernel):
     """I = identity: every output is one kept weight times 1 plus zeros, exact
@@ -102,6 +117,7 @@ def test_one_hot_bf16_exact():
 def test_all_complete_factors_is_a_dense_gemm():
     w = wl.Workload("dense_32x72", (2, 4, 2, 2), (1, 2, 4, 9), (1, 2, 4, 9), 300, wl.F32, 1, 2, 3)
     gh.check_parity(w, kernel=MFMA, ld_pad=0)
+    gh.check_parity(w, kernel=REG, expect_kernel=REG)
     gh.check_parity(w, kernel=GEN)
 
 
@@ -128,6 +144,9 @@ def test_shapes_across_the_kernel_table(idx, dtype):
     e1 = gh.check_parity(w, kernel=MFMA, tune=(1, 64, 0))
     e2 = gh.check_parity(w, kernel=MFMA, tune=(2, 128, 0))
     gh.check_parity(w, kernel=GEN)
+    if dtype == wl.F32 and idx >= 5:          # shapes inside the register family's table
+        for cluster in (1, 2):
+            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
 
 
 def test_masks_outside_rbgp4_roles_use_the_generic_kernel():
