@@ -72,7 +72,8 @@ enum {
   RBGP_TUNE_COLS_PER_LANE = 0,        /* MFMA: 1 or 2 */
   RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128 */
   RBGP_TUNE_GROUPS_PER_WORKGROUP = 2, /* MFMA: a divisor of |G_i.U| */
-  RBGP_TUNE_CLUSTER = 3               /* MFMA_REG: 16-row MFMA groups per wavefront, 1 or 2 */
+  RBGP_TUNE_WEIGHTS_IN_LDS = 3        /* MFMA_REG: 2 = copy the workgroup's weights to LDS first
+                                         (when they fit 160 KB) instead of streaming them */
 };
 
 /* Sample the four base graphs and build the mask (host only, no GPU call).

@@ -496,7 +496,7 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   const bool bf16 = dtype == RBGP_BF16_F32ACC;
 
   if (kernel == RBGP_KERNEL_MFMA_REG)
-    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_CLUSTER], N, dev_packed, dev_I, ldI,
+    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_WEIGHTS_IN_LDS], N, dev_packed, dev_I, ldI,
                            static_cast<float *>(dev_O), ldO, hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {

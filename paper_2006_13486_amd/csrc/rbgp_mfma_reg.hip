@@ -68,19 +68,21 @@ struct RegParams {
   const float *I;
   float *O;
   const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
-  const int32_t *stages;   // [ncl][2+U][64]: per stage (one per lane, first real stage in lane 2) the
-                           //   base row of the stage, the bit mask of MFMA groups with work, then per
-                           //   cluster member the index of its weight fragment block; -1 (mask 0) in
-                           //   lanes 0, 1 and past the end (sentinel stages) and when the member does
-                           //   not have the tile
-  const int32_t *counts;   // [ncl] stages of each cluster (<= 58)
-  const int32_t *members;  // [ncl][U] tile rows of each cluster (-1: none)
+  const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
+                           //   cluster member j_o * NSTG + (stage within the tile), the position of its
+                           //   weight fragment among the member's fragments; -1 past the end (sentinel
+                           //   stages) and when the member does not have the tile
+  const int32_t *counts;   // [ncl] stages of each cluster (<= 60)
+  const int32_t *members;  // [ncl][MG] tile rows of each cluster (-1: none)
   int64_t N, ldI, ldO;
   uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
   int a2, a3, a4, R;
-  int items_per_tile;      // ncl * a3
-  int wgs_per_tile;        // ceil(items_per_tile / waves per workgroup)
+  int fpm;                 // weight fragments per member: d_o * NSTG
+  int items;               // ncl * a3: (cluster, G_i vertex) pairs = workgroups per 4 column tiles
   int ntiles;              // ceil(N / 64)
+#ifdef RBGP_EXPERIMENT
+  unsigned long long *trace;   // [wave][8] timestamps
+#endif
 };
 
 constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
@@ -91,192 +93,267 @@ __device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int
   return f32x4{__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3])};
 }
 
-// KC: contraction steps per stage; RS: weight rows per tile row in a 16-row MFMA group;
-// P: MFMA groups per wave (cluster size U = P * 16 / RS).
-template <int KC, int RS, int P>
+// KC: contraction steps per stage; RS: weight rows per tile row in the 16-row MFMA group
+// (cluster size MG = 16 / RS); WLDS: the weights of the workgroup's (cluster, G_i vertex)
+// are copied to LDS once and read from there (they are the same for every column tile),
+// else they stream from global memory like I.
+template <int KC, int RS, bool WLDS>
 __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
-  constexpr int MG = 16 / RS;            // tile rows per MFMA group
-  constexpr int U = MG * P;
+  constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
-  constexpr int NQ = (NO + 3) / 4;       // weight registers per group and stage come as NQ 16-byte loads
+  constexpr int NQ = (NO + 3) / 4;       // weight registers per stage come as NQ 16-byte loads
   constexpr int QB = 4 * RS * 16;        // bytes of one such load across the fragment
   constexpr int FB = NQ * QB;            // bytes of one weight fragment (one tile row, one G_i vertex)
   constexpr int CW = 64;                 // columns per wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char wlds[];
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-  const int wpw = __builtin_amdgcn_readfirstlane(int(blockDim.x) >> 6);
+#ifdef RBGP_EXPERIMENT
+  unsigned long long *tr = p.trace + (size_t(blockIdx.x) * 4 + wid) * 8;
+  if (lane == 0) { tr[0] = __builtin_amdgcn_s_memrealtime(); tr[5] = __builtin_readcyclecounter(); }
+#endif
 
-  // same columns of I -> same XCD (one L2): workgroups are dealt round-robin to the 8 XCDs
+  // A workgroup is one (cluster, G_i vertex) pair on four neighbouring column tiles.  Same
+  // columns of I -> same XCD (one L2): workgroups are dealt round-robin to the 8 XCDs.
   const int bid = blockIdx.x, xcd = bid & 7, slot = bid >> 3;
-  const int nt = xcd + 8 * (slot / p.wgs_per_tile);
-  const int item = (slot % p.wgs_per_tile) * wpw + wid;
-  if (nt >= p.ntiles || item >= p.items_per_tile) return;
+  const int ntq = xcd + 8 * (slot / p.items), item = slot % p.items;
+  if (ntq * 4 >= p.ntiles) return;
   const int cl = item / p.a3, u3 = item - cl * p.a3;
+  const int nt = ntq * 4 + wid;
   const int64_t n0 = int64_t(nt) * CW;
   const int g = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;    // as a weight lane: member of the group, row of the member
 
+  // Everything the prologue needs is requested at once: cluster members, row table, stage
+  // table (one stage per lane, read back with readlane), stage count.
+  int mem[MG];
+#pragma unroll
+  for (int mm = 0; mm < MG; ++mm) mem[mm] = p.members[cl * MG + mm];
+  const int32_t *rt = p.rowtab + u3 * (NO * 4) + g;
+  int rrow[NO];
+#pragma unroll
+  for (int o = 0; o < NO; ++o) rrow[o] = rt[o * 4];
+  const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * 64 + lane;
+  const int tb = stg[0];
+  int tf[MG];
+#pragma unroll
+  for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
+  const int cnt = p.counts[cl];
+
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
   int off[NO];
-  {
-    const int32_t *rt = p.rowtab + u3 * (NO * 4) + g;
 #pragma unroll
-    for (int o = 0; o < NO; ++o) off[o] = int((int64_t(rt[o * 4]) * p.ldI + j * 4) * 4);
-  }
+  for (int o = 0; o < NO; ++o) off[o] = int((int64_t(rrow[o]) * p.ldI + j * 4) * 4);
   const int alane = (g * RS + ri) * 16;
-
-  // stage table of the cluster, one stage per lane, read back with readlane
-  const int32_t *stg = p.stages + int64_t(cl) * (2 + U) * 64 + lane;
-  const int tb = stg[0], ta = stg[64];
-  int tf[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) tf[u] = stg[(2 + u) * 64];
-  const int cnt = p.counts[cl];
-  // Drain the table loads here: a wait for them inside the loop would run on every
-  // iteration and drain the prefetched stages with it.
-  __builtin_amdgcn_s_waitcnt(0);
-
-  f32x16 acc[P][4];
-#pragma unroll
-  for (int pg = 0; pg < P; ++pg)
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[pg][w][v] = 0.f;
+  const bool valid = nt < p.ntiles;
 
   const __amdgpu_buffer_rsrc_t rw =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.Wp), 0, p.w_bytes, kRsrcFlags);
-
-  // Loads are unconditional so that the wait counts are exact: a stage past the end reads
-  // I through a descriptor of zero extent and a tile row that lacks the tile reads its
-  // weights at an offset past the buffer; both return zeros without touching memory.
+  // A stage past the end reads I through a descriptor of zero extent: zeros, no memory access.
   auto b_rsrc = [&](int s, int *sofs) {
     const int base_row = __builtin_amdgcn_readlane(tb, s);
     *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 4);
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.I), 0, base_row >= 0 ? p.i_bytes : 0u,
-                                             kRsrcFlags);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.I), 0,
+                                             (base_row >= 0 && valid) ? p.i_bytes : 0u, kRsrcFlags);
   };
-  // per-lane byte offset of the weights of MFMA group pg at stage s
-  auto a_voff = [&](int s, int pg) {
-    int voff = kOob;
+
+  f32x4 B0[NO], B1[NO];
+  f32x4 A0[NQ], A1[NQ];
+  if constexpr (WLDS) {
+    // the first two stages of I are requested before the weights are copied to LDS
+    {
+      int sofs;
+      const __amdgpu_buffer_rsrc_t r0 = b_rsrc(0, &sofs);
+#pragma unroll
+      for (int o = 0; o < NO; ++o) B0[o] = load_x4(r0, off[o], sofs);
+      const __amdgpu_buffer_rsrc_t r1 = b_rsrc(1, &sofs);
+#pragma unroll
+      for (int o = 0; o < NO; ++o) B1[o] = load_x4(r1, off[o], sofs);
+    }
+    // copy the fragments of all members (fpm each) and one all-zero fragment to LDS,
+    // eight 16-byte pieces per thread in flight
+    constexpr int C16 = FB / 16;
+    const int total = (MG * p.fpm + 1) * C16;
+    for (int base = 0; base < total; base += 8 * 256) {
+      f32x4 v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int idx = base + k * 256 + int(threadIdx.x);
+        const int f = idx / C16, c16 = idx - f * C16;
+        const int mm = f / p.fpm, fi = f - mm * p.fpm;
+        int u1 = -1;
+#pragma unroll
+        for (int t = 0; t < MG; ++t) u1 = mm == t ? mem[t] : u1;
+        v[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (idx < total && u1 >= 0)
+          v[k] = *reinterpret_cast<const f32x4 *>(p.Wp + ((int64_t(u1) * p.fpm + fi) * p.a3 + u3) * (FB / 4) + c16 * 4);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int idx = base + k * 256 + int(threadIdx.x);
+        if (idx < total) *reinterpret_cast<f32x4 *>(wlds + idx * 16) = v[k];
+      }
+    }
+    __syncthreads();
+  }
+  if (!valid) return;
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
+#endif
+  // Drain every outstanding load count here: a wait for the table loads inside the loop
+  // would run on every iteration and drain the prefetched stages with it.
+  if constexpr (!WLDS) __builtin_amdgcn_s_waitcnt(0);
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[w][v] = 0.f;
+
+  // Loads are unconditional so that the wait counts are exact: a stage past the end reads
+  // zeros (see b_rsrc); a tile row that lacks the tile reads the zero fragment (LDS) or an
+  // offset past the weight buffer (global), which returns zeros.
+  // per-lane byte address (LDS) or offset (global) of the stage's weights
+  auto a_addr = [&](int s) {
+    int addr = 0;
 #pragma unroll
     for (int mm = 0; mm < MG; ++mm) {
-      const int frag = __builtin_amdgcn_readlane(tf[pg * MG + mm], s);
-      const int sv = frag >= 0 ? (frag + u3) * FB : kOob;
-      voff = mi == mm ? sv : voff;
+      const int fi = __builtin_amdgcn_readlane(tf[mm], s);
+      int sv;
+      if constexpr (WLDS)
+        sv = (fi >= 0 ? mm * p.fpm + fi : MG * p.fpm) * FB;
+      else
+        sv = (fi >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
+      addr = mi == mm ? sv : addr;
     }
-    return voff + alane;
+    return addr + alane;
   };
+  auto a_load = [&](int addr, int q) {
+    if constexpr (WLDS)
+      return *reinterpret_cast<const f32x4 *>(wlds + addr + q * QB);
+    else
+      return load_x4(rw, addr, q * QB);
+  };
+
   // One stage: MFMAs of stage s from (B, A); every B slot and every weight quad is
-  // refilled for stage s + 2 right after its last use.  One uniform branch per MFMA group
-  // and stage; the last group's pass does the refills, and both sides of its branch issue
-  // the same loads in the same order.
-  auto stage = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[P][NQ]) {
-    const int active = __builtin_amdgcn_readlane(ta, s);
-    int sofs;
-    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(s + 2, &sofs);
-    int av[P];
+  // refilled for stage s + 2 right after its last use (RELOAD), so that about two stages
+  // of loads are in flight at any time.  Every real stage has work (the stage list is the
+  // union of the cluster's tiles), so the loop body is branch-free and its wait counts
+  // are exact.
+  auto stage = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NQ], auto reload) {
+    constexpr bool RELOAD = decltype(reload)::value;
+    int sofs = 0, av = 0;
+    __amdgpu_buffer_rsrc_t rb2 = rw;
+    if constexpr (RELOAD) {
+      rb2 = b_rsrc(s + 2, &sofs);
+      av = a_addr(s + 2);
+    }
+    static_for<0, NO>([&](auto oc) {
+      constexpr int o = decltype(oc)::value;
+      const float a = A[o / 4][o % 4];
 #pragma unroll
-    for (int pg = 0; pg < P; ++pg) av[pg] = a_voff(s + 2, pg);
-    static_for<0, P>([&](auto pgc) {
-      constexpr int pg = decltype(pgc)::value;
-      if (active & (1 << pg)) {
-        static_for<0, NO>([&](auto oc) {
-          constexpr int o = decltype(oc)::value;
-          const float a = A[pg][o / 4][o % 4];
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            acc[pg][w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, B[o][w], acc[pg][w], 0, 0, 0);
-          if constexpr (pg == P - 1) {
-            B[o] = load_x4(rb2, off[o], sofs);
-            if constexpr (o % 4 == 3 || o == NO - 1) {
-#pragma unroll
-              for (int p2 = 0; p2 < P; ++p2) A[p2][o / 4] = load_x4(rw, av[p2], (o / 4) * QB);
-            }
-          }
-        });
-      } else if constexpr (pg == P - 1) {
-        static_for<0, NO>([&](auto oc) {
-          constexpr int o = decltype(oc)::value;
-          B[o] = load_x4(rb2, off[o], sofs);
-          if constexpr (o % 4 == 3 || o == NO - 1) {
-#pragma unroll
-            for (int p2 = 0; p2 < P; ++p2) A[p2][o / 4] = load_x4(rw, av[p2], (o / 4) * QB);
-          }
-        });
+      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, B[o][w], acc[w], 0, 0, 0);
+      if constexpr (RELOAD) {
+        B[o] = load_x4(rb2, off[o], sofs);
+        if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
+        __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
       }
     });
   };
+  // loads of stage s in the same order as the refills above
+  auto fill = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NQ]) {
+    int sofs;
+    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(s, &sofs);
+    const int av = a_addr(s);
+    static_for<0, NO>([&](auto oc) {
+      constexpr int o = decltype(oc)::value;
+      B[o] = load_x4(rb2, off[o], sofs);
+      if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
 
-  // Two register sets alternate.  The first two passes find only sentinel stages (lanes 0
-  // and 1 of the table): they multiply nothing and just start the loads of the first two
-  // real stages, so the loop needs no separate prologue and every wait count is exact.
-  f32x4 B0[NO], B1[NO];
-  f32x4 A0[P][NQ], A1[P][NQ];
+  // Two register sets alternate; stages past the end read zeros (sentinel table lanes).
+  if constexpr (WLDS) {
+    const int av0 = a_addr(0), av1 = a_addr(1);
 #pragma unroll
-  for (int o = 0; o < NO; ++o) B0[o] = B1[o] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < NQ; ++q) A0[q] = a_load(av0, q);
 #pragma unroll
-  for (int pg = 0; pg < P; ++pg)
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) A0[pg][q] = A1[pg][q] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < cnt + 2; s += 2) {
-    stage(s, B0, A0);
-    stage(s + 1, B1, A1);
+    for (int q = 0; q < NQ; ++q) A1[q] = a_load(av1, q);
+  } else {
+    fill(0, B0, A0);
+    fill(1, B1, A1);
   }
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[2] = __builtin_amdgcn_s_memrealtime();
+#endif
+  int s = 0;
+  for (; s + 1 < cnt; s += 2) {
+    stage(s, B0, A0, std::true_type{});
+    stage(s + 1, B1, A1, std::true_type{});
+  }
+  if (s < cnt) stage(s, B0, A0, std::false_type{});
+  __builtin_amdgcn_s_waitcnt(0);
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); tr[7] = cnt; }
+#endif
 
   // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Register t of the sum
   // holds weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
   const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
 #pragma unroll
-  for (int pg = 0; pg < P; ++pg) {
+  for (int t = 0; t < 4; ++t) {
+    float v[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      float v[4];
+    for (int w = 0; w < 4; ++w) v[w] = (acc[w][t] + acc[w][4 + t]) + (acc[w][8 + t] + acc[w][12 + t]);
+    const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
+    int u1 = mem[0];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) v[w] = (acc[pg][w][t] + acc[pg][w][4 + t]) + (acc[pg][w][8 + t] + acc[pg][w][12 + t]);
-      const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
-      const int u1 = p.members[cl * U + pg * MG + mm];
-      if (u1 >= 0 && r < p.R) {
-        const int u2 = r / p.a4, u4 = r - u2 * p.a4;
-        const int64_t m = ((int64_t(u1) * p.a2 + u2) * p.a3 + u3) * p.a4 + u4;
-        float *o = p.O + m * p.ldO + n0 + j * 4;
-        if (vec_ok) {
-          *reinterpret_cast<f32x4 *>(o) = f32x4{v[0], v[1], v[2], v[3]};
-        } else {
+    for (int q = 1; q < MG; ++q) u1 = mm == q ? mem[q] : u1;
+    if (u1 >= 0 && r < p.R) {
+      const int u2 = r / p.a4, u4 = r - u2 * p.a4;
+      const int64_t m = ((int64_t(u1) * p.a2 + u2) * p.a3 + u3) * p.a4 + u4;
+      float *o = p.O + m * p.ldO + n0 + j * 4;
+      if (vec_ok) {
+        *reinterpret_cast<f32x4 *>(o) = f32x4{v[0], v[1], v[2], v[3]};
+      } else {
 #pragma unroll
-          for (int w = 0; w < 4; ++w)
-            if (n0 + j * 4 + w < p.N) o[w] = v[w];
-        }
+        for (int w = 0; w < 4; ++w)
+          if (n0 + j * 4 + w < p.N) o[w] = v[w];
       }
     }
   }
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) { tr[4] = __builtin_amdgcn_s_memrealtime(); tr[6] = __builtin_readcyclecounter(); }
+#endif
 }
 
 typedef void (*reg_fn)(RegParams);
 struct RegEntry {
-  int KC, RS, P;
-  reg_fn fn;
+  int KC, RS;
+  reg_fn lds_fn, global_fn;
 };
-#define RBGP_R(KC, RS) {KC, RS, 1, spmm_reg<KC, RS, 1>}, {KC, RS, 2, spmm_reg<KC, RS, 2>}
+#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>}
 const RegEntry kRegTable[] = {RBGP_R(8, 4),  RBGP_R(18, 2), RBGP_R(36, 2), RBGP_R(72, 2),
                               RBGP_R(18, 4), RBGP_R(36, 4), RBGP_R(72, 4),
                               RBGP_R(18, 8), RBGP_R(36, 8), RBGP_R(72, 8)};
 
-const RegEntry *find_reg(int KC, int RS, int P) {
+const RegEntry *find_reg(int KC, int RS) {
   for (const RegEntry &e : kRegTable)
-    if (e.KC == KC && e.RS == RS && e.P == P) return &e;
+    if (e.KC == KC && e.RS == RS) return &e;
   return nullptr;
 }
 
-struct RegTables {  // device tables for one cluster size U
-  int U = 0, ncl = 0, smax = 0;
+struct RegTables {  // device tables of the clustering
+  int ncl = 0;
   int32_t *stages = nullptr, *counts = nullptr, *members = nullptr;
 };
 
 struct RegState {
   int32_t *rowtab = nullptr;
-  std::map<int, RegTables> by_u;
+  RegTables tab;
+  bool lds_attr_set[2] = {false, false};
 };
 
 template <typename T>
@@ -286,12 +363,13 @@ int upload(const std::vector<T> &h, T **d) {
   return RBGP_OK;
 }
 
-// Group the tile rows into clusters of U whose adjacency lists overlap most
-// (greedy: seed with the lowest free tile row, add the free row that enlarges the
-// union of tiles least), and list for every cluster the stages it walks.
-int build_tables(const rbgp_mask *m, int U, RegTables *t) {
+// Group the tile rows into clusters of U = MG whose adjacency lists overlap most (greedy:
+// seed with the lowest free tile row, add the free row that enlarges the union of tiles
+// least), and list for every cluster the stages it walks.
+int build_tables(const rbgp_mask *m, RegTables *t) {
   const rbgp_reg_plan &pl = m->reg;
-  const int a1 = m->a[0], c1 = m->c[0], d1 = m->d[0], a3 = m->a[2];
+  const int U = pl.MG;
+  const int a1 = m->a[0], c1 = m->c[0], d1 = m->d[0];
   const int ncl = (a1 + U - 1) / U;
   std::vector<int32_t> members(size_t(ncl) * U, -1);
   std::vector<char> used(a1, 0);
@@ -314,44 +392,59 @@ int build_tables(const rbgp_mask *m, int U, RegTables *t) {
       for (int v = 0; v < c1; ++v) uni[v] |= has[best][v];
     }
   }
+  // Local search: swap members between two clusters while that lowers the larger of their
+  // two unions, or keeps it and lowers the sum.  The longest cluster sets the kernel's
+  // duration (one wave per SIMD), the sum its total work.
+  auto union_size = [&](int c) {
+    int n = 0;
+    for (int v = 0; v < c1; ++v) {
+      bool any = false;
+      for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v];
+      n += any;
+    }
+    return n;
+  };
+  for (bool improved = true; improved;) {
+    improved = false;
+    for (int ca = 0; ca < ncl; ++ca)
+      for (int cb = ca + 1; cb < ncl; ++cb)
+        for (int ka = 0; ka < U; ++ka)
+          for (int kb = 0; kb < U; ++kb) {
+            const int ua = union_size(ca), ub = union_size(cb);
+            std::swap(members[size_t(ca) * U + ka], members[size_t(cb) * U + kb]);
+            const int na = union_size(ca), nb = union_size(cb);
+            const bool better = std::max(na, nb) < std::max(ua, ub) ||
+                                (std::max(na, nb) == std::max(ua, ub) && na + nb < ua + ub);
+            if (better)
+              improved = true;
+            else
+              std::swap(members[size_t(ca) * U + ka], members[size_t(cb) * U + kb]);
+          }
+  }
   std::vector<int32_t> counts(ncl, 0);
-  std::vector<std::vector<int32_t>> rows(ncl);
-  int smax = 0;
+  std::vector<int32_t> stages(size_t(ncl) * (1 + U) * 64, -1);
   for (int c = 0; c < ncl; ++c) {
+    int st = 0;
     for (int v1 = 0; v1 < c1; ++v1) {
       bool any = false;
       for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v1];
       if (!any) continue;
-      for (int sg = 0; sg < pl.NSTG; ++sg) {
-        rows[c].push_back(int32_t((int64_t(v1) * m->c[1] + int64_t(sg) * pl.VC) * m->c[2] * m->c[3]));
-        int active = 0;
-        for (int k = 0; k < U; ++k)
-          if (members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v1]) active |= 1 << (k / pl.MG);
-        rows[c].push_back(active);
+      for (int sg = 0; sg < pl.NSTG; ++sg, ++st) {
+        if (st >= 60) return RBGP_EUNSUPPORTED;   // one stage per lane plus sentinels
+        stages[(size_t(c) * (1 + U)) * 64 + st] =
+            int32_t((int64_t(v1) * m->c[1] + int64_t(sg) * pl.VC) * m->c[2] * m->c[3]);
         for (int k = 0; k < U; ++k) {
           const int u1 = members[size_t(c) * U + k];
-          int frag = -1;
-          if (u1 >= 0 && has[u1][v1]) {
-            int j1 = 0;
-            while (m->adj[0][size_t(u1) * d1 + j1] != v1) ++j1;
-            frag = int32_t(((int64_t(u1) * d1 + j1) * pl.NSTG + sg) * a3);
-          }
-          rows[c].push_back(frag);
+          if (u1 < 0 || !has[u1][v1]) continue;
+          int j1 = 0;
+          while (m->adj[0][size_t(u1) * d1 + j1] != v1) ++j1;
+          stages[(size_t(c) * (1 + U) + 1 + k) * 64 + st] = j1 * pl.NSTG + sg;
         }
-        ++counts[c];
       }
     }
-    smax = std::max(smax, counts[c]);
+    counts[c] = st;
   }
-  if (smax > 58) return RBGP_EUNSUPPORTED;   // one stage per lane plus sentinels
-  std::vector<int32_t> stages(size_t(ncl) * (2 + U) * 64, -1);
-  for (int c = 0; c < ncl; ++c) {
-    for (int ln = 0; ln < 64; ++ln) stages[(size_t(c) * (2 + U) + 1) * 64 + ln] = 0;   // no group has work
-    for (int st = 0; st < counts[c]; ++st)
-      for (int f = 0; f < 2 + U; ++f)
-        stages[(size_t(c) * (2 + U) + f) * 64 + 2 + st] = rows[c][size_t(st) * (2 + U) + f];
-  }
-  t->U = U; t->ncl = ncl; t->smax = smax;
+  t->ncl = ncl;
   int rc = upload(stages, &t->stages);
   if (rc) return rc;
   rc = upload(counts, &t->counts);
@@ -364,23 +457,22 @@ int build_tables(const rbgp_mask *m, int U, RegTables *t) {
 bool rbgp_reg_covers(const rbgp_mask *m) {
   const rbgp_reg_plan &p = m->reg;
   if (!p.ok) return false;
-  if (int64_t(m->M) * m->rowdeg * 2 >= (int64_t(1) << 31)) return false;
-  return find_reg(p.KC, p.RS, 1) != nullptr;
+  // every cluster's stage list must fit the per-lane table: at most |G_o.V| * NSTG stages
+  if (int64_t(std::min(m->c[0], m->d[0] * p.MG)) * p.NSTG > 60) return false;
+  return find_reg(p.KC, p.RS) != nullptr;
 }
 
 void rbgp_reg_release(void *state) {
   RegState *st = static_cast<RegState *>(state);
   if (!st) return;
   if (st->rowtab) (void)hipFree(st->rowtab);
-  for (auto &kv : st->by_u) {
-    if (kv.second.stages) (void)hipFree(kv.second.stages);
-    if (kv.second.counts) (void)hipFree(kv.second.counts);
-    if (kv.second.members) (void)hipFree(kv.second.members);
-  }
+  if (st->tab.stages) (void)hipFree(st->tab.stages);
+  if (st->tab.counts) (void)hipFree(st->tab.counts);
+  if (st->tab.members) (void)hipFree(st->tab.members);
   delete st;
 }
 
-int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_u, int64_t N, const void *packed, const void *I,
+int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, const void *packed, const void *I,
                     int64_t ldI, float *O, int64_t ldO, void *stream) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
@@ -404,48 +496,65 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_u, int64_t N, con
     int rc = upload(rt, &st->rowtab);
     if (rc) return rc;
   }
-  const int cw = 64;
-  const int64_t ntiles = (N + cw - 1) / cw;
-  // MFMA groups per wave (cluster size U = P * MG): 2 if the launch then still has >= 1024
-  // waves (one per SIMD) and the cluster's stage list fits the per-lane table, else 1
-  int P = tune_u;
-  const bool auto_p = P <= 0;
-  if (auto_p) P = (int64_t((m->a[0] + 2 * pl.MG - 1) / (2 * pl.MG)) * m->a[2] * ntiles >= 1024) ? 2 : 1;
-  const RegEntry *e = nullptr;
-  RegTables *tp = nullptr;
-  int U = 0;
-  for (;; --P) {
-    e = find_reg(pl.KC, pl.RS, P);
-    if (!e) return RBGP_EUNSUPPORTED;
-    U = P * pl.MG;
-    tp = &st->by_u[U];
-    int rc = tp->stages ? RBGP_OK : build_tables(m, U, tp);
-    if (rc == RBGP_OK) break;
-    if (rc != RBGP_EUNSUPPORTED || !auto_p || P == 1) return rc;
+  if (!st->tab.stages) {
+    int rc = build_tables(m, &st->tab);
+    if (rc) return rc;
   }
-  RegTables &t = *tp;
+  const RegEntry *e = find_reg(pl.KC, pl.RS);
+  if (!e) return RBGP_EUNSUPPORTED;
+  const int64_t ntiles = (N + 63) / 64;
+  const int fpm = m->d[0] * pl.NSTG;
+  const int fb = pl.NQ * 4 * pl.RS * 16;
+  const size_t lds = size_t(pl.MG * fpm + 1) * fb;
+  // Weights stream from global memory by default: measured on the VGG19 conv5 shape, copying
+  // them to LDS first costs more at the start of the kernel than the cheaper stages give
+  // back.  The tuning knob (value 2) selects the LDS variant whenever they fit.
+  const bool wlds = tune_wlds == 2 && lds <= 160 * 1024;
+
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
   rp.I = static_cast<const float *>(I);
   rp.O = O;
   rp.rowtab = st->rowtab;
-  rp.stages = t.stages; rp.counts = t.counts; rp.members = t.members;
+  rp.stages = st->tab.stages; rp.counts = st->tab.counts; rp.members = st->tab.members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
   rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
-  rp.items_per_tile = t.ncl * m->a[2];
-  const int wpw = 4;
-  rp.wgs_per_tile = (rp.items_per_tile + wpw - 1) / wpw;
+  rp.fpm = fpm;
+  rp.items = st->tab.ncl * m->a[2];
   rp.ntiles = int(ntiles);
-#ifdef RBGP_EXPERIMENT
-  rp.mode = getenv("RBGP_MODE") ? atoi(getenv("RBGP_MODE")) : 0;
-#endif
-#ifdef RBGP_EXPERIMENT
-  rp.mode = getenv("RBGP_MODE") ? atoi(getenv("RBGP_MODE")) : 0;
-#endif
-  const int64_t nblocks = 8 * ((ntiles + 7) / 8) * rp.wgs_per_tile;
+  const int64_t nquads = (ntiles + 3) / 4;
+  const int64_t nblocks = 8 * ((nquads + 7) / 8) * rp.items;
   if (nblocks > 0x7fffffff) return RBGP_EUNSUPPORTED;
-  hipLaunchKernelGGL(e->fn, dim3(unsigned(nblocks)), dim3(wpw * 64), 0, static_cast<hipStream_t>(stream), rp);
+  reg_fn fn = wlds ? e->lds_fn : e->global_fn;
+  if (wlds && lds > 64 * 1024 && !st->lds_attr_set[0]) {
+    RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 int(lds)));
+    st->lds_attr_set[0] = true;
+  }
+#ifdef RBGP_EXPERIMENT
+  static unsigned long long *trace_buf = nullptr;
+  static int launches = 0;
+  const size_t trace_n = size_t(nblocks) * 4 * 8;
+  if (!trace_buf) RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&trace_buf), (size_t(1) << 24)));
+  rp.trace = trace_buf;
+  ++launches;
+  const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
+  if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
+#endif
+  hipLaunchKernelGGL(fn, dim3(unsigned(nblocks)), dim3(256), wlds ? lds : 0, static_cast<hipStream_t>(stream), rp);
+#ifdef RBGP_EXPERIMENT
+  if (dump) {
+    RBGP_HIP(hipDeviceSynchronize());
+    std::vector<unsigned long long> h(trace_n);
+    RBGP_HIP(hipMemcpy(h.data(), trace_buf, trace_n * 8, hipMemcpyDeviceToHost));
+    FILE *f = fopen(getenv("RBGP_TRACE"), "w");
+    for (size_t i = 0; i < trace_n; i += 8)
+      fprintf(f, "%zu %llu %llu %llu %llu %llu %llu %llu %llu\n", i / 8, h[i], h[i + 1], h[i + 2], h[i + 3], h[i + 4],
+              h[i + 5], h[i + 6], h[i + 7]);
+    fclose(f);
+  }
+#endif
   RBGP_HIP(hipGetLastError());
   return RBGP_OK;
 }

@@ -33,7 +33,7 @@ def test_config_tile_shapes(w, tune):
     gh.check_parity(w, N=1536 if w.N > 4096 else w.N, kernel=MFMA, tune=tune)
 
 
-@pytest.mark.parametrize("cluster", [1, 2])
+@pytest.mark.parametrize("cluster", [0, 1, 2])
 @pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.WRN_G1], ids=lambda w: w.name)
 def test_config_register_family_cluster_sizes(w, cluster):
     gh.check_parity(w, N=1000 if w.N > 4096 else w.N, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
