@@ -25,6 +25,9 @@ if ROOT not in sys.path:
 from paper_2006_13486_amd import binding as rb      # noqa: E402
 from paper_2006_13486_amd import workloads as wl    # noqa: E402
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
+# scaled by what the same counters read for a 64 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 PEAK_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix (= packed vector) peak
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 WORKLOADS = {"conv5": wl.VGG19_CONV5, "conv3": wl.VGG19_CONV3_BF16, "wrn": wl.WRN_G1, "tiny": wl.TINY}
@@ -67,6 +70,9 @@ def main():
     ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run ten 64 MiB device-to-device copies and exit (reference for the FETCH_SIZE / "
+                         "WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (sharding along N is described in DESIGN.md); use --gpus 1")
@@ -75,6 +81,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        a = torch.empty(64 * 2**20 // 4, device=dev, dtype=torch.float32).normal_()
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": a.numel() * 4, "copies": 10}))
+        return
     w = WORKLOADS[args.workload]
     bf16 = w.dtype == wl.BF16
 
@@ -131,6 +145,11 @@ def main():
         achieved = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            roof["traffic"] = json.load(f).get(w.name, {}).get("hbm_bytes_per_launch")
+    except OSError:
+        pass
     roof["kernel_ms"] = kern_ms
     roof["algorithmic_bytes"] = w.algorithmic_bytes
     roof["algorithmic_flops"] = w.flops
