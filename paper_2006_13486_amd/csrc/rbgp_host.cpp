@@ -173,7 +173,8 @@ void rbgp_plan_reg(rbgp_mask *m) {
     p.MG = 16 / p.RS;
     p.NO = (p.KC + 3) / 4;
     p.NQ = (p.NO + 3) / 4;
-    p.packed_elems = int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] * p.NQ * 4 * p.RS * 4;
+    // one more all-zero fragment ends the buffer
+    p.packed_elems = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * p.NQ * 4 * p.RS * 4;
   }
   m->reg = p;
 }

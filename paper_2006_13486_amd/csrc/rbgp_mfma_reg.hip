@@ -78,7 +78,10 @@ struct RegParams {
   uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
   int a2, a3, a4, R;
   int fpm;                 // weight fragments per member: d_o * NSTG
-  int items;               // ncl * a3: (cluster, G_i vertex) pairs = workgroups per 4 column tiles
+  int zero_frag;           // index of the all-zero fragment that ends the packed buffer
+  int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
+  int tm;                  // rows of one tile row: a_r * a_i * a_b
+  const int32_t *wsrc;     // [ncl][64]: per LDS fragment slot the packed fragment index of u_i = 0, -1: zeros
   int ntiles;              // ceil(N / 64)
 #ifdef RBGP_EXPERIMENT
   unsigned long long *trace;   // [wave][8] timestamps
@@ -109,16 +112,16 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
 #ifdef RBGP_EXPERIMENT
-  unsigned long long *tr = p.trace + (size_t(blockIdx.x) * 4 + wid) * 8;
+  unsigned long long *tr = p.trace + ((size_t(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + wid * 8;
   if (lane == 0) { tr[0] = __builtin_amdgcn_s_memrealtime(); tr[5] = __builtin_readcyclecounter(); }
 #endif
 
   // A workgroup is one (cluster, G_i vertex) pair on four neighbouring column tiles.  Same
   // columns of I -> same XCD (one L2): workgroups are dealt round-robin to the 8 XCDs.
-  const int bid = blockIdx.x, xcd = bid & 7, slot = bid >> 3;
-  const int ntq = xcd + 8 * (slot / p.items), item = slot % p.items;
+  // (grid x = 8 * clusters is a multiple of 8, so the XCD of a workgroup is x & 7 whatever y, z)
+  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.z;
+  const int ntq = xcd + 8 * int(blockIdx.y);
   if (ntq * 4 >= p.ntiles) return;
-  const int cl = item / p.a3, u3 = item - cl * p.a3;
   const int nt = ntq * 4 + wid;
   const int64_t n0 = int64_t(nt) * CW;
   const int g = lane >> 4, j = lane & 15;
@@ -139,12 +142,13 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #pragma unroll
   for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
   const int cnt = p.counts[cl];
+  const int rov = p.rowofs[lane & 15];   // lane-held copy, read back with bpermute in the epilogue
 
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
   int off[NO];
 #pragma unroll
-  for (int o = 0; o < NO; ++o) off[o] = int((int64_t(rrow[o]) * p.ldI + j * 4) * 4);
+  for (int o = 0; o < NO; ++o) off[o] = rrow[o] * (int(p.ldI) * 4) + j * 16;   // < 2^31: checked by the host
   const int alane = (g * RS + ri) * 16;
   const bool valid = nt < p.ntiles;
 
@@ -161,45 +165,43 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   f32x4 B0[NO], B1[NO];
   f32x4 A0[NQ], A1[NQ];
   if constexpr (WLDS) {
-    // the first two stages of I are requested before the weights are copied to LDS
+    // the first stage of I is requested before the weights are copied to LDS
     {
       int sofs;
       const __amdgpu_buffer_rsrc_t r0 = b_rsrc(0, &sofs);
 #pragma unroll
       for (int o = 0; o < NO; ++o) B0[o] = load_x4(r0, off[o], sofs);
-      const __amdgpu_buffer_rsrc_t r1 = b_rsrc(1, &sofs);
-#pragma unroll
-      for (int o = 0; o < NO; ++o) B1[o] = load_x4(r1, off[o], sofs);
     }
-    // copy the fragments of all members (fpm each) and one all-zero fragment to LDS,
-    // eight 16-byte pieces per thread in flight
+    // Copy the fragments of all members (fpm each) and one all-zero fragment to LDS with
+    // direct global->LDS loads (1 KB per wave instruction, no VGPR round trip).  The packed
+    // buffer ends with an all-zero fragment, the source for members the cluster lacks.
+#ifdef RBGP_EXPERIMENT
+    if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
+#endif
     constexpr int C16 = FB / 16;
-    const int total = (MG * p.fpm + 1) * C16;
-    for (int base = 0; base < total; base += 8 * 256) {
-      f32x4 v[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int idx = base + k * 256 + int(threadIdx.x);
-        const int f = idx / C16, c16 = idx - f * C16;
-        const int mm = f / p.fpm, fi = f - mm * p.fpm;
-        int u1 = -1;
-#pragma unroll
-        for (int t = 0; t < MG; ++t) u1 = mm == t ? mem[t] : u1;
-        v[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (idx < total && u1 >= 0)
-          v[k] = *reinterpret_cast<const f32x4 *>(p.Wp + ((int64_t(u1) * p.fpm + fi) * p.a3 + u3) * (FB / 4) + c16 * 4);
-      }
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int idx = base + k * 256 + int(threadIdx.x);
-        if (idx < total) *reinterpret_cast<f32x4 *>(wlds + idx * 16) = v[k];
-      }
+    const int nchunks = (MG * p.fpm + 1) * C16;
+    const int ninstr = (nchunks + 63) / 64;
+    const int wtab = p.wsrc[cl * 64 + lane];   // fragment slot -> packed fragment (lane-held table)
+    for (int i = wid; i < ninstr; i += 4) {
+      const int idx = i * 64 + lane;
+      const int idc = idx < nchunks ? idx : nchunks - 1;
+      const int f = idc / C16, c16 = idc - f * C16;
+      const int b = __builtin_amdgcn_ds_bpermute(f * 4, wtab);
+      const int frag = b >= 0 ? b + u3 : p.zero_frag;
+      const float *src = p.Wp + int64_t(frag) * (FB / 4) + c16 * 4;
+      if (idx < nchunks)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)(wlds + i * 1024), 16, 0, 0);
     }
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0);   // this wave's direct loads have landed in LDS
+#ifdef RBGP_EXPERIMENT
+    if (lane == 0) tr[7] = __builtin_amdgcn_s_memrealtime();
+#endif
+    __syncthreads();                 // ... and everybody else's
   }
   if (!valid) return;
 #ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
+  if (lane == 0) tr[6] = __builtin_amdgcn_s_memrealtime();
 #endif
   // Drain every outstanding load count here: a wait for the table loads inside the loop
   // would run on every iteration and drain the prefetched stages with it.
@@ -274,29 +276,48 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     });
   };
 
+  // Stage 0 starts as soon as its own data is there: the loads of stage 1 (into the second
+  // register set) and the refills for stage 2 are issued between its MFMAs.
+  auto first_stage = [&](f32x4 (&B)[NO], f32x4 (&A)[NQ], f32x4 (&Bn)[NO], f32x4 (&An)[NQ]) {
+    int sofs1, sofs2;
+    const __amdgpu_buffer_rsrc_t rb1 = b_rsrc(1, &sofs1), rb2 = b_rsrc(2, &sofs2);
+    const int av1 = a_addr(1), av2 = a_addr(2);
+    static_for<0, NO>([&](auto oc) {
+      constexpr int o = decltype(oc)::value;
+      const float a = A[o / 4][o % 4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, B[o][w], acc[w], 0, 0, 0);
+      Bn[o] = load_x4(rb1, off[o], sofs1);
+      B[o] = load_x4(rb2, off[o], sofs2);
+      if constexpr (o % 4 == 3 || o == NO - 1) {
+        An[o / 4] = a_load(av1, o / 4);
+        A[o / 4] = a_load(av2, o / 4);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
   // Two register sets alternate; stages past the end read zeros (sentinel table lanes).
   if constexpr (WLDS) {
-    const int av0 = a_addr(0), av1 = a_addr(1);
+    const int av0 = a_addr(0);
 #pragma unroll
     for (int q = 0; q < NQ; ++q) A0[q] = a_load(av0, q);
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) A1[q] = a_load(av1, q);
   } else {
     fill(0, B0, A0);
-    fill(1, B1, A1);
   }
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[2] = __builtin_amdgcn_s_memrealtime();
-#endif
-  int s = 0;
-  for (; s + 1 < cnt; s += 2) {
-    stage(s, B0, A0, std::true_type{});
-    stage(s + 1, B1, A1, std::true_type{});
+  first_stage(B0, A0, B1, A1);
+  if (cnt > 1) {   // the loop is reachable only through stage 1, which keeps its wait counts exact
+    stage(1, B1, A1, std::true_type{});
+    int s = 2;
+    for (; s + 1 < cnt; s += 2) {
+      stage(s, B0, A0, std::true_type{});
+      stage(s + 1, B1, A1, std::true_type{});
+    }
+    if (s < cnt) stage(s, B0, A0, std::false_type{});
   }
-  if (s < cnt) stage(s, B0, A0, std::false_type{});
   __builtin_amdgcn_s_waitcnt(0);
 #ifdef RBGP_EXPERIMENT
-  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); tr[7] = cnt; }
+  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); }
 #endif
 
   // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Register t of the sum
@@ -311,9 +332,9 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     int u1 = mem[0];
 #pragma unroll
     for (int q = 1; q < MG; ++q) u1 = mm == q ? mem[q] : u1;
+    const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
     if (u1 >= 0 && r < p.R) {
-      const int u2 = r / p.a4, u4 = r - u2 * p.a4;
-      const int64_t m = ((int64_t(u1) * p.a2 + u2) * p.a3 + u3) * p.a4 + u4;
+      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
       float *o = p.O + m * p.ldO + n0 + j * 4;
       if (vec_ok) {
         *reinterpret_cast<f32x4 *>(o) = f32x4{v[0], v[1], v[2], v[3]};
@@ -325,7 +346,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     }
   }
 #ifdef RBGP_EXPERIMENT
-  if (lane == 0) { tr[4] = __builtin_amdgcn_s_memrealtime(); tr[6] = __builtin_readcyclecounter(); }
+  if (lane == 0) { tr[4] = __builtin_amdgcn_s_memrealtime(); }
 #endif
 }
 
@@ -347,7 +368,7 @@ const RegEntry *find_reg(int KC, int RS) {
 
 struct RegTables {  // device tables of the clustering
   int ncl = 0;
-  int32_t *stages = nullptr, *counts = nullptr, *members = nullptr;
+  int32_t *stages = nullptr, *counts = nullptr, *members = nullptr, *wsrc = nullptr;
 };
 
 struct RegState {
@@ -421,6 +442,53 @@ int build_tables(const rbgp_mask *m, RegTables *t) {
               std::swap(members[size_t(ca) * U + ka], members[size_t(cb) * U + kb]);
           }
   }
+  // Pairs (U == 2): exhaustive matching by depth-first search with the local-search result
+  // as the bound, minimising (largest union, sum of unions); bounded effort.
+  if (U == 2 && a1 % 2 == 0 && a1 <= 64) {
+    std::vector<std::vector<int>> un(a1, std::vector<int>(a1, 0));
+    for (int x = 0; x < a1; ++x)
+      for (int y = 0; y < a1; ++y) {
+        int n = 0;
+        for (int v = 0; v < c1; ++v) n += has[x][v] || has[y][v];
+        un[x][y] = n;
+      }
+    int best_max = 0, best_sum = 0;
+    for (int c = 0; c < ncl; ++c) {
+      const int n = un[members[2 * c]][members[2 * c + 1]];
+      best_max = std::max(best_max, n);
+      best_sum += n;
+    }
+    std::vector<int32_t> cur(members.size()), best = members;
+    std::vector<char> taken(a1, 0);
+    long budget = 4000000;
+    // recursive lambda via explicit std::function-free trick
+    struct Rec {
+      const std::vector<std::vector<int>> &un; std::vector<int32_t> &cur, &best; std::vector<char> &taken;
+      int a1; int &best_max, &best_sum; long &budget;
+      void go(int depth, int cmax, int csum) {
+        if (budget-- <= 0) return;
+        int x = 0;
+        while (x < a1 && taken[x]) ++x;
+        if (x == a1) {
+          if (cmax < best_max || (cmax == best_max && csum < best_sum)) { best_max = cmax; best_sum = csum; best = cur; }
+          return;
+        }
+        taken[x] = 1;
+        for (int y = x + 1; y < a1; ++y) {
+          if (taken[y]) continue;
+          const int n = un[x][y], nmax = std::max(cmax, n), nsum = csum + n;
+          if (nmax > best_max || (nmax == best_max && nsum >= best_sum)) continue;
+          taken[y] = 1;
+          cur[2 * depth] = x; cur[2 * depth + 1] = y;
+          go(depth + 1, nmax, nsum);
+          taken[y] = 0;
+        }
+        taken[x] = 0;
+      }
+    } rec{un, cur, best, taken, a1, best_max, best_sum, budget};
+    rec.go(0, 0, 0);
+    members = best;
+  }
   std::vector<int32_t> counts(ncl, 0);
   std::vector<int32_t> stages(size_t(ncl) * (1 + U) * 64, -1);
   for (int c = 0; c < ncl; ++c) {
@@ -444,8 +512,19 @@ int build_tables(const rbgp_mask *m, RegTables *t) {
     }
     counts[c] = st;
   }
+  // LDS fragment slot mm * fpm + fi  ->  packed fragment index of G_i vertex 0 (-1: all zeros)
+  const int fpm = d1 * pl.NSTG;
+  std::vector<int32_t> wsrc(size_t(ncl) * 64, -1);
+  if (U * fpm <= 63)
+    for (int c = 0; c < ncl; ++c)
+      for (int k = 0; k < U; ++k)
+        for (int fi = 0; fi < fpm; ++fi)
+          if (members[size_t(c) * U + k] >= 0)
+            wsrc[size_t(c) * 64 + k * fpm + fi] = (members[size_t(c) * U + k] * fpm + fi) * m->a[2];
   t->ncl = ncl;
-  int rc = upload(stages, &t->stages);
+  int rc = upload(wsrc, &t->wsrc);
+  if (rc) return rc;
+  rc = upload(stages, &t->stages);
   if (rc) return rc;
   rc = upload(counts, &t->counts);
   if (rc) return rc;
@@ -469,6 +548,7 @@ void rbgp_reg_release(void *state) {
   if (st->tab.stages) (void)hipFree(st->tab.stages);
   if (st->tab.counts) (void)hipFree(st->tab.counts);
   if (st->tab.members) (void)hipFree(st->tab.members);
+  if (st->tab.wsrc) (void)hipFree(st->tab.wsrc);
   delete st;
 }
 
@@ -505,11 +585,12 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, 
   const int64_t ntiles = (N + 63) / 64;
   const int fpm = m->d[0] * pl.NSTG;
   const int fb = pl.NQ * 4 * pl.RS * 16;
-  const size_t lds = size_t(pl.MG * fpm + 1) * fb;
-  // Weights stream from global memory by default: measured on the VGG19 conv5 shape, copying
-  // them to LDS first costs more at the start of the kernel than the cheaper stages give
-  // back.  The tuning knob (value 2) selects the LDS variant whenever they fit.
-  const bool wlds = tune_wlds == 2 && lds <= 160 * 1024;
+  const size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
+  // Weights stream from global memory by default: measured on the VGG19 conv5 shape, filling
+  // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
+  // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
+  // LDS variant whenever the weights fit.
+  const bool wlds = tune_wlds == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
@@ -521,11 +602,14 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, 
   rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
   rp.fpm = fpm;
-  rp.items = st->tab.ncl * m->a[2];
+  rp.zero_frag = m->a[0] * fpm * m->a[2];
+  rp.tm = m->a[1] * m->a[2] * m->a[3];
+  for (int r = 0; r < 16; ++r) rp.rowofs[r] = (r / m->a[3]) * m->a[2] * m->a[3] + r % m->a[3];
+  rp.wsrc = st->tab.wsrc;
   rp.ntiles = int(ntiles);
   const int64_t nquads = (ntiles + 3) / 4;
-  const int64_t nblocks = 8 * ((nquads + 7) / 8) * rp.items;
-  if (nblocks > 0x7fffffff) return RBGP_EUNSUPPORTED;
+  const int64_t qgroups = (nquads + 7) / 8;
+  if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
   reg_fn fn = wlds ? e->lds_fn : e->global_fn;
   if (wlds && lds > 64 * 1024 && !st->lds_attr_set[0]) {
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -535,14 +619,14 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, 
 #ifdef RBGP_EXPERIMENT
   static unsigned long long *trace_buf = nullptr;
   static int launches = 0;
-  const size_t trace_n = size_t(nblocks) * 4 * 8;
+  const size_t trace_n = size_t(8 * st->tab.ncl) * qgroups * m->a[2] * 4 * 8;
   if (!trace_buf) RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&trace_buf), (size_t(1) << 24)));
   rp.trace = trace_buf;
   ++launches;
   const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
   if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
 #endif
-  hipLaunchKernelGGL(fn, dim3(unsigned(nblocks)), dim3(256), wlds ? lds : 0, static_cast<hipStream_t>(stream), rp);
+  hipLaunchKernelGGL(fn, dim3(unsigned(8 * st->tab.ncl), unsigned(qgroups), unsigned(m->a[2])), dim3(256), wlds ? lds : 0, static_cast<hipStream_t>(stream), rp);
 #ifdef RBGP_EXPERIMENT
   if (dump) {
     RBGP_HIP(hipDeviceSynchronize());
