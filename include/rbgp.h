@@ -63,8 +63,8 @@ enum {
   RBGP_KERNEL_AUTO = 0,
   RBGP_KERNEL_GENERIC = 1,  /* plain FMA, any four-factor mask, canonical layout */
   RBGP_KERNEL_MFMA = 2,     /* RBGP4 masks: I tiles staged in LDS, MFMA on the dense blocks */
-  RBGP_KERNEL_MFMA_REG = 3  /* RBGP4 masks, fp32: I rows streamed into registers and reused
-                               across a cluster of tile rows, MFMA on the dense blocks */
+  RBGP_KERNEL_MFMA_REG = 3  /* RBGP4 masks: I rows streamed into registers and reused across a
+                               cluster of tile rows, 16-row MFMA on the dense blocks */
 };
 
 /* tuning knobs (rbgp_mask_tune) */
@@ -155,8 +155,10 @@ int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *de
  * leading dimension ldO >= N, overwritten.  M and K must equal the mask's
  * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  The
  * RBGP_KERNEL_MFMA family needs dev_I 16-byte aligned and ldI a multiple of 4
- * (fp32) or 8 (bf16) elements (ESHAPE otherwise); the other families take any
- * alignment.  dev_packed must have been packed with the same kernel family and
+ * (fp32) or 8 (bf16) elements, the RBGP_KERNEL_MFMA_REG family in bf16 mode dev_I
+ * 8-byte aligned and ldI a multiple of 4 (ESHAPE otherwise; it reads the last row
+ * of I up to the next multiple of 4 columns, inside the K x ldI array); the other
+ * cases take any alignment.  dev_packed must have been packed with the same kernel family and
  * dtype.  Asynchronous on `hip_stream`. */
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
               const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,

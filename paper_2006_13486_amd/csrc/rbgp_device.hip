@@ -47,8 +47,8 @@ struct rbgp_device_state {
   int device = -1;
   int32_t *adj[4] = {nullptr, nullptr, nullptr, nullptr};
   int32_t *rowoff = nullptr;             // [a_i][KS]: stage-relative I row of each contraction step
-  int32_t *perm[RBGP_NUM_KERNELS] = {};  // pack permutation per kernel family
-  size_t perm_elems[RBGP_NUM_KERNELS] = {};
+  int32_t *perm[2 * RBGP_NUM_KERNELS] = {};  // pack permutation per kernel family and dtype
+  size_t perm_elems[2 * RBGP_NUM_KERNELS] = {};
   void *reg_state = nullptr;             // tables of the register-streaming family
   void *staging = nullptr;               // canonical values on their way through rbgp_pack
   size_t staging_bytes = 0;
@@ -60,7 +60,7 @@ void rbgp_device_release(rbgp_device_state *dev) {
   for (int i = 0; i < 4; ++i)
     if (dev->adj[i]) (void)hipFree(dev->adj[i]);
   if (dev->rowoff) (void)hipFree(dev->rowoff);
-  for (int i = 0; i < RBGP_NUM_KERNELS; ++i)
+  for (int i = 0; i < 2 * RBGP_NUM_KERNELS; ++i)
     if (dev->perm[i]) (void)hipFree(dev->perm[i]);
   rbgp_reg_release(dev->reg_state);
   if (dev->staging) (void)hipFree(dev->staging);
@@ -343,7 +343,7 @@ bool mfma_covers(const rbgp_mask *m) {
 // AUTO: the register-streaming family for fp32 masks whose I rows are shared by few
 // G_i vertices (little to gain from staging them in LDS), else the LDS family, else GENERIC.
 int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
-  const bool reg_ok = dtype == RBGP_F32 && rbgp_reg_covers(m);
+  const bool reg_ok = rbgp_reg_covers(m);
   switch (m->kernel_choice) {
     case RBGP_KERNEL_GENERIC: return RBGP_KERNEL_GENERIC;
     case RBGP_KERNEL_MFMA: return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
@@ -354,9 +354,9 @@ int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
   return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
 }
 
-int64_t packed_elems(const rbgp_mask *m, int kernel) {
+int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
   if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
-  if (kernel == RBGP_KERNEL_MFMA_REG) return m->reg.packed_elems;
+  if (kernel == RBGP_KERNEL_MFMA_REG) return dtype == RBGP_BF16_F32ACC ? m->reg.packed_elems_bf16 : m->reg.packed_elems;
   return m->nnz;
 }
 
@@ -392,13 +392,14 @@ int ensure_device(const rbgp_mask *m) {
   return RBGP_OK;
 }
 
-int ensure_perm(const rbgp_mask *m, int kernel) {
+int ensure_perm(const rbgp_mask *m, int kernel, bool bf16, int *slot) {
   rbgp_device_state *dev = m->dev;
-  if (dev->perm[kernel]) return RBGP_OK;
+  *slot = 2 * kernel + (bf16 ? 1 : 0);
+  if (dev->perm[*slot]) return RBGP_OK;
   std::vector<int32_t> perm;
-  rbgp_build_pack_perm(m, kernel, perm);
-  dev->perm_elems[kernel] = perm.size();
-  return upload(perm, &dev->perm[kernel]);
+  rbgp_build_pack_perm(m, kernel, bf16, perm);
+  dev->perm_elems[*slot] = perm.size();
+  return upload(perm, &dev->perm[*slot]);
 }
 
 size_t elem_bytes(rbgp_dtype_t dt) { return dt == RBGP_BF16_F32ACC ? 2 : 4; }
@@ -433,7 +434,7 @@ int rbgp_mask_tune(rbgp_mask_t *m, int knob, int value) {
 
 size_t rbgp_packed_bytes(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
   if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return 0;
-  return size_t(packed_elems(m, resolve_kernel(m, dtype))) * elem_bytes(dtype);
+  return size_t(packed_elems(m, resolve_kernel(m, dtype), dtype)) * elem_bytes(dtype);
 }
 
 int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
@@ -443,17 +444,18 @@ int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_v
   int rc = ensure_device(m);
   if (rc) return rc;
   const int kernel = resolve_kernel(m, dtype);
-  rc = ensure_perm(m, kernel);
+  int slot;
+  rc = ensure_perm(m, kernel, dtype == RBGP_BF16_F32ACC, &slot);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int64_t n = int64_t(m->dev->perm_elems[kernel]);
+  const int64_t n = int64_t(m->dev->perm_elems[slot]);
   const dim3 grid(unsigned((n + 255) / 256)), block(256);
   if (dtype == RBGP_F32)
-    pack_kernel<float><<<grid, block, 0, st>>>(static_cast<const float *>(dev_values), m->dev->perm[kernel],
+    pack_kernel<float><<<grid, block, 0, st>>>(static_cast<const float *>(dev_values), m->dev->perm[slot],
                                                static_cast<float *>(dev_packed), n);
   else
     pack_kernel<uint16_t><<<grid, block, 0, st>>>(static_cast<const uint16_t *>(dev_values),
-                                                  m->dev->perm[kernel], static_cast<uint16_t *>(dev_packed), n);
+                                                  m->dev->perm[slot], static_cast<uint16_t *>(dev_packed), n);
   RBGP_HIP(hipGetLastError());
   return RBGP_OK;
 }
@@ -496,7 +498,7 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   const bool bf16 = dtype == RBGP_BF16_F32ACC;
 
   if (kernel == RBGP_KERNEL_MFMA_REG)
-    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_WEIGHTS_IN_LDS], N, dev_packed, dev_I, ldI,
+    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_WEIGHTS_IN_LDS], bf16, N, dev_packed, dev_I, ldI,
                            static_cast<float *>(dev_O), ldO, hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {

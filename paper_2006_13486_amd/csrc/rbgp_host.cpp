@@ -175,6 +175,8 @@ void rbgp_plan_reg(rbgp_mask *m) {
     p.NQ = (p.NO + 3) / 4;
     // one more all-zero fragment ends the buffer
     p.packed_elems = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * p.NQ * 4 * p.RS * 4;
+    const int nq_bf16 = ((p.KC + 15) / 16 + 1) / 2;
+    p.packed_elems_bf16 = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * nq_bf16 * 4 * p.RS * 8;
   }
   m->reg = p;
 }
@@ -192,7 +194,33 @@ void rbgp_plan_reg(rbgp_mask *m) {
 //           group's (u_r, u_b) rows padded to a power of two) at kk = 16q + 4w + g,
 //           so that one 16-byte load per lane fetches a row's weights for four
 //           consecutive load slots.
-void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, std::vector<int32_t> &perm) {
+//  MFMA_REG, bf16: same fragment order; element (q, g, i, e) of a fragment, e = 0..7, is the
+//           weight of row i at kk = 16*(2q + e/4) + 4g + e%4: four consecutive contraction
+//           steps of a k-block per 8 bytes, two k-blocks per 16-byte load.
+void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
+  if (kernel == RBGP_KERNEL_MFMA_REG && bf16) {
+    const rbgp_reg_plan &p = m->reg;
+    const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
+    const int nq = ((p.KC + 15) / 16 + 1) / 2;
+    perm.assign(size_t(p.packed_elems_bf16), -1);
+    size_t pos = 0;
+    for (int u1 = 0; u1 < a1; ++u1)
+      for (int j1 = 0; j1 < d1; ++j1)
+        for (int sg = 0; sg < p.NSTG; ++sg)
+          for (int u3 = 0; u3 < a3; ++u3)
+            for (int q = 0; q < nq; ++q)
+              for (int g = 0; g < 4; ++g)
+                for (int r = 0; r < p.RS; ++r)
+                  for (int e = 0; e < 8; ++e, ++pos) {
+                    const int kk = 16 * (2 * q + e / 4) + 4 * g + e % 4;
+                    if (kk >= p.KC || r >= p.R) continue;
+                    const int u2 = r / a4, u4 = r % a4;
+                    const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
+                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + kk;
+                    perm[pos] = int32_t(row * m->rowdeg + t);
+                  }
+    return;
+  }
   if (kernel == RBGP_KERNEL_MFMA_REG) {
     const rbgp_reg_plan &p = m->reg;
     const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];

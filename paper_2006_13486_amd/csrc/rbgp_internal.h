@@ -34,7 +34,8 @@ struct rbgp_reg_plan {
   int NO = 0;    // load slots per stage: ceil(KC / 4)
   int NQ = 0;    // 16-byte weight loads per lane, group and stage: ceil(NO / 4)
   int SRC = 0;   // rows of I spanned by one stage: VC * |G_i.V| * |G_b.V|
-  int64_t packed_elems = 0;
+  int64_t packed_elems = 0;       // fp32 layout
+  int64_t packed_elems_bf16 = 0;  // bf16 layout
 };
 
 struct rbgp_mask {
@@ -57,11 +58,11 @@ void rbgp_device_release(rbgp_device_state *dev);
 void rbgp_set_hip_error(const char *msg);
 // register-streaming family (rbgp_mfma_reg.hip); `state` is its lazily built table cache
 bool rbgp_reg_covers(const rbgp_mask *m);
-int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_u, int64_t N, const void *packed, const void *I,
-                    int64_t ldI, float *O, int64_t ldO, void *stream);
+int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, int64_t N, const void *packed,
+                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream);
 void rbgp_reg_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
-void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, std::vector<int32_t> &perm);
+void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm);

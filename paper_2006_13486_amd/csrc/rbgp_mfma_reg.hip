@@ -64,8 +64,8 @@ __device__ __forceinline__ void static_for(F &&f) {
 }
 
 struct RegParams {
-  const float *Wp;
-  const float *I;
+  const float *Wp;         // packed weights (fp32, or bf16 bits for the bf16 kernels)
+  const float *I;          // activations (same)
   float *O;
   const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
   const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
@@ -350,12 +350,188 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #endif
 }
 
+// ----------------------------------------------------------------------------
+// bf16 inputs, fp32 accumulation: same decomposition, v_mfma_f32_16x16x16_bf16.
+// The matrix core wants, per lane, four consecutive contraction steps of ONE column, while
+// I holds consecutive columns of one row.  A lane therefore loads 8 bytes (columns 4j..4j+3)
+// from each of its four rows (contraction steps 16kb + 4kg .. +3 of k-block kb, kg = lane/16)
+// and transposes the 4x4 block of bf16 in registers (8 v_perm_b32), which yields the B
+// operands of four MFMAs (one per column offset w).  The weights are packed k-major on
+// the host side of rbgp_pack, so the A operand is a plain 8-byte piece of a 16-byte load.
+// ----------------------------------------------------------------------------
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x2 load_x2(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+}
+__device__ __forceinline__ u32x4 load_u4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+__device__ __forceinline__ s16x4 as_s16x4(unsigned lo, unsigned hi) {
+  u32x2 v = {lo, hi};
+  return __builtin_bit_cast(s16x4, v);
+}
+
+template <int KC, int RS>
+__global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
+  constexpr int MG = 16 / RS;
+  constexpr int NKB = (KC + 15) / 16;    // k-blocks (16 contraction steps) per stage
+  constexpr int NQ = (NKB + 1) / 2;      // weights of two k-blocks come as one 16-byte load
+  constexpr int QB = 4 * RS * 16;        // bytes of one such load across the fragment
+  constexpr int FB = NQ * QB;            // bytes of one weight fragment
+  constexpr int CW = 64;
+  const int lane = threadIdx.x & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.z;
+  const int ntq = xcd + 8 * int(blockIdx.y);
+  const int nt = ntq * 4 + wid;
+  if (nt >= p.ntiles) return;
+  const int64_t n0 = int64_t(nt) * CW;
+  const int kg = lane >> 4, j = lane & 15;
+  const int mi = j / RS, ri = j % RS;
+
+  int mem[MG];
+#pragma unroll
+  for (int mm = 0; mm < MG; ++mm) mem[mm] = p.members[cl * MG + mm];
+  const int32_t *rt = p.rowtab + u3 * (NKB * 16) + kg * 4;
+  int rrow[NKB][4];
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) rrow[kb][t] = rt[kb * 16 + t];
+  const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * 64 + lane;
+  const int tb = stg[0];
+  int tf[MG];
+#pragma unroll
+  for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
+  const int cnt = p.counts[cl];
+  const int rov = p.rowofs[lane & 15];
+
+  // byte offset of this lane's 8 bytes (4 bf16 columns) in each of its rows, relative to the stage base
+  int off[NKB][4];
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) off[kb][t] = rrow[kb][t] * (int(p.ldI) * 2) + j * 8;
+  const int alane = (kg * RS + ri) * 16;
+
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void *>(static_cast<const void *>(p.Wp)), 0, p.w_bytes, kRsrcFlags);
+  auto b_rsrc = [&](int s, int *sofs) {
+    const int base_row = __builtin_amdgcn_readlane(tb, s);
+    *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 2);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(static_cast<const void *>(p.I)), 0,
+                                             base_row >= 0 ? p.i_bytes : 0u, kRsrcFlags);
+  };
+  auto a_addr = [&](int s) {
+    int addr = 0;
+#pragma unroll
+    for (int mm = 0; mm < MG; ++mm) {
+      const int fi = __builtin_amdgcn_readlane(tf[mm], s);
+      const int sv = (fi >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
+      addr = mi == mm ? sv : addr;
+    }
+    return addr + alane;
+  };
+  __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
+
+  f32x4 acc[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // the MFMAs of one k-block: transpose the lane's 4x4 block of bf16, then one MFMA per column offset
+  auto kblock = [&](const u32x2 (&raw)[4], const u32x4 &aq, int half) {
+    const s16x4 a = half ? as_s16x4(aq[2], aq[3]) : as_s16x4(aq[0], aq[1]);
+    const unsigned x01l = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x05040100u);
+    const unsigned x23l = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x05040100u);
+    const unsigned x01h = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x07060302u);
+    const unsigned x23h = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x07060302u);
+    const unsigned y01l = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x05040100u);
+    const unsigned y23l = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x05040100u);
+    const unsigned y01h = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x07060302u);
+    const unsigned y23h = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x07060302u);
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(x01l, x23l), acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(x01h, x23h), acc[1], 0, 0, 0);
+    acc[2] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(y01l, y23l), acc[2], 0, 0, 0);
+    acc[3] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(y01h, y23h), acc[3], 0, 0, 0);
+  };
+
+  auto stage = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[NQ], auto reload) {
+    constexpr bool RELOAD = decltype(reload)::value;
+    int sofs = 0, av = 0;
+    __amdgpu_buffer_rsrc_t rb2 = rw;
+    if constexpr (RELOAD) {
+      rb2 = b_rsrc(s + 2, &sofs);
+      av = a_addr(s + 2);
+    }
+    static_for<0, NKB>([&](auto kc) {
+      constexpr int kb = decltype(kc)::value;
+      kblock(B[kb], A[kb / 2], kb % 2);
+      if constexpr (RELOAD) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
+        if constexpr (kb % 2 == 1 || kb == NKB - 1) A[kb / 2] = load_u4(rw, av, (kb / 2) * QB);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
+  };
+  auto fill = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[NQ]) {
+    int sofs;
+    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(s, &sofs);
+    const int av = a_addr(s);
+    static_for<0, NKB>([&](auto kc) {
+      constexpr int kb = decltype(kc)::value;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
+      if constexpr (kb % 2 == 1 || kb == NKB - 1) A[kb / 2] = load_u4(rw, av, (kb / 2) * QB);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  u32x2 B0[NKB][4], B1[NKB][4];
+  u32x4 A0[NQ], A1[NQ];
+  fill(0, B0, A0);
+  fill(1, B1, A1);
+  {
+    int s = 0;
+    for (; s + 1 < cnt; s += 2) {
+      stage(s, B0, A0, std::true_type{});
+      stage(s + 1, B1, A1, std::true_type{});
+    }
+    if (s < cnt) stage(s, B0, A0, std::false_type{});
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+
+  // epilogue: register t holds weight row 4*(lane/16) + t of the group, lane j the columns 4j + w
+  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int i16 = 4 * kg + t, mm = i16 / RS, r = i16 % RS;
+    int u1 = mem[0];
+#pragma unroll
+    for (int q = 1; q < MG; ++q) u1 = mm == q ? mem[q] : u1;
+    const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
+    if (u1 >= 0 && r < p.R) {
+      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
+      float *o = p.O + m * p.ldO + n0 + j * 4;
+      if (vec_ok) {
+        *reinterpret_cast<f32x4 *>(o) = f32x4{acc[0][t], acc[1][t], acc[2][t], acc[3][t]};
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          if (n0 + j * 4 + w < p.N) o[w] = acc[w][t];
+      }
+    }
+  }
+}
+
 typedef void (*reg_fn)(RegParams);
 struct RegEntry {
   int KC, RS;
-  reg_fn lds_fn, global_fn;
+  reg_fn lds_fn, global_fn, bf16_fn;
 };
-#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>}
+#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>, spmm_reg_bf16<KC, RS>}
 const RegEntry kRegTable[] = {RBGP_R(8, 4),  RBGP_R(18, 2), RBGP_R(36, 2), RBGP_R(72, 2),
                               RBGP_R(18, 4), RBGP_R(36, 4), RBGP_R(72, 4),
                               RBGP_R(18, 8), RBGP_R(36, 8), RBGP_R(72, 8)};
@@ -372,7 +548,8 @@ struct RegTables {  // device tables of the clustering
 };
 
 struct RegState {
-  int32_t *rowtab = nullptr;
+  int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
+  int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
   RegTables tab;
   bool lds_attr_set[2] = {false, false};
 };
@@ -545,6 +722,7 @@ void rbgp_reg_release(void *state) {
   RegState *st = static_cast<RegState *>(state);
   if (!st) return;
   if (st->rowtab) (void)hipFree(st->rowtab);
+  if (st->rowtab_bf16) (void)hipFree(st->rowtab_bf16);
   if (st->tab.stages) (void)hipFree(st->tab.stages);
   if (st->tab.counts) (void)hipFree(st->tab.counts);
   if (st->tab.members) (void)hipFree(st->tab.members);
@@ -552,28 +730,37 @@ void rbgp_reg_release(void *state) {
   delete st;
 }
 
-int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, const void *packed, const void *I,
-                    int64_t ldI, float *O, int64_t ldO, void *stream) {
+int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, int64_t N, const void *packed,
+                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
   // I and the packed weights are addressed through 32-bit buffer offsets
-  const int64_t i_bytes = ((m->K - 1) * ldI + N) * 4, w_bytes = pl.packed_elems * 4;
+  const int es = bf16 ? 2 : 4;
+  // (bf16: two columns share a dword, and a dword that crosses the end of the descriptor reads
+  // as zero, so the extent is rounded up to the 8 bytes a lane loads; ldI % 4 == 0 keeps that
+  // inside the K x ldI array)
+  const int64_t i_bytes = ((m->K - 1) * ldI + (bf16 ? (N + 3) / 4 * 4 : N)) * es;
+  const int64_t w_bytes = (bf16 ? pl.packed_elems_bf16 : pl.packed_elems) * es;
   if (i_bytes >= (int64_t(1) << 31) || w_bytes >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  // the bf16 kernels load 8 bytes (4 columns) per lane and row
+  if (bf16 && ((ldI % 4) || (reinterpret_cast<uintptr_t>(I) & 7))) return RBGP_ESHAPE;
   RegState *st = static_cast<RegState *>(*state);
   if (!st) {
     st = new (std::nothrow) RegState();
     if (!st) return RBGP_ENOMEM;
     *state = st;
   }
-  if (!st->rowtab) {
+  int32_t **rowtab = bf16 ? &st->rowtab_bf16 : &st->rowtab;
+  if (!*rowtab) {
     const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
-    std::vector<int32_t> rt(size_t(a3) * pl.NO * 4, 0);
+    const int len = bf16 ? ((pl.KC + 15) / 16) * 16 : pl.NO * 4;   // contraction steps, padded (padding -> row 0)
+    std::vector<int32_t> rt(size_t(a3) * len, 0);
     for (int u3 = 0; u3 < a3; ++u3)
       for (int kk = 0; kk < pl.KC; ++kk) {
         const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
-        rt[size_t(u3) * pl.NO * 4 + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
+        rt[size_t(u3) * len + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
       }
-    int rc = upload(rt, &st->rowtab);
+    int rc = upload(rt, rowtab);
     if (rc) return rc;
   }
   if (!st->tab.stages) {
@@ -584,19 +771,19 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, 
   if (!e) return RBGP_EUNSUPPORTED;
   const int64_t ntiles = (N + 63) / 64;
   const int fpm = m->d[0] * pl.NSTG;
-  const int fb = pl.NQ * 4 * pl.RS * 16;
+  const int fb = (bf16 ? ((pl.KC + 15) / 16 + 1) / 2 : pl.NQ) * 4 * pl.RS * 16;
   const size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
   // Weights stream from global memory by default: measured on the VGG19 conv5 shape, filling
   // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
   // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
   // LDS variant whenever the weights fit.
-  const bool wlds = tune_wlds == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
+  const bool wlds = !bf16 && tune_wlds == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
   rp.I = static_cast<const float *>(I);
   rp.O = O;
-  rp.rowtab = st->rowtab;
+  rp.rowtab = *rowtab;
   rp.stages = st->tab.stages; rp.counts = st->tab.counts; rp.members = st->tab.members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
   rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
@@ -610,7 +797,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, int64_t N, 
   const int64_t nquads = (ntiles + 3) / 4;
   const int64_t qgroups = (nquads + 7) / 8;
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
-  reg_fn fn = wlds ? e->lds_fn : e->global_fn;
+  reg_fn fn = bf16 ? e->bf16_fn : wlds ? e->lds_fn : e->global_fn;
   if (wlds && lds > 64 * 1024 && !st->lds_attr_set[0]) {
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));

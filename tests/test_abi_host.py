@@ -155,7 +155,7 @@ def test_kernel_selection_and_packed_size():
     w = wl.VGG19_CONV5
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
     assert rb.rbgp_mask_kernel(mask, rb.F32) == rb.KERNEL_MFMA_REG
-    assert rb.rbgp_mask_kernel(mask, rb.BF16_F32ACC) == rb.KERNEL_MFMA
+    assert rb.rbgp_mask_kernel(mask, rb.BF16_F32ACC) == rb.KERNEL_MFMA_REG
     padded = rb.rbgp_packed_bytes(mask, rb.F32)
     assert padded >= w.nnz * 4
     rb.rbgp_mask_set_kernel(mask, rb.KERNEL_GENERIC)

@@ -19,7 +19,7 @@ GEN, MFMA, REG = rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG
 @pytest.mark.parametrize("w", wl.CONFIGS, ids=lambda w: w.name)
 def test_config_full_size_default_launch(w):
     """The launch configuration bench.py times (library defaults)."""
-    gh.check_parity(w, expect_kernel=MFMA if w.dtype == wl.BF16 else REG)
+    gh.check_parity(w, expect_kernel=REG)
 
 
 @pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
@@ -34,13 +34,13 @@ def test_config_tile_shapes(w, tune):
 
 
 @pytest.mark.parametrize("cluster", [0, 1, 2])
-@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.WRN_G1], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16, wl.WRN_G1], ids=lambda w: w.name)
 def test_config_register_family_cluster_sizes(w, cluster):
     gh.check_parity(w, N=1000 if w.N > 4096 else w.N, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
 
 
-def test_fp32_lds_family_full_size():
-    for w in (wl.VGG19_CONV5, wl.WRN_G1):
+def test_lds_family_full_size():
+    for w in (wl.VGG19_CONV5, wl.VGG19_CONV3_BF16, wl.WRN_G1):
         gh.check_parity(w, kernel=MFMA, expect_kernel=MFMA)
 
 
@@ -57,9 +57,9 @@ def test_ragged_columns(N, ld_pad, dtype):
     for tune in [(1, 64, 0), (2, 128, 0)]:
         gh.check_parity(w, N=N, kernel=MFMA, tune=tune, ld_pad=pad)
     gh.check_parity(w, N=N, kernel=GEN, ld_pad=ld_pad)
-    if dtype == wl.F32:
-        for cluster in (1, 2):
-            gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, cluster), ld_pad=ld_pad, expect_kernel=REG)
+    for cluster in (1, 2):
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, cluster), ld_pad=ld_pad if dtype == wl.F32 else pad,
+                        expect_kernel=REG)
 
 
 def test_empty_input_is_a_noop():
@@ -107,7 +107,7 @@ def test_one_hot_bf16_exact():
     w = replace(wl.TINY, dtype=wl.BF16, name="tiny_bf16")
     vb = wl.to_bf16_bits(wl.kept_weights(w))
     Ib = wl.to_bf16_bits(np.eye(w.K, dtype=np.float32))
-    for kernel in (GEN, MFMA):
+    for kernel in (GEN, MFMA, REG):
         out, _ = gh.library_spmm(w, vb, Ib, kernel, tag="one-hot bf16")
         Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
         W = orc.scatter_values(orc.kron_mask(Bs), wl.bf16_bits_as_f32(vb))
@@ -144,7 +144,7 @@ def test_shapes_across_the_kernel_table(idx, dtype):
     e1 = gh.check_parity(w, kernel=MFMA, tune=(1, 64, 0))
     e2 = gh.check_parity(w, kernel=MFMA, tune=(2, 128, 0))
     gh.check_parity(w, kernel=GEN)
-    if dtype == wl.F32 and idx >= 5:          # shapes inside the register family's table
+    if idx >= 5:                              # shapes inside the register family's table
         for cluster in (1, 2):
             gh.check_parity(w, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
 
