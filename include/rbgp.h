@@ -72,8 +72,13 @@ enum {
   RBGP_TUNE_COLS_PER_LANE = 0,        /* MFMA: 1 or 2 */
   RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128 */
   RBGP_TUNE_GROUPS_PER_WORKGROUP = 2, /* MFMA: a divisor of |G_i.U| */
-  RBGP_TUNE_WEIGHTS_IN_LDS = 3        /* MFMA_REG: 2 = copy the workgroup's weights to LDS first
+  RBGP_TUNE_WEIGHTS_IN_LDS = 3,       /* MFMA_REG fp32: 2 = copy the workgroup's weights to LDS first
                                          (when they fit 160 KB) instead of streaming them */
+  RBGP_TUNE_ROW_GROUPS = 4,           /* MFMA_REG bf16: 16-row MFMA groups per wave, 1, 2 or 4 (each
+                                         loaded row of I is reused by all of them) */
+  RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG bf16: waves that share a column tile and split its
+                                         nonzero tiles between them, 1, 2 or 4 */
+  RBGP_NUM_TUNE = 6
 };
 
 /* Sample the four base graphs and build the mask (host only, no GPU call).

@@ -12,6 +12,7 @@ import numpy as np
 F32, BF16_F32ACC = 0, 1
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG = 0, 1, 2, 3
 TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_WEIGHTS_IN_LDS = 0, 1, 2, 3
+TUNE_ROW_GROUPS, TUNE_K_SPLIT = 4, 5
 SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE = 0, 1, 2
 OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 

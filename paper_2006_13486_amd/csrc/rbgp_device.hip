@@ -52,7 +52,7 @@ struct rbgp_device_state {
   void *reg_state = nullptr;             // tables of the register-streaming family
   void *staging = nullptr;               // canonical values on their way through rbgp_pack
   size_t staging_bytes = 0;
-  int tune[4] = {0, 0, 0, 0};            // RBGP_TUNE_* values, 0 = default
+  int tune[RBGP_NUM_TUNE] = {};            // RBGP_TUNE_* values, 0 = default
 };
 
 void rbgp_device_release(rbgp_device_state *dev) {
@@ -423,7 +423,7 @@ int rbgp_mask_kernel(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
 }
 
 int rbgp_mask_tune(rbgp_mask_t *m, int knob, int value) {
-  if (!m || knob < 0 || knob > 3 || value < 0) return RBGP_EINVAL;
+  if (!m || knob < 0 || knob >= RBGP_NUM_TUNE || value < 0) return RBGP_EINVAL;
   if (!m->dev) {
     m->dev = new (std::nothrow) rbgp_device_state();
     if (!m->dev) return RBGP_ENOMEM;
@@ -498,7 +498,7 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   const bool bf16 = dtype == RBGP_BF16_F32ACC;
 
   if (kernel == RBGP_KERNEL_MFMA_REG)
-    return rbgp_reg_launch(m, &dev->reg_state, dev->tune[RBGP_TUNE_WEIGHTS_IN_LDS], bf16, N, dev_packed, dev_I, ldI,
+    return rbgp_reg_launch(m, &dev->reg_state, dev->tune, bf16, N, dev_packed, dev_I, ldI,
                            static_cast<float *>(dev_O), ldO, hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {

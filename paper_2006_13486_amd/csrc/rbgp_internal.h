@@ -58,7 +58,7 @@ void rbgp_device_release(rbgp_device_state *dev);
 void rbgp_set_hip_error(const char *msg);
 // register-streaming family (rbgp_mfma_reg.hip); `state` is its lazily built table cache
 bool rbgp_reg_covers(const rbgp_mask *m);
-int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, int64_t N, const void *packed,
+int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
                     const void *I, int64_t ldI, float *O, int64_t ldO, void *stream);
 void rbgp_reg_release(void *state);
 // host part

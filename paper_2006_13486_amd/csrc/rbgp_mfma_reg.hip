@@ -37,6 +37,7 @@
 #include <vector>
 
 #include "rbgp_internal.h"
+#include "rbgp_reg_common.h"
 
 #define RBGP_HIP(call)                                                          \
   do {                                                                          \
@@ -49,52 +50,9 @@
     }                                                                           \
   } while (0)
 
+using namespace rbgp_reg;
+
 namespace {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-struct RegParams {
-  const float *Wp;         // packed weights (fp32, or bf16 bits for the bf16 kernels)
-  const float *I;          // activations (same)
-  float *O;
-  const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
-  const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
-                           //   cluster member j_o * NSTG + (stage within the tile), the position of its
-                           //   weight fragment among the member's fragments; -1 past the end (sentinel
-                           //   stages) and when the member does not have the tile
-  const int32_t *counts;   // [ncl] stages of each cluster (<= 60)
-  const int32_t *members;  // [ncl][MG] tile rows of each cluster (-1: none)
-  int64_t N, ldI, ldO;
-  uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
-  int a2, a3, a4, R;
-  int fpm;                 // weight fragments per member: d_o * NSTG
-  int zero_frag;           // index of the all-zero fragment that ends the packed buffer
-  int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
-  int tm;                  // rows of one tile row: a_r * a_i * a_b
-  const int32_t *wsrc;     // [ncl][64]: per LDS fragment slot the packed fragment index of u_i = 0, -1: zeros
-  int ntiles;              // ceil(N / 64)
-#ifdef RBGP_EXPERIMENT
-  unsigned long long *trace;   // [wave][8] timestamps
-#endif
-};
-
-constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
-constexpr int kOob = 0x40000000;        // byte offset beyond any packed weight buffer (reads return 0)
-
-__device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
-  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-  return f32x4{__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3])};
-}
 
 // KC: contraction steps per stage; RS: weight rows per tile row in the 16-row MFMA group
 // (cluster size MG = 16 / RS); WLDS: the weights of the workgroup's (cluster, G_i vertex)
@@ -112,15 +70,17 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
 #ifdef RBGP_EXPERIMENT
-  unsigned long long *tr = p.trace + ((size_t(blockIdx.z) * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + wid * 8;
+  unsigned long long *tr = p.trace + ((size_t(blockIdx.y) * gridDim.z + blockIdx.z) * gridDim.x + blockIdx.x) * 32 + wid * 8;
   if (lane == 0) { tr[0] = __builtin_amdgcn_s_memrealtime(); tr[5] = __builtin_readcyclecounter(); }
 #endif
 
   // A workgroup is one (cluster, G_i vertex) pair on four neighbouring column tiles.  Same
   // columns of I -> same XCD (one L2): workgroups are dealt round-robin to the 8 XCDs.
   // (grid x = 8 * clusters is a multiple of 8, so the XCD of a workgroup is x & 7 whatever y, z)
-  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.z;
-  const int ntq = xcd + 8 * int(blockIdx.y);
+  // The column-tile index is the slowest grid dimension: all (cluster, G_i vertex) pairs of the
+  // same columns are dispatched together, so I comes from HBM once however large N is.
+  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.y;
+  const int ntq = xcd + 8 * int(blockIdx.z);
   if (ntq * 4 >= p.ntiles) return;
   const int nt = ntq * 4 + wid;
   const int64_t n0 = int64_t(nt) * CW;
@@ -142,7 +102,8 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #pragma unroll
   for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
   const int cnt = p.counts[cl];
-  const int rov = p.rowofs[lane & 15];   // lane-held copy, read back with bpermute in the epilogue
+  const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
+  const int memv = p.members[cl * MG + (lane & (MG - 1))];
 
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
@@ -329,9 +290,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #pragma unroll
     for (int w = 0; w < 4; ++w) v[w] = (acc[w][t] + acc[w][4 + t]) + (acc[w][8 + t] + acc[w][12 + t]);
     const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
-    int u1 = mem[0];
-#pragma unroll
-    for (int q = 1; q < MG; ++q) u1 = mm == q ? mem[q] : u1;
+    const int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
     if (u1 >= 0 && r < p.R) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
@@ -350,188 +309,12 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #endif
 }
 
-// ----------------------------------------------------------------------------
-// bf16 inputs, fp32 accumulation: same decomposition, v_mfma_f32_16x16x16_bf16.
-// The matrix core wants, per lane, four consecutive contraction steps of ONE column, while
-// I holds consecutive columns of one row.  A lane therefore loads 8 bytes (columns 4j..4j+3)
-// from each of its four rows (contraction steps 16kb + 4kg .. +3 of k-block kb, kg = lane/16)
-// and transposes the 4x4 block of bf16 in registers (8 v_perm_b32), which yields the B
-// operands of four MFMAs (one per column offset w).  The weights are packed k-major on
-// the host side of rbgp_pack, so the A operand is a plain 8-byte piece of a 16-byte load.
-// ----------------------------------------------------------------------------
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ u32x2 load_x2(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
-}
-__device__ __forceinline__ u32x4 load_u4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-}
-__device__ __forceinline__ s16x4 as_s16x4(unsigned lo, unsigned hi) {
-  u32x2 v = {lo, hi};
-  return __builtin_bit_cast(s16x4, v);
-}
-
-template <int KC, int RS>
-__global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
-  constexpr int MG = 16 / RS;
-  constexpr int NKB = (KC + 15) / 16;    // k-blocks (16 contraction steps) per stage
-  constexpr int NQ = (NKB + 1) / 2;      // weights of two k-blocks come as one 16-byte load
-  constexpr int QB = 4 * RS * 16;        // bytes of one such load across the fragment
-  constexpr int FB = NQ * QB;            // bytes of one weight fragment
-  constexpr int CW = 64;
-  const int lane = threadIdx.x & 63;
-  const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.z;
-  const int ntq = xcd + 8 * int(blockIdx.y);
-  const int nt = ntq * 4 + wid;
-  if (nt >= p.ntiles) return;
-  const int64_t n0 = int64_t(nt) * CW;
-  const int kg = lane >> 4, j = lane & 15;
-  const int mi = j / RS, ri = j % RS;
-
-  int mem[MG];
-#pragma unroll
-  for (int mm = 0; mm < MG; ++mm) mem[mm] = p.members[cl * MG + mm];
-  const int32_t *rt = p.rowtab + u3 * (NKB * 16) + kg * 4;
-  int rrow[NKB][4];
-#pragma unroll
-  for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) rrow[kb][t] = rt[kb * 16 + t];
-  const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * 64 + lane;
-  const int tb = stg[0];
-  int tf[MG];
-#pragma unroll
-  for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
-  const int cnt = p.counts[cl];
-  const int rov = p.rowofs[lane & 15];
-
-  // byte offset of this lane's 8 bytes (4 bf16 columns) in each of its rows, relative to the stage base
-  int off[NKB][4];
-#pragma unroll
-  for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) off[kb][t] = rrow[kb][t] * (int(p.ldI) * 2) + j * 8;
-  const int alane = (kg * RS + ri) * 16;
-
-  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<void *>(static_cast<const void *>(p.Wp)), 0, p.w_bytes, kRsrcFlags);
-  auto b_rsrc = [&](int s, int *sofs) {
-    const int base_row = __builtin_amdgcn_readlane(tb, s);
-    *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 2);
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(static_cast<const void *>(p.I)), 0,
-                                             base_row >= 0 ? p.i_bytes : 0u, kRsrcFlags);
-  };
-  auto a_addr = [&](int s) {
-    int addr = 0;
-#pragma unroll
-    for (int mm = 0; mm < MG; ++mm) {
-      const int fi = __builtin_amdgcn_readlane(tf[mm], s);
-      const int sv = (fi >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
-      addr = mi == mm ? sv : addr;
-    }
-    return addr + alane;
-  };
-  __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
-
-  f32x4 acc[4];
-#pragma unroll
-  for (int w = 0; w < 4; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // the MFMAs of one k-block: transpose the lane's 4x4 block of bf16, then one MFMA per column offset
-  auto kblock = [&](const u32x2 (&raw)[4], const u32x4 &aq, int half) {
-    const s16x4 a = half ? as_s16x4(aq[2], aq[3]) : as_s16x4(aq[0], aq[1]);
-    const unsigned x01l = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x05040100u);
-    const unsigned x23l = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x05040100u);
-    const unsigned x01h = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x07060302u);
-    const unsigned x23h = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x07060302u);
-    const unsigned y01l = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x05040100u);
-    const unsigned y23l = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x05040100u);
-    const unsigned y01h = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x07060302u);
-    const unsigned y23h = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x07060302u);
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(x01l, x23l), acc[0], 0, 0, 0);
-    acc[1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(x01h, x23h), acc[1], 0, 0, 0);
-    acc[2] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(y01l, y23l), acc[2], 0, 0, 0);
-    acc[3] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, as_s16x4(y01h, y23h), acc[3], 0, 0, 0);
-  };
-
-  auto stage = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[NQ], auto reload) {
-    constexpr bool RELOAD = decltype(reload)::value;
-    int sofs = 0, av = 0;
-    __amdgpu_buffer_rsrc_t rb2 = rw;
-    if constexpr (RELOAD) {
-      rb2 = b_rsrc(s + 2, &sofs);
-      av = a_addr(s + 2);
-    }
-    static_for<0, NKB>([&](auto kc) {
-      constexpr int kb = decltype(kc)::value;
-      kblock(B[kb], A[kb / 2], kb % 2);
-      if constexpr (RELOAD) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
-        if constexpr (kb % 2 == 1 || kb == NKB - 1) A[kb / 2] = load_u4(rw, av, (kb / 2) * QB);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    });
-  };
-  auto fill = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[NQ]) {
-    int sofs;
-    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(s, &sofs);
-    const int av = a_addr(s);
-    static_for<0, NKB>([&](auto kc) {
-      constexpr int kb = decltype(kc)::value;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
-      if constexpr (kb % 2 == 1 || kb == NKB - 1) A[kb / 2] = load_u4(rw, av, (kb / 2) * QB);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-  };
-
-  u32x2 B0[NKB][4], B1[NKB][4];
-  u32x4 A0[NQ], A1[NQ];
-  fill(0, B0, A0);
-  fill(1, B1, A1);
-  {
-    int s = 0;
-    for (; s + 1 < cnt; s += 2) {
-      stage(s, B0, A0, std::true_type{});
-      stage(s + 1, B1, A1, std::true_type{});
-    }
-    if (s < cnt) stage(s, B0, A0, std::false_type{});
-  }
-  __builtin_amdgcn_s_waitcnt(0);
-
-  // epilogue: register t holds weight row 4*(lane/16) + t of the group, lane j the columns 4j + w
-  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int i16 = 4 * kg + t, mm = i16 / RS, r = i16 % RS;
-    int u1 = mem[0];
-#pragma unroll
-    for (int q = 1; q < MG; ++q) u1 = mm == q ? mem[q] : u1;
-    const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
-    if (u1 >= 0 && r < p.R) {
-      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
-      float *o = p.O + m * p.ldO + n0 + j * 4;
-      if (vec_ok) {
-        *reinterpret_cast<f32x4 *>(o) = f32x4{acc[0][t], acc[1][t], acc[2][t], acc[3][t]};
-      } else {
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-          if (n0 + j * 4 + w < p.N) o[w] = acc[w][t];
-      }
-    }
-  }
-}
-
-typedef void (*reg_fn)(RegParams);
+typedef rbgp_reg_fn reg_fn;
 struct RegEntry {
   int KC, RS;
-  reg_fn lds_fn, global_fn, bf16_fn;
+  reg_fn lds_fn, global_fn;
 };
-#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>, spmm_reg_bf16<KC, RS>}
+#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>}
 const RegEntry kRegTable[] = {RBGP_R(8, 4),  RBGP_R(18, 2), RBGP_R(36, 2), RBGP_R(72, 2),
                               RBGP_R(18, 4), RBGP_R(36, 4), RBGP_R(72, 4),
                               RBGP_R(18, 8), RBGP_R(36, 8), RBGP_R(72, 8)};
@@ -550,7 +333,9 @@ struct RegTables {  // device tables of the clustering
 struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
-  RegTables tab;
+  RegTables tab;                   // fp32: clusters of one 16-row group
+  RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
+  int tab_bf16_G = 0;
   bool lds_attr_set[2] = {false, false};
 };
 
@@ -561,12 +346,19 @@ int upload(const std::vector<T> &h, T **d) {
   return RBGP_OK;
 }
 
-// Group the tile rows into clusters of U = MG whose adjacency lists overlap most (greedy:
+void free_tables(RegTables *t) {
+  if (t->stages) (void)hipFree(t->stages);
+  if (t->counts) (void)hipFree(t->counts);
+  if (t->members) (void)hipFree(t->members);
+  if (t->wsrc) (void)hipFree(t->wsrc);
+  *t = RegTables();
+}
+
+// Group the tile rows into clusters of U whose adjacency lists overlap most (greedy:
 // seed with the lowest free tile row, add the free row that enlarges the union of tiles
 // least), and list for every cluster the stages it walks.
-int build_tables(const rbgp_mask *m, RegTables *t) {
+int build_tables(const rbgp_mask *m, int U, RegTables *t) {
   const rbgp_reg_plan &pl = m->reg;
-  const int U = pl.MG;
   const int a1 = m->a[0], c1 = m->c[0], d1 = m->d[0];
   const int ncl = (a1 + U - 1) / U;
   std::vector<int32_t> members(size_t(ncl) * U, -1);
@@ -723,14 +515,12 @@ void rbgp_reg_release(void *state) {
   if (!st) return;
   if (st->rowtab) (void)hipFree(st->rowtab);
   if (st->rowtab_bf16) (void)hipFree(st->rowtab_bf16);
-  if (st->tab.stages) (void)hipFree(st->tab.stages);
-  if (st->tab.counts) (void)hipFree(st->tab.counts);
-  if (st->tab.members) (void)hipFree(st->tab.members);
-  if (st->tab.wsrc) (void)hipFree(st->tab.wsrc);
+  free_tables(&st->tab);
+  free_tables(&st->tab_bf16);
   delete st;
 }
 
-int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, int64_t N, const void *packed,
+int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
                     const void *I, int64_t ldI, float *O, int64_t ldO, void *stream) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
@@ -763,28 +553,55 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, 
     int rc = upload(rt, rowtab);
     if (rc) return rc;
   }
-  if (!st->tab.stages) {
-    int rc = build_tables(m, &st->tab);
+  const int64_t ntiles = (N + 63) / 64;
+  // bf16: 16-row groups per wave (G) and waves per column tile (S).  More groups mean fewer
+  // passes of I through the load path; the split keeps at least two waves per SIMD in flight
+  // when that leaves few (cluster, column tile) pairs.
+  int G = 1, lgS = 0;
+  auto stages_fit = [&](int g) { return int64_t(std::min(m->c[0], m->d[0] * g * pl.MG)) * pl.NSTG <= 60; };
+  if (bf16) {
+    const int tg = tune[RBGP_TUNE_ROW_GROUPS], ts = tune[RBGP_TUNE_K_SPLIT];
+    if (tg) {
+      if ((tg != 1 && tg != 2 && tg != 4) || !stages_fit(tg)) return RBGP_EUNSUPPORTED;
+      G = tg;
+    } else {
+      while (G < 4 && G * pl.MG < m->a[0] && stages_fit(2 * G)) G *= 2;
+    }
+    const int64_t ncl = (m->a[0] + G * pl.MG - 1) / (G * pl.MG);
+    if (ts) {
+      if (ts != 1 && ts != 2 && ts != 4) return RBGP_EUNSUPPORTED;
+      lgS = ts == 4 ? 2 : ts == 2 ? 1 : 0;
+    } else {
+      while (lgS < 2 && ((ncl * m->a[2] * ntiles) << lgS) < 2048) ++lgS;
+    }
+  }
+  RegTables *tab = bf16 ? &st->tab_bf16 : &st->tab;
+  if (bf16 && st->tab_bf16_G != G) {
+    free_tables(tab);   // (hipFree waits for launches that still read the old tables)
+    st->tab_bf16_G = G;
+  }
+  if (!tab->stages) {
+    int rc = build_tables(m, G * pl.MG, tab);
     if (rc) return rc;
   }
   const RegEntry *e = find_reg(pl.KC, pl.RS);
   if (!e) return RBGP_EUNSUPPORTED;
-  const int64_t ntiles = (N + 63) / 64;
   const int fpm = m->d[0] * pl.NSTG;
   const int fb = (bf16 ? ((pl.KC + 15) / 16 + 1) / 2 : pl.NQ) * 4 * pl.RS * 16;
-  const size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
+  size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
   // Weights stream from global memory by default: measured on the VGG19 conv5 shape, filling
   // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
   // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
   // LDS variant whenever the weights fit.
-  const bool wlds = !bf16 && tune_wlds == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
+  const bool wlds = !bf16 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
+  if (bf16) lds = lgS ? size_t(4) * G * 4 * 1024 : 0;   // partial sums of the split: 4 waves x 4G units x 1 KB
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
   rp.I = static_cast<const float *>(I);
   rp.O = O;
   rp.rowtab = *rowtab;
-  rp.stages = st->tab.stages; rp.counts = st->tab.counts; rp.members = st->tab.members;
+  rp.stages = tab->stages; rp.counts = tab->counts; rp.members = tab->members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
   rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
@@ -792,12 +609,15 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, 
   rp.zero_frag = m->a[0] * fpm * m->a[2];
   rp.tm = m->a[1] * m->a[2] * m->a[3];
   for (int r = 0; r < 16; ++r) rp.rowofs[r] = (r / m->a[3]) * m->a[2] * m->a[3] + r % m->a[3];
-  rp.wsrc = st->tab.wsrc;
+  rp.wsrc = tab->wsrc;
   rp.ntiles = int(ntiles);
-  const int64_t nquads = (ntiles + 3) / 4;
+  rp.lgS = lgS;
+  const int64_t tiles_per_wg = 4 >> lgS;
+  const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
   const int64_t qgroups = (nquads + 7) / 8;
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
-  reg_fn fn = bf16 ? e->bf16_fn : wlds ? e->lds_fn : e->global_fn;
+  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G) : wlds ? e->lds_fn : e->global_fn;
+  if (!fn) return RBGP_EUNSUPPORTED;
   if (wlds && lds > 64 * 1024 && !st->lds_attr_set[0]) {
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));
@@ -806,14 +626,14 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, int tune_wlds, bool bf16, 
 #ifdef RBGP_EXPERIMENT
   static unsigned long long *trace_buf = nullptr;
   static int launches = 0;
-  const size_t trace_n = size_t(8 * st->tab.ncl) * qgroups * m->a[2] * 4 * 8;
+  const size_t trace_n = size_t(8 * tab->ncl) * qgroups * m->a[2] * 4 * 8;
   if (!trace_buf) RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&trace_buf), (size_t(1) << 24)));
   rp.trace = trace_buf;
   ++launches;
   const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
   if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
 #endif
-  hipLaunchKernelGGL(fn, dim3(unsigned(8 * st->tab.ncl), unsigned(qgroups), unsigned(m->a[2])), dim3(256), wlds ? lds : 0, static_cast<hipStream_t>(stream), rp);
+  hipLaunchKernelGGL(fn, dim3(unsigned(8 * tab->ncl), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), (wlds || bf16) ? lds : 0, static_cast<hipStream_t>(stream), rp);
 #ifdef RBGP_EXPERIMENT
   if (dump) {
     RBGP_HIP(hipDeviceSynchronize());

@@ -1,0 +1,66 @@
+// Shared by the register-streaming MFMA kernels (fp32 and bf16 translation units):
+// kernel parameter block and small device helpers.
+#ifndef RBGP_REG_COMMON_H
+#define RBGP_REG_COMMON_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <type_traits>
+
+namespace rbgp_reg {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+struct RegParams {
+  const float *Wp;         // packed weights (fp32, or bf16 bits for the bf16 kernels)
+  const float *I;          // activations (same)
+  float *O;
+  const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
+  const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
+                           //   cluster member j_o * NSTG + (stage within the tile), the position of its
+                           //   weight fragment among the member's fragments; -1 past the end (sentinel
+                           //   stages) and when the member does not have the tile
+  const int32_t *counts;   // [ncl] stages of each cluster (<= 60)
+  const int32_t *members;  // [ncl][MG] tile rows of each cluster (-1: none)
+  int64_t N, ldI, ldO;
+  uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
+  int a2, a3, a4, R;
+  int fpm;                 // weight fragments per member: d_o * NSTG
+  int zero_frag;           // index of the all-zero fragment that ends the packed buffer
+  int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
+  int tm;                  // rows of one tile row: a_r * a_i * a_b
+  const int32_t *wsrc;     // [ncl][64]: per LDS fragment slot the packed fragment index of u_i = 0, -1: zeros
+  int ntiles;              // ceil(N / 64)
+  int lgS;                 // bf16: log2 of the waves that share a column tile (split of the stage list)
+#ifdef RBGP_EXPERIMENT
+  unsigned long long *trace;   // [wave][8] timestamps
+#endif
+};
+
+constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
+constexpr int kOob = 0x40000000;        // byte offset beyond any packed weight buffer (reads return 0)
+
+__device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+  return f32x4{__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3])};
+}
+
+}  // namespace rbgp_reg
+
+typedef void (*rbgp_reg_fn)(rbgp_reg::RegParams);
+// bf16 kernel for KC contraction steps per stage, RS weight rows per tile row and G 16-row
+// groups per wave; nullptr when that combination is not built.
+rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G);
+
+#endif
