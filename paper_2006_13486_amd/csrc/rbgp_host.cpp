@@ -175,7 +175,7 @@ void rbgp_plan_reg(rbgp_mask *m) {
     p.NQ = (p.NO + 3) / 4;
     // one more all-zero fragment ends the buffer
     p.packed_elems = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * p.NQ * 4 * p.RS * 4;
-    const int nq_bf16 = ((p.KC + 15) / 16 + 1) / 2;
+    const int nq_bf16 = rbgp_bf16_blocks32(p.KC) + (rbgp_bf16_tail16(p.KC) ? 1 : 0);
     p.packed_elems_bf16 = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * nq_bf16 * 4 * p.RS * 8;
   }
   m->reg = p;
@@ -194,14 +194,17 @@ void rbgp_plan_reg(rbgp_mask *m) {
 //           group's (u_r, u_b) rows padded to a power of two) at kk = 16q + 4w + g,
 //           so that one 16-byte load per lane fetches a row's weights for four
 //           consecutive load slots.
-//  MFMA_REG, bf16: same fragment order; element (q, g, i, e) of a fragment, e = 0..7, is the
-//           weight of row i at kk = 16*(2q + e/4) + 4g + e%4: four consecutive contraction
-//           steps of a k-block per 8 bytes, two k-blocks per 16-byte load.
+//  MFMA_REG, bf16: same fragment order; the stage's contraction list is cut into blocks
+//           of 32 steps and possibly one last block of 16; element (q, g, i, e) of a
+//           fragment, e = 0..7, is the weight of row i at kk = 32q + 8g + e in a block of
+//           32 and at kk = 32q + 4g + e (e < 4; the rest is padding) in the block of 16:
+//           the consecutive contraction steps one lane feeds to the matrix core.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
   if (kernel == RBGP_KERNEL_MFMA_REG && bf16) {
     const rbgp_reg_plan &p = m->reg;
     const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
-    const int nq = ((p.KC + 15) / 16 + 1) / 2;
+    const int nk32 = rbgp_bf16_blocks32(p.KC);
+    const int nq = nk32 + (rbgp_bf16_tail16(p.KC) ? 1 : 0);
     perm.assign(size_t(p.packed_elems_bf16), -1);
     size_t pos = 0;
     for (int u1 = 0; u1 < a1; ++u1)
@@ -212,7 +215,8 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
               for (int g = 0; g < 4; ++g)
                 for (int r = 0; r < p.RS; ++r)
                   for (int e = 0; e < 8; ++e, ++pos) {
-                    const int kk = 16 * (2 * q + e / 4) + 4 * g + e % 4;
+                    if (q >= nk32 && e >= 4) continue;   // upper half of the block of 16: padding
+                    const int kk = q < nk32 ? 32 * q + 8 * g + e : 32 * q + 4 * g + e;
                     if (kk >= p.KC || r >= p.R) continue;
                     const int u2 = r / a4, u4 = r % a4;
                     const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;

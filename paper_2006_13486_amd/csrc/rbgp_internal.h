@@ -10,6 +10,11 @@
 
 struct rbgp_device_state;  // defined in rbgp_device.hip
 
+// MFMA_REG bf16 kernels: a stage of KC contraction steps = rbgp_bf16_blocks32(KC) blocks of 32 steps
+// plus, if rbgp_bf16_tail16(KC), one block of 16 (a remainder above 16 takes a whole block of 32)
+constexpr int rbgp_bf16_blocks32(int KC) { return KC / 32 + (KC % 32 > 16 ? 1 : 0); }
+constexpr bool rbgp_bf16_tail16(int KC) { return KC % 32 != 0 && KC % 32 <= 16; }
+
 // Shape of the MFMA kernels' work decomposition for one mask (see rbgp_device.hip).
 struct rbgp_mfma_plan {
   bool ok = false;

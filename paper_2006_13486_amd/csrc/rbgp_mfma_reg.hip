@@ -126,39 +126,55 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   f32x4 B0[NO], B1[NO];
   f32x4 A0[NQ], A1[NQ];
   if constexpr (WLDS) {
-    // the first stage of I is requested before the weights are copied to LDS
-    {
-      int sofs;
-      const __amdgpu_buffer_rsrc_t r0 = b_rsrc(0, &sofs);
-#pragma unroll
-      for (int o = 0; o < NO; ++o) B0[o] = load_x4(r0, off[o], sofs);
-    }
-    // Copy the fragments of all members (fpm each) and one all-zero fragment to LDS with
-    // direct global->LDS loads (1 KB per wave instruction, no VGPR round trip).  The packed
-    // buffer ends with an all-zero fragment, the source for members the cluster lacks.
+    // Copy the fragments of all members (fpm each) to LDS through registers.  One load
+    // instruction moves, for every member of the group, one 16-byte-per-lane row of its
+    // fragment fi, with the lane mapping of the in-loop weight loads (scalar addressing);
+    // wave w takes fragments w, w + 4, ..., two per pass.  The first stage of I is requested
+    // right behind the first pass, so that its HBM latency overlaps the copy.
 #ifdef RBGP_EXPERIMENT
     if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
 #endif
-    constexpr int C16 = FB / 16;
-    const int nchunks = (MG * p.fpm + 1) * C16;
-    const int ninstr = (nchunks + 63) / 64;
-    const int wtab = p.wsrc[cl * 64 + lane];   // fragment slot -> packed fragment (lane-held table)
-    for (int i = wid; i < ninstr; i += 4) {
-      const int idx = i * 64 + lane;
-      const int idc = idx < nchunks ? idx : nchunks - 1;
-      const int f = idc / C16, c16 = idc - f * C16;
-      const int b = __builtin_amdgcn_ds_bpermute(f * 4, wtab);
-      const int frag = b >= 0 ? b + u3 : p.zero_frag;
-      const float *src = p.Wp + int64_t(frag) * (FB / 4) + c16 * 4;
-      if (idx < nchunks)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(wlds + i * 1024), 16, 0, 0);
+    int f0 = wid;
+    do {   // (a pass past the last fragment loads zeros and stores nothing)
+      f32x4 t[2][NQ];
+      int dst[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int fi = f0 + 4 * h;
+        int src = 0;
+#pragma unroll
+        for (int mm = 0; mm < MG; ++mm) {
+          const int sv = (fi < p.fpm && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
+          src = mi == mm ? sv : src;
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) t[h][q] = load_x4(rw, src + alane, q * QB);
+        dst[h] = (mi * p.fpm + fi) * FB + alane;
+      }
+      if (f0 == wid) {
+        int sofs;
+        const __amdgpu_buffer_rsrc_t r0 = b_rsrc(0, &sofs);
+#pragma unroll
+        for (int o = 0; o < NO; ++o) B0[o] = load_x4(r0, off[o], sofs);
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        if (f0 + 4 * h < p.fpm) {
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) *reinterpret_cast<f32x4 *>(wlds + dst[h] + q * QB) = t[h][q];
+        }
+    } while ((f0 += 8) < p.fpm);
+    // the all-zero fragment that stands in for tiles a member lacks
+    if (wid == 3) {
+#pragma unroll
+      for (int q = 0; q < NQ; ++q)
+        *reinterpret_cast<f32x4 *>(wlds + MG * p.fpm * FB + q * QB + (lane & (QB / 16 - 1)) * 16) =
+            f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    __builtin_amdgcn_s_waitcnt(0);   // this wave's direct loads have landed in LDS
 #ifdef RBGP_EXPERIMENT
     if (lane == 0) tr[7] = __builtin_amdgcn_s_memrealtime();
 #endif
-    __syncthreads();                 // ... and everybody else's
+    __syncthreads();
   }
   if (!valid) return;
 #ifdef RBGP_EXPERIMENT
@@ -278,7 +294,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   }
   __builtin_amdgcn_s_waitcnt(0);
 #ifdef RBGP_EXPERIMENT
-  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); }
+  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); tr[2] = __builtin_readcyclecounter(); }
 #endif
 
   // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Register t of the sum
@@ -296,7 +312,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
       float *o = p.O + m * p.ldO + n0 + j * 4;
       if (vec_ok) {
-        *reinterpret_cast<f32x4 *>(o) = f32x4{v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4 *>(o));
       } else {
 #pragma unroll
         for (int w = 0; w < 4; ++w)
@@ -327,7 +343,7 @@ const RegEntry *find_reg(int KC, int RS) {
 
 struct RegTables {  // device tables of the clustering
   int ncl = 0;
-  int32_t *stages = nullptr, *counts = nullptr, *members = nullptr, *wsrc = nullptr;
+  int32_t *stages = nullptr, *counts = nullptr, *members = nullptr;
 };
 
 struct RegState {
@@ -336,7 +352,6 @@ struct RegState {
   RegTables tab;                   // fp32: clusters of one 16-row group
   RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
   int tab_bf16_G = 0;
-  bool lds_attr_set[2] = {false, false};
 };
 
 template <typename T>
@@ -350,7 +365,6 @@ void free_tables(RegTables *t) {
   if (t->stages) (void)hipFree(t->stages);
   if (t->counts) (void)hipFree(t->counts);
   if (t->members) (void)hipFree(t->members);
-  if (t->wsrc) (void)hipFree(t->wsrc);
   *t = RegTables();
 }
 
@@ -481,19 +495,8 @@ int build_tables(const rbgp_mask *m, int U, RegTables *t) {
     }
     counts[c] = st;
   }
-  // LDS fragment slot mm * fpm + fi  ->  packed fragment index of G_i vertex 0 (-1: all zeros)
-  const int fpm = d1 * pl.NSTG;
-  std::vector<int32_t> wsrc(size_t(ncl) * 64, -1);
-  if (U * fpm <= 63)
-    for (int c = 0; c < ncl; ++c)
-      for (int k = 0; k < U; ++k)
-        for (int fi = 0; fi < fpm; ++fi)
-          if (members[size_t(c) * U + k] >= 0)
-            wsrc[size_t(c) * 64 + k * fpm + fi] = (members[size_t(c) * U + k] * fpm + fi) * m->a[2];
   t->ncl = ncl;
-  int rc = upload(wsrc, &t->wsrc);
-  if (rc) return rc;
-  rc = upload(stages, &t->stages);
+  int rc = upload(stages, &t->stages);
   if (rc) return rc;
   rc = upload(counts, &t->counts);
   if (rc) return rc;
@@ -526,14 +529,28 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
   // I and the packed weights are addressed through 32-bit buffer offsets
   const int es = bf16 ? 2 : 4;
+  // bf16: a lane loads 8 bytes (4 columns; 64-column wave tile) or 16 bytes (8 columns;
+  // 128-column tile) per row.  The wide tile is the default where the operands allow it and
+  // enough column tiles remain to fill the chip.
+  int CW = 64;
+  if (bf16) {
+    const bool ok64 = (ldI % 4 == 0) && (reinterpret_cast<uintptr_t>(I) % 8 == 0);
+    const bool ok128 = (ldI % 8 == 0) && (reinterpret_cast<uintptr_t>(I) % 16 == 0);
+    const int tc = tune[RBGP_TUNE_COLS_PER_WORKGROUP];
+    if (tc != 0 && tc != 64 && tc != 128) return RBGP_EUNSUPPORTED;
+    if (tc)
+      CW = tc;
+    else if (ok128 && int64_t((m->a[0] + pl.MG - 1) / pl.MG) * m->a[2] * ((N + 127) / 128) >= 512)
+      CW = 128;
+    if (!(CW == 128 ? ok128 : ok64)) return RBGP_ESHAPE;
+  }
+  const int NC = CW / 16;
   // (bf16: two columns share a dword, and a dword that crosses the end of the descriptor reads
-  // as zero, so the extent is rounded up to the 8 bytes a lane loads; ldI % 4 == 0 keeps that
-  // inside the K x ldI array)
-  const int64_t i_bytes = ((m->K - 1) * ldI + (bf16 ? (N + 3) / 4 * 4 : N)) * es;
+  // as zero, so the extent is rounded up to the bytes a lane loads; the condition on ldI keeps
+  // that inside the K x ldI array)
+  const int64_t i_bytes = ((m->K - 1) * ldI + (bf16 ? (N + NC - 1) / NC * NC : N)) * es;
   const int64_t w_bytes = (bf16 ? pl.packed_elems_bf16 : pl.packed_elems) * es;
   if (i_bytes >= (int64_t(1) << 31) || w_bytes >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
-  // the bf16 kernels load 8 bytes (4 columns) per lane and row
-  if (bf16 && ((ldI % 4) || (reinterpret_cast<uintptr_t>(I) & 7))) return RBGP_ESHAPE;
   RegState *st = static_cast<RegState *>(*state);
   if (!st) {
     st = new (std::nothrow) RegState();
@@ -543,7 +560,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   int32_t **rowtab = bf16 ? &st->rowtab_bf16 : &st->rowtab;
   if (!*rowtab) {
     const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
-    const int len = bf16 ? ((pl.KC + 15) / 16) * 16 : pl.NO * 4;   // contraction steps, padded (padding -> row 0)
+    const int len = bf16 ? 32 * rbgp_bf16_blocks32(pl.KC) + (rbgp_bf16_tail16(pl.KC) ? 16 : 0) : pl.NO * 4;   // contraction steps, padded (padding -> row 0)
     std::vector<int32_t> rt(size_t(a3) * len, 0);
     for (int u3 = 0; u3 < a3; ++u3)
       for (int kk = 0; kk < pl.KC; ++kk) {
@@ -553,10 +570,11 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     int rc = upload(rt, rowtab);
     if (rc) return rc;
   }
-  const int64_t ntiles = (N + 63) / 64;
+  const int64_t ntiles = (N + CW - 1) / CW;
   // bf16: 16-row groups per wave (G) and waves per column tile (S).  More groups mean fewer
-  // passes of I through the load path; the split keeps at least two waves per SIMD in flight
-  // when that leaves few (cluster, column tile) pairs.
+  // passes of I through the load path at the price of multiplied zeros; measured on the VGG19
+  // conv3 shape the two balance out, so the default is one group.  The stage list is split
+  // when there are fewer (cluster, G_i vertex, column tile) triples than SIMDs.
   int G = 1, lgS = 0;
   auto stages_fit = [&](int g) { return int64_t(std::min(m->c[0], m->d[0] * g * pl.MG)) * pl.NSTG <= 60; };
   if (bf16) {
@@ -564,15 +582,13 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (tg) {
       if ((tg != 1 && tg != 2 && tg != 4) || !stages_fit(tg)) return RBGP_EUNSUPPORTED;
       G = tg;
-    } else {
-      while (G < 4 && G * pl.MG < m->a[0] && stages_fit(2 * G)) G *= 2;
     }
     const int64_t ncl = (m->a[0] + G * pl.MG - 1) / (G * pl.MG);
     if (ts) {
       if (ts != 1 && ts != 2 && ts != 4) return RBGP_EUNSUPPORTED;
       lgS = ts == 4 ? 2 : ts == 2 ? 1 : 0;
     } else {
-      while (lgS < 2 && ((ncl * m->a[2] * ntiles) << lgS) < 2048) ++lgS;
+      while (lgS < 2 && ((ncl * m->a[2] * ntiles) << lgS) < 1024) ++lgS;
     }
   }
   RegTables *tab = bf16 ? &st->tab_bf16 : &st->tab;
@@ -587,14 +603,15 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   const RegEntry *e = find_reg(pl.KC, pl.RS);
   if (!e) return RBGP_EUNSUPPORTED;
   const int fpm = m->d[0] * pl.NSTG;
-  const int fb = (bf16 ? ((pl.KC + 15) / 16 + 1) / 2 : pl.NQ) * 4 * pl.RS * 16;
+  const int fb = (bf16 ? rbgp_bf16_blocks32(pl.KC) + (rbgp_bf16_tail16(pl.KC) ? 1 : 0) : pl.NQ) * 4 * pl.RS * 16;
   size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
   // Weights stream from global memory by default: measured on the VGG19 conv5 shape, filling
   // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
   // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
   // LDS variant whenever the weights fit.
-  const bool wlds = !bf16 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024 && pl.MG * fpm <= 63;
-  if (bf16) lds = lgS ? size_t(4) * G * 4 * 1024 : 0;   // partial sums of the split: 4 waves x 4G units x 1 KB
+  const bool wlds = !bf16 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024;
+  // partial sums of the split: per wave the (S - 1) / S of its 4G units it does not own
+  if (bf16) lds = size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (NC / 4) * 1024;
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
@@ -606,23 +623,19 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
   rp.fpm = fpm;
-  rp.zero_frag = m->a[0] * fpm * m->a[2];
   rp.tm = m->a[1] * m->a[2] * m->a[3];
   for (int r = 0; r < 16; ++r) rp.rowofs[r] = (r / m->a[3]) * m->a[2] * m->a[3] + r % m->a[3];
-  rp.wsrc = tab->wsrc;
   rp.ntiles = int(ntiles);
   rp.lgS = lgS;
   const int64_t tiles_per_wg = 4 >> lgS;
   const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
   const int64_t qgroups = (nquads + 7) / 8;
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
-  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G) : wlds ? e->lds_fn : e->global_fn;
+  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : wlds ? e->lds_fn : e->global_fn;
   if (!fn) return RBGP_EUNSUPPORTED;
-  if (wlds && lds > 64 * 1024 && !st->lds_attr_set[0]) {
+  if (lds > 64 * 1024 && (wlds || bf16))   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));
-    st->lds_attr_set[0] = true;
-  }
 #ifdef RBGP_EXPERIMENT
   static unsigned long long *trace_buf = nullptr;
   static int launches = 0;

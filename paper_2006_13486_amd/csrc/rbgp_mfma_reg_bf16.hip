@@ -12,14 +12,19 @@
 //    (wave k takes stages k, k + S, ...), which keeps the chip full when larger clusters
 //    leave fewer independent (cluster, column tile) pairs; the partial sums meet in LDS.
 //
-// The matrix core wants, per lane, four consecutive contraction steps of ONE column, while
-// I holds consecutive columns of one row.  A lane therefore loads 8 bytes (columns 4j..4j+3)
-// from each of its four rows (contraction steps 16kb + 4kg .. +3 of k-block kb, kg = lane/16)
-// and transposes the 4x4 block of bf16 in registers (8 v_perm_b32), which yields the B
-// operands of four MFMAs (one per column offset w), shared by all G groups.  The weights
-// are packed k-major by rbgp_pack, so an A operand is an 8-byte piece of a 16-byte load.
+// The matrix core wants, per lane, eight (four in the 16-step form) consecutive contraction
+// steps of ONE column, while I holds consecutive columns of one row.  A lane therefore loads
+// NC = 4 or 8 columns (8 or 16 bytes; a wave covers 16 * NC columns) from each of its eight
+// rows (contraction steps 32b + 8kg .. +7 of block b, kg = lane/16) and transposes the
+// 8 x NC block of bf16 in registers (4 v_perm_b32 per column), which yields the B operands
+// of NC MFMAs (one per column offset w), shared by all G groups.  The 16-byte form moves twice the bytes per
+// load instruction, and the load path's rate is set by instructions (measured: about 29
+// bytes/clock/CU with 8-byte loads against 45-50 with 16-byte ones).  The weights are packed
+// k-major by rbgp_pack, so an A operand is one 16-byte load (its first 8 bytes in the
+// 16-step form).
 #include <hip/hip_runtime.h>
 
+#include "rbgp_internal.h"
 #include "rbgp_reg_common.h"
 
 using namespace rbgp_reg;
@@ -28,9 +33,25 @@ namespace {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ u32x2 load_x2(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+// one lane's piece of a row of I: LW dwords = 2 * LW bf16 columns
+template <int LW>
+struct Raw {
+  unsigned d[LW];
+};
+template <int LW>
+__device__ __forceinline__ Raw<LW> load_raw(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+  Raw<LW> x;
+  if constexpr (LW == 2) {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+    x.d[0] = v[0]; x.d[1] = v[1];
+  } else {
+    static_assert(LW == 4, "8 or 16 bytes per lane");
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    x.d[0] = v[0]; x.d[1] = v[1]; x.d[2] = v[2]; x.d[3] = v[3];
+  }
+  return x;
 }
 __device__ __forceinline__ u32x4 load_u4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
@@ -40,19 +61,29 @@ __device__ __forceinline__ s16x4 as_s16x4(unsigned lo, unsigned hi) {
   return __builtin_bit_cast(s16x4, v);
 }
 
-template <int KC, int RS, int G>
+template <int KC, int RS, int G, int CW>
 __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
+  constexpr int NC = CW / 16;            // columns per lane: 4 or 8
+  constexpr int LW = NC / 2;             // dwords per lane and row
+  constexpr int NH = NC / 4;             // 16-byte pieces of a lane's output row
   constexpr int MG = 16 / RS;            // tile rows per 16-row group
   constexpr int U = G * MG;              // tile rows per cluster
-  constexpr int NKB = (KC + 15) / 16;    // k-blocks (16 contraction steps) per stage
-  constexpr int NQ = (NKB + 1) / 2;      // weights of two k-blocks come as one 16-byte load
-  constexpr int QB = 4 * RS * 16;        // bytes of one such load across the fragment
-  constexpr int FB = NQ * QB;            // bytes of one weight fragment
-  constexpr int CW = 64;
-  extern __shared__ __attribute__((aligned(16))) unsigned char red[];   // [wave][G*4 units][64 lanes] x 16 B
+  // A stage's KC contraction steps are cut into NK32 blocks of 32 (v_mfma_f32_16x16x32_bf16)
+  // and, when at most 16 remain, one block of 16 (v_mfma_f32_16x16x16_bf16).
+  constexpr int NK32 = rbgp_bf16_blocks32(KC);
+  constexpr bool TAIL = rbgp_bf16_tail16(KC);
+  constexpr int NB = NK32 + (TAIL ? 1 : 0);   // blocks = 16-byte weight loads per lane and stage
+  constexpr int NLD = 8 * NK32 + (TAIL ? 4 : 0);   // rows of I a lane loads per stage
+  constexpr int QB = 4 * RS * 16;        // bytes of one weight load across the fragment
+  constexpr int FB = NB * QB;            // bytes of one weight fragment
+  extern __shared__ __attribute__((aligned(16))) unsigned char red[];   // partial sums of a split stage list
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   const int lgS = p.lgS, S = 1 << lgS;
+#ifdef RBGP_EXPERIMENT
+  unsigned long long *tr = p.trace + ((size_t(blockIdx.y) * gridDim.z + blockIdx.z) * gridDim.x + blockIdx.x) * 32 + wid * 8;
+  if (lane == 0) tr[0] = __builtin_amdgcn_s_memrealtime();
+#endif
   const int ks = wid & (S - 1);          // this wave's share of the stage list
   // workgroup -> (XCD, cluster, G_i vertex, 4/S neighbouring column tiles); see the fp32 kernel
   const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.y;
@@ -66,12 +97,17 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   int mem[U];
 #pragma unroll
   for (int mm = 0; mm < U; ++mm) mem[mm] = p.members[cl * U + mm];
-  const int32_t *rt = p.rowtab + u3 * (NKB * 16) + kg * 4;
-  int rrow[NKB][4];
+  // stage-relative row of I of each of the lane's loads (padding steps -> row 0)
+  const int32_t *rt = p.rowtab + u3 * (32 * NK32 + (TAIL ? 16 : 0));
+  int rrow[NLD];
 #pragma unroll
-  for (int kb = 0; kb < NKB; ++kb)
+  for (int b = 0; b < NK32; ++b)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) rrow[kb][t] = rt[kb * 16 + t];
+    for (int t = 0; t < 8; ++t) rrow[8 * b + t] = rt[32 * b + 8 * kg + t];
+  if constexpr (TAIL) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) rrow[8 * NK32 + t] = rt[32 * NK32 + 4 * kg + t];
+  }
   const int32_t *stg = p.stages + int64_t(cl) * (1 + U) * 64 + lane;
   const int tb = stg[0];
   int tf[U];
@@ -82,12 +118,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * U + (lane & (U - 1))];
 
-  // byte offset of this lane's 8 bytes (4 bf16 columns) in each of its rows, relative to the stage base
-  int off[NKB][4];
+  // byte offset of this lane's NC bf16 columns in each of its rows, relative to the stage base
+  int off[NLD];
 #pragma unroll
-  for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) off[kb][t] = rrow[kb][t] * (int(p.ldI) * 2) + j * 8;
+  for (int i = 0; i < NLD; ++i) off[i] = rrow[i] * (int(p.ldI) * 2) + j * (NC * 2);
   const int alane = (kg * RS + ri) * 16;
 
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
@@ -118,40 +152,71 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     return addr + alane;
   };
   __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
+#endif
 
-  f32x4 acc[G][4];
+  f32x4 acc[G][NC];
 #pragma unroll
   for (int gi = 0; gi < G; ++gi)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) acc[gi][w] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int w = 0; w < NC; ++w) acc[gi][w] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // the MFMAs of one k-block: transpose the lane's 4x4 block of bf16, then per group one MFMA
-  // per column offset
-  auto kblock = [&](const u32x2 (&raw)[4], const u32x4 (&A)[G][NQ], int q, int half) {
-    const unsigned x01l = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x05040100u);
-    const unsigned x23l = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x05040100u);
-    const unsigned x01h = __builtin_amdgcn_perm(raw[1][0], raw[0][0], 0x07060302u);
-    const unsigned x23h = __builtin_amdgcn_perm(raw[3][0], raw[2][0], 0x07060302u);
-    const unsigned y01l = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x05040100u);
-    const unsigned y23l = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x05040100u);
-    const unsigned y01h = __builtin_amdgcn_perm(raw[1][1], raw[0][1], 0x07060302u);
-    const unsigned y23h = __builtin_amdgcn_perm(raw[3][1], raw[2][1], 0x07060302u);
-    const s16x4 b0 = as_s16x4(x01l, x23l), b1 = as_s16x4(x01h, x23h);
-    const s16x4 b2 = as_s16x4(y01l, y23l), b3 = as_s16x4(y01h, y23h);
+  // The MFMAs of block b: transpose the lane's 8 x NC (4 x NC) block of bf16 (dword d of a
+  // row holds columns 2d and 2d+1), then per group one MFMA per column offset.
+  auto block = [&](auto bc, const Raw<LW> (&B)[NLD], const u32x4 (&A)[G][NB]) {
+    constexpr int b = decltype(bc)::value;
+    constexpr unsigned LO = 0x05040100u, HI = 0x07060302u;
+    if constexpr (b < NK32) {
+      const Raw<LW> *r = &B[8 * b];
+      bf16x8 bo[NC];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-      const s16x4 a = half ? as_s16x4(A[gi][q][2], A[gi][q][3]) : as_s16x4(A[gi][q][0], A[gi][q][1]);
-      acc[gi][0] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b0, acc[gi][0], 0, 0, 0);
-      acc[gi][1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b1, acc[gi][1], 0, 0, 0);
-      acc[gi][2] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b2, acc[gi][2], 0, 0, 0);
-      acc[gi][3] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b3, acc[gi][3], 0, 0, 0);
+      for (int d = 0; d < LW; ++d) {
+        bo[2 * d] = __builtin_bit_cast(
+            bf16x8, u32x4{__builtin_amdgcn_perm(r[1].d[d], r[0].d[d], LO), __builtin_amdgcn_perm(r[3].d[d], r[2].d[d], LO),
+                          __builtin_amdgcn_perm(r[5].d[d], r[4].d[d], LO), __builtin_amdgcn_perm(r[7].d[d], r[6].d[d], LO)});
+        bo[2 * d + 1] = __builtin_bit_cast(
+            bf16x8, u32x4{__builtin_amdgcn_perm(r[1].d[d], r[0].d[d], HI), __builtin_amdgcn_perm(r[3].d[d], r[2].d[d], HI),
+                          __builtin_amdgcn_perm(r[5].d[d], r[4].d[d], HI), __builtin_amdgcn_perm(r[7].d[d], r[6].d[d], HI)});
+      }
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, A[gi][b]);
+#pragma unroll
+        for (int w = 0; w < NC; ++w) acc[gi][w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bo[w], acc[gi][w], 0, 0, 0);
+      }
+    } else {
+      const Raw<LW> *r = &B[8 * NK32];
+      s16x4 bo[NC];
+#pragma unroll
+      for (int d = 0; d < LW; ++d) {
+        bo[2 * d] = as_s16x4(__builtin_amdgcn_perm(r[1].d[d], r[0].d[d], LO), __builtin_amdgcn_perm(r[3].d[d], r[2].d[d], LO));
+        bo[2 * d + 1] = as_s16x4(__builtin_amdgcn_perm(r[1].d[d], r[0].d[d], HI), __builtin_amdgcn_perm(r[3].d[d], r[2].d[d], HI));
+      }
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi) {
+        const s16x4 a = as_s16x4(A[gi][b][0], A[gi][b][1]);
+#pragma unroll
+        for (int w = 0; w < NC; ++w) acc[gi][w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, bo[w], acc[gi][w], 0, 0, 0);
+      }
     }
   };
+  // the loads of block b: its rows of I, then its weights for every group
+  auto load_block = [&](auto bc, Raw<LW> (&B)[NLD], u32x4 (&A)[G][NB], __amdgpu_buffer_rsrc_t rb2, int sofs,
+                        const int (&av)[G]) {
+    constexpr int b = decltype(bc)::value;
+    constexpr int first = 8 * b, n = b < NK32 ? 8 : 4;
+#pragma unroll
+    for (int t = 0; t < n; ++t) B[first + t] = load_raw<LW>(rb2, off[first + t], sofs);
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) A[gi][b] = load_u4(rw, av[gi], b * QB);
+    __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
+  };
 
-  // One stage: every k-block's rows of I and every pair of k-blocks' weights are refilled for
-  // the wave's stage s + 2 right after their last use, so about two stages of loads are in
-  // flight; the loop body is branch-free and its wait counts are exact.
-  auto stage = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[G][NQ], auto reload) {
+  // One stage: every block's rows of I and weights are refilled for the wave's stage s + 2
+  // right after their last use, so about two stages of loads are in flight; the loop body is
+  // branch-free and its wait counts are exact.
+  auto stage = [&](int s, Raw<LW> (&B)[NLD], u32x4 (&A)[G][NB], auto reload) {
     constexpr bool RELOAD = decltype(reload)::value;
     int sofs = 0, av[G] = {};
     __amdgpu_buffer_rsrc_t rb2 = rw;
@@ -161,42 +226,27 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
       for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, gi);
     }
-    static_for<0, NKB>([&](auto kc) {
-      constexpr int kb = decltype(kc)::value;
-      kblock(B[kb], A, kb / 2, kb % 2);
-      if constexpr (RELOAD) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
-        if constexpr (kb % 2 == 1 || kb == NKB - 1) {
-#pragma unroll
-          for (int gi = 0; gi < G; ++gi) A[gi][kb / 2] = load_u4(rw, av[gi], (kb / 2) * QB);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
-      }
+    static_for<0, NB>([&](auto bc) {
+      block(bc, B, A);
+      if constexpr (RELOAD) load_block(bc, B, A, rb2, sofs, av);
     });
   };
-  auto fill = [&](int s, u32x2 (&B)[NKB][4], u32x4 (&A)[G][NQ]) {
+  auto fill = [&](int s, Raw<LW> (&B)[NLD], u32x4 (&A)[G][NB]) {
     int sofs, av[G];
     const int tl = table_lane(s);
     const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(tl, &sofs);
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, gi);
-    static_for<0, NKB>([&](auto kc) {
-      constexpr int kb = decltype(kc)::value;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) B[kb][t] = load_x2(rb2, off[kb][t], sofs);
-      if constexpr (kb % 2 == 1 || kb == NKB - 1) {
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) A[gi][kb / 2] = load_u4(rw, av[gi], (kb / 2) * QB);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    });
+    static_for<0, NB>([&](auto bc) { load_block(bc, B, A, rb2, sofs, av); });
   };
 
-  u32x2 B0[NKB][4], B1[NKB][4];
-  u32x4 A0[G][NQ], A1[G][NQ];
+  Raw<LW> B0[NLD], B1[NLD];
+  u32x4 A0[G][NB], A1[G][NB];
   fill(0, B0, A0);
-  fill(1, B1, A1);
+  fill(1, B1, A1);   // (issued before any MFMA waits: measured faster than interleaving it with stage 0)
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[2] = __builtin_amdgcn_s_memrealtime();
+#endif
   {
     int s = 0;
     for (; s + 1 < cntw; s += 2) {
@@ -206,23 +256,32 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     if (s < cntw) stage(s, B0, A0, std::false_type{});
   }
   __builtin_amdgcn_s_waitcnt(0);
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[3] = __builtin_amdgcn_s_memrealtime();
+#endif
 
-  // Epilogue.  Unit (gi, t) = register t of group gi's four accumulators: weight row
-  // 4*(lane/16) + t of the group, lane j the columns 4j + w.
-  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
-  auto store_unit = [&](int gi, int t, f32x4 v) {
+  // Epilogue.  Unit (gi, t) = register t of group gi's NC accumulators: weight row
+  // 4*(lane/16) + t of the group, lane j the columns NC*j + w.
+  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * NC + NC <= p.N);
+  auto unit_piece = [&](int gi, int t, int h) {
+    return f32x4{acc[gi][4 * h][t], acc[gi][4 * h + 1][t], acc[gi][4 * h + 2][t], acc[gi][4 * h + 3][t]};
+  };
+  auto store_unit = [&](int gi, int t, const f32x4 (&v)[NH]) {
     const int i16 = 4 * kg + t, mm = i16 / RS, r = i16 % RS;
     const int u1 = __builtin_amdgcn_ds_bpermute((gi * MG + mm) * 4, memv);
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
     if (valid && u1 >= 0 && r < p.R) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
-      float *o = p.O + m * p.ldO + n0 + j * 4;
+      float *o = p.O + m * p.ldO + n0 + j * NC;
       if (vec_ok) {
-        *reinterpret_cast<f32x4 *>(o) = v;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) __builtin_nontemporal_store(v[h], reinterpret_cast<f32x4 *>(o) + h);
       } else {
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-          if (n0 + j * 4 + w < p.N) o[w] = v[w];
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            if (n0 + j * NC + 4 * h + w < p.N) o[4 * h + w] = v[h][w];
       }
     }
   };
@@ -230,52 +289,72 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) store_unit(gi, t, f32x4{acc[gi][0][t], acc[gi][1][t], acc[gi][2][t], acc[gi][3][t]});
-  } else {
-    // The S waves of a column tile each own the units u with u % S == their share: a wave
-    // leaves the other units in LDS and, after the barrier, adds up the ones it owns (in
-    // wave order, so the result does not depend on timing) and stores them.
-    f32x4 *mine = reinterpret_cast<f32x4 *>(red) + (wid * (G * 4)) * 64 + lane;
-#pragma unroll
-    for (int gi = 0; gi < G; ++gi)
-#pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const int u = gi * 4 + t;
-        if ((u & (S - 1)) != ks) mine[u * 64] = f32x4{acc[gi][0][t], acc[gi][1][t], acc[gi][2][t], acc[gi][3][t]};
+        f32x4 v[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) v[h] = unit_piece(gi, t, h);
+        store_unit(gi, t, v);
       }
+  } else {
+    // The S waves of a column tile each own the units u with u % S == their share.  A wave
+    // leaves the units it does not own in LDS (its region holds them densely: unit u of
+    // owner o sits at (u / S) * (S - 1) + o - (o > share)) and, after the barrier, adds up
+    // the ones it owns in wave order, so the result does not depend on timing.
+    constexpr int NU = G * 4;
+    f32x4 *const red4 = reinterpret_cast<f32x4 *>(red);
+    const int per_wave = (NU >> lgS) * (S - 1);
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int o = u & (S - 1);
+      if (o != ks) {
+        const int slot = wid * per_wave + (u >> lgS) * (S - 1) + o - (o > ks ? 1 : 0);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) red4[(slot * NH + h) * 64 + lane] = unit_piece(u / 4, u % 4, h);
+      }
+    }
     __syncthreads();
+#ifdef RBGP_EXPERIMENT
+    if (lane == 0) tr[7] = __builtin_amdgcn_s_memrealtime();
+#endif
     const int w0 = wid & ~(S - 1);
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi)
+    for (int u = 0; u < NU; ++u) {
+      if ((u & (S - 1)) == ks) {
+        f32x4 v[NH];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int u = gi * 4 + t;
-        if ((u & (S - 1)) == ks) {
-          f32x4 v = {0.f, 0.f, 0.f, 0.f};
-          for (int k = 0; k < S; ++k) {
-            const f32x4 part = k == ks ? f32x4{acc[gi][0][t], acc[gi][1][t], acc[gi][2][t], acc[gi][3][t]}
-                                       : reinterpret_cast<const f32x4 *>(red)[((w0 + k) * (G * 4) + u) * 64 + lane];
-            v += part;
+        for (int h = 0; h < NH; ++h) v[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < S; ++k) {
+          if (k == ks) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h) v[h] += unit_piece(u / 4, u % 4, h);
+          } else {
+            const int slot = (w0 + k) * per_wave + (u >> lgS) * (S - 1) + ks - (ks > k ? 1 : 0);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) v[h] += red4[(slot * NH + h) * 64 + lane];
           }
-          store_unit(gi, t, v);
         }
+        store_unit(u / 4, u % 4, v);
       }
+    }
   }
+#ifdef RBGP_EXPERIMENT
+  if (lane == 0) tr[4] = __builtin_amdgcn_s_memrealtime();
+#endif
 }
 
 struct Entry {
-  int KC, RS, G;
+  int KC, RS, G, CW;
   rbgp_reg_fn fn;
 };
-#define RBGP_B(KC, RS) {KC, RS, 1, spmm_reg_bf16<KC, RS, 1>}, {KC, RS, 2, spmm_reg_bf16<KC, RS, 2>}, \
-                       {KC, RS, 4, spmm_reg_bf16<KC, RS, 4>}
+#define RBGP_B1(KC, RS, G) {KC, RS, G, 64, spmm_reg_bf16<KC, RS, G, 64>}, {KC, RS, G, 128, spmm_reg_bf16<KC, RS, G, 128>}
+#define RBGP_B(KC, RS) RBGP_B1(KC, RS, 1), RBGP_B1(KC, RS, 2), RBGP_B1(KC, RS, 4)
 const Entry kTable[] = {RBGP_B(8, 4),  RBGP_B(18, 2), RBGP_B(36, 2), RBGP_B(72, 2), RBGP_B(18, 4),
                         RBGP_B(36, 4), RBGP_B(72, 4), RBGP_B(18, 8), RBGP_B(36, 8), RBGP_B(72, 8)};
 
 }  // namespace
 
-rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G) {
+rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G, int CW) {
   for (const Entry &e : kTable)
-    if (e.KC == KC && e.RS == RS && e.G == G) return e.fn;
+    if (e.KC == KC && e.RS == RS && e.G == G && e.CW == CW) return e.fn;
   return nullptr;
 }

@@ -37,11 +37,9 @@ struct RegParams {
   uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
   int a2, a3, a4, R;
   int fpm;                 // weight fragments per member: d_o * NSTG
-  int zero_frag;           // index of the all-zero fragment that ends the packed buffer
   int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
   int tm;                  // rows of one tile row: a_r * a_i * a_b
-  const int32_t *wsrc;     // [ncl][64]: per LDS fragment slot the packed fragment index of u_i = 0, -1: zeros
-  int ntiles;              // ceil(N / 64)
+  int ntiles;              // column tiles: ceil(N / columns per wave)
   int lgS;                 // bf16: log2 of the waves that share a column tile (split of the stage list)
 #ifdef RBGP_EXPERIMENT
   unsigned long long *trace;   // [wave][8] timestamps
@@ -59,8 +57,8 @@ __device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int
 }  // namespace rbgp_reg
 
 typedef void (*rbgp_reg_fn)(rbgp_reg::RegParams);
-// bf16 kernel for KC contraction steps per stage, RS weight rows per tile row and G 16-row
-// groups per wave; nullptr when that combination is not built.
-rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G);
+// bf16 kernel for KC contraction steps per stage, RS weight rows per tile row, G 16-row
+// groups per wave and CW (64 or 128) columns per wave; nullptr when that combination is not built.
+rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G, int CW);
 
 #endif

@@ -39,16 +39,18 @@ def test_config_register_family_cluster_sizes(w, cluster):
     gh.check_parity(w, N=1000 if w.N > 4096 else w.N, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
 
 
+@pytest.mark.parametrize("cw", [64, 128])
 @pytest.mark.parametrize("split", [1, 2, 4])
 @pytest.mark.parametrize("groups", [1, 2, 4])
-def test_bf16_register_family_row_groups_and_stage_split(groups, split):
-    """bf16 register kernels: every (16-row groups per wave, waves per column tile)
-    combination, on the conv3 shape (ragged last tile) and on a shape with fewer tile
-    rows than one cluster holds, partial 4-row block and an odd stage count."""
-    tune = (0, 0, 0, 0, groups, split)
+def test_bf16_register_family_row_groups_and_stage_split(groups, split, cw):
+    """bf16 register kernels: every (16-row groups per wave, waves per column tile,
+    columns per wave) combination, on the conv3 shape (ragged last tile) and on shapes
+    with fewer tile rows than one cluster holds, a partial 4-row block, an odd stage
+    count, 12 tile rows."""
+    tune = (0, cw, 0, 0, groups, split)
     gh.check_parity(wl.VGG19_CONV3_BF16, N=1000, kernel=REG, tune=tune, expect_kernel=REG)
     w = wl.Workload("bf16_small_cluster", (2, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9), 330, wl.BF16, 11, 12, 13, 1.0)
-    gh.check_parity(w, kernel=REG, tune=tune, ld_pad=2, expect_kernel=REG)   # (ldI must be a multiple of 4)
+    gh.check_parity(w, kernel=REG, tune=tune, ld_pad=6, expect_kernel=REG)   # (ldI must be a multiple of 8)
     w = wl.Workload("bf16_rs4", (6, 2, 4, 2), (6, 1, 4, 9), (3, 1, 2, 9), 200, wl.BF16, 21, 22, 23, 1.0)
     gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
     w = wl.Workload("bf16_12_tile_rows", (12, 1, 2, 3), (8, 1, 4, 9), (2, 1, 2, 9), 136, wl.BF16, 31, 32, 33, 1.0)
@@ -56,7 +58,7 @@ def test_bf16_register_family_row_groups_and_stage_split(groups, split):
 
 
 def test_bf16_register_family_full_size_split_shapes():
-    for tune in [(0, 0, 0, 0, 4, 4), (0, 0, 0, 0, 4, 2), (0, 0, 0, 0, 2, 2), (0, 0, 0, 0, 1, 1)]:
+    for tune in [(0, 128, 0, 0, 4, 4), (0, 128, 0, 0, 2, 2), (0, 64, 0, 0, 4, 2), (0, 64, 0, 0, 2, 2), (0, 64, 0, 0, 1, 1)]:
         gh.check_parity(wl.VGG19_CONV3_BF16, kernel=REG, tune=tune, expect_kernel=REG)
 
 
@@ -81,6 +83,9 @@ def test_ragged_columns(N, ld_pad, dtype):
     for cluster in (1, 2):
         gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, cluster), ld_pad=ld_pad if dtype == wl.F32 else pad,
                         expect_kernel=REG)
+    if dtype == wl.BF16:                              # 128-column wave tiles, with and without a stage split
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 128), ld_pad=pad, expect_kernel=REG)
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 128, 0, 0, 2, 2), ld_pad=pad, expect_kernel=REG)
 
 
 def test_empty_input_is_a_noop():
