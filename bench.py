@@ -59,6 +59,93 @@ def cpu_baseline(w, vals_f32, I_f32, out_gpu):
             "parity_err": err}
 
 
+def time_workload(w, args, torch, dev, steps, warmup, check_cols=0):
+    """Pack, run and time one workload; returns a dict (kernel time, rates, optional sampled parity)."""
+    bf16 = w.dtype == wl.BF16
+    vals = wl.kept_weights(w)
+    I = wl.activations(w)
+    if bf16:
+        vals_lib, I_lib = wl.to_bf16_bits(vals), wl.to_bf16_bits(I)
+        vals_f32, I_f32 = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(I_lib)
+    else:
+        vals_lib, I_lib, vals_f32, I_f32 = vals, I, vals, I
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    if args.kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mask, args.kernel)
+    if args.tune:
+        for knob, value in enumerate(int(x) for x in args.tune.split(",")):
+            rb.rbgp_mask_tune(mask, knob, value)
+    stream = torch.cuda.current_stream().cuda_stream
+    packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, w.dtype), 16), dtype=torch.uint8, device=dev)
+    rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
+    set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
+    nsets = max(2, min(16, -(-512 * 2**20 // set_bytes)))
+    I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
+    Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
+    Os = [torch.empty((w.M, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+    def step(i):
+        j = i % nsets
+        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
+                     Os[j].data_ptr(), w.N, stream)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / steps * 1e3
+    res = {"name": w.name, "M": w.M, "K": w.K, "N": w.N, "density": w.density,
+           "dtype": "bf16" if bf16 else "f32",
+           "rows": list(w.rows), "cols": list(w.cols), "row_deg": list(w.row_deg),
+           "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "kernel_us": us,
+           "eff_tflops": w.flops / us / 1e6, "algorithmic_gbs": w.algorithmic_bytes / us / 1e3}
+    if check_cols:
+        from oracle import naive_c
+        from oracle import rbgp_oracle as orc
+        Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+        dense_mask = orc.kron_mask(Bs)
+        W = orc.scatter_values(dense_mask, vals_f32)
+        g = np.random.Generator(np.random.PCG64(w.i_seed + 7))
+        cols = np.sort(g.choice(w.N, size=min(check_cols, w.N), replace=False))
+        Isub = np.ascontiguousarray(I_f32[:, cols])
+        ref, den = naive_c.spmm(dense_mask, W, Isub), naive_c.spmm_abs(dense_mask, W, Isub)
+        res["parity_err"] = orc.normalised_error(Os[0].cpu().numpy()[:, cols], ref, den)
+        res["parity_cols"] = int(len(cols))
+    return res
+
+
+def sweep_cases(which, args):
+    """The paper's own SDMM workloads (Tables 2 and 3) and the VGG19 layer sweep."""
+    if which == "table2":   # (sparsity of G_o, sparsity of G_i) as log2 of the inverse density
+        splits = [(0, 2), (1, 1), (0, 3), (1, 2), (2, 1), (0, 4), (1, 3), (2, 2), (3, 1)]
+        return [wl.sdmm4096_table2(o, i) for o, i in splits]
+    if which == "table3":
+        shapes = [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]
+        return [wl.sdmm4096_table3(gr, gb, d) for gr, gb in shapes for d in (2, 3, 4)]
+    dens = [int(x) for x in args.sweep_density.split(",")]
+    dts = {"f32": [wl.F32], "bf16": [wl.BF16], "both": [wl.F32, wl.BF16]}[args.sweep_dtype]
+    return [wl.vgg19_sweep_workload(layer, d, dt) for dt in dts for d in dens for layer in range(len(wl.VGG19_LAYERS))]
+
+
+def run_sweep(args, torch, dev):
+    cases = []
+    for w in sweep_cases(args.sweep, args):
+        try:
+            r = time_workload(w, args, torch, dev, args.sweep_steps, args.sweep_steps, args.sweep_check)
+        except rb.RbgpError as e:   # a cell whose factors cannot be sampled (recorded, not hidden)
+            r = {"name": w.name, "error": str(e)}
+        print(f"[sweep] {r}", file=sys.stderr, flush=True)
+        cases.append(r)
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": args.sweep, "unit": "us per rbgp_spmm launch (HIP events), effective TFLOP/s = 2*nnz*N/t",
+                      "steps": args.sweep_steps, "data": "synthetic", "cases": cases}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +157,13 @@ def main():
     ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", default="", choices=["", "table2", "table3", "vgg19"],
+                    help="time a family of workloads instead of the headline one: the paper's 4096^3 SDMM of "
+                         "Table 2 / Table 3, or the 16 VGG19 conv layers; prints one JSON line with all cases")
+    ap.add_argument("--sweep-steps", type=int, default=300)
+    ap.add_argument("--sweep-check", type=int, default=32, help="output columns per case checked against the oracle (0: none)")
+    ap.add_argument("--sweep-density", default="2,3", help="vgg19 sweep: log2 of the inverse densities")
+    ap.add_argument("--sweep-dtype", default="both", choices=["f32", "bf16", "both"])
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run ten 64 MiB device-to-device copies and exit (reference for the FETCH_SIZE / "
                          "WRITE_SIZE counters)")
@@ -88,6 +182,9 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": a.numel() * 4, "copies": 10}))
+        return
+    if args.sweep:
+        run_sweep(args, torch, dev)
         return
     w = WORKLOADS[args.workload]
     bf16 = w.dtype == wl.BF16

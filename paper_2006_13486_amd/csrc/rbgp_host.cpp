@@ -179,6 +179,144 @@ void rbgp_plan_reg(rbgp_mask *m) {
     p.packed_elems_bf16 = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * nq_bf16 * 4 * p.RS * 8;
   }
   m->reg = p;
+  if (p.ok) rbgp_reg_cluster(m, p.MG, &m->reg_clusters);
+}
+
+// Register-streaming family: group the tile rows into clusters of U whose adjacency lists
+// overlap most (greedy: seed with the lowest free tile row, add the free row that enlarges
+// the union of tiles least; then local search, and exhaustive matching for pairs), and
+// list for every cluster the stages it walks.
+void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
+  const rbgp_reg_plan &pl = m->reg;
+  const int a1 = m->a[0], c1 = m->c[0], d1 = m->d[0];
+  const int ncl = (a1 + U - 1) / U;
+  std::vector<int32_t> members(size_t(ncl) * U, -1);
+  std::vector<char> used(a1, 0);
+  std::vector<std::vector<char>> has(a1, std::vector<char>(c1, 0));
+  for (int u = 0; u < a1; ++u)
+    for (int j = 0; j < d1; ++j) has[u][m->adj[0][size_t(u) * d1 + j]] = 1;
+  for (int c = 0; c < ncl; ++c) {
+    std::vector<char> uni(c1, 0);
+    for (int k = 0; k < U; ++k) {
+      int best = -1, best_grow = 1 << 30;
+      for (int u = 0; u < a1; ++u) {
+        if (used[u]) continue;
+        int grow = 0;
+        for (int v = 0; v < c1; ++v) grow += has[u][v] && !uni[v];
+        if (grow < best_grow) { best_grow = grow; best = u; }
+      }
+      if (best < 0) break;
+      used[best] = 1;
+      members[size_t(c) * U + k] = best;
+      for (int v = 0; v < c1; ++v) uni[v] |= has[best][v];
+    }
+  }
+  // Local search: swap members between two clusters while that lowers the larger of their
+  // two unions, or keeps it and lowers the sum.  The longest cluster sets the kernel's
+  // duration (one wave per SIMD), the sum its total work.
+  auto union_size = [&](int c) {
+    int n = 0;
+    for (int v = 0; v < c1; ++v) {
+      bool any = false;
+      for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v];
+      n += any;
+    }
+    return n;
+  };
+  for (bool improved = true; improved;) {
+    improved = false;
+    for (int ca = 0; ca < ncl; ++ca)
+      for (int cb = ca + 1; cb < ncl; ++cb)
+        for (int ka = 0; ka < U; ++ka)
+          for (int kb = 0; kb < U; ++kb) {
+            const int ua = union_size(ca), ub = union_size(cb);
+            std::swap(members[size_t(ca) * U + ka], members[size_t(cb) * U + kb]);
+            const int na = union_size(ca), nb = union_size(cb);
+            const bool better = std::max(na, nb) < std::max(ua, ub) ||
+                                (std::max(na, nb) == std::max(ua, ub) && na + nb < ua + ub);
+            if (better)
+              improved = true;
+            else
+              std::swap(members[size_t(ca) * U + ka], members[size_t(cb) * U + kb]);
+          }
+  }
+  // Pairs (U == 2): exhaustive matching by depth-first search with the local-search result
+  // as the bound, minimising (largest union, sum of unions); bounded effort.
+  if (U == 2 && a1 % 2 == 0 && a1 <= 64) {
+    std::vector<std::vector<int>> un(a1, std::vector<int>(a1, 0));
+    for (int x = 0; x < a1; ++x)
+      for (int y = 0; y < a1; ++y) {
+        int n = 0;
+        for (int v = 0; v < c1; ++v) n += has[x][v] || has[y][v];
+        un[x][y] = n;
+      }
+    int best_max = 0, best_sum = 0;
+    for (int c = 0; c < ncl; ++c) {
+      const int n = un[members[2 * c]][members[2 * c + 1]];
+      best_max = std::max(best_max, n);
+      best_sum += n;
+    }
+    std::vector<int32_t> cur(members.size()), best = members;
+    std::vector<char> taken(a1, 0);
+    long budget = 4000000;
+    // recursive lambda via explicit std::function-free trick
+    struct Rec {
+      const std::vector<std::vector<int>> &un; std::vector<int32_t> &cur, &best; std::vector<char> &taken;
+      int a1; int &best_max, &best_sum; long &budget;
+      void go(int depth, int cmax, int csum) {
+        if (budget-- <= 0) return;
+        int x = 0;
+        while (x < a1 && taken[x]) ++x;
+        if (x == a1) {
+          if (cmax < best_max || (cmax == best_max && csum < best_sum)) { best_max = cmax; best_sum = csum; best = cur; }
+          return;
+        }
+        taken[x] = 1;
+        for (int y = x + 1; y < a1; ++y) {
+          if (taken[y]) continue;
+          const int n = un[x][y], nmax = std::max(cmax, n), nsum = csum + n;
+          if (nmax > best_max || (nmax == best_max && nsum >= best_sum)) continue;
+          taken[y] = 1;
+          cur[2 * depth] = x; cur[2 * depth + 1] = y;
+          go(depth + 1, nmax, nsum);
+          taken[y] = 0;
+        }
+        taken[x] = 0;
+      }
+    } rec{un, cur, best, taken, a1, best_max, best_sum, budget};
+    rec.go(0, 0, 0);
+    members = best;
+  }
+  std::vector<int32_t> counts(ncl, 0);
+  std::vector<int32_t> stages(size_t(ncl) * (1 + U) * 64, -1);
+  for (int c = 0; c < ncl; ++c) {
+    int st = 0;
+    for (int v1 = 0; v1 < c1; ++v1) {
+      bool any = false;
+      for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v1];
+      if (!any) continue;
+      for (int sg = 0; sg < pl.NSTG; ++sg, ++st) {
+        if (st >= 60) continue;   // does not fit the per-lane table: counted, not stored
+        stages[(size_t(c) * (1 + U)) * 64 + st] =
+            int32_t((int64_t(v1) * m->c[1] + int64_t(sg) * pl.VC) * m->c[2] * m->c[3]);
+        for (int k = 0; k < U; ++k) {
+          const int u1 = members[size_t(c) * U + k];
+          if (u1 < 0 || !has[u1][v1]) continue;
+          int j1 = 0;
+          while (m->adj[0][size_t(u1) * d1 + j1] != v1) ++j1;
+          stages[(size_t(c) * (1 + U) + 1 + k) * 64 + st] = j1 * pl.NSTG + sg;
+        }
+      }
+    }
+    counts[c] = st;
+  }
+  out->U = U;
+  out->ncl = ncl;
+  out->max_stages = 0;
+  for (int c = 0; c < ncl; ++c) out->max_stages = std::max(out->max_stages, int(counts[c]));
+  out->members.swap(members);
+  out->stages.swap(stages);
+  out->counts.swap(counts);
 }
 
 // Packed layouts.

@@ -43,6 +43,17 @@ struct rbgp_reg_plan {
   int64_t packed_elems_bf16 = 0;  // bf16 layout
 };
 
+// Clustering of the tile rows for the register-streaming family (host tables).
+struct rbgp_reg_clusters {
+  int U = 0;                      // tile rows per cluster
+  int ncl = 0;
+  int max_stages = 0;             // longest stage list (the kernels hold at most 60)
+  std::vector<int32_t> members;   // [ncl][U] tile rows, -1: none
+  std::vector<int32_t> stages;    // [ncl][1+U][64]: base row of I per stage, then per member the
+                                  //   position of its weight fragment (-1: member lacks the tile)
+  std::vector<int32_t> counts;    // [ncl] stages per cluster
+};
+
 struct rbgp_mask {
   int32_t a[4], c[4], d[4], e[4];     // rows, cols, left degree, right degree of each factor
   std::vector<int32_t> adj[4];        // adjacency lists, a[i] x d[i], ascending
@@ -52,11 +63,11 @@ struct rbgp_mask {
   int kernel_choice;                  // RBGP_KERNEL_*
   rbgp_mfma_plan plan;
   rbgp_reg_plan reg;
+  rbgp_reg_clusters reg_clusters;     // clusters of reg.MG tile rows (when reg.ok)
   mutable rbgp_device_state *dev;     // lazily created device tables
 };
 
-enum { RBGP_NUM_KERNELS = 4 };
-#define RBGP_REG_G 8   // lane groups of the register-streaming family (part of its packed layout)  // one more than the largest RBGP_KERNEL_* value
+enum { RBGP_NUM_KERNELS = 4 };   // one more than the largest RBGP_KERNEL_* value
 
 // device part
 void rbgp_device_release(rbgp_device_state *dev);
@@ -69,5 +80,6 @@ void rbgp_reg_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);
+void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm);
