@@ -70,14 +70,15 @@ enum {
 /* tuning knobs (rbgp_mask_tune) */
 enum {
   RBGP_TUNE_COLS_PER_LANE = 0,        /* MFMA: 1 or 2 */
-  RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128 */
+  RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128; MFMA_REG bf16: columns per wave, 64 or 128 */
   RBGP_TUNE_GROUPS_PER_WORKGROUP = 2, /* MFMA: a divisor of |G_i.U| */
   RBGP_TUNE_WEIGHTS_IN_LDS = 3,       /* MFMA_REG fp32: 2 = copy the workgroup's weights to LDS first
                                          (when they fit 160 KB) instead of streaming them */
   RBGP_TUNE_ROW_GROUPS = 4,           /* MFMA_REG bf16: 16-row MFMA groups per wave, 1, 2 or 4 (each
                                          loaded row of I is reused by all of them) */
-  RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG bf16: waves that share a column tile and split its
-                                         nonzero tiles between them, 1, 2 or 4 */
+  RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG: waves that share a column tile and split its
+                                         nonzero tiles between them, 1, 2 or 4 (default: 1 unless N
+                                         is too small to give every SIMD a wave) */
   RBGP_NUM_TUNE = 6
 };
 
@@ -161,8 +162,10 @@ int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *de
  * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  The
  * RBGP_KERNEL_MFMA family needs dev_I 16-byte aligned and ldI a multiple of 4
  * (fp32) or 8 (bf16) elements, the RBGP_KERNEL_MFMA_REG family in bf16 mode dev_I
- * 8-byte aligned and ldI a multiple of 4 (ESHAPE otherwise; it reads the last row
- * of I up to the next multiple of 4 columns, inside the K x ldI array); the other
+ * 8-byte aligned and ldI a multiple of 4 (64-column wave tiles), or 16-byte aligned
+ * and ldI a multiple of 8 (128-column tiles, taken by default when both hold and N
+ * is large enough); ESHAPE otherwise.  In bf16 mode it reads the last row of I up
+ * to the next multiple of 4 (8) columns, inside the K x ldI array.  The other
  * cases take any alignment.  dev_packed must have been packed with the same kernel family and
  * dtype.  Asynchronous on `hip_stream`. */
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,

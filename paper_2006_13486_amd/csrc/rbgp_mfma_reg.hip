@@ -79,10 +79,15 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // (grid x = 8 * clusters is a multiple of 8, so the XCD of a workgroup is x & 7 whatever y, z)
   // The column-tile index is the slowest grid dimension: all (cluster, G_i vertex) pairs of the
   // same columns are dispatched together, so I comes from HBM once however large N is.
+  // The stage list of a cluster can be split over S = 1, 2 or 4 waves of the workgroup (wave
+  // k takes stages k, k + S, ...; the partial sums meet in LDS): the workgroup then covers
+  // 4 / S column tiles.  Used when N is too small to give every SIMD a wave otherwise.
+  const int lgS = p.lgS, S = 1 << lgS;
+  const int ks = wid & (S - 1);
   const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.y;
   const int ntq = xcd + 8 * int(blockIdx.z);
-  if (ntq * 4 >= p.ntiles) return;
-  const int nt = ntq * 4 + wid;
+  if ((ntq << (2 - lgS)) >= p.ntiles) return;
+  const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
   const int g = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;    // as a weight lane: member of the group, row of the member
@@ -101,9 +106,15 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   int tf[MG];
 #pragma unroll
   for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
-  const int cnt = p.counts[cl];
+  const int cnt0 = p.counts[cl];
+  const int cnt = cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0;   // stages of this wave
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * MG + (lane & (MG - 1))];
+  // table lane of the wave's s-th stage; lanes past the cluster's count hold sentinels
+  auto table_lane = [&](int s) {
+    const int gs = ks + (s << lgS);
+    return gs < 63 ? gs : 63;
+  };
 
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
@@ -117,7 +128,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.Wp), 0, p.w_bytes, kRsrcFlags);
   // A stage past the end reads I through a descriptor of zero extent: zeros, no memory access.
   auto b_rsrc = [&](int s, int *sofs) {
-    const int base_row = __builtin_amdgcn_readlane(tb, s);
+    const int base_row = __builtin_amdgcn_readlane(tb, table_lane(s));
     *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 4);
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.I), 0,
                                              (base_row >= 0 && valid) ? p.i_bytes : 0u, kRsrcFlags);
@@ -176,7 +187,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #endif
     __syncthreads();
   }
-  if (!valid) return;
+  if (!valid && lgS == 0) return;   // (with a split stage list every wave reaches the barrier below)
 #ifdef RBGP_EXPERIMENT
   if (lane == 0) tr[6] = __builtin_amdgcn_s_memrealtime();
 #endif
@@ -196,9 +207,10 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // per-lane byte address (LDS) or offset (global) of the stage's weights
   auto a_addr = [&](int s) {
     int addr = 0;
+    const int tl = table_lane(s);
 #pragma unroll
     for (int mm = 0; mm < MG; ++mm) {
-      const int fi = __builtin_amdgcn_readlane(tf[mm], s);
+      const int fi = __builtin_amdgcn_readlane(tf[mm], tl);
       int sv;
       if constexpr (WLDS)
         sv = (fi >= 0 ? mm * p.fpm + fi : MG * p.fpm) * FB;
@@ -297,26 +309,59 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); tr[2] = __builtin_readcyclecounter(); }
 #endif
 
-  // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Register t of the sum
-  // holds weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
+  // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Unit t of the sum holds
+  // weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
   const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    float v[4];
+  auto unit = [&](int t) {
+    f32x4 v;
 #pragma unroll
     for (int w = 0; w < 4; ++w) v[w] = (acc[w][t] + acc[w][4 + t]) + (acc[w][8 + t] + acc[w][12 + t]);
+    return v;
+  };
+  auto store_unit = [&](int t, f32x4 v) {
     const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
     const int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
-    if (u1 >= 0 && r < p.R) {
+    if (valid && u1 >= 0 && r < p.R) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
       float *o = p.O + m * p.ldO + n0 + j * 4;
       if (vec_ok) {
-        __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4 *>(o));
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
       } else {
 #pragma unroll
         for (int w = 0; w < 4; ++w)
           if (n0 + j * 4 + w < p.N) o[w] = v[w];
+      }
+    }
+  };
+  if (lgS == 0) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) store_unit(t, unit(t));
+  } else {
+    // The S waves of a column tile each own the units t with t % S == their share.  A wave
+    // leaves the units it does not own in LDS (densely: unit t of owner o sits at
+    // (t / S) * (S - 1) + o - (o > share)) and, after the barrier, adds up the ones it owns in
+    // wave order, so the result does not depend on timing.
+    f32x4 *const red4 = reinterpret_cast<f32x4 *>(wlds);
+    const int per_wave = (4 >> lgS) * (S - 1);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int o = t & (S - 1);
+      if (o != ks) red4[(wid * per_wave + (t >> lgS) * (S - 1) + o - (o > ks ? 1 : 0)) * 64 + lane] = unit(t);
+    }
+    __syncthreads();
+    const int w0 = wid & ~(S - 1);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if ((t & (S - 1)) == ks) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < S; ++k) {
+          if (k == ks)
+            v += unit(t);
+          else
+            v += red4[((w0 + k) * per_wave + (t >> lgS) * (S - 1) + ks - (ks > k ? 1 : 0)) * 64 + lane];
+        }
+        store_unit(t, v);
       }
     }
   }
@@ -458,8 +503,8 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   // conv3 shape the two balance out, so the default is one group.  The stage list is split
   // when there are fewer (cluster, G_i vertex, column tile) triples than SIMDs.
   int G = 1, lgS = 0;
-  if (bf16) {
-    const int tg = tune[RBGP_TUNE_ROW_GROUPS], ts = tune[RBGP_TUNE_K_SPLIT];
+  {
+    const int tg = bf16 ? tune[RBGP_TUNE_ROW_GROUPS] : 0, ts = tune[RBGP_TUNE_K_SPLIT];
     if (tg) {
       if (tg != 1 && tg != 2 && tg != 4) return RBGP_EUNSUPPORTED;   // (too long a stage list is rejected below)
       G = tg;
@@ -490,9 +535,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
   // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
   // LDS variant whenever the weights fit.
-  const bool wlds = !bf16 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024;
+  // (the LDS-weights variant is built without the split: its LDS holds the weights)
+  const bool wlds = !bf16 && lgS == 0 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024;
   // partial sums of the split: per wave the (S - 1) / S of its 4G units it does not own
-  if (bf16) lds = size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (NC / 4) * 1024;
+  if (!wlds) lds = size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (bf16 ? NC / 4 : 1) * 1024;
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
@@ -514,7 +560,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
   reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : wlds ? e->lds_fn : e->global_fn;
   if (!fn) return RBGP_EUNSUPPORTED;
-  if (lds > 64 * 1024 && (wlds || bf16))   // (cheap host-side call; repeated because fn varies with the knobs)
+  if (lds > 64 * 1024)   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));
 #ifdef RBGP_EXPERIMENT
@@ -527,7 +573,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
   if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
 #endif
-  hipLaunchKernelGGL(fn, dim3(unsigned(8 * tab->ncl), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), (wlds || bf16) ? lds : 0, static_cast<hipStream_t>(stream), rp);
+  hipLaunchKernelGGL(fn, dim3(unsigned(8 * tab->ncl), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
 #ifdef RBGP_EXPERIMENT
   if (dump) {
     RBGP_HIP(hipDeviceSynchronize());

@@ -40,7 +40,7 @@ struct RegParams {
   int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
   int tm;                  // rows of one tile row: a_r * a_i * a_b
   int ntiles;              // column tiles: ceil(N / columns per wave)
-  int lgS;                 // bf16: log2 of the waves that share a column tile (split of the stage list)
+  int lgS;                 // log2 of the waves that share a column tile (split of the stage list)
 #ifdef RBGP_EXPERIMENT
   unsigned long long *trace;   // [wave][8] timestamps
 #endif

@@ -57,6 +57,17 @@ def test_bf16_register_family_row_groups_and_stage_split(groups, split, cw):
     gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
 
 
+@pytest.mark.parametrize("split", [2, 4])
+def test_fp32_register_family_stage_split(split):
+    """fp32 register kernels with the stage list split over 2 or 4 waves (LDS reduction)."""
+    tune = (0, 0, 0, 0, 0, split)
+    for w, N in [(wl.TINY, None), (wl.VGG19_CONV5, 520), (wl.WRN_G1, 1000)]:
+        gh.check_parity(w, N=N, kernel=REG, tune=tune, expect_kernel=REG)
+    w = wl.Workload("fp32_small_cluster", (2, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9), 331, wl.F32, 11, 12, 13, 1.0)
+    gh.check_parity(w, kernel=REG, tune=tune, ld_pad=2, expect_kernel=REG)   # odd leading dimension
+    gh.check_parity(wl.VGG19_CONV5, kernel=REG, tune=tune, expect_kernel=REG)
+
+
 def test_bf16_register_family_full_size_split_shapes():
     for tune in [(0, 128, 0, 0, 4, 4), (0, 128, 0, 0, 2, 2), (0, 64, 0, 0, 4, 2), (0, 64, 0, 0, 2, 2), (0, 64, 0, 0, 1, 1)]:
         gh.check_parity(wl.VGG19_CONV3_BF16, kernel=REG, tune=tune, expect_kernel=REG)
