@@ -166,7 +166,9 @@ int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *de
  * and ldI a multiple of 8 (128-column tiles, taken by default when both hold and N
  * is large enough); ESHAPE otherwise.  In bf16 mode it reads the last row of I up
  * to the next multiple of 4 (8) columns, inside the K x ldI array.  The other
- * cases take any alignment.  dev_packed must have been packed with the same kernel family and
+ * cases take any alignment.  I and O may exceed 4 GiB; the RBGP_KERNEL_MFMA_REG
+ * family returns EUNSUPPORTED when the rows of I that one of its stages spans
+ * (at most |G_r.V| * |G_i.V| * |G_b.V|) times ldI reach 2 GiB.  dev_packed must have been packed with the same kernel family and
  * dtype.  Asynchronous on `hip_stream`. */
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
               const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,

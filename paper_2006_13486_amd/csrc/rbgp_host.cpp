@@ -168,6 +168,7 @@ void rbgp_plan_reg(rbgp_mask *m) {
   if (p.ok) {
     p.KC = p.VC * per_v;
     p.NSTG = m->c[1] / p.VC;
+    p.SRC = p.VC * m->c[2] * m->c[3];
     p.RS = 1;
     while (p.RS < p.R) p.RS *= 2;
     p.MG = 16 / p.RS;

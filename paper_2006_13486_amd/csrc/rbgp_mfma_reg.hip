@@ -89,6 +89,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   if ((ntq << (2 - lgS)) >= p.ntiles) return;
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
+  const uint32_t n0b = uint32_t(nt) * uint32_t(CW * 4);   // byte offset of the wave's first column (< row_bytes when valid)
   const int g = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;    // as a weight lane: member of the group, row of the member
 
@@ -126,12 +127,36 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 
   const __amdgpu_buffer_rsrc_t rw =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.Wp), 0, p.w_bytes, kRsrcFlags);
-  // A stage past the end reads I through a descriptor of zero extent: zeros, no memory access.
+  // Once per stage (= per table lane), with vector instructions: where the stage's part of I
+  // starts and how far it extends, and where each member's weights are.  The loop then only
+  // reads these back (readlane), which keeps the scalar work between two stages short enough
+  // to hide behind the last MFMAs of a stage.
+  // The descriptor of a stage starts at the stage's first row and the wave's first column, so
+  // the 32-bit offsets inside it only span one stage (I itself may exceed 4 GiB).  A stage
+  // touches at most p.src_rows rows: its extent fits 32 bits, and only where the stage reaches
+  // the last row of I does the extent end inside it, at the last column.  A stage past the end
+  // gets extent zero: its loads return zeros without a memory access.
+  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tb < 0 ? 0 : tb)) * p.row_bytes + n0b;
+  const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
+  const int rows_left = p.last_row - tb < p.src_rows ? p.last_row - tb : p.src_rows;
+  const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
+  // per-lane byte address (LDS) or offset (global) of each member's weights: a tile row that
+  // lacks the tile reads the zero fragment (LDS) or an offset past the weight buffer (global)
+  int aoff[MG];
+#pragma unroll
+  for (int mm = 0; mm < MG; ++mm) {
+    if constexpr (WLDS)
+      aoff[mm] = (tf[mm] >= 0 ? mm * p.fpm + tf[mm] : MG * p.fpm) * FB;
+    else
+      aoff[mm] = (tf[mm] >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + tf[mm]) * p.a3 + u3) * FB : kOob;
+  }
   auto b_rsrc = [&](int s, int *sofs) {
-    const int base_row = __builtin_amdgcn_readlane(tb, table_lane(s));
-    *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 4);
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.I), 0,
-                                             (base_row >= 0 && valid) ? p.i_bytes : 0u, kRsrcFlags);
+    const int tl = table_lane(s);
+    const uint64_t base = uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_lo, tl))) |
+                          (uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_hi, tl))) << 32);
+    *sofs = 0;
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, __builtin_amdgcn_readlane(ib_ext, tl),
+                                             kRsrcFlags);
   };
 
   f32x4 B0[NO], B1[NO];
@@ -201,21 +226,14 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[w][v] = 0.f;
 
-  // Loads are unconditional so that the wait counts are exact: a stage past the end reads
-  // zeros (see b_rsrc); a tile row that lacks the tile reads the zero fragment (LDS) or an
-  // offset past the weight buffer (global), which returns zeros.
-  // per-lane byte address (LDS) or offset (global) of the stage's weights
+  // Loads are unconditional so that the wait counts are exact (sentinel stages and absent
+  // tiles read zeros, see above).
   auto a_addr = [&](int s) {
     int addr = 0;
     const int tl = table_lane(s);
 #pragma unroll
     for (int mm = 0; mm < MG; ++mm) {
-      const int fi = __builtin_amdgcn_readlane(tf[mm], tl);
-      int sv;
-      if constexpr (WLDS)
-        sv = (fi >= 0 ? mm * p.fpm + fi : MG * p.fpm) * FB;
-      else
-        sv = (fi >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
+      const int sv = __builtin_amdgcn_readlane(aoff[mm], tl);
       addr = mi == mm ? sv : addr;
     }
     return addr + alane;
@@ -473,11 +491,12 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   }
   const int NC = CW / 16;
   // (bf16: two columns share a dword, and a dword that crosses the end of the descriptor reads
-  // as zero, so the extent is rounded up to the bytes a lane loads; the condition on ldI keeps
-  // that inside the K x ldI array)
-  const int64_t i_bytes = ((m->K - 1) * ldI + (bf16 ? (N + NC - 1) / NC * NC : N)) * es;
+  // as zero, so the last row's extent (n_bytes below) is rounded up to the bytes a lane loads;
+  // the condition on ldI keeps that inside the K x ldI array)
   const int64_t w_bytes = (bf16 ? pl.packed_elems_bf16 : pl.packed_elems) * es;
-  if (i_bytes >= (int64_t(1) << 31) || w_bytes >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  // 32-bit offsets address one stage of I (its rows span SRC * ldI elements; I as a whole may be
+  // larger) and the packed weights
+  if ((int64_t(pl.SRC) * ldI + CW) * es >= (int64_t(1) << 31) || w_bytes >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
   RegState *st = static_cast<RegState *>(*state);
   if (!st) {
     st = new (std::nothrow) RegState();
@@ -547,7 +566,11 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.rowtab = *rowtab;
   rp.stages = tab->stages; rp.counts = tab->counts; rp.members = tab->members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
-  rp.i_bytes = uint32_t(i_bytes); rp.w_bytes = uint32_t(w_bytes);
+  rp.w_bytes = uint32_t(w_bytes);
+  rp.row_bytes = uint32_t(ldI * es);
+  rp.n_bytes = uint32_t((bf16 ? (N + NC - 1) / NC * NC : N) * es);
+  rp.last_row = int(m->K - 1);
+  rp.src_rows = pl.SRC;
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
   rp.fpm = fpm;
   rp.tm = m->a[1] * m->a[2] * m->a[3];

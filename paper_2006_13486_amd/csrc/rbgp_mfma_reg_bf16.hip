@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   const bool valid = nt < p.ntiles;
   if (lgS == 0 && !valid) return;        // (with S > 1 every wave reaches the barrier below)
   const int64_t n0 = int64_t(nt) * CW;
+  const uint32_t n0b = uint32_t(nt) * uint32_t(CW * 2);   // byte offset of the wave's first column
   const int kg = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;
 
@@ -132,21 +133,30 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     const int gs = ks + (s << lgS);
     return gs < 63 ? gs : 63;
   };
+  // Once per stage (= per table lane), with vector instructions: the start and extent of the
+  // stage's part of I and the offset of each tile row's weights (see the fp32 kernel); the
+  // loop only reads them back.  A tile row that lacks the tile reads past the end of the
+  // packed buffer, which returns zeros.
+  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tb < 0 ? 0 : tb)) * p.row_bytes + n0b;
+  const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
+  const int rows_left = p.last_row - tb < p.src_rows ? p.last_row - tb : p.src_rows;
+  const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
+  int aoff[U];
+#pragma unroll
+  for (int mm = 0; mm < U; ++mm)
+    aoff[mm] = (tf[mm] >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + tf[mm]) * p.a3 + u3) * FB : kOob;
   auto b_rsrc = [&](int tl, int *sofs) {
-    const int base_row = __builtin_amdgcn_readlane(tb, tl);
-    *sofs = int((int64_t(base_row < 0 ? 0 : base_row) * p.ldI + n0) * 2);
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(static_cast<const void *>(p.I)), 0,
-                                             (base_row >= 0 && valid) ? p.i_bytes : 0u, kRsrcFlags);
+    const uint64_t base = uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_lo, tl))) |
+                          (uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_hi, tl))) << 32);
+    *sofs = 0;
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, __builtin_amdgcn_readlane(ib_ext, tl),
+                                             kRsrcFlags);
   };
-  // per-lane byte offset of the stage's weights for group gi; a tile row that lacks the tile
-  // reads past the end of the packed buffer, which returns zeros
   auto a_addr = [&](int tl, int gi) {
     int addr = 0;
 #pragma unroll
     for (int mm = 0; mm < MG; ++mm) {
-      const int fi = __builtin_amdgcn_readlane(tf[gi * MG + mm], tl);
-      const int u1 = mem[gi * MG + mm];
-      const int sv = (fi >= 0 && u1 >= 0) ? ((u1 * p.fpm + fi) * p.a3 + u3) * FB : kOob;
+      const int sv = __builtin_amdgcn_readlane(aoff[gi * MG + mm], tl);
       addr = mi == mm ? sv : addr;
     }
     return addr + alane;

@@ -34,7 +34,10 @@ struct RegParams {
   const int32_t *counts;   // [ncl] stages of each cluster (<= 60)
   const int32_t *members;  // [ncl][MG] tile rows of each cluster (-1: none)
   int64_t N, ldI, ldO;
-  uint32_t i_bytes, w_bytes;  // extents of I and of the packed weights (buffer descriptors)
+  uint32_t w_bytes;        // extent of the packed weights (buffer descriptor)
+  uint32_t row_bytes;      // ldI in bytes
+  uint32_t n_bytes;        // N in bytes (N rounded up to a lane's load for bf16): extent of the last row of I
+  int last_row, src_rows;  // K - 1; rows of I one stage spans
   int a2, a3, a4, R;
   int fpm;                 // weight fragments per member: d_o * NSTG
   int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base

@@ -50,6 +50,16 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     return out[:, :N], used
 
 
+def family_covers(w, kernel):
+    """Whether a kernel family accepts this mask (host-side query, no GPU call)."""
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    try:
+        rb.rbgp_mask_set_kernel(mask, kernel)
+    except rb.RbgpError:
+        return False
+    return rb.rbgp_mask_kernel(mask, w.dtype) == kernel
+
+
 def oracle_spmm(w, vals_f32, I_f32):
     Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
     mask = orc.kron_mask(Bs)

@@ -170,7 +170,16 @@ FUZZ = [
     ((2, 4, 4, 2), (2, 2, 8, 9), (1, 2, 8, 9)),                    # KS=72
     ((4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9)),                    # R=3 (partial 4-row block)
     ((2, 3, 4, 2), (2, 2, 4, 9), (1, 2, 2, 9)),                    # R=6 (one full, one partial block)
+    # the remaining (stage size, row group) pairs of the register family's kernel table
+    ((2, 4, 16, 1), (2, 1, 16, 1), (2, 1, 8, 1)),                  # KC=8,  RS=4
+    ((4, 2, 4, 1), (4, 1, 4, 9), (2, 1, 2, 9)),                    # KC=18, RS=2
+    ((4, 2, 4, 1), (4, 2, 4, 9), (2, 2, 2, 9)),                    # KC=36, RS=2
+    ((4, 1, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9)),                    # KC=72, RS=2
+    ((4, 2, 4, 2), (4, 1, 4, 9), (2, 1, 2, 9)),                    # KC=18, RS=4
+    ((4, 2, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9)),                    # KC=72, RS=4
+    ((4, 4, 4, 2), (4, 1, 4, 9), (2, 1, 2, 9)),                    # KC=18, RS=8
 ]
+REG_COVERED = {5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15}               # must run on the register family
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
@@ -178,12 +187,33 @@ FUZZ = [
 def test_shapes_across_the_kernel_table(idx, dtype):
     rows, cols, deg = FUZZ[idx]
     w = wl.Workload(f"fuzz{idx}_{dtype}", rows, cols, deg, 328, dtype, 100 + idx, 200 + idx, 300 + idx, 1.0)
-    e1 = gh.check_parity(w, kernel=MFMA, tune=(1, 64, 0))
-    e2 = gh.check_parity(w, kernel=MFMA, tune=(2, 128, 0))
+    if gh.family_covers(w, MFMA):
+        gh.check_parity(w, kernel=MFMA, tune=(1, 64, 0))
+        gh.check_parity(w, kernel=MFMA, tune=(2, 128, 0))
+    else:
+        assert idx >= 9                       # the first nine shapes are inside the LDS family's table
     gh.check_parity(w, kernel=GEN)
-    if idx >= 5:                              # shapes inside the register family's table
-        for cluster in (1, 2):
-            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
+    covered = gh.family_covers(w, REG)
+    assert covered or idx not in REG_COVERED
+    if covered:
+        for tune in [(0, 0, 0, 1), (0, 0, 0, 2), (0, 0, 0, 0, 0, 2)] + ([(0, 64, 0, 0, 2, 1), (0, 128, 0, 0, 1, 4)] if dtype == wl.BF16 else []):
+            gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
+
+
+def test_activations_beyond_4_gib():
+    """An I of 4.6 GB (WRN shape, 2 000 037 columns, odd leading dimension): the kernels'
+    32-bit offsets must only span one stage.  A sample of output columns is checked."""
+    w = replace(wl.WRN_G1, N=2_000_037, name="wrn_4gib")
+    vl, Il, vf, If = gh.host_inputs(w)
+    cols = np.r_[0:64, 1_000_000:1_000_064, 1_999_936:2_000_037]
+    ref, den = gh.oracle_spmm(w, vf, np.ascontiguousarray(If[:, cols]))
+    for kernel in (rb.KERNEL_AUTO, MFMA, GEN):
+        out, used = gh.library_spmm(w, vl, Il, kernel=kernel, tune=(1, 64, 0) if kernel == MFMA else None,
+                                    ld_pad=3 if kernel == MFMA else 0, tag="beyond 4 GiB")
+        assert used == (REG if kernel == rb.KERNEL_AUTO else kernel)
+        err = orc.normalised_error(out[:, cols], ref, den)
+        assert err <= gh.TOL[w.dtype], err
+        assert np.all(np.isfinite(out[:, ::4099]))
 
 
 def test_masks_outside_rbgp4_roles_use_the_generic_kernel():
