@@ -140,6 +140,12 @@ int rbgp_mask_tune(rbgp_mask_t *mask, int knob, int value);
 /* Bytes of the device buffer that rbgp_pack fills (kernel layout incl. padding); 0 on error. */
 size_t rbgp_packed_bytes(const rbgp_mask_t *mask, rbgp_dtype_t dtype);
 
+/* The packed layout as a table (host only, no GPU call): out[p], for every element p of
+ * the packed buffer (rbgp_packed_bytes() / element size entries, caller-owned host
+ * memory), is the canonical index m*rowdeg + t of the kept value stored there, or -1
+ * for padding (stored as zero).  Every kept value appears exactly once. */
+int rbgp_pack_layout(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int32_t *out);
+
 /* Reorder the kept values from canonical order into the layout the SpMM kernel
  * reads, which stores the dense |G_r.U||G_b.U| x |G_b.V| blocks of one tile step
  * contiguously (the compact W tile that Algorithm 1 stages per step).

@@ -37,6 +37,7 @@ SIGNATURES = {
     "rbgp_mask_kernel": (ctypes.c_int, [_vp, ctypes.c_int]),
     "rbgp_mask_tune": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
     "rbgp_packed_bytes": (ctypes.c_size_t, [_vp, ctypes.c_int]),
+    "rbgp_pack_layout": (ctypes.c_int, [_vp, ctypes.c_int, _vp]),
     "rbgp_pack": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_pack_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_spmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
@@ -161,6 +162,14 @@ def rbgp_mask_tune(mask: Mask, knob: int, value: int):
 
 def rbgp_packed_bytes(mask: Mask, dtype: int) -> int:
     return int(load().rbgp_packed_bytes(mask.handle, dtype))
+
+
+def rbgp_pack_layout(mask: Mask, dtype: int) -> np.ndarray:
+    """int32 array, one entry per element of the packed buffer: canonical index or -1 (padding)."""
+    n = rbgp_packed_bytes(mask, dtype) // (4 if dtype == F32 else 2)
+    out = np.empty(n, dtype=np.int32)
+    _check(load().rbgp_pack_layout(mask.handle, dtype, out.ctypes.data_as(_vp)), "rbgp_pack_layout")
+    return out
 
 
 def rbgp_pack(mask: Mask, dtype: int, host_values: np.ndarray, dev_packed_ptr: int, stream: int = 0):

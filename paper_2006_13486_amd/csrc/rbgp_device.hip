@@ -23,6 +23,8 @@
 //    `abid` selecting the step.  No structural zero is multiplied.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -436,6 +438,14 @@ int rbgp_mask_tune(rbgp_mask_t *m, int knob, int value) {
 size_t rbgp_packed_bytes(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
   if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return 0;
   return size_t(packed_elems(m, resolve_kernel(m, dtype), dtype)) * elem_bytes(dtype);
+}
+
+int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
+  if (!m || !out || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return RBGP_EINVAL;
+  std::vector<int32_t> perm;
+  rbgp_build_pack_perm(m, resolve_kernel(m, dtype), dtype == RBGP_BF16_F32ACC, perm);
+  std::copy(perm.begin(), perm.end(), out);
+  return RBGP_OK;
 }
 
 int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,

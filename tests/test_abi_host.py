@@ -168,3 +168,40 @@ def test_kernel_selection_and_packed_size():
     with pytest.raises(rb.RbgpError) as ei:
         rb.rbgp_mask_set_kernel(m2, rb.KERNEL_MFMA)
     assert ei.value.code == rb.EUNSUPPORTED
+
+
+LAYOUT_SHAPES = [
+    (wl.TINY.rows, wl.TINY.cols, wl.TINY.row_deg),
+    (wl.VGG19_CONV5.rows, wl.VGG19_CONV5.cols, wl.VGG19_CONV5.row_deg),
+    (wl.VGG19_CONV3_BF16.rows, wl.VGG19_CONV3_BF16.cols, wl.VGG19_CONV3_BF16.row_deg),
+    (wl.WRN_G1.rows, wl.WRN_G1.cols, wl.WRN_G1.row_deg),
+    ((4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9)),        # R = 3: partial row block
+    ((2, 3, 4, 2), (2, 2, 4, 9), (1, 2, 2, 9)),        # R = 6
+    ((2, 4, 16, 1), (2, 1, 16, 1), (2, 1, 8, 1)),      # stage of 8 contraction steps
+    ((4, 2, 4, 1), (4, 1, 4, 9), (2, 1, 2, 9)),        # stage of 18
+    ((32, 4, 32, 1), (128, 1, 32, 1), (64, 1, 8, 1)),  # Table 2 of the paper
+]
+
+
+@pytest.mark.parametrize("dtype", [rb.F32, rb.BF16_F32ACC])
+@pytest.mark.parametrize("kernel", [rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG])
+@pytest.mark.parametrize("shape", LAYOUT_SHAPES, ids=lambda s: "x".join(map(str, s[0])))
+def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
+    """Whatever the kernel family's layout, packing is a permutation of the kept values
+    plus zero padding (host-side table, no GPU)."""
+    rows, cols, deg = shape
+    mask = rb.rbgp_make_mask(rows, cols, deg, 5)
+    try:
+        rb.rbgp_mask_set_kernel(mask, kernel)
+    except rb.RbgpError as e:
+        assert e.code == rb.EUNSUPPORTED
+        pytest.skip("family does not cover this mask")
+    nnz = rb.rbgp_mask_shape(mask)["nnz"]
+    layout = rb.rbgp_pack_layout(mask, dtype)
+    assert layout.size * (4 if dtype == rb.F32 else 2) == rb.rbgp_packed_bytes(mask, dtype)
+    kept = layout[layout >= 0]
+    assert kept.size == nnz
+    assert np.array_equal(np.sort(kept), np.arange(nnz, dtype=np.int32))
+    assert np.all(layout[layout < 0] == -1)
+    if rb.rbgp_mask_kernel(mask, dtype) == rb.KERNEL_GENERIC:
+        assert np.array_equal(layout, np.arange(nnz, dtype=np.int32))     # canonical order itself
