@@ -169,7 +169,7 @@ def main():
                          "WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (sharding along N is described in DESIGN.md); use --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (columns of I and O are independent: shard N across devices); use --gpus 1")
 
     import torch
     if not torch.cuda.is_available():
