@@ -157,6 +157,9 @@ def main():
     ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-conv", action="store_true",
+                    help="time rbgp_conv3x3 (3x3 convolution with the lowering folded into the loads, fp32) on the "
+                         "workload's layer instead of rbgp_spmm on the lowered input")
     ap.add_argument("--sweep", default="", choices=["", "table2", "table3", "vgg19"],
                     help="time a family of workloads instead of the headline one: the paper's 4096^3 SDMM of "
                          "Table 2 / Table 3, or the 16 VGG19 conv layers; prints one JSON line with all cases")
@@ -207,16 +210,34 @@ def main():
     packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
 
-    set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
+    algorithmic_bytes = w.algorithmic_bytes
+    if args.fused_conv:
+        if bf16 or w.name not in wl.CONV_GEOMETRY:
+            sys.exit("bench.py: --fused-conv needs an fp32 workload that is a lowered 3x3 convolution")
+        B, H, W = wl.CONV_GEOMETRY[w.name]
+        X = wl.conv_activations(w, B, H, W)
+        Xp = wl.zero_padded(X)
+        # the oracle's operand for the parity check: the same activations, lowered explicitly
+        from oracle import rbgp_oracle as orc
+        I_f32 = orc.im2col_3x3(X) if not args.no_cpu_baseline else None
+        algorithmic_bytes = Xp.nbytes + w.M * w.N * 4 + w.nnz * 4
+        set_bytes = Xp.nbytes + w.M * w.N * 4
+        I0 = torch.from_numpy(Xp).to(dev)
+    else:
+        set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
+        I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
     nsets = args.sets if args.sets > 0 else max(2, min(16, -(-512 * 2**20 // set_bytes)))
-    I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
     Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
     Os = [torch.empty((w.M, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
 
     def step(i):
         j = i % nsets
-        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
-                     Os[j].data_ptr(), w.N, stream)
+        if args.fused_conv:
+            rb.rbgp_conv3x3(mask, w.dtype, w.M, w.K // 9, B, H, W, packed.data_ptr(), Is[j].data_ptr(),
+                            Os[j].data_ptr(), w.N, stream)
+        else:
+            rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
+                         Os[j].data_ptr(), w.N, stream)
 
     for i in range(args.warmup):
         step(i)
@@ -239,16 +260,16 @@ def main():
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_F32_TFLOPS, "traffic": None}
     else:
-        achieved = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
+        achieved = algorithmic_bytes / (kern_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
     try:
         with open(TRAFFIC_FILE) as f:
-            roof["traffic"] = json.load(f).get(w.name, {}).get("hbm_bytes_per_launch")
+            roof["traffic"] = None if args.fused_conv else json.load(f).get(w.name, {}).get("hbm_bytes_per_launch")
     except OSError:
         pass
     roof["kernel_ms"] = kern_ms
-    roof["algorithmic_bytes"] = w.algorithmic_bytes
+    roof["algorithmic_bytes"] = algorithmic_bytes
     roof["algorithmic_flops"] = w.flops
 
     out = {"metric": "effective TFLOP/s (2*nnz*N) RBGP4 SpMM", "value": value, "unit": "TFLOP/s",
@@ -258,7 +279,7 @@ def main():
            "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "density": w.density,
                       "factors_rows": list(w.rows), "factors_cols": list(w.cols), "factors_row_deg": list(w.row_deg),
                       "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "tune": args.tune or "default",
-                      "buffer_sets": nsets},
+                      "buffer_sets": nsets, "entry_point": "rbgp_conv3x3" if args.fused_conv else "rbgp_spmm"},
            "roofline": roof}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, Os[0].cpu().numpy())

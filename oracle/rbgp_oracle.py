@@ -27,7 +27,8 @@ Pins (tests/ -m "not gpu"): published SplitMix64 outputs; 2-lift invariants;
 closed-form singular values (complete graph, 8-cycle, two 4-cycles, star
 forest); numpy.kron; degree/density products; the paper's worked examples
 (512 edges stored as 22; two factorings giving (64,16) at 75 %); spectrum of a
-product; brute-force matmul with explicit zeros; numpy.matmul for all-complete
+product; brute-force matmul with explicit zeros; scipy.signal.correlate2d for
+the lowered 3x3 convolution; numpy.matmul for all-complete
 factors; torch's bf16 conversion for the rounding routine.
 """
 from __future__ import annotations
@@ -263,6 +264,28 @@ def spmm_bruteforce_scalar(mask, W, I):
 
 # --------------------------------------------------------------------------
 # bf16 (round to nearest even), used to prepare identical inputs for both sides
+# --------------------------------------------------------------------------
+# convolution lowered to a matrix (Section 5 "GPU Implementation": the dense
+# operand is the batched input activations)
+# --------------------------------------------------------------------------
+def im2col_3x3(X: np.ndarray) -> np.ndarray:
+    """X[channel][image][H][W] -> I[9*channel + 3*(dy+1) + (dx+1)][(image*H + y)*W + x]
+    = X[channel][image][y+dy][x+dx], zero outside the image (3x3 taps, stride 1,
+    zero padding 1), written as explicit loops over the taps."""
+    C, B, H, W = X.shape
+    I = np.zeros((9 * C, B * H * W), dtype=X.dtype)
+    for c in range(C):
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                k = 9 * c + 3 * (dy + 1) + (dx + 1)
+                shifted = np.zeros((B, H, W), dtype=X.dtype)
+                ys, ye = max(0, -dy), min(H, H - dy)
+                xs, xe = max(0, -dx), min(W, W - dx)
+                shifted[:, ys:ye, xs:xe] = X[c, :, ys + dy:ye + dy, xs + dx:xe + dx]
+                I[k] = shifted.reshape(-1)
+    return I
+
+
 # --------------------------------------------------------------------------
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """IEEE float32 -> bfloat16 bit patterns (uint16), round-to-nearest-even."""

@@ -578,4 +578,21 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   return RBGP_OK;
 }
 
+int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in, int64_t images,
+                 int64_t height, int64_t width, const void *dev_packed, const void *dev_X, void *dev_O, int64_t ldO,
+                 void *hip_stream) {
+  if (!m) return RBGP_EINVAL;
+  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (images <= 0 || height <= 0 || width <= 0 || (width % 4)) return RBGP_ESHAPE;
+  const int64_t N = images * height * width;
+  if (channels_out != m->M || 9 * channels_in != m->K || ldO < N) return RBGP_ESHAPE;
+  if (dtype != RBGP_F32 || resolve_kernel(m, dtype) != RBGP_KERNEL_MFMA_REG) return RBGP_EUNSUPPORTED;
+  if (!dev_packed || !dev_X || !dev_O) return RBGP_EINVAL;
+  int rc = ensure_device(m);
+  if (rc) return rc;
+  const rbgp_conv_geometry geom = {images, height, width};
+  return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, false, N, dev_packed, dev_X, N,
+                         static_cast<float *>(dev_O), ldO, hip_stream, &geom);
+}
+
 }  // extern "C"

@@ -74,8 +74,15 @@ void rbgp_device_release(rbgp_device_state *dev);
 void rbgp_set_hip_error(const char *msg);
 // register-streaming family (rbgp_mfma_reg.hip); `state` is its lazily built table cache
 bool rbgp_reg_covers(const rbgp_mask *m);
+// geometry of a fused 3x3 convolution (stride 1, zero padding 1): N = images * height * width
+struct rbgp_conv_geometry {
+  int64_t images, height, width;
+};
+// conv == nullptr: I is the K x N matrix; else I is the zero-padded activation tensor
+// [K / 9][images][height + 2][width + 2] and ldI is ignored
 int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
-                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream);
+                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream,
+                    const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);

@@ -89,7 +89,9 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   if ((ntq << (2 - lgS)) >= p.ntiles) return;
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
-  const uint32_t n0b = uint32_t(nt) * uint32_t(CW * 4);   // byte offset of the wave's first column (< row_bytes when valid)
+  // byte offset of the wave's first column in a row of I (fused convolution: the lane's own
+  // column offset inside a channel of X, see `off` below)
+  const uint32_t n0b = p.conv ? 0u : uint32_t(nt) * uint32_t(CW * 4);
   const int g = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;    // as a weight lane: member of the group, row of the member
 
@@ -120,8 +122,22 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
   int off[NO];
+  if (p.conv) {
+    // Fused 3x3 convolution: column n = (image * H + y) * W + x of the lowered input is pixel
+    // (y + dy, x + dx) of the zero-padded image; the lane's four columns lie in one image row
+    // (W % 4 == 0), so a tap is a constant shift of one 16-byte load.  The table entry already
+    // holds channel * bytes per channel + shift of the tap.
+    const uint32_t n = uint32_t(n0) + 4u * uint32_t(j), hw = uint32_t(p.conv_h) * uint32_t(p.conv_w);
+    const uint32_t img = n / hw, rem = n - img * hw, y = rem / uint32_t(p.conv_w), x = rem - y * uint32_t(p.conv_w);
+    const int colbase = int64_t(n) < p.N
+                            ? int(((img * uint32_t(p.conv_h + 2) + y + 1) * uint32_t(p.conv_w + 2) + x + 1) * 4u)
+                            : (p.conv_w + 3) * 4;   // (columns past N: any pixel inside X; never stored)
 #pragma unroll
-  for (int o = 0; o < NO; ++o) off[o] = rrow[o] * (int(p.ldI) * 4) + j * 16;   // < 2^31: checked by the host
+    for (int o = 0; o < NO; ++o) off[o] = rrow[o] + colbase;
+  } else {
+#pragma unroll
+    for (int o = 0; o < NO; ++o) off[o] = rrow[o] * (int(p.ldI) * 4) + j * 16;   // < 2^31: checked by the host
+  }
   const int alane = (g * RS + ri) * 16;
   const bool valid = nt < p.ntiles;
 
@@ -136,9 +152,10 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // touches at most p.src_rows rows: its extent fits 32 bits, and only where the stage reaches
   // the last row of I does the extent end inside it, at the last column.  A stage past the end
   // gets extent zero: its loads return zeros without a memory access.
-  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tb < 0 ? 0 : tb)) * p.row_bytes + n0b;
+  const int tbu = p.conv ? int(uint32_t(tb < 0 ? 0 : tb) / 9u) : (tb < 0 ? 0 : tb);   // first row (channel) of the stage
+  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tbu)) * p.row_bytes + n0b;
   const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
-  const int rows_left = p.last_row - tb < p.src_rows ? p.last_row - tb : p.src_rows;
+  const int rows_left = p.last_row - tbu < p.src_rows ? p.last_row - tbu : p.src_rows;
   const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
   // per-lane byte address (LDS) or offset (global) of each member's weights: a tile row that
   // lacks the tile reads the zero fragment (LDS) or an offset past the weight buffer (global)
@@ -412,6 +429,8 @@ struct RegTables {  // device tables of the clustering
 struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
+  int32_t *rowtab_conv = nullptr;  // fused convolution (fp32): byte offsets for the geometry below
+  int64_t conv_key[3] = {0, 0, 0}; // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
   RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
   int tab_bf16_G = 0;
@@ -463,15 +482,27 @@ void rbgp_reg_release(void *state) {
   if (!st) return;
   if (st->rowtab) (void)hipFree(st->rowtab);
   if (st->rowtab_bf16) (void)hipFree(st->rowtab_bf16);
+  if (st->rowtab_conv) (void)hipFree(st->rowtab_conv);
   free_tables(&st->tab);
   free_tables(&st->tab_bf16);
   delete st;
 }
 
 int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
-                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream) {
+                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream, const rbgp_conv_geometry *conv) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
+  // Fused 3x3 convolution: fp32, the nine taps are the columns of a complete G_b, image rows hold
+  // whole 16-byte loads; "I" is then the padded activation tensor and ldI is not used.
+  int64_t chs = 0;   // bytes of one channel of X
+  if (conv) {
+    if (bf16 || m->c[3] != 9 || m->d[3] != 9) return RBGP_EUNSUPPORTED;
+    if (conv->images <= 0 || conv->height <= 0 || conv->width <= 0 || conv->width % 4) return RBGP_ESHAPE;
+    if (N != conv->images * conv->height * conv->width) return RBGP_ESHAPE;
+    chs = conv->images * (conv->height + 2) * (conv->width + 2) * 4;
+    if ((int64_t(pl.SRC) / 9 + 1) * chs >= (int64_t(1) << 31)) return RBGP_EUNSUPPORTED;
+    ldI = N;   // (only the checks below read it)
+  }
   // I and the packed weights are addressed through 32-bit buffer offsets
   const int es = bf16 ? 2 : 4;
   // bf16: a lane loads 8 bytes (4 columns; 64-column wave tile) or 16 bytes (8 columns;
@@ -496,14 +527,20 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   const int64_t w_bytes = (bf16 ? pl.packed_elems_bf16 : pl.packed_elems) * es;
   // 32-bit offsets address one stage of I (its rows span SRC * ldI elements; I as a whole may be
   // larger) and the packed weights
-  if ((int64_t(pl.SRC) * ldI + CW) * es >= (int64_t(1) << 31) || w_bytes >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  if ((!conv && (int64_t(pl.SRC) * ldI + CW) * es >= (int64_t(1) << 31)) || w_bytes >= (int64_t(1) << 30))
+    return RBGP_EUNSUPPORTED;
   RegState *st = static_cast<RegState *>(*state);
   if (!st) {
     st = new (std::nothrow) RegState();
     if (!st) return RBGP_ENOMEM;
     *state = st;
   }
-  int32_t **rowtab = bf16 ? &st->rowtab_bf16 : &st->rowtab;
+  int32_t **rowtab = conv ? &st->rowtab_conv : bf16 ? &st->rowtab_bf16 : &st->rowtab;
+  if (conv && *rowtab &&
+      (st->conv_key[0] != conv->images || st->conv_key[1] != conv->height || st->conv_key[2] != conv->width)) {
+    (void)hipFree(*rowtab);   // (waits for launches that still read the old table)
+    *rowtab = nullptr;
+  }
   if (!*rowtab) {
     const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
     const int len = bf16 ? 32 * rbgp_bf16_blocks32(pl.KC) + (rbgp_bf16_tail16(pl.KC) ? 16 : 0) : pl.NO * 4;   // contraction steps, padded (padding -> row 0)
@@ -513,6 +550,13 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
         const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
         rt[size_t(u3) * len + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
       }
+    if (conv) {   // stage-relative row 9 * channel + tap -> byte offset of the channel plus the shift of the tap
+      for (int32_t &r : rt) {
+        const int tap = r % 9, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        r = int32_t((r / 9) * chs + (dy * (conv->width + 2) + dx) * 4);
+      }
+      st->conv_key[0] = conv->images; st->conv_key[1] = conv->height; st->conv_key[2] = conv->width;
+    }
     int rc = upload(rt, rowtab);
     if (rc) return rc;
   }
@@ -571,6 +615,15 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.n_bytes = uint32_t((bf16 ? (N + NC - 1) / NC * NC : N) * es);
   rp.last_row = int(m->K - 1);
   rp.src_rows = pl.SRC;
+  rp.conv = conv ? 1 : 0;
+  rp.conv_h = conv ? int(conv->height) : 0;
+  rp.conv_w = conv ? int(conv->width) : 0;
+  if (conv) {   // the unit of the stage descriptors is a channel of X
+    rp.row_bytes = uint32_t(chs);
+    rp.n_bytes = uint32_t(chs);
+    rp.last_row = int(m->K / 9 - 1);
+    rp.src_rows = pl.SRC / 9;
+  }
   rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
   rp.fpm = fpm;
   rp.tm = m->a[1] * m->a[2] * m->a[3];

@@ -38,6 +38,13 @@ struct RegParams {
   uint32_t row_bytes;      // ldI in bytes
   uint32_t n_bytes;        // N in bytes (N rounded up to a lane's load for bf16): extent of the last row of I
   int last_row, src_rows;  // K - 1; rows of I one stage spans
+  // Fused 3x3 convolution (fp32 kernels): I is not materialised; row k = 9 * channel + tap of it is
+  // read from the zero-padded activations X[channel][image][H+2][W+2].  Then the "row" unit of the
+  // three fields above is a channel (row_bytes = bytes of one channel of X, last_row = channels - 1,
+  // src_rows = channels one stage spans, n_bytes = row_bytes) and rowtab holds byte offsets
+  // (channel and tap shift) instead of rows.
+  int conv;                // 1: fused convolution
+  int conv_h, conv_w;      // image height and width (W a multiple of 4)
   int a2, a3, a4, R;
   int fpm;                 // weight fragments per member: d_o * NSTG
   int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base

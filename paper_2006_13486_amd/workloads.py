@@ -81,6 +81,9 @@ WRN_G1 = Workload("wrn40_4_group1_fp32_64x576x131072_d8", (8, 2, 4, 1), (8, 2, 4
 
 CONFIGS = [TINY, VGG19_CONV5, VGG19_CONV3_BF16, WRN_G1]
 
+# (images, height, width) of the convolution each lowered configuration comes from: N = images * height * width
+CONV_GEOMETRY = {VGG19_CONV5.name: (128, 4, 4), VGG19_CONV3_BF16.name: (128, 8, 8), WRN_G1.name: (128, 32, 32)}
+
 # VGG19 on CIFAR (Table 1's network): (C_in, C_out, H) of the 16 conv layers.
 VGG19_LAYERS = [(3, 64, 32), (64, 64, 32), (64, 128, 16), (128, 128, 16),
                 (128, 256, 8), (256, 256, 8), (256, 256, 8), (256, 256, 8),
@@ -171,6 +174,23 @@ def activations(w: Workload, N: int | None = None) -> np.ndarray:
     x = g.standard_normal((w.K, N), dtype=np.float32)
     np.maximum(x, 0, out=x)
     return x
+
+
+def conv_activations(w: Workload, images: int, height: int, width: int) -> np.ndarray:
+    """X[channel][image][height][width] float32 ~ max(0, N(0,1)) for the fused 3x3
+    convolution (channels = K / 9), seeded like `activations`."""
+    g = np.random.Generator(np.random.PCG64(w.i_seed))
+    x = g.standard_normal((w.K // 9, images, height, width), dtype=np.float32)
+    np.maximum(x, 0, out=x)
+    return x
+
+
+def zero_padded(x: np.ndarray) -> np.ndarray:
+    """[C][B][H][W] -> [C][B][H+2][W+2] with a zero border (the layout rbgp_conv3x3 reads)."""
+    C, B, H, W = x.shape
+    out = np.zeros((C, B, H + 2, W + 2), dtype=x.dtype)
+    out[:, :, 1:-1, 1:-1] = x
+    return out
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:

@@ -50,6 +50,27 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     return out[:, :N], used
 
 
+def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
+    """Run rbgp_conv3x3 on X[C][B][H][W] (padded here: layout work, not arithmetic)."""
+    import torch
+    dev = torch.device("cuda:0")
+    C, B, H, W = X.shape
+    N = B * H * W
+    dtype = w.dtype if dtype is None else dtype
+    print(f"[gpu] conv3x3 {w.name} C={C} B={B} H={H} W={W} dtype={dtype} tune={tune} {tag}", flush=True)
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    for knob, value in enumerate(tune or ()):
+        rb.rbgp_mask_tune(mask, knob, value)
+    stream = torch.cuda.current_stream().cuda_stream
+    packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, dtype), 16), dtype=torch.uint8, device=dev)
+    rb.rbgp_pack(mask, dtype, np.ascontiguousarray(vals), packed.data_ptr(), stream)
+    X_d = torch.from_numpy(wl.zero_padded(X)).to(dev)
+    O_d = torch.full((w.M, N), float("nan"), dtype=torch.float32, device=dev)
+    rb.rbgp_conv3x3(mask, dtype, w.M, C, B, H, W, packed.data_ptr(), X_d.data_ptr(), O_d.data_ptr(), N, stream)
+    torch.cuda.synchronize()
+    return O_d.cpu().numpy()
+
+
 def family_covers(w, kernel):
     """Whether a kernel family accepts this mask (host-side query, no GPU call)."""
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)

@@ -216,6 +216,49 @@ def test_activations_beyond_4_gib():
         assert np.all(np.isfinite(out[:, ::4099]))
 
 
+# ------------------------------------------------------------------ fused 3x3 convolution
+CONV_CASES = [
+    # workload (K = 9 * channels), images, height, width
+    (wl.Workload("conv_small", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.F32, 61, 62, 63, 1.0), 3, 4, 8),
+    (wl.Workload("conv_ragged", (4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 64, 65, 66, 1.0), 5, 3, 4),
+    (wl.Workload("conv_wide", (4, 2, 4, 1), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 67, 68, 69, 1.0), 2, 5, 32),
+    (wl.VGG19_CONV5, 128, 4, 4),          # the headline layer: 512 -> 512 channels, 4x4 pixels, batch 128
+    (wl.WRN_G1, 8, 32, 32),               # WRN-40-4 group 1 at batch 8
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: c[0].name)
+def test_fused_conv3x3_equals_spmm_on_the_lowered_input(case):
+    """rbgp_conv3x3 on padded activations = the oracle's product with the explicitly
+    lowered input (im2col written out in the oracle)."""
+    w, B, H, W = case
+    vals = wl.kept_weights(w)
+    X = wl.conv_activations(w, B, H, W)
+    for tune in (None, (0, 0, 0, 0, 0, 2)):
+        out = gh.library_conv3x3(w, vals, X, tune=tune)
+        ref, den = gh.oracle_spmm(w, vals, orc.im2col_3x3(X))
+        err = orc.normalised_error(out, ref, den)
+        print(f"[gpu]   normalised error {err:.3e}", flush=True)
+        assert err <= gh.TOL[wl.F32], err
+
+
+def test_fused_conv3x3_argument_checks():
+    import torch
+    w, B, H, W = CONV_CASES[0]
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    buf = torch.zeros(1 << 20, dtype=torch.float32, device="cuda:0")
+    args = (buf.data_ptr(), buf.data_ptr(), buf.data_ptr())
+    for bad, code in [(dict(width=6), rb.ESHAPE), (dict(cin=w.K // 9 + 1), rb.ESHAPE), (dict(dtype=rb.BF16_F32ACC), rb.EUNSUPPORTED)]:
+        with pytest.raises(rb.RbgpError) as ei:
+            rb.rbgp_conv3x3(mask, bad.get("dtype", rb.F32), w.M, bad.get("cin", w.K // 9), B, H, bad.get("width", W),
+                            args[0], args[1], args[2], B * H * bad.get("width", W), 0)
+        assert ei.value.code == code
+    # a mask whose G_b does not have the nine taps
+    m2 = rb.rbgp_make_mask(wl.TINY.rows, wl.TINY.cols, wl.TINY.row_deg, 1)
+    with pytest.raises(rb.RbgpError):
+        rb.rbgp_conv3x3(m2, rb.F32, wl.TINY.M, wl.TINY.K // 9, 1, 4, 4, args[0], args[1], args[2], 16, 0)
+
+
 def test_masks_outside_rbgp4_roles_use_the_generic_kernel():
     """Sparse G_r / G_b (general four-factor RBGP) still multiply correctly."""
     w = wl.Workload("general_rbgp", (4, 4, 4, 2), (4, 4, 8, 4), (2, 2, 4, 2), 130, wl.F32, 5, 6, 7, 1.0)

@@ -389,3 +389,28 @@ def test_normalised_error_metric():
     den = np.array([[2.0, 0.0]])
     assert orc.normalised_error(np.array([[1.5, 0.0]]), ref, den) == pytest.approx(0.25)
     assert orc.normalised_error(np.array([[1.0, 1e-30]]), ref, den) == math.inf
+
+
+def test_im2col_3x3_against_scipy_correlation_and_by_hand():
+    """The lowered 3x3 convolution: a dense weight row times im2col(X) must equal
+    scipy's 2-D cross-correlation with zero fill; single taps checked by hand."""
+    from scipy.signal import correlate2d
+    g = np.random.Generator(np.random.PCG64(7))
+    C, B, H, W = 3, 2, 4, 5
+    X = g.standard_normal((C, B, H, W))
+    I = orc.im2col_3x3(X)
+    assert I.shape == (9 * C, B * H * W)
+    kern = g.standard_normal((C, 3, 3))
+    out = (kern.reshape(1, -1) @ I).reshape(B, H, W)
+    ref = np.zeros((B, H, W))
+    for b in range(B):
+        for c in range(C):
+            ref[b] += correlate2d(X[c, b], kern[c], mode="same", boundary="fill", fillvalue=0)
+    assert np.allclose(out, ref, rtol=0, atol=1e-12)
+    # by hand: centre tap is X itself; tap (dy,dx) = (-1,+1) of pixel (0,0) is outside; of (1,0) it is X[.,.,0,1]
+    assert np.array_equal(I[9 * 1 + 4], X[1].reshape(-1))
+    k = 9 * 2 + 3 * 0 + 2
+    assert I[k, (0 * H + 0) * W + 0] == 0.0
+    assert I[k, (1 * H + 1) * W + 0] == X[2, 1, 0, 1]
+    assert I[9 * 0 + 3 * 2 + 0, (0 * H + 3) * W + 2] == 0.0          # below the last row
+    assert I[9 * 0 + 3 * 1 + 0, (0 * H + 2) * W + 0] == 0.0          # left of the first column
