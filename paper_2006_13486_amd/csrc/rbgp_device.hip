@@ -586,12 +586,12 @@ int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out,
   if (images <= 0 || height <= 0 || width <= 0 || (width % 4)) return RBGP_ESHAPE;
   const int64_t N = images * height * width;
   if (channels_out != m->M || 9 * channels_in != m->K || ldO < N) return RBGP_ESHAPE;
-  if (dtype != RBGP_F32 || resolve_kernel(m, dtype) != RBGP_KERNEL_MFMA_REG) return RBGP_EUNSUPPORTED;
+  if (resolve_kernel(m, dtype) != RBGP_KERNEL_MFMA_REG) return RBGP_EUNSUPPORTED;
   if (!dev_packed || !dev_X || !dev_O) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
   const rbgp_conv_geometry geom = {images, height, width};
-  return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, false, N, dev_packed, dev_X, N,
+  return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, dtype == RBGP_BF16_F32ACC, N, dev_packed, dev_X, N,
                          static_cast<float *>(dev_O), ldO, hip_stream, &geom);
 }
 

@@ -429,8 +429,8 @@ struct RegTables {  // device tables of the clustering
 struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
-  int32_t *rowtab_conv = nullptr;  // fused convolution (fp32): byte offsets for the geometry below
-  int64_t conv_key[3] = {0, 0, 0}; // images, height, width of rowtab_conv
+  int32_t *rowtab_conv[2] = {nullptr, nullptr};   // fused convolution, fp32 / bf16: byte offsets for the geometry below
+  int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};  // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
   RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
   int tab_bf16_G = 0;
@@ -482,7 +482,8 @@ void rbgp_reg_release(void *state) {
   if (!st) return;
   if (st->rowtab) (void)hipFree(st->rowtab);
   if (st->rowtab_bf16) (void)hipFree(st->rowtab_bf16);
-  if (st->rowtab_conv) (void)hipFree(st->rowtab_conv);
+  for (int32_t *t : st->rowtab_conv)
+    if (t) (void)hipFree(t);
   free_tables(&st->tab);
   free_tables(&st->tab_bf16);
   delete st;
@@ -492,14 +493,16 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
                     const void *I, int64_t ldI, float *O, int64_t ldO, void *stream, const rbgp_conv_geometry *conv) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
-  // Fused 3x3 convolution: fp32, the nine taps are the columns of a complete G_b, image rows hold
-  // whole 16-byte loads; "I" is then the padded activation tensor and ldI is not used.
+  // Fused 3x3 convolution: the nine taps are the columns of a complete G_b and an image row holds
+  // whole lane loads (4 columns; 8 with the wide bf16 tile); "I" is then the padded activation
+  // tensor and ldI is not used.
   int64_t chs = 0;   // bytes of one channel of X
   if (conv) {
-    if (bf16 || m->c[3] != 9 || m->d[3] != 9) return RBGP_EUNSUPPORTED;
+    if (m->c[3] != 9 || m->d[3] != 9) return RBGP_EUNSUPPORTED;
     if (conv->images <= 0 || conv->height <= 0 || conv->width <= 0 || conv->width % 4) return RBGP_ESHAPE;
     if (N != conv->images * conv->height * conv->width) return RBGP_ESHAPE;
-    chs = conv->images * (conv->height + 2) * (conv->width + 2) * 4;
+    if (reinterpret_cast<uintptr_t>(I) % 4) return RBGP_ESHAPE;
+    chs = conv->images * (conv->height + 2) * (conv->width + 2) * (bf16 ? 2 : 4);
     if ((int64_t(pl.SRC) / 9 + 1) * chs >= (int64_t(1) << 31)) return RBGP_EUNSUPPORTED;
     ldI = N;   // (only the checks below read it)
   }
@@ -510,8 +513,8 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   // enough column tiles remain to fill the chip.
   int CW = 64;
   if (bf16) {
-    const bool ok64 = (ldI % 4 == 0) && (reinterpret_cast<uintptr_t>(I) % 8 == 0);
-    const bool ok128 = (ldI % 8 == 0) && (reinterpret_cast<uintptr_t>(I) % 16 == 0);
+    const bool ok64 = conv ? true : (ldI % 4 == 0) && (reinterpret_cast<uintptr_t>(I) % 8 == 0);
+    const bool ok128 = conv ? conv->width % 8 == 0 : (ldI % 8 == 0) && (reinterpret_cast<uintptr_t>(I) % 16 == 0);
     const int tc = tune[RBGP_TUNE_COLS_PER_WORKGROUP];
     if (tc != 0 && tc != 64 && tc != 128) return RBGP_EUNSUPPORTED;
     if (tc)
@@ -535,9 +538,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (!st) return RBGP_ENOMEM;
     *state = st;
   }
-  int32_t **rowtab = conv ? &st->rowtab_conv : bf16 ? &st->rowtab_bf16 : &st->rowtab;
-  if (conv && *rowtab &&
-      (st->conv_key[0] != conv->images || st->conv_key[1] != conv->height || st->conv_key[2] != conv->width)) {
+  int32_t **rowtab = conv ? &st->rowtab_conv[bf16] : bf16 ? &st->rowtab_bf16 : &st->rowtab;
+  int64_t *ckey = st->conv_key[bf16];
+  if (conv && *rowtab && (ckey[0] != conv->images || ckey[1] != conv->height || ckey[2] != conv->width)) {
     (void)hipFree(*rowtab);   // (waits for launches that still read the old table)
     *rowtab = nullptr;
   }
@@ -553,9 +556,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (conv) {   // stage-relative row 9 * channel + tap -> byte offset of the channel plus the shift of the tap
       for (int32_t &r : rt) {
         const int tap = r % 9, dy = tap / 3 - 1, dx = tap % 3 - 1;
-        r = int32_t((r / 9) * chs + (dy * (conv->width + 2) + dx) * 4);
+        r = int32_t((r / 9) * chs + (dy * (conv->width + 2) + dx) * es);
       }
-      st->conv_key[0] = conv->images; st->conv_key[1] = conv->height; st->conv_key[2] = conv->width;
+      ckey[0] = conv->images; ckey[1] = conv->height; ckey[2] = conv->width;
     }
     int rc = upload(rt, rowtab);
     if (rc) return rc;

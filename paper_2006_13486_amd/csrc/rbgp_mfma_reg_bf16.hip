@@ -91,7 +91,8 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   const bool valid = nt < p.ntiles;
   if (lgS == 0 && !valid) return;        // (with S > 1 every wave reaches the barrier below)
   const int64_t n0 = int64_t(nt) * CW;
-  const uint32_t n0b = uint32_t(nt) * uint32_t(CW * 2);   // byte offset of the wave's first column
+  // byte offset of the wave's first column (fused convolution: part of `off` below)
+  const uint32_t n0b = p.conv ? 0u : uint32_t(nt) * uint32_t(CW * 2);
   const int kg = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;
 
@@ -121,8 +122,21 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 
   // byte offset of this lane's NC bf16 columns in each of its rows, relative to the stage base
   int off[NLD];
+  if (p.conv) {
+    // Fused 3x3 convolution (see the fp32 kernel): the lane's NC columns are NC pixels of one
+    // image row (W % NC == 0); the table holds channel offset + tap shift in bytes.  A tap
+    // shift of one pixel makes the load 2-byte aligned, which the memory path accepts.
+    const uint32_t n = uint32_t(n0) + uint32_t(NC) * uint32_t(j), hw = uint32_t(p.conv_h) * uint32_t(p.conv_w);
+    const uint32_t img = n / hw, rem = n - img * hw, y = rem / uint32_t(p.conv_w), x = rem - y * uint32_t(p.conv_w);
+    const int colbase = int64_t(n) < p.N
+                            ? int(((img * uint32_t(p.conv_h + 2) + y + 1) * uint32_t(p.conv_w + 2) + x + 1) * 2u)
+                            : (p.conv_w + 3) * 2;
 #pragma unroll
-  for (int i = 0; i < NLD; ++i) off[i] = rrow[i] * (int(p.ldI) * 2) + j * (NC * 2);
+    for (int i = 0; i < NLD; ++i) off[i] = rrow[i] + colbase;
+  } else {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) off[i] = rrow[i] * (int(p.ldI) * 2) + j * (NC * 2);
+  }
   const int alane = (kg * RS + ri) * 16;
 
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
@@ -137,9 +151,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   // stage's part of I and the offset of each tile row's weights (see the fp32 kernel); the
   // loop only reads them back.  A tile row that lacks the tile reads past the end of the
   // packed buffer, which returns zeros.
-  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tb < 0 ? 0 : tb)) * p.row_bytes + n0b;
+  const int tbu = p.conv ? int(uint32_t(tb < 0 ? 0 : tb) / 9u) : (tb < 0 ? 0 : tb);   // first row (channel) of the stage
+  const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tbu)) * p.row_bytes + n0b;
   const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
-  const int rows_left = p.last_row - tb < p.src_rows ? p.last_row - tb : p.src_rows;
+  const int rows_left = p.last_row - tbu < p.src_rows ? p.last_row - tbu : p.src_rows;
   const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
   int aoff[U];
 #pragma unroll

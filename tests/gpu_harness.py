@@ -64,7 +64,8 @@ def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
     stream = torch.cuda.current_stream().cuda_stream
     packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, dtype), 16), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, dtype, np.ascontiguousarray(vals), packed.data_ptr(), stream)
-    X_d = torch.from_numpy(wl.zero_padded(X)).to(dev)
+    Xp = wl.zero_padded(X)
+    X_d = torch.from_numpy(Xp.view(np.int16) if Xp.dtype == np.uint16 else Xp).to(dev)
     O_d = torch.full((w.M, N), float("nan"), dtype=torch.float32, device=dev)
     rb.rbgp_conv3x3(mask, dtype, w.M, C, B, H, W, packed.data_ptr(), X_d.data_ptr(), O_d.data_ptr(), N, stream)
     torch.cuda.synchronize()

@@ -224,6 +224,9 @@ CONV_CASES = [
     (wl.Workload("conv_wide", (4, 2, 4, 1), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 67, 68, 69, 1.0), 2, 5, 32),
     (wl.VGG19_CONV5, 128, 4, 4),          # the headline layer: 512 -> 512 channels, 4x4 pixels, batch 128
     (wl.WRN_G1, 8, 32, 32),               # WRN-40-4 group 1 at batch 8
+    (wl.VGG19_CONV3_BF16, 128, 8, 8),     # bf16: 256 -> 256 channels, 8x8 pixels (128-column wave tiles)
+    (replace(wl.VGG19_CONV3_BF16, name="conv3_bf16_4x4"), 33, 4, 4),     # bf16, 64-column tiles, ragged N
+    (replace(wl.Workload("conv_small_bf16", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.BF16, 71, 72, 73, 1.0)), 3, 5, 8),
 ]
 
 
@@ -234,12 +237,18 @@ def test_fused_conv3x3_equals_spmm_on_the_lowered_input(case):
     w, B, H, W = case
     vals = wl.kept_weights(w)
     X = wl.conv_activations(w, B, H, W)
-    for tune in (None, (0, 0, 0, 0, 0, 2)):
-        out = gh.library_conv3x3(w, vals, X, tune=tune)
-        ref, den = gh.oracle_spmm(w, vals, orc.im2col_3x3(X))
+    if w.dtype == wl.BF16:                # both sides consume the same bf16 bits
+        vals_lib, X_lib = wl.to_bf16_bits(vals), wl.to_bf16_bits(X)
+        vals, X = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(X_lib)
+    else:
+        vals_lib, X_lib = vals, X
+    ref, den = gh.oracle_spmm(w, vals, orc.im2col_3x3(X))
+    tunes = [None, (0, 0, 0, 0, 0, 2)] + ([(0, 64, 0, 0, 2, 1)] if w.dtype == wl.BF16 else [])
+    for tune in tunes:
+        out = gh.library_conv3x3(w, vals_lib, X_lib, tune=tune)
         err = orc.normalised_error(out, ref, den)
         print(f"[gpu]   normalised error {err:.3e}", flush=True)
-        assert err <= gh.TOL[wl.F32], err
+        assert err <= gh.TOL[w.dtype], err
 
 
 def test_fused_conv3x3_argument_checks():
@@ -248,7 +257,7 @@ def test_fused_conv3x3_argument_checks():
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
     buf = torch.zeros(1 << 20, dtype=torch.float32, device="cuda:0")
     args = (buf.data_ptr(), buf.data_ptr(), buf.data_ptr())
-    for bad, code in [(dict(width=6), rb.ESHAPE), (dict(cin=w.K // 9 + 1), rb.ESHAPE), (dict(dtype=rb.BF16_F32ACC), rb.EUNSUPPORTED)]:
+    for bad, code in [(dict(width=6), rb.ESHAPE), (dict(cin=w.K // 9 + 1), rb.ESHAPE)]:
         with pytest.raises(rb.RbgpError) as ei:
             rb.rbgp_conv3x3(mask, bad.get("dtype", rb.F32), w.M, bad.get("cin", w.K // 9), B, H, bad.get("width", W),
                             args[0], args[1], args[2], B * H * bad.get("width", W), 0)
