@@ -59,16 +59,32 @@ def cpu_baseline(w, vals_f32, I_f32, out_gpu):
             "parity_err": err}
 
 
-def time_workload(w, args, torch, dev, steps, warmup, check_cols=0):
-    """Pack, run and time one workload; returns a dict (kernel time, rates, optional sampled parity)."""
+def time_workload(w, args, torch, dev, steps, warmup, check_cols=0, geom=None):
+    """Pack, run and time one workload; returns a dict (kernel time, rates, optional sampled parity).
+    geom = (images, height, width): run the layer through rbgp_conv3x3 instead of rbgp_spmm."""
     bf16 = w.dtype == wl.BF16
     vals = wl.kept_weights(w)
-    I = wl.activations(w)
-    if bf16:
-        vals_lib, I_lib = wl.to_bf16_bits(vals), wl.to_bf16_bits(I)
-        vals_f32, I_f32 = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(I_lib)
+    if geom:
+        X = wl.conv_activations(w, *geom)
+        if bf16:
+            Xbits = wl.to_bf16_bits(X)
+            X = wl.bf16_bits_as_f32(Xbits)
+            I_lib = wl.zero_padded(Xbits)
+        else:
+            I_lib = wl.zero_padded(X)
+        I_f32 = None
     else:
-        vals_lib, I_lib, vals_f32, I_f32 = vals, I, vals, I
+        I = wl.activations(w)
+    if bf16:
+        vals_lib = wl.to_bf16_bits(vals)
+        vals_f32 = wl.bf16_bits_as_f32(vals_lib)
+        if not geom:
+            I_lib = wl.to_bf16_bits(I)
+            I_f32 = wl.bf16_bits_as_f32(I_lib)
+    else:
+        vals_lib, vals_f32 = vals, vals
+        if not geom:
+            I_lib, I_f32 = I, I
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
     if args.kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask, args.kernel)
@@ -78,16 +94,21 @@ def time_workload(w, args, torch, dev, steps, warmup, check_cols=0):
     stream = torch.cuda.current_stream().cuda_stream
     packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, w.dtype), 16), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
-    set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
+    set_bytes = I_lib.nbytes + w.M * w.N * 4
     nsets = max(2, min(16, -(-512 * 2**20 // set_bytes)))
     I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
     Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
     Os = [torch.empty((w.M, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+    algorithmic_bytes = I_lib.nbytes + w.M * w.N * 4 + w.nnz * w.in_bytes
 
     def step(i):
         j = i % nsets
-        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
-                     Os[j].data_ptr(), w.N, stream)
+        if geom:
+            rb.rbgp_conv3x3(mask, w.dtype, w.M, w.K // 9, geom[0], geom[1], geom[2], packed.data_ptr(),
+                            Is[j].data_ptr(), Os[j].data_ptr(), w.N, stream)
+        else:
+            rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
+                         Os[j].data_ptr(), w.N, stream)
 
     for i in range(warmup):
         step(i)
@@ -103,7 +124,8 @@ def time_workload(w, args, torch, dev, steps, warmup, check_cols=0):
            "dtype": "bf16" if bf16 else "f32",
            "rows": list(w.rows), "cols": list(w.cols), "row_deg": list(w.row_deg),
            "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "kernel_us": us,
-           "eff_tflops": w.flops / us / 1e6, "algorithmic_gbs": w.algorithmic_bytes / us / 1e3}
+           "entry_point": "rbgp_conv3x3" if geom else "rbgp_spmm",
+           "eff_tflops": w.flops / us / 1e6, "algorithmic_gbs": algorithmic_bytes / us / 1e3}
     if check_cols:
         from oracle import naive_c
         from oracle import rbgp_oracle as orc
@@ -112,7 +134,7 @@ def time_workload(w, args, torch, dev, steps, warmup, check_cols=0):
         W = orc.scatter_values(dense_mask, vals_f32)
         g = np.random.Generator(np.random.PCG64(w.i_seed + 7))
         cols = np.sort(g.choice(w.N, size=min(check_cols, w.N), replace=False))
-        Isub = np.ascontiguousarray(I_f32[:, cols])
+        Isub = np.ascontiguousarray((orc.im2col_3x3(X) if geom else I_f32)[:, cols])
         ref, den = naive_c.spmm(dense_mask, W, Isub), naive_c.spmm_abs(dense_mask, W, Isub)
         res["parity_err"] = orc.normalised_error(Os[0].cpu().numpy()[:, cols], ref, den)
         res["parity_cols"] = int(len(cols))
@@ -129,14 +151,24 @@ def sweep_cases(which, args):
         return [wl.sdmm4096_table3(gr, gb, d) for gr, gb in shapes for d in (2, 3, 4)]
     dens = [int(x) for x in args.sweep_density.split(",")]
     dts = {"f32": [wl.F32], "bf16": [wl.BF16], "both": [wl.F32, wl.BF16]}[args.sweep_dtype]
-    return [wl.vgg19_sweep_workload(layer, d, dt) for dt in dts for d in dens for layer in range(len(wl.VGG19_LAYERS))]
+    cases = []
+    for dt in dts:
+        for d in dens:
+            for layer in range(len(wl.VGG19_LAYERS)):
+                w = wl.vgg19_sweep_workload(layer, d, dt)
+                h = wl.VGG19_LAYERS[layer][2]
+                # --fused-conv: layers whose image rows hold whole lane loads go through rbgp_conv3x3
+                fused = args.fused_conv and layer > 0 and h % 4 == 0
+                cases.append((w, (w.N // (h * h), h, h)) if fused else w)
+    return cases
 
 
 def run_sweep(args, torch, dev):
     cases = []
-    for w in sweep_cases(args.sweep, args):
+    for case in sweep_cases(args.sweep, args):
+        w, geom = case if isinstance(case, tuple) else (case, None)
         try:
-            r = time_workload(w, args, torch, dev, args.sweep_steps, args.sweep_steps, args.sweep_check)
+            r = time_workload(w, args, torch, dev, args.sweep_steps, args.sweep_steps, args.sweep_check, geom)
         except rb.RbgpError as e:   # a cell whose factors cannot be sampled (recorded, not hidden)
             r = {"name": w.name, "error": str(e)}
         print(f"[sweep] {r}", file=sys.stderr, flush=True)
