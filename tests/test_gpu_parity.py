@@ -284,3 +284,44 @@ def test_sdmm4096_paper_workload_sampled():
     cols = np.r_[0:64, 2000:2064, 4032:4096]
     ref, den = gh.oracle_spmm(w, vf, np.ascontiguousarray(If[:, cols]))
     assert orc.normalised_error(out[:, cols], ref, den) <= gh.TOL[w.dtype]
+
+
+# ------------------------------------------------------------------ random masks, library defaults
+def _random_shapes(count, seed):
+    """Seeded random four-factor shapes (G_r, G_b complete) that the sampler accepts."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    while len(shapes) < count:
+        lo, li = int(g.integers(0, 3)), int(g.integers(0, 3))            # log2 of G_o's / G_i's inverse density
+        a_o = int(g.choice([1, 2, 3, 4, 6, 8, 12, 16])) << lo
+        c_o = int(g.choice([1, 2, 3, 4, 8])) << lo
+        a_i = int(g.choice([1, 2, 4])) << li
+        c_i = int(g.choice([1, 2, 4])) << li
+        a_r, c_r = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 2, 3, 4]))
+        a_b, c_b = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 3, 9, 9]))
+        rows, cols = (a_o, a_r, a_i, a_b), (c_o, c_r, c_i, c_b)
+        deg = (c_o >> lo, c_r, c_i >> li, c_b)
+        if a_o * a_r * a_i * a_b > 2048 or c_o * c_r * c_i * c_b > 4096:
+            continue
+        try:
+            rb.rbgp_make_mask(rows, cols, deg, 900 + len(shapes))
+        except rb.RbgpError:
+            continue
+        shapes.append((rows, cols, deg, int(g.integers(1, 700))))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_random_masks_with_library_defaults(dtype):
+    """Forty seeded random shapes, ragged column counts, whatever kernel and launch shape the
+    library chooses for them."""
+    used = set()
+    for idx, (rows, cols, deg, N) in enumerate(_random_shapes(40, 2024)):
+        w = wl.Workload(f"random{idx}_{dtype}", rows, cols, deg, N, dtype, 900 + idx, 1000 + idx, 1100 + idx, 1.0)
+        vl, Il, vf, If = gh.host_inputs(w)
+        out, kernel = gh.library_spmm(w, vl, Il, ld_pad=(-N) % 8)    # a leading dimension every family accepts
+        used.add(kernel)
+        ref, den = gh.oracle_spmm(w, vf, If)
+        err = orc.normalised_error(out, ref, den)
+        assert err <= gh.TOL[dtype], (rows, cols, deg, N, kernel, err)
+    assert rb.KERNEL_MFMA_REG in used and len(used) >= 2, used
