@@ -14,7 +14,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=de
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    """Compile every source and link librbgp.so (always recompiles)."""
+    """Compile every source and link librbgp.so (always recompiles).
+    extra: more hipcc flags, e.g. ["-DRBGP_EXPERIMENT"] for the instrumented build that records
+    per-wave time stamps (RBGP_TRACE=<file> RBGP_TRACE_AT=<launch number> at run time)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []

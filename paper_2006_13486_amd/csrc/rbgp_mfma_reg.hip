@@ -1,5 +1,6 @@
 // Register-streaming MFMA kernels for O = W_s x I (Section 5, "GPU
-// Implementation"), fp32.
+// Implementation"): the fp32 kernel, and the launcher and device tables of both
+// dtypes (the bf16 kernel is in rbgp_mfma_reg_bf16.hip).
 //
 // Work decomposition.  One wavefront owns: a cluster of U tile rows u_o, one G_i
 // vertex u_i (so, per tile row, the R = |G_r.U|*|G_b.U| rows that share a column
@@ -9,9 +10,13 @@
 // touches are loaded straight from global memory into VGPRs and each loaded row
 // is used for every tile row of the cluster that has the tile: the register-level
 // reuse the paper obtains from row repetition, extended across tile rows.  No
-// LDS, no barrier: waves are independent; loads are issued two stages ahead, slot
-// by slot, into the registers the previous MFMAs just released, and the
-// compiler's vmcnt bookkeeping provides the software pipeline.
+// LDS, no barrier in the main loop: waves are independent; loads are issued two
+// stages ahead, slot by slot, into the registers the previous MFMAs just released,
+// and the compiler's vmcnt bookkeeping provides the software pipeline.  (LDS is
+// used once, after the loop, when the stage list of a cluster is split over
+// several waves for small N; and optionally to hold the workgroup's weights.)
+// The same kernel serves the fused 3x3 convolution: only the addresses of the
+// loads differ (see `off` in the prologue).
 //
 // Arithmetic.  v_mfma_f32_16x16x1_4b_f32: four independent 16x16 outer products
 // per instruction.  The 64 lanes form 4 groups of 16 (= the 4 blocks).  One
