@@ -330,9 +330,9 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
 //  MFMA_REG: [u_o][j_o][stage][u_i][q][g][i][w]: the stage's contraction list
 //           kk = ((v_r % VC) * d_i + j_i) * |G_b.V| + v_b is dealt to 4 lane
 //           groups g; element (q, g, i, w) is the weight of row i (< RS, the
-//           group's (u_r, u_b) rows padded to a power of two) at kk = 16q + 4w + g,
-//           so that one 16-byte load per lane fetches a row's weights for four
-//           consecutive load slots.
+//           group's (u_r, u_b) rows padded to a power of two) at position kk = 16q + 4w + g
+//           (= step rbgp_reg_step(kk) of the list), so that one 16-byte load per lane
+//           fetches a row's weights for four consecutive load slots.
 //  MFMA_REG, bf16: same fragment order; the stage's contraction list is cut into blocks
 //           of 32 steps and possibly one last block of 16; element (q, g, i, e) of a
 //           fragment, e = 0..7, is the weight of row i at kk = 32q + 8g + e in a block of
@@ -381,7 +381,7 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
                     if (kk >= p.KC || r >= p.R) continue;
                     const int u2 = r / a4, u4 = r % a4;
                     const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
-                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + kk;
+                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + rbgp_reg_step(m, kk);
                     perm[pos] = int32_t(row * m->rowdeg + t);
                   }
     return;

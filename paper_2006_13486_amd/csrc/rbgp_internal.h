@@ -43,6 +43,16 @@ struct rbgp_reg_plan {
   int64_t packed_elems_bf16 = 0;  // bf16 layout
 };
 
+// fp32 register-streaming kernels: which step of a stage's contraction list
+// ((v_r % VC) * d_i + j_i) * |G_b.V| + v_b  sits at position kk of the packed fragment and of the
+// row table (position kk = 4 * slot + lane group).  Identity, except for masks whose G_b is the
+// nine taps of a 3x3 convolution (|G_b.V| = 9 complete) with a stage of a multiple of 12 steps:
+// there the three horizontal taps (dx = -1, 0, +1) of one (channel, dy) pair occupy three
+// consecutive slots of ONE lane group, so that the fused convolution can build all three from
+// one load of the pixel row.  The order of the steps inside a stage does not matter to the product.
+inline bool rbgp_reg_tap_grouped(const rbgp_mask *m);
+inline int rbgp_reg_step(const rbgp_mask *m, int kk);
+
 // Clustering of the tile rows for the register-streaming family (host tables).
 struct rbgp_reg_clusters {
   int U = 0;                      // tile rows per cluster
@@ -66,6 +76,17 @@ struct rbgp_mask {
   rbgp_reg_clusters reg_clusters;     // clusters of reg.MG tile rows (when reg.ok)
   mutable rbgp_device_state *dev;     // lazily created device tables
 };
+
+inline bool rbgp_reg_tap_grouped(const rbgp_mask *m) {
+  return m->reg.ok && m->c[3] == 9 && m->d[3] == 9 && m->reg.KC % 12 == 0;
+}
+inline int rbgp_reg_step(const rbgp_mask *m, int kk) {
+  if (!rbgp_reg_tap_grouped(m)) return kk;
+  const int slot = kk / 4, g = kk % 4;
+  const int pair = (slot / 3) * 4 + g;          // (channel-like index, dy) pair handled by lane group g
+  const int dxi = slot % 3, dyi = pair % 3;
+  return (pair / 3) * 9 + 3 * dyi + dxi;
+}
 
 enum { RBGP_NUM_KERNELS = 4 };   // one more than the largest RBGP_KERNEL_* value
 

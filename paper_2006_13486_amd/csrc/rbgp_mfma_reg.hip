@@ -555,7 +555,8 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     std::vector<int32_t> rt(size_t(a3) * len, 0);
     for (int u3 = 0; u3 < a3; ++u3)
       for (int kk = 0; kk < pl.KC; ++kk) {
-        const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
+        const int st = bf16 ? kk : rbgp_reg_step(m, kk);   // step of the contraction list at position kk
+        const int v4 = st % c4, j3 = (st / c4) % d3, vv = st / (c4 * d3);
         rt[size_t(u3) * len + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
       }
     if (conv) {   // stage-relative row 9 * channel + tap -> byte offset of the channel plus the shift of the tap
