@@ -63,8 +63,13 @@ namespace {
 // (cluster size MG = 16 / RS); WLDS: the weights of the workgroup's (cluster, G_i vertex)
 // are copied to LDS once and read from there (they are the same for every column tile),
 // else they stream from global memory like I.
-template <int KC, int RS, bool WLDS>
+// TAPS (fused 3x3 convolution on a tap-grouped layout, image width dividing 64): slots 3p,
+// 3p+1, 3p+2 of a lane group are the taps dx = -1, 0, +1 of one (channel, dy) pair, i.e. three
+// windows of the same pixel row shifted by one pixel.  Only the middle one is loaded; the other
+// two are put together from it and the neighbouring lane's pixel (DPP), zero at an image border.
+template <int KC, int RS, bool WLDS, bool TAPS = false>
 __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
+  static_assert(!TAPS || (!WLDS && KC % 12 == 0), "tap-grouped stages are multiples of 12 steps");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
   constexpr int NQ = (NO + 3) / 4;       // weight registers per stage come as NQ 16-byte loads
@@ -127,6 +132,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
   int off[NO];
+  bool row_start = false, row_end = false;   // TAPS: the lane's four pixels touch the left / right image border
   if (p.conv) {
     // Fused 3x3 convolution: column n = (image * H + y) * W + x of the lowered input is pixel
     // (y + dy, x + dx) of the zero-padded image; the lane's four columns lie in one image row
@@ -139,6 +145,8 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
                             : (p.conv_w + 3) * 4;   // (columns past N: any pixel inside X; never stored)
 #pragma unroll
     for (int o = 0; o < NO; ++o) off[o] = rrow[o] + colbase;
+    row_start = x == 0;
+    row_end = x + 4 == uint32_t(p.conv_w);
   } else {
 #pragma unroll
     for (int o = 0; o < NO; ++o) off[o] = rrow[o] * (int(p.ldI) * 4) + j * 16;   // < 2^31: checked by the host
@@ -267,6 +275,28 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
       return load_x4(rw, addr, q * QB);
   };
 
+  // The four B operands of slot o (one per column offset w).  TAPS: from the pair's middle window
+  // c (pixels x .. x+3): dx = -1 is {left neighbour, c0, c1, c2}, dx = +1 is {c1, c2, c3, right
+  // neighbour}; the neighbours are the adjacent lanes' pixels, or zero outside the image.
+  auto operand = [&](const f32x4 (&B)[NO], auto oc) {
+    constexpr int o = decltype(oc)::value;
+    if constexpr (!TAPS) {
+      return B[o];
+    } else {
+      constexpr int dxi = o % 3;
+      const f32x4 c = B[o - dxi + 1];
+      if constexpr (dxi == 1) {
+        return c;
+      } else if constexpr (dxi == 0) {
+        const int nb = __builtin_amdgcn_update_dpp(0, __float_as_int(c[3]), 0x111 /* row_shr:1 */, 0xf, 0xf, true);
+        return f32x4{row_start ? 0.f : __int_as_float(nb), c[0], c[1], c[2]};
+      } else {
+        const int nb = __builtin_amdgcn_update_dpp(0, __float_as_int(c[0]), 0x101 /* row_shl:1 */, 0xf, 0xf, true);
+        return f32x4{c[1], c[2], c[3], row_end ? 0.f : __int_as_float(nb)};
+      }
+    }
+  };
+
   // One stage: MFMAs of stage s from (B, A); every B slot and every weight quad is
   // refilled for stage s + 2 right after its last use (RELOAD), so that about two stages
   // of loads are in flight at any time.  Every real stage has work (the stage list is the
@@ -283,10 +313,14 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
       const float a = A[o / 4][o % 4];
+      const f32x4 b = operand(B, oc);
 #pragma unroll
-      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, B[o][w], acc[w], 0, 0, 0);
+      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[w], 0, 0, 0);
       if constexpr (RELOAD) {
-        B[o] = load_x4(rb2, off[o], sofs);
+        if constexpr (!TAPS)
+          B[o] = load_x4(rb2, off[o], sofs);
+        else if constexpr (o % 3 == 2)
+          B[o - 1] = load_x4(rb2, off[o - 1], sofs);   // the pair's middle window, after its last use
         if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
         __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
       }
@@ -299,7 +333,10 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     const int av = a_addr(s);
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
-      B[o] = load_x4(rb2, off[o], sofs);
+      if constexpr (!TAPS)
+        B[o] = load_x4(rb2, off[o], sofs);
+      else if constexpr (o % 3 == 2)
+        B[o - 1] = load_x4(rb2, off[o - 1], sofs);
       if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -314,10 +351,16 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
       const float a = A[o / 4][o % 4];
+      const f32x4 b = operand(B, oc);
 #pragma unroll
-      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, B[o][w], acc[w], 0, 0, 0);
-      Bn[o] = load_x4(rb1, off[o], sofs1);
-      B[o] = load_x4(rb2, off[o], sofs2);
+      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[w], 0, 0, 0);
+      if constexpr (!TAPS) {
+        Bn[o] = load_x4(rb1, off[o], sofs1);
+        B[o] = load_x4(rb2, off[o], sofs2);
+      } else if constexpr (o % 3 == 2) {
+        Bn[o - 1] = load_x4(rb1, off[o - 1], sofs1);
+        B[o - 1] = load_x4(rb2, off[o - 1], sofs2);
+      }
       if constexpr (o % 4 == 3 || o == NO - 1) {
         An[o / 4] = a_load(av1, o / 4);
         A[o / 4] = a_load(av2, o / 4);
@@ -411,11 +454,18 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 }
 
 typedef rbgp_reg_fn reg_fn;
+template <int KC, int RS>
+constexpr reg_fn taps_kernel() {   // the tap-grouped variant exists for stages of a multiple of 12 steps
+  if constexpr (KC % 12 == 0)
+    return spmm_reg<KC, RS, false, true>;
+  else
+    return nullptr;
+}
 struct RegEntry {
   int KC, RS;
-  reg_fn lds_fn, global_fn;
+  reg_fn lds_fn, global_fn, taps_fn;
 };
-#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>}
+#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>, taps_kernel<KC, RS>()}
 const RegEntry kRegTable[] = {RBGP_R(8, 4),  RBGP_R(18, 2), RBGP_R(36, 2), RBGP_R(72, 2),
                               RBGP_R(18, 4), RBGP_R(36, 4), RBGP_R(72, 4),
                               RBGP_R(18, 8), RBGP_R(36, 8), RBGP_R(72, 8)};
@@ -643,7 +693,13 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
   const int64_t qgroups = (nquads + 7) / 8;
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
-  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : wlds ? e->lds_fn : e->global_fn;
+  // fused convolution on a tap-grouped layout whose image rows tile the 64 columns of a wave:
+  // the variant that loads one of the three horizontal taps and builds the others.  Measured on
+  // the VGG19 layers: 5-15 % faster for images 8 to 32 pixels wide, slower for 4-pixel-wide ones
+  // (every lane is a whole image row there: nothing to share, only the extra instructions).
+  const bool taps = conv && !bf16 && !wlds && rbgp_reg_tap_grouped(m) && e->taps_fn && conv->width >= 8 &&
+                    64 % conv->width == 0;
+  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : wlds ? e->lds_fn : e->global_fn;
   if (!fn) return RBGP_EUNSUPPORTED;
   if (lds > 64 * 1024)   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
