@@ -251,6 +251,32 @@ def test_fused_conv3x3_equals_spmm_on_the_lowered_input(case):
         assert err <= gh.TOL[w.dtype], err
 
 
+def test_fused_conv3x3_random_geometries():
+    """Thirty seeded random (mask, images, height, width, dtype, stage split) combinations."""
+    g = np.random.Generator(np.random.PCG64(77))
+    shapes = [c[0] for c in CONV_CASES[:3]] + [
+        wl.Workload("conv_r6", (2, 3, 4, 2), (2, 2, 4, 9), (1, 2, 2, 9), 0, wl.F32, 81, 82, 83, 1.0),
+        wl.Workload("conv_kc18", (4, 2, 4, 2), (4, 1, 4, 9), (2, 1, 2, 9), 0, wl.F32, 84, 85, 86, 1.0),
+        wl.Workload("conv_8x8", (8, 2, 4, 1), (8, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 87, 88, 89, 1.0)]
+    ran = 0
+    for it in range(30):
+        dtype = int(g.integers(0, 2))
+        w = replace(shapes[it % len(shapes)], dtype=dtype, name=f"conv_random{it}")
+        B, H, W = int(g.integers(1, 7)), int(g.integers(1, 8)), int(g.choice([4, 8, 12, 16, 20, 32, 64]))
+        vals, X = wl.kept_weights(w), wl.conv_activations(w, B, H, W)
+        if dtype == wl.BF16:
+            vals_lib, X_lib = wl.to_bf16_bits(vals), wl.to_bf16_bits(X)
+            vals, X = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(X_lib)
+        else:
+            vals_lib, X_lib = vals, X
+        out = gh.library_conv3x3(w, vals_lib, X_lib, tune=(0, 0, 0, 0, 0, int(g.choice([0, 1, 2, 4]))))
+        ref, den = gh.oracle_spmm(w, vals, orc.im2col_3x3(X))
+        err = orc.normalised_error(out, ref, den)
+        assert err <= gh.TOL[dtype], (w.rows, B, H, W, dtype, err)
+        ran += 1
+    assert ran == 30
+
+
 def test_fused_conv3x3_argument_checks():
     import torch
     w, B, H, W = CONV_CASES[0]
