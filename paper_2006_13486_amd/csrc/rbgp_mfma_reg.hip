@@ -138,15 +138,13 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     // (y + dy, x + dx) of the zero-padded image; the lane's four columns lie in one image row
     // (W % 4 == 0), so a tap is a constant shift of one 16-byte load.  The table entry already
     // holds channel * bytes per channel + shift of the tap.
-    const uint32_t n = uint32_t(n0) + 4u * uint32_t(j), hw = uint32_t(p.conv_h) * uint32_t(p.conv_w);
-    const uint32_t img = n / hw, rem = n - img * hw, y = rem / uint32_t(p.conv_w), x = rem - y * uint32_t(p.conv_w);
-    const int colbase = int64_t(n) < p.N
-                            ? int(((img * uint32_t(p.conv_h + 2) + y + 1) * uint32_t(p.conv_w + 2) + x + 1) * 4u)
-                            : (p.conv_w + 3) * 4;   // (columns past N: any pixel inside X; never stored)
+    // (host table: no integer division here; its two low bits flag the image borders)
+    const int cb = p.colbase[nt < p.ntiles ? int(n0 >> 2) + j : 0];   // (a wave past the last tile loads nothing)
+    const int colbase = cb & ~3;
 #pragma unroll
     for (int o = 0; o < NO; ++o) off[o] = rrow[o] + colbase;
-    row_start = x == 0;
-    row_end = x + 4 == uint32_t(p.conv_w);
+    row_start = cb & 1;
+    row_end = cb & 2;
   } else {
 #pragma unroll
     for (int o = 0; o < NO; ++o) off[o] = rrow[o] * (int(p.ldI) * 4) + j * 16;   // < 2^31: checked by the host
@@ -485,6 +483,7 @@ struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
   int32_t *rowtab_conv[2] = {nullptr, nullptr};   // fused convolution, fp32 / bf16: byte offsets for the geometry below
+  int32_t *colbase[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};   // [dtype][wide tile]: pixel offsets of the column groups
   int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};  // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
   RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
@@ -539,6 +538,9 @@ void rbgp_reg_release(void *state) {
   if (st->rowtab_bf16) (void)hipFree(st->rowtab_bf16);
   for (int32_t *t : st->rowtab_conv)
     if (t) (void)hipFree(t);
+  for (auto &pair : st->colbase)
+    for (int32_t *t : pair)
+      if (t) (void)hipFree(t);
   free_tables(&st->tab);
   free_tables(&st->tab_bf16);
   delete st;
@@ -598,6 +600,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (conv && *rowtab && (ckey[0] != conv->images || ckey[1] != conv->height || ckey[2] != conv->width)) {
     (void)hipFree(*rowtab);   // (waits for launches that still read the old table)
     *rowtab = nullptr;
+    for (int32_t *&t : st->colbase[bf16]) {
+      if (t) (void)hipFree(t);
+      t = nullptr;
+    }
   }
   if (!*rowtab) {
     const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
@@ -674,6 +680,25 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.n_bytes = uint32_t((bf16 ? (N + NC - 1) / NC * NC : N) * es);
   rp.last_row = int(m->K - 1);
   rp.src_rows = pl.SRC;
+  rp.colbase = nullptr;
+  if (conv) {
+    // pixel offset of every group of NC columns (one lane's load), padded to whole wave tiles with a
+    // pixel inside X; fp32: bit 0 / bit 1 flag a group at the left / right border of its image row
+    int32_t **cbt = &st->colbase[bf16][CW == 128];
+    if (!*cbt) {
+      const int64_t H = conv->height, W = conv->width;
+      std::vector<int32_t> cb(size_t(ntiles) * (CW / NC), int32_t((W + 3) * es));
+      for (int64_t n = 0; n < N; n += NC) {
+        const int64_t img = n / (H * W), y = (n % (H * W)) / W, x = n % W;
+        int32_t v = int32_t(((img * (H + 2) + y + 1) * (W + 2) + x + 1) * es);
+        if (!bf16) v |= (x == 0 ? 1 : 0) | (x + 4 == W ? 2 : 0);
+        cb[size_t(n / NC)] = v;
+      }
+      int rc = upload(cb, cbt);
+      if (rc) return rc;
+    }
+    rp.colbase = *cbt;
+  }
   rp.conv = conv ? 1 : 0;
   rp.conv_h = conv ? int(conv->height) : 0;
   rp.conv_w = conv ? int(conv->width) : 0;

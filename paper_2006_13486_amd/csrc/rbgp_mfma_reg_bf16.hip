@@ -126,11 +126,7 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     // Fused 3x3 convolution (see the fp32 kernel): the lane's NC columns are NC pixels of one
     // image row (W % NC == 0); the table holds channel offset + tap shift in bytes.  A tap
     // shift of one pixel makes the load 2-byte aligned, which the memory path accepts.
-    const uint32_t n = uint32_t(n0) + uint32_t(NC) * uint32_t(j), hw = uint32_t(p.conv_h) * uint32_t(p.conv_w);
-    const uint32_t img = n / hw, rem = n - img * hw, y = rem / uint32_t(p.conv_w), x = rem - y * uint32_t(p.conv_w);
-    const int colbase = int64_t(n) < p.N
-                            ? int(((img * uint32_t(p.conv_h + 2) + y + 1) * uint32_t(p.conv_w + 2) + x + 1) * 2u)
-                            : (p.conv_w + 3) * 2;
+    const int colbase = p.colbase[nt < p.ntiles ? int(n0 / NC) + j : 0];   // (host table: no integer division here)
 #pragma unroll
     for (int i = 0; i < NLD; ++i) off[i] = rrow[i] + colbase;
   } else {

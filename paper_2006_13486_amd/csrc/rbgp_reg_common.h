@@ -45,6 +45,8 @@ struct RegParams {
   // (channel and tap shift) instead of rows.
   int conv;                // 1: fused convolution
   int conv_h, conv_w;      // image height and width (W a multiple of 4)
+  const int32_t *colbase;  // fused convolution: byte offset, inside a channel of X, of the first pixel of every
+                           //   group of columns one lane loads (4, or 8 with the wide bf16 tile); padded to whole tiles
   int a2, a3, a4, R;
   int fpm;                 // weight fragments per member: d_o * NSTG
   int rowofs[16];          // output row of weight row r of a group, relative to its (tile row, u_i) base
