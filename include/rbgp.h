@@ -186,13 +186,14 @@ int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K,
  * matrix, Section 5 "GPU Implementation"; here the lowering is folded into the loads: the
  * nine taps are the columns of the complete factor G_b.)
  * The mask must have |G_b.V| = 9 complete, K = 9 * channels_in, M = channels_out.
- * dev_X: activations [channels_in][images][height + 2][width + 2], fp32, with a border of
- * one pixel that the caller keeps at zero.  Row k = 9 * c + 3 * (dy + 1) + (dx + 1) of the
- * lowered input is pixel (y + dy, x + dx) of channel c; column n = (image * height + y) *
- * width + x.  dev_O: M x N row-major fp32, N = images * height * width, leading dimension
- * ldO >= N, overwritten.  dev_packed: as for rbgp_spmm (same layout).
- * Runs on the RBGP_KERNEL_MFMA_REG family in fp32 only: EUNSUPPORTED for other masks,
- * families or dtypes; ESHAPE unless width is a multiple of 4 and the sizes match the mask.
+ * dev_X: activations [channels_in][images][height + 2][width + 2] in the dtype's input type
+ * (fp32, or bf16 bits), 4-byte aligned, with a border of one pixel that the caller keeps at
+ * zero.  Row k = 9 * c + 3 * (dy + 1) + (dx + 1) of the lowered input is pixel (y + dy, x + dx)
+ * of channel c; column n = (image * height + y) * width + x.  dev_O: M x N row-major fp32,
+ * N = images * height * width, leading dimension ldO >= N, overwritten.  dev_packed: as for
+ * rbgp_spmm (same layout, same dtype).
+ * Runs on the RBGP_KERNEL_MFMA_REG family only: EUNSUPPORTED for masks or kernel choices
+ * outside it; ESHAPE unless width is a multiple of 4 and the sizes match the mask.
  * Asynchronous on `hip_stream`. */
 int rbgp_conv3x3(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
                  int64_t images, int64_t height, int64_t width, const void *dev_packed, const void *dev_X,
