@@ -174,13 +174,12 @@ int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *de
  * to the next multiple of 4 (8) columns, inside the K x ldI array.  The other
  * cases take any alignment.  I and O may exceed 4 GiB; the RBGP_KERNEL_MFMA_REG
  * family returns EUNSUPPORTED when the rows of I that one of its stages spans
- * (at most |G_r.V| * |G_i.V| * |G_b.V|) times ldI reach 2 GiB.  dev_packed must have been packed with the same kernel family and
- * dtype.  Asynchronous on `hip_stream`. */
+ * (at most |G_r.V| * |G_i.V| * |G_b.V|) times ldI reach 2 GiB.  dev_packed must have
+ * been packed with the same kernel family and dtype.  Asynchronous on `hip_stream`. */
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
               const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,
               void *hip_stream);
 
-/* Static description of an error code / of the last HIP failure in this thread. */
 /* Fused 3x3 convolution (stride 1, zero padding 1): O = W_s x im2col(X) without the lowered
  * input ever being stored.  (The paper feeds its kernel batched activations lowered to a
  * matrix, Section 5 "GPU Implementation"; here the lowering is folded into the loads: the
@@ -199,6 +198,7 @@ int rbgp_conv3x3(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_o
                  int64_t images, int64_t height, int64_t width, const void *dev_packed, const void *dev_X,
                  void *dev_O, int64_t ldO, void *hip_stream);
 
+/* Static description of an error code / of the last HIP failure in this thread. */
 const char *rbgp_strerror(int code);
 const char *rbgp_last_hip_error(void);
 
