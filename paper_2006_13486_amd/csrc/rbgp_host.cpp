@@ -153,7 +153,8 @@ void rbgp_plan_mfma(rbgp_mask *m) {
 }
 
 // Register-streaming family: a stage is VC columns of G_r of one nonzero tile;
-// its contraction list (v_r, j_i, v_b) has KC <= 72 entries, consumed two at a time.
+// its contraction list (v_r, j_i, v_b) has KCR <= 72 entries, padded to a stage size the
+// kernels are built for.
 void rbgp_plan_reg(rbgp_mask *m) {
   rbgp_reg_plan p;
   const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
@@ -166,10 +167,11 @@ void rbgp_plan_reg(rbgp_mask *m) {
     if (m->c[1] % vc == 0 && vc * per_v <= 72) { p.VC = vc; break; }
   p.ok = roles && p.VC > 0 && p.R <= 16;
   if (p.ok) {
-    p.KC = p.VC * per_v;
+    p.KCR = p.VC * per_v;
+    p.KC = p.KCR <= 8 ? 8 : p.KCR <= 18 ? 18 : p.KCR <= 36 ? 36 : 72;
     p.NSTG = m->c[1] / p.VC;
     p.SRC = p.VC * m->c[2] * m->c[3];
-    p.RS = 1;
+    p.RS = 2;
     while (p.RS < p.R) p.RS *= 2;
     p.MG = 16 / p.RS;
     p.NO = (p.KC + 3) / 4;
@@ -356,10 +358,10 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
                   for (int e = 0; e < 8; ++e, ++pos) {
                     if (q >= nk32 && e >= 4) continue;   // upper half of the block of 16: padding
                     const int kk = q < nk32 ? 32 * q + 8 * g + e : 32 * q + 4 * g + e;
-                    if (kk >= p.KC || r >= p.R) continue;
+                    if (kk >= p.KCR || r >= p.R) continue;
                     const int u2 = r / a4, u4 = r % a4;
                     const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
-                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + kk;
+                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KCR + kk;
                     perm[pos] = int32_t(row * m->rowdeg + t);
                   }
     return;
@@ -378,10 +380,10 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
                 for (int r = 0; r < p.RS; ++r)
                   for (int w = 0; w < 4; ++w, ++pos) {
                     const int kk = 16 * q + 4 * w + g;
-                    if (kk >= p.KC || r >= p.R) continue;
+                    if (kk >= p.KCR || r >= p.R) continue;
                     const int u2 = r / a4, u4 = r % a4;
                     const int64_t row = ((int64_t(u1) * a2 + u2) * a3 + u3) * a4 + u4;
-                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KC + rbgp_reg_step(m, kk);
+                    const int64_t t = int64_t(j1) * p.KT + int64_t(sg) * p.KCR + rbgp_reg_step(m, kk);
                     perm[pos] = int32_t(row * m->rowdeg + t);
                   }
     return;

@@ -32,7 +32,9 @@ struct rbgp_reg_plan {
   int R = 0, RB = 0;
   int KT = 0;    // contraction length of one group in one tile: |G_r.V| * d_i * |G_b.V|
   int VC = 0;    // G_r columns per stage
-  int KC = 0;    // contraction length per stage: VC * d_i * |G_b.V|
+  int KCR = 0;   // contraction length per stage: VC * d_i * |G_b.V|
+  int KC = 0;    // KCR rounded up to a stage size the kernels are built for (8, 18, 36, 72); the
+                 //   positions past KCR hold zero weights and read row 0 of the stage
   int NSTG = 0;  // stages per tile: |G_r.V| / VC
   int RS = 0;    // weight rows per tile row inside a 16-row MFMA group: R rounded up to 2^k
   int MG = 0;    // tile rows per MFMA group: 16 / RS
@@ -78,7 +80,7 @@ struct rbgp_mask {
 };
 
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m) {
-  return m->reg.ok && m->c[3] == 9 && m->d[3] == 9 && m->reg.KC % 12 == 0;
+  return m->reg.ok && m->c[3] == 9 && m->d[3] == 9 && m->reg.KC % 12 == 0 && m->reg.KCR == m->reg.KC;
 }
 inline int rbgp_reg_step(const rbgp_mask *m, int kk) {
   if (!rbgp_reg_tap_grouped(m)) return kk;

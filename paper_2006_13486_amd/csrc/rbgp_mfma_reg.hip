@@ -464,9 +464,10 @@ struct RegEntry {
   reg_fn lds_fn, global_fn, taps_fn;
 };
 #define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>, taps_kernel<KC, RS>()}
-const RegEntry kRegTable[] = {RBGP_R(8, 4),  RBGP_R(18, 2), RBGP_R(36, 2), RBGP_R(72, 2),
-                              RBGP_R(18, 4), RBGP_R(36, 4), RBGP_R(72, 4),
-                              RBGP_R(18, 8), RBGP_R(36, 8), RBGP_R(72, 8)};
+const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
+                              RBGP_R(8, 4),  RBGP_R(18, 4),  RBGP_R(36, 4),  RBGP_R(72, 4),
+                              RBGP_R(8, 8),  RBGP_R(18, 8),  RBGP_R(36, 8),  RBGP_R(72, 8),
+                              RBGP_R(8, 16), RBGP_R(18, 16), RBGP_R(36, 16), RBGP_R(72, 16)};
 
 const RegEntry *find_reg(int KC, int RS) {
   for (const RegEntry &e : kRegTable)
@@ -610,7 +611,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     const int len = bf16 ? 32 * rbgp_bf16_blocks32(pl.KC) + (rbgp_bf16_tail16(pl.KC) ? 16 : 0) : pl.NO * 4;   // contraction steps, padded (padding -> row 0)
     std::vector<int32_t> rt(size_t(a3) * len, 0);
     for (int u3 = 0; u3 < a3; ++u3)
-      for (int kk = 0; kk < pl.KC; ++kk) {
+      for (int kk = 0; kk < pl.KCR; ++kk) {
         const int st = bf16 ? kk : rbgp_reg_step(m, kk);   // step of the contraction list at position kk
         const int v4 = st % c4, j3 = (st / c4) % d3, vv = st / (c4 * d3);
         rt[size_t(u3) * len + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;

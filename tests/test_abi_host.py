@@ -180,6 +180,10 @@ LAYOUT_SHAPES = [
     ((2, 4, 16, 1), (2, 1, 16, 1), (2, 1, 8, 1)),      # stage of 8 contraction steps
     ((4, 2, 4, 1), (4, 1, 4, 9), (2, 1, 2, 9)),        # stage of 18
     ((32, 4, 32, 1), (128, 1, 32, 1), (64, 1, 8, 1)),  # Table 2 of the paper
+    ((4, 2, 4, 2), (4, 2, 4, 3), (2, 2, 2, 3)),        # stage of 12 steps, padded to 18
+    ((2, 1, 8, 4), (2, 3, 8, 3), (1, 3, 2, 3)),        # stage of 18 from 3 x 2 x 3
+    ((4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9)),       # stage of 54, padded to 72
+    ((4, 4, 4, 1), (4, 5, 4, 1), (2, 5, 1, 1)),        # stage of 5, padded to 8
 ]
 
 

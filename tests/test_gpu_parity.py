@@ -178,8 +178,14 @@ FUZZ = [
     ((4, 2, 4, 2), (4, 1, 4, 9), (2, 1, 2, 9)),                    # KC=18, RS=4
     ((4, 2, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9)),                    # KC=72, RS=4
     ((4, 4, 4, 2), (4, 1, 4, 9), (2, 1, 2, 9)),                    # KC=18, RS=8
+    # stages whose length is padded to the next kernel size
+    ((4, 2, 4, 2), (4, 2, 4, 3), (2, 2, 2, 3)),                    # 12 steps in KC=18
+    ((2, 1, 8, 4), (2, 3, 8, 3), (1, 3, 2, 3)),                    # 18 = 3 x 2 x 3
+    ((4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9)),                   # 54 steps in KC=72
+    ((4, 4, 4, 1), (4, 5, 4, 1), (2, 5, 1, 1)),                    # 5 steps in KC=8
+    ((4, 1, 8, 3), (4, 3, 8, 3), (2, 3, 2, 3)),                    # R=3, 18 steps
 ]
-REG_COVERED = {5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15}               # must run on the register family
+REG_COVERED = set(range(5, 21))               # must run on the register family
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
@@ -227,6 +233,10 @@ CONV_CASES = [
     (wl.VGG19_CONV3_BF16, 128, 8, 8),     # bf16: 256 -> 256 channels, 8x8 pixels (128-column wave tiles)
     (replace(wl.VGG19_CONV3_BF16, name="conv3_bf16_4x4"), 33, 4, 4),     # bf16, 64-column tiles, ragged N
     (replace(wl.Workload("conv_small_bf16", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.BF16, 71, 72, 73, 1.0)), 3, 5, 8),
+    # stages padded to the next kernel size: 54 -> 72 steps, 9 -> 18 steps, 27 -> 36 steps with 16 rows per tile row
+    (wl.Workload("conv_pad54", (4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9), 0, wl.F32, 74, 75, 76, 1.0), 2, 4, 8),
+    (wl.Workload("conv_pad9_bf16", (4, 1, 2, 1), (4, 1, 2, 9), (2, 1, 1, 9), 0, wl.BF16, 77, 78, 79, 1.0), 3, 3, 12),
+    (wl.Workload("conv_pad27_r16", (4, 4, 4, 4), (4, 3, 4, 9), (2, 3, 1, 9), 0, wl.F32, 80, 81, 82, 1.0), 2, 4, 16),
 ]
 
 
@@ -323,7 +333,7 @@ def _random_shapes(count, seed):
         c_o = int(g.choice([1, 2, 3, 4, 8])) << lo
         a_i = int(g.choice([1, 2, 4])) << li
         c_i = int(g.choice([1, 2, 4])) << li
-        a_r, c_r = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 2, 3, 4]))
+        a_r, c_r = int(g.choice([1, 2, 3, 4, 8])), int(g.choice([1, 2, 3, 4]))
         a_b, c_b = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 3, 9, 9]))
         rows, cols = (a_o, a_r, a_i, a_b), (c_o, c_r, c_i, c_b)
         deg = (c_o >> lo, c_r, c_i >> li, c_b)
