@@ -16,6 +16,8 @@ meant to be checked against the paper by eye:
   order because every adjacency list ascends.
 * spmm_definition -- Section 5 "GPU Implementation": O = W_s x I, written out
   as the masked sum  O[m][n] = sum_k mask[m][k] * W[m][k] * I[k][n]  in float64.
+* transpose_order, spmm_transposed_definition, sddmm_definition -- the two
+  gradients of that product for a fixed mask (Section 6), as masked sums.
 
 Readings taken where the paper is silent (random source, vertex numbering of a
 lift, tie handling of the bound, degenerate factors) are the ones listed in
@@ -29,7 +31,9 @@ forest); numpy.kron; degree/density products; the paper's worked examples
 (512 edges stored as 22; two factorings giving (64,16) at 75 %); spectrum of a
 product; brute-force matmul with explicit zeros; scipy.signal.correlate2d for
 the lowered 3x3 convolution; numpy.matmul for all-complete
-factors; torch's bf16 conversion for the rounding routine.
+factors; torch's bf16 conversion for the rounding routine; torch autograd on
+the dense masked weight, the adjoint identity and (A (x) B)^T = A^T (x) B^T for
+the backward products.
 """
 from __future__ import annotations
 
@@ -263,7 +267,56 @@ def spmm_bruteforce_scalar(mask, W, I):
 
 
 # --------------------------------------------------------------------------
-# bf16 (round to nearest even), used to prepare identical inputs for both sides
+# Backward products of O = W_s x I with the mask held fixed (Section 6: the
+# masks are predefined and stay fixed during training).  The paper does not
+# spell these out; they are the two gradients of the product by the chain rule.
+# --------------------------------------------------------------------------
+def transpose_order(mask: np.ndarray) -> np.ndarray:
+    """perm[s] = t: the s-th kept value of W_s^T (canonical order of the
+    transposed mask, i.e. row by row of mask^T, ascending column) is the t-th
+    kept value of W_s (canonical order of mask)."""
+    M, K = mask.shape
+    index = np.full((M, K), -1, dtype=np.int64)
+    t = 0
+    for m in range(M):
+        for k in range(K):
+            if mask[m, k]:
+                index[m, k] = t
+                t += 1
+    perm = []
+    for k in range(K):
+        for m in range(M):
+            if mask[m, k]:
+                perm.append(index[m, k])
+    return np.array(perm, dtype=np.int64)
+
+
+def spmm_transposed_definition(mask: np.ndarray, W: np.ndarray, dO: np.ndarray) -> np.ndarray:
+    """dI[k][n] = sum_m mask[m][k] W[m][k] dO[m][n], float64 (gradient of the
+    product with respect to I)."""
+    M, K = mask.shape
+    dI = np.zeros((K, dO.shape[1]), dtype=np.float64)
+    dO64 = dO.astype(np.float64)
+    for m in range(M):
+        for k in range(K):
+            if mask[m, k]:
+                dI[k] += float(W[m, k]) * dO64[m]
+    return dI
+
+
+def sddmm_definition(mask: np.ndarray, dO: np.ndarray, I: np.ndarray) -> np.ndarray:
+    """dW[m][t] = sum_n dO[m][n] I[k][n] for the t-th kept column k of row m,
+    float64, data[M][rowdeg] in canonical order (gradient of the product with
+    respect to the kept values; nothing is computed off the mask)."""
+    cols = canonical_columns(mask)
+    dO64, I64 = dO.astype(np.float64), I.astype(np.float64)
+    dW = np.zeros(cols.shape, dtype=np.float64)
+    for m in range(mask.shape[0]):
+        for t, k in enumerate(cols[m]):
+            dW[m, t] = float(np.sum(dO64[m] * I64[k]))
+    return dW
+
+
 # --------------------------------------------------------------------------
 # convolution lowered to a matrix (Section 5 "GPU Implementation": the dense
 # operand is the batched input activations)

@@ -414,3 +414,75 @@ def test_im2col_3x3_against_scipy_correlation_and_by_hand():
     assert I[k, (1 * H + 1) * W + 0] == X[2, 1, 0, 1]
     assert I[9 * 0 + 3 * 2 + 0, (0 * H + 3) * W + 2] == 0.0          # below the last row
     assert I[9 * 0 + 3 * 1 + 0, (0 * H + 2) * W + 0] == 0.0          # left of the first column
+
+
+# ---------------------------------------------------------------- backward products
+def _small_backward_case(seed):
+    Bs, _ = orc.sample_factors((4, 2, 4, 2), (4, 2, 8, 3), (2, 2, 2, 3), seed)
+    mask = orc.kron_mask(Bs)
+    g = np.random.Generator(np.random.PCG64(seed))
+    rowdeg = int(mask[0].sum())
+    vals = g.standard_normal((mask.shape[0], rowdeg))
+    I = g.standard_normal((mask.shape[1], 13))
+    dO = g.standard_normal((mask.shape[0], 13))
+    return Bs, mask, vals, I, dO
+
+
+def test_backward_products_against_torch_autograd():
+    """Both gradients of sum(O * dO), O = (mask * W) I, from torch's autograd on the dense
+    masked weight (a library routine that knows nothing of the canonical order)."""
+    import torch
+    Bs, mask, vals, I, dO = _small_backward_case(5)
+    W = orc.scatter_values(mask, vals)
+    Wt = torch.tensor(W, dtype=torch.float64, requires_grad=True)
+    It = torch.tensor(I, dtype=torch.float64, requires_grad=True)
+    O = (Wt * torch.tensor(mask, dtype=torch.float64)) @ It
+    (O * torch.tensor(dO, dtype=torch.float64)).sum().backward()
+    dI = orc.spmm_transposed_definition(mask, W, dO)
+    assert np.allclose(dI, It.grad.numpy(), rtol=1e-12, atol=1e-12)
+    dW = orc.sddmm_definition(mask, dO, I)
+    dense = Wt.grad.numpy()
+    cols = orc.canonical_columns(mask)
+    for m in range(mask.shape[0]):
+        assert np.allclose(dW[m], dense[m, cols[m]], rtol=1e-12, atol=1e-12)
+    # and nothing off the mask is kept: the kept entries account for the whole masked gradient
+    assert np.isclose(np.abs(dW).sum(), np.abs(dense * mask).sum())
+
+
+def test_backward_data_product_is_the_adjoint():
+    """<W I, dO> = <I, W^T dO> for any I, dO."""
+    Bs, mask, vals, I, dO = _small_backward_case(6)
+    W = orc.scatter_values(mask, vals)
+    lhs = np.sum(orc.spmm_definition(mask, W, I) * dO)
+    rhs = np.sum(I * orc.spmm_transposed_definition(mask, W, dO))
+    assert math.isclose(lhs, rhs, rel_tol=1e-12)
+
+
+def test_transposed_mask_is_the_product_of_transposed_factors_and_order_is_a_bijection():
+    Bs, mask, vals, I, dO = _small_backward_case(7)
+    maskT = orc.kron_mask([B.T.copy() for B in Bs])
+    assert np.array_equal(maskT, mask.T)                 # (A (x) B)^T = A^T (x) B^T
+    perm = orc.transpose_order(mask)
+    assert np.array_equal(np.sort(perm), np.arange(vals.size))
+    # values carried over by the order rebuild the transposed dense matrix
+    valsT = vals.reshape(-1)[perm].reshape(maskT.shape[0], -1)
+    assert np.array_equal(orc.scatter_values(maskT, valsT), orc.scatter_values(mask, vals).T)
+    # so the forward definition on the transposed mask is the backward data product
+    W = orc.scatter_values(mask, vals)
+    assert np.allclose(orc.spmm_definition(maskT, orc.scatter_values(maskT, valsT), dO),
+                       orc.spmm_transposed_definition(mask, W, dO), rtol=1e-12, atol=1e-12)
+
+
+def test_sddmm_one_hot_inputs_pick_single_products():
+    """dO = e_m e_n^T and I = e_k e_n^T give dW = 1 at (m, k) when it is kept and 0 elsewhere."""
+    Bs, mask, vals, I, dO = _small_backward_case(8)
+    cols = orc.canonical_columns(mask)
+    m, t = 5, 7
+    k = cols[m, t]
+    dO1 = np.zeros_like(dO); dO1[m, 3] = 1.0
+    I1 = np.zeros_like(I); I1[k, 3] = 1.0
+    dW = orc.sddmm_definition(mask, dO1, I1)
+    expect = np.zeros_like(dW); expect[m, t] = 1.0
+    assert np.array_equal(dW, expect)
+    I1[k, 3] = 0.0; I1[k, 4] = 1.0                       # different column of the batch: no overlap
+    assert not orc.sddmm_definition(mask, dO1, I1).any()
