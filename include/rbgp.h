@@ -161,6 +161,48 @@ int rbgp_pack(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *host_valu
 int rbgp_pack_device(const rbgp_mask_t *mask, rbgp_dtype_t dtype, const void *dev_values,
                      void *dev_packed, void *hip_stream);
 
+/* Backward products for training with the mask held fixed (Section 6: the masks are
+ * predefined and do not change during training).  The paper times the forward product only;
+ * these are its two gradients, computed without ever forming a dense M x K matrix.
+ *
+ * rbgp_mask_transpose: the mask of W_s^T.  The transpose of a product of biadjacency matrices
+ * is the product of the transposed factors (Section 3), so it is again a four-factor mask
+ * (G_o^T, G_r^T, G_i^T, G_b^T; adjacency lists = the co-adjacency lists of `mask`, ascending)
+ * and every entry point above works on it with M and K exchanged; dI = W_s^T x dO is
+ * rbgp_spmm on it.  Host only, no GPU call.  *out is independent of `mask` and owned by the
+ * caller (rbgp_mask_free).  Errors: EINVAL, ENOMEM. */
+int rbgp_mask_transpose(const rbgp_mask_t *mask, rbgp_mask_t **out);
+
+/* out[s] (caller-owned host memory, nnz int32) = canonical index in `mask` (m * rowdeg + t) of
+ * the kept value that has canonical index s in the transposed mask (k * coldeg + position of m
+ * among the rows adjacent to column k, ascending). */
+int rbgp_transpose_order(const rbgp_mask_t *mask, int32_t *out);
+
+/* rbgp_pack / rbgp_pack_device for a mask made by rbgp_mask_transpose, with the values given in
+ * the canonical order of the ORIGINAL mask (nnz elements): the same weights can be packed for the
+ * forward product and for the backward data product without a reordering by the caller.
+ * EINVAL for a mask that was not made by rbgp_mask_transpose. */
+int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values,
+                         void *dev_packed, void *hip_stream);
+int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
+                                void *dev_packed, void *hip_stream);
+
+/* Gradient of the kept values: dW[m][t] = sum_n dO[m][n] * I[k][n] for the t-th kept column k
+ * of row m -- the product dO x I^T sampled on the mask, nothing off the mask is computed.
+ * dev_dO: M x N row-major, leading dimension ld_dO >= N; dev_I: K x N row-major, leading
+ * dimension ldI >= N; both in the dtype's input type (fp32, or bf16 bits), 4-byte aligned
+ * (bf16 with an odd leading dimension runs on the plain kernel).
+ * dev_dW: nnz fp32 in canonical order, overwritten (N == 0 stores zeros).  RBGP4 masks that the
+ * RBGP_KERNEL_MFMA_REG family covers run on MFMA kernels (unless the mask's kernel choice is
+ * RBGP_KERNEL_GENERIC), every other mask on a plain kernel.  Sums over n are taken in a fixed
+ * order: results are reproducible run to run.  Uses a partial-sum buffer that the library keeps
+ * with the mask and grows as needed (a growing call synchronises the device).  Errors: ESHAPE
+ * (sizes do not match the mask, leading dimension, alignment), EINVAL, EHIP.  Asynchronous on
+ * `hip_stream`. */
+int rbgp_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
+               const void *dev_dO, int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW,
+               void *hip_stream);
+
 /* O = W_s x I (Section 5, "GPU Implementation"; Algorithm 1 with C overwritten).
  * dev_I: K x N row-major with leading dimension ldI >= N elements (the lowered
  * convolution input, N = batch*H*W contiguous); dev_O: M x N row-major fp32 with

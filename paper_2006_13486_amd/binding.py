@@ -40,6 +40,12 @@ SIGNATURES = {
     "rbgp_pack_layout": (ctypes.c_int, [_vp, ctypes.c_int, _vp]),
     "rbgp_pack": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_pack_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
+    "rbgp_mask_transpose": (ctypes.c_int, [_vp, ctypes.POINTER(_vp)]),
+    "rbgp_transpose_order": (ctypes.c_int, [_vp, _vp]),
+    "rbgp_pack_transposed": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
+    "rbgp_pack_transposed_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
+    "rbgp_sddmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                  _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, _vp]),
     "rbgp_spmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                  _vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]),
     "rbgp_conv3x3": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, _vp, _vp, ctypes.c_int64, _vp]),
@@ -185,6 +191,40 @@ def rbgp_pack(mask: Mask, dtype: int, host_values: np.ndarray, dev_packed_ptr: i
 
 def rbgp_pack_device(mask: Mask, dtype: int, dev_values_ptr: int, dev_packed_ptr: int, stream: int = 0):
     _check(load().rbgp_pack_device(mask.handle, dtype, dev_values_ptr, dev_packed_ptr, stream), "rbgp_pack_device")
+
+
+def rbgp_mask_transpose(mask: Mask) -> Mask:
+    out = _vp()
+    _check(load().rbgp_mask_transpose(mask.handle, ctypes.byref(out)), "rbgp_mask_transpose")
+    return Mask(out)
+
+
+def rbgp_transpose_order(mask: Mask) -> np.ndarray:
+    out = np.empty(rbgp_mask_shape(mask)["nnz"], dtype=np.int32)
+    _check(load().rbgp_transpose_order(mask.handle, out.ctypes.data), "rbgp_transpose_order")
+    return out
+
+
+def rbgp_pack_transposed(mask_t: Mask, dtype: int, host_values: np.ndarray, dev_packed_ptr: int, stream: int = 0):
+    """host_values: the kept values in the ORIGINAL mask's canonical order."""
+    want = np.float32 if dtype == F32 else np.uint16
+    if host_values.dtype != want or not host_values.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"host_values must be C-contiguous {want}")
+    if host_values.size != rbgp_mask_shape(mask_t)["nnz"]:
+        raise ValueError("host_values must hold nnz elements")
+    _check(load().rbgp_pack_transposed(mask_t.handle, dtype, host_values.ctypes.data, dev_packed_ptr, stream),
+           "rbgp_pack_transposed")
+
+
+def rbgp_pack_transposed_device(mask_t: Mask, dtype: int, dev_values_ptr: int, dev_packed_ptr: int, stream: int = 0):
+    _check(load().rbgp_pack_transposed_device(mask_t.handle, dtype, dev_values_ptr, dev_packed_ptr, stream),
+           "rbgp_pack_transposed_device")
+
+
+def rbgp_sddmm(mask: Mask, dtype: int, M: int, K: int, N: int, dev_dO_ptr: int, ld_dO: int, dev_I_ptr: int, ldI: int,
+               dev_dW_ptr: int, stream: int = 0):
+    _check(load().rbgp_sddmm(mask.handle, dtype, M, K, N, dev_dO_ptr, ld_dO, dev_I_ptr, ldI, dev_dW_ptr, stream),
+           "rbgp_sddmm")
 
 
 def rbgp_conv3x3(mask: Mask, dtype: int, channels_out: int, channels_in: int, images: int, height: int, width: int,

@@ -49,9 +49,12 @@ struct rbgp_device_state {
   int device = -1;
   int32_t *adj[4] = {nullptr, nullptr, nullptr, nullptr};
   int32_t *rowoff = nullptr;             // [a_i][KS]: stage-relative I row of each contraction step
-  int32_t *perm[2 * RBGP_NUM_KERNELS] = {};  // pack permutation per kernel family and dtype
-  size_t perm_elems[2 * RBGP_NUM_KERNELS] = {};
+  // pack permutation per kernel family and dtype; second half: composed with the order of the
+  // original mask (transposed masks, values given in the original's canonical order)
+  int32_t *perm[4 * RBGP_NUM_KERNELS] = {};
+  size_t perm_elems[4 * RBGP_NUM_KERNELS] = {};
   void *reg_state = nullptr;             // tables of the register-streaming family
+  void *sddmm_state = nullptr;           // tables and partial sums of the weight-gradient kernels
   void *staging = nullptr;               // canonical values on their way through rbgp_pack
   size_t staging_bytes = 0;
   int tune[RBGP_NUM_TUNE] = {};            // RBGP_TUNE_* values, 0 = default
@@ -62,9 +65,10 @@ void rbgp_device_release(rbgp_device_state *dev) {
   for (int i = 0; i < 4; ++i)
     if (dev->adj[i]) (void)hipFree(dev->adj[i]);
   if (dev->rowoff) (void)hipFree(dev->rowoff);
-  for (int i = 0; i < 2 * RBGP_NUM_KERNELS; ++i)
-    if (dev->perm[i]) (void)hipFree(dev->perm[i]);
+  for (int32_t *t : dev->perm)
+    if (t) (void)hipFree(t);
   rbgp_reg_release(dev->reg_state);
+  rbgp_sddmm_release(dev->sddmm_state);
   if (dev->staging) (void)hipFree(dev->staging);
   delete dev;
 }
@@ -395,12 +399,15 @@ int ensure_device(const rbgp_mask *m) {
   return RBGP_OK;
 }
 
-int ensure_perm(const rbgp_mask *m, int kernel, bool bf16, int *slot) {
+int ensure_perm(const rbgp_mask *m, int kernel, bool bf16, bool original_order, int *slot) {
   rbgp_device_state *dev = m->dev;
-  *slot = 2 * kernel + (bf16 ? 1 : 0);
+  *slot = 2 * kernel + (bf16 ? 1 : 0) + (original_order ? 2 * RBGP_NUM_KERNELS : 0);
   if (dev->perm[*slot]) return RBGP_OK;
   std::vector<int32_t> perm;
   rbgp_build_pack_perm(m, kernel, bf16, perm);
+  if (original_order)
+    for (int32_t &s : perm)
+      if (s >= 0) s = m->from_original[size_t(s)];
   dev->perm_elems[*slot] = perm.size();
   return upload(perm, &dev->perm[*slot]);
 }
@@ -448,15 +455,16 @@ int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
   return RBGP_OK;
 }
 
-int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
-                     void *hip_stream) {
+static int pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *dev_values,
+                       void *dev_packed, void *hip_stream) {
   if (!m || !dev_values || !dev_packed) return RBGP_EINVAL;
   if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (original_order && m->from_original.empty()) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
   const int kernel = resolve_kernel(m, dtype);
   int slot;
-  rc = ensure_perm(m, kernel, dtype == RBGP_BF16_F32ACC, &slot);
+  rc = ensure_perm(m, kernel, dtype == RBGP_BF16_F32ACC, original_order, &slot);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t n = int64_t(m->dev->perm_elems[slot]);
@@ -471,10 +479,21 @@ int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_v
   return RBGP_OK;
 }
 
-int rbgp_pack(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
-              void *hip_stream) {
+int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
+                     void *hip_stream) {
+  return pack_device(m, dtype, false, dev_values, dev_packed, hip_stream);
+}
+
+int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
+                                void *dev_packed, void *hip_stream) {
+  return pack_device(mask_t, dtype, true, dev_values, dev_packed, hip_stream);
+}
+
+static int pack_host(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *host_values,
+                     void *dev_packed, void *hip_stream) {
   if (!m || !host_values || !dev_packed) return RBGP_EINVAL;
   if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (original_order && m->from_original.empty()) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
   rbgp_device_state *dev = m->dev;
@@ -488,10 +507,39 @@ int rbgp_pack(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values,
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   RBGP_HIP(hipMemcpyAsync(dev->staging, host_values, bytes, hipMemcpyHostToDevice, st));
-  rc = rbgp_pack_device(m, dtype, dev->staging, dev_packed, hip_stream);
+  rc = pack_device(m, dtype, original_order, dev->staging, dev_packed, hip_stream);
   if (rc) return rc;
   RBGP_HIP(hipStreamSynchronize(st));
   return RBGP_OK;
+}
+
+int rbgp_pack(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+              void *hip_stream) {
+  return pack_host(m, dtype, false, host_values, dev_packed, hip_stream);
+}
+
+int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+                         void *hip_stream) {
+  return pack_host(mask_t, dtype, true, host_values, dev_packed, hip_stream);
+}
+
+int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+               int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
+  if (!m) return RBGP_EINVAL;
+  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (M != m->M || K != m->K || N < 0 || ld_dO < N || ldI < N) return RBGP_ESHAPE;
+  if (!dev_dW || (N > 0 && (!dev_dO || !dev_I))) return RBGP_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dev_dO) | reinterpret_cast<uintptr_t>(dev_I) | reinterpret_cast<uintptr_t>(dev_dW)) & 3)
+    return RBGP_ESHAPE;
+  int rc = ensure_device(m);
+  if (rc) return rc;
+  rbgp_device_state *dev = m->dev;
+  const bool bf16 = dtype == RBGP_BF16_F32ACC;
+  // the MFMA kernel loads 16 bytes at dword-aligned addresses: bf16 rows must start on a dword
+  const bool aligned = !bf16 || (ld_dO % 2 == 0 && ldI % 2 == 0);
+  const bool use_mfma = m->kernel_choice != RBGP_KERNEL_GENERIC && rbgp_reg_covers(m) && aligned;
+  return rbgp_sddmm_launch(m, &dev->sddmm_state, dev->adj, use_mfma, bf16, N, dev_dO, ld_dO, dev_I, ldI, dev_dW,
+                           hip_stream);
 }
 
 int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,

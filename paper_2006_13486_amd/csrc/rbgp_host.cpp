@@ -490,6 +490,88 @@ int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t r
   return RBGP_OK;
 }
 
+// The s-th kept value of W_s^T (row k of the transpose, positions in the order of the
+// co-adjacency lists, i.e. ascending original row) is the kept value (row, t) of W_s, t being the
+// position of k's factor vertices in the adjacency lists of the row's factor vertices.
+static void transposed_order(const rbgp_mask *m, const std::vector<int32_t> coadj[4], int32_t *out) {
+  std::vector<int32_t> pos[4];   // pos[i][u * c + v] = position of v in adj[i][u], -1: not adjacent
+  for (int i = 0; i < 4; ++i) {
+    pos[i].assign(size_t(m->a[i]) * m->c[i], -1);
+    for (int u = 0; u < m->a[i]; ++u)
+      for (int j = 0; j < m->d[i]; ++j) pos[i][size_t(u) * m->c[i] + m->adj[i][size_t(u) * m->d[i] + j]] = j;
+  }
+  const int32_t *a = m->a, *c = m->c, *d = m->d, *e = m->e;
+  int64_t s = 0;
+  for (int v0 = 0; v0 < c[0]; ++v0)
+    for (int v1 = 0; v1 < c[1]; ++v1)
+      for (int v2 = 0; v2 < c[2]; ++v2)
+        for (int v3 = 0; v3 < c[3]; ++v3)
+          for (int j0 = 0; j0 < e[0]; ++j0)
+            for (int j1 = 0; j1 < e[1]; ++j1)
+              for (int j2 = 0; j2 < e[2]; ++j2)
+                for (int j3 = 0; j3 < e[3]; ++j3) {
+                  const int u0 = coadj[0][size_t(v0) * e[0] + j0], u1 = coadj[1][size_t(v1) * e[1] + j1],
+                            u2 = coadj[2][size_t(v2) * e[2] + j2], u3 = coadj[3][size_t(v3) * e[3] + j3];
+                  const int64_t row = ((int64_t(u0) * a[1] + u1) * a[2] + u2) * a[3] + u3;
+                  const int64_t t = ((int64_t(pos[0][size_t(u0) * c[0] + v0]) * d[1] + pos[1][size_t(u1) * c[1] + v1]) * d[2] +
+                                     pos[2][size_t(u2) * c[2] + v2]) * d[3] + pos[3][size_t(u3) * c[3] + v3];
+                  out[s++] = int32_t(row * m->rowdeg + t);
+                }
+}
+
+static void co_adjacency(const rbgp_mask *m, std::vector<int32_t> coadj[4]) {
+  for (int i = 0; i < 4; ++i) {
+    coadj[i].assign(size_t(m->c[i]) * m->e[i], 0);
+    std::vector<int> fill(size_t(m->c[i]), 0);
+    for (int u = 0; u < m->a[i]; ++u)       // ascending u: every list ascends
+      for (int j = 0; j < m->d[i]; ++j) {
+        const int v = m->adj[i][size_t(u) * m->d[i] + j];
+        coadj[i][size_t(v) * m->e[i] + fill[size_t(v)]++] = u;
+      }
+  }
+}
+
+int rbgp_transpose_order(const rbgp_mask_t *m, int32_t *out) {
+  if (!m || !out) return RBGP_EINVAL;
+  try {
+    std::vector<int32_t> coadj[4];
+    co_adjacency(m, coadj);
+    transposed_order(m, coadj, out);
+  } catch (const std::bad_alloc &) {
+    return RBGP_ENOMEM;
+  }
+  return RBGP_OK;
+}
+
+int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
+  if (!m || !out) return RBGP_EINVAL;
+  if (m->K * m->coldeg >= (int64_t(1) << 31)) return RBGP_EINVAL;
+  rbgp_mask *t = new (std::nothrow) rbgp_mask();
+  if (!t) return RBGP_ENOMEM;
+  try {
+    std::vector<int32_t> coadj[4];
+    co_adjacency(m, coadj);
+    for (int i = 0; i < 4; ++i) {
+      t->a[i] = m->c[i]; t->c[i] = m->a[i]; t->d[i] = m->e[i]; t->e[i] = m->d[i];
+      t->sigma1[i] = m->sigma1[i]; t->sigma2[i] = m->sigma2[i]; t->bound[i] = m->bound[i];   // singular values of B^T are B's
+      t->status[i] = m->status[i]; t->tries[i] = m->tries[i];
+    }
+    t->from_original.resize(size_t(m->nnz));
+    transposed_order(m, coadj, t->from_original.data());
+    for (int i = 0; i < 4; ++i) t->adj[i] = std::move(coadj[i]);
+    t->M = m->K; t->K = m->M; t->rowdeg = m->coldeg; t->coldeg = m->rowdeg; t->nnz = m->nnz;
+    t->kernel_choice = RBGP_KERNEL_AUTO;
+    t->dev = nullptr;
+    rbgp_plan_mfma(t);
+    rbgp_plan_reg(t);
+  } catch (const std::bad_alloc &) {
+    delete t;
+    return RBGP_ENOMEM;
+  }
+  *out = t;
+  return RBGP_OK;
+}
+
 void rbgp_mask_free(rbgp_mask_t *mask) {
   if (!mask) return;
   if (mask->dev) rbgp_device_release(mask->dev);

@@ -73,6 +73,8 @@ struct rbgp_mask {
   int status[4], tries[4];
   int64_t M, K, rowdeg, coldeg, nnz;
   int kernel_choice;                  // RBGP_KERNEL_*
+  std::vector<int32_t> from_original; // masks made by rbgp_mask_transpose: canonical index in the
+                                      //   original mask of every kept value, in this mask's order
   rbgp_mfma_plan plan;
   rbgp_reg_plan reg;
   rbgp_reg_clusters reg_clusters;     // clusters of reg.MG tile rows (when reg.ok)
@@ -107,6 +109,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
                     const void *I, int64_t ldI, float *O, int64_t ldO, void *stream,
                     const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
+// weight-gradient kernels (rbgp_sddmm.hip); use_mfma needs rbgp_reg_covers(m)
+int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
+                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream);
+void rbgp_sddmm_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);

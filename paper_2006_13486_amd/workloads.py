@@ -176,6 +176,14 @@ def activations(w: Workload, N: int | None = None) -> np.ndarray:
     return x
 
 
+def output_gradients(w: Workload, N: int | None = None) -> np.ndarray:
+    """dO[M][N] float32 ~ N(0, 1): the gradient arriving at the layer's output in a training
+    step (dense, signed), seeded from the activations' seed."""
+    N = w.N if N is None else N
+    g = np.random.Generator(np.random.PCG64(w.i_seed + 7919))
+    return g.standard_normal((w.M, N), dtype=np.float32)
+
+
 def conv_activations(w: Workload, images: int, height: int, width: int) -> np.ndarray:
     """X[channel][image][height][width] float32 ~ max(0, N(0,1)) for the fused 3x3
     convolution (channels = K / 9), seeded like `activations`."""

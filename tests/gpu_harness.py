@@ -72,6 +72,88 @@ def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
     return O_d.cpu().numpy()
 
 
+def _to_device(a, ld_pad):
+    """Host matrix -> device tensor with `ld_pad` extra columns (NaN / bf16 NaN bits) per row."""
+    import torch
+    rows, N = a.shape
+    if a.dtype == np.uint16:
+        host = np.full((rows, N + ld_pad), 0x7FC0, dtype=np.uint16)
+        host[:, :N] = a
+        return torch.from_numpy(host.view(np.int16)).to("cuda:0")
+    host = np.full((rows, N + ld_pad), np.nan, dtype=np.float32)
+    host[:, :N] = a
+    return torch.from_numpy(host).to("cuda:0")
+
+
+def library_spmm_transposed(w, vals_lib, dO_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0, tag=""):
+    """dI = W_s^T x dO through rbgp_mask_transpose / rbgp_pack_transposed / rbgp_spmm; vals_lib are
+    the kept values in the canonical order of the forward mask."""
+    import torch
+    N = dO_lib.shape[1]
+    print(f"[gpu] transposed {w.name} N={N} kernel={kernel} tune={tune} ld_pad={ld_pad} {tag}", flush=True)
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask_t = rb.rbgp_mask_transpose(mask)
+    if kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mask_t, kernel)
+    for knob, value in enumerate(tune or ()):
+        rb.rbgp_mask_tune(mask_t, knob, value)
+    stream = torch.cuda.current_stream().cuda_stream
+    packed = torch.zeros(max(rb.rbgp_packed_bytes(mask_t, w.dtype), 16), dtype=torch.uint8, device="cuda:0")
+    rb.rbgp_pack_transposed(mask_t, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
+    dO_d = _to_device(dO_lib, ld_pad)
+    if ld_pad:   # the padding columns are inside the leading dimension and may be read by the bf16 kernels
+        dO_d[:, N:] = 0
+    ld = N + ld_pad
+    dI_d = torch.full((w.K, max(ld, 1)), float("nan"), dtype=torch.float32, device="cuda:0")
+    rb.rbgp_spmm(mask_t, w.dtype, w.K, w.M, N, packed.data_ptr(), dO_d.data_ptr(), ld, dI_d.data_ptr(), ld, stream)
+    torch.cuda.synchronize()
+    out = dI_d.cpu().numpy()
+    if ld_pad:
+        assert np.all(np.isnan(out[:, N:])), "kernel wrote outside the N columns"
+    return out[:, :N], rb.rbgp_mask_kernel(mask_t, w.dtype)
+
+
+def library_sddmm(w, dO_lib, I_lib, kernel=rb.KERNEL_AUTO, ld_pad=0, calls=1, tag=""):
+    """dW[M][rowdeg] = (dO x I^T) on the mask through rbgp_sddmm."""
+    import torch
+    N = I_lib.shape[1]
+    print(f"[gpu] sddmm {w.name} N={N} kernel={kernel} ld_pad={ld_pad} {tag}", flush=True)
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    if kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mask, kernel)
+    stream = torch.cuda.current_stream().cuda_stream
+    dO_d, I_d = _to_device(dO_lib, ld_pad), _to_device(I_lib, ld_pad)
+    dW_d = torch.full((w.M * w.rowdeg + 64,), float("nan"), dtype=torch.float32, device="cuda:0")
+    for _ in range(calls):
+        rb.rbgp_sddmm(mask, w.dtype, w.M, w.K, N, dO_d.data_ptr(), N + ld_pad, I_d.data_ptr(), N + ld_pad,
+                      dW_d.data_ptr(), stream)
+    torch.cuda.synchronize()
+    out = dW_d.cpu().numpy()
+    assert np.all(np.isnan(out[w.M * w.rowdeg:])), "kernel wrote past the nnz values"
+    return out[:w.M * w.rowdeg].reshape(w.M, w.rowdeg)
+
+
+def oracle_backward(w, vals_f32, I_f32, dO_f32):
+    """(dI, its denominators sum_m |W||dO|, dW, its denominators sum_n |dO||I|) from the oracle."""
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = orc.kron_mask(Bs)
+    W = orc.scatter_values(mask, vals_f32)
+    maskT, WT = np.ascontiguousarray(mask.T), np.ascontiguousarray(W.T)
+    dI, dI_den = naive_c.spmm(maskT, WT, dO_f32), naive_c.spmm_abs(maskT, WT, dO_f32)
+    dW = orc.sddmm_definition(mask, dO_f32, I_f32)
+    dW_den = orc.sddmm_definition(mask, np.abs(dO_f32), np.abs(I_f32))
+    return dI, dI_den, dW, dW_den
+
+
+def backward_inputs(w, N=None):
+    """(vals, I, dO for the library; float32 views of the same bits for the oracle)."""
+    vals, I, dO = wl.kept_weights(w), wl.activations(w, N), wl.output_gradients(w, N)
+    if w.dtype == wl.BF16:
+        b = [wl.to_bf16_bits(x) for x in (vals, I, dO)]
+        return b, [wl.bf16_bits_as_f32(x) for x in b]
+    return [vals, I, dO], [vals, I, dO]
+
+
 def family_covers(w, kernel):
     """Whether a kernel family accepts this mask (host-side query, no GPU call)."""
     mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)

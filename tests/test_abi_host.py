@@ -209,3 +209,56 @@ def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
     assert np.all(layout[layout < 0] == -1)
     if rb.rbgp_mask_kernel(mask, dtype) == rb.KERNEL_GENERIC:
         assert np.array_equal(layout, np.arange(nnz, dtype=np.int32))     # canonical order itself
+
+
+# ---------------------------------------------------------------- transposed mask (backward data product)
+@pytest.mark.parametrize("shape", LAYOUT_SHAPES[:6] + LAYOUT_SHAPES[9:], ids=lambda s: "x".join(map(str, s[0])))
+def test_transposed_mask_and_order_match_the_oracle(shape):
+    rows, cols, deg = shape
+    seed = 5
+    mask = rb.rbgp_make_mask(rows, cols, deg, seed)
+    mask_t = rb.rbgp_mask_transpose(mask)
+    sh, sht = rb.rbgp_mask_shape(mask), rb.rbgp_mask_shape(mask_t)
+    assert (sht["M"], sht["K"], sht["rowdeg"], sht["coldeg"], sht["nnz"]) == \
+           (sh["K"], sh["M"], sh["coldeg"], sh["rowdeg"], sh["nnz"])
+    Bs, _ = orc.sample_factors(rows, cols, deg, seed)
+    dense = orc.kron_mask(Bs)
+    assert np.array_equal(rb.rbgp_mask_dense(mask_t), dense.T)
+    order = rb.rbgp_transpose_order(mask)
+    if dense.size <= 1 << 22:          # the oracle's order is a Python double loop
+        assert np.array_equal(order, orc.transpose_order(dense))
+    else:                              # large masks: a bijection that moves every value to its transposed place
+        assert np.array_equal(np.sort(order), np.arange(sh["nnz"]))
+        cols_f = rb.rbgp_mask_columns(mask).reshape(-1)
+        cols_t = rb.rbgp_mask_columns(mask_t).reshape(-1)
+        s = np.arange(sh["nnz"])
+        assert np.array_equal(cols_f[order], s // sht["rowdeg"])         # row of W^T = column of W
+        assert np.array_equal(cols_t, order // sh["rowdeg"])             # column of W^T = row of W
+    # spectrum and factor sizes of the transposed factors
+    for i in range(4):
+        f, ft = rb.rbgp_mask_factor(mask, i), rb.rbgp_mask_factor(mask_t, i)
+        assert (ft[0], ft[1]) == (f[1], f[0])
+        assert rb.rbgp_mask_spectrum(mask_t, i) == rb.rbgp_mask_spectrum(mask, i)
+    # transposing twice gives the mask back
+    assert np.array_equal(rb.rbgp_mask_dense(rb.rbgp_mask_transpose(mask_t)), dense)
+
+
+def test_pack_transposed_needs_a_transposed_mask():
+    w = wl.TINY
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    vals = np.zeros(w.M * w.rowdeg, dtype=np.float32)
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_pack_transposed(mask, rb.F32, vals, 256)
+    assert ei.value.code == rb.EINVAL
+
+
+def test_sddmm_argument_checks_need_no_gpu():
+    w = wl.TINY
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    lib = rb.load()
+    assert lib.rbgp_sddmm(mask.handle, 0, w.M + 1, w.K, 8, 256, 8, 256, 8, 256, None) == rb.ESHAPE
+    assert lib.rbgp_sddmm(mask.handle, 0, w.M, w.K, 8, 256, 4, 256, 8, 256, None) == rb.ESHAPE     # ld_dO < N
+    assert lib.rbgp_sddmm(mask.handle, 0, w.M, w.K, 8, 256, 8, 256, 8, None, None) == rb.EINVAL    # no output
+    assert lib.rbgp_sddmm(mask.handle, 0, w.M, w.K, 8, 258, 8, 256, 8, 256, None) == rb.ESHAPE     # misaligned
+    assert lib.rbgp_sddmm(mask.handle, 7, w.M, w.K, 8, 256, 8, 256, 8, 256, None) == rb.EINVAL
+    assert lib.rbgp_sddmm(None, 0, w.M, w.K, 8, 256, 8, 256, 8, 256, None) == rb.EINVAL

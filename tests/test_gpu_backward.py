@@ -1,0 +1,102 @@
+"""GPU parity of the backward products (gradients of O = W_s x I for a fixed mask, Section 6)
+against the CPU oracle, through the C ABI: dI = W_s^T x dO on the transposed mask, and
+dW = (dO x I^T) sampled on the mask."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import rbgp_oracle as orc
+from paper_2006_13486_amd import binding as rb
+from paper_2006_13486_amd import workloads as wl
+from tests import gpu_harness as gh
+from tests.test_gpu_parity import FUZZ
+
+pytestmark = pytest.mark.gpu
+
+GEN, MFMA, REG = rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG
+
+
+def _check_backward(w, N=None, ld_pad=0, kernels=(rb.KERNEL_AUTO,), data=True, weights=True):
+    lib, f32 = gh.backward_inputs(w, N)
+    dI_ref, dI_den, dW_ref, dW_den = gh.oracle_backward(w, *f32)
+    for kernel in kernels:
+        if data:
+            dI, used = gh.library_spmm_transposed(w, lib[0], lib[2], kernel=kernel, ld_pad=ld_pad)
+            err = orc.normalised_error(dI, dI_ref, dI_den)
+            print(f"[gpu]   dI kernel {used} normalised error {err:.3e}", flush=True)
+            assert err <= gh.TOL[w.dtype], ("dI", w.name, kernel, err)
+        if weights:
+            dW = gh.library_sddmm(w, lib[2], lib[1], kernel=kernel, ld_pad=ld_pad)
+            err = orc.normalised_error(dW, dW_ref, dW_den)
+            print(f"[gpu]   dW normalised error {err:.3e}", flush=True)
+            assert err <= gh.TOL[w.dtype], ("dW", w.name, kernel, err)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("idx", range(len(FUZZ)))
+def test_backward_products_across_the_kernel_table(idx, dtype):
+    rows, cols, deg = FUZZ[idx]
+    w = wl.Workload(f"bwd{idx}_{dtype}", rows, cols, deg, 328, dtype, 400 + idx, 500 + idx, 600 + idx, 1.0)
+    _check_backward(w, kernels=(rb.KERNEL_AUTO, GEN))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("N,ld_pad", [(1, 7), (15, 1), (16, 0), (33, 3), (200, 8), (1000, 0), (2049, 15)])
+def test_backward_products_ragged_batch(N, ld_pad, dtype):
+    """Batch sizes around the kernels' column steps (16 / 32 per iteration, ranges of the split),
+    odd leading dimensions included (bf16 with an odd one runs on the plain kernel)."""
+    w = wl.Workload(f"bwd_ragged_{dtype}", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), N, dtype, 41, 42, 43, 1.0)
+    _check_backward(w, ld_pad=ld_pad)
+
+
+@pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16], ids=lambda w: w.name)
+def test_backward_products_config_full_size(w):
+    _check_backward(w)
+
+
+def test_weight_gradient_wrn_full_batch():
+    """131072 columns: the batch is cut into many ranges whose partial sums are added in a second kernel."""
+    _check_backward(wl.WRN_G1, data=False)
+
+
+def test_backward_data_product_wrn_sampled_batch():
+    _check_backward(replace(wl.WRN_G1, N=4096), weights=False)
+
+
+def test_weight_gradient_repeated_calls_and_growing_batch():
+    """The partial-sum buffer is kept with the mask: a small batch first, then a larger one, then the
+    small one again, every result checked."""
+    mask_w = wl.Workload("bwd_grow", (4, 2, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9), 0, wl.F32, 51, 52, 53, 1.0)
+    for N in (96, 4000, 96):
+        _check_backward(replace(mask_w, N=N), data=False)
+
+
+def test_weight_gradient_empty_batch_stores_zeros():
+    w = replace(wl.TINY, N=0)
+    dW = gh.library_sddmm(w, np.zeros((w.M, 0), np.float32), np.zeros((w.K, 0), np.float32))
+    assert not dW.any()
+
+
+@pytest.mark.parametrize("kernel", [rb.KERNEL_AUTO, GEN])
+def test_weight_gradient_one_hot_inputs_are_exact(kernel):
+    """dO = ones in column n of every row, I = distinct powers of two in the same column: dW repeats
+    the value of I at each kept column exactly."""
+    w = replace(wl.TINY, N=40)
+    dO = np.zeros((w.M, w.N), np.float32); dO[:, 17] = 1.0
+    I = np.zeros((w.K, w.N), np.float32); I[:, 17] = np.ldexp(1.0, np.arange(w.K) % 24 - 12).astype(np.float32)
+    I[:, 3] = 5.0                                   # a column that dO does not touch
+    dW = gh.library_sddmm(w, dO, I, kernel=kernel)
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    cols = rb.rbgp_mask_columns(mask).reshape(w.M, w.rowdeg)
+    assert np.array_equal(dW, I[cols, 17])
+
+
+def test_masks_outside_rbgp4_roles_take_the_plain_kernels():
+    w = wl.Workload("bwd_sparse_gr", (4, 4, 4, 2), (4, 4, 4, 2), (2, 2, 2, 2), 100, wl.F32, 1, 2, 3, 1.0)
+    _check_backward(w)
+
+
+def test_weight_gradient_bf16_odd_leading_dimension():
+    w = wl.Workload("bwd_odd_ld", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 77, wl.BF16, 44, 45, 46, 1.0)
+    _check_backward(w, data=False)
