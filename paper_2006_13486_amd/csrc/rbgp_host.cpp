@@ -158,14 +158,21 @@ void rbgp_plan_mfma(rbgp_mask *m) {
 void rbgp_plan_reg(rbgp_mask *m) {
   rbgp_reg_plan p;
   const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
-  p.R = m->a[1] * m->a[3];
+  p.A2 = m->a[1];
+  while (p.A2 > 1 && p.A2 * m->a[3] > 16) {   // largest divisor of |G_r.U| that fits the MFMA group
+    --p.A2;
+    while (m->a[1] % p.A2) --p.A2;
+  }
+  p.fold = m->a[1] / p.A2;
+  p.TR = m->a[0] * p.fold;
+  p.R = p.A2 * m->a[3];
   p.RB = (p.R + 3) / 4;
   p.KT = m->c[1] * m->d[2] * m->c[3];
   const int per_v = m->d[2] * m->c[3];
   p.VC = 0;
   for (int vc = m->c[1]; vc >= 1; --vc)
     if (m->c[1] % vc == 0 && vc * per_v <= 72) { p.VC = vc; break; }
-  p.ok = roles && p.VC > 0 && p.R <= 16;
+  p.ok = roles && p.VC > 0 && p.R <= 16;   // (R > 16 only when |G_b.U| alone exceeds 16)
   if (p.ok) {
     p.KCR = p.VC * per_v;
     p.KC = p.KCR <= 8 ? 8 : p.KCR <= 18 ? 18 : p.KCR <= 36 ? 36 : 72;
@@ -177,9 +184,9 @@ void rbgp_plan_reg(rbgp_mask *m) {
     p.NO = (p.KC + 3) / 4;
     p.NQ = (p.NO + 3) / 4;
     // one more all-zero fragment ends the buffer
-    p.packed_elems = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * p.NQ * 4 * p.RS * 4;
+    p.packed_elems = (int64_t(p.TR) * m->d[0] * p.NSTG * m->a[2] + 1) * p.NQ * 4 * p.RS * 4;
     const int nq_bf16 = rbgp_bf16_blocks32(p.KC) + (rbgp_bf16_tail16(p.KC) ? 1 : 0);
-    p.packed_elems_bf16 = (int64_t(m->a[0]) * m->d[0] * p.NSTG * m->a[2] + 1) * nq_bf16 * 4 * p.RS * 8;
+    p.packed_elems_bf16 = (int64_t(p.TR) * m->d[0] * p.NSTG * m->a[2] + 1) * nq_bf16 * 4 * p.RS * 8;
   }
   m->reg = p;
   if (p.ok) rbgp_reg_cluster(m, p.MG, &m->reg_clusters);
@@ -191,13 +198,13 @@ void rbgp_plan_reg(rbgp_mask *m) {
 // list for every cluster the stages it walks.
 void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
   const rbgp_reg_plan &pl = m->reg;
-  const int a1 = m->a[0], c1 = m->c[0], d1 = m->d[0];
+  const int a1 = pl.TR, c1 = m->c[0], d1 = m->d[0];   // tile rows; tile row u has G_o's row u / fold
   const int ncl = (a1 + U - 1) / U;
   std::vector<int32_t> members(size_t(ncl) * U, -1);
   std::vector<char> used(a1, 0);
   std::vector<std::vector<char>> has(a1, std::vector<char>(c1, 0));
   for (int u = 0; u < a1; ++u)
-    for (int j = 0; j < d1; ++j) has[u][m->adj[0][size_t(u) * d1 + j]] = 1;
+    for (int j = 0; j < d1; ++j) has[u][m->adj[0][size_t(u / pl.fold) * d1 + j]] = 1;
   for (int c = 0; c < ncl; ++c) {
     std::vector<char> uni(c1, 0);
     for (int k = 0; k < U; ++k) {
@@ -306,7 +313,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
           const int u1 = members[size_t(c) * U + k];
           if (u1 < 0 || !has[u1][v1]) continue;
           int j1 = 0;
-          while (m->adj[0][size_t(u1) * d1 + j1] != v1) ++j1;
+          while (m->adj[0][size_t(u1 / pl.fold) * d1 + j1] != v1) ++j1;
           stages[(size_t(c) * (1 + U) + 1 + k) * 64 + st] = j1 * pl.NSTG + sg;
         }
       }
@@ -343,7 +350,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
   if (kernel == RBGP_KERNEL_MFMA_REG && bf16) {
     const rbgp_reg_plan &p = m->reg;
-    const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
+    const int a1 = p.TR, a2 = p.A2, a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
     const int nk32 = rbgp_bf16_blocks32(p.KC);
     const int nq = nk32 + (rbgp_bf16_tail16(p.KC) ? 1 : 0);
     perm.assign(size_t(p.packed_elems_bf16), -1);
@@ -368,7 +375,7 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
   }
   if (kernel == RBGP_KERNEL_MFMA_REG) {
     const rbgp_reg_plan &p = m->reg;
-    const int a1 = m->a[0], a2 = m->a[1], a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
+    const int a1 = p.TR, a2 = p.A2, a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];
     perm.assign(size_t(p.packed_elems), -1);
     size_t pos = 0;
     for (int u1 = 0; u1 < a1; ++u1)

@@ -29,7 +29,12 @@ struct rbgp_mfma_plan {
 // Shape of the register-streaming MFMA kernels (see rbgp_mfma_reg.hip).
 struct rbgp_reg_plan {
   bool ok = false;
-  int R = 0, RB = 0;
+  int fold = 1;  // G_r being complete, G_o (x) G_r = (G_o with every row repeated `fold` times) (x)
+                 //   (a complete graph on |G_r.U| / fold rows): when |G_r.U| * |G_b.U| exceeds the 16 rows
+                 //   of an MFMA group, `fold` of G_r's rows move into the tile-row index
+  int TR = 0;    // tile rows: |G_o.U| * fold; tile row u has the tiles of G_o's row u / fold
+  int A2 = 0;    // rows of G_r inside a tile row: |G_r.U| / fold
+  int R = 0, RB = 0;   // rows of a tile row that share one column set: A2 * |G_b.U|
   int KT = 0;    // contraction length of one group in one tile: |G_r.V| * d_i * |G_b.V|
   int VC = 0;    // G_r columns per stage
   int KCR = 0;   // contraction length per stage: VC * d_i * |G_b.V|

@@ -577,7 +577,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (tc != 0 && tc != 64 && tc != 128) return RBGP_EUNSUPPORTED;
     if (tc)
       CW = tc;
-    else if (ok128 && int64_t((m->a[0] + pl.MG - 1) / pl.MG) * m->a[2] * ((N + 127) / 128) >= 512)
+    else if (ok128 && int64_t((pl.TR + pl.MG - 1) / pl.MG) * m->a[2] * ((N + 127) / 128) >= 512)
       CW = 128;
     if (!(CW == 128 ? ok128 : ok64)) return RBGP_ESHAPE;
   }
@@ -638,7 +638,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       if (tg != 1 && tg != 2 && tg != 4) return RBGP_EUNSUPPORTED;   // (too long a stage list is rejected below)
       G = tg;
     }
-    const int64_t ncl = (m->a[0] + G * pl.MG - 1) / (G * pl.MG);
+    const int64_t ncl = (pl.TR + G * pl.MG - 1) / (G * pl.MG);
     if (ts) {
       if (ts != 1 && ts != 2 && ts != 4) return RBGP_EUNSUPPORTED;
       lgS = ts == 4 ? 2 : ts == 2 ? 1 : 0;
@@ -709,9 +709,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     rp.last_row = int(m->K / 9 - 1);
     rp.src_rows = pl.SRC / 9;
   }
-  rp.a2 = m->a[1]; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
+  rp.a2 = pl.A2; rp.a3 = m->a[2]; rp.a4 = m->a[3]; rp.R = pl.R;
   rp.fpm = fpm;
-  rp.tm = m->a[1] * m->a[2] * m->a[3];
+  rp.tm = pl.A2 * m->a[2] * m->a[3];
   for (int r = 0; r < 16; ++r) rp.rowofs[r] = (r / m->a[3]) * m->a[2] * m->a[3] + r % m->a[3];
   rp.ntiles = int(ntiles);
   rp.lgS = lgS;

@@ -351,7 +351,7 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   p.out = nsplit > 1 ? st->partial : dW;
   p.units = st->units; p.stages = st->stages; p.members = st->members; p.rowtab = st->rowtab;
   p.N = N; p.ld_dO = ld_dO; p.ldI = ldI; p.nnz = nnz; p.chunk = chunk;
-  p.a2 = m->a[1]; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
+  p.a2 = pl.A2; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
   p.lgRS = 0;
   while ((1 << p.lgRS) < pl.RS) ++p.lgRS;
   p.MG = pl.MG; p.KCR = pl.KCR; p.rowdeg = int(m->rowdeg);

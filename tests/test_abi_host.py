@@ -184,6 +184,8 @@ LAYOUT_SHAPES = [
     ((2, 1, 8, 4), (2, 3, 8, 3), (1, 3, 2, 3)),        # stage of 18 from 3 x 2 x 3
     ((4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9)),       # stage of 54, padded to 72
     ((4, 4, 4, 1), (4, 5, 4, 1), (2, 5, 1, 1)),        # stage of 5, padded to 8
+    ((2, 8, 4, 3), (2, 2, 4, 9), (1, 2, 2, 9)),        # R = 24: two of G_r's rows move into the tile-row index
+    ((4, 4, 2, 9), (4, 4, 4, 2), (2, 4, 2, 2)),        # R = 36 (a transposed 3x3 layer): all four of them do
 ]
 
 

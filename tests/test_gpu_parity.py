@@ -184,8 +184,11 @@ FUZZ = [
     ((4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9)),                   # 54 steps in KC=72
     ((4, 4, 4, 1), (4, 5, 4, 1), (2, 5, 1, 1)),                    # 5 steps in KC=8
     ((4, 1, 8, 3), (4, 3, 8, 3), (2, 3, 2, 3)),                    # R=3, 18 steps
+    # more than 16 rows per tile row: rows of G_r move into the tile-row index
+    ((2, 8, 4, 3), (2, 2, 4, 9), (1, 2, 2, 9)),                    # R=24 -> 2 x 12
+    ((4, 4, 2, 9), (4, 4, 4, 2), (2, 4, 2, 2)),                    # R=36 -> 4 x 9 (a transposed 3x3 layer)
 ]
-REG_COVERED = set(range(5, 21))               # must run on the register family
+REG_COVERED = set(range(5, 23))               # must run on the register family
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
@@ -334,7 +337,7 @@ def _random_shapes(count, seed):
         a_i = int(g.choice([1, 2, 4])) << li
         c_i = int(g.choice([1, 2, 4])) << li
         a_r, c_r = int(g.choice([1, 2, 3, 4, 8])), int(g.choice([1, 2, 3, 4]))
-        a_b, c_b = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 3, 9, 9]))
+        a_b, c_b = int(g.choice([1, 2, 3, 4, 24])), int(g.choice([1, 3, 9, 9]))
         rows, cols = (a_o, a_r, a_i, a_b), (c_o, c_r, c_i, c_b)
         deg = (c_o >> lo, c_r, c_i >> li, c_b)
         if a_o * a_r * a_i * a_b > 2048 or c_o * c_r * c_i * c_b > 4096:
