@@ -229,6 +229,81 @@ def fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream, check, steps=
     return res
 
 
+def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream, check, steps=1000, warmup=300,
+                     only=None):
+    """The two gradients of the product for a fixed mask (Section 6), timed on the same workload:
+    dI = W_s^T x dO (rbgp_spmm on the transposed mask) and dW = (dO x I^T) on the mask (rbgp_sddmm).
+    Reported beside the headline number; same flop count 2 * nnz * N each."""
+    bf16 = w.dtype == wl.BF16
+    dO = wl.output_gradients(w)
+    if bf16:
+        dO_lib = wl.to_bf16_bits(dO)
+        dO_f32 = wl.bf16_bits_as_f32(dO_lib)
+    else:
+        dO_lib = dO_f32 = dO
+    mask_t = rb.rbgp_mask_transpose(mask)
+    packed_t = torch.zeros(rb.rbgp_packed_bytes(mask_t, w.dtype), dtype=torch.uint8, device=dev)
+    rb.rbgp_pack_transposed(mask_t, w.dtype, np.ascontiguousarray(vals_lib), packed_t.data_ptr(), stream)
+    set_bytes = (w.M + w.K) * w.N * (w.in_bytes + 4)
+    nsets = max(2, min(16, -(-512 * 2**20 // set_bytes)))
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16) if bf16 else a).to(dev)
+    dOs = [as_dev(dO_lib) for _ in range(nsets)]
+    Is = [as_dev(I_lib) for _ in range(nsets)]
+    dIs = [torch.empty((w.K, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+    dWs = [torch.empty(w.nnz, dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+    def data_step(i):
+        j = i % nsets
+        rb.rbgp_spmm(mask_t, w.dtype, w.K, w.M, w.N, packed_t.data_ptr(), dOs[j].data_ptr(), w.N,
+                     dIs[j].data_ptr(), w.N, stream)
+
+    def weight_step(i):
+        j = i % nsets
+        rb.rbgp_sddmm(mask, w.dtype, w.M, w.K, w.N, dOs[j].data_ptr(), w.N, Is[j].data_ptr(), w.N,
+                      dWs[j].data_ptr(), stream)
+
+    out = {}
+    for name, step, abytes in (
+            ("backward_data", data_step, w.M * w.N * w.in_bytes + w.K * w.N * 4 + w.nnz * w.in_bytes),
+            ("weight_gradient", weight_step, (w.M + w.K) * w.N * w.in_bytes + w.nnz * 4)):
+        if only and name != only:
+            continue
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for i in range(steps):
+            step(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / steps
+        tf = w.flops / (ms * 1e-3) / 1e12
+        out[name] = {"entry_point": "rbgp_spmm on rbgp_mask_transpose" if name == "backward_data" else "rbgp_sddmm",
+                     "ms": ms, "value": tf, "unit": "TFLOP/s", "frac_of_fp32_mfma_peak": tf / PEAK_F32_TFLOPS,
+                     "algorithmic_bytes": abytes, "algorithmic_gbs": abytes / (ms * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": abytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "steps": steps, "buffer_sets": nsets}
+    if check:
+        from oracle import naive_c
+        from oracle import rbgp_oracle as orc
+        Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+        dense_mask = orc.kron_mask(Bs)
+        Wd = orc.scatter_values(dense_mask, vals_f32)
+        if "backward_data" in out:       # sampled columns of dI
+            ncols = int(min(w.N, max(64, (1 << 31) // max(w.nnz, 1))))
+            mT, WT = np.ascontiguousarray(dense_mask.T), np.ascontiguousarray(Wd.T)
+            sub = np.ascontiguousarray(dO_f32[:, :ncols])
+            ref, den = naive_c.spmm(mT, WT, sub), naive_c.spmm_abs(mT, WT, sub)
+            out["backward_data"]["parity_err"] = orc.normalised_error(dIs[0].cpu().numpy()[:, :ncols], ref, den)
+        if "weight_gradient" in out:     # sampled rows of dW (every one needs the whole batch)
+            rows = np.unique(np.linspace(0, w.M - 1, 48).astype(np.int64))
+            ref = orc.sddmm_definition(dense_mask[rows], dO_f32[rows], I_f32)
+            den = orc.sddmm_definition(dense_mask[rows], np.abs(dO_f32[rows]), np.abs(I_f32))
+            got = dWs[0].cpu().numpy().reshape(w.M, w.rowdeg)[rows]
+            out["weight_gradient"]["parity_err"] = orc.normalised_error(got, ref, den)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -243,6 +318,9 @@ def main():
     ap.add_argument("--fused-conv", action="store_true",
                     help="time rbgp_conv3x3 (3x3 convolution with the lowering folded into the loads, fp32) on the "
                          "workload's layer instead of rbgp_spmm on the lowered input")
+    ap.add_argument("--backward", default="", choices=["", "backward_data", "weight_gradient", "both"],
+                    help="time the backward products of the workload (dI = W^T dO, dW = dO I^T on the mask) "
+                         "instead of the forward product; prints one JSON line with them")
     ap.add_argument("--sweep", default="", choices=["", "table2", "table3", "vgg19"],
                     help="time a family of workloads instead of the headline one: the paper's 4096^3 SDMM of "
                          "Table 2 / Table 3, or the 16 VGG19 conv layers; prints one JSON line with all cases")
@@ -293,6 +371,13 @@ def main():
     packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device=dev)
     rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals_lib), packed.data_ptr(), stream)
 
+    if args.backward:
+        res = backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream,
+                               check=not args.no_cpu_baseline, steps=args.steps, warmup=args.warmup,
+                               only=None if args.backward == "both" else args.backward)
+        print(json.dumps({"workload": w.name, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+                          "steps": args.steps, "warmup": args.warmup, **res}))
+        return
     algorithmic_bytes = w.algorithmic_bytes
     if args.fused_conv:
         if w.name not in wl.CONV_GEOMETRY:
@@ -374,6 +459,9 @@ def main():
     if not args.fused_conv and w.name in wl.CONV_GEOMETRY:
         out["fused_conv3x3"] = fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream,
                                                check=not args.no_cpu_baseline)
+    if not args.fused_conv and args.workload == "conv5":
+        out["backward"] = backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream,
+                                           check=not args.no_cpu_baseline)
     print(json.dumps(out))
 
 

@@ -2,20 +2,29 @@
 // fixed during training):  dW[m][t] = sum_n dO[m][n] * I[k][n]  for the t-th kept column k of
 // row m -- the dense product dO x I^T sampled on the mask.
 //
-// MFMA kernel (RBGP4 masks covered by the register-streaming family).  The work unit is what the
-// forward kernel calls a stage, seen from the other side: for one cluster of tile rows, one
-// nonzero tile of G_o, VC columns of G_r and one G_i vertex u_i, the kept values form a dense
-// block of (16 weight rows = the cluster's MG tile rows x RS rows) x (KCR contraction steps), and
-// that block is the product of 16 rows of dO with KCR rows of I, contracted over the batch
-// columns n.  One wave owns a unit and a range of columns: a lane loads 16 bytes of "its" row
-// (row lane % 16 of the 16 dO rows, and of each block of 16 I rows) at column offset
-// 4 (8 for bf16) * (lane / 16), which is exactly the operand layout of v_mfma_f32_16x16x4_f32
-// (four of them per load, one per loaded column) / v_mfma_f32_16x16x32_bf16 (one per load);
-// the accumulators hold the 16 x 16 blocks of dW.  Rows of the unit that do not exist (a member
-// without the tile, R < RS, KCR not a multiple of 16) load some valid row instead and their
-// results are dropped: an output element depends on its own two rows only.
-// The batch is cut into `nsplit` ranges so that the chip is filled; each range writes its own
-// partial dW and a second kernel adds the partials in a fixed order (reproducible sums).
+// MFMA kernel (RBGP4 masks covered by the register-streaming family).  The work unit is a nonzero
+// tile column seen from the weights' side: for one column v_o of G_o, VC columns of G_r (a
+// "stage" of the forward kernels) and one G_i vertex u_i, every tile row that has the tile (the
+// co-adjacency list of v_o, e_o entries) owns a dense block of R kept rows x KCR contraction
+// steps, and all these blocks together are ONE dense product: (e_o * R rows of dO) x (KCR rows
+// of I)^T, contracted over the batch columns n.  Rows are grouped 16 at a time (MG = 16 / RS
+// tile rows x RS rows, as in the forward kernels' MFMA groups), steps 16 at a time; a wave owns
+// RB row groups x NB step groups (all of the stage) and a range of columns, so that every loaded
+// row of I is used for RB * 16 rows of dO and vice versa.
+// The operand layout of v_mfma_f32_16x16x4_f32 (four of them per 16-byte load, one per loaded
+// column) and of v_mfma_f32_16x16x32_bf16 (one per load) is: lane l holds row l % 16 of the 16
+// rows at column offset 4 (8 for bf16) * (l / 16).  Loading in that layout makes every group of
+// four consecutive lanes touch four cache lines and runs at a third of the L1 rate, so the loads
+// use a layout with 64 contiguous bytes per four lanes and the data passes through a wave-private
+// LDS tile (one 16-byte write and one 16-byte read per lane and load) into the operand layout.
+// (ds_bpermute, one per register, does the same without memory but costs 16 cycles each, which
+// made the LDS crossbar the bound.)  The accumulators hold the 16 x 16 blocks of dW.  Rows that
+// do not exist (list shorter than the row groups, R < RS, KCR not a multiple of 16) load some
+// valid row instead and their results are dropped: an output element depends on its own two
+// rows only.
+// The batch is cut into ranges so that the chip is filled: the four waves of a workgroup take
+// consecutive ranges and add their accumulators through LDS; several workgroups per unit write
+// partial dW's and a second kernel adds those in a fixed order (reproducible sums).
 //
 // Plain kernel (any four-factor mask): one wave per kept value, lanes stride over n.
 #include <hip/hip_runtime.h>
@@ -44,16 +53,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef f32x4 f32x4_u __attribute__((aligned(4)));
 typedef bf16x8 bf16x8_u __attribute__((aligned(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct SddmmParams {
   const void *dO, *I;
-  float *out;               // [nsplit][nnz] partial sums (dW itself when nsplit == 1)
-  const int32_t *units;     // [nunits] cluster * 64 + stage of the cluster's stage list
-  const int32_t *stages;    // [ncl][1 + MG][64], as for the forward kernels
-  const int32_t *members;   // [ncl][MG]
+  float *out;               // [workgroups per unit][nnz] partial sums (dW itself when there is one)
+  const int32_t *colrows;   // [c_o][EO]: tile rows that have tile column v_o, ascending
+  const int32_t *colpos;    // [c_o][EO]: position of v_o in that tile row's adjacency list
   const int32_t *rowtab;    // [a_i][16 * NB]: stage-relative row of I of contraction step kk (padding -> 0)
   int64_t N, ld_dO, ldI, nnz;
   int64_t chunk;            // columns per range (a multiple of the columns per iteration)
+  int EO, RBG;              // tile rows per tile column; groups of RB row groups per unit
+  int NSTG, stage_rows;     // stages per tile; rows of I between the bases of consecutive stages (VC * c_i * c_b)
+  int tile_rows;            // rows of I per tile column (c_r * c_i * c_b)
   int a2, a3, a4, R, lgRS, MG, KCR, rowdeg;
 };
 
@@ -63,6 +75,7 @@ template <>
 struct Operand<false> {
   typedef f32x4 reg;
   static constexpr int CPL = 4;   // columns per lane and load
+  static __device__ __forceinline__ reg zero() { return reg{0.f, 0.f, 0.f, 0.f}; }
   static __device__ __forceinline__ reg load(const void *base, int64_t elem) {
     return *reinterpret_cast<const f32x4_u *>(static_cast<const float *>(base) + elem);
   }
@@ -82,6 +95,7 @@ template <>
 struct Operand<true> {
   typedef bf16x8 reg;
   static constexpr int CPL = 8;
+  static __device__ __forceinline__ reg zero() { return reg{0, 0, 0, 0, 0, 0, 0, 0}; }
   static __device__ __forceinline__ reg load(const void *base, int64_t elem) {
     return *reinterpret_cast<const bf16x8_u *>(static_cast<const uint16_t *>(base) + elem);
   }
@@ -97,78 +111,156 @@ struct Operand<true> {
   }
 };
 
-// NB: blocks of 16 contraction steps per stage (KCR <= 16 * NB)
-template <int NB, bool BF16>
-__global__ __launch_bounds__(64) void sddmm_reg(SddmmParams p) {
+// RB: groups of 16 rows of dO per wave; NB: groups of 16 contraction steps per stage (KCR <= 16 * NB).
+// grid.x = ((v_o * NSTG + stage) * a_i + u_i) * RBG + group of RB row groups; grid.y = workgroups
+// along the batch.
+template <int RB, int NB, bool BF16>
+__global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   typedef Operand<BF16> Op;
   typedef typename Op::reg reg;
   constexpr int CPL = Op::CPL, CPI = 4 * CPL;   // columns per lane load / per iteration
-  const int lane = threadIdx.x, j = lane & 15, q = lane >> 4;
-  const int unit = blockIdx.x / p.a3, u3 = blockIdx.x % p.a3;
-  const int code = p.units[unit];
-  const int cl = code >> 6, s = code & 63;
+  constexpr int NL = RB + NB;                   // loads per iteration
+  __shared__ float red[4][RB * NB * 4][64];
+  __shared__ u32x4 stage[4][NL][64];   // per wave: one 16 x 64-byte tile per load of an iteration
+  const int lane = threadIdx.x & 63, j = lane & 15, q = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // load layout: lane l reads row l / 4 of the 16, 16-byte segment l % 4; operand layout: lane l
+  // holds row l % 16, segment l / 16
+  const int lr = lane >> 2, ls = lane & 3;
+  // a tile in LDS: 16-byte slot 4 * row + (segment ^ ((row >> 1) & 3)); the exclusive-or spreads both
+  // the writes (load layout) and the reads (operand layout) of eight consecutive lanes over all banks
+  const int wslot = 4 * lr + (ls ^ ((lr >> 1) & 3)), rslot = 4 * j + (q ^ ((j >> 1) & 3));
+  int x = blockIdx.x;
+  const int g = x % p.RBG; x /= p.RBG;
+  const int u3 = x % p.a3; x /= p.a3;
+  const int sg = x % p.NSTG, v1 = x / p.NSTG;
   const int RS = 1 << p.lgRS;
-  const int32_t *stg = p.stages + int64_t(cl) * (1 + p.MG) * 64 + s;
-  const int base = stg[0];
+  const int32_t *crow = p.colrows + v1 * p.EO, *cpos = p.colpos + v1 * p.EO;
+  const int base = v1 * p.tile_rows + sg * p.stage_rows;
 
-  // this lane's row of dO (row j of the 16): member j / RS, row j % RS of its R rows
-  int64_t arow = 0;
-  {
-    const int mm = j >> p.lgRS, ri = j & (RS - 1);
-    const int mem = p.members[cl * p.MG + mm];
-    if (mem >= 0 && stg[(1 + mm) * 64] >= 0 && ri < p.R)
-      arow = ((int64_t(mem) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
+  int64_t off[NL];   // element offset of this lane's 16 bytes in iteration 0: dO rows, then I rows
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int idx = (g * RB + rb) * p.MG + (lr >> p.lgRS), ri = lr & (RS - 1);
+    int64_t row = 0;
+    if (idx < p.EO && ri < p.R) row = ((int64_t(crow[idx]) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
+    off[rb] = row * p.ld_dO + ls * CPL;
   }
-  int64_t brow[NB];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) brow[b] = base + p.rowtab[(u3 * NB + b) * 16 + j];   // padding: row 0 of the stage
-
-  const int64_t n_lo = int64_t(blockIdx.y) * p.chunk;
-  const int64_t n_hi = n_lo + p.chunk < p.N ? n_lo + p.chunk : p.N;
-  const int64_t aoff = arow * p.ld_dO + q * CPL;
-  int64_t boff[NB];
+  for (int b = 0; b < NB; ++b)   // padding steps read row 0 of the stage
+    off[RB + b] = int64_t(base + p.rowtab[(u3 * NB + b) * 16 + lr]) * p.ldI + ls * CPL;
+  auto load_all = [&](reg *r, int64_t n) {
 #pragma unroll
-  for (int b = 0; b < NB; ++b) boff[b] = brow[b] * p.ldI + q * CPL;
-
-  f32x4 acc[NB];
+    for (int i = 0; i < RB; ++i) r[i] = Op::load(p.dO, off[i] + n);
 #pragma unroll
-  for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = RB; i < NL; ++i) r[i] = Op::load(p.I, off[i] + n);
+  };
+  // load layout -> operand layout through this wave's tiles (LDS instructions of one wave execute in order)
+  auto transpose_all = [&](reg *d, const reg *r) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) stage[wave][i][wslot] = __builtin_bit_cast(u32x4, r[i]);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < NL; ++i) d[i] = __builtin_bit_cast(reg, stage[wave][i][rslot]);
+    __builtin_amdgcn_wave_barrier();
+  };
+  f32x4 acc[RB][NB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[rb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto mac_all = [&](const reg *o) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) Op::mac(o[rb], o[RB + b], acc[rb][b]);
+  };
 
+  const int64_t n_lo = (int64_t(blockIdx.y) * 4 + wave) * p.chunk;
+  const int64_t n_hi = n_lo + p.chunk < p.N ? n_lo + p.chunk : p.N;   // (n_lo may lie past N: empty range)
   int64_t n = n_lo;
-#pragma unroll 2
-  for (; n + CPI <= n_hi; n += CPI) {
-    const reg a = Op::load(p.dO, aoff + n);
-    reg bv[NB];
+  const int64_t iters = n_hi > n_lo ? (n_hi - n_lo) / CPI : 0;   // whole iterations
+  if (iters > 0) {
+    // In flight: the global loads of iterations k + 1 .. k + D - 1 (a ring of D register sets), the
+    // permutation of iteration k, the MFMAs of k - 1.  One loop body fills, runs and drains the
+    // pipeline, so that the distance between a load and its use is the same on every path into
+    // the loop, and it has no branch, so that the permutations and loads are issued between the
+    // MFMAs: steps that have nothing to multiply (k = 0, and k > iters when the loop overshoots)
+    // multiply zeros.  Past the last iteration the loads repeat the last one (in bounds).
+    constexpr int D = 3;
+    // iterations in ascending column order: the two 64-byte halves of a cache line are consumed by
+    // consecutive iterations, while the line is still in the L1
+    const int64_t n_last = n_lo + (iters - 1) * CPI;
+    auto column = [&](int64_t k) {
+      const int64_t c = n_lo + k * CPI;
+      return c < n_last ? c : n_last;
+    };
+    reg raw[D][NL], cur[NL], nxt[NL];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) bv[b] = Op::load(p.I, boff[b] + n);
+    for (int d = 0; d < D; ++d) load_all(raw[d], column(d));
 #pragma unroll
-    for (int b = 0; b < NB; ++b) Op::mac(a, bv[b], acc[b]);
+    for (int i = 0; i < NL; ++i) cur[i] = Op::zero();
+    for (int64_t k0 = 0; k0 <= iters; k0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const int64_t k = k0 + d;
+        transpose_all(nxt, raw[d]);
+        load_all(raw[d], column(k + D));
+        mac_all(cur);
+        const bool live = k < iters;   // nxt holds iteration k
+#pragma unroll
+        for (int i = 0; i < RB; ++i) cur[i] = live ? nxt[i] : Op::zero();
+#pragma unroll
+        for (int i = RB; i < NL; ++i) cur[i] = nxt[i];
+        // issue order of this step: LDS writes and reads, then the loads, spread behind the MFMAs
+        constexpr int M = RB * NB * (BF16 ? 1 : 4), DS = NL * 2, VM = NL;
+        constexpr int Md = M >= 4 ? (M * 3) / 4 : M, Mv = M - Md;
+        constexpr int dsq = (DS + Md - 1) / Md, vmq = Mv ? (VM + Mv - 1) / Mv : VM;
+#pragma unroll
+        for (int mi = 0; mi < M; ++mi) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
+          if (mi < Md) __builtin_amdgcn_sched_group_barrier(0x080, dsq, 0);       // LDS
+          else __builtin_amdgcn_sched_group_barrier(0x020, vmq, 0);               // global loads
+        }
+        if (Mv == 0) __builtin_amdgcn_sched_group_barrier(0x020, vmq, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    n = n_lo + iters * CPI;
   }
   if (n < n_hi) {   // ragged end of the batch: columns at and past n_hi count as zero on both sides
-    const int64_t left = n_hi - (n + q * CPL);
+    const int64_t left = n_hi - (n + ls * CPL);
     const int valid = left <= 0 ? 0 : left >= CPL ? CPL : int(left);
-    const reg a = Op::load_tail(p.dO, aoff + n, valid);
+    reg r[NL], o[NL];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const reg bv = Op::load_tail(p.I, boff[b] + n, valid);
-      Op::mac(a, bv, acc[b]);
-    }
+    for (int i = 0; i < NL; ++i) r[i] = Op::load_tail(i < RB ? p.dO : p.I, off[i] + n, valid);
+    transpose_all(o, r);
+    mac_all(o);
   }
 
-  // acc[b][i] = dW block element (row 4 * q + i of the 16, contraction step 16 * b + j)
-  float *out = p.out + int64_t(blockIdx.y) * p.nnz;
+  // acc[rb][b][i] = dW block element (row 4 * q + i of row group rb, contraction step 16 * b + j);
+  // after the exchange wave w holds the sums for i == w
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r16 = 4 * q + i, mm = r16 >> p.lgRS, ri = r16 & (RS - 1);
-    const int mem = p.members[cl * p.MG + mm];
-    const int f = stg[(1 + mm) * 64];   // position of the stage among the member's weight fragments
-    if (mem < 0 || f < 0 || ri >= p.R) continue;
-    const int64_t row = ((int64_t(mem) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
-    float *dst = out + row * p.rowdeg + int64_t(f) * p.KCR;
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) red[wave][(rb * NB + b) * 4 + i][lane] = acc[rb][b][i];
+  __syncthreads();
+  const int r16 = 4 * q + wave, ri = r16 & (RS - 1);
+  if (ri >= p.R) return;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int idx = (g * RB + rb) * p.MG + (r16 >> p.lgRS);
+    if (idx >= p.EO) continue;
+    const int64_t row = ((int64_t(crow[idx]) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
+    // the stage is fragment cpos * NSTG + sg of the row: KCR consecutive kept values
+    float *dst = p.out + int64_t(blockIdx.y) * p.nnz + row * p.rowdeg + int64_t(cpos[idx] * p.NSTG + sg) * p.KCR;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      const int kk = 16 * b + j;
-      if (kk < p.KCR) dst[kk] = acc[b][i];
+      const int kk = 16 * b + j, e = (rb * NB + b) * 4 + wave;
+      const float v = (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
+      if (kk < p.KCR) dst[kk] = v;
     }
   }
 }
@@ -227,8 +319,8 @@ __global__ __launch_bounds__(256) void sddmm_generic(GenericParams p, const TIn 
 }
 
 struct SddmmState {
-  int32_t *units = nullptr, *stages = nullptr, *members = nullptr, *rowtab = nullptr;
-  int nunits = 0;
+  int32_t *colrows = nullptr, *colpos = nullptr, *rowtab = nullptr;
+  int EO = 0;
   float *partial = nullptr;
   size_t partial_bytes = 0;
 };
@@ -241,24 +333,38 @@ int upload(const std::vector<T> &h, T **d) {
 }
 
 typedef void (*sddmm_fn)(SddmmParams);
-sddmm_fn find_kernel(int NB, bool bf16) {
+template <int RB, bool BF16>
+sddmm_fn pick_nb(int NB) {
   switch (NB) {
-    case 1: return bf16 ? sddmm_reg<1, true> : sddmm_reg<1, false>;
-    case 2: return bf16 ? sddmm_reg<2, true> : sddmm_reg<2, false>;
-    case 3: return bf16 ? sddmm_reg<3, true> : sddmm_reg<3, false>;
-    case 4: return bf16 ? sddmm_reg<4, true> : sddmm_reg<4, false>;
-    case 5: return bf16 ? sddmm_reg<5, true> : sddmm_reg<5, false>;
+    case 1: return sddmm_reg<RB, 1, BF16>;
+    case 2: return sddmm_reg<RB, 2, BF16>;
+    case 3: return sddmm_reg<RB, 3, BF16>;
+    case 4: return sddmm_reg<RB, 4, BF16>;
+    case 5: return sddmm_reg<RB, 5, BF16>;
+  }
+  return nullptr;
+}
+sddmm_fn find_kernel(int RB, int NB, bool bf16) {
+  switch (RB) {
+    case 1: return bf16 ? pick_nb<1, true>(NB) : pick_nb<1, false>(NB);
+    case 2: return bf16 ? pick_nb<2, true>(NB) : pick_nb<2, false>(NB);
   }
   return nullptr;
 }
 
 int build_state(const rbgp_mask *m, SddmmState *st) {
   const rbgp_reg_plan &pl = m->reg;
-  const rbgp_reg_clusters &cl = m->reg_clusters;
   const int NB = (pl.KCR + 15) / 16;
-  std::vector<int32_t> units;
-  for (int c = 0; c < cl.ncl; ++c)
-    for (int s = 0; s < cl.counts[size_t(c)]; ++s) units.push_back(c * 64 + s);
+  // co-adjacency of the tile rows: tile row u has the tiles of G_o's row u / fold
+  const int c1 = m->c[0], d1 = m->d[0], EO = m->e[0] * pl.fold;
+  std::vector<int32_t> colrows(size_t(c1) * EO), colpos(size_t(c1) * EO);
+  std::vector<int> fill(size_t(c1), 0);
+  for (int u = 0; u < pl.TR; ++u)
+    for (int jj = 0; jj < d1; ++jj) {
+      const int v = m->adj[0][size_t(u / pl.fold) * d1 + jj];
+      colrows[size_t(v) * EO + fill[size_t(v)]] = u;
+      colpos[size_t(v) * EO + fill[size_t(v)]++] = jj;
+    }
   const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
   std::vector<int32_t> rt(size_t(a3) * NB * 16, 0);
   for (int u3 = 0; u3 < a3; ++u3)
@@ -266,11 +372,10 @@ int build_state(const rbgp_mask *m, SddmmState *st) {
       const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
       rt[(size_t(u3) * NB) * 16 + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
     }
-  int rc = upload(units, &st->units);
-  if (!rc) rc = upload(cl.stages, &st->stages);
-  if (!rc) rc = upload(cl.members, &st->members);
+  int rc = upload(colrows, &st->colrows);
+  if (!rc) rc = upload(colpos, &st->colpos);
   if (!rc) rc = upload(rt, &st->rowtab);
-  st->nunits = int(units.size());
+  st->EO = EO;
   return rc;
 }
 
@@ -279,9 +384,8 @@ int build_state(const rbgp_mask *m, SddmmState *st) {
 void rbgp_sddmm_release(void *state) {
   SddmmState *st = static_cast<SddmmState *>(state);
   if (!st) return;
-  if (st->units) (void)hipFree(st->units);
-  if (st->stages) (void)hipFree(st->stages);
-  if (st->members) (void)hipFree(st->members);
+  if (st->colrows) (void)hipFree(st->colrows);
+  if (st->colpos) (void)hipFree(st->colpos);
   if (st->rowtab) (void)hipFree(st->rowtab);
   if (st->partial) (void)hipFree(st->partial);
   delete st;
@@ -321,21 +425,29 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
     if (!st) return RBGP_ENOMEM;
     *state = st;
   }
-  if (!st->units) {
+  if (!st->colrows) {
     int rc = build_state(m, st);
     if (rc) return rc;
   }
   const int NB = (pl.KCR + 15) / 16;
-  sddmm_fn fn = find_kernel(NB, bf16);
+  // row groups of 16 (MG tile rows) per tile column, RB of them per wave
+  const int groups = (st->EO + pl.MG - 1) / pl.MG;
+  // two row groups per wave halve the rows of I fetched per MFMA; four would starve the chip of
+  // waves at the layer sizes of the paper (measured: slower on every VGG19 / WRN shape tried)
+  const int RB = groups >= 2 ? 2 : 1;
+  const int RBG = (groups + RB - 1) / RB;
+  sddmm_fn fn = find_kernel(RB, NB, bf16);
   if (!fn) return RBGP_EUNSUPPORTED;
-  // ranges of the batch: enough waves for several per SIMD (1024 SIMDs), at least two iterations each
+  // ranges of the batch: enough waves for a few per SIMD (1024 SIMDs), at least two iterations each
   const int cpi = bf16 ? 32 : 16;
-  const int64_t blocks = int64_t(st->nunits) * m->a[2];
-  int64_t nsplit = (8192 + blocks - 1) / blocks;
-  nsplit = std::max<int64_t>(1, std::min(nsplit, (N + 2 * cpi - 1) / (2 * cpi)));
-  nsplit = std::min<int64_t>(nsplit, 1024);
-  const int64_t chunk = ((N + nsplit - 1) / nsplit + cpi - 1) / cpi * cpi;
-  nsplit = (N + chunk - 1) / chunk;
+  const int64_t blocks = int64_t(m->c[0]) * pl.NSTG * m->a[2] * RBG;
+  // one wave per SIMD (1024 SIMDs): longer ranges amortise the fill of the load pipeline and keep
+  // the partial sums few; more waves per SIMD measured slower
+  int64_t ranges = (1024 + blocks - 1) / blocks;                         // column ranges = waves per unit
+  ranges = std::max<int64_t>(1, std::min(ranges, (N + 2 * cpi - 1) / (2 * cpi)));
+  ranges = std::min<int64_t>((ranges + 3) / 4 * 4, 4096);                // four per workgroup
+  const int64_t chunk = ((N + ranges - 1) / ranges + cpi - 1) / cpi * cpi;
+  const int64_t nsplit = ((N + chunk - 1) / chunk + 3) / 4;              // workgroups per unit = partial sums
   if (nsplit > 1) {
     const size_t need = size_t(nsplit) * size_t(nnz) * sizeof(float);
     if (st->partial_bytes < need) {
@@ -349,13 +461,15 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   SddmmParams p;
   p.dO = dO; p.I = I;
   p.out = nsplit > 1 ? st->partial : dW;
-  p.units = st->units; p.stages = st->stages; p.members = st->members; p.rowtab = st->rowtab;
+  p.colrows = st->colrows; p.colpos = st->colpos; p.rowtab = st->rowtab;
   p.N = N; p.ld_dO = ld_dO; p.ldI = ldI; p.nnz = nnz; p.chunk = chunk;
+  p.EO = st->EO; p.RBG = RBG; p.NSTG = pl.NSTG; p.stage_rows = pl.SRC;
+  p.tile_rows = m->c[1] * m->c[2] * m->c[3];
   p.a2 = pl.A2; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
   p.lgRS = 0;
   while ((1 << p.lgRS) < pl.RS) ++p.lgRS;
   p.MG = pl.MG; p.KCR = pl.KCR; p.rowdeg = int(m->rowdeg);
-  fn<<<dim3(unsigned(blocks), unsigned(nsplit)), dim3(64), 0, hs>>>(p);
+  fn<<<dim3(unsigned(blocks), unsigned(nsplit)), dim3(256), 0, hs>>>(p);
   RBGP_HIP(hipGetLastError());
   if (nsplit > 1) {
     sddmm_reduce<<<dim3(unsigned((nnz + 255) / 256)), dim3(256), 0, hs>>>(st->partial, dW, nnz, int(nsplit));
