@@ -196,7 +196,8 @@ int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, c
  * RBGP_KERNEL_MFMA_REG family covers run on MFMA kernels (unless the mask's kernel choice is
  * RBGP_KERNEL_GENERIC), every other mask on a plain kernel.  Sums over n are taken in a fixed
  * order: results are reproducible run to run.  Uses a partial-sum buffer that the library keeps
- * with the mask and grows as needed (a growing call synchronises the device).  Errors: ESHAPE
+ * with the mask and grows as needed (a growing call synchronises the device): calls for one mask
+ * must not overlap in time (put them on one stream).  Errors: ESHAPE
  * (sizes do not match the mask, leading dimension, alignment), EINVAL, EHIP.  Asynchronous on
  * `hip_stream`. */
 int rbgp_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
