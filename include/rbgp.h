@@ -56,7 +56,12 @@ enum {
 };
 
 /* per-factor result of the spectral test */
-enum { RBGP_SPEC_OK = 0, RBGP_SPEC_COMPLETE = 1, RBGP_SPEC_DEGENERATE = 2 };
+enum {
+  RBGP_SPEC_OK = 0,
+  RBGP_SPEC_COMPLETE = 1,
+  RBGP_SPEC_DEGENERATE = 2,
+  RBGP_SPEC_PRODUCT = 3   /* a factor made of several base graphs, each tested on its own (rbgp_make_mask_k) */
+};
 
 /* kernel families */
 enum {
@@ -96,6 +101,30 @@ enum {
  * divisible by it, M or K above 2^24), ENOTRAMANUJAN, ENOMEM. */
 int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t row_deg[4],
                    uint64_t seed, int32_t max_tries, rbgp_mask_t **out);
+
+/* The general configuration of Section 5 ("RBGP4 sparsity pattern": a mask is configured by the
+ * number of base graphs K and the type, sparse or complete, of each): `count` (1..16) base graphs
+ * G_1 .. G_count, sampled like those of rbgp_make_mask (coin stream keyed by (seed, index of the base
+ * graph, attempt)), whose product G_1 (x) ... (x) G_count is the mask.  roles[i] in 0..3, non-decreasing,
+ * says which of the four factors G_o, G_r, G_i, G_b of the kernels' view base graph i belongs to: the
+ * factor is the product of its base graphs (a role without any is the trivial graph on (1, 1) vertices),
+ * which is again biregular, so the mask object, its canonical order (ascending column per row) and every
+ * other entry point are those of a four-factor mask, and by associativity of the product the mask is
+ * exactly G_1 (x) ... (x) G_count.  The MFMA kernel families need the factors of roles 1 and 3 complete.
+ * rbgp_mask_spectrum of a factor made of several base graphs reports the singular values of the
+ * product (products of the base graphs' singular values), the bound of the product's degrees and
+ * RBGP_SPEC_PRODUCT; rbgp_mask_base reports each base graph.  rbgp_make_mask(rows, cols, row_deg, ...)
+ * is rbgp_make_mask_k(4, rows, cols, row_deg, {0, 1, 2, 3}, ...).  Errors as for rbgp_make_mask. */
+int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, const int32_t *row_deg,
+                     const int32_t *roles, uint64_t seed, int32_t max_tries, rbgp_mask_t **out);
+
+/* Number of base graphs of the mask, and base graph i: sizes, left degree, role, a borrowed pointer to
+ * its adjacency list (rows*deg int32, valid until mask_free) and its spectral data (any output
+ * pointer may be NULL). */
+int rbgp_mask_num_base(const rbgp_mask_t *mask);
+int rbgp_mask_base(const rbgp_mask_t *mask, int i, int32_t *rows, int32_t *cols, int32_t *deg, int32_t *role,
+                   const int32_t **adj, double *sigma1, double *sigma2, double *bound, int *status,
+                   int *tries);
 
 /* Release the mask and its device tables.  NULL is allowed. */
 void rbgp_mask_free(rbgp_mask_t *mask);

@@ -13,7 +13,7 @@ F32, BF16_F32ACC = 0, 1
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG = 0, 1, 2, 3
 TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_WEIGHTS_IN_LDS = 0, 1, 2, 3
 TUNE_ROW_GROUPS, TUNE_K_SPLIT = 4, 5
-SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE = 0, 1, 2
+SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE, SPEC_PRODUCT = 0, 1, 2, 3
 OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librbgp.so")
@@ -27,6 +27,13 @@ _vp = ctypes.c_void_p
 
 SIGNATURES = {
     "rbgp_make_mask": (ctypes.c_int, [_i32p, _i32p, _i32p, ctypes.c_uint64, ctypes.c_int32, ctypes.POINTER(_vp)]),
+    "rbgp_make_mask_k": (ctypes.c_int, [ctypes.c_int32, _i32p, _i32p, _i32p, _i32p, ctypes.c_uint64, ctypes.c_int32,
+                                        ctypes.POINTER(_vp)]),
+    "rbgp_mask_num_base": (ctypes.c_int, [_vp]),
+    "rbgp_mask_base": (ctypes.c_int, [_vp, ctypes.c_int, _i32p, _i32p, _i32p, _i32p, ctypes.POINTER(_i32p),
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int),
+                                      ctypes.POINTER(ctypes.c_int)]),
     "rbgp_mask_free": (None, [_vp]),
     "rbgp_mask_shape": (ctypes.c_int, [_vp, _i64p, _i64p, _i64p, _i64p, _i64p]),
     "rbgp_mask_factor": (ctypes.c_int, [_vp, ctypes.c_int, _i32p, _i32p, _i32p, ctypes.POINTER(_i32p)]),
@@ -110,6 +117,31 @@ def rbgp_make_mask(rows, cols, row_deg, seed: int, max_tries: int = 0) -> Mask:
     _check(load().rbgp_make_mask(_i32x4(rows), _i32x4(cols), _i32x4(row_deg), int(seed), int(max_tries),
                                  ctypes.byref(out)), "rbgp_make_mask")
     return Mask(out)
+
+
+def rbgp_make_mask_k(rows, cols, row_deg, roles, seed: int, max_tries: int = 0) -> Mask:
+    n = len(rows)
+    arr = lambda v: (ctypes.c_int32 * n)(*[int(x) for x in v])
+    out = _vp()
+    _check(load().rbgp_make_mask_k(n, arr(rows), arr(cols), arr(row_deg), arr(roles), int(seed), int(max_tries),
+                                   ctypes.byref(out)), "rbgp_make_mask_k")
+    return Mask(out)
+
+
+def rbgp_mask_num_base(mask: Mask) -> int:
+    return int(load().rbgp_mask_num_base(mask.handle))
+
+
+def rbgp_mask_base(mask: Mask, i: int) -> dict:
+    r, c, d, role = (ctypes.c_int32() for _ in range(4))
+    adj = _i32p()
+    s1, s2, b = (ctypes.c_double() for _ in range(3))
+    st, tr = ctypes.c_int(), ctypes.c_int()
+    _check(load().rbgp_mask_base(mask.handle, i, *[ctypes.byref(x) for x in (r, c, d, role, adj, s1, s2, b, st, tr)]),
+           "rbgp_mask_base")
+    a = np.ctypeslib.as_array(adj, shape=(r.value, d.value)).copy()
+    return dict(rows=r.value, cols=c.value, deg=d.value, role=role.value, adj=a, sigma1=s1.value, sigma2=s2.value,
+                bound=b.value, status=st.value, tries=tr.value)
 
 
 def rbgp_mask_free(mask: Mask):

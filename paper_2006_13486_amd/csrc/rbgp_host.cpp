@@ -425,17 +425,94 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
 
 extern "C" {
 
-int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t row_deg[4],
-                   uint64_t seed, int32_t max_tries, rbgp_mask_t **out) {
-  if (!rows || !cols || !row_deg || !out) return RBGP_EINVAL;
+// Sample one base graph (Appendix "Ramanujan Bipartite Graph Generation"): complete when d == c, else
+// 2-lifts of a complete graph, resampled with coin stream (seed, index, attempt) until Ramanujan.
+static int sample_base(int a, int c, int d, uint64_t seed, int index, int max_tries, rbgp_base_graph *g) {
+  if (a <= 0 || c <= 0 || d <= 0 || d > c || c % d) return RBGP_EINVAL;
+  const int lifts = ilog2_exact(c / d);
+  if (lifts < 0 || a % (1 << lifts)) return RBGP_EINVAL;
+  const int e = int(int64_t(a) * d / c);
+  g->a = a; g->c = c; g->d = d; g->e = e;
+  g->bound = std::sqrt(double(d - 1)) + std::sqrt(double(e - 1));
+  Bits B;
+  if (d == c) {
+    B.assign(size_t(a) * c, 1);
+    g->sigma1 = std::sqrt(double(a) * c);
+    g->sigma2 = 0;
+    g->status = RBGP_SPEC_COMPLETE;
+    g->tries = 0;
+  } else {
+    bool accepted = false;
+    for (int t = 0; t < max_tries && !accepted; ++t) {
+      Coins coins(seed, uint64_t(index), uint64_t(t));
+      B = sample_biregular(a, c, lifts, coins);
+      top_singular(B, a, c, &g->sigma1, &g->sigma2);
+      g->tries = t + 1;
+      if (std::min(d, e) == 1) {
+        g->status = RBGP_SPEC_DEGENERATE;
+        accepted = true;
+      } else if (g->sigma2 <= g->bound * (1.0 + 1e-9)) {
+        g->status = RBGP_SPEC_OK;
+        accepted = true;
+      }
+    }
+    if (!accepted) return RBGP_ENOTRAMANUJAN;
+  }
+  g->adj.resize(size_t(a) * d);
+  for (int u = 0; u < a; ++u) {
+    int j = 0;
+    for (int v = 0; v < c; ++v)
+      if (B[size_t(u) * c + v]) g->adj[size_t(u) * d + j++] = v;
+  }
+  return RBGP_OK;
+}
+
+// Factor `role` of the four-factor mask = the product of the base graphs of that role, in order
+// (Section 3: the product's biadjacency matrix is the Kronecker product of theirs).  Vertex tuples
+// are numbered with the last graph fastest; the neighbours of a tuple are the tuples of neighbours
+// in lexicographic order, which ascends because every list ascends.
+static void merge_role(rbgp_mask *m, int role) {
+  int32_t a = 1, c = 1, d = 1, e = 1;
+  std::vector<int32_t> adj(1, 0);   // the trivial graph on (1, 1) vertices
+  double s1 = 1, s2 = 0;
+  int count = 0, status = RBGP_SPEC_COMPLETE, tries = 0;
+  bool all_complete = true, degenerate = false;
+  for (const rbgp_base_graph &g : m->base) {
+    if (g.role != role) continue;
+    std::vector<int32_t> next(size_t(a) * g.a * d * g.d);
+    for (int u = 0; u < a; ++u)
+      for (int ug = 0; ug < g.a; ++ug)
+        for (int j = 0; j < d; ++j)
+          for (int jg = 0; jg < g.d; ++jg)
+            next[(size_t(u) * g.a + ug) * d * g.d + size_t(j) * g.d + jg] =
+                adj[size_t(u) * d + j] * g.c + g.adj[size_t(ug) * g.d + jg];
+    adj.swap(next);
+    // singular values of a Kronecker product are the products of the factors' singular values
+    s2 = std::max(s2 * g.sigma1, s1 * g.sigma2);
+    s1 *= g.sigma1;
+    a *= g.a; c *= g.c; d *= g.d; e *= g.e;
+    all_complete = all_complete && g.status == RBGP_SPEC_COMPLETE;
+    degenerate = degenerate || g.status == RBGP_SPEC_DEGENERATE;
+    status = g.status;
+    tries += g.tries;
+    ++count;
+  }
+  if (count > 1) status = all_complete ? RBGP_SPEC_COMPLETE : degenerate ? RBGP_SPEC_DEGENERATE : RBGP_SPEC_PRODUCT;
+  m->a[role] = a; m->c[role] = c; m->d[role] = d; m->e[role] = e;
+  m->adj[role].swap(adj);
+  m->sigma1[role] = s1; m->sigma2[role] = s2;
+  m->bound[role] = std::sqrt(double(d - 1)) + std::sqrt(double(e - 1));
+  m->status[role] = status; m->tries[role] = tries;
+}
+
+int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, const int32_t *row_deg,
+                     const int32_t *roles, uint64_t seed, int32_t max_tries, rbgp_mask_t **out) {
+  if (!rows || !cols || !row_deg || !roles || !out || count < 1 || count > 16) return RBGP_EINVAL;
   if (max_tries <= 0) max_tries = 1000;
-  int lifts[4];
   int64_t M = 1, K = 1, rowdeg = 1, coldeg = 1;
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < count; ++i) {
     if (rows[i] <= 0 || cols[i] <= 0 || row_deg[i] <= 0 || row_deg[i] > cols[i]) return RBGP_EINVAL;
-    if (cols[i] % row_deg[i]) return RBGP_EINVAL;
-    lifts[i] = ilog2_exact(cols[i] / row_deg[i]);
-    if (lifts[i] < 0 || rows[i] % (1 << lifts[i])) return RBGP_EINVAL;
+    if (roles[i] < 0 || roles[i] > 3 || (i && roles[i] < roles[i - 1])) return RBGP_EINVAL;
     M *= rows[i];
     K *= cols[i];
     rowdeg *= row_deg[i];
@@ -446,44 +523,16 @@ int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t r
   rbgp_mask *m = new (std::nothrow) rbgp_mask();
   if (!m) return RBGP_ENOMEM;
   try {
-    for (int i = 0; i < 4; ++i) {
-      const int a = rows[i], c = cols[i], d = row_deg[i], e = int(int64_t(a) * d / c);
-      m->a[i] = a; m->c[i] = c; m->d[i] = d; m->e[i] = e;
-      m->bound[i] = std::sqrt(double(d - 1)) + std::sqrt(double(e - 1));
-      Bits B;
-      if (d == c) {
-        B.assign(size_t(a) * c, 1);
-        m->sigma1[i] = std::sqrt(double(a) * c);
-        m->sigma2[i] = 0;
-        m->status[i] = RBGP_SPEC_COMPLETE;
-        m->tries[i] = 0;
-      } else {
-        bool accepted = false;
-        for (int t = 0; t < max_tries && !accepted; ++t) {
-          Coins coins(seed, uint64_t(i), uint64_t(t));
-          B = sample_biregular(a, c, lifts[i], coins);
-          top_singular(B, a, c, &m->sigma1[i], &m->sigma2[i]);
-          m->tries[i] = t + 1;
-          if (std::min(d, e) == 1) {
-            m->status[i] = RBGP_SPEC_DEGENERATE;
-            accepted = true;
-          } else if (m->sigma2[i] <= m->bound[i] * (1.0 + 1e-9)) {
-            m->status[i] = RBGP_SPEC_OK;
-            accepted = true;
-          }
-        }
-        if (!accepted) {
-          delete m;
-          return RBGP_ENOTRAMANUJAN;
-        }
-      }
-      m->adj[i].resize(size_t(a) * d);
-      for (int u = 0; u < a; ++u) {
-        int j = 0;
-        for (int v = 0; v < c; ++v)
-          if (B[size_t(u) * c + v]) m->adj[i][size_t(u) * d + j++] = v;
+    m->base.resize(size_t(count));
+    for (int i = 0; i < count; ++i) {
+      m->base[size_t(i)].role = roles[i];
+      const int rc = sample_base(rows[i], cols[i], row_deg[i], seed, i, max_tries, &m->base[size_t(i)]);
+      if (rc) {
+        delete m;
+        return rc;
       }
     }
+    for (int role = 0; role < 4; ++role) merge_role(m, role);
   } catch (const std::bad_alloc &) {
     delete m;
     return RBGP_ENOMEM;
@@ -494,6 +543,31 @@ int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t r
   rbgp_plan_mfma(m);
   rbgp_plan_reg(m);
   *out = m;
+  return RBGP_OK;
+}
+
+int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t row_deg[4],
+                   uint64_t seed, int32_t max_tries, rbgp_mask_t **out) {
+  static const int32_t roles[4] = {0, 1, 2, 3};
+  return rbgp_make_mask_k(4, rows, cols, row_deg, roles, seed, max_tries, out);
+}
+
+int rbgp_mask_num_base(const rbgp_mask_t *m) { return m ? int(m->base.size()) : RBGP_EINVAL; }
+
+int rbgp_mask_base(const rbgp_mask_t *m, int i, int32_t *rows, int32_t *cols, int32_t *deg, int32_t *role,
+                   const int32_t **adj, double *sigma1, double *sigma2, double *bound, int *status, int *tries) {
+  if (!m || i < 0 || i >= int(m->base.size())) return RBGP_EINVAL;
+  const rbgp_base_graph &g = m->base[size_t(i)];
+  if (rows) *rows = g.a;
+  if (cols) *cols = g.c;
+  if (deg) *deg = g.d;
+  if (role) *role = g.role;
+  if (adj) *adj = g.adj.data();
+  if (sigma1) *sigma1 = g.sigma1;
+  if (sigma2) *sigma2 = g.sigma2;
+  if (bound) *bound = g.bound;
+  if (status) *status = g.status;
+  if (tries) *tries = g.tries;
   return RBGP_OK;
 }
 
@@ -562,6 +636,19 @@ int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
       t->a[i] = m->c[i]; t->c[i] = m->a[i]; t->d[i] = m->e[i]; t->e[i] = m->d[i];
       t->sigma1[i] = m->sigma1[i]; t->sigma2[i] = m->sigma2[i]; t->bound[i] = m->bound[i];   // singular values of B^T are B's
       t->status[i] = m->status[i]; t->tries[i] = m->tries[i];
+    }
+    for (const rbgp_base_graph &g : m->base) {   // the transposed base graphs, for introspection
+      rbgp_base_graph gt;
+      gt.a = g.c; gt.c = g.a; gt.d = g.e; gt.e = g.d; gt.role = g.role;
+      gt.sigma1 = g.sigma1; gt.sigma2 = g.sigma2; gt.bound = g.bound; gt.status = g.status; gt.tries = g.tries;
+      gt.adj.assign(size_t(g.c) * g.e, 0);
+      std::vector<int> fill(size_t(g.c), 0);
+      for (int u = 0; u < g.a; ++u)
+        for (int j = 0; j < g.d; ++j) {
+          const int v = g.adj[size_t(u) * g.d + j];
+          gt.adj[size_t(v) * g.e + fill[size_t(v)]++] = u;
+        }
+      t->base.push_back(std::move(gt));
     }
     t->from_original.resize(size_t(m->nnz));
     transposed_order(m, coadj, t->from_original.data());

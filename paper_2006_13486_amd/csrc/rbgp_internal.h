@@ -71,6 +71,14 @@ struct rbgp_reg_clusters {
   std::vector<int32_t> counts;    // [ncl] stages per cluster
 };
 
+// One sampled base graph of a mask made from more than four of them.
+struct rbgp_base_graph {
+  int32_t a, c, d, e, role;
+  std::vector<int32_t> adj;           // a x d, ascending
+  double sigma1, sigma2, bound;
+  int status, tries;
+};
+
 struct rbgp_mask {
   int32_t a[4], c[4], d[4], e[4];     // rows, cols, left degree, right degree of each factor
   std::vector<int32_t> adj[4];        // adjacency lists, a[i] x d[i], ascending
@@ -78,6 +86,7 @@ struct rbgp_mask {
   int status[4], tries[4];
   int64_t M, K, rowdeg, coldeg, nnz;
   int kernel_choice;                  // RBGP_KERNEL_*
+  std::vector<rbgp_base_graph> base;  // the sampled base graphs, in product order (four for rbgp_make_mask)
   std::vector<int32_t> from_original; // masks made by rbgp_mask_transpose: canonical index in the
                                       //   original mask of every kept value, in this mask's order
   rbgp_mfma_plan plan;

@@ -34,6 +34,7 @@ class Workload:
     i_seed: int = 3
     w_std: float = 0.02
     i_dist: str = "relu_normal"          # or "uniform"
+    roles: Tuple[int, ...] = ()          # more than four base graphs: the factor (0..3) each belongs to
 
     @property
     def M(self) -> int:

@@ -10,6 +10,13 @@ from paper_2006_13486_amd import workloads as wl
 TOL = {wl.F32: 1e-5, wl.BF16: 1e-2}     # max |err| / sum_k |W||I| per output
 
 
+def make_mask(w):
+    """The library's mask of a workload: four base graphs, or more with their roles."""
+    if w.roles:
+        return rb.rbgp_make_mask_k(w.rows, w.cols, w.row_deg, w.roles, w.mask_seed)
+    return rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+
+
 def host_inputs(w, N=None, vals=None, I=None):
     """(values for the library, I for the library, float32 views for the oracle)."""
     vals = wl.kept_weights(w) if vals is None else vals
@@ -25,7 +32,7 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     dev = torch.device("cuda:0")
     N = I_lib.shape[1]
     print(f"[gpu] {w.name} N={N} kernel={kernel} tune={tune} ld_pad={ld_pad} {tag}", flush=True)
-    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = make_mask(w)
     if kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask, kernel)
     for knob, value in enumerate(tune or ()):
@@ -58,7 +65,7 @@ def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
     N = B * H * W
     dtype = w.dtype if dtype is None else dtype
     print(f"[gpu] conv3x3 {w.name} C={C} B={B} H={H} W={W} dtype={dtype} tune={tune} {tag}", flush=True)
-    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = make_mask(w)
     for knob, value in enumerate(tune or ()):
         rb.rbgp_mask_tune(mask, knob, value)
     stream = torch.cuda.current_stream().cuda_stream
@@ -91,7 +98,7 @@ def library_spmm_transposed(w, vals_lib, dO_lib, kernel=rb.KERNEL_AUTO, tune=Non
     import torch
     N = dO_lib.shape[1]
     print(f"[gpu] transposed {w.name} N={N} kernel={kernel} tune={tune} ld_pad={ld_pad} {tag}", flush=True)
-    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = make_mask(w)
     mask_t = rb.rbgp_mask_transpose(mask)
     if kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask_t, kernel)
@@ -118,7 +125,7 @@ def library_sddmm(w, dO_lib, I_lib, kernel=rb.KERNEL_AUTO, ld_pad=0, calls=1, ta
     import torch
     N = I_lib.shape[1]
     print(f"[gpu] sddmm {w.name} N={N} kernel={kernel} ld_pad={ld_pad} {tag}", flush=True)
-    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = make_mask(w)
     if kernel != rb.KERNEL_AUTO:
         rb.rbgp_mask_set_kernel(mask, kernel)
     stream = torch.cuda.current_stream().cuda_stream
@@ -156,7 +163,7 @@ def backward_inputs(w, N=None):
 
 def family_covers(w, kernel):
     """Whether a kernel family accepts this mask (host-side query, no GPU call)."""
-    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = make_mask(w)
     try:
         rb.rbgp_mask_set_kernel(mask, kernel)
     except rb.RbgpError:

@@ -264,3 +264,73 @@ def test_sddmm_argument_checks_need_no_gpu():
     assert lib.rbgp_sddmm(mask.handle, 0, w.M, w.K, 8, 258, 8, 256, 8, 256, None) == rb.ESHAPE     # misaligned
     assert lib.rbgp_sddmm(mask.handle, 7, w.M, w.K, 8, 256, 8, 256, 8, 256, None) == rb.EINVAL
     assert lib.rbgp_sddmm(None, 0, w.M, w.K, 8, 256, 8, 256, 8, 256, None) == rb.EINVAL
+
+
+# ---------------------------------------------------------------- more than four base graphs
+K_MASKS = [
+    # rows, cols, row_deg, roles
+    ((2, 2, 2, 4, 2, 2), (4, 2, 2, 8, 3, 3), (2, 1, 2, 4, 3, 3), (0, 0, 1, 2, 3, 3)),   # two sparse graphs in G_o, 3 x 3 taps
+    ((4, 2, 4), (8, 2, 4), (2, 2, 2), (0, 1, 2)),                                       # three: no G_b
+    ((4, 4, 2, 2, 3), (4, 8, 2, 4, 1), (2, 4, 2, 2, 1), (0, 2, 2, 2, 3)),                # three graphs in G_i, none in G_r
+    ((8,), (16,), (4,), (2,)),                                                          # a single sparse graph
+]
+
+
+@pytest.mark.parametrize("case", K_MASKS, ids=lambda c: "x".join(map(str, c[0])))
+def test_general_k_mask_is_the_product_of_its_base_graphs(case):
+    rows, cols, deg, roles = case
+    seed = 11
+    mask = rb.rbgp_make_mask_k(rows, cols, deg, roles, seed)
+    Bs, infos = orc.sample_factors(rows, cols, deg, seed)
+    dense = orc.kron_mask(Bs)
+    assert np.array_equal(rb.rbgp_mask_dense(mask), dense)
+    sh = rb.rbgp_mask_shape(mask)
+    assert (sh["M"], sh["K"]) == dense.shape and sh["rowdeg"] == int(dense[0].sum())
+    # canonical order = ascending column per row
+    assert np.array_equal(rb.rbgp_mask_columns(mask).reshape(sh["M"], -1), orc.canonical_columns(dense))
+    # the base graphs, one by one
+    assert rb.rbgp_mask_num_base(mask) == len(rows)
+    for i, (B, info) in enumerate(zip(Bs, infos)):
+        g = rb.rbgp_mask_base(mask, i)
+        assert (g["rows"], g["cols"], g["deg"], g["role"]) == (rows[i], cols[i], deg[i], roles[i])
+        assert np.array_equal(g["adj"], orc.adjacency_lists(B))
+        assert g["status"] == info["status"] and g["tries"] == info["tries"]
+        assert math.isclose(g["sigma1"], info["sigma1"], rel_tol=1e-9)
+        assert math.isclose(g["sigma2"], info["sigma2"], rel_tol=1e-7, abs_tol=1e-9)
+    # the four factors of the kernels' view: products of the base graphs of each role
+    for role in range(4):
+        mine = [B for B, r in zip(Bs, roles) if r == role]
+        F = orc.kron_mask(mine) if mine else np.ones((1, 1), dtype=np.uint8)
+        r_, c_, d_, adj = rb.rbgp_mask_factor(mask, role)
+        assert (r_, c_) == F.shape and np.array_equal(adj, orc.adjacency_lists(F))
+        sp = rb.rbgp_mask_spectrum(mask, role)
+        sv = np.linalg.svd(F.astype(np.float64), compute_uv=False)
+        assert math.isclose(sp["sigma1"], sv[0], rel_tol=1e-9)
+        assert math.isclose(sp["sigma2"], sv[1] if sv.size > 1 else 0.0, rel_tol=1e-7, abs_tol=1e-7)
+        if len(mine) > 1 and not all(int(B.min()) == 1 for B in mine):
+            assert sp["status"] in (rb.SPEC_PRODUCT, rb.SPEC_DEGENERATE)
+    # transposing keeps the base graphs (transposed)
+    mt = rb.rbgp_mask_transpose(mask)
+    assert rb.rbgp_mask_num_base(mt) == len(rows)
+    assert np.array_equal(rb.rbgp_mask_base(mt, 0)["adj"], orc.adjacency_lists(Bs[0].T.copy()))
+
+
+def test_four_base_graphs_in_order_is_rbgp_make_mask():
+    w = wl.VGG19_CONV5
+    a = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 3)
+    b = rb.rbgp_make_mask_k(w.rows, w.cols, w.row_deg, (0, 1, 2, 3), 3)
+    assert np.array_equal(rb.rbgp_mask_columns(a), rb.rbgp_mask_columns(b))
+    for i in range(4):
+        assert rb.rbgp_mask_spectrum(a, i) == rb.rbgp_mask_spectrum(b, i)
+
+
+def test_general_k_argument_checks():
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_make_mask_k((2, 2), (2, 2), (2, 2), (1, 0), 1)          # roles must not decrease
+    assert ei.value.code == rb.EINVAL
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_make_mask_k((2, 2), (2, 2), (2, 2), (0, 4), 1)          # role out of range
+    assert ei.value.code == rb.EINVAL
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_make_mask_k((2,) * 17, (2,) * 17, (2,) * 17, (0,) * 17, 1)
+    assert ei.value.code == rb.EINVAL

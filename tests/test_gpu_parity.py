@@ -364,3 +364,35 @@ def test_random_masks_with_library_defaults(dtype):
         err = orc.normalised_error(out, ref, den)
         assert err <= gh.TOL[dtype], (rows, cols, deg, N, kernel, err)
     assert rb.KERNEL_MFMA_REG in used and len(used) >= 2, used
+
+
+# ------------------------------------------------------------------ more than four base graphs
+K_WORKLOADS = [
+    wl.Workload("k6_two_sparse_in_go_taps_3x3", (2, 2, 2, 4, 2, 2), (4, 2, 2, 8, 3, 3), (2, 1, 2, 4, 3, 3), 200, wl.F32,
+                91, 92, 93, 1.0, roles=(0, 0, 1, 2, 3, 3)),
+    wl.Workload("k5_three_in_gi", (4, 4, 2, 2, 3), (4, 8, 2, 4, 1), (2, 4, 2, 2, 1), 136, wl.F32,
+                94, 95, 96, 1.0, roles=(0, 2, 2, 2, 3)),
+    wl.Workload("k3_no_gb", (4, 2, 4), (8, 2, 4), (2, 2, 2), 72, wl.F32, 97, 98, 99, 1.0, roles=(0, 1, 2)),
+    wl.Workload("k5_sparse_gr", (4, 2, 2, 4, 2), (4, 4, 2, 4, 2), (2, 2, 2, 2, 2), 100, wl.F32,
+                100, 101, 102, 1.0, roles=(0, 1, 1, 2, 3)),          # G_r not complete: generic kernel
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("w", K_WORKLOADS, ids=lambda w: w.name)
+def test_masks_of_more_than_four_base_graphs(w, dtype):
+    """Section 5: a mask is configured by the number of base graphs and their types; the library
+    folds them into the four factors of its kernels."""
+    w = replace(w, dtype=dtype)
+    err = gh.check_parity(w)
+    if "sparse_gr" not in w.name:
+        assert gh.family_covers(w, REG)
+        gh.check_parity(w, kernel=REG, expect_kernel=REG)
+    gh.check_parity(w, kernel=GEN)
+    # backward products of the same masks
+    lib, f32 = gh.backward_inputs(w)
+    dI_ref, dI_den, dW_ref, dW_den = gh.oracle_backward(w, *f32)
+    dI, _ = gh.library_spmm_transposed(w, lib[0], lib[2])
+    assert orc.normalised_error(dI, dI_ref, dI_den) <= gh.TOL[dtype]
+    dW = gh.library_sddmm(w, lib[2], lib[1])
+    assert orc.normalised_error(dW, dW_ref, dW_den) <= gh.TOL[dtype]
