@@ -315,6 +315,9 @@ def main():
     ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ld-pad", type=int, default=0,
+                    help="extra elements in the leading dimension of I and O (rbgp_spmm only): a row stride that is "
+                         "not a multiple of 4 KiB spreads the rows of a stage over more memory channels")
     ap.add_argument("--fused-conv", action="store_true",
                     help="time rbgp_conv3x3 (3x3 convolution with the lowering folded into the loads, fp32) on the "
                          "workload's layer instead of rbgp_spmm on the lowered input")
@@ -397,11 +400,15 @@ def main():
         set_bytes = Xp.nbytes + w.M * w.N * 4
         I0 = torch.from_numpy(Xp).to(dev)
     else:
-        set_bytes = w.K * w.N * w.in_bytes + w.M * w.N * 4
-        I0 = torch.from_numpy(I_lib.view(np.int16) if bf16 else I_lib).to(dev)
+        ld = w.N + args.ld_pad
+        set_bytes = (w.K * w.in_bytes + w.M * 4) * ld
+        I_pad = np.zeros((w.K, ld), dtype=I_lib.dtype)
+        I_pad[:, :w.N] = I_lib
+        I0 = torch.from_numpy(I_pad.view(np.int16) if bf16 else I_pad).to(dev)
     nsets = args.sets if args.sets > 0 else max(2, min(16, -(-512 * 2**20 // set_bytes)))
     Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
-    Os = [torch.empty((w.M, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+    ldO = w.N if args.fused_conv else w.N + args.ld_pad
+    Os = [torch.empty((w.M, ldO), dtype=torch.float32, device=dev) for _ in range(nsets)]
 
     def step(i):
         j = i % nsets
@@ -409,8 +416,8 @@ def main():
             rb.rbgp_conv3x3(mask, w.dtype, w.M, w.K // 9, B, H, W, packed.data_ptr(), Is[j].data_ptr(),
                             Os[j].data_ptr(), w.N, stream)
         else:
-            rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), w.N,
-                         Os[j].data_ptr(), w.N, stream)
+            rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), ldO,
+                         Os[j].data_ptr(), ldO, stream)
 
     for i in range(args.warmup):
         step(i)
@@ -452,10 +459,11 @@ def main():
            "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "density": w.density,
                       "factors_rows": list(w.rows), "factors_cols": list(w.cols), "factors_row_deg": list(w.row_deg),
                       "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "tune": args.tune or "default",
-                      "buffer_sets": nsets, "entry_point": "rbgp_conv3x3" if args.fused_conv else "rbgp_spmm"},
+                      "buffer_sets": nsets, "ld_pad": 0 if args.fused_conv else args.ld_pad,
+                      "entry_point": "rbgp_conv3x3" if args.fused_conv else "rbgp_spmm"},
            "roofline": roof}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, Os[0].cpu().numpy())
+        out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, Os[0].cpu().numpy()[:, :w.N])
     if not args.fused_conv and w.name in wl.CONV_GEOMETRY:
         out["fused_conv3x3"] = fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream,
                                                check=not args.no_cpu_baseline)

@@ -100,3 +100,26 @@ def test_masks_outside_rbgp4_roles_take_the_plain_kernels():
 def test_weight_gradient_bf16_odd_leading_dimension():
     w = wl.Workload("bwd_odd_ld", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 77, wl.BF16, 44, 45, 46, 1.0)
     _check_backward(w, data=False)
+
+
+def test_pack_transposed_from_device_values_matches_host_values():
+    """The same kept values, resident on the device in the forward mask's order, packed for both products."""
+    import torch
+    w = wl.Workload("bwd_devpack", (4, 2, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9), 64, wl.F32, 54, 55, 56, 1.0)
+    mask = gh.make_mask(w)
+    mask_t = rb.rbgp_mask_transpose(mask)
+    vals = wl.kept_weights(w).reshape(-1)
+    stream = torch.cuda.current_stream().cuda_stream
+    nbytes = rb.rbgp_packed_bytes(mask_t, w.dtype)
+    a = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    b = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    rb.rbgp_pack_transposed(mask_t, w.dtype, vals, a.data_ptr(), stream)
+    vals_d = torch.from_numpy(vals).to("cuda:0")
+    rb.rbgp_pack_transposed_device(mask_t, w.dtype, vals_d.data_ptr(), b.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    # and it is the transposed mask's own packing of the reordered values
+    c = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    rb.rbgp_pack(mask_t, w.dtype, np.ascontiguousarray(vals[rb.rbgp_transpose_order(mask)]), c.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.equal(a, c)
