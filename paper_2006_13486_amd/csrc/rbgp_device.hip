@@ -357,8 +357,28 @@ int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
     case RBGP_KERNEL_MFMA_REG: return reg_ok ? RBGP_KERNEL_MFMA_REG : RBGP_KERNEL_GENERIC;
     default: break;
   }
+  const bool lds_ok = mfma_covers(m);
+  if (reg_ok && lds_ok) {
+    // The register family multiplies whole clusters of MG tile rows at every tile of their union:
+    // where G_o is so sparse that the tile rows of a cluster share few tiles, most of those MFMA
+    // rows are padding.  That costs nothing while the product waits for HBM (WRN-40-4 group 1:
+    // 25 % useful rows, still the faster family) and decides where the matrix core is the bound
+    // (the 4096^3 SDMM of Table 2 with G_o at 1/8: 29 % useful rows, 253 us against 148 us on the
+    // LDS family, which has no clusters).  Estimate both times per column of I: an MFMA of a stage
+    // step serves 64 columns and issues every ~36 cycles on one of 1024 SIMDs at ~2.07 GHz; HBM
+    // streams ~5 TB/s.
+    const rbgp_reg_clusters &cl = m->reg_clusters;
+    int64_t walked = 0;
+    for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
+    const double useful = double(m->reg.TR) * m->d[0] * m->reg.NSTG / (double(walked) * m->reg.MG);
+    const double t_mfma = double(walked) * m->a[2] * m->reg.KC * 36.0 / (64.0 * 1024.0 * 2.07e9);
+    const double t_hbm = double(m->M + m->K) * 4.0 / 5.0e12;
+    // (VGG19 layers at density 1/16 with 27-42 % useful rows and t_mfma up to 1.3 t_hbm are still faster
+    // on the register family; the SDMM above has t_mfma = 8 t_hbm)
+    return useful < 0.45 && t_mfma > 4.0 * t_hbm ? RBGP_KERNEL_MFMA : RBGP_KERNEL_MFMA_REG;
+  }
   if (reg_ok) return RBGP_KERNEL_MFMA_REG;
-  return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
+  return lds_ok ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
 }
 
 int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
