@@ -101,9 +101,118 @@ std::vector<double> sym_eigenvalues(std::vector<double> A, int n) {
   return ev;
 }
 
+// Largest eigenvalue of the symmetric tridiagonal matrix (diagonal al, off-diagonal be) by bisection
+// on the number of eigenvalues above x (Sturm sequence of the leading principal minors).
+double tridiagonal_top(const std::vector<double> &al, const std::vector<double> &be) {
+  const int n = int(al.size());
+  double lo = al[0], hi = al[0];
+  for (int i = 0; i < n; ++i) {
+    const double r = (i ? std::fabs(be[size_t(i) - 1]) : 0) + (i + 1 < n ? std::fabs(be[size_t(i)]) : 0);
+    lo = std::min(lo, al[size_t(i)] - r);
+    hi = std::max(hi, al[size_t(i)] + r);
+  }
+  auto above = [&](double x) {   // eigenvalues > x
+    int count = 0;
+    double q = 1;
+    for (int i = 0; i < n; ++i) {
+      const double b2 = i ? be[size_t(i) - 1] * be[size_t(i) - 1] : 0;
+      q = al[size_t(i)] - x - (i ? b2 / q : 0);
+      if (q == 0) q = 1e-300;
+      if (q > 0) ++count;
+    }
+    return count;
+  };
+  for (int it = 0; it < 200 && hi - lo > 4e-16 * std::max(std::fabs(lo), std::fabs(hi)); ++it) {
+    const double mid = 0.5 * (lo + hi);
+    if (above(mid) >= 1) lo = mid; else hi = mid;
+  }
+  return 0.5 * (lo + hi);
+}
+
+// Second largest singular value of a large biregular graph.  Its largest one is sqrt(d_l d_r) with
+// constant singular vectors, so the second is the largest singular value on the complement of the
+// constant vector: Lanczos iteration on the smaller Gram operator restricted to that complement, with
+// full reorthogonalisation, until the top Ritz value stands still.  Returns false when it has not
+// converged within the step limit (the caller then takes the dense solver).
+bool lanczos_sigma2(const Bits &B, int a, int c, double *s2) {
+  const bool rows_small = a <= c;
+  const int n = rows_small ? a : c, other = rows_small ? c : a;
+  std::vector<std::vector<int>> nb_small(static_cast<size_t>(n)), nb_other(static_cast<size_t>(other));
+  for (int u = 0; u < a; ++u)
+    for (int v = 0; v < c; ++v)
+      if (B[size_t(u) * c + v]) {
+        nb_small[size_t(rows_small ? u : v)].push_back(rows_small ? v : u);
+        nb_other[size_t(rows_small ? v : u)].push_back(rows_small ? u : v);
+      }
+  std::vector<double> mid(static_cast<size_t>(other));
+  auto apply = [&](const std::vector<double> &x, std::vector<double> &y) {   // y = (Gram operator) x
+    for (int o = 0; o < other; ++o) {
+      double t = 0;
+      for (int i : nb_other[size_t(o)]) t += x[size_t(i)];
+      mid[size_t(o)] = t;
+    }
+    for (int i = 0; i < n; ++i) {
+      double t = 0;
+      for (int o : nb_small[size_t(i)]) t += mid[size_t(o)];
+      y[size_t(i)] = t;
+    }
+  };
+  auto deflate = [&](std::vector<double> &x) {   // remove the constant component
+    double mean = 0;
+    for (double t : x) mean += t;
+    mean /= n;
+    for (double &t : x) t -= mean;
+  };
+  const int max_steps = std::min(n - 1, 600);
+  std::vector<std::vector<double>> Q;
+  std::vector<double> al, be, q(static_cast<size_t>(n)), w(static_cast<size_t>(n));
+  uint64_t state = 0x243F6A8885A308D3ull;   // fixed start vector
+  for (double &t : q) {
+    state = state * 6364136223846793005ull + 1442695040888963407ull;
+    t = double(state >> 11) / double(1ull << 53) - 0.5;
+  }
+  deflate(q);
+  double nrm = 0;
+  for (double t : q) nrm += t * t;
+  nrm = std::sqrt(nrm);
+  for (double &t : q) t /= nrm;
+  double previous = -1;
+  for (int step = 0; step < max_steps; ++step) {
+    Q.push_back(q);
+    apply(q, w);
+    double alpha = 0;
+    for (int i = 0; i < n; ++i) alpha += w[size_t(i)] * q[size_t(i)];
+    al.push_back(alpha);
+    for (int pass = 0; pass < 2; ++pass) {   // orthogonal to everything so far, and to the constants
+      for (const std::vector<double> &p : Q) {
+        double dot = 0;
+        for (int i = 0; i < n; ++i) dot += w[size_t(i)] * p[size_t(i)];
+        for (int i = 0; i < n; ++i) w[size_t(i)] -= dot * p[size_t(i)];
+      }
+      deflate(w);
+    }
+    double beta = 0;
+    for (double t : w) beta += t * t;
+    beta = std::sqrt(beta);
+    const bool exhausted = beta <= 1e-12 * std::max(1.0, std::fabs(alpha));   // invariant subspace
+    if (exhausted || step % 10 == 9 || step + 1 == max_steps) {
+      const double top = tridiagonal_top(al, be);
+      if (exhausted || (previous >= 0 && std::fabs(top - previous) <= 1e-13 * std::max(top, 1.0))) {
+        *s2 = std::sqrt(std::max(0.0, top));
+        return true;
+      }
+      previous = top;
+    }
+    if (exhausted) break;
+    be.push_back(beta);
+    for (int i = 0; i < n; ++i) q[size_t(i)] = w[size_t(i)] / beta;
+  }
+  return false;
+}
+
 // Two largest singular values of the a x c 0/1 matrix B (eigenvalues of the
 // smaller Gram matrix).  lambda_2 of the bipartite graph equals sigma_2.
-void top_singular(const Bits &B, int a, int c, double *s1, double *s2) {
+void top_singular_dense(const Bits &B, int a, int c, double *s1, double *s2) {
   const bool rows_small = a <= c;
   const int n = rows_small ? a : c;
   std::vector<double> G(size_t(n) * n, 0.0);
@@ -119,6 +228,22 @@ void top_singular(const Bits &B, int a, int c, double *s1, double *s2) {
   std::vector<double> ev = sym_eigenvalues(G, n);
   *s1 = std::sqrt(std::max(0.0, ev[0]));
   *s2 = n > 1 ? std::sqrt(std::max(0.0, ev[1])) : 0.0;
+}
+
+// The same for a biregular graph with degrees (d, e) whose Ramanujan bound is `bound`: small graphs
+// take the dense solver; larger ones (the dense one costs O(n^3): minutes at a thousand vertices)
+// the iteration above, unless it fails to converge or lands so close to the bound that its last
+// digits would decide the test.
+void top_singular(const Bits &B, int a, int c, int d, int e, double bound, double *s1, double *s2) {
+  if (std::min(a, c) > 192) {
+    double s = 0;
+    if (lanczos_sigma2(B, a, c, &s) && std::fabs(s - bound) > 1e-6 * bound) {
+      *s1 = std::sqrt(double(d) * e);
+      *s2 = s;
+      return;
+    }
+  }
+  top_singular_dense(B, a, c, s1, s2);
 }
 
 int ilog2_exact(int q) {  // log2(q) if q is a power of two, else -1
@@ -205,7 +330,14 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
   std::vector<std::vector<char>> has(a1, std::vector<char>(c1, 0));
   for (int u = 0; u < a1; ++u)
     for (int j = 0; j < d1; ++j) has[u][m->adj[0][size_t(u / pl.fold) * d1 + j]] = 1;
-  for (int c = 0; c < ncl; ++c) {
+  // The searches below cost about a1^2 * c1 (greedy) and ncl^2 * U^3 * c1 per pass (local search):
+  // fine for the tile counts of a layer, not for base graphs of thousands of vertices, whose tile
+  // rows share few tiles whatever the grouping; those keep consecutive tile rows together.
+  const double greedy_cost = double(a1) * a1 * c1, search_cost = double(ncl) * ncl * U * U * U * c1;
+  const bool cheap = greedy_cost <= 2e8;
+  if (!cheap)
+    for (int u = 0; u < a1; ++u) members[size_t(u)] = u;
+  for (int c = 0; cheap && c < ncl; ++c) {
     std::vector<char> uni(c1, 0);
     for (int k = 0; k < U; ++k) {
       int best = -1, best_grow = 1 << 30;
@@ -233,7 +365,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
     }
     return n;
   };
-  for (bool improved = true; improved;) {
+  for (bool improved = cheap && search_cost <= 2e8; improved;) {
     improved = false;
     for (int ca = 0; ca < ncl; ++ca)
       for (int cb = ca + 1; cb < ncl; ++cb)
@@ -446,7 +578,7 @@ static int sample_base(int a, int c, int d, uint64_t seed, int index, int max_tr
     for (int t = 0; t < max_tries && !accepted; ++t) {
       Coins coins(seed, uint64_t(index), uint64_t(t));
       B = sample_biregular(a, c, lifts, coins);
-      top_singular(B, a, c, &g->sigma1, &g->sigma2);
+      top_singular(B, a, c, d, e, g->bound, &g->sigma1, &g->sigma2);
       g->tries = t + 1;
       if (std::min(d, e) == 1) {
         g->status = RBGP_SPEC_DEGENERATE;

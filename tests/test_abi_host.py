@@ -334,3 +334,20 @@ def test_general_k_argument_checks():
     with pytest.raises(rb.RbgpError) as ei:
         rb.rbgp_make_mask_k((2,) * 17, (2,) * 17, (2,) * 17, (0,) * 17, 1)
     assert ei.value.code == rb.EINVAL
+
+
+@pytest.mark.parametrize("shape", [(512, 1024, 16), (1024, 1024, 16), (768, 384, 6)], ids=lambda s: "x".join(map(str, s)))
+def test_base_graphs_of_a_thousand_vertices_match_the_oracle(shape):
+    """Appendix, "Generating RBG graph": graphs with thousands of vertices.  Above 192 vertices the
+    library finds sigma_2 by Lanczos iteration on the complement of the constant vector instead of
+    a dense eigen-solver; the oracle takes numpy's SVD.  Same samples accepted, same graph."""
+    a, c, d = shape
+    seed = 1
+    mask = rb.rbgp_make_mask((a, 1, 1, 1), (c, 1, 1, 1), (d, 1, 1, 1), seed)
+    Bs, infos = orc.sample_factors((a,), (c,), (d,), seed)
+    assert np.array_equal(rb.rbgp_mask_factor(mask, 0)[3], orc.adjacency_lists(Bs[0]))
+    sp = rb.rbgp_mask_spectrum(mask, 0)
+    assert sp["tries"] == infos[0]["tries"] and sp["status"] == infos[0]["status"]
+    assert math.isclose(sp["sigma1"], infos[0]["sigma1"], rel_tol=1e-10)
+    assert math.isclose(sp["sigma2"], infos[0]["sigma2"], rel_tol=1e-9)
+    assert sp["sigma2"] <= sp["bound"]
