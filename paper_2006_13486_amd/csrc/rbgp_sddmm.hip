@@ -52,6 +52,7 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef f32x4 f32x4_u __attribute__((aligned(4)));
 typedef bf16x8 bf16x8_u __attribute__((aligned(4)));
@@ -88,10 +89,12 @@ struct Operand<false> {
     for (int e = 0; e < 4; ++e) r[e] = e < valid ? p[e] : 0.f;
     return r;
   }
-  static __device__ __forceinline__ void mac(const reg &a, const reg &b, f32x4 &acc) {
+  typedef f32x4 accum;
+  static __device__ __forceinline__ void mac(const reg &a, const reg &b, accum &acc) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
   }
+  static __device__ __forceinline__ float total(const accum &acc, int i) { return acc[i]; }
 };
 template <>
 struct Operand<true> {
@@ -108,9 +111,11 @@ struct Operand<true> {
     for (int e = 0; e < 8; ++e) r.h[e] = e < valid ? p[e] : uint16_t(0);
     return r.v;
   }
-  static __device__ __forceinline__ void mac(const reg &a, const reg &b, f32x4 &acc) {
+  typedef f32x4 accum;
+  static __device__ __forceinline__ void mac(const reg &a, const reg &b, accum &acc) {
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
   }
+  static __device__ __forceinline__ float total(const accum &acc, int i) { return acc[i]; }
 };
 
 // RB: groups of 16 rows of dO per wave; NB: groups of 16 contraction steps per stage (KCR <= 16 * NB).
@@ -132,7 +137,15 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   // a tile in LDS: 16-byte slot 4 * row + (segment ^ ((row >> 1) & 3)); the exclusive-or spreads both
   // the writes (load layout) and the reads (operand layout) of eight consecutive lanes over all banks
   const int wslot = 4 * lr + (ls ^ ((lr >> 1) & 3)), rslot = 4 * j + (q ^ ((j >> 1) & 3));
+  // Workgroups go to the eight XCDs round-robin in launch order, and each XCD has its own L2: the
+  // a_i * RBG workgroups that share the rows of I of one (tile column, stage) take launch slots with
+  // the same remainder modulo 8 (when the number of such groups is a multiple of 8).
   int x = blockIdx.x;
+  const int per_group = p.a3 * p.RBG, groups = gridDim.x / per_group;
+  if (groups % 8 == 0) {
+    const int xcd = x % 8, slot = x / 8;
+    x = ((slot / per_group) * 8 + xcd) * per_group + slot % per_group;
+  }
   const int g = x % p.RBG; x /= p.RBG;
   const int u3 = x % p.a3; x /= p.a3;
   const int sg = x % p.NSTG, v1 = x / p.NSTG;
@@ -166,11 +179,13 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
     for (int i = 0; i < NL; ++i) d[i] = __builtin_bit_cast(reg, stage[wave][i][rslot]);
     __builtin_amdgcn_wave_barrier();
   };
-  f32x4 acc[RB][NB];
+  typename Op::accum acc[RB][NB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int b = 0; b < NB; ++b) acc[rb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int e = 0; e < int(sizeof(typename Op::accum) / sizeof(float)); ++e) acc[rb][b][e] = 0.f;
   auto mac_all = [&](const reg *o) {
 #pragma unroll
     for (int b = 0; b < NB; ++b)
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) red[wave][(rb * NB + b) * 4 + i][lane] = acc[rb][b][i];
+      for (int i = 0; i < 4; ++i) red[wave][(rb * NB + b) * 4 + i][lane] = Op::total(acc[rb][b], i);
   __syncthreads();
   const int r16 = 4 * q + wave, ri = r16 & (RS - 1);
   if (ri >= p.R) return;
