@@ -262,11 +262,27 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
         rb.rbgp_sddmm(mask, w.dtype, w.M, w.K, w.N, dOs[j].data_ptr(), w.N, Is[j].data_ptr(), w.N,
                       dWs[j].data_ptr(), stream)
 
+    steps_list = [("backward_data", data_step, w.M * w.N * w.in_bytes + w.K * w.N * 4 + w.nnz * w.in_bytes),
+                  ("weight_gradient", weight_step, (w.M + w.K) * w.N * w.in_bytes + w.nnz * 4)]
+    geom = wl.CONV_GEOMETRY.get(w.name)
+    if geom and (not bf16 or geom[2] % 8 == 0):
+        # the same gradient from the activations themselves (the lowered input is never stored)
+        B, H, W = geom
+        X = wl.conv_activations(w, B, H, W)
+        Xbits = wl.to_bf16_bits(X) if bf16 else None
+        X_f32 = wl.bf16_bits_as_f32(Xbits) if bf16 else X
+        Xp = wl.zero_padded(Xbits).view(np.int16) if bf16 else wl.zero_padded(X)
+        Xs = [torch.from_numpy(Xp).to(dev) for _ in range(nsets)]
+
+        def fused_step(i):
+            j = i % nsets
+            rb.rbgp_conv3x3_sddmm(mask, w.dtype, w.M, w.K // 9, B, H, W, dOs[j].data_ptr(), w.N, Xs[j].data_ptr(),
+                                  dWs[j].data_ptr(), stream)
+        steps_list.append(("weight_gradient_fused_conv3x3", fused_step,
+                           w.M * w.N * w.in_bytes + Xp.nbytes + w.nnz * 4))
     out = {}
-    for name, step, abytes in (
-            ("backward_data", data_step, w.M * w.N * w.in_bytes + w.K * w.N * 4 + w.nnz * w.in_bytes),
-            ("weight_gradient", weight_step, (w.M + w.K) * w.N * w.in_bytes + w.nnz * 4)):
-        if only and name != only:
+    for name, step, abytes in steps_list:
+        if only and name != only and not (only == "weight_gradient" and name.startswith("weight_gradient")):
             continue
         for i in range(warmup):
             step(i)
@@ -279,7 +295,8 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
         torch.cuda.synchronize()
         ms = ev0.elapsed_time(ev1) / steps
         tf = w.flops / (ms * 1e-3) / 1e12
-        out[name] = {"entry_point": "rbgp_spmm on rbgp_mask_transpose" if name == "backward_data" else "rbgp_sddmm",
+        out[name] = {"entry_point": {"backward_data": "rbgp_spmm on rbgp_mask_transpose", "weight_gradient": "rbgp_sddmm",
+                                     "weight_gradient_fused_conv3x3": "rbgp_conv3x3_sddmm"}[name],
                      "ms": ms, "value": tf, "unit": "TFLOP/s", "frac_of_fp32_mfma_peak": tf / PEAK_F32_TFLOPS,
                      "algorithmic_bytes": abytes, "algorithmic_gbs": abytes / (ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": abytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "steps": steps, "buffer_sets": nsets}
@@ -295,8 +312,16 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
             sub = np.ascontiguousarray(dO_f32[:, :ncols])
             ref, den = naive_c.spmm(mT, WT, sub), naive_c.spmm_abs(mT, WT, sub)
             out["backward_data"]["parity_err"] = orc.normalised_error(dIs[0].cpu().numpy()[:, :ncols], ref, den)
-        if "weight_gradient" in out:     # sampled rows of dW (every one needs the whole batch)
-            rows = np.unique(np.linspace(0, w.M - 1, 48).astype(np.int64))
+        rows = np.unique(np.linspace(0, w.M - 1, 48).astype(np.int64))   # sampled rows of dW (each needs the whole batch)
+        if "weight_gradient_fused_conv3x3" in out:     # (timed last: dWs hold its result)
+            I_x = orc.im2col_3x3(X_f32)
+            ref = orc.sddmm_definition(dense_mask[rows], dO_f32[rows], I_x)
+            den = orc.sddmm_definition(dense_mask[rows], np.abs(dO_f32[rows]), np.abs(I_x))
+            got = dWs[0].cpu().numpy().reshape(w.M, w.rowdeg)[rows]
+            out["weight_gradient_fused_conv3x3"]["parity_err"] = orc.normalised_error(got, ref, den)
+        if "weight_gradient" in out:
+            weight_step(0)
+            torch.cuda.synchronize()
             ref = orc.sddmm_definition(dense_mask[rows], dO_f32[rows], I_f32)
             den = orc.sddmm_definition(dense_mask[rows], np.abs(dO_f32[rows]), np.abs(I_f32))
             got = dWs[0].cpu().numpy().reshape(w.M, w.rowdeg)[rows]

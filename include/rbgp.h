@@ -270,6 +270,17 @@ int rbgp_conv3x3(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_o
                  int64_t images, int64_t height, int64_t width, const void *dev_packed, const void *dev_X,
                  void *dev_O, int64_t ldO, void *hip_stream);
 
+/* Weight gradient of the fused 3x3 convolution: rbgp_sddmm with I = im2col(X) never stored, i.e.
+ * dW[m][t] = sum_n dO[m][n] * X[c][image][y + dy][x + dx] for the kept column k = 9 * c + 3 * (dy + 1) + (dx + 1)
+ * (same layouts and conventions as rbgp_conv3x3 and rbgp_sddmm: dev_X zero-padded
+ * [channels_in][images][height + 2][width + 2], below 2 GiB; dev_dO M x N with N = images * height * width;
+ * dev_dW nnz fp32 in canonical order).  Runs on the MFMA kernel of rbgp_sddmm only: EUNSUPPORTED for
+ * masks outside the RBGP_KERNEL_MFMA_REG family or with |G_b.V| != 9 complete; ESHAPE unless width is
+ * a multiple of 4 (fp32) or 8 (bf16) and the sizes match the mask.  Asynchronous on `hip_stream`. */
+int rbgp_conv3x3_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
+                       int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
+                       const void *dev_X, float *dev_dW, void *hip_stream);
+
 /* Static description of an error code / of the last HIP failure in this thread. */
 const char *rbgp_strerror(int code);
 const char *rbgp_last_hip_error(void);

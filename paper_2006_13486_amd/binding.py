@@ -56,6 +56,7 @@ SIGNATURES = {
     "rbgp_spmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                  _vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]),
     "rbgp_conv3x3": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, _vp, _vp, ctypes.c_int64, _vp]),
+    "rbgp_conv3x3_sddmm": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, ctypes.c_int64, _vp, _vp, _vp]),
     "rbgp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "rbgp_last_hip_error": (ctypes.c_char_p, []),
 }
@@ -263,6 +264,12 @@ def rbgp_conv3x3(mask: Mask, dtype: int, channels_out: int, channels_in: int, im
                  dev_packed_ptr: int, dev_X_ptr: int, dev_O_ptr: int, ldO: int, stream: int = 0):
     _check(load().rbgp_conv3x3(mask.handle, dtype, channels_out, channels_in, images, height, width,
                                dev_packed_ptr, dev_X_ptr, dev_O_ptr, ldO, stream), "rbgp_conv3x3")
+
+
+def rbgp_conv3x3_sddmm(mask: Mask, dtype: int, channels_out: int, channels_in: int, images: int, height: int, width: int,
+                       dev_dO_ptr: int, ld_dO: int, dev_X_ptr: int, dev_dW_ptr: int, stream: int = 0):
+    _check(load().rbgp_conv3x3_sddmm(mask.handle, dtype, channels_out, channels_in, images, height, width,
+                                     dev_dO_ptr, ld_dO, dev_X_ptr, dev_dW_ptr, stream), "rbgp_conv3x3_sddmm")
 
 
 def rbgp_spmm(mask: Mask, dtype: int, M: int, K: int, N: int, dev_packed_ptr: int, dev_I_ptr: int, ldI: int,

@@ -663,4 +663,26 @@ int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out,
                          static_cast<float *>(dev_O), ldO, hip_stream, &geom);
 }
 
+int rbgp_conv3x3_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
+                       int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
+                       const void *dev_X, float *dev_dW, void *hip_stream) {
+  if (!m) return RBGP_EINVAL;
+  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  const bool bf16 = dtype == RBGP_BF16_F32ACC;
+  if (images <= 0 || height <= 0 || width <= 0 || (width % (bf16 ? 8 : 4))) return RBGP_ESHAPE;
+  const int64_t N = images * height * width;
+  if (channels_out != m->M || 9 * channels_in != m->K || ld_dO < N) return RBGP_ESHAPE;
+  if (m->c[3] != 9 || m->d[3] != 9 || m->kernel_choice == RBGP_KERNEL_GENERIC || !rbgp_reg_covers(m))
+    return RBGP_EUNSUPPORTED;
+  if (!dev_dO || !dev_X || !dev_dW) return RBGP_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dev_dO) | reinterpret_cast<uintptr_t>(dev_X) | reinterpret_cast<uintptr_t>(dev_dW)) & 3)
+    return RBGP_ESHAPE;
+  if (bf16 && ld_dO % 2) return RBGP_ESHAPE;
+  int rc = ensure_device(m);
+  if (rc) return rc;
+  const rbgp_conv_geometry geom = {images, height, width};
+  return rbgp_sddmm_launch(m, &m->dev->sddmm_state, m->dev->adj, true, bf16, N, dev_dO, ld_dO, dev_X, N, dev_dW,
+                           hip_stream, &geom);
+}
+
 }  // extern "C"

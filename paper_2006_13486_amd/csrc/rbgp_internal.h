@@ -124,8 +124,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
                     const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
 // weight-gradient kernels (rbgp_sddmm.hip); use_mfma needs rbgp_reg_covers(m)
+// conv != nullptr (needs use_mfma): I is the zero-padded activation tensor of a 3x3 convolution, ldI is ignored
 int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
-                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream);
+                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream,
+                      const rbgp_conv_geometry *conv = nullptr);
 void rbgp_sddmm_release(void *state);
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);

@@ -70,6 +70,13 @@ struct SddmmParams {
   int NSTG, stage_rows;     // stages per tile; rows of I between the bases of consecutive stages (VC * c_i * c_b)
   int tile_rows;            // rows of I per tile column (c_r * c_i * c_b)
   int a2, a3, a4, R, lgRS, MG, KCR, rowdeg;
+  // Fused 3x3 convolution (CONV kernels): I is not materialised; row k = 9 * channel + tap of it is read
+  // from the zero-padded activations X[channel][image][H + 2][W + 2] (pointer I).
+  const int32_t *colbase;   // element offset, inside a channel of X, of the first pixel of every group of
+                            //   columns one lane loads (4 fp32 / 8 bf16), padded with valid offsets
+  int64_t chan_elems;       // elements of one channel of X
+  int64_t x_bytes;          // size of X
+  int conv_w2;              // W + 2
 };
 
 template <bool BF16>
@@ -121,7 +128,7 @@ struct Operand<true> {
 // RB: groups of 16 rows of dO per wave; NB: groups of 16 contraction steps per stage (KCR <= 16 * NB).
 // grid.x = ((v_o * NSTG + stage) * a_i + u_i) * RBG + group of RB row groups; grid.y = workgroups
 // along the batch.
-template <int RB, int NB, bool BF16>
+template <int RB, int NB, bool BF16, bool CONV>
 __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   typedef Operand<BF16> Op;
   typedef typename Op::reg reg;
@@ -162,13 +169,35 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
     off[rb] = row * p.ld_dO + ls * CPL;
   }
 #pragma unroll
-  for (int b = 0; b < NB; ++b)   // padding steps read row 0 of the stage
-    off[RB + b] = int64_t(base + p.rowtab[(u3 * NB + b) * 16 + lr]) * p.ldI + ls * CPL;
+  for (int b = 0; b < NB; ++b) {   // padding steps read row 0 of the stage
+    const int k = base + p.rowtab[(u3 * NB + b) * 16 + lr];
+    if constexpr (CONV) {   // channel k / 9, tap k % 9 = 3 * (dy + 1) + (dx + 1): the shift of the tap inside the channel
+      const int tap = k % 9;
+      off[RB + b] = int64_t(k / 9) * p.chan_elems + (tap / 3 - 1) * p.conv_w2 + (tap % 3 - 1);
+    } else {
+      off[RB + b] = int64_t(k) * p.ldI + ls * CPL;
+    }
+  }
+  // CONV: where this lane's group of columns starts inside a channel (columns are pixels in image order)
+  auto pixel = [&](int64_t n) { return CONV ? int64_t(p.colbase[n / CPL + ls]) : n; };
+  // CONV: the tap shifts leave the 16-byte loads of X aligned to an element only (2 bytes for bf16), so
+  // they go through a buffer descriptor (any alignment, 32-bit byte offsets: X is below 2 GiB)
+  constexpr int ES = BF16 ? 2 : 4;
+  __amdgpu_buffer_rsrc_t xrsrc;
+  if constexpr (CONV)
+    xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.I), 0, int(p.x_bytes), 0x00020000);
+  auto load_x = [&](int64_t elem) {
+    return __builtin_bit_cast(reg, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, int(elem * ES), 0, 0));
+  };
   auto load_all = [&](reg *r, int64_t n) {
 #pragma unroll
     for (int i = 0; i < RB; ++i) r[i] = Op::load(p.dO, off[i] + n);
+    const int64_t at = pixel(n);
 #pragma unroll
-    for (int i = RB; i < NL; ++i) r[i] = Op::load(p.I, off[i] + n);
+    for (int i = RB; i < NL; ++i) {
+      if constexpr (CONV) r[i] = load_x(off[i] + at);
+      else r[i] = Op::load(p.I, off[i] + at);
+    }
   };
   // load layout -> operand layout through this wave's tiles (LDS instructions of one wave execute in order)
   auto transpose_all = [&](reg *d, const reg *r) {
@@ -250,7 +279,13 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
     const int valid = left <= 0 ? 0 : left >= CPL ? CPL : int(left);
     reg r[NL], o[NL];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) r[i] = Op::load_tail(i < RB ? p.dO : p.I, off[i] + n, valid);
+    for (int i = 0; i < RB; ++i) r[i] = Op::load_tail(p.dO, off[i] + n, valid);
+    const int64_t at = pixel(n);   // (CONV: N is a multiple of the group, so `valid` is all or nothing)
+#pragma unroll
+    for (int i = RB; i < NL; ++i) {
+      if constexpr (CONV) r[i] = valid ? load_x(off[i] + at) : Op::zero();
+      else r[i] = Op::load_tail(p.I, off[i] + at, valid);
+    }
     transpose_all(o, r);
     mac_all(o);
   }
@@ -340,6 +375,8 @@ struct SddmmState {
   int EO = 0;
   float *partial = nullptr;
   size_t partial_bytes = 0;
+  int32_t *colbase[2] = {nullptr, nullptr};           // fused convolution, fp32 / bf16 groups
+  int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};    // images, height, width of colbase
 };
 
 template <typename T>
@@ -350,21 +387,22 @@ int upload(const std::vector<T> &h, T **d) {
 }
 
 typedef void (*sddmm_fn)(SddmmParams);
-template <int RB, bool BF16>
+template <int RB, bool BF16, bool CONV>
 sddmm_fn pick_nb(int NB) {
   switch (NB) {
-    case 1: return sddmm_reg<RB, 1, BF16>;
-    case 2: return sddmm_reg<RB, 2, BF16>;
-    case 3: return sddmm_reg<RB, 3, BF16>;
-    case 4: return sddmm_reg<RB, 4, BF16>;
-    case 5: return sddmm_reg<RB, 5, BF16>;
+    case 1: return sddmm_reg<RB, 1, BF16, CONV>;
+    case 2: return sddmm_reg<RB, 2, BF16, CONV>;
+    case 3: return sddmm_reg<RB, 3, BF16, CONV>;
+    case 4: return sddmm_reg<RB, 4, BF16, CONV>;
+    case 5: return sddmm_reg<RB, 5, BF16, CONV>;
   }
   return nullptr;
 }
+template <bool CONV>
 sddmm_fn find_kernel(int RB, int NB, bool bf16) {
   switch (RB) {
-    case 1: return bf16 ? pick_nb<1, true>(NB) : pick_nb<1, false>(NB);
-    case 2: return bf16 ? pick_nb<2, true>(NB) : pick_nb<2, false>(NB);
+    case 1: return bf16 ? pick_nb<1, true, CONV>(NB) : pick_nb<1, false, CONV>(NB);
+    case 2: return bf16 ? pick_nb<2, true, CONV>(NB) : pick_nb<2, false, CONV>(NB);
   }
   return nullptr;
 }
@@ -405,11 +443,15 @@ void rbgp_sddmm_release(void *state) {
   if (st->colpos) (void)hipFree(st->colpos);
   if (st->rowtab) (void)hipFree(st->rowtab);
   if (st->partial) (void)hipFree(st->partial);
+  for (int32_t *t : st->colbase)
+    if (t) (void)hipFree(t);
   delete st;
 }
 
 int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
-                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream) {
+                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream,
+                      const rbgp_conv_geometry *conv) {
+  if (conv && !use_mfma) return RBGP_EUNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const int64_t nnz = m->nnz;
   if (N == 0) {
@@ -453,7 +495,7 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   // waves at the layer sizes of the paper (measured: slower on every VGG19 / WRN shape tried)
   const int RB = groups >= 2 ? 2 : 1;
   const int RBG = (groups + RB - 1) / RB;
-  sddmm_fn fn = find_kernel(RB, NB, bf16);
+  sddmm_fn fn = conv ? find_kernel<true>(RB, NB, bf16) : find_kernel<false>(RB, NB, bf16);
   if (!fn) return RBGP_EUNSUPPORTED;
   // ranges of the batch: enough waves for a few per SIMD (1024 SIMDs), at least two iterations each
   const int cpi = bf16 ? 32 : 16;
@@ -476,6 +518,33 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
     }
   }
   SddmmParams p;
+  p.colbase = nullptr; p.chan_elems = 0; p.conv_w2 = 0; p.x_bytes = 0;
+  if (conv) {
+    const int64_t H = conv->height, W = conv->width, grp = bf16 ? 8 : 4;
+    int64_t *key = st->conv_key[bf16];
+    int32_t **cb = &st->colbase[bf16];
+    if (*cb && (key[0] != conv->images || key[1] != H || key[2] != W)) {
+      RBGP_HIP(hipFree(*cb));   // (waits for launches that still read the old table)
+      *cb = nullptr;
+    }
+    if (!*cb) {
+      // one entry per group of columns (pixels n .. n + grp - 1 of one image row), then enough valid
+      // entries for the lanes of a last, partly empty iteration
+      std::vector<int32_t> h(size_t((N + grp - 1) / grp + 8), int32_t(W + 3));
+      for (int64_t n = 0; n < N; n += grp) {
+        const int64_t img = n / (H * W), y = (n % (H * W)) / W, x = n % W;
+        h[size_t(n / grp)] = int32_t((img * (H + 2) + y + 1) * (W + 2) + x + 1);
+      }
+      int rc = upload(h, cb);
+      if (rc) return rc;
+      key[0] = conv->images; key[1] = H; key[2] = W;
+    }
+    p.colbase = *cb;
+    p.chan_elems = conv->images * (H + 2) * (W + 2);
+    p.conv_w2 = int(W + 2);
+    p.x_bytes = p.chan_elems * (m->K / 9) * (bf16 ? 2 : 4);
+    if (p.x_bytes >= (int64_t(1) << 31)) return RBGP_EUNSUPPORTED;
+  }
   p.dO = dO; p.I = I;
   p.out = nsplit > 1 ? st->partial : dW;
   p.colrows = st->colrows; p.colpos = st->colpos; p.rowtab = st->rowtab;

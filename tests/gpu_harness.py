@@ -140,6 +140,25 @@ def library_sddmm(w, dO_lib, I_lib, kernel=rb.KERNEL_AUTO, ld_pad=0, calls=1, ta
     return out[:w.M * w.rowdeg].reshape(w.M, w.rowdeg)
 
 
+def library_conv3x3_sddmm(w, dO_lib, X, tag=""):
+    """dW through rbgp_conv3x3_sddmm on X[C][B][H][W] (padded here: layout work, not arithmetic)."""
+    import torch
+    C, B, H, W = X.shape
+    N = B * H * W
+    print(f"[gpu] conv3x3 sddmm {w.name} C={C} B={B} H={H} W={W} dtype={w.dtype} {tag}", flush=True)
+    mask = make_mask(w)
+    stream = torch.cuda.current_stream().cuda_stream
+    Xp = wl.zero_padded(X)
+    X_d = torch.from_numpy(Xp.view(np.int16) if Xp.dtype == np.uint16 else Xp).to("cuda:0")
+    dO_d = _to_device(dO_lib, 0)
+    dW_d = torch.full((w.M * w.rowdeg + 64,), float("nan"), dtype=torch.float32, device="cuda:0")
+    rb.rbgp_conv3x3_sddmm(mask, w.dtype, w.M, C, B, H, W, dO_d.data_ptr(), N, X_d.data_ptr(), dW_d.data_ptr(), stream)
+    torch.cuda.synchronize()
+    out = dW_d.cpu().numpy()
+    assert np.all(np.isnan(out[w.M * w.rowdeg:])), "kernel wrote past the nnz values"
+    return out[:w.M * w.rowdeg].reshape(w.M, w.rowdeg)
+
+
 def oracle_backward(w, vals_f32, I_f32, dO_f32):
     """(dI, its denominators sum_m |W||dO|, dW, its denominators sum_n |dO||I|) from the oracle."""
     Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)

@@ -123,3 +123,53 @@ def test_pack_transposed_from_device_values_matches_host_values():
     rb.rbgp_pack(mask_t, w.dtype, np.ascontiguousarray(vals[rb.rbgp_transpose_order(mask)]), c.data_ptr(), stream)
     torch.cuda.synchronize()
     assert torch.equal(a, c)
+
+
+# ------------------------------------------------------------------ weight gradient of the fused 3x3 convolution
+CONV_GRAD_CASES = [
+    # workload (K = 9 * channels), images, height, width
+    (wl.Workload("cgrad_small", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.F32, 61, 62, 63, 1.0), 3, 4, 8),
+    (wl.Workload("cgrad_ragged", (4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 64, 65, 66, 1.0), 5, 3, 4),
+    (wl.Workload("cgrad_wide", (4, 2, 4, 1), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.F32, 67, 68, 69, 1.0), 2, 5, 32),
+    (wl.Workload("cgrad_pad54", (4, 2, 4, 1), (4, 1, 12, 9), (2, 1, 6, 9), 0, wl.F32, 74, 75, 76, 1.0), 2, 4, 8),
+    (wl.Workload("cgrad_bf16", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.BF16, 71, 72, 73, 1.0), 3, 5, 8),
+    (wl.Workload("cgrad_bf16_wide", (4, 2, 4, 1), (4, 2, 4, 9), (2, 2, 2, 9), 0, wl.BF16, 77, 78, 79, 1.0), 7, 3, 16),
+    (wl.VGG19_CONV5, 128, 4, 4),                                        # the headline layer
+    (replace(wl.VGG19_CONV3_BF16, name="cgrad_conv3_bf16"), 128, 8, 8),
+    (replace(wl.WRN_G1, name="cgrad_wrn_batch8"), 8, 32, 32),
+]
+
+
+@pytest.mark.parametrize("case", CONV_GRAD_CASES, ids=lambda c: c[0].name)
+def test_fused_conv3x3_weight_gradient_equals_sddmm_on_the_lowered_input(case):
+    w, B, H, W = case
+    w = replace(w, N=B * H * W)
+    X = wl.conv_activations(w, B, H, W)
+    dO = wl.output_gradients(w)
+    if w.dtype == wl.BF16:
+        Xl, dOl = wl.to_bf16_bits(X), wl.to_bf16_bits(dO)
+        X, dO = wl.bf16_bits_as_f32(Xl), wl.bf16_bits_as_f32(dOl)
+    else:
+        Xl, dOl = X, dO
+    got = gh.library_conv3x3_sddmm(w, dOl, Xl)
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = orc.kron_mask(Bs)
+    I = orc.im2col_3x3(X)
+    ref, den = orc.sddmm_definition(mask, dO, I), orc.sddmm_definition(mask, np.abs(dO), np.abs(I))
+    err = orc.normalised_error(got, ref, den)
+    print(f"[gpu]   normalised error {err:.3e}", flush=True)
+    assert err <= gh.TOL[w.dtype], err
+
+
+def test_fused_conv3x3_weight_gradient_argument_checks():
+    w = wl.Workload("cgrad_args", (4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9), 0, wl.F32, 1, 2, 3, 1.0)
+    mask = gh.make_mask(w)
+    lib = rb.load()
+    C = w.K // 9
+    assert lib.rbgp_conv3x3_sddmm(mask.handle, 0, w.M, C, 2, 4, 6, 256, 48, 256, 256, None) == rb.ESHAPE      # width % 4
+    assert lib.rbgp_conv3x3_sddmm(mask.handle, 1, w.M, C, 2, 4, 4, 256, 32, 256, 256, None) == rb.ESHAPE      # bf16: width % 8
+    assert lib.rbgp_conv3x3_sddmm(mask.handle, 0, w.M, C + 1, 2, 4, 4, 256, 32, 256, 256, None) == rb.ESHAPE
+    assert lib.rbgp_conv3x3_sddmm(mask.handle, 0, w.M, C, 2, 4, 4, 256, 16, 256, 256, None) == rb.ESHAPE      # ld_dO < N
+    assert lib.rbgp_conv3x3_sddmm(mask.handle, 0, w.M, C, 2, 4, 4, 256, 32, None, 256, None) == rb.EINVAL
+    tiny = gh.make_mask(wl.TINY)                                                                             # |G_b.V| != 9
+    assert lib.rbgp_conv3x3_sddmm(tiny.handle, 0, wl.TINY.M, wl.TINY.K // 9, 1, 1, 4, 256, 4, 256, 256, None) in (rb.ESHAPE, rb.EUNSUPPORTED)
