@@ -280,9 +280,24 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
                                   dWs[j].data_ptr(), stream)
         steps_list.append(("weight_gradient_fused_conv3x3", fused_step,
                            w.M * w.N * w.in_bytes + Xp.nbytes + w.nnz * 4))
+        # dX: the transposed convolution of dO through rbgp_conv3x3 (the lowered gradient is never stored)
+        mask_x = rb.rbgp_mask_conv3x3_transpose(mask)
+        packed_x = torch.zeros(rb.rbgp_packed_bytes(mask_x, w.dtype), dtype=torch.uint8, device=dev)
+        rb.rbgp_pack_transposed(mask_x, w.dtype, np.ascontiguousarray(vals_lib), packed_x.data_ptr(), stream)
+        dOp = wl.zero_padded(np.ascontiguousarray(dO_lib).reshape(w.M, B, H, W))
+        dOps = [torch.from_numpy(dOp.view(np.int16) if bf16 else dOp).to(dev) for _ in range(nsets)]
+        dXs = [torch.empty((w.K // 9, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+        def input_step(i):
+            j = i % nsets
+            rb.rbgp_conv3x3(mask_x, w.dtype, w.K // 9, w.M, B, H, W, packed_x.data_ptr(), dOps[j].data_ptr(),
+                            dXs[j].data_ptr(), w.N, stream)
+        steps_list.append(("input_gradient_fused_conv3x3", input_step,
+                           dOp.nbytes + (w.K // 9) * w.N * 4 + w.nnz * w.in_bytes))
     out = {}
     for name, step, abytes in steps_list:
-        if only and name != only and not (only == "weight_gradient" and name.startswith("weight_gradient")):
+        if only and name != only and not (only == "weight_gradient" and name.startswith("weight_gradient")) \
+                and not (only == "backward_data" and name.startswith("input_gradient")):
             continue
         for i in range(warmup):
             step(i)
@@ -296,7 +311,8 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
         ms = ev0.elapsed_time(ev1) / steps
         tf = w.flops / (ms * 1e-3) / 1e12
         out[name] = {"entry_point": {"backward_data": "rbgp_spmm on rbgp_mask_transpose", "weight_gradient": "rbgp_sddmm",
-                                     "weight_gradient_fused_conv3x3": "rbgp_conv3x3_sddmm"}[name],
+                                     "weight_gradient_fused_conv3x3": "rbgp_conv3x3_sddmm",
+                                     "input_gradient_fused_conv3x3": "rbgp_conv3x3 on rbgp_mask_conv3x3_transpose"}[name],
                      "ms": ms, "value": tf, "unit": "TFLOP/s", "frac_of_fp32_mfma_peak": tf / PEAK_F32_TFLOPS,
                      "algorithmic_bytes": abytes, "algorithmic_gbs": abytes / (ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": abytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "steps": steps, "buffer_sets": nsets}
@@ -312,6 +328,12 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
             sub = np.ascontiguousarray(dO_f32[:, :ncols])
             ref, den = naive_c.spmm(mT, WT, sub), naive_c.spmm_abs(mT, WT, sub)
             out["backward_data"]["parity_err"] = orc.normalised_error(dIs[0].cpu().numpy()[:, :ncols], ref, den)
+        if "input_gradient_fused_conv3x3" in out:      # whole dX: col2im of the oracle's W^T dO
+            mT, WT = np.ascontiguousarray(dense_mask.T), np.ascontiguousarray(Wd.T)
+            Bq, Hq, Wq = geom
+            ref = orc.col2im_3x3(naive_c.spmm(mT, WT, dO_f32), Bq, Hq, Wq).reshape(w.K // 9, -1)
+            den = orc.col2im_3x3(naive_c.spmm_abs(mT, WT, dO_f32), Bq, Hq, Wq).reshape(w.K // 9, -1)
+            out["input_gradient_fused_conv3x3"]["parity_err"] = orc.normalised_error(dXs[0].cpu().numpy(), ref, den)
         rows = np.unique(np.linspace(0, w.M - 1, 48).astype(np.int64))   # sampled rows of dW (each needs the whole batch)
         if "weight_gradient_fused_conv3x3" in out:     # (timed last: dWs hold its result)
             I_x = orc.im2col_3x3(X_f32)

@@ -210,7 +210,7 @@ int rbgp_transpose_order(const rbgp_mask_t *mask, int32_t *out);
 /* rbgp_pack / rbgp_pack_device for a mask made by rbgp_mask_transpose, with the values given in
  * the canonical order of the ORIGINAL mask (nnz elements): the same weights can be packed for the
  * forward product and for the backward data product without a reordering by the caller.
- * EINVAL for a mask that was not made by rbgp_mask_transpose. */
+ * EINVAL for a mask that was not made by rbgp_mask_transpose (or rbgp_mask_conv3x3_transpose). */
 int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values,
                          void *dev_packed, void *hip_stream);
 int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
@@ -280,6 +280,23 @@ int rbgp_conv3x3(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_o
 int rbgp_conv3x3_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
                        int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
                        const void *dev_X, float *dev_dW, void *hip_stream);
+
+/* Gradient of the fused 3x3 convolution with respect to its input.  With O = W_s x im2col(X), dX is
+ * again a 3x3 convolution (stride 1, zero padding 1), of dO, whose weights W'[c][9 m + tap'] =
+ * W_s[m][9 c + (8 - tap')] have the four-factor mask G_o^T (x) G_r^T (x) (G_i^T (x) J) (x) taps
+ * (J complete on (1, |G_b.U|) vertices).  This call builds that mask (host only, as
+ * rbgp_mask_transpose does for the plain product); then
+ *   rbgp_pack_transposed(mask_x, dtype, values in the canonical order of `mask`, packed_x, stream)
+ *   rbgp_conv3x3(mask_x, dtype, channels_in, channels_out, images, height, width, packed_x,
+ *                dO zero-padded [channels_out][images][height + 2][width + 2], dX as a channels_in x N matrix, ...)
+ * computes dX without the lowered gradient (9 x larger) ever being stored.  EUNSUPPORTED unless
+ * |G_b.V| = 9 complete. */
+int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *mask, rbgp_mask_t **out);
+
+/* For a mask made by rbgp_mask_transpose or rbgp_mask_conv3x3_transpose: out[s] (caller-owned host
+ * memory, nnz int32) = canonical index, in the mask it was made from, of the kept value that has
+ * canonical index s in this mask (what rbgp_pack_transposed applies).  EINVAL for other masks. */
+int rbgp_mask_original_order(const rbgp_mask_t *derived, int32_t *out);
 
 /* Static description of an error code / of the last HIP failure in this thread. */
 const char *rbgp_strerror(int code);

@@ -339,6 +339,22 @@ def im2col_3x3(X: np.ndarray) -> np.ndarray:
     return I
 
 
+def col2im_3x3(Z: np.ndarray, B: int, H: int, W: int) -> np.ndarray:
+    """Adjoint of im2col_3x3: Z[9*channel + 3*(dy+1) + (dx+1)][(image*H + y)*W + x] is
+    added to X[channel][image][y+dy][x+dx] wherever that pixel lies inside the image
+    (the gradient of the lowered input flows back to the activations)."""
+    C = Z.shape[0] // 9
+    X = np.zeros((C, B, H, W), dtype=np.float64)
+    for c in range(C):
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                z = Z[9 * c + 3 * (dy + 1) + (dx + 1)].reshape(B, H, W)
+                ys, ye = max(0, -dy), min(H, H - dy)
+                xs, xe = max(0, -dx), min(W, W - dx)
+                X[c, :, ys + dy:ye + dy, xs + dx:xe + dx] += z[:, ys:ye, xs:xe]
+    return X
+
+
 # --------------------------------------------------------------------------
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """IEEE float32 -> bfloat16 bit patterns (uint16), round-to-nearest-even."""

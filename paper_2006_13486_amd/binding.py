@@ -48,6 +48,8 @@ SIGNATURES = {
     "rbgp_pack": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_pack_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_mask_transpose": (ctypes.c_int, [_vp, ctypes.POINTER(_vp)]),
+    "rbgp_mask_conv3x3_transpose": (ctypes.c_int, [_vp, ctypes.POINTER(_vp)]),
+    "rbgp_mask_original_order": (ctypes.c_int, [_vp, _vp]),
     "rbgp_transpose_order": (ctypes.c_int, [_vp, _vp]),
     "rbgp_pack_transposed": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_pack_transposed_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
@@ -230,6 +232,18 @@ def rbgp_mask_transpose(mask: Mask) -> Mask:
     out = _vp()
     _check(load().rbgp_mask_transpose(mask.handle, ctypes.byref(out)), "rbgp_mask_transpose")
     return Mask(out)
+
+
+def rbgp_mask_conv3x3_transpose(mask: Mask) -> Mask:
+    out = _vp()
+    _check(load().rbgp_mask_conv3x3_transpose(mask.handle, ctypes.byref(out)), "rbgp_mask_conv3x3_transpose")
+    return Mask(out)
+
+
+def rbgp_mask_original_order(derived: Mask) -> np.ndarray:
+    out = np.empty(rbgp_mask_shape(derived)["nnz"], dtype=np.int32)
+    _check(load().rbgp_mask_original_order(derived.handle, out.ctypes.data), "rbgp_mask_original_order")
+    return out
 
 
 def rbgp_transpose_order(mask: Mask) -> np.ndarray:

@@ -798,6 +798,90 @@ int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
   return RBGP_OK;
 }
 
+// The mask of the transposed 3x3 convolution.  O = W_s x im2col(X) means
+//   O[m][y][x] = sum_{c, dy, dx} W[m][9c + 3(dy+1) + (dx+1)] X[c][y+dy][x+dx],
+// so the gradient with respect to X is again a 3x3 convolution, of dO:
+//   dX[c][y][x] = sum_{m, dy', dx'} W'[c][9m + 3(dy'+1) + (dx'+1)] dO[m][y+dy'][x+dx'],
+//   W'[c][9m + tap'] = W[m][9c + (8 - tap')]            (dy' = -dy, dx' = -dx).
+// Its mask over rows c = (v_o, v_r, v_i) and columns (u_o, u_r, u_i, u_b, tap') is
+//   G_o^T (x) G_r^T (x) (G_i^T (x) J(1, |G_b.U|)) (x) J(1, 9)
+// with J(a, c) the complete graph: a four-factor mask of the same family (G_b complete makes every
+// (u_b, tap') adjacent to every row), with the nine taps innermost as the fused kernel wants them.
+int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
+  if (!m || !out) return RBGP_EINVAL;
+  if (m->c[3] != 9 || m->d[3] != 9) return RBGP_EUNSUPPORTED;
+  if ((m->K / 9) * (m->coldeg * 9) >= (int64_t(1) << 31) || m->M * 9 > (1 << 24)) return RBGP_EINVAL;
+  rbgp_mask *t = new (std::nothrow) rbgp_mask();
+  if (!t) return RBGP_ENOMEM;
+  try {
+    std::vector<int32_t> coadj[4];
+    co_adjacency(m, coadj);
+    const int ab = m->a[3];
+    for (int i = 0; i < 3; ++i) {
+      rbgp_base_graph g;
+      g.a = m->c[i]; g.c = m->a[i]; g.d = m->e[i]; g.e = m->d[i]; g.role = i;
+      g.adj = coadj[i];
+      g.sigma1 = m->sigma1[i]; g.sigma2 = m->sigma2[i]; g.bound = m->bound[i];
+      g.status = m->status[i]; g.tries = m->tries[i];
+      t->base.push_back(std::move(g));
+    }
+    for (int i = 0; i < 2; ++i) {   // J(1, |G_b.U|) joins G_i^T; J(1, 9) are the taps
+      rbgp_base_graph g;
+      g.a = 1; g.c = i ? 9 : ab; g.d = g.c; g.e = 1; g.role = i ? 3 : 2;
+      g.adj.resize(size_t(g.c));
+      for (int v = 0; v < g.c; ++v) g.adj[size_t(v)] = v;
+      g.sigma1 = std::sqrt(double(g.c)); g.sigma2 = 0; g.bound = std::sqrt(double(g.c - 1));
+      g.status = RBGP_SPEC_COMPLETE; g.tries = 0;
+      t->base.push_back(std::move(g));
+    }
+    for (int role = 0; role < 4; ++role) merge_role(t, role);
+    t->M = m->K / 9; t->K = m->M * 9;
+    t->rowdeg = int64_t(t->d[0]) * t->d[1] * t->d[2] * t->d[3];
+    t->coldeg = int64_t(t->e[0]) * t->e[1] * t->e[2] * t->e[3];
+    t->nnz = m->nnz;
+    // where each kept value of W' comes from
+    std::vector<int32_t> pos[3];
+    for (int i = 0; i < 3; ++i) {
+      pos[i].assign(size_t(m->a[i]) * m->c[i], -1);
+      for (int u = 0; u < m->a[i]; ++u)
+        for (int j = 0; j < m->d[i]; ++j) pos[i][size_t(u) * m->c[i] + m->adj[i][size_t(u) * m->d[i] + j]] = j;
+    }
+    t->from_original.resize(size_t(m->nnz));
+    const int32_t *a = m->a, *c = m->c, *d = m->d, *e = m->e;
+    int64_t s = 0;
+    for (int v0 = 0; v0 < c[0]; ++v0)
+      for (int v1 = 0; v1 < c[1]; ++v1)
+        for (int v2 = 0; v2 < c[2]; ++v2)
+          for (int j0 = 0; j0 < e[0]; ++j0)
+            for (int j1 = 0; j1 < e[1]; ++j1)
+              for (int j2 = 0; j2 < e[2]; ++j2)
+                for (int ub = 0; ub < ab; ++ub)
+                  for (int tap = 0; tap < 9; ++tap) {
+                    const int u0 = coadj[0][size_t(v0) * e[0] + j0], u1 = coadj[1][size_t(v1) * e[1] + j1],
+                              u2 = coadj[2][size_t(v2) * e[2] + j2];
+                    const int64_t row = ((int64_t(u0) * a[1] + u1) * a[2] + u2) * ab + ub;
+                    const int64_t at = ((int64_t(pos[0][size_t(u0) * c[0] + v0]) * d[1] + pos[1][size_t(u1) * c[1] + v1]) * d[2] +
+                                        pos[2][size_t(u2) * c[2] + v2]) * 9 + (8 - tap);
+                    t->from_original[size_t(s++)] = int32_t(row * m->rowdeg + at);
+                  }
+    t->kernel_choice = RBGP_KERNEL_AUTO;
+    t->dev = nullptr;
+    rbgp_plan_mfma(t);
+    rbgp_plan_reg(t);
+  } catch (const std::bad_alloc &) {
+    delete t;
+    return RBGP_ENOMEM;
+  }
+  *out = t;
+  return RBGP_OK;
+}
+
+int rbgp_mask_original_order(const rbgp_mask_t *m, int32_t *out) {
+  if (!m || !out || m->from_original.empty()) return RBGP_EINVAL;
+  std::copy(m->from_original.begin(), m->from_original.end(), out);
+  return RBGP_OK;
+}
+
 void rbgp_mask_free(rbgp_mask_t *mask) {
   if (!mask) return;
   if (mask->dev) rbgp_device_release(mask->dev);

@@ -159,6 +159,26 @@ def library_conv3x3_sddmm(w, dO_lib, X, tag=""):
     return out[:w.M * w.rowdeg].reshape(w.M, w.rowdeg)
 
 
+def library_conv3x3_input_gradient(w, vals_lib, dO_lib, B, H, W, tag=""):
+    """dX[C][B*H*W] of the fused 3x3 convolution: rbgp_conv3x3 on the mask of the transposed convolution,
+    reading dO[M][B][H][W] zero-padded."""
+    import torch
+    N = B * H * W
+    print(f"[gpu] conv3x3 input gradient {w.name} B={B} H={H} W={W} dtype={w.dtype} {tag}", flush=True)
+    mask = make_mask(w)
+    mx = rb.rbgp_mask_conv3x3_transpose(mask)
+    stream = torch.cuda.current_stream().cuda_stream
+    packed = torch.zeros(max(rb.rbgp_packed_bytes(mx, w.dtype), 16), dtype=torch.uint8, device="cuda:0")
+    rb.rbgp_pack_transposed(mx, w.dtype, np.ascontiguousarray(vals_lib).reshape(-1), packed.data_ptr(), stream)
+    dOp = wl.zero_padded(np.ascontiguousarray(dO_lib).reshape(w.M, B, H, W))
+    dO_d = torch.from_numpy(dOp.view(np.int16) if dOp.dtype == np.uint16 else dOp).to("cuda:0")
+    C = w.K // 9
+    dX_d = torch.full((C, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    rb.rbgp_conv3x3(mx, w.dtype, C, w.M, B, H, W, packed.data_ptr(), dO_d.data_ptr(), dX_d.data_ptr(), N, stream)
+    torch.cuda.synchronize()
+    return dX_d.cpu().numpy(), rb.rbgp_mask_kernel(mx, w.dtype)
+
+
 def oracle_backward(w, vals_f32, I_f32, dO_f32):
     """(dI, its denominators sum_m |W||dO|, dW, its denominators sum_n |dO||I|) from the oracle."""
     Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)

@@ -351,3 +351,36 @@ def test_base_graphs_of_a_thousand_vertices_match_the_oracle(shape):
     assert math.isclose(sp["sigma1"], infos[0]["sigma1"], rel_tol=1e-10)
     assert math.isclose(sp["sigma2"], infos[0]["sigma2"], rel_tol=1e-9)
     assert sp["sigma2"] <= sp["bound"]
+
+
+# ---------------------------------------------------------------- transposed 3x3 convolution
+@pytest.mark.parametrize("shape", [((4, 2, 2, 4), (4, 2, 4, 9), (2, 2, 4, 9)), ((4, 1, 4, 3), (4, 2, 4, 9), (2, 2, 2, 9)),
+                                   ((2, 3, 4, 1), (2, 2, 4, 9), (1, 2, 2, 9))], ids=lambda s: "x".join(map(str, s[0])))
+def test_conv3x3_transposed_mask_holds_the_flipped_kernel(shape):
+    """W'[c][9 m + tap'] = W[m][9 c + (8 - tap')]: mask and value order of the convolution that
+    computes the gradient with respect to the input."""
+    rows, cols, deg = shape
+    mask = rb.rbgp_make_mask(rows, cols, deg, 4)
+    mx = rb.rbgp_mask_conv3x3_transpose(mask)
+    sh, shx = rb.rbgp_mask_shape(mask), rb.rbgp_mask_shape(mx)
+    M, K = sh["M"], sh["K"]
+    assert (shx["M"], shx["K"], shx["nnz"]) == (K // 9, 9 * M, sh["nnz"])
+    dense = rb.rbgp_mask_dense(mask).astype(np.int64)
+    vals = np.arange(1, sh["nnz"] + 1, dtype=np.float64).reshape(M, -1)
+    W = orc.scatter_values(dense, vals)                                   # distinct values: tracks every entry
+    Wx = np.zeros((K // 9, 9 * M))
+    for m in range(M):
+        for c in range(K // 9):
+            for tap in range(9):
+                Wx[c, 9 * m + tap] = W[m, 9 * c + 8 - tap]
+    assert np.array_equal(rb.rbgp_mask_dense(mx), (Wx != 0).astype(np.uint8))
+    order = rb.rbgp_mask_original_order(mx)
+    valsx = vals.reshape(-1)[order].reshape(shx["M"], -1)
+    assert np.array_equal(orc.scatter_values((Wx != 0).astype(np.uint8), valsx), Wx)
+    # the plain transpose reports the same table as rbgp_transpose_order
+    assert np.array_equal(rb.rbgp_mask_original_order(rb.rbgp_mask_transpose(mask)), rb.rbgp_transpose_order(mask))
+    with pytest.raises(rb.RbgpError):
+        rb.rbgp_mask_original_order(mask)
+    with pytest.raises(rb.RbgpError) as ei:
+        rb.rbgp_mask_conv3x3_transpose(rb.rbgp_make_mask(wl.TINY.rows, wl.TINY.cols, wl.TINY.row_deg, 1))
+    assert ei.value.code == rb.EUNSUPPORTED

@@ -173,3 +173,29 @@ def test_fused_conv3x3_weight_gradient_argument_checks():
     assert lib.rbgp_conv3x3_sddmm(mask.handle, 0, w.M, C, 2, 4, 4, 256, 32, None, 256, None) == rb.EINVAL
     tiny = gh.make_mask(wl.TINY)                                                                             # |G_b.V| != 9
     assert lib.rbgp_conv3x3_sddmm(tiny.handle, 0, wl.TINY.M, wl.TINY.K // 9, 1, 1, 4, 256, 4, 256, 256, None) in (rb.ESHAPE, rb.EUNSUPPORTED)
+
+
+# ------------------------------------------------------------------ gradient of the fused convolution w.r.t. its input
+@pytest.mark.parametrize("case", CONV_GRAD_CASES, ids=lambda c: c[0].name)
+def test_fused_conv3x3_input_gradient_is_the_transposed_convolution(case):
+    w, B, H, W = case
+    w = replace(w, N=B * H * W)
+    vals, dO = wl.kept_weights(w), wl.output_gradients(w)
+    if w.dtype == wl.BF16:
+        vl, dOl = wl.to_bf16_bits(vals), wl.to_bf16_bits(dO)
+        vals, dO = wl.bf16_bits_as_f32(vl), wl.bf16_bits_as_f32(dOl)
+    else:
+        vl, dOl = vals, dO
+    got, used = gh.library_conv3x3_input_gradient(w, vl, dOl, B, H, W)
+    assert used == REG
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = orc.kron_mask(Bs)
+    Wd = orc.scatter_values(mask, vals)
+    maskT, WT = np.ascontiguousarray(mask.T), np.ascontiguousarray(Wd.T)
+    from oracle import naive_c
+    dI, dI_den = naive_c.spmm(maskT, WT, dO), naive_c.spmm_abs(maskT, WT, dO)
+    ref = orc.col2im_3x3(dI, B, H, W).reshape(w.K // 9, -1)
+    den = orc.col2im_3x3(dI_den, B, H, W).reshape(w.K // 9, -1)
+    err = orc.normalised_error(got, ref, den)
+    print(f"[gpu]   normalised error {err:.3e}", flush=True)
+    assert err <= gh.TOL[w.dtype], err

@@ -486,3 +486,24 @@ def test_sddmm_one_hot_inputs_pick_single_products():
     assert np.array_equal(dW, expect)
     I1[k, 3] = 0.0; I1[k, 4] = 1.0                       # different column of the batch: no overlap
     assert not orc.sddmm_definition(mask, dO1, I1).any()
+
+
+def test_col2im_3x3_is_the_adjoint_of_im2col_and_matches_torch_autograd():
+    import torch
+    g = np.random.Generator(np.random.PCG64(9))
+    C, B, H, W = 3, 2, 4, 5
+    X = g.standard_normal((C, B, H, W))
+    Z = g.standard_normal((9 * C, B * H * W))
+    lhs = np.sum(orc.im2col_3x3(X) * Z)
+    rhs = np.sum(X * orc.col2im_3x3(Z, B, H, W))
+    assert math.isclose(lhs, rhs, rel_tol=1e-12)
+    # gradient of a 3x3 convolution with respect to its input, from torch
+    Wt = torch.tensor(g.standard_normal((4, C, 3, 3)))
+    Xt = torch.tensor(X.transpose(1, 0, 2, 3).copy(), requires_grad=True)        # [B][C][H][W]
+    Ot = torch.nn.functional.conv2d(Xt, Wt, padding=1)
+    dO = torch.tensor(g.standard_normal(tuple(Ot.shape)))
+    (Ot * dO).sum().backward()
+    Wm = Wt.numpy().reshape(4, 9 * C)                                            # k = 9c + 3(dy+1) + (dx+1)
+    dOm = dO.numpy().transpose(1, 0, 2, 3).reshape(4, B * H * W)
+    dX = orc.col2im_3x3(Wm.T @ dOm, B, H, W)
+    assert np.allclose(dX, Xt.grad.numpy().transpose(1, 0, 2, 3), rtol=1e-12, atol=1e-12)
