@@ -138,6 +138,12 @@ def time_workload(w, args, torch, dev, steps, warmup, check_cols=0, geom=None):
         ref, den = naive_c.spmm(dense_mask, W, Isub), naive_c.spmm_abs(dense_mask, W, Isub)
         res["parity_err"] = orc.normalised_error(Os[0].cpu().numpy()[:, cols], ref, den)
         res["parity_cols"] = int(len(cols))
+    if getattr(args, "sweep_backward", False) and not geom:
+        del Is, Os
+        torch.cuda.empty_cache()
+        res["backward"] = backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream,
+                                           check=bool(check_cols), steps=steps, warmup=warmup,
+                                           geom=getattr(args, "layer_geom", {}).get(w.name), light_check=True)
     return res
 
 
@@ -159,6 +165,8 @@ def sweep_cases(which, args):
                 h = wl.VGG19_LAYERS[layer][2]
                 # --fused-conv: layers whose image rows hold whole lane loads go through rbgp_conv3x3
                 fused = args.fused_conv and layer > 0 and h % 4 == 0
+                if layer > 0 and h % 4 == 0:   # (--sweep-backward: the fused gradients need the layer's geometry)
+                    args.layer_geom = dict(getattr(args, "layer_geom", {}), **{w.name: (w.N // (h * h), h, h)})
                 cases.append((w, (w.N // (h * h), h, h)) if fused else w)
     return cases
 
@@ -230,7 +238,7 @@ def fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream, check, steps=
 
 
 def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream, check, steps=1000, warmup=300,
-                     only=None):
+                     only=None, geom=None, light_check=False):
     """The two gradients of the product for a fixed mask (Section 6), timed on the same workload:
     dI = W_s^T x dO (rbgp_spmm on the transposed mask) and dW = (dO x I^T) on the mask (rbgp_sddmm).
     Reported beside the headline number; same flop count 2 * nnz * N each."""
@@ -264,10 +272,11 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
 
     steps_list = [("backward_data", data_step, w.M * w.N * w.in_bytes + w.K * w.N * 4 + w.nnz * w.in_bytes),
                   ("weight_gradient", weight_step, (w.M + w.K) * w.N * w.in_bytes + w.nnz * 4)]
-    geom = wl.CONV_GEOMETRY.get(w.name)
+    geom = geom or wl.CONV_GEOMETRY.get(w.name)
+    if geom:
+        B, H, W = geom
     if geom and (not bf16 or geom[2] % 8 == 0):
         # the same gradient from the activations themselves (the lowered input is never stored)
-        B, H, W = geom
         X = wl.conv_activations(w, B, H, W)
         Xbits = wl.to_bf16_bits(X) if bf16 else None
         X_f32 = wl.bf16_bits_as_f32(Xbits) if bf16 else X
@@ -280,6 +289,7 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
                                   dWs[j].data_ptr(), stream)
         steps_list.append(("weight_gradient_fused_conv3x3", fused_step,
                            w.M * w.N * w.in_bytes + Xp.nbytes + w.nnz * 4))
+    if geom:
         # dX: the transposed convolution of dO through rbgp_conv3x3 (the lowered gradient is never stored)
         mask_x = rb.rbgp_mask_conv3x3_transpose(mask)
         packed_x = torch.zeros(rb.rbgp_packed_bytes(mask_x, w.dtype), dtype=torch.uint8, device=dev)
@@ -323,18 +333,22 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
         dense_mask = orc.kron_mask(Bs)
         Wd = orc.scatter_values(dense_mask, vals_f32)
         if "backward_data" in out:       # sampled columns of dI
-            ncols = int(min(w.N, max(64, (1 << 31) // max(w.nnz, 1))))
+            ncols = int(min(w.N, 32 if light_check else max(64, (1 << 31) // max(w.nnz, 1))))
             mT, WT = np.ascontiguousarray(dense_mask.T), np.ascontiguousarray(Wd.T)
             sub = np.ascontiguousarray(dO_f32[:, :ncols])
             ref, den = naive_c.spmm(mT, WT, sub), naive_c.spmm_abs(mT, WT, sub)
             out["backward_data"]["parity_err"] = orc.normalised_error(dIs[0].cpu().numpy()[:, :ncols], ref, den)
-        if "input_gradient_fused_conv3x3" in out:      # whole dX: col2im of the oracle's W^T dO
+        if "input_gradient_fused_conv3x3" in out:      # dX: col2im of the oracle's W^T dO (light: first two images)
             mT, WT = np.ascontiguousarray(dense_mask.T), np.ascontiguousarray(Wd.T)
             Bq, Hq, Wq = geom
-            ref = orc.col2im_3x3(naive_c.spmm(mT, WT, dO_f32), Bq, Hq, Wq).reshape(w.K // 9, -1)
-            den = orc.col2im_3x3(naive_c.spmm_abs(mT, WT, dO_f32), Bq, Hq, Wq).reshape(w.K // 9, -1)
-            out["input_gradient_fused_conv3x3"]["parity_err"] = orc.normalised_error(dXs[0].cpu().numpy(), ref, den)
-        rows = np.unique(np.linspace(0, w.M - 1, 48).astype(np.int64))   # sampled rows of dW (each needs the whole batch)
+            Bc = min(Bq, 2) if light_check else Bq
+            sub = np.ascontiguousarray(dO_f32[:, :Bc * Hq * Wq])
+            ref = orc.col2im_3x3(naive_c.spmm(mT, WT, sub), Bc, Hq, Wq).reshape(w.K // 9, -1)
+            den = orc.col2im_3x3(naive_c.spmm_abs(mT, WT, sub), Bc, Hq, Wq).reshape(w.K // 9, -1)
+            out["input_gradient_fused_conv3x3"]["parity_err"] = orc.normalised_error(
+                dXs[0].cpu().numpy()[:, :Bc * Hq * Wq], ref, den)
+        # sampled rows of dW (each needs the whole batch)
+        rows = np.unique(np.linspace(0, w.M - 1, 8 if light_check else 48).astype(np.int64))
         if "weight_gradient_fused_conv3x3" in out:     # (timed last: dWs hold its result)
             I_x = orc.im2col_3x3(X_f32)
             ref = orc.sddmm_definition(dense_mask[rows], dO_f32[rows], I_x)
@@ -374,6 +388,8 @@ def main():
     ap.add_argument("--sweep", default="", choices=["", "table2", "table3", "vgg19"],
                     help="time a family of workloads instead of the headline one: the paper's 4096^3 SDMM of "
                          "Table 2 / Table 3, or the 16 VGG19 conv layers; prints one JSON line with all cases")
+    ap.add_argument("--sweep-backward", action="store_true",
+                    help="sweeps: also time the backward products of every case (dI, dW, and for 3x3 layers the fused dX, dW)")
     ap.add_argument("--sweep-steps", type=int, default=300)
     ap.add_argument("--sweep-check", type=int, default=32, help="output columns per case checked against the oracle (0: none)")
     ap.add_argument("--sweep-density", default="2,3", help="vgg19 sweep: log2 of the inverse densities")
