@@ -199,3 +199,60 @@ def test_fused_conv3x3_input_gradient_is_the_transposed_convolution(case):
     err = orc.normalised_error(got, ref, den)
     print(f"[gpu]   normalised error {err:.3e}", flush=True)
     assert err <= gh.TOL[w.dtype], err
+
+
+def test_training_step_replays_from_a_hip_graph():
+    """Forward, input gradient and weight gradient of a fused 3x3 layer captured into one graph after a
+    warm-up call (which builds the library's tables and its partial-sum buffer): three replays on fresh
+    inputs, with eager work and synchronisations in between, each compared with the eager result."""
+    import torch
+    w = wl.Workload("graph_layer", (4, 2, 4, 2), (4, 2, 8, 9), (2, 2, 4, 9), 0, wl.F32, 31, 32, 33, 1.0)
+    B, H, W = 6, 8, 8
+    N = B * H * W
+    C = w.K // 9
+    mask = gh.make_mask(w)
+    mask_x = rb.rbgp_mask_conv3x3_transpose(mask)
+    vals = wl.kept_weights(w).reshape(-1)
+    dev = "cuda:0"
+    packed = torch.zeros(rb.rbgp_packed_bytes(mask, w.dtype), dtype=torch.uint8, device=dev)
+    packed_x = torch.zeros(rb.rbgp_packed_bytes(mask_x, w.dtype), dtype=torch.uint8, device=dev)
+    st0 = torch.cuda.current_stream().cuda_stream
+    rb.rbgp_pack(mask, w.dtype, vals, packed.data_ptr(), st0)
+    rb.rbgp_pack_transposed(mask_x, w.dtype, vals, packed_x.data_ptr(), st0)
+    X = torch.zeros(C, B, H + 2, W + 2, device=dev)
+    dO = torch.zeros(w.M, B, H + 2, W + 2, device=dev)          # padded: read by the input-gradient convolution
+    dO_flat = torch.zeros(w.M, N, device=dev)                   # the same values as a matrix: read by the weight gradient
+    O = torch.zeros(w.M, N, device=dev)
+    dX = torch.zeros(C, N, device=dev)
+    dW = torch.zeros(w.M * w.rowdeg, device=dev)
+
+    def step(stream):
+        rb.rbgp_conv3x3(mask, w.dtype, w.M, C, B, H, W, packed.data_ptr(), X.data_ptr(), O.data_ptr(), N, stream)
+        rb.rbgp_conv3x3(mask_x, w.dtype, C, w.M, B, H, W, packed_x.data_ptr(), dO.data_ptr(), dX.data_ptr(), N, stream)
+        rb.rbgp_conv3x3_sddmm(mask, w.dtype, w.M, C, B, H, W, dO_flat.data_ptr(), N, X.data_ptr(), dW.data_ptr(), stream)
+
+    def fresh_inputs(seed):
+        g = torch.Generator(device=dev).manual_seed(seed)
+        X[:, :, 1:-1, 1:-1] = torch.randn(C, B, H, W, device=dev, generator=g)
+        d = torch.randn(w.M, B, H, W, device=dev, generator=g)
+        dO[:, :, 1:-1, 1:-1] = d
+        dO_flat.copy_(d.reshape(w.M, N))
+
+    fresh_inputs(0)
+    step(st0)                                                    # warm-up: tables, partial sums
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)
+    for seed in (1, 2, 3):
+        fresh_inputs(seed)
+        step(torch.cuda.current_stream().cuda_stream)            # eager reference
+        torch.cuda.synchronize()
+        ref = [t.clone() for t in (O, dX, dW)]
+        for t in (O, dX, dW):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((O, dX, dW), ref):
+            assert torch.equal(got, want)                        # same kernels, same order of sums: bit-identical
