@@ -70,6 +70,13 @@ struct SddmmParams {
   int NSTG, stage_rows;     // stages per tile; rows of I between the bases of consecutive stages (VC * c_i * c_b)
   int tile_rows;            // rows of I per tile column (c_r * c_i * c_b)
   int a2, a3, a4, R, lgRS, MG, KCR, rowdeg;
+  // "All of G_i" units (GI kernels): a unit is a (tile column, stage) and takes the rows of every G_i vertex
+  // together -- 16-row groups run over (tile row of the list, u_i, row of R) -- against ALL rows of I the
+  // stage spans, whether G_i connects them or not; the epilogue stores the kept products only.  For
+  // masks with few rows per (tile column, u_i) (sparse G_o, small G_r, G_b) this fills the 16 MFMA rows
+  // that would be padding, and every row of I is loaded once instead of once per adjacent u_i.
+  int src_rows;             // gi: rows of I one stage spans (VC * c_i * c_b)
+  const int32_t *spos;      // gi: [a_i][16 * NB]: position inside the stage's kept values of (u_i, stage row), -1: not kept
   // Fused 3x3 convolution (CONV kernels): I is not materialised; row k = 9 * channel + tap of it is read
   // from the zero-padded activations X[channel][image][H + 2][W + 2] (pointer I).
   const int32_t *colbase;   // element offset, inside a channel of X, of the first pixel of every group of
@@ -128,7 +135,7 @@ struct Operand<true> {
 // RB: groups of 16 rows of dO per wave; NB: groups of 16 contraction steps per stage (KCR <= 16 * NB).
 // grid.x = ((v_o * NSTG + stage) * a_i + u_i) * RBG + group of RB row groups; grid.y = workgroups
 // along the batch.
-template <int RB, int NB, bool BF16, bool CONV>
+template <int RB, int NB, bool BF16, bool CONV, bool GI>
 __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   typedef Operand<BF16> Op;
   typedef typename Op::reg reg;
@@ -148,29 +155,47 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   // a_i * RBG workgroups that share the rows of I of one (tile column, stage) take launch slots with
   // the same remainder modulo 8 (when the number of such groups is a multiple of 8).
   int x = blockIdx.x;
-  const int per_group = p.a3 * p.RBG, groups = gridDim.x / per_group;
+  const int per_group = (GI ? 1 : p.a3) * p.RBG, groups = gridDim.x / per_group;
   if (groups % 8 == 0) {
     const int xcd = x % 8, slot = x / 8;
     x = ((slot / per_group) * 8 + xcd) * per_group + slot % per_group;
   }
   const int g = x % p.RBG; x /= p.RBG;
-  const int u3 = x % p.a3; x /= p.a3;
+  int u3 = 0;
+  if constexpr (!GI) { u3 = x % p.a3; x /= p.a3; }
   const int sg = x % p.NSTG, v1 = x / p.NSTG;
   const int RS = 1 << p.lgRS;
   const int32_t *crow = p.colrows + v1 * p.EO, *cpos = p.colpos + v1 * p.EO;
   const int base = v1 * p.tile_rows + sg * p.stage_rows;
 
+  // row r16 of row group rb of this workgroup: (row of dO, or -1; its entry of the tile-row list; its u_i)
+  struct RowOf { int64_t row; int entry, ui; };
+  auto row_of = [&](int rb, int r16) {
+    RowOf o{-1, 0, u3};
+    int ri;
+    if constexpr (GI) {
+      const int rho = (g * RB + rb) * 16 + r16;
+      ri = rho % p.R;
+      o.ui = (rho / p.R) % p.a3;
+      o.entry = rho / (p.R * p.a3);
+    } else {
+      o.entry = (g * RB + rb) * p.MG + (r16 >> p.lgRS);
+      ri = r16 & (RS - 1);
+    }
+    if (o.entry < p.EO && ri < p.R)
+      o.row = ((int64_t(crow[o.entry]) * p.a2 + ri / p.a4) * p.a3 + o.ui) * p.a4 + ri % p.a4;
+    return o;
+  };
   int64_t off[NL];   // element offset of this lane's 16 bytes in iteration 0: dO rows, then I rows
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const int idx = (g * RB + rb) * p.MG + (lr >> p.lgRS), ri = lr & (RS - 1);
-    int64_t row = 0;
-    if (idx < p.EO && ri < p.R) row = ((int64_t(crow[idx]) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
-    off[rb] = row * p.ld_dO + ls * CPL;
+    const int64_t row = row_of(rb, lr).row;
+    off[rb] = (row < 0 ? 0 : row) * p.ld_dO + ls * CPL;
   }
 #pragma unroll
   for (int b = 0; b < NB; ++b) {   // padding steps read row 0 of the stage
-    const int k = base + p.rowtab[(u3 * NB + b) * 16 + lr];
+    const int sr = 16 * b + lr;
+    const int k = base + (GI ? (sr < p.src_rows ? sr : 0) : p.rowtab[(u3 * NB + b) * 16 + lr]);
     if constexpr (CONV) {   // channel k / 9, tap k % 9 = 3 * (dy + 1) + (dx + 1): the shift of the tap inside the channel
       const int tap = k % 9;
       off[RB + b] = int64_t(k / 9) * p.chan_elems + (tap / 3 - 1) * p.conv_w2 + (tap % 3 - 1);
@@ -299,20 +324,20 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) red[wave][(rb * NB + b) * 4 + i][lane] = Op::total(acc[rb][b], i);
   __syncthreads();
-  const int r16 = 4 * q + wave, ri = r16 & (RS - 1);
-  if (ri >= p.R) return;
+  const int r16 = 4 * q + wave;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const int idx = (g * RB + rb) * p.MG + (r16 >> p.lgRS);
-    if (idx >= p.EO) continue;
-    const int64_t row = ((int64_t(crow[idx]) * p.a2 + ri / p.a4) * p.a3 + u3) * p.a4 + ri % p.a4;
+    const RowOf o = row_of(rb, r16);
+    if (o.row < 0) continue;
     // the stage is fragment cpos * NSTG + sg of the row: KCR consecutive kept values
-    float *dst = p.out + int64_t(blockIdx.y) * p.nnz + row * p.rowdeg + int64_t(cpos[idx] * p.NSTG + sg) * p.KCR;
+    float *dst = p.out + int64_t(blockIdx.y) * p.nnz + o.row * p.rowdeg + int64_t(cpos[o.entry] * p.NSTG + sg) * p.KCR;
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-      const int kk = 16 * b + j, e = (rb * NB + b) * 4 + wave;
+      const int e = (rb * NB + b) * 4 + wave;
+      // contraction step of this lane's column: 16 * b + j, or (gi) wherever G_i puts stage row 16 * b + j for u_i
+      const int kk = GI ? p.spos[(o.ui * NB + b) * 16 + j] : (16 * b + j < p.KCR ? 16 * b + j : -1);
       const float v = (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
-      if (kk < p.KCR) dst[kk] = v;
+      if (kk >= 0) dst[kk] = v;
     }
   }
 }
@@ -371,7 +396,7 @@ __global__ __launch_bounds__(256) void sddmm_generic(GenericParams p, const TIn 
 }
 
 struct SddmmState {
-  int32_t *colrows = nullptr, *colpos = nullptr, *rowtab = nullptr;
+  int32_t *colrows = nullptr, *colpos = nullptr, *rowtab = nullptr, *spos = nullptr;
   int EO = 0;
   float *partial = nullptr;
   size_t partial_bytes = 0;
@@ -387,22 +412,22 @@ int upload(const std::vector<T> &h, T **d) {
 }
 
 typedef void (*sddmm_fn)(SddmmParams);
-template <int RB, bool BF16, bool CONV>
+template <int RB, bool BF16, bool CONV, bool GI>
 sddmm_fn pick_nb(int NB) {
   switch (NB) {
-    case 1: return sddmm_reg<RB, 1, BF16, CONV>;
-    case 2: return sddmm_reg<RB, 2, BF16, CONV>;
-    case 3: return sddmm_reg<RB, 3, BF16, CONV>;
-    case 4: return sddmm_reg<RB, 4, BF16, CONV>;
-    case 5: return sddmm_reg<RB, 5, BF16, CONV>;
+    case 1: return sddmm_reg<RB, 1, BF16, CONV, GI>;
+    case 2: return sddmm_reg<RB, 2, BF16, CONV, GI>;
+    case 3: return sddmm_reg<RB, 3, BF16, CONV, GI>;
+    case 4: return sddmm_reg<RB, 4, BF16, CONV, GI>;
+    case 5: return sddmm_reg<RB, 5, BF16, CONV, GI>;
   }
   return nullptr;
 }
-template <bool CONV>
+template <bool CONV, bool GI>
 sddmm_fn find_kernel(int RB, int NB, bool bf16) {
   switch (RB) {
-    case 1: return bf16 ? pick_nb<1, true, CONV>(NB) : pick_nb<1, false, CONV>(NB);
-    case 2: return bf16 ? pick_nb<2, true, CONV>(NB) : pick_nb<2, false, CONV>(NB);
+    case 1: return bf16 ? pick_nb<1, true, CONV, GI>(NB) : pick_nb<1, false, CONV, GI>(NB);
+    case 2: return bf16 ? pick_nb<2, true, CONV, GI>(NB) : pick_nb<2, false, CONV, GI>(NB);
   }
   return nullptr;
 }
@@ -427,9 +452,18 @@ int build_state(const rbgp_mask *m, SddmmState *st) {
       const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
       rt[(size_t(u3) * NB) * 16 + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
     }
+  // "all of G_i" units: where G_i puts every row of a stage, per u_i
+  const int NBG = (pl.SRC + 15) / 16;
+  std::vector<int32_t> sp(size_t(a3) * NBG * 16, -1);
+  for (int u3 = 0; u3 < a3; ++u3)
+    for (int j3 = 0; j3 < d3; ++j3)
+      for (int vv = 0; vv < pl.VC; ++vv)
+        for (int v4 = 0; v4 < c4; ++v4)
+          sp[size_t(u3) * NBG * 16 + (size_t(vv) * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4] = (vv * d3 + j3) * c4 + v4;
   int rc = upload(colrows, &st->colrows);
   if (!rc) rc = upload(colpos, &st->colpos);
   if (!rc) rc = upload(rt, &st->rowtab);
+  if (!rc) rc = upload(sp, &st->spos);
   st->EO = EO;
   return rc;
 }
@@ -442,6 +476,7 @@ void rbgp_sddmm_release(void *state) {
   if (st->colrows) (void)hipFree(st->colrows);
   if (st->colpos) (void)hipFree(st->colpos);
   if (st->rowtab) (void)hipFree(st->rowtab);
+  if (st->spos) (void)hipFree(st->spos);
   if (st->partial) (void)hipFree(st->partial);
   for (int32_t *t : st->colbase)
     if (t) (void)hipFree(t);
@@ -488,18 +523,24 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
     int rc = build_state(m, st);
     if (rc) return rc;
   }
-  const int NB = (pl.KCR + 15) / 16;
-  // row groups of 16 (MG tile rows) per tile column, RB of them per wave
-  const int groups = (st->EO + pl.MG - 1) / pl.MG;
-  // two row groups per wave halve the rows of I fetched per MFMA; four would starve the chip of
-  // waves at the layer sizes of the paper (measured: slower on every VGG19 / WRN shape tried)
-  const int RB = groups >= 2 ? 2 : 1;
-  const int RBG = (groups + RB - 1) / RB;
-  sddmm_fn fn = conv ? find_kernel<true>(RB, NB, bf16) : find_kernel<false>(RB, NB, bf16);
+  // row groups of 16 (MG tile rows) per tile column and u_i, RB of them per wave: two row groups per wave
+  // halve the rows of I fetched per MFMA; four would starve the chip of waves at the layer sizes of
+  // the paper (measured: slower on every VGG19 / WRN shape tried)
+  int NB = (pl.KCR + 15) / 16;
+  int groups = (st->EO + pl.MG - 1) / pl.MG;
+  int RB = groups >= 2 ? 2 : 1;
+  int RBG = (groups + RB - 1) / RB;
+  // or "all of G_i" units, where they need fewer MFMAs per column of the batch
+  const int gi_groups = (st->EO * m->a[2] * pl.R + 15) / 16, gi_NB = (pl.SRC + 15) / 16;
+  const int gi_RB = gi_groups >= 2 ? 2 : 1, gi_RBG = (gi_groups + gi_RB - 1) / gi_RB;
+  const bool gi = gi_NB <= 5 && gi_RBG * gi_RB * gi_NB < m->a[2] * RBG * RB * NB;
+  if (gi) { NB = gi_NB; groups = gi_groups; RB = gi_RB; RBG = gi_RBG; }
+  sddmm_fn fn = conv ? (gi ? find_kernel<true, true>(RB, NB, bf16) : find_kernel<true, false>(RB, NB, bf16))
+                     : (gi ? find_kernel<false, true>(RB, NB, bf16) : find_kernel<false, false>(RB, NB, bf16));
   if (!fn) return RBGP_EUNSUPPORTED;
   // ranges of the batch: enough waves for a few per SIMD (1024 SIMDs), at least two iterations each
   const int cpi = bf16 ? 32 : 16;
-  const int64_t blocks = int64_t(m->c[0]) * pl.NSTG * m->a[2] * RBG;
+  const int64_t blocks = int64_t(m->c[0]) * pl.NSTG * (gi ? 1 : m->a[2]) * RBG;
   // one wave per SIMD (1024 SIMDs): longer ranges amortise the fill of the load pipeline and keep
   // the partial sums few; more waves per SIMD measured slower
   int64_t ranges = (1024 + blocks - 1) / blocks;                         // column ranges = waves per unit
@@ -549,6 +590,7 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   p.out = nsplit > 1 ? st->partial : dW;
   p.colrows = st->colrows; p.colpos = st->colpos; p.rowtab = st->rowtab;
   p.N = N; p.ld_dO = ld_dO; p.ldI = ldI; p.nnz = nnz; p.chunk = chunk;
+  p.src_rows = pl.SRC; p.spos = st->spos;
   p.EO = st->EO; p.RBG = RBG; p.NSTG = pl.NSTG; p.stage_rows = pl.SRC;
   p.tile_rows = m->c[1] * m->c[2] * m->c[3];
   p.a2 = pl.A2; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
