@@ -67,6 +67,7 @@ struct SddmmParams {
   int64_t N, ld_dO, ldI, nnz;
   int64_t chunk;            // columns per range (a multiple of the columns per iteration)
   int EO, RBG;              // tile rows per tile column; groups of RB row groups per unit
+  int nbt, halves;          // 16-step groups of a stage; workgroups that share them (each takes NB consecutive ones)
   int NSTG, stage_rows;     // stages per tile; rows of I between the bases of consecutive stages (VC * c_i * c_b)
   int tile_rows;            // rows of I per tile column (c_r * c_i * c_b)
   int a2, a3, a4, R, lgRS, MG, KCR, rowdeg;
@@ -155,11 +156,12 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   // a_i * RBG workgroups that share the rows of I of one (tile column, stage) take launch slots with
   // the same remainder modulo 8 (when the number of such groups is a multiple of 8).
   int x = blockIdx.x;
-  const int per_group = (GI ? 1 : p.a3) * p.RBG, groups = gridDim.x / per_group;
+  const int per_group = (GI ? 1 : p.a3) * p.RBG * p.halves, groups = gridDim.x / per_group;
   if (groups % 8 == 0) {
     const int xcd = x % 8, slot = x / 8;
     x = ((slot / per_group) * 8 + xcd) * per_group + slot % per_group;
   }
+  const int b0 = (x % p.halves) * NB; x /= p.halves;   // first 16-step group of this workgroup
   const int g = x % p.RBG; x /= p.RBG;
   int u3 = 0;
   if constexpr (!GI) { u3 = x % p.a3; x /= p.a3; }
@@ -194,8 +196,8 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   }
 #pragma unroll
   for (int b = 0; b < NB; ++b) {   // padding steps read row 0 of the stage
-    const int sr = 16 * b + lr;
-    const int k = base + (GI ? (sr < p.src_rows ? sr : 0) : p.rowtab[(u3 * NB + b) * 16 + lr]);
+    const int sr = 16 * (b0 + b) + lr;
+    const int k = base + (GI ? (sr < p.src_rows ? sr : 0) : (b0 + b < p.nbt ? p.rowtab[(u3 * p.nbt + b0 + b) * 16 + lr] : 0));
     if constexpr (CONV) {   // channel k / 9, tap k % 9 = 3 * (dy + 1) + (dx + 1): the shift of the tap inside the channel
       const int tap = k % 9;
       off[RB + b] = int64_t(k / 9) * p.chan_elems + (tap / 3 - 1) * p.conv_w2 + (tap % 3 - 1);
@@ -335,7 +337,8 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
     for (int b = 0; b < NB; ++b) {
       const int e = (rb * NB + b) * 4 + wave;
       // contraction step of this lane's column: 16 * b + j, or (gi) wherever G_i puts stage row 16 * b + j for u_i
-      const int kk = GI ? p.spos[(o.ui * NB + b) * 16 + j] : (16 * b + j < p.KCR ? 16 * b + j : -1);
+      const int st = 16 * (b0 + b) + j;
+      const int kk = b0 + b >= p.nbt ? -1 : GI ? p.spos[o.ui * p.nbt * 16 + st] : (st < p.KCR ? st : -1);
       const float v = (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
       if (kk >= 0) dst[kk] = v;
     }
@@ -535,12 +538,23 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   const int gi_RB = gi_groups >= 2 ? 2 : 1, gi_RBG = (gi_groups + gi_RB - 1) / gi_RB;
   const bool gi = gi_NB <= 5 && gi_RBG * gi_RB * gi_NB < m->a[2] * RBG * RB * NB;
   if (gi) { NB = gi_NB; groups = gi_groups; RB = gi_RB; RBG = gi_RBG; }
+  const int nbt = NB;
+  // ranges of the batch: enough waves for a few per SIMD (1024 SIMDs), at least two iterations each
+  const int cpi = bf16 ? 32 : 16;
+  int64_t blocks = int64_t(m->c[0]) * pl.NSTG * (gi ? 1 : m->a[2]) * RBG;
+  // Where one wave per SIMD would need five to eight column ranges per unit, i.e. two workgroups and the
+  // second kernel that adds their partial sums, two workgroups that split the stage's 16-step groups
+  // instead need neither (conv5 shape: 24.4 -> 22.5 us fp32, 13.7 -> 11.0 us bf16; the fused-convolution
+  // variant, whose loads of X cost more, is slower that way and keeps whole stages).
+  int halves = 1;
+  if (!conv && NB >= 4 && blocks * 4 < 1024 && blocks * 8 >= 1024 && N >= 8 * 2 * cpi) {
+    halves = 2;
+    NB = (NB + 1) / 2;
+    blocks *= 2;
+  }
   sddmm_fn fn = conv ? (gi ? find_kernel<true, true>(RB, NB, bf16) : find_kernel<true, false>(RB, NB, bf16))
                      : (gi ? find_kernel<false, true>(RB, NB, bf16) : find_kernel<false, false>(RB, NB, bf16));
   if (!fn) return RBGP_EUNSUPPORTED;
-  // ranges of the batch: enough waves for a few per SIMD (1024 SIMDs), at least two iterations each
-  const int cpi = bf16 ? 32 : 16;
-  const int64_t blocks = int64_t(m->c[0]) * pl.NSTG * (gi ? 1 : m->a[2]) * RBG;
   // one wave per SIMD (1024 SIMDs): longer ranges amortise the fill of the load pipeline and keep
   // the partial sums few; more waves per SIMD measured slower
   int64_t ranges = (1024 + blocks - 1) / blocks;                         // column ranges = waves per unit
@@ -591,6 +605,7 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   p.colrows = st->colrows; p.colpos = st->colpos; p.rowtab = st->rowtab;
   p.N = N; p.ld_dO = ld_dO; p.ldI = ldI; p.nnz = nnz; p.chunk = chunk;
   p.src_rows = pl.SRC; p.spos = st->spos;
+  p.nbt = nbt; p.halves = halves;
   p.EO = st->EO; p.RBG = RBG; p.NSTG = pl.NSTG; p.stage_rows = pl.SRC;
   p.tile_rows = m->c[1] * m->c[2] * m->c[3];
   p.a2 = pl.A2; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
