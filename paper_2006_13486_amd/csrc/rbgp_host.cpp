@@ -664,7 +664,21 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
         return rc;
       }
     }
+    // The kernels' view wants the factors of roles 1 and 3 complete (Section 5: G_r and G_b).  Where the
+    // caller's grouping has a sparse graph there, the graphs of that role up to its last sparse one join
+    // the role before (0 or 2), which may be sparse; by associativity the mask, its canonical order and
+    // M, K do not change.  rbgp_mask_base keeps reporting the role the caller gave.
+    std::vector<int32_t> given(static_cast<size_t>(count), 0);
+    for (int i = 0; i < count; ++i) given[size_t(i)] = m->base[size_t(i)].role;
+    for (int role : {1, 3}) {
+      int last_sparse = -1;
+      for (int i = 0; i < count; ++i)
+        if (m->base[size_t(i)].role == role && m->base[size_t(i)].status != RBGP_SPEC_COMPLETE) last_sparse = i;
+      for (int i = 0; i <= last_sparse; ++i)
+        if (m->base[size_t(i)].role == role) m->base[size_t(i)].role = role - 1;
+    }
     for (int role = 0; role < 4; ++role) merge_role(m, role);
+    for (int i = 0; i < count; ++i) m->base[size_t(i)].role = given[size_t(i)];
   } catch (const std::bad_alloc &) {
     delete m;
     return RBGP_ENOMEM;

@@ -162,11 +162,21 @@ def test_kernel_selection_and_packed_size():
     assert rb.rbgp_mask_kernel(mask, rb.F32) == rb.KERNEL_GENERIC
     assert rb.rbgp_packed_bytes(mask, rb.F32) == w.nnz * 4
     assert rb.rbgp_packed_bytes(mask, rb.BF16_F32ACC) == w.nnz * 2
-    # a mask whose G_r is sparse is outside the RBGP4 roles: generic only
-    m2 = rb.rbgp_make_mask((4, 4, 4, 2), (4, 4, 4, 2), (2, 2, 2, 2), 1)
-    assert rb.rbgp_mask_kernel(m2, rb.F32) == rb.KERNEL_GENERIC
+    # a mask whose G_r and G_b are sparse: the kernels' view moves them into G_o and G_i (same mask, same
+    # canonical order), so the MFMA families still apply; the inputs stay visible as base graphs
+    m2 = rb.rbgp_make_mask((4, 4, 4, 4), (4, 4, 4, 4), (2, 2, 2, 2), 1)
+    assert rb.rbgp_mask_kernel(m2, rb.F32) == rb.KERNEL_MFMA_REG
+    assert [rb.rbgp_mask_factor(m2, i)[:3] for i in range(4)] == [(16, 16, 4), (1, 1, 1), (16, 16, 4), (1, 1, 1)]
+    assert [(g["rows"], g["cols"], g["deg"], g["role"]) for g in (rb.rbgp_mask_base(m2, i) for i in range(4))] == \
+           [(4, 4, 2, 0), (4, 4, 2, 1), (4, 4, 2, 2), (4, 4, 2, 3)]
+    Bs, _ = orc.sample_factors((4, 4, 4, 4), (4, 4, 4, 4), (2, 2, 2, 2), 1)
+    assert np.array_equal(rb.rbgp_mask_dense(m2), orc.kron_mask(Bs))
+    assert np.array_equal(rb.rbgp_mask_columns(m2).reshape(256, -1), orc.canonical_columns(orc.kron_mask(Bs)))
+    # more than 16 rows in G_b alone is outside the register family; 64 tiles per tile row outside both
+    m3 = rb.rbgp_make_mask((2, 1, 2, 32), (2, 1, 4, 1), (2, 1, 2, 1), 1)
+    assert rb.rbgp_mask_kernel(m3, rb.F32) != rb.KERNEL_MFMA_REG
     with pytest.raises(rb.RbgpError) as ei:
-        rb.rbgp_mask_set_kernel(m2, rb.KERNEL_MFMA)
+        rb.rbgp_mask_set_kernel(m3, rb.KERNEL_MFMA_REG)
     assert ei.value.code == rb.EUNSUPPORTED
 
 

@@ -308,9 +308,15 @@ def test_fused_conv3x3_argument_checks():
 
 
 def test_masks_outside_rbgp4_roles_use_the_generic_kernel():
-    """Sparse G_r / G_b (general four-factor RBGP) still multiply correctly."""
+    """Sparse G_r / G_b (general four-factor RBGP): the kernels' view folds them into G_o / G_i and the MFMA
+    kernels run; more than 16 rows in G_b alone leaves the register family."""
     w = wl.Workload("general_rbgp", (4, 4, 4, 2), (4, 4, 8, 4), (2, 2, 4, 2), 130, wl.F32, 5, 6, 7, 1.0)
-    gh.check_parity(w, expect_kernel=GEN)
+    gh.check_parity(w, expect_kernel=REG)
+    gh.check_parity(w, kernel=GEN)
+    gh.check_parity(replace(w, dtype=wl.BF16), ld_pad=2, expect_kernel=REG)     # (bf16: leading dimension a multiple of 4)
+    big_gb = wl.Workload("big_gb", (2, 1, 2, 32), (2, 1, 4, 3), (2, 1, 2, 3), 96, wl.F32, 8, 9, 10, 1.0)
+    assert not gh.family_covers(big_gb, REG)
+    gh.check_parity(big_gb)
 
 
 def test_sdmm4096_paper_workload_sampled():
@@ -374,7 +380,9 @@ K_WORKLOADS = [
                 94, 95, 96, 1.0, roles=(0, 2, 2, 2, 3)),
     wl.Workload("k3_no_gb", (4, 2, 4), (8, 2, 4), (2, 2, 2), 72, wl.F32, 97, 98, 99, 1.0, roles=(0, 1, 2)),
     wl.Workload("k5_sparse_gr", (4, 2, 2, 4, 2), (4, 4, 2, 4, 2), (2, 2, 2, 2, 2), 100, wl.F32,
-                100, 101, 102, 1.0, roles=(0, 1, 1, 2, 3)),          # G_r not complete: generic kernel
+                100, 101, 102, 1.0, roles=(0, 1, 1, 2, 3)),          # sparse graph given to G_r: regrouped by the library
+    wl.Workload("k5_sparse_graph_joins_go", (4, 2, 2, 4, 2), (4, 4, 2, 4, 2), (2, 2, 2, 2, 2), 100, wl.F32,
+                100, 101, 102, 1.0, roles=(0, 0, 1, 2, 3)),          # the same graphs, the sparse second one in G_o: MFMA
 ]
 
 
@@ -385,9 +393,8 @@ def test_masks_of_more_than_four_base_graphs(w, dtype):
     folds them into the four factors of its kernels."""
     w = replace(w, dtype=dtype)
     err = gh.check_parity(w)
-    if "sparse_gr" not in w.name:
-        assert gh.family_covers(w, REG)
-        gh.check_parity(w, kernel=REG, expect_kernel=REG)
+    assert gh.family_covers(w, REG)
+    gh.check_parity(w, kernel=REG, expect_kernel=REG)
     gh.check_parity(w, kernel=GEN)
     # backward products of the same masks
     lib, f32 = gh.backward_inputs(w)
