@@ -94,9 +94,12 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // 4 / S column tiles.  Used when N is too small to give every SIMD a wave otherwise.
   const int lgS = p.lgS, S = 1 << lgS;
   const int ks = wid & (S - 1);
-  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.y;
-  const int ntq = xcd + 8 * int(blockIdx.z);
-  if ((ntq << (2 - lgS)) >= p.ntiles) return;
+  // With fewer than eight groups of column tiles the spare XCD slots take further clusters, so that
+  // a small batch still spreads over all eight XCDs.
+  const int xcd = blockIdx.x & 7, u3 = blockIdx.y;
+  const int cl = ((blockIdx.x >> 3) << (3 - p.lgX)) + (xcd >> p.lgX);
+  const int ntq = (xcd & ((1 << p.lgX) - 1)) + (int(blockIdx.z) << p.lgX);
+  if (cl >= p.ncl || (ntq << (2 - lgS)) >= p.ntiles) return;
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
   // byte offset of the wave's first column in a row of I (fused convolution: the lane's own
@@ -717,8 +720,13 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.lgS = lgS;
   const int64_t tiles_per_wg = 4 >> lgS;
   const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-  const int64_t qgroups = (nquads + 7) / 8;
+  int lgX = 3;   // groups of column tiles dealt to the XCDs side by side: the power of two >= nquads, at most 8
+  while (lgX > 0 && (int64_t(1) << (lgX - 1)) >= nquads) --lgX;
+  const int64_t qgroups = (nquads + (int64_t(1) << lgX) - 1) >> lgX;
+  const int64_t xgroups = (tab->ncl + (8 >> lgX) - 1) / (8 >> lgX);
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
+  rp.lgX = lgX;
+  rp.ncl = tab->ncl;
   // fused convolution on a tap-grouped layout whose image rows tile the 64 columns of a wave:
   // the variant that loads one of the three horizontal taps and builds the others.  Measured on
   // the VGG19 layers: 5-15 % faster for images 8 to 32 pixels wide, slower for 4-pixel-wide ones
@@ -733,14 +741,14 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
 #ifdef RBGP_EXPERIMENT
   static unsigned long long *trace_buf = nullptr;
   static int launches = 0;
-  const size_t trace_n = size_t(8 * tab->ncl) * qgroups * m->a[2] * 4 * 8;
+  const size_t trace_n = size_t(8 * xgroups) * qgroups * m->a[2] * 4 * 8;
   if (!trace_buf) RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&trace_buf), (size_t(1) << 24)));
   rp.trace = trace_buf;
   ++launches;
   const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
   if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
 #endif
-  hipLaunchKernelGGL(fn, dim3(unsigned(8 * tab->ncl), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
+  hipLaunchKernelGGL(fn, dim3(unsigned(8 * xgroups), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
 #ifdef RBGP_EXPERIMENT
   if (dump) {
     RBGP_HIP(hipDeviceSynchronize());

@@ -86,8 +86,11 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #endif
   const int ks = wid & (S - 1);          // this wave's share of the stage list
   // workgroup -> (XCD, cluster, G_i vertex, 4/S neighbouring column tiles); see the fp32 kernel
-  const int xcd = blockIdx.x & 7, cl = blockIdx.x >> 3, u3 = blockIdx.y;
-  const int nt = ((xcd + 8 * int(blockIdx.z)) << (2 - lgS)) + (wid >> lgS);
+  const int xcd = blockIdx.x & 7, u3 = blockIdx.y;
+  const int cl = ((blockIdx.x >> 3) << (3 - p.lgX)) + (xcd >> p.lgX);
+  if (cl >= p.ncl) return;               // (the whole workgroup)
+  const int ntq = (xcd & ((1 << p.lgX) - 1)) + (int(blockIdx.z) << p.lgX);
+  const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const bool valid = nt < p.ntiles;
   if (lgS == 0 && !valid) return;        // (with S > 1 every wave reaches the barrier below)
   const int64_t n0 = int64_t(nt) * CW;

@@ -53,6 +53,8 @@ struct RegParams {
   int tm;                  // rows of one tile row: a_r * a_i * a_b
   int ntiles;              // column tiles: ceil(N / columns per wave)
   int lgS;                 // log2 of the waves that share a column tile (split of the stage list)
+  int lgX, ncl;            // eight consecutive workgroups (one per XCD) = 2^lgX groups of column tiles x 8 / 2^lgX clusters;
+                           //   number of clusters
 #ifdef RBGP_EXPERIMENT
   unsigned long long *trace;   // [wave][8] timestamps
 #endif
