@@ -382,6 +382,8 @@ def main():
     ap.add_argument("--fused-conv", action="store_true",
                     help="time rbgp_conv3x3 (3x3 convolution with the lowering folded into the loads, fp32) on the "
                          "workload's layer instead of rbgp_spmm on the lowered input")
+    ap.add_argument("--out-bf16", action="store_true",
+                    help="bf16 workloads: store O as bf16 (dtype RBGP_BF16) instead of fp32")
     ap.add_argument("--backward", default="", choices=["", "backward_data", "weight_gradient", "both"],
                     help="time the backward products of the workload (dI = W^T dO, dW = dO I^T on the mask) "
                          "instead of the forward product; prints one JSON line with them")
@@ -418,6 +420,10 @@ def main():
         return
     w = WORKLOADS[args.workload]
     bf16 = w.dtype == wl.BF16
+    if args.out_bf16 and not bf16:
+        sys.exit("bench.py: --out-bf16 needs a bf16 workload (conv3)")
+    call_dtype = rb.BF16 if args.out_bf16 else w.dtype
+    out_bytes = 2 if args.out_bf16 else 4
 
     vals = wl.kept_weights(w)
     I = wl.activations(w)
@@ -444,7 +450,7 @@ def main():
         print(json.dumps({"workload": w.name, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
                           "steps": args.steps, "warmup": args.warmup, **res}))
         return
-    algorithmic_bytes = w.algorithmic_bytes
+    algorithmic_bytes = w.algorithmic_bytes - w.M * w.N * (4 - out_bytes)
     if args.fused_conv:
         if w.name not in wl.CONV_GEOMETRY:
             sys.exit("bench.py: --fused-conv needs a workload that is a lowered 3x3 convolution")
@@ -459,27 +465,28 @@ def main():
         # the oracle's operand for the parity check: the same activations, lowered explicitly
         from oracle import rbgp_oracle as orc
         I_f32 = orc.im2col_3x3(X) if not args.no_cpu_baseline else None
-        algorithmic_bytes = Xp.nbytes + w.M * w.N * 4 + w.nnz * w.in_bytes
-        set_bytes = Xp.nbytes + w.M * w.N * 4
+        algorithmic_bytes = Xp.nbytes + w.M * w.N * out_bytes + w.nnz * w.in_bytes
+        set_bytes = Xp.nbytes + w.M * w.N * out_bytes
         I0 = torch.from_numpy(Xp).to(dev)
     else:
         ld = w.N + args.ld_pad
-        set_bytes = (w.K * w.in_bytes + w.M * 4) * ld
+        set_bytes = (w.K * w.in_bytes + w.M * out_bytes) * ld
         I_pad = np.zeros((w.K, ld), dtype=I_lib.dtype)
         I_pad[:, :w.N] = I_lib
         I0 = torch.from_numpy(I_pad.view(np.int16) if bf16 else I_pad).to(dev)
     nsets = args.sets if args.sets > 0 else max(2, min(16, -(-512 * 2**20 // set_bytes)))
     Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
     ldO = w.N if args.fused_conv else w.N + args.ld_pad
-    Os = [torch.empty((w.M, ldO), dtype=torch.float32, device=dev) for _ in range(nsets)]
+    Os = [torch.empty((w.M, ldO), dtype=torch.int16 if args.out_bf16 else torch.float32, device=dev)
+          for _ in range(nsets)]
 
     def step(i):
         j = i % nsets
         if args.fused_conv:
-            rb.rbgp_conv3x3(mask, w.dtype, w.M, w.K // 9, B, H, W, packed.data_ptr(), Is[j].data_ptr(),
+            rb.rbgp_conv3x3(mask, call_dtype, w.M, w.K // 9, B, H, W, packed.data_ptr(), Is[j].data_ptr(),
                             Os[j].data_ptr(), w.N, stream)
         else:
-            rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), ldO,
+            rb.rbgp_spmm(mask, call_dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), ldO,
                          Os[j].data_ptr(), ldO, stream)
 
     for i in range(args.warmup):
@@ -519,14 +526,17 @@ def main():
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-           "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "density": w.density,
+           "config": {"workload": w.name, "output": "bf16" if args.out_bf16 else "f32", "M": w.M, "K": w.K, "N": w.N, "density": w.density,
                       "factors_rows": list(w.rows), "factors_cols": list(w.cols), "factors_row_deg": list(w.row_deg),
                       "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "tune": args.tune or "default",
                       "buffer_sets": nsets, "ld_pad": 0 if args.fused_conv else args.ld_pad,
                       "entry_point": "rbgp_conv3x3" if args.fused_conv else "rbgp_spmm"},
            "roofline": roof}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, Os[0].cpu().numpy()[:, :w.N])
+        O_host = Os[0].cpu().numpy()[:, :w.N]
+        if args.out_bf16:      # (bf16 bits widened exactly; the rounding stays inside the bf16 tolerance of the check)
+            O_host = wl.bf16_bits_as_f32(O_host.view(np.uint16))
+        out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, O_host)
     if not args.fused_conv and w.name in wl.CONV_GEOMETRY:
         out["fused_conv3x3"] = fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream,
                                                check=not args.no_cpu_baseline)

@@ -42,8 +42,12 @@ extern "C" {
 
 typedef struct rbgp_mask rbgp_mask_t; /* opaque, host memory */
 
-/* RBGP_F32: W, I fp32; RBGP_BF16_F32ACC: W, I bfloat16, fp32 accumulation.  O is fp32 in both. */
-typedef enum { RBGP_F32 = 0, RBGP_BF16_F32ACC = 1 } rbgp_dtype_t;
+/* RBGP_F32: W, I, O fp32.  RBGP_BF16_F32ACC: W, I bfloat16, fp32 accumulation, O fp32.
+ * RBGP_BF16: as RBGP_BF16_F32ACC, and rbgp_spmm / rbgp_conv3x3 round the fp32 sums to bfloat16
+ * (nearest, ties to even) when they store O; everywhere else (packing, layouts, kernel choice,
+ * rbgp_sddmm, whose dW stays fp32) the two bf16 modes are the same mode, and buffers packed for
+ * one serve the other.  (The paper states no precision: Section 5.) */
+typedef enum { RBGP_F32 = 0, RBGP_BF16_F32ACC = 1, RBGP_BF16 = 2 } rbgp_dtype_t;
 
 enum {
   RBGP_OK = 0,
@@ -238,9 +242,10 @@ int rbgp_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K
 
 /* O = W_s x I (Section 5, "GPU Implementation"; Algorithm 1 with C overwritten).
  * dev_I: K x N row-major with leading dimension ldI >= N elements (the lowered
- * convolution input, N = batch*H*W contiguous); dev_O: M x N row-major fp32 with
- * leading dimension ldO >= N, overwritten.  M and K must equal the mask's
- * (ESHAPE otherwise).  N == 0 is a no-op.  Buffers must not overlap.  The
+ * convolution input, N = batch*H*W contiguous); dev_O: M x N row-major fp32 (bf16 bits
+ * in RBGP_BF16 mode, 2-byte aligned) with leading dimension ldO >= N elements,
+ * overwritten.  M and K must equal the mask's (ESHAPE otherwise).  N == 0 is a
+ * no-op.  Buffers must not overlap.  The
  * RBGP_KERNEL_MFMA family needs dev_I 16-byte aligned and ldI a multiple of 4
  * (fp32) or 8 (bf16) elements, the RBGP_KERNEL_MFMA_REG family in bf16 mode dev_I
  * 8-byte aligned and ldI a multiple of 4 (64-column wave tiles), or 16-byte aligned
@@ -263,8 +268,8 @@ int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K,
  * dev_X: activations [channels_in][images][height + 2][width + 2] in the dtype's input type
  * (fp32, or bf16 bits), 4-byte aligned, with a border of one pixel that the caller keeps at
  * zero.  Row k = 9 * c + 3 * (dy + 1) + (dx + 1) of the lowered input is pixel (y + dy, x + dx)
- * of channel c; column n = (image * height + y) * width + x.  dev_O: M x N row-major fp32,
- * N = images * height * width, leading dimension ldO >= N, overwritten.  dev_packed: as for
+ * of channel c; column n = (image * height + y) * width + x.  dev_O: M x N row-major fp32
+ * (bf16 bits in RBGP_BF16 mode), N = images * height * width, leading dimension ldO >= N, overwritten.  dev_packed: as for
  * rbgp_spmm (same layout, same dtype).
  * Runs on the RBGP_KERNEL_MFMA_REG family only: EUNSUPPORTED for masks or kernel choices
  * outside it; ESHAPE unless width is a multiple of 4 and the sizes match the mask.

@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-F32, BF16_F32ACC = 0, 1
+F32, BF16_F32ACC, BF16 = 0, 1, 2   # BF16: as BF16_F32ACC with O stored as bf16 bits
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG = 0, 1, 2, 3
 TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_WEIGHTS_IN_LDS = 0, 1, 2, 3
 TUNE_ROW_GROUPS, TUNE_K_SPLIT = 4, 5

@@ -33,6 +33,7 @@
 #include <vector>
 
 #include "rbgp_internal.h"
+#include "rbgp_reg_common.h"
 
 #define RBGP_HIP(call)                                                              \
   do {                                                                              \
@@ -108,12 +109,18 @@ struct GenericParams {
   int64_t M, N, ldI, ldO, rowdeg;
 };
 
+bool valid_dtype(rbgp_dtype_t d) { return d == RBGP_F32 || d == RBGP_BF16_F32ACC || d == RBGP_BF16; }
+bool bf16_in(rbgp_dtype_t d) { return d != RBGP_F32; }
+
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(uint16_t x) { return __uint_as_float(uint32_t(x) << 16); }
 
-template <typename TIn>
+__device__ inline void store_out(float *o, float x) { *o = x; }
+__device__ inline void store_out(uint16_t *o, float x) { *o = uint16_t(rbgp_reg::bf16_bits(x)); }
+
+template <typename TIn, typename TOut>
 __global__ __launch_bounds__(256) void spmm_generic(GenericParams p, const TIn *__restrict__ W,
-                                                    const TIn *__restrict__ I, float *__restrict__ O) {
+                                                    const TIn *__restrict__ I, TOut *__restrict__ O) {
   const int64_t n = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
   for (int64_t m = blockIdx.y; m < p.M; m += gridDim.y) {
     int64_t r = m;
@@ -137,7 +144,7 @@ __global__ __launch_bounds__(256) void spmm_generic(GenericParams p, const TIn *
         }
       }
     }
-    if (n < p.N) O[m * p.ldO + n] = acc;
+    if (n < p.N) store_out(O + m * p.ldO + n, acc);
   }
 }
 
@@ -147,7 +154,8 @@ __global__ __launch_bounds__(256) void spmm_generic(GenericParams p, const TIn *
 struct MfmaParams {
   const void *Wp;
   const void *I;
-  float *O;
+  float *O;               // fp32, or bf16 bits when obf16 is set (ldO counts elements of that type)
+  int obf16;              // bf16 kernels: round the sums to bf16 when storing O
   const int32_t *adj0;    // [a_o][d_o]
   const int32_t *rowoff;  // [a_i][KS]
   int64_t N, ldI, ldO;
@@ -296,6 +304,30 @@ __global__ __launch_bounds__(512) void spmm_mfma(MfmaParams p) {
 
   // epilogue: lane holds columns n0 + nsub*64*T + lane*T + t of rows rb*4 + i of its group
   const int64_t nbase = n0 + nsub * 64 * T + lane * T;
+  if constexpr (BF16) {
+    if (p.obf16) {
+      uint16_t *const Ob = reinterpret_cast<uint16_t *>(p.O);
+      const bool pair_ok = (T == 2) && (p.ldO % 2 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 4 == 0) && (nbase + 2 <= p.N);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = rb * 4 + i;
+          if (r >= p.R) continue;
+          const int u2 = r / p.a4, u4 = r - u2 * p.a4;
+          const int64_t m = ((int64_t(u1) * p.a2 + u2) * p.a3 + u3) * p.a4 + u4;
+          uint16_t *o = Ob + m * p.ldO + nbase;
+          if (pair_ok) {
+            *reinterpret_cast<uint32_t *>(o) = rbgp_reg::bf16_pair(acc[rb][0][i], acc[rb][T - 1][i]);
+          } else {
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+              if (nbase + t < p.N) o[t] = uint16_t(rbgp_reg::bf16_bits(acc[rb][t][i]));
+          }
+        }
+      return;
+    }
+  }
   const bool vec_ok = (T > 1) && ((p.ldO % T) == 0) && ((reinterpret_cast<uintptr_t>(p.O) % (4 * T)) == 0) &&
                       (nbase + T <= p.N);
 #pragma unroll
@@ -383,7 +415,7 @@ int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
 
 int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
   if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
-  if (kernel == RBGP_KERNEL_MFMA_REG) return dtype == RBGP_BF16_F32ACC ? m->reg.packed_elems_bf16 : m->reg.packed_elems;
+  if (kernel == RBGP_KERNEL_MFMA_REG) return bf16_in(dtype) ? m->reg.packed_elems_bf16 : m->reg.packed_elems;
   return m->nnz;
 }
 
@@ -432,7 +464,7 @@ int ensure_perm(const rbgp_mask *m, int kernel, bool bf16, bool original_order, 
   return upload(perm, &dev->perm[*slot]);
 }
 
-size_t elem_bytes(rbgp_dtype_t dt) { return dt == RBGP_BF16_F32ACC ? 2 : 4; }
+size_t elem_bytes(rbgp_dtype_t dt) { return bf16_in(dt) ? 2 : 4; }
 
 }  // namespace
 
@@ -448,7 +480,7 @@ int rbgp_mask_set_kernel(rbgp_mask_t *m, int kernel) {
 }
 
 int rbgp_mask_kernel(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
-  if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return RBGP_EINVAL;
+  if (!m || !valid_dtype(dtype)) return RBGP_EINVAL;
   return resolve_kernel(m, dtype);
 }
 
@@ -463,14 +495,14 @@ int rbgp_mask_tune(rbgp_mask_t *m, int knob, int value) {
 }
 
 size_t rbgp_packed_bytes(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
-  if (!m || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return 0;
+  if (!m || !valid_dtype(dtype)) return 0;
   return size_t(packed_elems(m, resolve_kernel(m, dtype), dtype)) * elem_bytes(dtype);
 }
 
 int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
-  if (!m || !out || (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC)) return RBGP_EINVAL;
+  if (!m || !out || !valid_dtype(dtype)) return RBGP_EINVAL;
   std::vector<int32_t> perm;
-  rbgp_build_pack_perm(m, resolve_kernel(m, dtype), dtype == RBGP_BF16_F32ACC, perm);
+  rbgp_build_pack_perm(m, resolve_kernel(m, dtype), bf16_in(dtype), perm);
   std::copy(perm.begin(), perm.end(), out);
   return RBGP_OK;
 }
@@ -478,13 +510,13 @@ int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
 static int pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *dev_values,
                        void *dev_packed, void *hip_stream) {
   if (!m || !dev_values || !dev_packed) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
   if (original_order && m->from_original.empty()) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
   const int kernel = resolve_kernel(m, dtype);
   int slot;
-  rc = ensure_perm(m, kernel, dtype == RBGP_BF16_F32ACC, original_order, &slot);
+  rc = ensure_perm(m, kernel, bf16_in(dtype), original_order, &slot);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t n = int64_t(m->dev->perm_elems[slot]);
@@ -512,7 +544,7 @@ int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, c
 static int pack_host(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *host_values,
                      void *dev_packed, void *hip_stream) {
   if (!m || !host_values || !dev_packed) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
   if (original_order && m->from_original.empty()) return RBGP_EINVAL;
   int rc = ensure_device(m);
   if (rc) return rc;
@@ -546,7 +578,7 @@ int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const vo
 int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
                int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
   if (M != m->M || K != m->K || N < 0 || ld_dO < N || ldI < N) return RBGP_ESHAPE;
   if (!dev_dW || (N > 0 && (!dev_dO || !dev_I))) return RBGP_EINVAL;
   if ((reinterpret_cast<uintptr_t>(dev_dO) | reinterpret_cast<uintptr_t>(dev_I) | reinterpret_cast<uintptr_t>(dev_dW)) & 3)
@@ -554,7 +586,7 @@ int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, i
   int rc = ensure_device(m);
   if (rc) return rc;
   rbgp_device_state *dev = m->dev;
-  const bool bf16 = dtype == RBGP_BF16_F32ACC;
+  const bool bf16 = bf16_in(dtype);
   // the MFMA kernel loads 16 bytes at dword-aligned addresses: bf16 rows must start on a dword
   const bool aligned = !bf16 || (ld_dO % 2 == 0 && ldI % 2 == 0);
   const bool use_mfma = m->kernel_choice != RBGP_KERNEL_GENERIC && rbgp_reg_covers(m) && aligned;
@@ -565,7 +597,7 @@ int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, i
 int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,
               const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
   if (M != m->M || K != m->K || N < 0 || ldI < N || ldO < N) return RBGP_ESHAPE;
   if (N == 0) return RBGP_OK;
   if (!dev_packed || !dev_I || !dev_O) return RBGP_EINVAL;
@@ -574,11 +606,12 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   rbgp_device_state *dev = m->dev;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int kernel = resolve_kernel(m, dtype);
-  const bool bf16 = dtype == RBGP_BF16_F32ACC;
+  const bool bf16 = bf16_in(dtype), out_bf16 = dtype == RBGP_BF16;
+  if (out_bf16 && (reinterpret_cast<uintptr_t>(dev_O) & 1)) return RBGP_ESHAPE;
 
   if (kernel == RBGP_KERNEL_MFMA_REG)
-    return rbgp_reg_launch(m, &dev->reg_state, dev->tune, bf16, N, dev_packed, dev_I, ldI,
-                           static_cast<float *>(dev_O), ldO, hip_stream);
+    return rbgp_reg_launch(m, &dev->reg_state, dev->tune, bf16, out_bf16, N, dev_packed, dev_I, ldI, dev_O, ldO,
+                           hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {
     GenericParams gp;
@@ -590,13 +623,18 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
     }
     gp.M = M; gp.N = N; gp.ldI = ldI; gp.ldO = ldO; gp.rowdeg = m->rowdeg;
     const dim3 grid(unsigned((N + 255) / 256), unsigned(M < 32768 ? M : 32768)), block(256);
-    if (bf16)
-      spmm_generic<uint16_t><<<grid, block, 0, st>>>(gp, static_cast<const uint16_t *>(dev_packed),
-                                                     static_cast<const uint16_t *>(dev_I),
-                                                     static_cast<float *>(dev_O));
+    if (out_bf16)
+      spmm_generic<uint16_t, uint16_t><<<grid, block, 0, st>>>(gp, static_cast<const uint16_t *>(dev_packed),
+                                                               static_cast<const uint16_t *>(dev_I),
+                                                               static_cast<uint16_t *>(dev_O));
+    else if (bf16)
+      spmm_generic<uint16_t, float><<<grid, block, 0, st>>>(gp, static_cast<const uint16_t *>(dev_packed),
+                                                            static_cast<const uint16_t *>(dev_I),
+                                                            static_cast<float *>(dev_O));
     else
-      spmm_generic<float><<<grid, block, 0, st>>>(gp, static_cast<const float *>(dev_packed),
-                                                  static_cast<const float *>(dev_I), static_cast<float *>(dev_O));
+      spmm_generic<float, float><<<grid, block, 0, st>>>(gp, static_cast<const float *>(dev_packed),
+                                                         static_cast<const float *>(dev_I),
+                                                         static_cast<float *>(dev_O));
     RBGP_HIP(hipGetLastError());
     return RBGP_OK;
   }
@@ -624,6 +662,7 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
 
   MfmaParams mp;
   mp.Wp = dev_packed; mp.I = dev_I; mp.O = static_cast<float *>(dev_O);
+  mp.obf16 = out_bf16 ? 1 : 0;
   mp.adj0 = dev->adj[0]; mp.rowoff = dev->rowoff;
   mp.N = N; mp.ldI = ldI; mp.ldO = ldO;
   mp.a1 = m->a[0]; mp.a2 = m->a[1]; mp.a3 = m->a[2]; mp.a4 = m->a[3];
@@ -650,25 +689,26 @@ int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out,
                  int64_t height, int64_t width, const void *dev_packed, const void *dev_X, void *dev_O, int64_t ldO,
                  void *hip_stream) {
   if (!m) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
   if (images <= 0 || height <= 0 || width <= 0 || (width % 4)) return RBGP_ESHAPE;
   const int64_t N = images * height * width;
   if (channels_out != m->M || 9 * channels_in != m->K || ldO < N) return RBGP_ESHAPE;
   if (resolve_kernel(m, dtype) != RBGP_KERNEL_MFMA_REG) return RBGP_EUNSUPPORTED;
   if (!dev_packed || !dev_X || !dev_O) return RBGP_EINVAL;
+  if (dtype == RBGP_BF16 && (reinterpret_cast<uintptr_t>(dev_O) & 1)) return RBGP_ESHAPE;
   int rc = ensure_device(m);
   if (rc) return rc;
   const rbgp_conv_geometry geom = {images, height, width};
-  return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, dtype == RBGP_BF16_F32ACC, N, dev_packed, dev_X, N,
-                         static_cast<float *>(dev_O), ldO, hip_stream, &geom);
+  return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, bf16_in(dtype), dtype == RBGP_BF16, N, dev_packed, dev_X,
+                         N, dev_O, ldO, hip_stream, &geom);
 }
 
 int rbgp_conv3x3_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
                        int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
                        const void *dev_X, float *dev_dW, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
-  if (dtype != RBGP_F32 && dtype != RBGP_BF16_F32ACC) return RBGP_EINVAL;
-  const bool bf16 = dtype == RBGP_BF16_F32ACC;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
+  const bool bf16 = bf16_in(dtype);
   if (images <= 0 || height <= 0 || width <= 0 || (width % (bf16 ? 8 : 4))) return RBGP_ESHAPE;
   const int64_t N = images * height * width;
   if (channels_out != m->M || 9 * channels_in != m->K || ld_dO < N) return RBGP_ESHAPE;

@@ -118,9 +118,9 @@ struct rbgp_conv_geometry {
   int64_t images, height, width;
 };
 // conv == nullptr: I is the K x N matrix; else I is the zero-padded activation tensor
-// [K / 9][images][height + 2][width + 2] and ldI is ignored
-int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
-                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream,
+// [K / 9][images][height + 2][width + 2] and ldI is ignored.  out_bf16 (bf16 only): O holds bf16 bits
+int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, bool out_bf16, int64_t N,
+                    const void *packed, const void *I, int64_t ldI, void *O, int64_t ldO, void *stream,
                     const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
 // weight-gradient kernels (rbgp_sddmm.hip); use_mfma needs rbgp_reg_covers(m)

@@ -550,10 +550,12 @@ void rbgp_reg_release(void *state) {
   delete st;
 }
 
-int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, int64_t N, const void *packed,
-                    const void *I, int64_t ldI, float *O, int64_t ldO, void *stream, const rbgp_conv_geometry *conv) {
+int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16, bool out_bf16, int64_t N,
+                    const void *packed, const void *I, int64_t ldI, void *O, int64_t ldO, void *stream,
+                    const rbgp_conv_geometry *conv) {
   const rbgp_reg_plan &pl = m->reg;
   if (!rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
+  if (out_bf16 && !bf16) return RBGP_EINVAL;
   // Fused 3x3 convolution: the nine taps are the columns of a complete G_b and an image row holds
   // whole lane loads (4 columns; 8 with the wide bf16 tile); "I" is then the padded activation
   // tensor and ldI is not used.
@@ -675,7 +677,8 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
   rp.I = static_cast<const float *>(I);
-  rp.O = O;
+  rp.O = static_cast<float *>(O);
+  rp.obf16 = out_bf16 ? 1 : 0;
   rp.rowtab = *rowtab;
   rp.stages = tab->stages; rp.counts = tab->counts; rp.members = tab->members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;

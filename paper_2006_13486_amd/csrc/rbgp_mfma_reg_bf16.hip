@@ -286,7 +286,11 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 
   // Epilogue.  Unit (gi, t) = register t of group gi's NC accumulators: weight row
   // 4*(lane/16) + t of the group, lane j the columns NC*j + w.
-  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * NC + NC <= p.N);
+  // (bf16 output: a lane's NC columns are 2 * NC bytes, stored whole when they are aligned)
+  const bool obf = p.obf16 != 0;
+  const bool vec_ok = (n0 + j * NC + NC <= p.N) &&
+                      (obf ? (p.ldO % NC == 0) && (reinterpret_cast<uintptr_t>(p.O) % (2 * NC) == 0)
+                           : (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0));
   auto unit_piece = [&](int gi, int t, int h) {
     return f32x4{acc[gi][4 * h][t], acc[gi][4 * h + 1][t], acc[gi][4 * h + 2][t], acc[gi][4 * h + 3][t]};
   };
@@ -296,6 +300,26 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
     if (valid && u1 >= 0 && r < p.R) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
+      if (obf) {
+        uint16_t *o = reinterpret_cast<uint16_t *>(p.O) + m * p.ldO + n0 + j * NC;
+        if (vec_ok) {
+          if constexpr (NH == 2) {
+            const u32x4 w = {bf16_pair(v[0][0], v[0][1]), bf16_pair(v[0][2], v[0][3]), bf16_pair(v[1][0], v[1][1]),
+                             bf16_pair(v[1][2], v[1][3])};
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(o));
+          } else {
+            const u32x2 w = {bf16_pair(v[0][0], v[0][1]), bf16_pair(v[0][2], v[0][3])};
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(o));
+          }
+        } else {
+#pragma unroll
+          for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+              if (n0 + j * NC + 4 * h + w < p.N) o[4 * h + w] = uint16_t(bf16_bits(v[h][w]));
+        }
+        return;
+      }
       float *o = p.O + m * p.ldO + n0 + j * NC;
       if (vec_ok) {
 #pragma unroll

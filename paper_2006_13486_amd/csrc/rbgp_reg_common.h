@@ -22,10 +22,21 @@ __device__ __forceinline__ void static_for(F &&f) {
   }
 }
 
+// fp32 -> bfloat16 bits, round to nearest, ties to even: the conversion instruction of gfx950
+// (v_cvt_pk_bf16_f32, two values each), which the compiler selects for these casts.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ uint32_t bf16_bits(float x) { return bf16_pair(x, 0.f) & 0xffffu; }
+
 struct RegParams {
   const float *Wp;         // packed weights (fp32, or bf16 bits for the bf16 kernels)
   const float *I;          // activations (same)
-  float *O;
+  float *O;                // fp32, or bf16 bits when obf16 is set (ldO counts elements of that type)
+  int obf16;               // bf16 kernels: round the sums to bf16 when storing O
   const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
   const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
                            //   cluster member j_o * NSTG + (stage within the tile), the position of its

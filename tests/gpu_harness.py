@@ -27,7 +27,22 @@ def host_inputs(w, N=None, vals=None, I=None):
     return vals, I, vals, I
 
 
-def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0, tag=""):
+def _output(rows, ld, out_bf16):
+    """Device matrix for O filled with NaN (fp32, or bf16 NaN bits for the bf16-output mode)."""
+    import torch
+    if out_bf16:
+        return torch.full((rows, max(ld, 1)), 0x7FC0, dtype=torch.int16, device="cuda:0")
+    return torch.full((rows, max(ld, 1)), float("nan"), dtype=torch.float32, device="cuda:0")
+
+
+def _output_to_host(O_d, out_bf16):
+    """fp32 values of O (bf16 bits widened exactly; this is a reinterpretation, not arithmetic)."""
+    if out_bf16:
+        return wl.bf16_bits_as_f32(O_d.cpu().numpy().view(np.uint16))
+    return O_d.cpu().numpy()
+
+
+def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0, tag="", out_bf16=False):
     import torch
     dev = torch.device("cuda:0")
     N = I_lib.shape[1]
@@ -47,17 +62,18 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     I_d = torch.from_numpy(I_host.view(np.int16) if w.dtype == wl.BF16 else I_host).to(dev)
     assert I_d.dtype == tdt
     ldO = N + ld_pad
-    O_d = torch.full((w.M, max(ldO, 1)), float("nan"), dtype=torch.float32, device=dev)
-    rb.rbgp_spmm(mask, w.dtype, w.M, w.K, N, packed.data_ptr(), I_d.data_ptr(), ldI, O_d.data_ptr(), ldO, stream)
+    O_d = _output(w.M, ldO, out_bf16)
+    rb.rbgp_spmm(mask, rb.BF16 if out_bf16 else w.dtype, w.M, w.K, N, packed.data_ptr(), I_d.data_ptr(), ldI,
+                 O_d.data_ptr(), ldO, stream)
     torch.cuda.synchronize()
-    out = O_d.cpu().numpy()
+    out = _output_to_host(O_d, out_bf16)
     if ld_pad:
         assert np.all(np.isnan(out[:, N:])), "kernel wrote outside the N columns"
     used = rb.rbgp_mask_kernel(mask, w.dtype)
     return out[:, :N], used
 
 
-def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
+def library_conv3x3(w, vals, X, dtype=None, tune=None, tag="", out_bf16=False):
     """Run rbgp_conv3x3 on X[C][B][H][W] (padded here: layout work, not arithmetic)."""
     import torch
     dev = torch.device("cuda:0")
@@ -73,10 +89,11 @@ def library_conv3x3(w, vals, X, dtype=None, tune=None, tag=""):
     rb.rbgp_pack(mask, dtype, np.ascontiguousarray(vals), packed.data_ptr(), stream)
     Xp = wl.zero_padded(X)
     X_d = torch.from_numpy(Xp.view(np.int16) if Xp.dtype == np.uint16 else Xp).to(dev)
-    O_d = torch.full((w.M, N), float("nan"), dtype=torch.float32, device=dev)
-    rb.rbgp_conv3x3(mask, dtype, w.M, C, B, H, W, packed.data_ptr(), X_d.data_ptr(), O_d.data_ptr(), N, stream)
+    O_d = _output(w.M, N, out_bf16)
+    rb.rbgp_conv3x3(mask, rb.BF16 if out_bf16 else dtype, w.M, C, B, H, W, packed.data_ptr(), X_d.data_ptr(),
+                    O_d.data_ptr(), N, stream)
     torch.cuda.synchronize()
-    return O_d.cpu().numpy()
+    return _output_to_host(O_d, out_bf16)
 
 
 def _to_device(a, ld_pad):

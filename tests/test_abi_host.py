@@ -223,6 +223,24 @@ def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
         assert np.array_equal(layout, np.arange(nnz, dtype=np.int32))     # canonical order itself
 
 
+def test_the_two_bf16_modes_share_kernel_choice_and_layout():
+    """RBGP_BF16 only changes how rbgp_spmm / rbgp_conv3x3 store O: packed buffers are interchangeable."""
+    for rows, cols, deg in LAYOUT_SHAPES[:4]:
+        mask = rb.rbgp_make_mask(rows, cols, deg, 5)
+        for kernel in (rb.KERNEL_AUTO, rb.KERNEL_GENERIC):
+            rb.rbgp_mask_set_kernel(mask, kernel)
+            assert rb.rbgp_mask_kernel(mask, rb.BF16) == rb.rbgp_mask_kernel(mask, rb.BF16_F32ACC)
+            assert rb.rbgp_packed_bytes(mask, rb.BF16) == rb.rbgp_packed_bytes(mask, rb.BF16_F32ACC)
+            assert np.array_equal(rb.rbgp_pack_layout(mask, rb.BF16), rb.rbgp_pack_layout(mask, rb.BF16_F32ACC))
+    lib = rb.load()
+    assert lib.rbgp_mask_kernel(mask.handle, 3) == rb.EINVAL
+    assert lib.rbgp_packed_bytes(mask.handle, 3) == 0
+    w = wl.TINY
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, 1)
+    assert lib.rbgp_spmm(mask.handle, rb.BF16, w.M + 1, w.K, 8, None, None, 8, None, 8, None) == rb.ESHAPE
+    assert lib.rbgp_spmm(mask.handle, rb.BF16, w.M, w.K, 0, None, None, 0, None, 0, None) == rb.OK
+
+
 # ---------------------------------------------------------------- transposed mask (backward data product)
 @pytest.mark.parametrize("shape", LAYOUT_SHAPES[:6] + LAYOUT_SHAPES[9:], ids=lambda s: "x".join(map(str, s[0])))
 def test_transposed_mask_and_order_match_the_oracle(shape):
