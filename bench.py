@@ -537,7 +537,8 @@ def main():
         if args.out_bf16:      # (bf16 bits widened exactly; the rounding stays inside the bf16 tolerance of the check)
             O_host = wl.bf16_bits_as_f32(O_host.view(np.uint16))
         out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, O_host)
-    if not args.fused_conv and w.name in wl.CONV_GEOMETRY:
+    if not args.fused_conv and w.name in wl.CONV_GEOMETRY and \
+            rb.rbgp_mask_kernel(mask, w.dtype) == rb.KERNEL_MFMA_REG:     # (the fused call runs on that family only)
         out["fused_conv3x3"] = fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream,
                                                check=not args.no_cpu_baseline)
     if not args.fused_conv and args.workload == "conv5":

@@ -72,8 +72,14 @@ enum {
   RBGP_KERNEL_AUTO = 0,
   RBGP_KERNEL_GENERIC = 1,  /* plain FMA, any four-factor mask, canonical layout */
   RBGP_KERNEL_MFMA = 2,     /* RBGP4 masks: I tiles staged in LDS, MFMA on the dense blocks */
-  RBGP_KERNEL_MFMA_REG = 3  /* RBGP4 masks: I rows streamed into registers and reused across a
+  RBGP_KERNEL_MFMA_REG = 3, /* RBGP4 masks: I rows streamed into registers and reused across a
                                cluster of tile rows, 16-row MFMA on the dense blocks */
+  RBGP_KERNEL_MFMA_TILE = 4 /* bf16 modes only, never chosen by AUTO: every nonzero of G_o as a dense
+                               block of W_s (zeros where the inner graphs have no edge), I staged in
+                               LDS once per workgroup, 32-row MFMA.  Any inner graphs; needs
+                               |G_r.U| |G_i.U| |G_b.U| = 32 or 64 and |G_r.V| |G_i.V| |G_b.V| <= 320.
+                               rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8
+                               (ESHAPE); rbgp_conv3x3 and fp32 do not run on it (EUNSUPPORTED) */
 };
 
 /* tuning knobs (rbgp_mask_tune) */

@@ -55,6 +55,7 @@ struct rbgp_device_state {
   int32_t *perm[4 * RBGP_NUM_KERNELS] = {};
   size_t perm_elems[4 * RBGP_NUM_KERNELS] = {};
   void *reg_state = nullptr;             // tables of the register-streaming family
+  void *tile_state = nullptr;            // tables of the tile family
   void *sddmm_state = nullptr;           // tables and partial sums of the weight-gradient kernels
   void *staging = nullptr;               // canonical values on their way through rbgp_pack
   size_t staging_bytes = 0;
@@ -69,6 +70,7 @@ void rbgp_device_release(rbgp_device_state *dev) {
   for (int32_t *t : dev->perm)
     if (t) (void)hipFree(t);
   rbgp_reg_release(dev->reg_state);
+  rbgp_tile_release(dev->tile_state);
   rbgp_sddmm_release(dev->sddmm_state);
   if (dev->staging) (void)hipFree(dev->staging);
   delete dev;
@@ -383,6 +385,8 @@ bool mfma_covers(const rbgp_mask *m) {
 // else the LDS family, else GENERIC.
 int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
   const bool reg_ok = rbgp_reg_covers(m);
+  // (the tile family has bf16 kernels only: fp32 calls on such a mask take the default choice)
+  if (m->kernel_choice == RBGP_KERNEL_MFMA_TILE && bf16_in(dtype) && rbgp_plan_tile(m).ok) return RBGP_KERNEL_MFMA_TILE;
   switch (m->kernel_choice) {
     case RBGP_KERNEL_GENERIC: return RBGP_KERNEL_GENERIC;
     case RBGP_KERNEL_MFMA: return mfma_covers(m) ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
@@ -415,6 +419,7 @@ int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
 
 int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
   if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
+  if (kernel == RBGP_KERNEL_MFMA_TILE) return rbgp_plan_tile(m).packed_elems;
   if (kernel == RBGP_KERNEL_MFMA_REG) return bf16_in(dtype) ? m->reg.packed_elems_bf16 : m->reg.packed_elems;
   return m->nnz;
 }
@@ -475,6 +480,7 @@ int rbgp_mask_set_kernel(rbgp_mask_t *m, int kernel) {
   if (kernel < RBGP_KERNEL_AUTO || kernel >= RBGP_NUM_KERNELS) return RBGP_EINVAL;
   if (kernel == RBGP_KERNEL_MFMA && !mfma_covers(m)) return RBGP_EUNSUPPORTED;
   if (kernel == RBGP_KERNEL_MFMA_REG && !rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
+  if (kernel == RBGP_KERNEL_MFMA_TILE && !rbgp_plan_tile(m).ok) return RBGP_EUNSUPPORTED;
   m->kernel_choice = kernel;
   return RBGP_OK;
 }
@@ -612,6 +618,9 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   if (kernel == RBGP_KERNEL_MFMA_REG)
     return rbgp_reg_launch(m, &dev->reg_state, dev->tune, bf16, out_bf16, N, dev_packed, dev_I, ldI, dev_O, ldO,
                            hip_stream);
+
+  if (kernel == RBGP_KERNEL_MFMA_TILE)
+    return rbgp_tile_launch(m, &dev->tile_state, out_bf16, N, dev_packed, dev_I, ldI, dev_O, ldO, hip_stream);
 
   if (kernel == RBGP_KERNEL_GENERIC) {
     GenericParams gp;

@@ -480,6 +480,37 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
 //           32 and at kk = 32q + 4g + e (e < 4; the rest is padding) in the block of 16:
 //           the consecutive contraction steps one lane feeds to the matrix core.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
+  if (kernel == RBGP_KERNEL_MFMA_TILE) {
+    // [u_o][j_o][c][h][row][e]: element e = 0..7 is the weight of row `row` of the tile at tile column
+    // 16c + 8h + e (the eight consecutive contraction steps one lane feeds to a 16-step MFMA); tile column
+    // (v_r * |G_i.V| + v_i) * |G_b.V| + v_b; zero where an inner graph has no edge and past TK.
+    const rbgp_tile_plan p = rbgp_plan_tile(m);
+    perm.assign(size_t(p.packed_elems), -1);
+    std::vector<int32_t> where[4];   // where[i][u * c_i + v]: position of v in adj_i[u], -1: no edge
+    for (int i = 1; i < 4; ++i) {
+      where[i].assign(size_t(m->a[i]) * m->c[i], -1);
+      for (int u = 0; u < m->a[i]; ++u)
+        for (int j = 0; j < m->d[i]; ++j) where[i][size_t(u) * m->c[i] + m->adj[i][size_t(u) * m->d[i] + j]] = j;
+    }
+    size_t pos = 0;
+    for (int u1 = 0; u1 < m->a[0]; ++u1)
+      for (int j1 = 0; j1 < m->d[0]; ++j1)
+        for (int c = 0; c < p.TKP / 16; ++c)
+          for (int h = 0; h < 2; ++h)
+            for (int row = 0; row < p.TM; ++row)
+              for (int e = 0; e < 8; ++e, ++pos) {
+                const int kk = 16 * c + 8 * h + e;
+                if (kk >= p.TK) continue;
+                const int v4 = kk % m->c[3], v3 = (kk / m->c[3]) % m->c[2], v2 = kk / (m->c[3] * m->c[2]);
+                const int u4 = row % m->a[3], u3 = (row / m->a[3]) % m->a[2], u2 = row / (m->a[3] * m->a[2]);
+                const int j2 = where[1][size_t(u2) * m->c[1] + v2], j3 = where[2][size_t(u3) * m->c[2] + v3],
+                          j4 = where[3][size_t(u4) * m->c[3] + v4];
+                if (j2 < 0 || j3 < 0 || j4 < 0) continue;
+                const int64_t t = ((int64_t(j1) * m->d[1] + j2) * m->d[2] + j3) * m->d[3] + j4;
+                perm[pos] = int32_t((int64_t(u1) * p.TM + row) * m->rowdeg + t);
+              }
+    return;
+  }
   if (kernel == RBGP_KERNEL_MFMA_REG && bf16) {
     const rbgp_reg_plan &p = m->reg;
     const int a1 = p.TR, a2 = p.A2, a3 = m->a[2], a4 = m->a[3], d1 = m->d[0];

@@ -106,7 +106,29 @@ inline int rbgp_reg_step(const rbgp_mask *m, int kk) {
   return (pair / 3) * 9 + 3 * dyi + dxi;
 }
 
-enum { RBGP_NUM_KERNELS = 4 };   // one more than the largest RBGP_KERNEL_* value
+enum { RBGP_NUM_KERNELS = 5 };   // one more than the largest RBGP_KERNEL_* value
+
+// Shape of the tile kernels (rbgp_mfma_tile.hip): every nonzero of G_o is a dense TM x TK block of W_s
+// (zero where the inner graphs have no edge), multiplied in 32-row blocks by 16-step MFMAs.
+struct rbgp_tile_plan {
+  bool ok = false;
+  int TM = 0;    // rows of a tile: |G_r.U| * |G_i.U| * |G_b.U| (32)
+  int TK = 0;    // columns of a tile: |G_r.V| * |G_i.V| * |G_b.V|
+  int TKP = 0;   // TK rounded up to a stage length the kernels are built for (16 x 2, 4, 5, 8, 9, 16, 18, 20);
+                 //   the padding holds zero weights
+  int64_t packed_elems = 0;   // |G_o.U| * d_o * TKP * TM
+};
+inline rbgp_tile_plan rbgp_plan_tile(const rbgp_mask *m) {
+  rbgp_tile_plan p;
+  const int64_t tm = int64_t(m->a[1]) * m->a[2] * m->a[3], tk = int64_t(m->c[1]) * m->c[2] * m->c[3];
+  if (tm != 32 || tk > 320 || m->c[0] > 256) return p;
+  p.TM = int(tm); p.TK = int(tk);
+  for (int nc : {20, 18, 16, 9, 8, 5, 4, 2})
+    if (16 * nc >= tk) p.TKP = 16 * nc;
+  p.packed_elems = int64_t(m->a[0]) * m->d[0] * p.TKP * p.TM;
+  p.ok = p.packed_elems * 2 < (int64_t(1) << 30);   // (32-bit offsets into the packed weights)
+  return p;
+}
 
 // device part
 void rbgp_device_release(rbgp_device_state *dev);
@@ -123,6 +145,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
                     const void *packed, const void *I, int64_t ldI, void *O, int64_t ldO, void *stream,
                     const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
+// tile family (rbgp_mfma_tile.hip; bf16 inputs only); needs rbgp_plan_tile(m).ok
+int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N, const void *packed, const void *I,
+                     int64_t ldI, void *O, int64_t ldO, void *stream);
+void rbgp_tile_release(void *state);
 // weight-gradient kernels (rbgp_sddmm.hip); use_mfma needs rbgp_reg_covers(m)
 // conv != nullptr (needs use_mfma): I is the zero-padded activation tensor of a 3x3 convolution, ldI is ignored
 int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,

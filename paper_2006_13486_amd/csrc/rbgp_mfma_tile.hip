@@ -1,0 +1,417 @@
+// Tile kernel for O = W_s x I (Section 5, "GPU Implementation"), bf16 inputs with fp32
+// accumulation: v_mfma_f32_32x32x16_bf16.
+//
+// The level of the pattern this kernel uses is the outermost one: every nonzero of G_o is a
+// TM x TK block of W_s (TM = |G_r.U| |G_i.U| |G_b.U| rows, TK = |G_r.V| |G_i.V| |G_b.V| columns), and the
+// rows of I one block multiplies are consecutive (tile skipping through G_o's adjacency, as in
+// Section 5).  Inside a block the weights are stored dense, with zeros where the inner graphs
+// have no edge: the bf16 matrix core has the room (a 32x32x16 MFMA issues every ~35 cycles), and
+// in return the B operand needs no gather, every row of a tile row is useful to every MFMA, and
+// a workgroup can stage I in LDS ONCE for all its tile rows -- the register-streaming family is
+// bound by the bytes of I that cross the L1 path (every cluster and G_i vertex loads its own).
+//
+// Workgroup = 4 consecutive tile rows x 64 columns.  Stage = one tile column that any of
+// the four tile rows has (host table, ascending): its TKP rows x 64 columns of I are loaded with
+// 16-byte loads (a lane takes 8 rows x 8 columns), transposed in registers (v_perm_b32) into, per
+// column, eight consecutive contraction steps (what one lane feeds the matrix core), and written
+// to LDS as [8-row block][column position][16 bytes], position = column ^ (2 * ((column / 16) % 4) + block % 2):
+// the 16-byte writes of 16 neighbouring lanes (8 column octets x 2 blocks, same column offset) then fall
+// on 16 different bank groups, while the 32 lanes of a read still cover 512 contiguous bytes.  Two buffers:
+// the loads of stage s + 1 are issued before the MFMAs of stage s and land in LDS after them.
+// A wave whose tile row lacks the tile column skips the MFMAs of the stage (its weight loads
+// point past the packed buffer and return zeros without a memory access).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "rbgp_internal.h"
+#include "rbgp_reg_common.h"
+
+using namespace rbgp_reg;
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kInline = 240;
+
+struct TileParams {
+  const void *Wp;          // packed weights: [tile row][j_o][TKP / 16][2][TM][8] bf16
+  const void *I;           // K x ldI bf16
+  void *O;                 // M x ldO fp32, or bf16 bits when obf16 is set
+  const int32_t *stages;   // [row groups][max_stages][5]: tile column, then per wave the index j_o of the tile
+                           //   in its tile row's adjacency list (-1: the tile row lacks it)
+  const int32_t *counts;   // [row groups] stages
+  int64_t N, ldI, ldO, K;
+  int obf16;
+  int max_stages;
+  int a_o, d_o;
+  int TK;
+  int tab_bytes;           // LDS bytes of the stage list (a multiple of 16)
+  int inl_ok;              // the stage lists and counts of all row groups fit `inl` (then stages / counts are unused):
+                           //   kernel arguments are at hand when a wave starts, a table in global memory costs two
+                           //   dependent round trips (measured: 7.5 us against 3.5 us to the first barrier)
+  int32_t inl[kInline];    // [row groups][max_stages][5], then [row groups] counts
+#ifdef RBGP_EXPERIMENT
+  int ablate;              // timing experiments: 1 skips the LDS writes, 2 the MFMAs, 4 the loads of I
+#endif
+  int ntiles, RG;          // column tiles of 64, row groups of 4 tile rows
+  uint32_t w_bytes;
+  uint32_t n_round_bytes;  // N rounded up to 8 columns, in bytes: the extent of the last row of I
+};
+
+constexpr int kCW = 64;        // columns per workgroup
+constexpr int kMaxTasks = 2;   // (8 rows x 8 columns) load tasks per producer thread and stage: TKP <= 320 gives <= 320 tasks
+
+struct RawSet {
+  u32x4 r[kMaxTasks][8];
+};
+
+// Workgroup = 8 waves: waves 0..3 are consumers (one tile row each: weights from global memory, B
+// operands from LDS, MFMAs), waves 4..7 producers (rows of I from global memory to LDS).  The two
+// kinds share a SIMD pairwise, so the matrix core runs while the other wave waits for memory, and
+// each kind has its own in-order load counter: a consumer's wait for weights never waits for I.
+// NC: 16-step blocks of a stage (TKP = 16 * NC), a compile-time constant so that a consumer can hold
+// the weights of a whole stage in registers: those of stage s + 1 are requested before the MFMAs
+// of stage s.
+template <int NC>
+__global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  constexpr int TM = 32;
+  constexpr int TKP = 16 * NC;
+  constexpr int NBLK = 2 * NC;                 // 8-row blocks of a stage
+  constexpr int BUF = NBLK * kCW * 16;         // bytes of one stage in LDS
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // workgroups are dealt round-robin to the 8 XCDs: the row groups of one column tile share an L2
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rg = slot % p.RG, nt = (slot / p.RG) * 8 + xcd;
+  if (nt >= p.ntiles) return;   // (the whole workgroup)
+  const int64_t n0 = int64_t(nt) * kCW;
+  // The stage list of the row group comes from the kernel arguments when it fits them, else it is copied
+  // to LDS first (reading it later must not wait for the loads in flight).
+  const bool inl = p.inl_ok != 0;
+  const int cnt = inl ? p.inl[p.RG * p.max_stages * 5 + rg] : p.counts[rg];
+  int32_t *const tab = reinterpret_cast<int32_t *>(lds_raw);
+  unsigned char *const lds = lds_raw + p.tab_bytes;
+  if (!inl) {
+    const int32_t *stg = p.stages + int64_t(rg) * p.max_stages * 5;
+    for (int i = tid; i < cnt * 5; i += 512) tab[i] = stg[i];
+    __syncthreads();
+  }
+  const int inl_base = rg * p.max_stages * 5;
+  auto table = [&](int i) { return inl ? p.inl[inl_base + i] : __builtin_amdgcn_readfirstlane(tab[i]); };
+#ifdef RBGP_EXPERIMENT
+  if (p.ablate & 32) return;
+#endif
+
+  if (wid >= 4) {
+    // ---------------------------------------------------------------- producer
+    const int ptid = tid - 256;
+    constexpr int NTASK = NBLK * 8;       // x 8 column octets; task t = (block t / 8, octet t % 8)
+    static_assert(NTASK <= 256 * kMaxTasks, "stage too long");
+    const int row_bytes = int(p.ldI) * 2;
+    int t_off[kMaxTasks], t_lds[kMaxTasks];
+#pragma unroll
+    for (int q = 0; q < kMaxTasks; ++q) {
+      const int t = ptid + 256 * q, blk = t >> 3, oct = t & 7;
+      t_off[q] = t < NTASK ? blk * 8 * row_bytes + oct * 16 : kOob;   // < 2^30: checked by the host
+      t_lds[q] = (blk * kCW + oct * 8) * 16;
+    }
+    // position swizzle inside a block (see the file header): both tasks of a thread have the same octet and
+    // the same block parity (256 / 8 is even)
+    const int swz = (((ptid & 7) >> 1) << 1) | ((ptid >> 3) & 1);
+    // Loads of stage s (zeros without a memory access past the last stage): the descriptor starts at
+    // the stage's first row and the workgroup's first column; its extent ends with the last row of I.
+    auto issue_loads = [&](int s, RawSet &set) {
+      const bool live = s < cnt;
+      const int v_o = live ? table(s * 5) : 0;
+      const int64_t row0 = int64_t(v_o) * p.TK;
+      const int64_t rows_left = p.K - row0;      // >= TK
+      const uint64_t base = reinterpret_cast<uint64_t>(p.I) + uint64_t(row0 * p.ldI + n0) * 2;
+      int64_t ext = rows_left > TKP ? int64_t(TKP) * p.ldI * 2
+                                    : (rows_left - 1) * p.ldI * 2 + (int64_t(p.n_round_bytes) - n0 * 2);
+      if (!live) ext = 0;
+#ifdef RBGP_EXPERIMENT
+      if (p.ablate & 4) ext = 0;
+#endif
+      const __amdgpu_buffer_rsrc_t rb =
+          __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, int(ext), kRsrcFlags);
+#pragma unroll
+      for (int q = 0; q < kMaxTasks; ++q) {
+        if (q * 256 < NTASK) {
+#pragma unroll
+          for (int r = 0; r < 8; ++r)
+            set.r[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rb, t_off[q] + r * row_bytes, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // transpose the 8 x 8 blocks (dword d of a row holds columns 2d and 2d + 1) and write them to LDS buffer b
+    auto to_lds = [&](int b, const RawSet &set) {
+      constexpr unsigned LO = 0x05040100u, HI = 0x07060302u;
+      unsigned char *dst = lds + b * BUF;
+#pragma unroll
+      for (int q = 0; q < kMaxTasks; ++q) {
+        if (q * 256 < NTASK && ptid + 256 * q < NTASK) {
+          const u32x4 *r = set.r[q];
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const u32x4 lo = {__builtin_amdgcn_perm(r[1][d], r[0][d], LO), __builtin_amdgcn_perm(r[3][d], r[2][d], LO),
+                              __builtin_amdgcn_perm(r[5][d], r[4][d], LO), __builtin_amdgcn_perm(r[7][d], r[6][d], LO)};
+            const u32x4 hi = {__builtin_amdgcn_perm(r[1][d], r[0][d], HI), __builtin_amdgcn_perm(r[3][d], r[2][d], HI),
+                              __builtin_amdgcn_perm(r[5][d], r[4][d], HI), __builtin_amdgcn_perm(r[7][d], r[6][d], HI)};
+            *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d) ^ swz) << 4)) = lo;
+            *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d + 1) ^ swz) << 4)) = hi;
+          }
+        }
+      }
+    };
+    // Three register sets: the loads of stages s + 2 and s + 3 are in flight while stage s + 1 moves to LDS
+    // (one stage of lead leaves the producers waiting a memory latency per stage).
+    RawSet setA, setB, setC;
+    issue_loads(0, setA);
+    issue_loads(1, setB);
+    issue_loads(2, setC);
+    to_lds(0, setA);
+    __syncthreads();
+    // iteration s: request stage s + 3 into the set stage s came from, move stage s + 1 to LDS
+    auto pstep = [&](int s, RawSet &free_set, RawSet &cur) {
+      issue_loads(s + 3, free_set);
+#ifdef RBGP_EXPERIMENT
+      if (!(p.ablate & 1))
+#endif
+      if (s + 1 < cnt) to_lds((s + 1) & 1, cur);
+      __syncthreads();
+    };
+    for (int s = 0; s < cnt; s += 3) {
+      pstep(s, setA, setB);
+      if (s + 1 < cnt) pstep(s + 1, setB, setC);
+      if (s + 2 < cnt) pstep(s + 2, setC, setA);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    return;
+  }
+
+  // ------------------------------------------------------------------ consumer
+  const int u_o = rg * 4 + wid;
+  const bool row_ok = u_o < p.a_o;
+  const __amdgpu_buffer_rsrc_t rw =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.Wp), 0, p.w_bytes, kRsrcFlags);
+  constexpr int FRAG = TKP * TM * 2;       // bytes of one tile's weights
+  const int n32 = lane & 31, h2 = lane >> 5;
+  const int alane = (h2 * TM + n32) * 16;
+  // byte offset inside a block of the lane's column 32 h + n32: position (column ^ key), key from the
+  // column's octet and the block parity
+  const int boff0 = (n32 ^ ((((n32 >> 3) >> 1) << 1) | h2)) << 4;
+  const int boff1 = ((32 + n32) ^ (((((32 + n32) >> 3) >> 1) & 3) << 1 | h2)) << 4;
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[h][r] = 0.f;
+
+  // index of stage s's tile in the tile row's adjacency list, -1: the tile row lacks it
+  auto tile_of = [&](int s) { return (row_ok && s < cnt) ? table(s * 5 + 1 + wid) : -1; };
+  // the weights of stage s (zeros without a memory access when the tile row lacks the tile)
+  auto issue_weights = [&](int s, u32x4 (&A)[NC]) {
+    int j = tile_of(s);
+#ifdef RBGP_EXPERIMENT
+    if (p.ablate & 8) j = -1;
+#endif
+    const int off = (j >= 0 ? (u_o * p.d_o + j) * FRAG : kOob) + alane;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) A[c] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, c * (2 * TM * 16), 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto compute = [&](int s, const u32x4 (&A)[NC]) {
+    if (tile_of(s) < 0) return;
+#ifdef RBGP_EXPERIMENT
+    if (p.ablate & 2) return;
+#endif
+    const unsigned char *src = lds + (s & 1) * BUF;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const unsigned char *bsrc = src + ((2 * c + h2) * kCW) * 16;   // (block parity = h2: the swizzle is per lane)
+      const u32x4 B0 = *reinterpret_cast<const u32x4 *>(bsrc + boff0);
+      const u32x4 B1 = *reinterpret_cast<const u32x4 *>(bsrc + boff1);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[c]), __builtin_bit_cast(bf16x8, B0),
+                                                        acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[c]), __builtin_bit_cast(bf16x8, B1),
+                                                        acc[1], 0, 0, 0);
+    }
+  };
+  u32x4 W0[NC], W1[NC];
+  issue_weights(0, W0);
+  __syncthreads();
+  for (int s = 0; s < cnt; s += 2) {
+    issue_weights(s + 1, W1);
+    compute(s, W0);
+    __syncthreads();
+    if (s + 1 < cnt) {
+      issue_weights(s + 2, W0);
+      compute(s + 1, W1);
+      __syncthreads();
+    }
+  }
+
+  // Epilogue.  32x32 accumulator: register r of lane (n32, h2) is row 8 * (r / 4) + 4 * h2 + r % 4,
+  // column n32 of the block.
+  if (!row_ok) return;
+#ifdef RBGP_EXPERIMENT
+  if (p.ablate & 16) return;
+#endif
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int64_t n = n0 + 32 * h + n32;
+    if (n >= p.N) continue;
+    const int64_t m0 = int64_t(u_o) * TM + 4 * h2;
+    if (p.obf16) {
+      uint16_t *o = reinterpret_cast<uint16_t *>(p.O) + m0 * p.ldO + n;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * p.ldO] = uint16_t(bf16_bits(acc[h][r]));
+    } else {
+      float *o = reinterpret_cast<float *>(p.O) + m0 * p.ldO + n;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * p.ldO] = acc[h][r];
+    }
+  }
+}
+
+typedef void (*tile_fn)(TileParams);
+struct TileEntry {
+  int NC;
+  tile_fn fn;
+  int lds_set;   // largest dynamic LDS size requested for fn so far
+};
+TileEntry kTileTable[] = {{2, spmm_tile_bf16<2>, 0},   {4, spmm_tile_bf16<4>, 0},   {5, spmm_tile_bf16<5>, 0},
+                          {8, spmm_tile_bf16<8>, 0},   {9, spmm_tile_bf16<9>, 0},   {16, spmm_tile_bf16<16>, 0},
+                          {18, spmm_tile_bf16<18>, 0}, {20, spmm_tile_bf16<20>, 0}};
+
+struct TileState {
+  int32_t *stages = nullptr, *counts = nullptr;
+  int max_stages = 0, RG = 0;
+  std::vector<int32_t> host_table;   // stages then counts: what the kernel arguments carry when it is short enough
+};
+
+#define RBGP_HIP(call)                                                              \
+  do {                                                                              \
+    hipError_t e_ = (call);                                                         \
+    if (e_ != hipSuccess) {                                                         \
+      char buf_[256];                                                               \
+      std::snprintf(buf_, sizeof buf_, "%s: %s", #call, hipGetErrorString(e_));     \
+      rbgp_set_hip_error(buf_);                                                     \
+      return RBGP_EHIP;                                                             \
+    }                                                                               \
+  } while (0)
+
+int build_state(const rbgp_mask *m, TileState *st) {
+  const int a_o = m->a[0], d_o = m->d[0], c_o = m->c[0];
+  const int RG = (a_o + 3) / 4;
+  std::vector<std::vector<int32_t>> rows(static_cast<size_t>(RG));
+  int max_stages = 1;
+  for (int rg = 0; rg < RG; ++rg) {
+    std::vector<int32_t> &out = rows[size_t(rg)];
+    for (int v = 0; v < c_o; ++v) {
+      int32_t jj[4] = {-1, -1, -1, -1};
+      bool any = false;
+      for (int w = 0; w < 4; ++w) {
+        const int u = rg * 4 + w;
+        if (u >= a_o) continue;
+        for (int j = 0; j < d_o; ++j)
+          if (m->adj[0][size_t(u) * d_o + j] == v) {
+            jj[w] = j;
+            any = true;
+          }
+      }
+      if (!any) continue;
+      out.push_back(v);
+      out.insert(out.end(), jj, jj + 4);
+    }
+    max_stages = std::max(max_stages, int(out.size() / 5));
+  }
+  std::vector<int32_t> stages(size_t(RG) * max_stages * 5, -1), counts(static_cast<size_t>(RG), 0);
+  for (int rg = 0; rg < RG; ++rg) {
+    std::copy(rows[size_t(rg)].begin(), rows[size_t(rg)].end(), stages.begin() + size_t(rg) * max_stages * 5);
+    counts[size_t(rg)] = int32_t(rows[size_t(rg)].size() / 5);
+  }
+  RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->stages), stages.size() * 4));
+  RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->counts), counts.size() * 4));
+  RBGP_HIP(hipMemcpy(st->stages, stages.data(), stages.size() * 4, hipMemcpyHostToDevice));
+  RBGP_HIP(hipMemcpy(st->counts, counts.data(), counts.size() * 4, hipMemcpyHostToDevice));
+  st->max_stages = max_stages;
+  st->RG = RG;
+  st->host_table = stages;
+  st->host_table.insert(st->host_table.end(), counts.begin(), counts.end());
+  return RBGP_OK;
+}
+
+}  // namespace
+
+void rbgp_tile_release(void *state) {
+  TileState *st = static_cast<TileState *>(state);
+  if (!st) return;
+  if (st->stages) (void)hipFree(st->stages);
+  if (st->counts) (void)hipFree(st->counts);
+  delete st;
+}
+
+int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N, const void *packed, const void *I,
+                     int64_t ldI, void *O, int64_t ldO, void *stream) {
+  const rbgp_tile_plan pl = rbgp_plan_tile(m);
+  if (!pl.ok) return RBGP_EUNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(I) & 15) || (ldI % 8)) return RBGP_ESHAPE;
+  // 32-bit offsets address the rows of one stage (and stay below the out-of-range offset of idle load slots)
+  if (int64_t(pl.TKP) * ldI * 2 + 256 >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  TileState *st = static_cast<TileState *>(*state);
+  if (!st) {
+    st = new (std::nothrow) TileState();
+    if (!st) return RBGP_ENOMEM;
+    *state = st;
+  }
+  if (!st->stages) {
+    int rc = build_state(m, st);
+    if (rc) return rc;
+  }
+  TileParams p;
+  p.Wp = packed; p.I = I; p.O = O;
+  p.stages = st->stages; p.counts = st->counts;
+  p.N = N; p.ldI = ldI; p.ldO = ldO; p.K = m->K;
+  p.obf16 = out_bf16 ? 1 : 0;
+  p.max_stages = st->max_stages;
+  p.a_o = m->a[0]; p.d_o = m->d[0];
+  p.TK = pl.TK;
+  p.inl_ok = int(st->host_table.size()) <= kInline;
+  p.tab_bytes = p.inl_ok ? 0 : (st->max_stages * 5 * 4 + 15) / 16 * 16;
+  if (p.inl_ok) std::copy(st->host_table.begin(), st->host_table.end(), p.inl);
+#ifdef RBGP_EXPERIMENT
+  p.ablate = getenv("RBGP_TILE_ABLATE") ? atoi(getenv("RBGP_TILE_ABLATE")) : 0;
+#endif
+  const int64_t ntiles = (N + kCW - 1) / kCW;
+  p.ntiles = int(ntiles); p.RG = st->RG;
+  p.w_bytes = uint32_t(pl.packed_elems * 2);
+  p.n_round_bytes = uint32_t((N + 7) / 8 * 8 * 2);
+  const int64_t blocks = 8 * ((ntiles + 7) / 8) * st->RG;
+  if (blocks > 0x7fffffff || N * 2 + 16 >= (int64_t(1) << 32)) return RBGP_EUNSUPPORTED;
+  TileEntry *te = nullptr;
+  for (TileEntry &e : kTileTable)
+    if (e.NC * 16 == pl.TKP) te = &e;
+  if (!te) return RBGP_EUNSUPPORTED;
+  const tile_fn fn = te->fn;
+  const size_t lds = size_t(p.tab_bytes) + size_t(2) * (pl.TKP / 8) * kCW * 16;
+  if (lds > 160 * 1024) return RBGP_EUNSUPPORTED;
+  // (the attribute call costs microseconds on the host: once per kernel and size, not per launch; a racing
+  // second thread at worst repeats the call)
+  if (lds > 64 * 1024 && int(lds) > te->lds_set) {
+    RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+    te->lds_set = int(lds);
+  }
+  hipLaunchKernelGGL(fn, dim3(unsigned(blocks)), dim3(512), lds, static_cast<hipStream_t>(stream), p);
+  RBGP_HIP(hipGetLastError());
+  return RBGP_OK;
+}

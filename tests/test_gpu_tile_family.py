@@ -1,0 +1,82 @@
+"""GPU parity of the tile family (RBGP_KERNEL_MFMA_TILE, bf16 modes): every nonzero of G_o as a
+dense block, I staged in LDS by producer waves, 32-row MFMAs; against the CPU oracle."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import rbgp_oracle as orc
+from paper_2006_13486_amd import binding as rb
+from paper_2006_13486_amd import workloads as wl
+from tests import gpu_harness as gh
+from tests.test_gpu_bf16_output import check_bf16_output
+
+pytestmark = pytest.mark.gpu
+
+TILE = rb.KERNEL_MFMA_TILE
+
+SHAPES = [
+    # rows, cols, row degrees: 32 rows per tile; stage lengths 288, 144, 72 (padded to 80), 32, 36 (padded to 64), 320
+    ((8, 4, 4, 2), (8, 4, 8, 9), (4, 4, 4, 9)),
+    ((4, 2, 8, 2), (8, 2, 8, 9), (4, 2, 4, 9)),
+    ((6, 2, 4, 4), (6, 2, 4, 9), (3, 2, 2, 9)),
+    ((8, 4, 8, 1), (16, 1, 32, 1), (4, 1, 8, 1)),
+    ((2, 1, 32, 1), (2, 1, 4, 9), (2, 1, 2, 9)),
+    ((3, 4, 4, 2), (3, 4, 8, 10), (3, 4, 4, 10)),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s[1])))
+@pytest.mark.parametrize("N", [64, 200, 1000])
+def test_shapes(shape, N):
+    rows, cols, deg = shape
+    w = wl.Workload("tile_" + "x".join(map(str, cols)), rows, cols, deg, N, wl.BF16, 91, 92, 93, 1.0)
+    gh.check_parity(w, kernel=TILE, ld_pad=(-N) % 8, expect_kernel=TILE)
+
+
+def test_conv3_full_size_and_bf16_output():
+    gh.check_parity(wl.VGG19_CONV3_BF16, kernel=TILE, expect_kernel=TILE)
+    assert check_bf16_output(wl.VGG19_CONV3_BF16, N=1000, kernel=TILE) == TILE
+
+
+@pytest.mark.parametrize("N,ld_pad", [(1, 7), (63, 1), (65, 7), (257, 15), (8190, 2)])
+def test_ragged_columns(N, ld_pad):
+    gh.check_parity(wl.VGG19_CONV3_BF16, N=N, kernel=TILE, ld_pad=ld_pad, expect_kernel=TILE)
+
+
+def test_one_hot_input_returns_the_dense_weights():
+    """I = identity: O must equal the dense W_s bit for bit (pins the packing and every index)."""
+    w = wl.Workload("tile_one_hot", (4, 2, 8, 2), (8, 2, 8, 9), (4, 2, 4, 9), 0, wl.BF16, 94, 95, 96, 1.0)
+    w = replace(w, N=w.K)
+    vb = wl.to_bf16_bits(wl.kept_weights(w))
+    eye = wl.to_bf16_bits(np.eye(w.K, dtype=np.float32))
+    out, used = gh.library_spmm(w, vb, eye, kernel=TILE)
+    assert used == TILE
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    dense = orc.scatter_values(orc.kron_mask(Bs), wl.bf16_bits_as_f32(vb))
+    assert np.array_equal(out, dense.astype(np.float32))
+
+
+def test_family_limits():
+    import torch
+    mask = gh.make_mask(wl.VGG19_CONV5)                      # fp32 calls take the default family
+    rb.rbgp_mask_set_kernel(mask, TILE)
+    assert rb.rbgp_mask_kernel(mask, rb.F32) == rb.KERNEL_MFMA_REG
+    assert rb.rbgp_mask_kernel(mask, rb.BF16_F32ACC) == TILE
+    w = wl.WRN_G1                                            # 8 rows per tile: not covered
+    with pytest.raises(rb.RbgpError) as e:
+        rb.rbgp_mask_set_kernel(gh.make_mask(w), TILE)
+    assert e.value.code == rb.EUNSUPPORTED
+    w = replace(wl.VGG19_CONV3_BF16, N=64)
+    mask = gh.make_mask(w)
+    rb.rbgp_mask_set_kernel(mask, TILE)
+    packed = torch.zeros(rb.rbgp_packed_bytes(mask, rb.BF16), dtype=torch.uint8, device="cuda:0")
+    I_d = torch.zeros((w.K, w.N + 4), dtype=torch.int16, device="cuda:0")
+    O_d = torch.zeros((w.M, w.N), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(rb.RbgpError) as e:                   # leading dimension not a multiple of 8
+        rb.rbgp_spmm(mask, rb.BF16_F32ACC, w.M, w.K, w.N, packed.data_ptr(), I_d.data_ptr(), w.N + 4, O_d.data_ptr(), w.N, 0)
+    assert e.value.code == rb.ESHAPE
+    with pytest.raises(rb.RbgpError) as e:                   # the fused convolution runs on the register family only
+        rb.rbgp_conv3x3(mask, rb.BF16_F32ACC, w.M, w.K // 9, 1, 8, 8, packed.data_ptr(), I_d.data_ptr(), O_d.data_ptr(), 64, 0)
+    assert e.value.code == rb.EUNSUPPORTED
+    torch.cuda.synchronize()
