@@ -382,6 +382,9 @@ def main():
     ap.add_argument("--fused-conv", action="store_true",
                     help="time rbgp_conv3x3 (3x3 convolution with the lowering folded into the loads, fp32) on the "
                          "workload's layer instead of rbgp_spmm on the lowered input")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="time the forward product only: no fused-convolution and backward objects in the JSON line "
+                         "(keeps a profile of the run to the one kernel)")
     ap.add_argument("--out-bf16", action="store_true",
                     help="bf16 workloads: store O as bf16 (dtype RBGP_BF16) instead of fp32")
     ap.add_argument("--backward", default="", choices=["", "backward_data", "weight_gradient", "both"],
@@ -537,11 +540,11 @@ def main():
         if args.out_bf16:      # (bf16 bits widened exactly; the rounding stays inside the bf16 tolerance of the check)
             O_host = wl.bf16_bits_as_f32(O_host.view(np.uint16))
         out["cpu_baseline"] = cpu_baseline(w, vals_f32, I_f32, O_host)
-    if not args.fused_conv and w.name in wl.CONV_GEOMETRY and \
+    if not args.fused_conv and not args.forward_only and w.name in wl.CONV_GEOMETRY and \
             rb.rbgp_mask_kernel(mask, w.dtype) == rb.KERNEL_MFMA_REG:     # (the fused call runs on that family only)
         out["fused_conv3x3"] = fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream,
                                                check=not args.no_cpu_baseline)
-    if not args.fused_conv and args.workload == "conv5":
+    if not args.fused_conv and not args.forward_only and args.workload == "conv5":
         out["backward"] = backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream,
                                            check=not args.no_cpu_baseline)
     print(json.dumps(out))
