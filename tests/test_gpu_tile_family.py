@@ -34,6 +34,37 @@ def test_shapes(shape, N):
     gh.check_parity(w, kernel=TILE, ld_pad=(-N) % 8, expect_kernel=TILE)
 
 
+def _random_tile_shapes(count, seed):
+    """Seeded random shapes with 32 rows per tile and at most 320 columns per tile that the sampler accepts."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    while len(shapes) < count:
+        lo, li = int(g.integers(0, 3)), int(g.integers(0, 3))
+        a_o = int(g.choice([1, 2, 3, 4, 5, 6, 8, 12])) << lo
+        c_o = int(g.choice([1, 2, 3, 4, 8])) << lo
+        a_r, a_b = [(1, 1), (2, 1), (1, 2), (4, 1), (2, 2), (4, 2), (2, 4), (8, 1)][int(g.integers(0, 8))]
+        a_i = 32 // (a_r * a_b)
+        c_i = int(g.choice([1, 2, 4])) << li
+        c_r, c_b = int(g.choice([1, 2, 3, 4])), int(g.choice([1, 3, 9, 10]))
+        rows, cols = (a_o, a_r, a_i, a_b), (c_o, c_r, c_i, c_b)
+        deg = (c_o >> lo, c_r, c_i >> li, c_b)
+        if c_r * c_i * c_b > 320:
+            continue
+        try:
+            mask = rb.rbgp_make_mask(rows, cols, deg, 700 + len(shapes))
+            rb.rbgp_mask_set_kernel(mask, TILE)
+        except rb.RbgpError:
+            continue
+        shapes.append((rows, cols, deg, int(g.integers(1, 700))))
+    return shapes
+
+
+def test_random_shapes():
+    for idx, (rows, cols, deg, N) in enumerate(_random_tile_shapes(24, 77)):
+        w = wl.Workload(f"tile_random{idx}", rows, cols, deg, N, wl.BF16, 700 + idx, 800 + idx, 900 + idx, 1.0)
+        gh.check_parity(w, kernel=TILE, ld_pad=(-N) % 8, expect_kernel=TILE)
+
+
 def test_conv3_full_size_and_bf16_output():
     gh.check_parity(wl.VGG19_CONV3_BF16, kernel=TILE, expect_kernel=TILE)
     assert check_bf16_output(wl.VGG19_CONV3_BF16, N=1000, kernel=TILE) == TILE
