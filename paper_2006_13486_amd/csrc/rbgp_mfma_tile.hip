@@ -10,16 +10,20 @@
 // a workgroup can stage I in LDS ONCE for all its tile rows -- the register-streaming family is
 // bound by the bytes of I that cross the L1 path (every cluster and G_i vertex loads its own).
 //
-// Workgroup = 4 consecutive tile rows x 64 columns.  Stage = one tile column that any of
-// the four tile rows has (host table, ascending): its TKP rows x 64 columns of I are loaded with
-// 16-byte loads (a lane takes 8 rows x 8 columns), transposed in registers (v_perm_b32) into, per
-// column, eight consecutive contraction steps (what one lane feeds the matrix core), and written
-// to LDS as [8-row block][column position][16 bytes], position = column ^ (2 * ((column / 16) % 4) + block % 2):
+// Workgroup = 4 consecutive tile rows x 64 columns, 8 waves.  Stage = one tile column that any of
+// the four tile rows has (host table, ascending): producer waves load its TKP rows x 64 columns of I
+// with 16-byte loads (a lane takes 8 rows x 8 columns), transpose them in registers (v_perm_b32)
+// into, per column, eight consecutive contraction steps (what one lane feeds the matrix core), and
+// write them to LDS as [8-row block][column position][16 bytes], position = column ^ (2 * ((column / 16) % 4) + block % 2):
 // the 16-byte writes of 16 neighbouring lanes (8 column octets x 2 blocks, same column offset) then fall
-// on 16 different bank groups, while the 32 lanes of a read still cover 512 contiguous bytes.  Two buffers:
-// the loads of stage s + 1 are issued before the MFMAs of stage s and land in LDS after them.
-// A wave whose tile row lacks the tile column skips the MFMAs of the stage (its weight loads
-// point past the packed buffer and return zeros without a memory access).
+// on 16 different bank groups, while the 32 lanes of a read still cover 512 contiguous bytes.
+// Two LDS buffers and one barrier per stage: consumers multiply stage s while producers fill the
+// buffer of stage s + 1, with the loads of stages s + 2 and s + 3 in flight (three register sets).
+// A consumer wave whose tile row lacks the tile column skips the MFMAs of the stage (its weight
+// loads point past the packed buffer and return zeros without a memory access).
+// Measured against the register-streaming family on the VGG19 layers in bf16: faster where the
+// tiles are dense (density 1/2 on the large layers, by 15-20 %), slower elsewhere; never chosen
+// by RBGP_KERNEL_AUTO.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -53,8 +57,8 @@ struct TileParams {
   int TK;
   int tab_bytes;           // LDS bytes of the stage list (a multiple of 16)
   int inl_ok;              // the stage lists and counts of all row groups fit `inl` (then stages / counts are unused):
-                           //   kernel arguments are at hand when a wave starts, a table in global memory costs two
-                           //   dependent round trips (measured: 7.5 us against 3.5 us to the first barrier)
+                           //   saves the copy of the table to LDS and its barrier (measured on the VGG19 conv3 shape:
+                           //   21.0 us against 21.3 us)
   int32_t inl[kInline];    // [row groups][max_stages][5], then [row groups] counts
 #ifdef RBGP_EXPERIMENT
   int ablate;              // timing experiments: 1 skips the LDS writes, 2 the MFMAs, 4 the loads of I
@@ -387,6 +391,9 @@ int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N,
   p.a_o = m->a[0]; p.d_o = m->d[0];
   p.TK = pl.TK;
   p.inl_ok = int(st->host_table.size()) <= kInline;
+#ifdef RBGP_EXPERIMENT
+  if (getenv("RBGP_TILE_NOINL")) p.inl_ok = 0;
+#endif
   p.tab_bytes = p.inl_ok ? 0 : (st->max_stages * 5 * 4 + 15) / 16 * 16;
   if (p.inl_ok) std::copy(st->host_table.begin(), st->host_table.end(), p.inl);
 #ifdef RBGP_EXPERIMENT
