@@ -167,8 +167,9 @@ int rbgp_mask_dense(const rbgp_mask_t *mask, uint8_t *out);
 /* Choose the kernel family used by rbgp_packed_bytes / rbgp_pack / rbgp_spmm for
  * this mask: AUTO (default: an MFMA family when the mask's shape is covered, else
  * GENERIC) or one family (EUNSUPPORTED if it does not cover the mask's shape; a
- * family that does not cover the dtype falls back to GENERIC).  Each family has
- * its own packed layout: changing it invalidates buffers packed before. */
+ * family that does not cover the dtype falls back to GENERIC, RBGP_KERNEL_MFMA_TILE
+ * in fp32 mode to what AUTO would take).  Each family has its own packed layout:
+ * changing it invalidates buffers packed before. */
 int rbgp_mask_set_kernel(rbgp_mask_t *mask, int kernel);
 
 /* Kernel family (never AUTO) that rbgp_pack / rbgp_spmm use for this dtype. */
