@@ -97,6 +97,15 @@ enum {
   RBGP_NUM_TUNE = 6
 };
 
+/* Device tables.  A mask keeps small index tables in device memory (adjacency lists, stage lists,
+ * pack permutations; a few KB to a few hundred KB), built on first use: the first rbgp_pack /
+ * rbgp_spmm / rbgp_conv3x3 / rbgp_sddmm call on a mask -- and the first after another kernel choice or
+ * tuning value, with another convolution geometry, or, for rbgp_sddmm, with a larger N -- allocates
+ * and uploads them (hipMalloc, synchronous copies).  Every later call with the same configuration
+ * only launches kernels on `hip_stream`: it may be recorded into a HIP graph and replayed (make one
+ * eager call first).  The tables belong to the mask and go with rbgp_mask_free.  All calls that use
+ * one mask come from one thread at a time. */
+
 /* Sample the four base graphs and build the mask (host only, no GPU call).
  * Appendix "Ramanujan Bipartite Graph Generation": a factor with row_deg < cols
  * is produced by L = log2(cols/row_deg) random 2-lifts of the complete bipartite
