@@ -30,6 +30,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "rbgp_internal.h"
@@ -47,8 +48,8 @@ struct TileParams {
   const void *Wp;          // packed weights: [tile row][j_o][TKP / 16][2][TM][8] bf16
   const void *I;           // K x ldI bf16
   void *O;                 // M x ldO fp32, or bf16 bits when obf16 is set
-  const int32_t *stages;   // [row groups][max_stages][5]: tile column, then per wave the index j_o of the tile
-                           //   in its tile row's adjacency list (-1: the tile row lacks it)
+  const int32_t *stages;   // [row groups][max_stages + 4 * d_o]: tile column of every stage, then per consumer wave
+                           //   the stage of each tile of its tile row (adjacency-list order = ascending)
   const int32_t *counts;   // [row groups] stages
   int64_t N, ldI, ldO, K;
   int obf16;
@@ -59,7 +60,7 @@ struct TileParams {
   int inl_ok;              // the stage lists and counts of all row groups fit `inl` (then stages / counts are unused):
                            //   saves the copy of the table to LDS and its barrier (measured on the VGG19 conv3 shape:
                            //   21.0 us against 21.3 us)
-  int32_t inl[kInline];    // [row groups][max_stages][5], then [row groups] counts
+  int32_t inl[kInline];    // the table above, then [row groups] counts
 #ifdef RBGP_EXPERIMENT
   int ablate;              // timing experiments: 1 skips the LDS writes, 2 the MFMAs, 4 the loads of I
 #endif
@@ -69,10 +70,10 @@ struct TileParams {
 };
 
 constexpr int kCW = 64;        // columns per workgroup
-constexpr int kMaxTasks = 2;   // (8 rows x 8 columns) load tasks per producer thread and stage: TKP <= 320 gives <= 320 tasks
 
+template <int NT>
 struct RawSet {
-  u32x4 r[kMaxTasks][8];
+  u32x4 r[NT > 0 ? NT : 1][8];
 };
 
 // Workgroup = 8 waves: waves 0..3 are consumers (one tile row each: weights from global memory, B
@@ -80,8 +81,8 @@ struct RawSet {
 // kinds share a SIMD pairwise, so the matrix core runs while the other wave waits for memory, and
 // each kind has its own in-order load counter: a consumer's wait for weights never waits for I.
 // NC: 16-step blocks of a stage (TKP = 16 * NC), a compile-time constant so that a consumer can hold
-// the weights of a whole stage in registers: those of stage s + 1 are requested before the MFMAs
-// of stage s.
+// the weights of a whole tile in registers: those of its next tile are requested before the MFMAs
+// of the current one.
 template <int NC>
 __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -96,18 +97,20 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   const int rg = slot % p.RG, nt = (slot / p.RG) * 8 + xcd;
   if (nt >= p.ntiles) return;   // (the whole workgroup)
   const int64_t n0 = int64_t(nt) * kCW;
-  // The stage list of the row group comes from the kernel arguments when it fits them, else it is copied
-  // to LDS first (reading it later must not wait for the loads in flight).
+  // The table of the row group (tile column of every stage, then per consumer wave the stage of each of
+  // its tiles) comes from the kernel arguments when it fits them, else it is copied to LDS first
+  // (reading it later must not wait for the loads in flight).
   const bool inl = p.inl_ok != 0;
-  const int cnt = inl ? p.inl[p.RG * p.max_stages * 5 + rg] : p.counts[rg];
+  const int rec = p.max_stages + 4 * p.d_o;    // words per row group
+  const int cnt = inl ? p.inl[p.RG * rec + rg] : p.counts[rg];
   int32_t *const tab = reinterpret_cast<int32_t *>(lds_raw);
   unsigned char *const lds = lds_raw + p.tab_bytes;
   if (!inl) {
-    const int32_t *stg = p.stages + int64_t(rg) * p.max_stages * 5;
-    for (int i = tid; i < cnt * 5; i += 512) tab[i] = stg[i];
+    const int32_t *stg = p.stages + int64_t(rg) * rec;
+    for (int i = tid; i < rec; i += 512) tab[i] = stg[i];
     __syncthreads();
   }
-  const int inl_base = rg * p.max_stages * 5;
+  const int inl_base = rg * rec;
   auto table = [&](int i) { return inl ? p.inl[inl_base + i] : __builtin_amdgcn_readfirstlane(tab[i]); };
 #ifdef RBGP_EXPERIMENT
   if (p.ablate & 32) return;
@@ -115,95 +118,104 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
 
   if (wid >= 4) {
     // ---------------------------------------------------------------- producer
+    // Load tasks: (8 rows x 8 columns) pieces of the stage, task t = (block t / 8, column octet t % 8),
+    // dealt to the 256 producer threads in rounds; the last round may cover only some of the waves, so
+    // the code below exists for both task counts (a wave-uniform choice: every wave's count of loads in
+    // flight is a compile-time constant).
     const int ptid = tid - 256;
-    constexpr int NTASK = NBLK * 8;       // x 8 column octets; task t = (block t / 8, octet t % 8)
-    static_assert(NTASK <= 256 * kMaxTasks, "stage too long");
-    const int row_bytes = int(p.ldI) * 2;
-    int t_off[kMaxTasks], t_lds[kMaxTasks];
+    constexpr int NTASK = NBLK * 8, FULL = NTASK / 256, REM = NTASK % 256;
+    auto producer = [&](auto nt_c) {
+      constexpr int NT = decltype(nt_c)::value;
+      const int row_bytes = int(p.ldI) * 2;
+      int t_off[NT > 0 ? NT : 1], t_lds[NT > 0 ? NT : 1];
 #pragma unroll
-    for (int q = 0; q < kMaxTasks; ++q) {
-      const int t = ptid + 256 * q, blk = t >> 3, oct = t & 7;
-      t_off[q] = t < NTASK ? blk * 8 * row_bytes + oct * 16 : kOob;   // < 2^30: checked by the host
-      t_lds[q] = (blk * kCW + oct * 8) * 16;
-    }
-    // position swizzle inside a block (see the file header): both tasks of a thread have the same octet and
-    // the same block parity (256 / 8 is even)
-    const int swz = (((ptid & 7) >> 1) << 1) | ((ptid >> 3) & 1);
-    // Loads of stage s (zeros without a memory access past the last stage): the descriptor starts at
-    // the stage's first row and the workgroup's first column; its extent ends with the last row of I.
-    auto issue_loads = [&](int s, RawSet &set) {
-      const bool live = s < cnt;
-      const int v_o = live ? table(s * 5) : 0;
-      const int64_t row0 = int64_t(v_o) * p.TK;
-      const int64_t rows_left = p.K - row0;      // >= TK
-      const uint64_t base = reinterpret_cast<uint64_t>(p.I) + uint64_t(row0 * p.ldI + n0) * 2;
-      int64_t ext = rows_left > TKP ? int64_t(TKP) * p.ldI * 2
-                                    : (rows_left - 1) * p.ldI * 2 + (int64_t(p.n_round_bytes) - n0 * 2);
-      if (!live) ext = 0;
+      for (int q = 0; q < NT; ++q) {
+        const int t = ptid + 256 * q, blk = t >> 3, oct = t & 7;
+        t_off[q] = t < NTASK ? blk * 8 * row_bytes + oct * 16 : kOob;   // < 2^30: checked by the host
+        t_lds[q] = (blk * kCW + oct * 8) * 16;
+      }
+      // position swizzle inside a block (see the file header): all tasks of a thread have the same octet
+      // and the same block parity (256 / 8 is even)
+      const int swz = (((ptid & 7) >> 1) << 1) | ((ptid >> 3) & 1);
+      // Loads of stage s (zeros without a memory access past the last stage): the descriptor starts at
+      // the stage's first row and the workgroup's first column; its extent ends with the last row of I.
+      auto issue_loads = [&](int s, RawSet<NT> &set) {
+        const bool live = s < cnt;
+        const int v_o = live ? table(s) : 0;
+        const int64_t row0 = int64_t(v_o) * p.TK;
+        const int64_t rows_left = p.K - row0;      // >= TK
+        const uint64_t base = reinterpret_cast<uint64_t>(p.I) + uint64_t(row0 * p.ldI + n0) * 2;
+        int64_t ext = rows_left > TKP ? int64_t(TKP) * p.ldI * 2
+                                      : (rows_left - 1) * p.ldI * 2 + (int64_t(p.n_round_bytes) - n0 * 2);
+        if (!live) ext = 0;
 #ifdef RBGP_EXPERIMENT
-      if (p.ablate & 4) ext = 0;
+        if (p.ablate & 4) ext = 0;
 #endif
-      const __amdgpu_buffer_rsrc_t rb =
-          __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, int(ext), kRsrcFlags);
+        const __amdgpu_buffer_rsrc_t rb =
+            __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, int(ext), kRsrcFlags);
 #pragma unroll
-      for (int q = 0; q < kMaxTasks; ++q) {
-        if (q * 256 < NTASK) {
+        for (int q = 0; q < NT; ++q)
 #pragma unroll
           for (int r = 0; r < 8; ++r)
             set.r[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rb, t_off[q] + r * row_bytes, 0, 0);
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    // transpose the 8 x 8 blocks (dword d of a row holds columns 2d and 2d + 1) and write them to LDS buffer b
-    auto to_lds = [&](int b, const RawSet &set) {
-      constexpr unsigned LO = 0x05040100u, HI = 0x07060302u;
-      unsigned char *dst = lds + b * BUF;
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      // transpose the 8 x 8 blocks (dword d of a row holds columns 2d and 2d + 1) and write them to LDS buffer b
+      auto to_lds = [&](int b, const RawSet<NT> &set) {
+        constexpr unsigned LO = 0x05040100u, HI = 0x07060302u;
+        unsigned char *dst = lds + b * BUF;
 #pragma unroll
-      for (int q = 0; q < kMaxTasks; ++q) {
-        if (q * 256 < NTASK && ptid + 256 * q < NTASK) {
-          const u32x4 *r = set.r[q];
+        for (int q = 0; q < NT; ++q) {
+          if (ptid + 256 * q < NTASK) {
+            const u32x4 *r = set.r[q];
 #pragma unroll
-          for (int d = 0; d < 4; ++d) {
-            const u32x4 lo = {__builtin_amdgcn_perm(r[1][d], r[0][d], LO), __builtin_amdgcn_perm(r[3][d], r[2][d], LO),
-                              __builtin_amdgcn_perm(r[5][d], r[4][d], LO), __builtin_amdgcn_perm(r[7][d], r[6][d], LO)};
-            const u32x4 hi = {__builtin_amdgcn_perm(r[1][d], r[0][d], HI), __builtin_amdgcn_perm(r[3][d], r[2][d], HI),
-                              __builtin_amdgcn_perm(r[5][d], r[4][d], HI), __builtin_amdgcn_perm(r[7][d], r[6][d], HI)};
-            *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d) ^ swz) << 4)) = lo;
-            *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d + 1) ^ swz) << 4)) = hi;
+            for (int d = 0; d < 4; ++d) {
+              const u32x4 lo = {__builtin_amdgcn_perm(r[1][d], r[0][d], LO), __builtin_amdgcn_perm(r[3][d], r[2][d], LO),
+                                __builtin_amdgcn_perm(r[5][d], r[4][d], LO), __builtin_amdgcn_perm(r[7][d], r[6][d], LO)};
+              const u32x4 hi = {__builtin_amdgcn_perm(r[1][d], r[0][d], HI), __builtin_amdgcn_perm(r[3][d], r[2][d], HI),
+                                __builtin_amdgcn_perm(r[5][d], r[4][d], HI), __builtin_amdgcn_perm(r[7][d], r[6][d], HI)};
+              *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d) ^ swz) << 4)) = lo;
+              *reinterpret_cast<u32x4 *>(dst + t_lds[q] + (((2 * d + 1) ^ swz) << 4)) = hi;
+            }
           }
         }
-      }
-    };
-    // Three register sets: the loads of stages s + 2 and s + 3 are in flight while stage s + 1 moves to LDS
-    // (one stage of lead leaves the producers waiting a memory latency per stage).
-    RawSet setA, setB, setC;
-    issue_loads(0, setA);
-    issue_loads(1, setB);
-    issue_loads(2, setC);
-    to_lds(0, setA);
-    __syncthreads();
-    // iteration s: request stage s + 3 into the set stage s came from, move stage s + 1 to LDS
-    auto pstep = [&](int s, RawSet &free_set, RawSet &cur) {
-      issue_loads(s + 3, free_set);
-#ifdef RBGP_EXPERIMENT
-      if (!(p.ablate & 1))
-#endif
-      if (s + 1 < cnt) to_lds((s + 1) & 1, cur);
+      };
+      // Three register sets: the loads of stages s + 2 and s + 3 are in flight while stage s + 1 moves to LDS
+      // (one stage of lead leaves the producers waiting a memory latency per stage).
+      RawSet<NT> setA, setB, setC;
+      issue_loads(0, setA);
+      issue_loads(1, setB);
+      issue_loads(2, setC);
+      to_lds(0, setA);
       __syncthreads();
+      // iteration s: request stage s + 3 into the set stage s came from, move stage s + 1 to LDS
+      auto pstep = [&](int s, RawSet<NT> &free_set, RawSet<NT> &cur) {
+        issue_loads(s + 3, free_set);
+#ifdef RBGP_EXPERIMENT
+        if (!(p.ablate & 1))
+#endif
+        if (s + 1 < cnt) to_lds((s + 1) & 1, cur);
+        __syncthreads();
+      };
+      for (int s = 0; s < cnt; s += 3) {
+        pstep(s, setA, setB);
+        if (s + 1 < cnt) pstep(s + 1, setB, setC);
+        if (s + 2 < cnt) pstep(s + 2, setC, setA);
+      }
+      __builtin_amdgcn_s_waitcnt(0);
     };
-    for (int s = 0; s < cnt; s += 3) {
-      pstep(s, setA, setB);
-      if (s + 1 < cnt) pstep(s + 1, setB, setC);
-      if (s + 2 < cnt) pstep(s + 2, setC, setA);
-    }
-    __builtin_amdgcn_s_waitcnt(0);
+    if ((wid - 4) * 64 < REM)
+      producer(std::integral_constant<int, FULL + 1>{});
+    else
+      producer(std::integral_constant<int, FULL>{});
     return;
   }
 
   // ------------------------------------------------------------------ consumer
+  // A consumer walks the tiles of its own tile row only (tile j sits in stage table(max_stages + wave * d_o + j)
+  // of the row group) and passes the barriers of the stages in between.
   const int u_o = rg * 4 + wid;
-  const bool row_ok = u_o < p.a_o;
+  const int ntile = u_o < p.a_o ? p.d_o : 0;
   const __amdgpu_buffer_rsrc_t rw =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.Wp), 0, p.w_bytes, kRsrcFlags);
   constexpr int FRAG = TKP * TM * 2;       // bytes of one tile's weights
@@ -220,21 +232,17 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[h][r] = 0.f;
 
-  // index of stage s's tile in the tile row's adjacency list, -1: the tile row lacks it
-  auto tile_of = [&](int s) { return (row_ok && s < cnt) ? table(s * 5 + 1 + wid) : -1; };
-  // the weights of stage s (zeros without a memory access when the tile row lacks the tile)
-  auto issue_weights = [&](int s, u32x4 (&A)[NC]) {
-    int j = tile_of(s);
+  // the weights of the tile row's tile j (zeros without a memory access past its last tile)
+  auto issue_weights = [&](int j, u32x4 (&A)[NC]) {
 #ifdef RBGP_EXPERIMENT
-    if (p.ablate & 8) j = -1;
+    if (p.ablate & 8) j = ntile;
 #endif
-    const int off = (j >= 0 ? (u_o * p.d_o + j) * FRAG : kOob) + alane;
+    const int off = (j < ntile ? (u_o * p.d_o + j) * FRAG : kOob) + alane;
 #pragma unroll
     for (int c = 0; c < NC; ++c) A[c] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, c * (2 * TM * 16), 0);
     __builtin_amdgcn_sched_barrier(0);
   };
   auto compute = [&](int s, const u32x4 (&A)[NC]) {
-    if (tile_of(s) < 0) return;
 #ifdef RBGP_EXPERIMENT
     if (p.ablate & 2) return;
 #endif
@@ -252,21 +260,25 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   };
   u32x4 W0[NC], W1[NC];
   issue_weights(0, W0);
-  __syncthreads();
-  for (int s = 0; s < cnt; s += 2) {
-    issue_weights(s + 1, W1);
-    compute(s, W0);
+  __syncthreads();          // stage 0 is in LDS
+  int done = 0;             // stages whose closing barrier this wave has passed
+  auto cstep = [&](int j, const u32x4 (&cur)[NC], u32x4 (&nxt)[NC]) {
+    const int s = table(p.max_stages + wid * p.d_o + j);
+    for (; done < s; ++done) __syncthreads();   // stages of tile columns this tile row lacks
+    issue_weights(j + 1, nxt);
+    compute(s, cur);
     __syncthreads();
-    if (s + 1 < cnt) {
-      issue_weights(s + 2, W0);
-      compute(s + 1, W1);
-      __syncthreads();
-    }
+    ++done;
+  };
+  for (int j = 0; j < ntile; j += 2) {
+    cstep(j, W0, W1);
+    if (j + 1 < ntile) cstep(j + 1, W1, W0);
   }
+  for (; done < cnt; ++done) __syncthreads();
 
   // Epilogue.  32x32 accumulator: register r of lane (n32, h2) is row 8 * (r / 4) + 4 * h2 + r % 4,
   // column n32 of the block.
-  if (!row_ok) return;
+  if (ntile == 0) return;
 #ifdef RBGP_EXPERIMENT
   if (p.ablate & 16) return;
 #endif
@@ -317,32 +329,31 @@ struct TileState {
 int build_state(const rbgp_mask *m, TileState *st) {
   const int a_o = m->a[0], d_o = m->d[0], c_o = m->c[0];
   const int RG = (a_o + 3) / 4;
-  std::vector<std::vector<int32_t>> rows(static_cast<size_t>(RG));
+  // stage list of a row group: the tile columns that any of its four tile rows has, ascending
+  std::vector<std::vector<int32_t>> cols(static_cast<size_t>(RG));
   int max_stages = 1;
   for (int rg = 0; rg < RG; ++rg) {
-    std::vector<int32_t> &out = rows[size_t(rg)];
-    for (int v = 0; v < c_o; ++v) {
-      int32_t jj[4] = {-1, -1, -1, -1};
-      bool any = false;
-      for (int w = 0; w < 4; ++w) {
-        const int u = rg * 4 + w;
-        if (u >= a_o) continue;
-        for (int j = 0; j < d_o; ++j)
-          if (m->adj[0][size_t(u) * d_o + j] == v) {
-            jj[w] = j;
-            any = true;
-          }
-      }
-      if (!any) continue;
-      out.push_back(v);
-      out.insert(out.end(), jj, jj + 4);
-    }
-    max_stages = std::max(max_stages, int(out.size() / 5));
+    std::vector<char> has(static_cast<size_t>(c_o), 0);
+    for (int u = rg * 4; u < std::min(a_o, rg * 4 + 4); ++u)
+      for (int j = 0; j < d_o; ++j) has[size_t(m->adj[0][size_t(u) * d_o + j])] = 1;
+    for (int v = 0; v < c_o; ++v)
+      if (has[size_t(v)]) cols[size_t(rg)].push_back(v);
+    max_stages = std::max(max_stages, int(cols[size_t(rg)].size()));
   }
-  std::vector<int32_t> stages(size_t(RG) * max_stages * 5, -1), counts(static_cast<size_t>(RG), 0);
+  const int rec = max_stages + 4 * d_o;
+  std::vector<int32_t> stages(size_t(RG) * rec, 0), counts(static_cast<size_t>(RG), 0);
   for (int rg = 0; rg < RG; ++rg) {
-    std::copy(rows[size_t(rg)].begin(), rows[size_t(rg)].end(), stages.begin() + size_t(rg) * max_stages * 5);
-    counts[size_t(rg)] = int32_t(rows[size_t(rg)].size() / 5);
+    const std::vector<int32_t> &cl = cols[size_t(rg)];
+    int32_t *out = stages.data() + size_t(rg) * rec;
+    std::copy(cl.begin(), cl.end(), out);
+    counts[size_t(rg)] = int32_t(cl.size());
+    for (int w = 0; w < 4; ++w) {
+      const int u = rg * 4 + w;
+      for (int j = 0; j < d_o && u < a_o; ++j) {
+        const int32_t v = m->adj[0][size_t(u) * d_o + j];
+        out[max_stages + w * d_o + j] = int32_t(std::lower_bound(cl.begin(), cl.end(), v) - cl.begin());
+      }
+    }
   }
   RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->stages), stages.size() * 4));
   RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->counts), counts.size() * 4));
@@ -394,7 +405,7 @@ int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N,
 #ifdef RBGP_EXPERIMENT
   if (getenv("RBGP_TILE_NOINL")) p.inl_ok = 0;
 #endif
-  p.tab_bytes = p.inl_ok ? 0 : (st->max_stages * 5 * 4 + 15) / 16 * 16;
+  p.tab_bytes = p.inl_ok ? 0 : ((st->max_stages + 4 * m->d[0]) * 4 + 15) / 16 * 16;
   if (p.inl_ok) std::copy(st->host_table.begin(), st->host_table.end(), p.inl);
 #ifdef RBGP_EXPERIMENT
   p.ablate = getenv("RBGP_TILE_ABLATE") ? atoi(getenv("RBGP_TILE_ABLATE")) : 0;
