@@ -18,7 +18,7 @@
 // the 16-byte writes of 16 neighbouring lanes (8 column octets x 2 blocks, same column offset) then fall
 // on 16 different bank groups, while the 32 lanes of a read still cover 512 contiguous bytes.
 // Two LDS buffers and one barrier per stage: consumers multiply stage s while producers fill the
-// buffer of stage s + 1, with the loads of stages s + 2 and s + 3 in flight (three register sets).
+// buffer of stage s + 1, with the loads of stage s + 2 in flight (two register sets).
 // A consumer wave whose tile row lacks the tile column skips the MFMAs of the stage (its weight
 // loads point past the packed buffer and return zeros without a memory access).
 // Measured against the register-streaming family on the VGG19 layers in bf16: faster where the
@@ -180,28 +180,29 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
           }
         }
       };
-      // Three register sets: the loads of stages s + 2 and s + 3 are in flight while stage s + 1 moves to LDS
-      // (one stage of lead leaves the producers waiting a memory latency per stage).
-      RawSet<NT> setA, setB, setC;
-      issue_loads(0, setA);
-      issue_loads(1, setB);
-      issue_loads(2, setC);
-      to_lds(0, setA);
+      // NS register sets: the loads of stages s + 2 .. s + NS are in flight while stage s + 1 moves to LDS.
+      // Measured on the VGG19 conv3 shape (us per launch): NS = 1: 18.6, 2: 17.4, 3: 18.6, 6: 20.0 -- one
+      // stage of lead hides the latency; more loads in flight only queue in front of the consumers' weight
+      // loads (and 64 or more per wave exceed the hardware's load counter: NS = 4 with two tasks, 41.6).
+      constexpr int NS = 2;
+      RawSet<NT> sets[NS];
+      static_for<0, NS>([&](auto ic) { issue_loads(decltype(ic)::value, sets[decltype(ic)::value]); });
+      to_lds(0, sets[0]);
       __syncthreads();
-      // iteration s: request stage s + 3 into the set stage s came from, move stage s + 1 to LDS
+      // iteration s: request stage s + NS into the set stage s came from, move stage s + 1 to LDS
       auto pstep = [&](int s, RawSet<NT> &free_set, RawSet<NT> &cur) {
-        issue_loads(s + 3, free_set);
+        issue_loads(s + NS, free_set);
 #ifdef RBGP_EXPERIMENT
         if (!(p.ablate & 1))
 #endif
         if (s + 1 < cnt) to_lds((s + 1) & 1, cur);
         __syncthreads();
       };
-      for (int s = 0; s < cnt; s += 3) {
-        pstep(s, setA, setB);
-        if (s + 1 < cnt) pstep(s + 1, setB, setC);
-        if (s + 2 < cnt) pstep(s + 2, setC, setA);
-      }
+      for (int s = 0; s < cnt; s += NS)
+        static_for<0, NS>([&](auto ic) {
+          constexpr int i = decltype(ic)::value;
+          if (s + i < cnt) pstep(s + i, sets[i], sets[(i + 1) % NS]);
+        });
       __builtin_amdgcn_s_waitcnt(0);
     };
     if ((wid - 4) * 64 < REM)
