@@ -490,8 +490,9 @@ struct RegState {
   int32_t *colbase[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};   // [dtype][wide tile]: pixel offsets of the column groups
   int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};  // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
-  RegTables tab_bf16;              // bf16: clusters of tab_bf16_G groups
-  int tab_bf16_G = 0;
+  RegTables tab_bf16[3];           // bf16: clusters of 1, 2, 4 groups
+  int g2_stages = -1, g2_ncl = 0;  // longest stage list and number of the clusters of two groups (-2: too long,
+                                   //   or their stage lists add up to more than 0.8 of those of one group)
 };
 
 template <typename T>
@@ -546,7 +547,7 @@ void rbgp_reg_release(void *state) {
     for (int32_t *t : pair)
       if (t) (void)hipFree(t);
   free_tables(&st->tab);
-  free_tables(&st->tab_bf16);
+  for (RegTables &t : st->tab_bf16) free_tables(&t);
   delete st;
 }
 
@@ -633,15 +634,37 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   }
   const int64_t ntiles = (N + CW - 1) / CW;
   // bf16: 16-row groups per wave (G) and waves per column tile (S).  More groups mean fewer
-  // passes of I through the load path at the price of multiplied zeros; measured on the VGG19
-  // conv3 shape the two balance out, so the default is one group.  The stage list is split
-  // when there are fewer (cluster, G_i vertex, column tile) triples than SIMDs.
+  // passes of I through the load path at the price of multiplied zeros; on the VGG19 conv3 shape
+  // the two balance out, so the default is one group unless the rule below finds two worth it.
+  // The stage list is split when there are fewer (cluster, G_i vertex, column tile) triples than SIMDs.
   int G = 1, lgS = 0;
   {
     const int tg = bf16 ? tune[RBGP_TUNE_ROW_GROUPS] : 0, ts = tune[RBGP_TUNE_K_SPLIT];
     if (tg) {
       if (tg != 1 && tg != 2 && tg != 4) return RBGP_EUNSUPPORTED;   // (too long a stage list is rejected below)
       G = tg;
+    } else if (bf16 && !conv && !ts && (pl.TR + pl.MG - 1) / pl.MG >= 2) {
+      // Two groups per wave halve the bytes of I that cross the L1 path.  Measured on the VGG19 layers (bf16,
+      // densities 1/2 and 1/4): that pays (3-22 %) where the larger clusters still give every SIMD a wave
+      // without a split, or where each wave of the split keeps a dozen stages to amortise the reduction; it
+      // costs 7-25 % where neither holds, and 7-15 % where G_o is so sparse that the tile rows of a larger
+      // cluster share few tiles (density 1/16: the stage lists of the clusters then add up to nearly as many
+      // stages as before, each multiplied into twice the rows).
+      if (st->g2_stages == -1) {
+        rbgp_reg_clusters c2;
+        rbgp_reg_cluster(m, 2 * pl.MG, &c2);
+        int64_t total1 = 0, total2 = 0;
+        for (int32_t c : m->reg_clusters.counts) total1 += c;
+        for (int32_t c : c2.counts) total2 += c;
+        st->g2_stages = (c2.max_stages > 60 || m->reg_clusters.U != pl.MG || 5 * total2 > 4 * total1) ? -2 : c2.max_stages;
+        st->g2_ncl = c2.ncl;
+      }
+      if (st->g2_stages > 0) {
+        const int64_t waves2 = int64_t(st->g2_ncl) * m->a[2] * ntiles;
+        int S2 = 1;
+        while (S2 < 4 && waves2 * S2 < 1024) S2 *= 2;
+        if (waves2 * S2 >= 1024 && (S2 == 1 || st->g2_stages / S2 >= 12)) G = 2;
+      }
     }
     const int64_t ncl = (pl.TR + G * pl.MG - 1) / (G * pl.MG);
     if (ts) {
@@ -651,11 +674,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       while (lgS < 2 && ((ncl * m->a[2] * ntiles) << lgS) < 1024) ++lgS;
     }
   }
-  RegTables *tab = bf16 ? &st->tab_bf16 : &st->tab;
-  if (bf16 && st->tab_bf16_G != G) {
-    free_tables(tab);   // (hipFree waits for launches that still read the old tables)
-    st->tab_bf16_G = G;
-  }
+  RegTables *tab = bf16 ? &st->tab_bf16[G == 4 ? 2 : G == 2 ? 1 : 0] : &st->tab;
   if (!tab->stages) {
     int rc = build_tables(m, G * pl.MG, tab);
     if (rc) return rc;
