@@ -143,3 +143,73 @@ def test_argument_checks():
         rb.rbgp_spmm(mask, 3, w.M, w.K, w.N, packed.data_ptr(), I_d.data_ptr(), w.N, O_d.data_ptr(), w.N, 0)
     assert e.value.code == rb.EINVAL
     torch.cuda.synchronize()
+
+
+def test_two_layer_chain_in_bf16_from_a_hip_graph():
+    """What the mode is for: layer 1 stores its output as bf16 and layer 2 reads it as its input, no
+    conversion pass in between.  Layer 1 on the tile family, layer 2 on the register family; both
+    launches captured into one graph after a warm-up call; three replays on fresh inputs, each bit-equal
+    to the eager calls and, for the final output, within the bf16 tolerance of the oracle's two products
+    (the oracle rounds its own intermediate to bf16 with its own converter)."""
+    import torch
+    N = 1000
+    w1 = wl.Workload("chain_l1", (8, 4, 4, 2), (8, 4, 8, 9), (4, 4, 4, 9), N, wl.BF16, 21, 22, 23, 0.05)
+    w2 = wl.Workload("chain_l2", (4, 2, 4, 2), (8, 2, 4, 4), (4, 2, 2, 4), N, wl.BF16, 24, 25, 26, 0.05)
+    assert w1.M == w2.K
+    m1, m2 = gh.make_mask(w1), gh.make_mask(w2)
+    rb.rbgp_mask_set_kernel(m1, rb.KERNEL_MFMA_TILE)
+    v1, v2 = wl.to_bf16_bits(wl.kept_weights(w1)), wl.to_bf16_bits(wl.kept_weights(w2))
+    dev = "cuda:0"
+    st0 = torch.cuda.current_stream().cuda_stream
+    p1 = torch.zeros(rb.rbgp_packed_bytes(m1, rb.BF16), dtype=torch.uint8, device=dev)
+    p2 = torch.zeros(rb.rbgp_packed_bytes(m2, rb.BF16), dtype=torch.uint8, device=dev)
+    rb.rbgp_pack(m1, rb.BF16, v1, p1.data_ptr(), st0)
+    rb.rbgp_pack(m2, rb.BF16, v2, p2.data_ptr(), st0)
+    I1 = torch.zeros((w1.K, N), dtype=torch.int16, device=dev)
+    O1 = torch.zeros((w1.M, N), dtype=torch.int16, device=dev)      # bf16 bits: output of layer 1, input of layer 2
+    O2 = torch.zeros((w2.M, N), dtype=torch.float32, device=dev)
+
+    def step(stream):
+        rb.rbgp_spmm(m1, rb.BF16, w1.M, w1.K, N, p1.data_ptr(), I1.data_ptr(), N, O1.data_ptr(), N, stream)
+        rb.rbgp_spmm(m2, rb.BF16_F32ACC, w2.M, w2.K, N, p2.data_ptr(), O1.data_ptr(), N, O2.data_ptr(), N, stream)
+
+    print("[gpu] bf16 chain: warm-up", flush=True)
+    step(st0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)
+    Bs1, _ = orc.sample_factors(w1.rows, w1.cols, w1.row_deg, w1.mask_seed)
+    Bs2, _ = orc.sample_factors(w2.rows, w2.cols, w2.row_deg, w2.mask_seed)
+    mk1, mk2 = orc.kron_mask(Bs1), orc.kron_mask(Bs2)
+    W1 = orc.scatter_values(mk1, wl.bf16_bits_as_f32(v1))
+    W2 = orc.scatter_values(mk2, wl.bf16_bits_as_f32(v2))
+    for seed in (1, 2, 3):
+        print(f"[gpu] bf16 chain: replay {seed}", flush=True)
+        Ib = wl.to_bf16_bits(wl.activations(replace(w1, i_seed=100 + seed)))
+        I1.copy_(torch.from_numpy(Ib.view(np.int16)))
+        step(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref1, ref2 = O1.clone(), O2.clone()
+        O1.fill_(0x7FC0)
+        O2.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O1, ref1) and torch.equal(O2, ref2)
+        mid = orc.spmm_definition(mk1, W1, wl.bf16_bits_as_f32(Ib))
+        mid_bits = orc.f32_to_bf16_bits(mid.astype(np.float32))
+        got_mid = O1.cpu().numpy().view(np.uint16)
+        # the two sides round sums that differ in their last bits, so a few codes differ (by more than one unit
+        # where a sum cancels to nearly nothing); the bound is the one of check_bf16_output
+        differ = np.count_nonzero(got_mid != mid_bits)
+        den1 = orc.spmm_definition(mk1, np.abs(W1), np.abs(wl.bf16_bits_as_f32(Ib)))
+        bound = HALF_ULP * np.abs(mid) + ACC_TOL * den1 + 1e-38
+        assert float(np.max(np.abs(orc.bf16_bits_to_f32(got_mid).astype(np.float64) - mid) / bound)) <= 1.0
+        assert differ <= mid_bits.size // 200, differ
+        mid_f = orc.bf16_bits_to_f32(mid_bits)
+        exact = orc.spmm_definition(mk2, W2, mid_f)
+        den = orc.spmm_definition(mk2, np.abs(W2), np.abs(mid_f))
+        err = orc.normalised_error(O2.cpu().numpy(), exact, den)
+        print(f"[gpu]   codes that differ {differ} of {mid_bits.size}, final normalised error {err:.2e}", flush=True)
+        assert err <= gh.TOL[wl.BF16]
