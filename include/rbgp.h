@@ -78,8 +78,8 @@ enum {
                                block of W_s (zeros where the inner graphs have no edge), I staged in
                                LDS once per workgroup, 32-row MFMA.  Any inner graphs; needs
                                |G_r.U| |G_i.U| |G_b.U| = 32 or 64 and |G_r.V| |G_i.V| |G_b.V| <= 320.
-                               rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8
-                               (ESHAPE); rbgp_conv3x3 and fp32 do not run on it (EUNSUPPORTED) */
+                               rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8,
+                               rbgp_conv3x3 an image width that is a multiple of 8 (ESHAPE) */
 };
 
 /* tuning knobs (rbgp_mask_tune) */
@@ -287,8 +287,9 @@ int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K,
  * of channel c; column n = (image * height + y) * width + x.  dev_O: M x N row-major fp32
  * (bf16 bits in RBGP_BF16 mode), N = images * height * width, leading dimension ldO >= N, overwritten.  dev_packed: as for
  * rbgp_spmm (same layout, same dtype).
- * Runs on the RBGP_KERNEL_MFMA_REG family only: EUNSUPPORTED for masks or kernel choices
- * outside it; ESHAPE unless width is a multiple of 4 and the sizes match the mask.
+ * Runs on the RBGP_KERNEL_MFMA_REG family (and, for masks set to it, on RBGP_KERNEL_MFMA_TILE):
+ * EUNSUPPORTED for masks or kernel choices outside them; ESHAPE unless width is a multiple of 4
+ * (8 on RBGP_KERNEL_MFMA_TILE) and the sizes match the mask.
  * Asynchronous on `hip_stream`. */
 int rbgp_conv3x3(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
                  int64_t images, int64_t height, int64_t width, const void *dev_packed, const void *dev_X,

@@ -702,12 +702,16 @@ int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out,
   if (images <= 0 || height <= 0 || width <= 0 || (width % 4)) return RBGP_ESHAPE;
   const int64_t N = images * height * width;
   if (channels_out != m->M || 9 * channels_in != m->K || ldO < N) return RBGP_ESHAPE;
-  if (resolve_kernel(m, dtype) != RBGP_KERNEL_MFMA_REG) return RBGP_EUNSUPPORTED;
+  const int kernel = resolve_kernel(m, dtype);
+  if (kernel != RBGP_KERNEL_MFMA_REG && kernel != RBGP_KERNEL_MFMA_TILE) return RBGP_EUNSUPPORTED;
   if (!dev_packed || !dev_X || !dev_O) return RBGP_EINVAL;
   if (dtype == RBGP_BF16 && (reinterpret_cast<uintptr_t>(dev_O) & 1)) return RBGP_ESHAPE;
   int rc = ensure_device(m);
   if (rc) return rc;
   const rbgp_conv_geometry geom = {images, height, width};
+  if (kernel == RBGP_KERNEL_MFMA_TILE)
+    return rbgp_tile_launch(m, &m->dev->tile_state, dtype == RBGP_BF16, N, dev_packed, dev_X, N, dev_O, ldO, hip_stream,
+                            &geom);
   return rbgp_reg_launch(m, &m->dev->reg_state, m->dev->tune, bf16_in(dtype), dtype == RBGP_BF16, N, dev_packed, dev_X,
                          N, dev_O, ldO, hip_stream, &geom);
 }

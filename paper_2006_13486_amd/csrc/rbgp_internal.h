@@ -145,9 +145,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
                     const void *packed, const void *I, int64_t ldI, void *O, int64_t ldO, void *stream,
                     const rbgp_conv_geometry *conv = nullptr);
 void rbgp_reg_release(void *state);
-// tile family (rbgp_mfma_tile.hip; bf16 inputs only); needs rbgp_plan_tile(m).ok
+// tile family (rbgp_mfma_tile.hip; bf16 inputs only); needs rbgp_plan_tile(m).ok; conv as for rbgp_reg_launch
+// (image width a multiple of 8)
 int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N, const void *packed, const void *I,
-                     int64_t ldI, void *O, int64_t ldO, void *stream);
+                     int64_t ldI, void *O, int64_t ldO, void *stream, const rbgp_conv_geometry *conv = nullptr);
 void rbgp_tile_release(void *state);
 // weight-gradient kernels (rbgp_sddmm.hip); use_mfma needs rbgp_reg_covers(m)
 // conv != nullptr (needs use_mfma): I is the zero-padded activation tensor of a 3x3 convolution, ldI is ignored

@@ -21,9 +21,11 @@
 // buffer of stage s + 1, with the loads of stage s + 2 in flight (two register sets).
 // A consumer wave whose tile row lacks the tile column skips the MFMAs of the stage (its weight
 // loads point past the packed buffer and return zeros without a memory access).
+// The fused 3x3 convolution runs here too: only the producers' addresses change (stage row k is
+// tap k % 9 of channel k / 9 of the zero-padded activations).
 // Measured against the register-streaming family on the VGG19 layers in bf16: faster where the
-// tiles are dense (density 1/2 on the large layers, by 15-20 %), slower elsewhere; never chosen
-// by RBGP_KERNEL_AUTO.
+// tiles are dense (density 1/2 on the layers with many columns, by 13-30 %), slower elsewhere;
+// never chosen by RBGP_KERNEL_AUTO.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -65,6 +67,14 @@ struct TileParams {
   int ablate;              // timing experiments: 1 skips the LDS writes, 2 the MFMAs, 4 the loads of I
 #endif
   int ntiles, RG;          // column tiles of 64, row groups of 4 tile rows
+  // Fused 3x3 convolution: I is the zero-padded activation tensor X[channel][image][H + 2][W + 2] (bf16) and row
+  // k = 9 * channel + tap of the lowered input is read from it: a tile column is TK / 9 consecutive channels.
+  int conv;                // 1: fused convolution
+  int conv_w2;             // W + 2 (pixels of a padded image row)
+  uint32_t chan_bytes;     // bytes of one channel of X
+  int64_t x_bytes;         // bytes of X (< 2^31)
+  const int32_t *colbase;  // [ntiles * 8]: byte offset, inside a channel of X, of the first pixel of every group of
+                           //   8 columns (8 pixels of one image row: W % 8 == 0); padded to whole tiles
   uint32_t w_bytes;
   uint32_t n_round_bytes;  // N rounded up to 8 columns, in bytes: the extent of the last row of I
 };
@@ -127,11 +137,28 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
     auto producer = [&](auto nt_c) {
       constexpr int NT = decltype(nt_c)::value;
       const int row_bytes = int(p.ldI) * 2;
-      int t_off[NT > 0 ? NT : 1], t_lds[NT > 0 ? NT : 1];
+      // byte offset of every load of this thread inside the stage's descriptor.  Plain product: row of the stage
+      // times the row pitch plus the octet's columns.  Fused convolution: stage row k is tap k % 9 of the stage's
+      // channel k / 9 -- channel pitch, plus the octet's first pixel in the padded image (host table), plus the
+      // shift of the tap (the loads are then 2-byte aligned, which the memory path accepts).
+      int l_off[NT > 0 ? NT : 1][8], t_lds[NT > 0 ? NT : 1];
 #pragma unroll
       for (int q = 0; q < NT; ++q) {
         const int t = ptid + 256 * q, blk = t >> 3, oct = t & 7;
-        t_off[q] = t < NTASK ? blk * 8 * row_bytes + oct * 16 : kOob;   // < 2^30: checked by the host
+        const int pix = p.conv ? p.colbase[(nt * 8 + oct)] : 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const int k = blk * 8 + r;
+          int off;
+          if (p.conv) {
+            const int ch = int(uint32_t(k) / 9u), tap = k - 9 * ch;
+            const int dy = tap / 3 - 1, dx = tap - 3 * (tap / 3) - 1;
+            off = int(uint32_t(ch) * p.chan_bytes) + pix + (dy * p.conv_w2 + dx) * 2;
+          } else {
+            off = k * row_bytes + oct * 16;   // < 2^30: checked by the host
+          }
+          l_off[q][r] = t < NTASK ? off : kOob;
+        }
         t_lds[q] = (blk * kCW + oct * 8) * 16;
       }
       // position swizzle inside a block (see the file header): all tasks of a thread have the same octet
@@ -144,9 +171,14 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
         const int v_o = live ? table(s) : 0;
         const int64_t row0 = int64_t(v_o) * p.TK;
         const int64_t rows_left = p.K - row0;      // >= TK
-        const uint64_t base = reinterpret_cast<uint64_t>(p.I) + uint64_t(row0 * p.ldI + n0) * 2;
+        uint64_t base = reinterpret_cast<uint64_t>(p.I) + uint64_t(row0 * p.ldI + n0) * 2;
         int64_t ext = rows_left > TKP ? int64_t(TKP) * p.ldI * 2
                                       : (rows_left - 1) * p.ldI * 2 + (int64_t(p.n_round_bytes) - n0 * 2);
+        if (p.conv) {   // the descriptor starts at the stage's first channel and ends with X
+          const int64_t first = int64_t(v_o) * (p.TK / 9) * p.chan_bytes;
+          base = reinterpret_cast<uint64_t>(p.I) + uint64_t(first);
+          ext = p.x_bytes - first;
+        }
         if (!live) ext = 0;
 #ifdef RBGP_EXPERIMENT
         if (p.ablate & 4) ext = 0;
@@ -157,7 +189,7 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
         for (int q = 0; q < NT; ++q)
 #pragma unroll
           for (int r = 0; r < 8; ++r)
-            set.r[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rb, t_off[q] + r * row_bytes, 0, 0);
+            set.r[q][r] = __builtin_amdgcn_raw_buffer_load_b128(rb, l_off[q][r], 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       };
       // transpose the 8 x 8 blocks (dword d of a row holds columns 2d and 2d + 1) and write them to LDS buffer b
@@ -314,6 +346,8 @@ struct TileState {
   int32_t *stages = nullptr, *counts = nullptr;
   int max_stages = 0, RG = 0;
   std::vector<int32_t> host_table;   // stages then counts: what the kernel arguments carry when it is short enough
+  int32_t *colbase = nullptr;        // fused convolution: pixel offsets of the column octets for the geometry below
+  int64_t conv_key[3] = {0, 0, 0};   // images, height, width
 };
 
 #define RBGP_HIP(call)                                                              \
@@ -374,16 +408,30 @@ void rbgp_tile_release(void *state) {
   if (!st) return;
   if (st->stages) (void)hipFree(st->stages);
   if (st->counts) (void)hipFree(st->counts);
+  if (st->colbase) (void)hipFree(st->colbase);
   delete st;
 }
 
 int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N, const void *packed, const void *I,
-                     int64_t ldI, void *O, int64_t ldO, void *stream) {
+                     int64_t ldI, void *O, int64_t ldO, void *stream, const rbgp_conv_geometry *conv) {
   const rbgp_tile_plan pl = rbgp_plan_tile(m);
   if (!pl.ok) return RBGP_EUNSUPPORTED;
-  if ((reinterpret_cast<uintptr_t>(I) & 15) || (ldI % 8)) return RBGP_ESHAPE;
-  // 32-bit offsets address the rows of one stage (and stay below the out-of-range offset of idle load slots)
-  if (int64_t(pl.TKP) * ldI * 2 + 256 >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  int64_t chan_bytes = 0, x_bytes = 0;
+  if (conv) {
+    // the nine taps are the columns of a complete G_b; a lane's eight columns are eight pixels of one image row
+    if (m->c[3] != 9 || m->d[3] != 9) return RBGP_EUNSUPPORTED;
+    if (conv->images <= 0 || conv->height <= 0 || conv->width <= 0 || conv->width % 8) return RBGP_ESHAPE;
+    if (N != conv->images * conv->height * conv->width) return RBGP_ESHAPE;
+    if (reinterpret_cast<uintptr_t>(I) % 4) return RBGP_ESHAPE;
+    chan_bytes = conv->images * (conv->height + 2) * (conv->width + 2) * 2;
+    x_bytes = (m->K / 9) * chan_bytes;
+    if (x_bytes + 64 >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;   // 32-bit offsets, below the idle slots' offset
+    ldI = 8;   // (unused by the kernel)
+  } else {
+    if ((reinterpret_cast<uintptr_t>(I) & 15) || (ldI % 8)) return RBGP_ESHAPE;
+    // 32-bit offsets address the rows of one stage (and stay below the out-of-range offset of idle load slots)
+    if (int64_t(pl.TKP) * ldI * 2 + 256 >= (int64_t(1) << 30)) return RBGP_EUNSUPPORTED;
+  }
   TileState *st = static_cast<TileState *>(*state);
   if (!st) {
     st = new (std::nothrow) TileState();
@@ -413,6 +461,31 @@ int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N,
 #endif
   const int64_t ntiles = (N + kCW - 1) / kCW;
   p.ntiles = int(ntiles); p.RG = st->RG;
+  p.conv = conv ? 1 : 0;
+  p.conv_w2 = conv ? int(conv->width + 2) : 0;
+  p.chan_bytes = uint32_t(chan_bytes);
+  p.x_bytes = x_bytes;
+  p.colbase = nullptr;
+  if (conv) {
+    int64_t *key = st->conv_key;
+    if (st->colbase && (key[0] != conv->images || key[1] != conv->height || key[2] != conv->width)) {
+      (void)hipFree(st->colbase);   // (waits for launches that still read the old table)
+      st->colbase = nullptr;
+    }
+    if (!st->colbase) {
+      // padding octets of the last tile point at the first pixel: their columns are never stored
+      const int64_t H = conv->height, W = conv->width;
+      std::vector<int32_t> cb(size_t(ntiles) * 8, int32_t((W + 3) * 2));
+      for (int64_t n = 0; n < N; n += 8) {
+        const int64_t img = n / (H * W), y = (n % (H * W)) / W, x = n % W;
+        cb[size_t(n / 8)] = int32_t(((img * (H + 2) + y + 1) * (W + 2) + x + 1) * 2);
+      }
+      RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->colbase), cb.size() * 4));
+      RBGP_HIP(hipMemcpy(st->colbase, cb.data(), cb.size() * 4, hipMemcpyHostToDevice));
+      key[0] = conv->images; key[1] = conv->height; key[2] = conv->width;
+    }
+    p.colbase = st->colbase;
+  }
   p.w_bytes = uint32_t(pl.packed_elems * 2);
   p.n_round_bytes = uint32_t((N + 7) / 8 * 8 * 2);
   const int64_t blocks = 8 * ((ntiles + 7) / 8) * st->RG;

@@ -73,15 +73,17 @@ def library_spmm(w, vals_lib, I_lib, kernel=rb.KERNEL_AUTO, tune=None, ld_pad=0,
     return out[:, :N], used
 
 
-def library_conv3x3(w, vals, X, dtype=None, tune=None, tag="", out_bf16=False):
+def library_conv3x3(w, vals, X, dtype=None, tune=None, tag="", out_bf16=False, kernel=rb.KERNEL_AUTO):
     """Run rbgp_conv3x3 on X[C][B][H][W] (padded here: layout work, not arithmetic)."""
     import torch
     dev = torch.device("cuda:0")
     C, B, H, W = X.shape
     N = B * H * W
     dtype = w.dtype if dtype is None else dtype
-    print(f"[gpu] conv3x3 {w.name} C={C} B={B} H={H} W={W} dtype={dtype} tune={tune} {tag}", flush=True)
+    print(f"[gpu] conv3x3 {w.name} C={C} B={B} H={H} W={W} dtype={dtype} tune={tune} kernel={kernel} {tag}", flush=True)
     mask = make_mask(w)
+    if kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mask, kernel)
     for knob, value in enumerate(tune or ()):
         rb.rbgp_mask_tune(mask, knob, value)
     stream = torch.cuda.current_stream().cuda_stream

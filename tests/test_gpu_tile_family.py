@@ -107,7 +107,33 @@ def test_family_limits():
     with pytest.raises(rb.RbgpError) as e:                   # leading dimension not a multiple of 8
         rb.rbgp_spmm(mask, rb.BF16_F32ACC, w.M, w.K, w.N, packed.data_ptr(), I_d.data_ptr(), w.N + 4, O_d.data_ptr(), w.N, 0)
     assert e.value.code == rb.ESHAPE
-    with pytest.raises(rb.RbgpError) as e:                   # the fused convolution runs on the register family only
-        rb.rbgp_conv3x3(mask, rb.BF16_F32ACC, w.M, w.K // 9, 1, 8, 8, packed.data_ptr(), I_d.data_ptr(), O_d.data_ptr(), 64, 0)
-    assert e.value.code == rb.EUNSUPPORTED
+    with pytest.raises(rb.RbgpError) as e:                   # fused convolution: image width a multiple of 8
+        rb.rbgp_conv3x3(mask, rb.BF16_F32ACC, w.M, w.K // 9, 4, 4, 4, packed.data_ptr(), I_d.data_ptr(), O_d.data_ptr(), 64, 0)
+    assert e.value.code == rb.ESHAPE
     torch.cuda.synchronize()
+
+
+CONV_CASES = [
+    # workload (32 rows per tile, K = 9 * channels), images, height, width
+    (wl.VGG19_CONV3_BF16, 128, 8, 8),                                   # 256 -> 256 channels, 8x8 pixels, batch 128
+    (replace(wl.VGG19_CONV3_BF16, name="tile_conv3_ragged"), 33, 8, 8),  # 33 column tiles
+    (wl.Workload("tile_conv_w16", (4, 2, 8, 2), (8, 2, 8, 9), (4, 2, 4, 9), 0, wl.BF16, 61, 62, 63, 1.0), 3, 5, 16),
+    (wl.Workload("tile_conv_w32", (6, 2, 4, 4), (6, 2, 4, 9), (3, 2, 2, 9), 0, wl.BF16, 64, 65, 66, 1.0), 2, 3, 32),
+    (wl.Workload("tile_conv_pad", (2, 1, 32, 1), (2, 1, 4, 9), (2, 1, 2, 9), 0, wl.BF16, 67, 68, 69, 1.0), 5, 4, 8),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: c[0].name)
+def test_fused_conv3x3(case):
+    """rbgp_conv3x3 on the tile family (the producers read the padded activations instead of the lowered
+    matrix) = the oracle's product with the explicitly lowered input; fp32 and bf16 output."""
+    w, B, H, W = case
+    vals_lib, X_lib = wl.to_bf16_bits(wl.kept_weights(w)), wl.to_bf16_bits(wl.conv_activations(w, B, H, W))
+    vals, X = wl.bf16_bits_as_f32(vals_lib), wl.bf16_bits_as_f32(X_lib)
+    ref, den = gh.oracle_spmm(w, vals, orc.im2col_3x3(X))
+    out = gh.library_conv3x3(w, vals_lib, X_lib, kernel=TILE)
+    err = orc.normalised_error(out, ref, den)
+    print(f"[gpu]   normalised error {err:.3e}", flush=True)
+    assert err <= gh.TOL[wl.BF16], err
+    out16 = gh.library_conv3x3(w, vals_lib, X_lib, kernel=TILE, out_bf16=True)
+    assert np.array_equal((out16.view(np.uint32) >> 16).astype(np.uint16), orc.f32_to_bf16_bits(out))
