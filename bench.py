@@ -304,6 +304,25 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
                             dXs[j].data_ptr(), w.N, stream)
         steps_list.append(("input_gradient_fused_conv3x3", input_step,
                            dOp.nbytes + (w.K // 9) * w.N * 4 + w.nnz * w.in_bytes))
+        # the same on the tile family, where it covers the mask of the transposed convolution (bf16, 32 rows per tile)
+        dXts = None
+        if bf16 and W % 8 == 0:
+            mask_xt = rb.rbgp_mask_conv3x3_transpose(mask)
+            try:
+                rb.rbgp_mask_set_kernel(mask_xt, rb.KERNEL_MFMA_TILE)
+            except rb.RbgpError:
+                mask_xt = None
+            if mask_xt is not None:
+                packed_xt = torch.zeros(rb.rbgp_packed_bytes(mask_xt, w.dtype), dtype=torch.uint8, device=dev)
+                rb.rbgp_pack_transposed(mask_xt, w.dtype, np.ascontiguousarray(vals_lib), packed_xt.data_ptr(), stream)
+                dXts = [torch.empty((w.K // 9, w.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+
+                def input_step_tile(i):
+                    j = i % nsets
+                    rb.rbgp_conv3x3(mask_xt, w.dtype, w.K // 9, w.M, B, H, W, packed_xt.data_ptr(), dOps[j].data_ptr(),
+                                    dXts[j].data_ptr(), w.N, stream)
+                steps_list.append(("input_gradient_fused_conv3x3_tile", input_step_tile,
+                                   dOp.nbytes + (w.K // 9) * w.N * 4 + w.nnz * w.in_bytes))
     out = {}
     for name, step, abytes in steps_list:
         if only and name != only and not (only == "weight_gradient" and name.startswith("weight_gradient")) \
@@ -322,7 +341,9 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
         tf = w.flops / (ms * 1e-3) / 1e12
         out[name] = {"entry_point": {"backward_data": "rbgp_spmm on rbgp_mask_transpose", "weight_gradient": "rbgp_sddmm",
                                      "weight_gradient_fused_conv3x3": "rbgp_conv3x3_sddmm",
-                                     "input_gradient_fused_conv3x3": "rbgp_conv3x3 on rbgp_mask_conv3x3_transpose"}[name],
+                                     "input_gradient_fused_conv3x3": "rbgp_conv3x3 on rbgp_mask_conv3x3_transpose",
+                                     "input_gradient_fused_conv3x3_tile":
+                                         "rbgp_conv3x3 on rbgp_mask_conv3x3_transpose, RBGP_KERNEL_MFMA_TILE"}[name],
                      "ms": ms, "value": tf, "unit": "TFLOP/s", "frac_of_fp32_mfma_peak": tf / PEAK_F32_TFLOPS,
                      "algorithmic_bytes": abytes, "algorithmic_gbs": abytes / (ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": abytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "steps": steps, "buffer_sets": nsets}
@@ -347,6 +368,9 @@ def backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stre
             den = orc.col2im_3x3(naive_c.spmm_abs(mT, WT, sub), Bc, Hq, Wq).reshape(w.K // 9, -1)
             out["input_gradient_fused_conv3x3"]["parity_err"] = orc.normalised_error(
                 dXs[0].cpu().numpy()[:, :Bc * Hq * Wq], ref, den)
+            if "input_gradient_fused_conv3x3_tile" in out:
+                out["input_gradient_fused_conv3x3_tile"]["parity_err"] = orc.normalised_error(
+                    dXts[0].cpu().numpy()[:, :Bc * Hq * Wq], ref, den)
         # sampled rows of dW (each needs the whole batch)
         rows = np.unique(np.linspace(0, w.M - 1, 8 if light_check else 48).astype(np.int64))
         if "weight_gradient_fused_conv3x3" in out:     # (timed last: dWs hold its result)

@@ -178,7 +178,7 @@ def library_conv3x3_sddmm(w, dO_lib, X, tag=""):
     return out[:w.M * w.rowdeg].reshape(w.M, w.rowdeg)
 
 
-def library_conv3x3_input_gradient(w, vals_lib, dO_lib, B, H, W, tag=""):
+def library_conv3x3_input_gradient(w, vals_lib, dO_lib, B, H, W, tag="", kernel=rb.KERNEL_AUTO):
     """dX[C][B*H*W] of the fused 3x3 convolution: rbgp_conv3x3 on the mask of the transposed convolution,
     reading dO[M][B][H][W] zero-padded."""
     import torch
@@ -186,6 +186,8 @@ def library_conv3x3_input_gradient(w, vals_lib, dO_lib, B, H, W, tag=""):
     print(f"[gpu] conv3x3 input gradient {w.name} B={B} H={H} W={W} dtype={w.dtype} {tag}", flush=True)
     mask = make_mask(w)
     mx = rb.rbgp_mask_conv3x3_transpose(mask)
+    if kernel != rb.KERNEL_AUTO:
+        rb.rbgp_mask_set_kernel(mx, kernel)
     stream = torch.cuda.current_stream().cuda_stream
     packed = torch.zeros(max(rb.rbgp_packed_bytes(mx, w.dtype), 16), dtype=torch.uint8, device="cuda:0")
     rb.rbgp_pack_transposed(mx, w.dtype, np.ascontiguousarray(vals_lib).reshape(-1), packed.data_ptr(), stream)

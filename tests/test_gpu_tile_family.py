@@ -137,3 +137,31 @@ def test_fused_conv3x3(case):
     assert err <= gh.TOL[wl.BF16], err
     out16 = gh.library_conv3x3(w, vals_lib, X_lib, kernel=TILE, out_bf16=True)
     assert np.array_equal((out16.view(np.uint32) >> 16).astype(np.uint16), orc.f32_to_bf16_bits(out))
+
+
+@pytest.mark.parametrize("case", [
+    (wl.VGG19_CONV3_BF16, 16, 8, 8),                                     # transposed: 32 x 288 tiles again
+    (wl.Workload("tile_dx_w16", (4, 4, 4, 2), (4, 4, 8, 9), (2, 4, 8, 9), 0, wl.BF16, 71, 72, 73, 1.0), 3, 5, 16),
+    (wl.Workload("tile_dx_ragged", (8, 2, 2, 4), (4, 4, 8, 9), (4, 4, 4, 9), 0, wl.BF16, 74, 75, 76, 1.0), 5, 3, 8),
+], ids=lambda c: c[0].name)
+def test_fused_conv3x3_input_gradient(case):
+    """dX of the fused convolution = rbgp_conv3x3 of the zero-padded dO on the mask of the transposed
+    convolution (32 rows per tile whenever |G_r.V| |G_i.V| = 32), run on the tile family; against the
+    oracle's transposed product folded back onto the pixels."""
+    from oracle import naive_c
+    w, B, H, W = case
+    w = replace(w, N=B * H * W)
+    vl, dOl = wl.to_bf16_bits(wl.kept_weights(w)), wl.to_bf16_bits(wl.output_gradients(w))
+    vals, dO = wl.bf16_bits_as_f32(vl), wl.bf16_bits_as_f32(dOl)
+    got, used = gh.library_conv3x3_input_gradient(w, vl, dOl, B, H, W, kernel=TILE)
+    assert used == TILE
+    Bs, _ = orc.sample_factors(w.rows, w.cols, w.row_deg, w.mask_seed)
+    mask = orc.kron_mask(Bs)
+    Wd = orc.scatter_values(mask, vals)
+    maskT, WT = np.ascontiguousarray(mask.T), np.ascontiguousarray(Wd.T)
+    dI, dI_den = naive_c.spmm(maskT, WT, dO), naive_c.spmm_abs(maskT, WT, dO)
+    ref = orc.col2im_3x3(dI, B, H, W).reshape(w.K // 9, -1)
+    den = orc.col2im_3x3(dI_den, B, H, W).reshape(w.K // 9, -1)
+    err = orc.normalised_error(got, ref, den)
+    print(f"[gpu]   normalised error {err:.3e}", flush=True)
+    assert err <= gh.TOL[wl.BF16], err
