@@ -132,7 +132,10 @@ int rbgp_make_mask(const int32_t rows[4], const int32_t cols[4], const int32_t r
  * exactly G_1 (x) ... (x) G_count.  The MFMA kernel families need the factors of roles 1 and 3 complete:
  * where a role 1 or 3 is given a sparse base graph, the graphs of that role up to its last sparse one
  * join role 0 or 2 in the kernels' view (rbgp_mask_factor / rbgp_mask_spectrum report that view, the
- * mask, its canonical order and rbgp_mask_base do not change).  The same holds for rbgp_make_mask.
+ * mask, its canonical order and rbgp_mask_base do not change).  And where every base graph of role 2
+ * is complete (all the sparsity in G_o), they join role 1 in that view: a complete G_i repeats rows
+ * exactly as G_r does, and the kernels fill their row groups better from it.  The same holds for
+ * rbgp_make_mask.
  * rbgp_mask_spectrum of a factor made of several base graphs reports the singular values of the
  * product (products of the base graphs' singular values), the bound of the product's degrees and
  * RBGP_SPEC_PRODUCT; rbgp_mask_base reports each base graph.  rbgp_make_mask(rows, cols, row_deg, ...)

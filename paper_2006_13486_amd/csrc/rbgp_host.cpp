@@ -708,6 +708,21 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
       for (int i = 0; i <= last_sparse; ++i)
         if (m->base[size_t(i)].role == role) m->base[size_t(i)].role = role - 1;
     }
+    // A complete G_i is row repetition like G_r (Section 5: every row of the block has the same columns), and the
+    // kernels make more of it there: rows that share a column set fill the 16 rows of an MFMA group without
+    // pairing tile rows that share only some of their tiles.  So where every graph in the role of G_i is complete,
+    // they join G_r in the kernels' view (G_i becomes the single-vertex graph).
+    {
+      bool any = false, all_complete = true;
+      for (int i = 0; i < count; ++i)
+        if (m->base[size_t(i)].role == 2) {
+          any = true;
+          all_complete = all_complete && m->base[size_t(i)].status == RBGP_SPEC_COMPLETE;
+        }
+      if (any && all_complete)
+        for (int i = 0; i < count; ++i)
+          if (m->base[size_t(i)].role == 2) m->base[size_t(i)].role = 1;
+    }
     for (int role = 0; role < 4; ++role) merge_role(m, role);
     for (int i = 0; i < count; ++i) m->base[size_t(i)].role = given[size_t(i)];
   } catch (const std::bad_alloc &) {
