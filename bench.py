@@ -397,7 +397,8 @@ def main():
                     help="untimed steps; the shader clock needs some hundred launches to settle")
     ap.add_argument("--workload", default="conv5", choices=sorted(WORKLOADS))
     ap.add_argument("--sets", type=int, default=0, help="distinct (I,O) buffer sets to rotate over (0 = auto)")
-    ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in order: cols_per_lane,cols_per_workgroup,groups_per_workgroup,cluster")
+    ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in their order in include/rbgp.h (0 = default): cols_per_lane,"
+                         "cols_per_workgroup,groups_per_workgroup,weights_in_lds,row_groups,k_split")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ld-pad", type=int, default=0,
