@@ -56,7 +56,8 @@ enum {
   RBGP_ENOTRAMANUJAN = -3, /* no sample met the bound within max_tries */
   RBGP_ESHAPE = -4,        /* M, K, ld* do not match the mask */
   RBGP_EHIP = -5,          /* a HIP call failed (message via rbgp_last_hip_error) */
-  RBGP_EUNSUPPORTED = -6   /* requested kernel cannot run this mask / dtype */
+  RBGP_EUNSUPPORTED = -6,  /* requested kernel cannot run this mask / dtype */
+  RBGP_EINTERNAL = -7      /* rbgp_mask_check_tables found an inconsistent index table */
 };
 
 /* per-factor result of the spectral test */
@@ -87,8 +88,13 @@ enum {
   RBGP_TUNE_COLS_PER_LANE = 0,        /* MFMA: 1 or 2 */
   RBGP_TUNE_COLS_PER_WORKGROUP = 1,   /* MFMA: 64 or 128; MFMA_REG bf16: columns per wave, 64 or 128 */
   RBGP_TUNE_GROUPS_PER_WORKGROUP = 2, /* MFMA: a divisor of |G_i.U| */
-  RBGP_TUNE_WEIGHTS_IN_LDS = 3,       /* MFMA_REG fp32: 2 = copy the workgroup's weights to LDS first
-                                         (when they fit 160 KB) instead of streaming them */
+  RBGP_TUNE_ROW_PAIRING = 3,          /* MFMA_REG fp32, masks whose rows repeat in groups of 5..8 (two tile
+                                         rows per 16-row MFMA group): 1 = fixed pairs of tile rows, each wave
+                                         walking the union of its pair's tiles; 2 = a wave owns one tile row
+                                         and pairs it, tile by tile, with one of two partner rows that has
+                                         the same tile (EUNSUPPORTED where that kernel does not apply: bf16,
+                                         other group sizes, more than 32 tile rows, with RBGP_TUNE_K_SPLIT);
+                                         default: 2 where it walks fewer tiles and N fills the chip */
   RBGP_TUNE_ROW_GROUPS = 4,           /* MFMA_REG bf16: 16-row MFMA groups per wave, 1, 2 or 4 (each
                                          loaded row of I is reused by all of them) */
   RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG: waves that share a column tile and split its
@@ -325,6 +331,22 @@ int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *mask, rbgp_mask_t **out);
  * memory, nnz int32) = canonical index, in the mask it was made from, of the kept value that has
  * canonical index s in this mask (what rbgp_pack_transposed applies).  EINVAL for other masks. */
 int rbgp_mask_original_order(const rbgp_mask_t *derived, int32_t *out);
+
+/* How the RBGP_KERNEL_MFMA_REG family walks this mask (host only; Section 5: G_o skips tiles, G_r and
+ * G_b repeat rows).  info[0] = tile rows per 16-row MFMA group (0: the family does not cover the mask,
+ * the rest is 0 too), [1] = stages per nonzero tile, [2] = contraction steps per stage (padded),
+ * [3] = tile rows; fixed clusters of tile rows: [4] = clusters, [5] = longest stage list, [6] = sum of
+ * the stage lists; tile-by-tile pairing (RBGP_TUNE_ROW_PAIRING = 2; all 0 where it does not apply):
+ * [7] = quads of tile rows, [8] = most stages on one SIMD (two waves), [9] = sum of the stage lists,
+ * [10] = longest stage list of a wave, [11] / [12] = distinct stages of I wanted by the first / the first
+ * two stages of all waves together.  [13..15] = 0. */
+int rbgp_mask_reg_plan(const rbgp_mask_t *mask, int32_t info[16]);
+
+/* Host-only self check of the index tables the RBGP_KERNEL_MFMA_REG kernels read for this mask: every
+ * (tile row, nonzero tile, stage) is multiplied exactly once, by a stage whose rows of I are that
+ * tile's and lie inside K, with a weight-fragment position inside the packed buffer; stage lists fit
+ * their tables and end in sentinels.  RBGP_OK, or RBGP_EINTERNAL (a bug in the library). */
+int rbgp_mask_check_tables(const rbgp_mask_t *mask);
 
 /* Static description of an error code / of the last HIP failure in this thread. */
 const char *rbgp_strerror(int code);

@@ -11,10 +11,10 @@ import numpy as np
 
 F32, BF16_F32ACC, BF16 = 0, 1, 2   # BF16: as BF16_F32ACC with O stored as bf16 bits
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG, KERNEL_MFMA_TILE = 0, 1, 2, 3, 4
-TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_WEIGHTS_IN_LDS = 0, 1, 2, 3
+TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_ROW_PAIRING = 0, 1, 2, 3
 TUNE_ROW_GROUPS, TUNE_K_SPLIT = 4, 5
 SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE, SPEC_PRODUCT = 0, 1, 2, 3
-OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED, EINTERNAL = 0, -1, -2, -3, -4, -5, -6, -7
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librbgp.so")
 _lib = None
@@ -59,6 +59,8 @@ SIGNATURES = {
                                  _vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]),
     "rbgp_conv3x3": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, _vp, _vp, ctypes.c_int64, _vp]),
     "rbgp_conv3x3_sddmm": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, ctypes.c_int64, _vp, _vp, _vp]),
+    "rbgp_mask_reg_plan": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_int32)]),
+    "rbgp_mask_check_tables": (ctypes.c_int, [_vp]),
     "rbgp_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "rbgp_last_hip_error": (ctypes.c_char_p, []),
 }
@@ -78,13 +80,15 @@ def load():
     """Load librbgp.so (built by paper_2006_13486_amd.build); fails loudly if absent."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # RBGP_LIB names another build of the same library (the host-only sanitizer build of the CPU tests)
+        path = os.environ.get("RBGP_LIB") or _LIB_PATH
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         # torch bundles its own HIP runtime (SONAME libamdhip64.so.7).  Import it first so
         # that librbgp.so binds to that copy: two HIP runtimes in one process do not share
         # the device and the second one reports "no ROCm-capable device".
         import torch  # noqa: F401
-        lib = ctypes.CDLL(_LIB_PATH)
+        lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype = res
@@ -166,6 +170,16 @@ def rbgp_mask_factor(mask: Mask, i: int):
                                    ctypes.byref(adj)), "rbgp_mask_factor")
     a = np.ctypeslib.as_array(adj, shape=(r.value, d.value)).copy()
     return int(r.value), int(c.value), int(d.value), a
+
+
+def rbgp_mask_reg_plan(mask: Mask) -> list:
+    info = (ctypes.c_int32 * 16)()
+    _check(load().rbgp_mask_reg_plan(mask.handle, info), "rbgp_mask_reg_plan")
+    return [int(v) for v in info]
+
+
+def rbgp_mask_check_tables(mask: Mask) -> None:
+    _check(load().rbgp_mask_check_tables(mask.handle), "rbgp_mask_check_tables")
 
 
 def rbgp_mask_spectrum(mask: Mask, i: int) -> dict:

@@ -315,6 +315,7 @@ void rbgp_plan_reg(rbgp_mask *m) {
   }
   m->reg = p;
   if (p.ok) rbgp_reg_cluster(m, p.MG, &m->reg_clusters);
+  rbgp_reg_plan_dual(m, &m->reg_dual);
 }
 
 // Register-streaming family: group the tile rows into clusters of U whose adjacency lists
@@ -459,6 +460,227 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
   out->members.swap(members);
   out->stages.swap(stages);
   out->counts.swap(counts);
+}
+
+// Register-streaming family, lo/hi pairing (see rbgp_reg_dual): choose the quads (L0, L1, H0, H1)
+// and give every tile of an H row to a wave whose L row has the same tile.  The two waves of an L
+// row share a SIMD, so a quad costs, per L row, the tiles of that row plus its share of the H tiles
+// that no L row can carry; the search minimises (longest pair of waves, total) over the partitions of
+// the tile rows into quads: depth first, candidates in order of cost, bounded effort.  Two rows with
+// complementary tile sets (the two clones of a vertex after the last 2-lift of a complete graph,
+// Appendix) make a perfect L pair for any such H pair: every stage then multiplies 16 rows of the mask.
+void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
+  *out = rbgp_reg_dual();
+  const rbgp_reg_plan &pl = m->reg;
+  if (!pl.ok || pl.MG != 2 || pl.TR < 2) return;
+  const int TR = pl.TR, TRP = (TR + 3) / 4 * 4, c1 = m->c[0], d1 = m->d[0];
+  if (TRP > 32 || c1 > 256) return;
+  constexpr int W = 4;   // 64-bit words of a tile set
+  struct Set { uint64_t w[W]; };
+  std::vector<Set> has(static_cast<size_t>(TRP), Set{{0, 0, 0, 0}});
+  for (int u = 0; u < TR; ++u)
+    for (int j = 0; j < d1; ++j) {
+      const int v = m->adj[0][size_t(u / pl.fold) * d1 + j];
+      has[size_t(u)].w[v >> 6] |= uint64_t(1) << (v & 63);
+    }
+  auto tiles = [&](int u) { return u < TR ? d1 : 0; };
+  // stages of the busier L row and of the whole quad for the ordered roles (L0, L1, H0, H1)
+  auto cost = [&](int l0, int l1, int h0, int h1, int *total) {
+    int extra = 0;
+    for (int k = 0; k < W; ++k) {
+      const uint64_t a = has[size_t(l0)].w[k], b = has[size_t(l1)].w[k], x = has[size_t(h0)].w[k], y = has[size_t(h1)].w[k];
+      extra += __builtin_popcountll(x & ~(a | b)) + __builtin_popcountll(y & ~(a | b)) + __builtin_popcountll(x & y & (a ^ b));
+    }
+    const int t0 = tiles(l0), t1 = tiles(l1);
+    *total = t0 + t1 + extra;
+    return std::max(std::max(t0, t1), (*total + 1) / 2);
+  };
+  struct Cand { int mx, tot, r[4]; };
+  const int nq = TRP / 4;
+  std::vector<int32_t> cur(static_cast<size_t>(TRP), 0), best;
+  int best_max = 1 << 30, best_tot = 1 << 30;
+  std::vector<char> taken(static_cast<size_t>(TRP), 0);
+  long budget = 200000;
+  const int lb_tot = (TR * d1 + 1) / 2;
+  struct Rec {
+    decltype(cost) &cost; std::vector<int32_t> &cur, &best; std::vector<char> &taken;
+    int TRP, nq, d1, lb_tot; int &best_max, &best_tot; long &budget;
+    bool done() const { return best_max <= d1 && best_tot <= lb_tot; }
+    void go(int depth, int cmax, int ctot) {
+      if (depth == nq) {
+        if (cmax < best_max || (cmax == best_max && ctot < best_tot)) { best_max = cmax; best_tot = ctot; best = cur; }
+        return;
+      }
+      int x = 0;
+      while (taken[size_t(x)]) ++x;
+      std::vector<Cand> cands;
+      for (int y = x + 1; y < TRP; ++y) {
+        if (taken[size_t(y)]) continue;
+        for (int z = y + 1; z < TRP; ++z) {
+          if (taken[size_t(z)]) continue;
+          for (int w = z + 1; w < TRP; ++w) {
+            if (taken[size_t(w)]) continue;
+            const int q[4] = {x, y, z, w};
+            // the six choices of the L pair
+            for (int a = 0; a < 4; ++a)
+              for (int b = a + 1; b < 4; ++b) {
+                int h[2], nh = 0;
+                for (int k = 0; k < 4; ++k)
+                  if (k != a && k != b) h[nh++] = q[k];
+                Cand c;
+                c.mx = cost(q[a], q[b], h[0], h[1], &c.tot);
+                c.r[0] = q[a]; c.r[1] = q[b]; c.r[2] = h[0]; c.r[3] = h[1];
+                cands.push_back(c);
+              }
+          }
+        }
+      }
+      std::stable_sort(cands.begin(), cands.end(), [](const Cand &p, const Cand &q) {
+        return p.mx != q.mx ? p.mx < q.mx : p.tot < q.tot;
+      });
+      for (const Cand &c : cands) {
+        if (budget-- <= 0 || done()) return;
+        const int nmax = std::max(cmax, c.mx), ntot = ctot + c.tot;
+        if (nmax > best_max || (nmax == best_max && ntot >= best_tot)) continue;
+        for (int k = 0; k < 4; ++k) { taken[size_t(c.r[k])] = 1; cur[size_t(4 * depth + k)] = c.r[k]; }
+        go(depth + 1, nmax, ntot);
+        for (int k = 0; k < 4; ++k) taken[size_t(c.r[k])] = 0;
+      }
+    }
+  } rec{cost, cur, best, taken, TRP, nq, d1, lb_tot, best_max, best_tot, budget};
+  rec.go(0, 0, 0);
+  if (best.empty()) return;
+
+  // Stage lists of the four waves (x, y) = (L_x, H_y) of every quad.
+  auto has_tile = [&](int u, int v) { return u < TR && ((has[size_t(u)].w[v >> 6] >> (v & 63)) & 1); };
+  auto pos = [&](int u, int v) {   // position of v in u's adjacency list
+    int j = 0;
+    while (m->adj[0][size_t(u / pl.fold) * d1 + j] != v) ++j;
+    return j;
+  };
+  struct Stage { int v, lo, hi; };   // tile, position in L_x's list (-1: none), position in H_y's list (-1: none)
+  out->members.assign(size_t(nq) * 4, -1);
+  out->stages.assign(size_t(nq) * 4 * 3 * 64, -1);
+  out->counts.assign(size_t(nq) * 4, 0);
+  std::vector<std::vector<Stage>> lists(size_t(nq) * 4);
+  for (int q = 0; q < nq; ++q) {
+    const int L[2] = {best[size_t(4 * q)], best[size_t(4 * q + 1)]}, H[2] = {best[size_t(4 * q + 2)], best[size_t(4 * q + 3)]};
+    for (int k = 0; k < 4; ++k) out->members[size_t(4 * q + k)] = best[size_t(4 * q + k)] < TR ? best[size_t(4 * q + k)] : -1;
+    std::vector<Stage> st[2][2];
+    std::vector<std::pair<int, int>> lo_only, hi_only;   // (tile, x) / (tile, y) without a partner
+    for (int v = 0; v < c1; ++v) {
+      int hs[2], nh = 0;
+      for (int y = 0; y < 2; ++y)
+        if (has_tile(H[y], v)) hs[nh++] = y;
+      const bool l[2] = {has_tile(L[0], v), has_tile(L[1], v)};
+      int used = 0;
+      if (l[0] && l[1] && nh == 2) {
+        st[0][0].push_back({v, pos(L[0], v), pos(H[0], v)});
+        st[1][1].push_back({v, pos(L[1], v), pos(H[1], v)});
+        used = 2;
+      } else {
+        for (int x = 0; x < 2; ++x) {
+          if (!l[x]) continue;
+          if (used < nh) {
+            st[x][hs[used]].push_back({v, pos(L[x], v), pos(H[hs[used]], v)});
+            ++used;
+          } else {
+            lo_only.push_back({v, x});
+          }
+        }
+      }
+      for (; used < nh; ++used) hi_only.push_back({v, hs[used]});
+    }
+    // a tile of L_x alone goes to the shorter of L_x's two waves; a tile of H_y alone to the L row
+    // with fewer stages so far (the two waves of an L row share a SIMD)
+    for (const auto &e : lo_only) {
+      const int x = e.second, y = st[x][1].size() < st[x][0].size() ? 1 : 0;
+      st[x][y].push_back({e.first, pos(L[x], e.first), -1});
+    }
+    for (const auto &e : hi_only) {
+      const int y = e.second;
+      const int x = st[1][0].size() + st[1][1].size() < st[0][0].size() + st[0][1].size() ? 1 : 0;
+      st[x][y].push_back({e.first, -1, pos(H[y], e.first)});
+    }
+    for (int x = 0; x < 2; ++x)
+      for (int y = 0; y < 2; ++y) lists[(size_t(q) * 2 + x) * 2 + y] = st[x][y];
+  }
+  // Order of the tiles.  All waves start together and walk their lists at the same pace, so the r-th
+  // tiles of all waves are wanted from HBM at the same time: a tile that several waves read in the same
+  // round is fetched once for all of them.  Every wave sorts its tiles by one common order of the tiles,
+  // chosen (pairwise exchanges from a few starting orders, deterministic) to keep the number of distinct
+  // tiles wanted up to each round small; ascending order asks for half of I in the first round on a
+  // random G_o, the best order for a quarter (four waves per tile).
+  std::vector<int> order(static_cast<size_t>(c1));
+  for (int v = 0; v < c1; ++v) order[size_t(v)] = v;
+  if (c1 <= 64) {
+    size_t rounds = 0;
+    for (const auto &l : lists) rounds = std::max(rounds, l.size());
+    auto front = [&](const std::vector<int> &rank) {   // sum over rounds of the distinct tiles wanted so far
+      std::vector<std::vector<int>> sorted(lists.size());
+      for (size_t i = 0; i < lists.size(); ++i) {
+        for (const Stage &sg_ : lists[i]) sorted[i].push_back(rank[size_t(sg_.v)]);
+        std::sort(sorted[i].begin(), sorted[i].end());
+      }
+      uint64_t seen = 0;
+      long total = 0;
+      for (size_t r = 0; r < rounds; ++r) {
+        for (const auto &l : sorted)
+          if (r < l.size()) seen |= uint64_t(1) << l[r];
+        total += __builtin_popcountll(seen);
+      }
+      return total;
+    };
+    std::vector<int> rank(static_cast<size_t>(c1)), best_rank;
+    long best_front = -1;
+    uint64_t lcg = 0x9E3779B97F4A7C15ull;
+    for (int start = 0; start < 16; ++start) {
+      for (int v = 0; v < c1; ++v) rank[size_t(v)] = v;
+      if (start)
+        for (int v = c1 - 1; v > 0; --v) {   // a fixed pseudo-random starting order
+          lcg = lcg * 6364136223846793005ull + 1442695040888963407ull;
+          std::swap(rank[size_t(v)], rank[size_t((lcg >> 33) % uint64_t(v + 1))]);
+        }
+      long cur_front = front(rank);
+      for (bool improved = true; improved;) {
+        improved = false;
+        for (int a = 0; a < c1; ++a)
+          for (int b = a + 1; b < c1; ++b) {
+            std::swap(rank[size_t(a)], rank[size_t(b)]);
+            const long f = front(rank);
+            if (f < cur_front) { cur_front = f; improved = true; }
+            else std::swap(rank[size_t(a)], rank[size_t(b)]);
+          }
+      }
+      if (best_front < 0 || cur_front < best_front) { best_front = cur_front; best_rank = rank; }
+    }
+    order = best_rank;   // order[v] = rank of tile v
+  }
+  for (int q = 0; q < nq; ++q) {
+    for (int x = 0; x < 2; ++x) {
+      int both = 0;
+      for (int y = 0; y < 2; ++y) {
+        std::vector<Stage> &l = lists[(size_t(q) * 2 + x) * 2 + y];
+        std::stable_sort(l.begin(), l.end(), [&](const Stage &a, const Stage &b) { return order[size_t(a.v)] < order[size_t(b.v)]; });
+        int n = 0;
+        int32_t *tab = &out->stages[((size_t(q) * 2 + x) * 2 + y) * 3 * 64];
+        for (const Stage &sg_ : l)
+          for (int sg = 0; sg < pl.NSTG; ++sg, ++n) {
+            if (n >= 60) continue;   // does not fit the per-lane table: counted, not stored
+            tab[n] = int32_t((int64_t(sg_.v) * m->c[1] + int64_t(sg) * pl.VC) * m->c[2] * m->c[3]);
+            tab[64 + n] = sg_.lo >= 0 ? sg_.lo * pl.NSTG + sg : -1;
+            tab[128 + n] = sg_.hi >= 0 ? sg_.hi * pl.NSTG + sg : -1;
+          }
+        out->counts[(size_t(q) * 2 + x) * 2 + y] = n;
+        out->max_wave = std::max(out->max_wave, n);
+        out->total_stages += n;
+        both += n;
+      }
+      out->max_stages = std::max(out->max_stages, both);
+    }
+  }
+  out->nq = nq;
+  out->ok = out->max_wave <= 60;
 }
 
 // Packed layouts.
@@ -1013,6 +1235,96 @@ int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
   return RBGP_OK;
 }
 
+int rbgp_mask_reg_plan(const rbgp_mask_t *m, int32_t info[16]) {
+  if (!m || !info) return RBGP_EINVAL;
+  for (int i = 0; i < 16; ++i) info[i] = 0;
+  const rbgp_reg_plan &p = m->reg;
+  if (!p.ok) return RBGP_OK;
+  info[0] = p.MG; info[1] = p.NSTG; info[2] = p.KC; info[3] = p.TR;
+  const rbgp_reg_clusters &cl = m->reg_clusters;
+  info[4] = cl.ncl; info[5] = cl.max_stages;
+  for (int32_t c : cl.counts) info[6] += c;
+  const rbgp_reg_dual &d = m->reg_dual;
+  if (d.ok) {
+    info[7] = d.nq; info[8] = d.max_stages; info[9] = int32_t(d.total_stages); info[10] = d.max_wave;
+    // distinct stage bases wanted by the r-th stages of all waves, r = 0 and r <= 1
+    std::vector<int32_t> seen;
+    for (int r = 0; r < 2; ++r) {
+      for (int wv = 0; wv < d.nq * 4; ++wv)
+        if (d.counts[size_t(wv)] > r) {
+          const int32_t base = d.stages[size_t(wv) * 3 * 64 + r];
+          if (std::find(seen.begin(), seen.end(), base) == seen.end()) seen.push_back(base);
+        }
+      info[11 + r] = int32_t(seen.size());
+    }
+  }
+  return RBGP_OK;
+}
+
+// Every (tile row, tile, stage of the tile) must be multiplied exactly once, by a stage whose base
+// row is that tile's, with a fragment position inside the tile row's fragments; stage lists must fit
+// their per-lane tables and end in sentinels.
+int rbgp_mask_check_tables(const rbgp_mask_t *m) {
+  if (!m) return RBGP_EINVAL;
+  const rbgp_reg_plan &p = m->reg;
+  if (!p.ok) return RBGP_OK;
+  try {
+    const int d1 = m->d[0], fpm = d1 * p.NSTG;
+    const int64_t stage_rows = int64_t(p.VC) * m->c[2] * m->c[3];
+    // expected base row of fragment f of tile row u
+    auto base_of = [&](int u, int f) {
+      const int v = m->adj[0][size_t(u / p.fold) * d1 + f / p.NSTG];
+      return (int64_t(v) * m->c[1] + int64_t(f % p.NSTG) * p.VC) * m->c[2] * m->c[3];
+    };
+    auto check_use = [&](std::vector<int> &used, int u, int f, int64_t base) {
+      if (u < 0 || u >= p.TR || f < 0 || f >= fpm) return false;
+      if (base != base_of(u, f) || base < 0 || base + stage_rows > m->K) return false;
+      return ++used[size_t(u) * fpm + f] == 1;
+    };
+    {
+      const rbgp_reg_clusters &cl = m->reg_clusters;
+      std::vector<int> used(size_t(p.TR) * fpm, 0);
+      if (cl.max_stages <= 60) {
+        for (int c = 0; c < cl.ncl; ++c) {
+          const int n = cl.counts[size_t(c)];
+          if (n < 0 || n > 60) return RBGP_EINTERNAL;
+          for (int st = 0; st < 64; ++st) {
+            const int32_t base = cl.stages[(size_t(c) * (1 + cl.U)) * 64 + st];
+            if ((st < n) != (base >= 0)) return RBGP_EINTERNAL;
+            for (int k = 0; k < cl.U; ++k) {
+              const int32_t f = cl.stages[(size_t(c) * (1 + cl.U) + 1 + k) * 64 + st];
+              if (st >= n && f != -1) return RBGP_EINTERNAL;
+              if (f >= 0 && !check_use(used, cl.members[size_t(c) * cl.U + k], f, base)) return RBGP_EINTERNAL;
+            }
+          }
+        }
+        for (int c : used)
+          if (c != 1) return RBGP_EINTERNAL;
+      }
+    }
+    const rbgp_reg_dual &d = m->reg_dual;
+    if (d.ok) {
+      std::vector<int> used(size_t(p.TR) * fpm, 0);
+      for (int wv = 0; wv < d.nq * 4; ++wv) {
+        const int q = wv / 4, x = (wv / 2) % 2, y = wv % 2, n = d.counts[size_t(wv)];
+        if (n < 0 || n > 60) return RBGP_EINTERNAL;
+        const int32_t *tab = &d.stages[size_t(wv) * 3 * 64];
+        for (int st = 0; st < 64; ++st) {
+          if ((st < n) != (tab[st] >= 0)) return RBGP_EINTERNAL;
+          if (st >= n && (tab[64 + st] != -1 || tab[128 + st] != -1)) return RBGP_EINTERNAL;
+          if (tab[64 + st] >= 0 && !check_use(used, d.members[size_t(q) * 4 + x], tab[64 + st], tab[st])) return RBGP_EINTERNAL;
+          if (tab[128 + st] >= 0 && !check_use(used, d.members[size_t(q) * 4 + 2 + y], tab[128 + st], tab[st])) return RBGP_EINTERNAL;
+        }
+      }
+      for (int c : used)
+        if (c != 1) return RBGP_EINTERNAL;
+    }
+  } catch (const std::bad_alloc &) {
+    return RBGP_ENOMEM;
+  }
+  return RBGP_OK;
+}
+
 const char *rbgp_strerror(int code) {
   switch (code) {
     case RBGP_OK: return "ok";
@@ -1022,6 +1334,7 @@ const char *rbgp_strerror(int code) {
     case RBGP_ESHAPE: return "shape, leading dimension or alignment does not match the mask";
     case RBGP_EHIP: return "HIP call failed";
     case RBGP_EUNSUPPORTED: return "kernel does not cover this mask or dtype";
+    case RBGP_EINTERNAL: return "an index table of the library is inconsistent";
     default: return "unknown error";
   }
 }

@@ -71,6 +71,25 @@ struct rbgp_reg_clusters {
   std::vector<int32_t> counts;    // [ncl] stages per cluster
 };
 
+// Lo/hi pairing of the tile rows for the fp32 register-streaming kernels whose MFMA groups hold two
+// tile rows of 8 rows (rbgp_mfma_reg_dual.hip).  Tile rows come in quads (L0, L1, H0, H1).  Wave
+// (x, y) of a quad multiplies the tiles that L_x and H_y share: L_x's weights in rows 0..7 of the
+// group, H_y's in rows 8..15.  A tile that finds no partner in the quad gets a stage with the other
+// half zero.  Every (tile row, tile) pair is multiplied exactly once; the two waves of L_x together
+// walk L_x's tiles (and run on one SIMD), the sums of a tile row are added up from its two waves.
+struct rbgp_reg_dual {
+  bool ok = false;
+  int nq = 0;                     // quads
+  int max_stages = 0;             // most stages of the two waves of an L row
+  int max_wave = 0;               // longest stage list of a wave
+  int64_t total_stages = 0;       // over all waves
+  std::vector<int32_t> members;   // [nq][4]: L0, L1, H0, H1 (-1: none)
+  std::vector<int32_t> stages;    // [nq][x][y][3][64]: per wave and stage (one per lane) the base row of I, the
+                                  //   position of L_x's weight fragment among L_x's (-1: none), the position of
+                                  //   H_y's among its own (-1: none); -1 past the end (sentinel stages)
+  std::vector<int32_t> counts;    // [nq][x][y]: stages of the wave
+};
+
 // One sampled base graph of a mask made from more than four of them.
 struct rbgp_base_graph {
   int32_t a, c, d, e, role;
@@ -92,6 +111,7 @@ struct rbgp_mask {
   rbgp_mfma_plan plan;
   rbgp_reg_plan reg;
   rbgp_reg_clusters reg_clusters;     // clusters of reg.MG tile rows (when reg.ok)
+  rbgp_reg_dual reg_dual;             // lo/hi pairing (when reg.ok, reg.MG == 2 and at most 32 tile rows)
   mutable rbgp_device_state *dev;     // lazily created device tables
 };
 
@@ -160,5 +180,6 @@ void rbgp_sddmm_release(void *state);
 void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);
 void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out);
+void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm);

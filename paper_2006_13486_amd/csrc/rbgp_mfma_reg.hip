@@ -14,7 +14,7 @@
 // stages ahead, slot by slot, into the registers the previous MFMAs just released,
 // and the compiler's vmcnt bookkeeping provides the software pipeline.  (LDS is
 // used once, after the loop, when the stage list of a cluster is split over
-// several waves for small N; and optionally to hold the workgroup's weights.)
+// several waves for small N.)
 // The same kernel serves the fused 3x3 convolution: only the addresses of the
 // loads differ (see `off` in the prologue).
 //
@@ -60,16 +60,14 @@ using namespace rbgp_reg;
 namespace {
 
 // KC: contraction steps per stage; RS: weight rows per tile row in the 16-row MFMA group
-// (cluster size MG = 16 / RS); WLDS: the weights of the workgroup's (cluster, G_i vertex)
-// are copied to LDS once and read from there (they are the same for every column tile),
-// else they stream from global memory like I.
+// (cluster size MG = 16 / RS).  The weights stream from global memory like I (they are L2 hits).
 // TAPS (fused 3x3 convolution on a tap-grouped layout, image width dividing 64): slots 3p,
 // 3p+1, 3p+2 of a lane group are the taps dx = -1, 0, +1 of one (channel, dy) pair, i.e. three
 // windows of the same pixel row shifted by one pixel.  Only the middle one is loaded; the other
 // two are put together from it and the neighbouring lane's pixel (DPP), zero at an image border.
-template <int KC, int RS, bool WLDS, bool TAPS = false>
+template <int KC, int RS, bool TAPS = false>
 __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
-  static_assert(!TAPS || (!WLDS && KC % 12 == 0), "tap-grouped stages are multiples of 12 steps");
+  static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
   constexpr int NQ = (NO + 3) / 4;       // weight registers per stage come as NQ 16-byte loads
@@ -79,10 +77,6 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char wlds[];
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-#ifdef RBGP_EXPERIMENT
-  unsigned long long *tr = p.trace + ((size_t(blockIdx.y) * gridDim.z + blockIdx.z) * gridDim.x + blockIdx.x) * 32 + wid * 8;
-  if (lane == 0) { tr[0] = __builtin_amdgcn_s_memrealtime(); tr[5] = __builtin_readcyclecounter(); }
-#endif
 
   // A workgroup is one (cluster, G_i vertex) pair on four neighbouring column tiles.  Same
   // columns of I -> same XCD (one L2): workgroups are dealt round-robin to the 8 XCDs.
@@ -171,16 +165,12 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
   const int rows_left = p.last_row - tbu < p.src_rows ? p.last_row - tbu : p.src_rows;
   const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
-  // per-lane byte address (LDS) or offset (global) of each member's weights: a tile row that
-  // lacks the tile reads the zero fragment (LDS) or an offset past the weight buffer (global)
+  // per-lane byte offset of each member's weights: a tile row that lacks the tile reads at an
+  // offset past the weight buffer (zeros)
   int aoff[MG];
 #pragma unroll
-  for (int mm = 0; mm < MG; ++mm) {
-    if constexpr (WLDS)
-      aoff[mm] = (tf[mm] >= 0 ? mm * p.fpm + tf[mm] : MG * p.fpm) * FB;
-    else
-      aoff[mm] = (tf[mm] >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + tf[mm]) * p.a3 + u3) * FB : kOob;
-  }
+  for (int mm = 0; mm < MG; ++mm)
+    aoff[mm] = (tf[mm] >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + tf[mm]) * p.a3 + u3) * FB : kOob;
   auto b_rsrc = [&](int s, int *sofs) {
     const int tl = table_lane(s);
     const uint64_t base = uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_lo, tl))) |
@@ -192,64 +182,10 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
 
   f32x4 B0[NO], B1[NO];
   f32x4 A0[NQ], A1[NQ];
-  if constexpr (WLDS) {
-    // Copy the fragments of all members (fpm each) to LDS through registers.  One load
-    // instruction moves, for every member of the group, one 16-byte-per-lane row of its
-    // fragment fi, with the lane mapping of the in-loop weight loads (scalar addressing);
-    // wave w takes fragments w, w + 4, ..., two per pass.  The first stage of I is requested
-    // right behind the first pass, so that its HBM latency overlaps the copy.
-#ifdef RBGP_EXPERIMENT
-    if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
-#endif
-    int f0 = wid;
-    do {   // (a pass past the last fragment loads zeros and stores nothing)
-      f32x4 t[2][NQ];
-      int dst[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int fi = f0 + 4 * h;
-        int src = 0;
-#pragma unroll
-        for (int mm = 0; mm < MG; ++mm) {
-          const int sv = (fi < p.fpm && mem[mm] >= 0) ? ((mem[mm] * p.fpm + fi) * p.a3 + u3) * FB : kOob;
-          src = mi == mm ? sv : src;
-        }
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) t[h][q] = load_x4(rw, src + alane, q * QB);
-        dst[h] = (mi * p.fpm + fi) * FB + alane;
-      }
-      if (f0 == wid) {
-        int sofs;
-        const __amdgpu_buffer_rsrc_t r0 = b_rsrc(0, &sofs);
-#pragma unroll
-        for (int o = 0; o < NO; ++o) B0[o] = load_x4(r0, off[o], sofs);
-      }
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        if (f0 + 4 * h < p.fpm) {
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) *reinterpret_cast<f32x4 *>(wlds + dst[h] + q * QB) = t[h][q];
-        }
-    } while ((f0 += 8) < p.fpm);
-    // the all-zero fragment that stands in for tiles a member lacks
-    if (wid == 3) {
-#pragma unroll
-      for (int q = 0; q < NQ; ++q)
-        *reinterpret_cast<f32x4 *>(wlds + MG * p.fpm * FB + q * QB + (lane & (QB / 16 - 1)) * 16) =
-            f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-#ifdef RBGP_EXPERIMENT
-    if (lane == 0) tr[7] = __builtin_amdgcn_s_memrealtime();
-#endif
-    __syncthreads();
-  }
   if (!valid && lgS == 0) return;   // (with a split stage list every wave reaches the barrier below)
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[6] = __builtin_amdgcn_s_memrealtime();
-#endif
   // Drain every outstanding load count here: a wait for the table loads inside the loop
   // would run on every iteration and drain the prefetched stages with it.
-  if constexpr (!WLDS) __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_s_waitcnt(0);
 
   f32x16 acc[4];
 #pragma unroll
@@ -269,12 +205,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     }
     return addr + alane;
   };
-  auto a_load = [&](int addr, int q) {
-    if constexpr (WLDS)
-      return *reinterpret_cast<const f32x4 *>(wlds + addr + q * QB);
-    else
-      return load_x4(rw, addr, q * QB);
-  };
+  auto a_load = [&](int addr, int q) { return load_x4(rw, addr, q * QB); };
 
   // The four B operands of slot o (one per column offset w).  TAPS: from the pair's middle window
   // c (pixels x .. x+3): dx = -1 is {left neighbour, c0, c1, c2}, dx = +1 is {c1, c2, c3, right
@@ -371,13 +302,7 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   };
 
   // Two register sets alternate; stages past the end read zeros (sentinel table lanes).
-  if constexpr (WLDS) {
-    const int av0 = a_addr(0);
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) A0[q] = a_load(av0, q);
-  } else {
-    fill(0, B0, A0);
-  }
+  fill(0, B0, A0);
   first_stage(B0, A0, B1, A1);
   if (cnt > 1) {   // the loop is reachable only through stage 1, which keeps its wait counts exact
     stage(1, B1, A1, std::true_type{});
@@ -389,9 +314,6 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
     if (s < cnt) stage(s, B0, A0, std::false_type{});
   }
   __builtin_amdgcn_s_waitcnt(0);
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) { tr[3] = __builtin_amdgcn_s_memrealtime(); tr[2] = __builtin_readcyclecounter(); }
-#endif
 
   // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Unit t of the sum holds
   // weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
@@ -449,24 +371,21 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
       }
     }
   }
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) { tr[4] = __builtin_amdgcn_s_memrealtime(); }
-#endif
 }
 
 typedef rbgp_reg_fn reg_fn;
 template <int KC, int RS>
 constexpr reg_fn taps_kernel() {   // the tap-grouped variant exists for stages of a multiple of 12 steps
   if constexpr (KC % 12 == 0)
-    return spmm_reg<KC, RS, false, true>;
+    return spmm_reg<KC, RS, true>;
   else
     return nullptr;
 }
 struct RegEntry {
   int KC, RS;
-  reg_fn lds_fn, global_fn, taps_fn;
+  reg_fn global_fn, taps_fn;
 };
-#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS, true>, spmm_reg<KC, RS, false>, taps_kernel<KC, RS>()}
+#define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS>, taps_kernel<KC, RS>()}
 const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
                               RBGP_R(8, 4),  RBGP_R(18, 4),  RBGP_R(36, 4),  RBGP_R(72, 4),
                               RBGP_R(8, 8),  RBGP_R(18, 8),  RBGP_R(36, 8),  RBGP_R(72, 8),
@@ -485,11 +404,13 @@ struct RegTables {  // device tables of the clustering
 
 struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
+  std::vector<int32_t> rowtab_host;   //   and its host copy (travels in the kernel arguments of the pairing kernel)
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
   int32_t *rowtab_conv[2] = {nullptr, nullptr};   // fused convolution, fp32 / bf16: byte offsets for the geometry below
   int32_t *colbase[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};   // [dtype][wide tile]: pixel offsets of the column groups
   int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};  // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
+  RegTables tab_dual;              // fp32: lo/hi pairing (tables of rbgp_reg_dual; ncl = quads)
   RegTables tab_bf16[3];           // bf16: clusters of 1, 2, 4 groups
   bool g2_shared = false;          // the clusters of two groups have (nearly) half the stages in total: their tile rows share their tiles
   int g2_stages = -1, g2_ncl = 0;  // longest stage list and number of the clusters of two groups (-2: too long,
@@ -510,6 +431,22 @@ void free_tables(RegTables *t) {
   *t = RegTables();
 }
 
+// Upload three tables; the state is touched only when all three are on the device.
+int upload_tables(int ncl, const std::vector<int32_t> &stages, const std::vector<int32_t> &counts,
+                  const std::vector<int32_t> &members, RegTables *t) {
+  RegTables fresh;
+  fresh.ncl = ncl;
+  int rc = upload(stages, &fresh.stages);
+  if (!rc) rc = upload(counts, &fresh.counts);
+  if (!rc) rc = upload(members, &fresh.members);
+  if (rc) {
+    free_tables(&fresh);
+    return rc;
+  }
+  *t = fresh;
+  return RBGP_OK;
+}
+
 // Upload the clustering of the tile rows (clusters of U) and its stage tables.
 int build_tables(const rbgp_mask *m, int U, RegTables *t) {
   rbgp_reg_clusters fresh;
@@ -519,12 +456,7 @@ int build_tables(const rbgp_mask *m, int U, RegTables *t) {
     cl = &fresh;
   }
   if (cl->max_stages > 60) return RBGP_EUNSUPPORTED;   // one stage per lane plus sentinels
-  t->ncl = cl->ncl;
-  int rc = upload(cl->stages, &t->stages);
-  if (rc) return rc;
-  rc = upload(cl->counts, &t->counts);
-  if (rc) return rc;
-  return upload(cl->members, &t->members);
+  return upload_tables(cl->ncl, cl->stages, cl->counts, cl->members, t);
 }
 
 }  // namespace
@@ -548,6 +480,7 @@ void rbgp_reg_release(void *state) {
     for (int32_t *t : pair)
       if (t) (void)hipFree(t);
   free_tables(&st->tab);
+  free_tables(&st->tab_dual);
   for (RegTables &t : st->tab_bf16) free_tables(&t);
   delete st;
 }
@@ -632,6 +565,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     }
     int rc = upload(rt, rowtab);
     if (rc) return rc;
+    if (!conv && !bf16) st->rowtab_host = rt;
   }
   const int64_t ntiles = (N + CW - 1) / CW;
   // bf16: 16-row groups per wave (G) and waves per column tile (S).  More groups mean fewer
@@ -680,24 +614,36 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       while (lgS < 2 && ((ncl * m->a[2] * ntiles) << lgS) < 1024) ++lgS;
     }
   }
-  RegTables *tab = bf16 ? &st->tab_bf16[G == 4 ? 2 : G == 2 ? 1 : 0] : &st->tab;
-  if (!tab->stages) {
-    int rc = build_tables(m, G * pl.MG, tab);
-    if (rc) return rc;
-  }
   const RegEntry *e = find_reg(pl.KC, pl.RS);
   if (!e) return RBGP_EUNSUPPORTED;
+  // fused convolution on a tap-grouped layout whose image rows tile the 64 columns of a wave:
+  // the variant that loads one of the three horizontal taps and builds the others.  Measured on
+  // the VGG19 layers: 5-15 % faster for images 8 to 32 pixels wide, slower for 4-pixel-wide ones
+  // (every lane is a whole image row there: nothing to share, only the extra instructions).
+  const bool taps = conv && !bf16 && rbgp_reg_tap_grouped(m) && e->taps_fn && conv->width >= 8 && 64 % conv->width == 0;
+  // fp32, two tile rows per MFMA group: lo/hi pairing of the tile rows (rbgp_mfma_reg_dual.hip) where its
+  // busiest SIMD walks fewer stages than the longest cluster of the fixed pairs, and there are enough
+  // (tile row, G_i vertex, column tile) triples to fill every SIMD without splitting stage lists.
+  bool dual = false;
+  {
+    const int tp = tune[RBGP_TUNE_ROW_PAIRING];
+    if (tp < 0 || tp > 2) return RBGP_EUNSUPPORTED;
+    const bool can = !bf16 && !taps && m->reg_dual.ok && rbgp_reg_dual_kernel(pl.KC) && !tune[RBGP_TUNE_K_SPLIT];
+    if (tp == 2 && !can) return RBGP_EUNSUPPORTED;
+    dual = can && (tp == 2 || (tp == 0 && lgS == 0 && m->reg_dual.max_stages < m->reg_clusters.max_stages));
+  }
+  if (dual) lgS = 1;   // (two column tiles per workgroup, as with a stage list split in two)
+  RegTables *tab = dual ? &st->tab_dual : bf16 ? &st->tab_bf16[G == 4 ? 2 : G == 2 ? 1 : 0] : &st->tab;
+  if (!tab->stages) {
+    int rc = dual ? upload_tables(m->reg_dual.nq, m->reg_dual.stages, m->reg_dual.counts, m->reg_dual.members, tab)
+                  : build_tables(m, G * pl.MG, tab);
+    if (rc) return rc;
+  }
   const int fpm = m->d[0] * pl.NSTG;
-  const int fb = (bf16 ? rbgp_bf16_blocks32(pl.KC) + (rbgp_bf16_tail16(pl.KC) ? 1 : 0) : pl.NQ) * 4 * pl.RS * 16;
-  size_t lds = ((size_t(pl.MG * fpm + 1) * fb + 1023) / 1024) * 1024;
-  // Weights stream from global memory by default: measured on the VGG19 conv5 shape, filling
-  // LDS first (direct global->LDS loads run at a few bytes per clock per CU) costs more at the
-  // start of the kernel than the cheaper stages give back.  Tuning knob value 2 selects the
-  // LDS variant whenever the weights fit.
-  // (the LDS-weights variant is built without the split: its LDS holds the weights)
-  const bool wlds = !bf16 && lgS == 0 && tune[RBGP_TUNE_WEIGHTS_IN_LDS] == 2 && lds <= 160 * 1024;
-  // partial sums of the split: per wave the (S - 1) / S of its 4G units it does not own
-  if (!wlds) lds = size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (bf16 ? NC / 4 : 1) * 1024;
+  // LDS: partial sums of the split -- per wave the (S - 1) / S of its 4G units it does not own; lo/hi pairing:
+  // the four units of half of the eight waves
+  size_t lds = dual ? size_t(16) * 1024
+                    : size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (bf16 ? NC / 4 : 1) * 1024;
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
@@ -755,40 +701,43 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
   rp.lgX = lgX;
   rp.ncl = tab->ncl;
-  // fused convolution on a tap-grouped layout whose image rows tile the 64 columns of a wave:
-  // the variant that loads one of the three horizontal taps and builds the others.  Measured on
-  // the VGG19 layers: 5-15 % faster for images 8 to 32 pixels wide, slower for 4-pixel-wide ones
-  // (every lane is a whole image row there: nothing to share, only the extra instructions).
-  const bool taps = conv && !bf16 && !wlds && rbgp_reg_tap_grouped(m) && e->taps_fn && conv->width >= 8 &&
-                    64 % conv->width == 0;
-  reg_fn fn = bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : wlds ? e->lds_fn : e->global_fn;
-  if (!fn) return RBGP_EUNSUPPORTED;
-  if (lds > 64 * 1024)   // (cheap host-side call; repeated because fn varies with the knobs)
+  reg_fn fn = dual ? nullptr : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : e->global_fn;
+  if (!fn && !dual) return RBGP_EUNSUPPORTED;
+  if (lds > 64 * 1024 && fn)   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));
-#ifdef RBGP_EXPERIMENT
-  static unsigned long long *trace_buf = nullptr;
-  static int launches = 0;
-  const size_t trace_n = size_t(8 * xgroups) * qgroups * m->a[2] * 4 * 8;
-  if (!trace_buf) RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&trace_buf), (size_t(1) << 24)));
-  rp.trace = trace_buf;
-  ++launches;
-  const bool dump = getenv("RBGP_TRACE") && launches == (getenv("RBGP_TRACE_AT") ? atoi(getenv("RBGP_TRACE_AT")) : 100);
-  if (dump) RBGP_HIP(hipMemset(trace_buf, 0, trace_n * 8));
-#endif
-  hipLaunchKernelGGL(fn, dim3(unsigned(8 * xgroups), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
-#ifdef RBGP_EXPERIMENT
-  if (dump) {
-    RBGP_HIP(hipDeviceSynchronize());
-    std::vector<unsigned long long> h(trace_n);
-    RBGP_HIP(hipMemcpy(h.data(), trace_buf, trace_n * 8, hipMemcpyDeviceToHost));
-    FILE *f = fopen(getenv("RBGP_TRACE"), "w");
-    for (size_t i = 0; i < trace_n; i += 8)
-      fprintf(f, "%zu %llu %llu %llu %llu %llu %llu %llu %llu\n", i / 8, h[i], h[i + 1], h[i + 2], h[i + 3], h[i + 4],
-              h[i + 5], h[i + 6], h[i + 7]);
-    fclose(f);
+  if (dual) {
+    // one-dimensional grid: XCD = id & 7 takes a block of the (G_i vertex, pair of column tiles) units
+    const int64_t units = int64_t(m->a[2]) * nquads, per_xcd = (units + 7) / 8;
+    if (per_xcd * tab->ncl * 8 > 0x7fffffff || per_xcd > 0x7fffffff) return RBGP_EUNSUPPORTED;
+    rp.lgX = int(per_xcd);
+    DualParams dq;
+    dq.r = rp;
+    dq.in_args = 0;
+    dq.cmax = 64;
+    dq.o_stages = dq.o_counts = dq.o_members = 0;
+    // the tables travel in the kernel arguments when they fit
+    const rbgp_reg_dual &du = m->reg_dual;
+    const int n_row = m->a[2] * pl.NO * 4, cmax = std::max(du.max_wave, 1);
+    const int n_stages = du.nq * 4 * 3 * cmax, n_counts = du.nq * 4, n_members = du.nq * 4;
+    if (!conv && n_row + n_stages + n_counts + n_members <= kDualTableWords) {
+      dq.in_args = 1;
+      dq.cmax = cmax;
+      dq.o_stages = n_row; dq.o_counts = n_row + n_stages; dq.o_members = n_row + n_stages + n_counts;
+      const std::vector<int32_t> &rt = st->rowtab_host;
+      std::copy(rt.begin(), rt.begin() + n_row, dq.tab);
+      for (int wv = 0; wv < du.nq * 4; ++wv)
+        for (int k = 0; k < 3; ++k)
+          std::copy(&du.stages[(size_t(wv) * 3 + k) * 64], &du.stages[(size_t(wv) * 3 + k) * 64] + cmax,
+                    dq.tab + dq.o_stages + (wv * 3 + k) * cmax);
+      std::copy(du.counts.begin(), du.counts.end(), dq.tab + dq.o_counts);
+      std::copy(du.members.begin(), du.members.end(), dq.tab + dq.o_members);
+    }
+    rbgp_dual_fn dfn = rbgp_reg_dual_kernel(pl.KC);
+    hipLaunchKernelGGL(dfn, dim3(unsigned(8 * per_xcd * tab->ncl)), dim3(512), lds, static_cast<hipStream_t>(stream), dq);
+  } else {
+    hipLaunchKernelGGL(fn, dim3(unsigned(8 * xgroups), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
   }
-#endif
   RBGP_HIP(hipGetLastError());
   return RBGP_OK;
 }

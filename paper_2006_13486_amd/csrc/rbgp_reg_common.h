@@ -81,9 +81,30 @@ __device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int
 
 }  // namespace rbgp_reg
 
+namespace rbgp_reg {
+// Parameter block of the lo/hi pairing kernel (rbgp_mfma_reg_dual.hip): RegParams plus, when they fit
+// (the kernel arguments hold 4 KB), the kernel's index tables themselves.  A wave then has everything
+// it needs to address its first loads of I after ONE memory round trip (the kernel arguments)
+// instead of two (arguments, then tables through the pointers in them).
+constexpr int kDualTableWords = 920;
+struct DualParams {
+  RegParams r;
+  int in_args;      // 1: the tables below are valid; 0: read them through r.rowtab / r.stages / r.counts / r.members
+  int cmax;         // stages stored per wave and table row (>= the longest stage list; 64 for the tables in memory)
+  int o_stages;     // word offsets into tab[] of: stages [quad][x][y][3][cmax]
+  int o_counts;     //   counts [quad][x][y]
+  int o_members;    //   members [quad][4]
+  int32_t tab[kDualTableWords];   // row table [a_i][NO * 4] first
+};
+}  // namespace rbgp_reg
+
 typedef void (*rbgp_reg_fn)(rbgp_reg::RegParams);
+typedef void (*rbgp_dual_fn)(rbgp_reg::DualParams);
 // bf16 kernel for KC contraction steps per stage, RS weight rows per tile row, G 16-row
 // groups per wave and CW (64 or 128) columns per wave; nullptr when that combination is not built.
 rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G, int CW);
+// fp32 kernel with lo/hi pairing of the tile rows (8-row halves; tables of rbgp_reg_dual in the
+// stages / counts / members fields); nullptr when KC is not built.
+rbgp_dual_fn rbgp_reg_dual_kernel(int KC);
 
 #endif

@@ -33,10 +33,43 @@ def test_config_tile_shapes(w, tune):
     gh.check_parity(w, N=1536 if w.N > 4096 else w.N, kernel=MFMA, tune=tune)
 
 
-@pytest.mark.parametrize("cluster", [0, 1, 2])
+@pytest.mark.parametrize("pairing", [0, 1, 2])
 @pytest.mark.parametrize("w", [wl.TINY, wl.VGG19_CONV5, wl.VGG19_CONV3_BF16, wl.WRN_G1], ids=lambda w: w.name)
-def test_config_register_family_cluster_sizes(w, cluster):
-    gh.check_parity(w, N=1000 if w.N > 4096 else w.N, kernel=REG, tune=(0, 0, 0, cluster), expect_kernel=REG)
+def test_config_register_family_row_pairing(w, pairing):
+    """Fixed pairs of tile rows (1) and tile-by-tile pairing (2; fp32 masks with two tile rows of 8
+    per MFMA group only: the conv5 shape, the others must refuse it), at a ragged N."""
+    N = 1000 if w.N > 4096 else w.N
+    if pairing == 2 and w is not wl.VGG19_CONV5:
+        with pytest.raises(rb.RbgpError) as e:
+            gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, pairing), expect_kernel=REG)
+        assert e.value.code == rb.EUNSUPPORTED
+        return
+    gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, pairing), expect_kernel=REG)
+
+
+# masks with two tile rows of 8 rows per MFMA group, for the tile-by-tile pairing of the fp32 register kernels
+PAIRING_SHAPES = [
+    ((4, 4, 4, 2), (4, 4, 8, 9), (2, 4, 2, 9)),     # 4 tile rows: one quad
+    ((8, 2, 2, 3), (8, 2, 4, 3), (4, 2, 2, 3)),     # R = 6 (two idle rows per half), stages of 12 steps padded to 18
+    ((6, 4, 2, 2), (4, 1, 4, 9), (2, 1, 2, 9)),     # 6 tile rows: a quad with two rows missing
+    ((2, 8, 2, 1), (4, 2, 2, 4), (2, 2, 1, 4)),     # 2 tile rows: a quad with one L row and one H row
+    ((16, 1, 2, 8), (16, 2, 4, 2), (4, 2, 2, 2)),   # 16 tile rows of degree 4 (two lifts): tiles without a partner
+    ((4, 21, 2, 1), (4, 1, 2, 9), (2, 1, 1, 9)),    # |G_r.U| = 21: three tile rows of 7 per row of G_o
+]
+
+
+@pytest.mark.parametrize("shape", range(len(PAIRING_SHAPES)))
+def test_fp32_register_family_tile_by_tile_pairing(shape):
+    """The pairing kernel against the oracle (and the fixed-pair kernel on the same inputs) on small masks
+    that exercise incomplete quads, idle rows, padded stages and partnerless tiles, at two ragged N with
+    an odd leading dimension; the host tables pass the library's own consistency check."""
+    a, c, d = PAIRING_SHAPES[shape]
+    for N in (200, 129):
+        w = wl.Workload(f"pairing_{shape}", a, c, d, N, wl.F32, 100 + shape, 200 + shape, 300 + shape, 1.0)
+        rb.rbgp_mask_check_tables(gh.make_mask(w))
+        assert rb.rbgp_mask_reg_plan(gh.make_mask(w))[7] > 0
+        gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 2), ld_pad=3, expect_kernel=REG)
+        gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 1), ld_pad=3, expect_kernel=REG)
 
 
 @pytest.mark.parametrize("cw", [64, 128])
@@ -91,8 +124,8 @@ def test_ragged_columns(N, ld_pad, dtype):
     for tune in [(1, 64, 0), (2, 128, 0)]:
         gh.check_parity(w, N=N, kernel=MFMA, tune=tune, ld_pad=pad)
     gh.check_parity(w, N=N, kernel=GEN, ld_pad=ld_pad)
-    for cluster in (1, 2):
-        gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, cluster), ld_pad=ld_pad if dtype == wl.F32 else pad,
+    for pairing in (1, 2):
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, pairing if dtype == wl.F32 else 1), ld_pad=ld_pad if dtype == wl.F32 else pad,
                         expect_kernel=REG)
     if dtype == wl.BF16:                              # 128-column wave tiles, with and without a stage split
         gh.check_parity(w, N=N, kernel=REG, tune=(0, 128), ld_pad=pad, expect_kernel=REG)
