@@ -186,6 +186,50 @@ def run_sweep(args, torch, dev):
                       "steps": args.sweep_steps, "data": "synthetic", "cases": cases}))
 
 
+def sweep_sums(torch, dev, steps=100, warmup=50):
+    """All 16 VGG19 conv layers at the four densities, fp32 and bf16, through rbgp_spmm with library defaults:
+    per (dtype, density) the sum of the per-layer launch times.  Inputs are generated on the device (seeded,
+    ReLU(N(0,1)) as everywhere); the outputs of these cells are checked in the GPU tests, not here."""
+    sums, stream = {}, torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device=dev)
+    for layer in range(len(wl.VGG19_LAYERS)):
+        w0 = wl.vgg19_sweep_workload(layer, 1, wl.F32)
+        gen.manual_seed(w0.i_seed)
+        I32 = torch.randn((w0.K, w0.N), generator=gen, device=dev).clamp_(min=0)
+        I16 = I32.to(torch.bfloat16).view(torch.int16)
+        for dt, I0 in ((wl.F32, I32), (wl.BF16, I16)):
+            nsets = max(2, min(16, -(-512 * 2**20 // (I0.numel() * I0.element_size() + w0.M * w0.N * 4))))
+            Is = [I0] + [I0.clone() for _ in range(nsets - 1)]
+            Os = [torch.empty((w0.M, w0.N), dtype=torch.float32, device=dev) for _ in range(nsets)]
+            for d in (1, 2, 3, 4):
+                w = wl.vgg19_sweep_workload(layer, d, dt)
+                key = f"{'bf16' if dt == wl.BF16 else 'f32'}_d{1 << d}"
+                try:
+                    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+                    vals = wl.kept_weights(w)
+                    vals = wl.to_bf16_bits(vals) if dt == wl.BF16 else vals
+                    packed = torch.zeros(max(rb.rbgp_packed_bytes(mask, w.dtype), 16), dtype=torch.uint8, device=dev)
+                    rb.rbgp_pack(mask, w.dtype, np.ascontiguousarray(vals), packed.data_ptr(), stream)
+                    for i in range(warmup):
+                        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[i % nsets].data_ptr(), w.N,
+                                     Os[i % nsets].data_ptr(), w.N, stream)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(steps):
+                        rb.rbgp_spmm(mask, w.dtype, w.M, w.K, w.N, packed.data_ptr(), Is[i % nsets].data_ptr(), w.N,
+                                     Os[i % nsets].data_ptr(), w.N, stream)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    sums[key] = sums.get(key, 0.0) + e0.elapsed_time(e1) / steps * 1e3
+                except rb.RbgpError as e:
+                    sums[key + "_errors"] = sums.get(key + "_errors", 0) + 1
+            del Is, Os
+        del I32, I16
+        torch.cuda.empty_cache()
+    return {"unit": "us, sum over the 16 VGG19 conv layers of one rbgp_spmm launch each (layer 0 dense)",
+            "steps_per_layer": steps, "sum_us": {k: round(v, 1) for k, v in sorted(sums.items())}}
+
+
 def fused_conv_line(w, mask, packed, vals_f32, torch, dev, stream, check, steps=2000, warmup=1000):
     """The same layer through rbgp_conv3x3 (lowering folded into the loads; the K x N input is never
     stored): reported beside the headline number, which stays the product with I resident in HBM."""
@@ -393,14 +437,17 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=1000,
-                    help="untimed steps; the shader clock needs some hundred launches to settle")
+    ap.add_argument("--warmup", type=int, default=1000, help="untimed steps before the timed ones")
+    ap.add_argument("--settle", type=int, default=1000,
+                    help="untimed set-up launches of the same call before the warm-up steps (clock settling; 0: none)")
     ap.add_argument("--workload", default="conv5", choices=sorted(WORKLOADS))
     ap.add_argument("--sets", type=int, default=0, help="distinct (I,O) buffer sets to rotate over (0 = auto)")
     ap.add_argument("--tune", default="", help="values of the RBGP_TUNE_* knobs in their order in include/rbgp.h (0 = default): cols_per_lane,"
-                         "cols_per_workgroup,groups_per_workgroup,weights_in_lds,row_groups,k_split")
+                         "cols_per_workgroup,groups_per_workgroup,row_pairing,row_groups,k_split")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep-sums", action="store_true",
+                    help="leave the summed VGG19 layer times (16 layers x 4 densities x 2 dtypes) out of the line")
     ap.add_argument("--ld-pad", type=int, default=0,
                     help="extra elements in the leading dimension of I and O (rbgp_spmm only): a row stride that is "
                          "not a multiple of 4 KiB spreads the rows of a stage over more memory channels")
@@ -517,6 +564,11 @@ def main():
             rb.rbgp_spmm(mask, call_dtype, w.M, w.K, w.N, packed.data_ptr(), Is[j].data_ptr(), ldO,
                          Os[j].data_ptr(), ldO, stream)
 
+    # Set-up, untimed and not counted as warm-up steps: the same call, launched until the shader clock has
+    # settled (a GPU that comes out of idle runs its first few hundred launches some 5 % slower; with
+    # `--steps 20 --warmup 5` the timed region would otherwise measure the clock ramp, not the kernel).
+    for i in range(args.settle):
+        step(i)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -530,6 +582,15 @@ def main():
     wall = time.perf_counter() - t0
     kern_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
+    # the same measurement over a long run (what the other objects of the line are timed with)
+    settled_steps = max(args.steps, 2000)
+    ev2, ev3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev2.record()
+    for i in range(settled_steps):
+        step(i)
+    ev3.record()
+    torch.cuda.synchronize()
+    settled_ms = ev2.elapsed_time(ev3) / settled_steps
 
     value = w.flops / (ms_per_step * 1e-3) / 1e12
     bound = BOUND[args.workload]
@@ -549,6 +610,10 @@ def main():
     roof["kernel_ms"] = kern_ms
     roof["algorithmic_bytes"] = algorithmic_bytes
     roof["algorithmic_flops"] = w.flops
+    roof["settled_kernel_ms"] = settled_ms
+    roof["settled_steps"] = settled_steps
+    roof["settled_frac"] = (w.flops / (settled_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS if bound == "mfma"
+                            else algorithmic_bytes / (settled_ms * 1e-3) / 1e9 / PEAK_HBM_GBS)
 
     out = {"metric": "effective TFLOP/s (2*nnz*N) RBGP4 SpMM", "value": value, "unit": "TFLOP/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -557,7 +622,8 @@ def main():
            "config": {"workload": w.name, "output": "bf16" if args.out_bf16 else "f32", "M": w.M, "K": w.K, "N": w.N, "density": w.density,
                       "factors_rows": list(w.rows), "factors_cols": list(w.cols), "factors_row_deg": list(w.row_deg),
                       "kernel": rb.rbgp_mask_kernel(mask, w.dtype), "tune": args.tune or "default",
-                      "buffer_sets": nsets, "ld_pad": 0 if args.fused_conv else args.ld_pad,
+                      "buffer_sets": nsets, "settle_launches": args.settle, "ld_pad": 0 if args.fused_conv else args.ld_pad,
+                      "reg_plan": rb.rbgp_mask_reg_plan(mask),
                       "entry_point": "rbgp_conv3x3" if args.fused_conv else "rbgp_spmm"},
            "roofline": roof}
     if not args.no_cpu_baseline:
@@ -572,6 +638,10 @@ def main():
     if not args.fused_conv and not args.forward_only and args.workload == "conv5":
         out["backward"] = backward_objects(w, mask, vals_lib, vals_f32, I_lib, I_f32, torch, dev, stream,
                                            check=not args.no_cpu_baseline)
+    if not args.fused_conv and not args.forward_only and args.workload == "conv5" and not args.no_sweep_sums:
+        del Is, Os
+        torch.cuda.empty_cache()
+        out["vgg19_sweep"] = sweep_sums(torch, dev)
     print(json.dumps(out))
 
 

@@ -15,9 +15,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=de
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    """Compile every source and link librbgp.so (always recompiles).
-    extra: more hipcc flags, e.g. ["-DRBGP_EXPERIMENT"] for the instrumented build that records
-    per-wave time stamps (RBGP_TRACE=<file> RBGP_TRACE_AT=<launch number> at run time)."""
+    """Compile every source and link librbgp.so (always recompiles).  extra: more hipcc flags."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
@@ -40,18 +38,5 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     return LIB
 
 
-def build_probe() -> str:
-    """Compile the stand-alone MFMA probe (csrc/mfma_probe.hip) to paper_2006_13486_amd/mfma_probe."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    exe = os.path.join(_HERE, "mfma_probe")
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-result",
-                           "-o", exe, os.path.join(CSRC, "mfma_probe.hip")])
-    return exe
-
-
 if __name__ == "__main__":
-    if "probe" in sys.argv:
-        print(build_probe())
-    else:
-        print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv))

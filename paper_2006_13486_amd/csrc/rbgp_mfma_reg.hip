@@ -404,13 +404,14 @@ struct RegTables {  // device tables of the clustering
 
 struct RegState {
   int32_t *rowtab = nullptr;       // fp32 kernels: [a_i][NO*4]
-  std::vector<int32_t> rowtab_host;   //   and its host copy (travels in the kernel arguments of the pairing kernel)
+  std::vector<int32_t> rowtab_host, rowtab_conv_host;   //   host copies, plain and fused convolution (they travel in the
+                                                        //   kernel arguments of the pairing kernel)
   int32_t *rowtab_bf16 = nullptr;  // bf16 kernels: [a_i][NKB*16]
   int32_t *rowtab_conv[2] = {nullptr, nullptr};   // fused convolution, fp32 / bf16: byte offsets for the geometry below
   int32_t *colbase[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};   // [dtype][wide tile]: pixel offsets of the column groups
   int64_t conv_key[2][3] = {{0, 0, 0}, {0, 0, 0}};  // images, height, width of rowtab_conv
   RegTables tab;                   // fp32: clusters of one 16-row group
-  RegTables tab_dual;              // fp32: lo/hi pairing (tables of rbgp_reg_dual; ncl = quads)
+  int32_t *dual_tab[2] = {nullptr, nullptr};   // fp32 lo/hi pairing: the kernel's one table buffer, plain / fused convolution
   RegTables tab_bf16[3];           // bf16: clusters of 1, 2, 4 groups
   bool g2_shared = false;          // the clusters of two groups have (nearly) half the stages in total: their tile rows share their tiles
   int g2_stages = -1, g2_ncl = 0;  // longest stage list and number of the clusters of two groups (-2: too long,
@@ -480,7 +481,8 @@ void rbgp_reg_release(void *state) {
     for (int32_t *t : pair)
       if (t) (void)hipFree(t);
   free_tables(&st->tab);
-  free_tables(&st->tab_dual);
+  for (int32_t *t : st->dual_tab)
+    if (t) (void)hipFree(t);
   for (RegTables &t : st->tab_bf16) free_tables(&t);
   delete st;
 }
@@ -541,6 +543,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (conv && *rowtab && (ckey[0] != conv->images || ckey[1] != conv->height || ckey[2] != conv->width)) {
     (void)hipFree(*rowtab);   // (waits for launches that still read the old table)
     *rowtab = nullptr;
+    if (!bf16 && st->dual_tab[1]) {
+      (void)hipFree(st->dual_tab[1]);
+      st->dual_tab[1] = nullptr;
+    }
     for (int32_t *&t : st->colbase[bf16]) {
       if (t) (void)hipFree(t);
       t = nullptr;
@@ -565,7 +571,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     }
     int rc = upload(rt, rowtab);
     if (rc) return rc;
-    if (!conv && !bf16) st->rowtab_host = rt;
+    if (!bf16) (conv ? st->rowtab_conv_host : st->rowtab_host) = rt;
   }
   const int64_t ntiles = (N + CW - 1) / CW;
   // bf16: 16-row groups per wave (G) and waves per column tile (S).  More groups mean fewer
@@ -633,12 +639,12 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     dual = can && (tp == 2 || (tp == 0 && lgS == 0 && m->reg_dual.max_stages < m->reg_clusters.max_stages));
   }
   if (dual) lgS = 1;   // (two column tiles per workgroup, as with a stage list split in two)
-  RegTables *tab = dual ? &st->tab_dual : bf16 ? &st->tab_bf16[G == 4 ? 2 : G == 2 ? 1 : 0] : &st->tab;
-  if (!tab->stages) {
-    int rc = dual ? upload_tables(m->reg_dual.nq, m->reg_dual.stages, m->reg_dual.counts, m->reg_dual.members, tab)
-                  : build_tables(m, G * pl.MG, tab);
+  RegTables *tab = bf16 ? &st->tab_bf16[G == 4 ? 2 : G == 2 ? 1 : 0] : &st->tab;
+  if (!dual && !tab->stages) {
+    int rc = build_tables(m, G * pl.MG, tab);
     if (rc) return rc;
   }
+  const int ncl = dual ? m->reg_dual.nq : tab->ncl;
   const int fpm = m->d[0] * pl.NSTG;
   // LDS: partial sums of the split -- per wave the (S - 1) / S of its 4G units it does not own; lo/hi pairing:
   // the four units of half of the eight waves
@@ -651,7 +657,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.O = static_cast<float *>(O);
   rp.obf16 = out_bf16 ? 1 : 0;
   rp.rowtab = *rowtab;
-  rp.stages = tab->stages; rp.counts = tab->counts; rp.members = tab->members;
+  rp.stages = dual ? nullptr : tab->stages; rp.counts = dual ? nullptr : tab->counts; rp.members = dual ? nullptr : tab->members;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
   rp.w_bytes = uint32_t(w_bytes);
   rp.row_bytes = uint32_t(ldI * es);
@@ -697,10 +703,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   int lgX = 3;   // groups of column tiles dealt to the XCDs side by side: the power of two >= nquads, at most 8
   while (lgX > 0 && (int64_t(1) << (lgX - 1)) >= nquads) --lgX;
   const int64_t qgroups = (nquads + (int64_t(1) << lgX) - 1) >> lgX;
-  const int64_t xgroups = (tab->ncl + (8 >> lgX) - 1) / (8 >> lgX);
+  const int64_t xgroups = (ncl + (8 >> lgX) - 1) / (8 >> lgX);
   if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
   rp.lgX = lgX;
-  rp.ncl = tab->ncl;
+  rp.ncl = ncl;
   reg_fn fn = dual ? nullptr : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : e->global_fn;
   if (!fn && !dual) return RBGP_EUNSUPPORTED;
   if (lds > 64 * 1024 && fn)   // (cheap host-side call; repeated because fn varies with the knobs)
@@ -709,32 +715,38 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   if (dual) {
     // one-dimensional grid: XCD = id & 7 takes a block of the (G_i vertex, pair of column tiles) units
     const int64_t units = int64_t(m->a[2]) * nquads, per_xcd = (units + 7) / 8;
-    if (per_xcd * tab->ncl * 8 > 0x7fffffff || per_xcd > 0x7fffffff) return RBGP_EUNSUPPORTED;
+    if (per_xcd * ncl * 8 > 0x7fffffff || per_xcd > 0x7fffffff) return RBGP_EUNSUPPORTED;
     rp.lgX = int(per_xcd);
     DualParams dq;
     dq.r = rp;
-    dq.in_args = 0;
-    dq.cmax = 64;
-    dq.o_stages = dq.o_counts = dq.o_members = 0;
-    // the tables travel in the kernel arguments when they fit
     const rbgp_reg_dual &du = m->reg_dual;
-    const int n_row = m->a[2] * pl.NO * 4, cmax = std::max(du.max_wave, 1);
-    const int n_stages = du.nq * 4 * 3 * cmax, n_counts = du.nq * 4, n_members = du.nq * 4;
-    if (!conv && n_row + n_stages + n_counts + n_members <= kDualTableWords) {
-      dq.in_args = 1;
-      dq.cmax = cmax;
-      dq.o_stages = n_row; dq.o_counts = n_row + n_stages; dq.o_members = n_row + n_stages + n_counts;
-      const std::vector<int32_t> &rt = st->rowtab_host;
-      std::copy(rt.begin(), rt.begin() + n_row, dq.tab);
+    const int NP4 = (pl.NO + 3) / 4 * 4, n_row = m->a[2] * 4 * NP4, cmax = std::max(du.max_wave, 1);
+    dq.rt_stride = NP4;
+    dq.cmax = cmax;
+    dq.o_stages = n_row;
+    dq.o_quads = dq.o_stages + du.nq * 4 * cmax * 4;
+    int32_t **dtab = &st->dual_tab[conv ? 1 : 0];
+    if (!*dtab) {   // (the fused convolution's table goes with its row table when the geometry changes)
+      std::vector<int32_t> h(size_t(dq.o_quads) + size_t(du.nq) * 8, 0);
+      const std::vector<int32_t> &rt = conv ? st->rowtab_conv_host : st->rowtab_host;
+      for (int u = 0; u < m->a[2]; ++u)
+        for (int o = 0; o < pl.NO; ++o)
+          for (int gg = 0; gg < 4; ++gg) h[(size_t(u) * 4 + gg) * NP4 + o] = rt[(size_t(u) * pl.NO + o) * 4 + gg];
       for (int wv = 0; wv < du.nq * 4; ++wv)
-        for (int k = 0; k < 3; ++k)
-          std::copy(&du.stages[(size_t(wv) * 3 + k) * 64], &du.stages[(size_t(wv) * 3 + k) * 64] + cmax,
-                    dq.tab + dq.o_stages + (wv * 3 + k) * cmax);
-      std::copy(du.counts.begin(), du.counts.end(), dq.tab + dq.o_counts);
-      std::copy(du.members.begin(), du.members.end(), dq.tab + dq.o_members);
+        for (int sg = 0; sg < cmax; ++sg)
+          for (int k = 0; k < 3; ++k)
+            h[size_t(dq.o_stages) + (size_t(wv) * cmax + sg) * 4 + k] = du.stages[(size_t(wv) * 3 + k) * 64 + sg];
+      for (int q = 0; q < du.nq; ++q)
+        for (int k = 0; k < 4; ++k) {
+          h[size_t(dq.o_quads) + size_t(q) * 8 + k] = du.members[size_t(q) * 4 + k];
+          h[size_t(dq.o_quads) + size_t(q) * 8 + 4 + k] = du.counts[size_t(q) * 4 + k];
+        }
+      int rc = upload(h, dtab);
+      if (rc) return rc;
     }
+    dq.tab = *dtab;
     rbgp_dual_fn dfn = rbgp_reg_dual_kernel(pl.KC);
-    hipLaunchKernelGGL(dfn, dim3(unsigned(8 * per_xcd * tab->ncl)), dim3(512), lds, static_cast<hipStream_t>(stream), dq);
+    hipLaunchKernelGGL(dfn, dim3(unsigned(8 * per_xcd * ncl)), dim3(512), lds, static_cast<hipStream_t>(stream), dq);
   } else {
     hipLaunchKernelGGL(fn, dim3(unsigned(8 * xgroups), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
   }

@@ -80,10 +80,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   const int lane = threadIdx.x & 63;
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   const int lgS = p.lgS, S = 1 << lgS;
-#ifdef RBGP_EXPERIMENT
-  unsigned long long *tr = p.trace + ((size_t(blockIdx.y) * gridDim.z + blockIdx.z) * gridDim.x + blockIdx.x) * 32 + wid * 8;
-  if (lane == 0) tr[0] = __builtin_amdgcn_s_memrealtime();
-#endif
   const int ks = wid & (S - 1);          // this wave's share of the stage list
   // workgroup -> (XCD, cluster, G_i vertex, 4/S neighbouring column tiles); see the fp32 kernel
   const int xcd = blockIdx.x & 7, u3 = blockIdx.y;
@@ -176,9 +172,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     return addr + alane;
   };
   __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[1] = __builtin_amdgcn_s_memrealtime();
-#endif
 
   f32x4 acc[G][NC];
 #pragma unroll
@@ -268,9 +261,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   u32x4 A0[G][NB], A1[G][NB];
   fill(0, B0, A0);
   fill(1, B1, A1);   // (issued before any MFMA waits: measured faster than interleaving it with stage 0)
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[2] = __builtin_amdgcn_s_memrealtime();
-#endif
   {
     int s = 0;
     for (; s + 1 < cntw; s += 2) {
@@ -280,9 +270,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     if (s < cntw) stage(s, B0, A0, std::false_type{});
   }
   __builtin_amdgcn_s_waitcnt(0);
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[3] = __builtin_amdgcn_s_memrealtime();
-#endif
 
   // Epilogue.  Unit (gi, t) = register t of group gi's NC accumulators: weight row
   // 4*(lane/16) + t of the group, lane j the columns NC*j + w.
@@ -361,9 +348,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
       }
     }
     __syncthreads();
-#ifdef RBGP_EXPERIMENT
-    if (lane == 0) tr[7] = __builtin_amdgcn_s_memrealtime();
-#endif
     const int w0 = wid & ~(S - 1);
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
@@ -385,9 +369,6 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
       }
     }
   }
-#ifdef RBGP_EXPERIMENT
-  if (lane == 0) tr[4] = __builtin_amdgcn_s_memrealtime();
-#endif
 }
 
 struct Entry {

@@ -63,9 +63,6 @@ struct TileParams {
                            //   saves the copy of the table to LDS and its barrier (measured on the VGG19 conv3 shape:
                            //   21.0 us against 21.3 us)
   int32_t inl[kInline];    // the table above, then [row groups] counts
-#ifdef RBGP_EXPERIMENT
-  int ablate;              // timing experiments: 1 skips the LDS writes, 2 the MFMAs, 4 the loads of I
-#endif
   int ntiles, RG;          // column tiles of 64, row groups of 4 tile rows
   // Fused 3x3 convolution: I is the zero-padded activation tensor X[channel][image][H + 2][W + 2] (bf16) and row
   // k = 9 * channel + tap of the lowered input is read from it: a tile column is TK / 9 consecutive channels.
@@ -122,9 +119,6 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   }
   const int inl_base = rg * rec;
   auto table = [&](int i) { return inl ? p.inl[inl_base + i] : __builtin_amdgcn_readfirstlane(tab[i]); };
-#ifdef RBGP_EXPERIMENT
-  if (p.ablate & 32) return;
-#endif
 
   if (wid >= 4) {
     // ---------------------------------------------------------------- producer
@@ -180,9 +174,6 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
           ext = p.x_bytes - first;
         }
         if (!live) ext = 0;
-#ifdef RBGP_EXPERIMENT
-        if (p.ablate & 4) ext = 0;
-#endif
         const __amdgpu_buffer_rsrc_t rb =
             __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, int(ext), kRsrcFlags);
 #pragma unroll
@@ -224,9 +215,6 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
       // iteration s: request stage s + NS into the set stage s came from, move stage s + 1 to LDS
       auto pstep = [&](int s, RawSet<NT> &free_set, RawSet<NT> &cur) {
         issue_loads(s + NS, free_set);
-#ifdef RBGP_EXPERIMENT
-        if (!(p.ablate & 1))
-#endif
         if (s + 1 < cnt) to_lds((s + 1) & 1, cur);
         __syncthreads();
       };
@@ -267,18 +255,12 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
 
   // the weights of the tile row's tile j (zeros without a memory access past its last tile)
   auto issue_weights = [&](int j, u32x4 (&A)[NC]) {
-#ifdef RBGP_EXPERIMENT
-    if (p.ablate & 8) j = ntile;
-#endif
     const int off = (j < ntile ? (u_o * p.d_o + j) * FRAG : kOob) + alane;
 #pragma unroll
     for (int c = 0; c < NC; ++c) A[c] = __builtin_amdgcn_raw_buffer_load_b128(rw, off, c * (2 * TM * 16), 0);
     __builtin_amdgcn_sched_barrier(0);
   };
   auto compute = [&](int s, const u32x4 (&A)[NC]) {
-#ifdef RBGP_EXPERIMENT
-    if (p.ablate & 2) return;
-#endif
     const unsigned char *src = lds + (s & 1) * BUF;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -312,9 +294,6 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   // Epilogue.  32x32 accumulator: register r of lane (n32, h2) is row 8 * (r / 4) + 4 * h2 + r % 4,
   // column n32 of the block.
   if (ntile == 0) return;
-#ifdef RBGP_EXPERIMENT
-  if (p.ablate & 16) return;
-#endif
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int64_t n = n0 + 32 * h + n32;
@@ -451,14 +430,8 @@ int rbgp_tile_launch(const rbgp_mask *m, void **state, bool out_bf16, int64_t N,
   p.a_o = m->a[0]; p.d_o = m->d[0];
   p.TK = pl.TK;
   p.inl_ok = int(st->host_table.size()) <= kInline;
-#ifdef RBGP_EXPERIMENT
-  if (getenv("RBGP_TILE_NOINL")) p.inl_ok = 0;
-#endif
   p.tab_bytes = p.inl_ok ? 0 : ((st->max_stages + 4 * m->d[0]) * 4 + 15) / 16 * 16;
   if (p.inl_ok) std::copy(st->host_table.begin(), st->host_table.end(), p.inl);
-#ifdef RBGP_EXPERIMENT
-  p.ablate = getenv("RBGP_TILE_ABLATE") ? atoi(getenv("RBGP_TILE_ABLATE")) : 0;
-#endif
   const int64_t ntiles = (N + kCW - 1) / kCW;
   p.ntiles = int(ntiles); p.RG = st->RG;
   p.conv = conv ? 1 : 0;

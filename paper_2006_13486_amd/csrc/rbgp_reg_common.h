@@ -66,9 +66,6 @@ struct RegParams {
   int lgS;                 // log2 of the waves that share a column tile (split of the stage list)
   int lgX, ncl;            // eight consecutive workgroups (one per XCD) = 2^lgX groups of column tiles x 8 / 2^lgX clusters;
                            //   number of clusters
-#ifdef RBGP_EXPERIMENT
-  unsigned long long *trace;   // [wave][8] timestamps
-#endif
 };
 
 constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
@@ -82,19 +79,21 @@ __device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int
 }  // namespace rbgp_reg
 
 namespace rbgp_reg {
-// Parameter block of the lo/hi pairing kernel (rbgp_mfma_reg_dual.hip): RegParams plus, when they fit
-// (the kernel arguments hold 4 KB), the kernel's index tables themselves.  A wave then has everything
-// it needs to address its first loads of I after ONE memory round trip (the kernel arguments)
-// instead of two (arguments, then tables through the pointers in them).
-constexpr int kDualTableWords = 920;
+// Parameter block of the lo/hi pairing kernel (rbgp_mfma_reg_dual.hip): RegParams plus one table
+// buffer in device memory laid out for few, wide loads (a wave reads it with 7 load instructions; 2048
+// waves reading the same few KB with 25 narrow loads each is a burst of 50 000 load instructions at the
+// head of every launch).  Measured alternatives for the 1.4 us between wave start and "tables there":
+// tables inside the kernel arguments read by vector loads 1.6 us, by scalar loads 2.7 - 5 us (only the
+// first bytes of the arguments arrive fast, 0.3 us); 16 copies of the buffer on different L2 channels
+// 1.6 - 2.3 us (the one copy is fetched from memory once and then shared; it is not a hot spot).
 struct DualParams {
-  RegParams r;
-  int in_args;      // 1: the tables below are valid; 0: read them through r.rowtab / r.stages / r.counts / r.members
-  int cmax;         // stages stored per wave and table row (>= the longest stage list; 64 for the tables in memory)
-  int o_stages;     // word offsets into tab[] of: stages [quad][x][y][3][cmax]
-  int o_counts;     //   counts [quad][x][y]
-  int o_members;    //   members [quad][4]
-  int32_t tab[kDualTableWords];   // row table [a_i][NO * 4] first
+  RegParams r;          // (rowtab / stages / counts / members are not used)
+  const int32_t *tab;   // row table [a_i][4 lane groups][rt_stride] (stage-relative row of I of step 4 * o + g at [g][o]) first
+  int rt_stride;        // NO rounded up to 4
+  int cmax;             // stages stored per wave (>= the longest stage list)
+  int o_stages;         // word offsets into tab of: stages [quad][x][y][cmax][4] (base row of I, position of L_x's
+                        //   weight fragment, of H_y's, unused)
+  int o_quads;          //   [quad][8]: L0, L1, H0, H1 (-1: none), then the stage counts of waves (0,0) (0,1) (1,0) (1,1)
 };
 }  // namespace rbgp_reg
 

@@ -177,6 +177,18 @@ def activations(w: Workload, N: int | None = None) -> np.ndarray:
     return x
 
 
+def device_activations(w: Workload, device):
+    """I[K][N] float32 on `device`, max(0, N(0,1)) (U[-1,1] for "uniform") from torch's seeded generator: for
+    full-size cells whose host copy would take longer to draw than the product to check.  The values differ
+    from activations() (another generator); callers read back the columns they hand to the oracle."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(w.i_seed)
+    if w.i_dist == "uniform":
+        return torch.rand((w.K, w.N), generator=g, device=device) * 2 - 1
+    return torch.randn((w.K, w.N), generator=g, device=device).clamp_(min=0)
+
+
 def output_gradients(w: Workload, N: int | None = None) -> np.ndarray:
     """dO[M][N] float32 ~ N(0, 1): the gradient arriving at the layer's output in a training
     step (dense, signed), seeded from the activations' seed."""

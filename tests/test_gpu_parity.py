@@ -244,7 +244,10 @@ def test_shapes_across_the_kernel_table(idx, dtype):
     covered = gh.family_covers(w, REG)
     assert covered or idx not in REG_COVERED
     if covered:
-        for tune in [(0, 0, 0, 1), (0, 0, 0, 2), (0, 0, 0, 0, 0, 2)] + ([(0, 64, 0, 0, 2, 1), (0, 128, 0, 0, 1, 4)] if dtype == wl.BF16 else []):
+        # tile-by-tile pairing of the tile rows where the library's plan has it (fp32, two tile rows per MFMA group)
+        pairing = dtype == wl.F32 and rb.rbgp_mask_reg_plan(gh.make_mask(w))[7] > 0
+        for tune in [(0, 0, 0, 1), (0, 0, 0, 0, 0, 2)] + ([(0, 0, 0, 2)] if pairing else []) + \
+                ([(0, 64, 0, 0, 2, 1), (0, 128, 0, 0, 1, 4)] if dtype == wl.BF16 else []):
             gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
 
 
