@@ -57,7 +57,8 @@ enum {
   RBGP_ESHAPE = -4,        /* M, K, ld* do not match the mask */
   RBGP_EHIP = -5,          /* a HIP call failed (message via rbgp_last_hip_error) */
   RBGP_EUNSUPPORTED = -6,  /* requested kernel cannot run this mask / dtype */
-  RBGP_EINTERNAL = -7      /* rbgp_mask_check_tables found an inconsistent index table */
+  RBGP_EINTERNAL = -7,     /* rbgp_mask_check_tables found an inconsistent index table */
+  RBGP_ETOOLARGE = -8      /* rbgp_sddmm_static: the problem needs more scratch memory than its fixed array holds */
 };
 
 /* per-factor result of the spectral test */
@@ -264,6 +265,24 @@ int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, c
 int rbgp_sddmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
                const void *dev_dO, int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW,
                void *hip_stream);
+
+/* rbgp_sddmm for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving or training loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * results as rbgp_sddmm (bit for bit), but the call allocates and frees nothing on the device and
+ * does not touch the mask's own device tables: the index tables and the partial sums of the kernels
+ * live in one fixed array of 16.25 MiB (256 KiB of tables, 16 MiB of partial sums) that is part of
+ * the library's code object on every GPU the library runs on, until the process ends.  The tables
+ * reach it as kernel arguments (small launches on `hip_stream`), whenever the array holds another
+ * mask's; the partial sums of a call overwrite those of the last.
+ * Limits: RBGP_ETOOLARGE when the tables of the mask exceed 256 KiB or the call needs more than
+ * 16 MiB of partial sums (partial sums = ceil(N / columns per workgroup) x nnz floats; the VGG19 and
+ * WRN-40-4 layers of the paper need none to 1.2 MiB); at most 64 GPUs.
+ * All calls on one GPU share the one array: calls that overlap in time on a GPU (two streams, two
+ * threads) race on it, whatever masks they use; so does a call of this kind that overlaps one whose
+ * tables it replaces.  Errors otherwise as rbgp_sddmm.  Asynchronous on `hip_stream`. */
+int rbgp_sddmm_static(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
+                      const void *dev_dO, int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW,
+                      void *hip_stream);
 
 /* O = W_s x I (Section 5, "GPU Implementation"; Algorithm 1 with C overwritten).
  * dev_I: K x N row-major with leading dimension ldI >= N elements (the lowered

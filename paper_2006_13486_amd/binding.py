@@ -14,7 +14,7 @@ KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG, KERNEL_MFMA_TILE = 0,
 TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_ROW_PAIRING = 0, 1, 2, 3
 TUNE_ROW_GROUPS, TUNE_K_SPLIT = 4, 5
 SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE, SPEC_PRODUCT = 0, 1, 2, 3
-OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED, EINTERNAL = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED, EINTERNAL, ETOOLARGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librbgp.so")
 _lib = None
@@ -55,6 +55,8 @@ SIGNATURES = {
     "rbgp_pack_transposed_device": (ctypes.c_int, [_vp, ctypes.c_int, _vp, _vp, _vp]),
     "rbgp_sddmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                   _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, _vp]),
+    "rbgp_sddmm_static": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp, _vp]),
     "rbgp_spmm": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                  _vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]),
     "rbgp_conv3x3": (ctypes.c_int, [_vp, ctypes.c_int] + [ctypes.c_int64] * 5 + [_vp, _vp, _vp, ctypes.c_int64, _vp]),
@@ -286,6 +288,12 @@ def rbgp_sddmm(mask: Mask, dtype: int, M: int, K: int, N: int, dev_dO_ptr: int, 
                dev_dW_ptr: int, stream: int = 0):
     _check(load().rbgp_sddmm(mask.handle, dtype, M, K, N, dev_dO_ptr, ld_dO, dev_I_ptr, ldI, dev_dW_ptr, stream),
            "rbgp_sddmm")
+
+
+def rbgp_sddmm_static(mask: Mask, dtype: int, M: int, K: int, N: int, dev_dO_ptr: int, ld_dO: int, dev_I_ptr: int,
+                      ldI: int, dev_dW_ptr: int, stream: int = 0):
+    _check(load().rbgp_sddmm_static(mask.handle, dtype, M, K, N, dev_dO_ptr, ld_dO, dev_I_ptr, ldI, dev_dW_ptr, stream),
+           "rbgp_sddmm_static")
 
 
 def rbgp_conv3x3(mask: Mask, dtype: int, channels_out: int, channels_in: int, images: int, height: int, width: int,

@@ -600,6 +600,20 @@ int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, i
                            hip_stream);
 }
 
+int rbgp_sddmm_static(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+                      int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
+  if (!m) return RBGP_EINVAL;
+  if (!valid_dtype(dtype)) return RBGP_EINVAL;
+  if (M != m->M || K != m->K || N < 0 || ld_dO < N || ldI < N) return RBGP_ESHAPE;
+  if (!dev_dW || (N > 0 && (!dev_dO || !dev_I))) return RBGP_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dev_dO) | reinterpret_cast<uintptr_t>(dev_I) | reinterpret_cast<uintptr_t>(dev_dW)) & 3)
+    return RBGP_ESHAPE;
+  const bool bf16 = bf16_in(dtype);
+  const bool aligned = !bf16 || (ld_dO % 2 == 0 && ldI % 2 == 0);
+  const bool use_mfma = m->kernel_choice != RBGP_KERNEL_GENERIC && rbgp_reg_covers(m) && aligned;
+  return rbgp_sddmm_static_launch(m, use_mfma, bf16, N, dev_dO, ld_dO, dev_I, ldI, dev_dW, hip_stream);
+}
+
 int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,
               const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO, void *hip_stream) {
   if (!m) return RBGP_EINVAL;

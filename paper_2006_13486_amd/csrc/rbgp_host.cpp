@@ -6,6 +6,7 @@
 // until the graph meets the bound of Section 3.  Section 3: bipartite graph
 // product = Kronecker product of biadjacency matrices.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -256,6 +257,11 @@ int ilog2_exact(int q) {  // log2(q) if q is a power of two, else -1
 thread_local char g_hip_error[256] = "";
 
 }  // namespace
+
+uint64_t rbgp_next_uid() {
+  static std::atomic<uint64_t> next{1};
+  return next.fetch_add(1);
+}
 
 void rbgp_set_hip_error(const char *msg) {
   std::strncpy(g_hip_error, msg ? msg : "", sizeof(g_hip_error) - 1);
@@ -904,6 +910,7 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
   }
   m->M = M; m->K = K; m->rowdeg = rowdeg; m->coldeg = coldeg; m->nnz = M * rowdeg;
   m->kernel_choice = RBGP_KERNEL_AUTO;
+  m->uid = rbgp_next_uid();
   m->dev = nullptr;
   rbgp_plan_mfma(m);
   rbgp_plan_reg(m);
@@ -1020,6 +1027,7 @@ int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
     for (int i = 0; i < 4; ++i) t->adj[i] = std::move(coadj[i]);
     t->M = m->K; t->K = m->M; t->rowdeg = m->coldeg; t->coldeg = m->rowdeg; t->nnz = m->nnz;
     t->kernel_choice = RBGP_KERNEL_AUTO;
+    t->uid = rbgp_next_uid();
     t->dev = nullptr;
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
@@ -1098,6 +1106,7 @@ int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
                     t->from_original[size_t(s++)] = int32_t(row * m->rowdeg + at);
                   }
     t->kernel_choice = RBGP_KERNEL_AUTO;
+    t->uid = rbgp_next_uid();
     t->dev = nullptr;
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
@@ -1286,6 +1295,7 @@ const char *rbgp_strerror(int code) {
     case RBGP_EHIP: return "HIP call failed";
     case RBGP_EUNSUPPORTED: return "kernel does not cover this mask or dtype";
     case RBGP_EINTERNAL: return "an index table of the library is inconsistent";
+    case RBGP_ETOOLARGE: return "the problem needs more scratch memory than the allocation-free entry point has";
     default: return "unknown error";
   }
 }

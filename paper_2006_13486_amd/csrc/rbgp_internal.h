@@ -104,6 +104,7 @@ struct rbgp_mask {
   double sigma1[4], sigma2[4], bound[4];
   int status[4], tries[4];
   int64_t M, K, rowdeg, coldeg, nnz;
+  uint64_t uid;                       // unique per mask object of the process (never 0)
   int kernel_choice;                  // RBGP_KERNEL_*
   std::vector<rbgp_base_graph> base;  // the sampled base graphs, in product order (four for rbgp_make_mask)
   std::vector<int32_t> from_original; // masks made by rbgp_mask_transpose: canonical index in the
@@ -175,7 +176,11 @@ void rbgp_tile_release(void *state);
 int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
                       int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream,
                       const rbgp_conv_geometry *conv = nullptr);
+// the same through the static scratch array of rbgp_sddmm.hip: no device allocation, tables uploaded as kernel arguments
+int rbgp_sddmm_static_launch(const rbgp_mask *m, bool use_mfma, bool bf16, int64_t N, const void *dO, int64_t ld_dO,
+                             const void *I, int64_t ldI, float *dW, void *stream);
 void rbgp_sddmm_release(void *state);
+uint64_t rbgp_next_uid();
 // host part
 void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);

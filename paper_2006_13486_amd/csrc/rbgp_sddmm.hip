@@ -435,40 +435,93 @@ sddmm_fn find_kernel(int RB, int NB, bool bf16) {
   return nullptr;
 }
 
-int build_state(const rbgp_mask *m, SddmmState *st) {
+// Host tables of the MFMA kernel.
+struct SddmmHostTables {
+  std::vector<int32_t> colrows, colpos, rt, sp;
+  int EO = 0;
+};
+
+void make_host_tables(const rbgp_mask *m, SddmmHostTables *h) {
   const rbgp_reg_plan &pl = m->reg;
   const int NB = (pl.KCR + 15) / 16;
   // co-adjacency of the tile rows: tile row u has the tiles of G_o's row u / fold
   const int c1 = m->c[0], d1 = m->d[0], EO = m->e[0] * pl.fold;
-  std::vector<int32_t> colrows(size_t(c1) * EO), colpos(size_t(c1) * EO);
+  h->colrows.assign(size_t(c1) * EO, 0);
+  h->colpos.assign(size_t(c1) * EO, 0);
   std::vector<int> fill(size_t(c1), 0);
   for (int u = 0; u < pl.TR; ++u)
     for (int jj = 0; jj < d1; ++jj) {
       const int v = m->adj[0][size_t(u / pl.fold) * d1 + jj];
-      colrows[size_t(v) * EO + fill[size_t(v)]] = u;
-      colpos[size_t(v) * EO + fill[size_t(v)]++] = jj;
+      h->colrows[size_t(v) * EO + fill[size_t(v)]] = u;
+      h->colpos[size_t(v) * EO + fill[size_t(v)]++] = jj;
     }
   const int a3 = m->a[2], d3 = m->d[2], c3 = m->c[2], c4 = m->c[3];
-  std::vector<int32_t> rt(size_t(a3) * NB * 16, 0);
+  h->rt.assign(size_t(a3) * NB * 16, 0);
   for (int u3 = 0; u3 < a3; ++u3)
     for (int kk = 0; kk < pl.KCR; ++kk) {
       const int v4 = kk % c4, j3 = (kk / c4) % d3, vv = kk / (c4 * d3);
-      rt[(size_t(u3) * NB) * 16 + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
+      h->rt[(size_t(u3) * NB) * 16 + kk] = (vv * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4;
     }
   // "all of G_i" units: where G_i puts every row of a stage, per u_i
   const int NBG = (pl.SRC + 15) / 16;
-  std::vector<int32_t> sp(size_t(a3) * NBG * 16, -1);
+  h->sp.assign(size_t(a3) * NBG * 16, -1);
   for (int u3 = 0; u3 < a3; ++u3)
     for (int j3 = 0; j3 < d3; ++j3)
       for (int vv = 0; vv < pl.VC; ++vv)
         for (int v4 = 0; v4 < c4; ++v4)
-          sp[size_t(u3) * NBG * 16 + (size_t(vv) * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4] = (vv * d3 + j3) * c4 + v4;
-  int rc = upload(colrows, &st->colrows);
-  if (!rc) rc = upload(colpos, &st->colpos);
-  if (!rc) rc = upload(rt, &st->rowtab);
-  if (!rc) rc = upload(sp, &st->spos);
-  st->EO = EO;
-  return rc;
+          h->sp[size_t(u3) * NBG * 16 + (size_t(vv) * c3 + m->adj[2][size_t(u3) * d3 + j3]) * c4 + v4] = (vv * d3 + j3) * c4 + v4;
+  h->EO = EO;
+}
+
+// The state is touched only when every table is on the device.
+int build_state(const rbgp_mask *m, SddmmState *st) {
+  SddmmHostTables h;
+  make_host_tables(m, &h);
+  int32_t *colrows = nullptr, *colpos = nullptr, *rowtab = nullptr, *spos = nullptr;
+  int rc = upload(h.colrows, &colrows);
+  if (!rc) rc = upload(h.colpos, &colpos);
+  if (!rc) rc = upload(h.rt, &rowtab);
+  if (!rc) rc = upload(h.sp, &spos);
+  if (rc) {
+    if (colrows) (void)hipFree(colrows);
+    if (colpos) (void)hipFree(colpos);
+    if (rowtab) (void)hipFree(rowtab);
+    if (spos) (void)hipFree(spos);
+    return rc;
+  }
+  st->colrows = colrows; st->colpos = colpos; st->rowtab = rowtab; st->spos = spos;
+  st->EO = h.EO;
+  return RBGP_OK;
+}
+
+// What a launch reads and writes besides the caller's buffers: the index tables and the partial sums,
+// in memory of the mask's state (rbgp_sddmm) or in the static scratch array (rbgp_sddmm_static).
+struct SddmmBuffers {
+  const int32_t *adj[4] = {nullptr, nullptr, nullptr, nullptr};   // plain kernel
+  const int32_t *colrows = nullptr, *colpos = nullptr, *rowtab = nullptr, *spos = nullptr;   // MFMA kernel
+  int EO = 0;
+  float *partial = nullptr;
+  size_t partial_bytes = 0;
+  SddmmState *grow = nullptr;   // may enlarge `partial` with hipMalloc (nullptr: a larger need is RBGP_ETOOLARGE)
+};
+
+// Allocation-free variant: everything above lives in this array, per GPU.
+constexpr size_t kStaticTableBytes = size_t(256) << 10;
+constexpr size_t kStaticPartialBytes = size_t(16) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticTableBytes + kStaticPartialBytes];
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+  unsigned char *ptr = nullptr;   // device address of `scratch` on this GPU
+  uint64_t key = 0;               // uid of the mask whose tables the array holds (0: none)
+};
+StaticSlot g_static[kMaxDevices];
+
+// Tables reach the array as kernel arguments, a chunk per launch: no staging copy, nothing allocated.
+struct ArgChunk {
+  int32_t v[960];
+};
+__global__ __launch_bounds__(256) void table_write(ArgChunk c, int32_t *__restrict__ dst, int n) {
+  for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.v[i];
 }
 
 }  // namespace
@@ -486,11 +539,10 @@ void rbgp_sddmm_release(void *state) {
   delete st;
 }
 
-int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
-                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream,
-                      const rbgp_conv_geometry *conv) {
-  if (conv && !use_mfma) return RBGP_EUNSUPPORTED;
-  hipStream_t hs = static_cast<hipStream_t>(stream);
+namespace {
+
+int launch_core(const rbgp_mask *m, SddmmBuffers &B, SddmmState *st, bool use_mfma, bool bf16, int64_t N, const void *dO,
+                int64_t ld_dO, const void *I, int64_t ldI, float *dW, hipStream_t hs, const rbgp_conv_geometry *conv) {
   const int64_t nnz = m->nnz;
   if (N == 0) {
     sddmm_zero<<<dim3(unsigned((nnz + 255) / 256)), dim3(256), 0, hs>>>(dW, nnz);
@@ -500,7 +552,7 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   if (!use_mfma) {
     GenericParams gp;
     for (int i = 0; i < 4; ++i) {
-      gp.adj[i] = dev_adj[i];
+      gp.adj[i] = B.adj[i];
       gp.a[i] = m->a[i]; gp.c[i] = m->c[i]; gp.d[i] = m->d[i];
     }
     gp.N = N; gp.ld_dO = ld_dO; gp.ldI = ldI; gp.nnz = nnz; gp.rowdeg = int(m->rowdeg);
@@ -516,25 +568,15 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   }
 
   const rbgp_reg_plan &pl = m->reg;
-  SddmmState *st = static_cast<SddmmState *>(*state);
-  if (!st) {
-    st = new (std::nothrow) SddmmState();
-    if (!st) return RBGP_ENOMEM;
-    *state = st;
-  }
-  if (!st->colrows) {
-    int rc = build_state(m, st);
-    if (rc) return rc;
-  }
   // row groups of 16 (MG tile rows) per tile column and u_i, RB of them per wave: two row groups per wave
   // halve the rows of I fetched per MFMA; four would starve the chip of waves at the layer sizes of
   // the paper (measured: slower on every VGG19 / WRN shape tried)
   int NB = (pl.KCR + 15) / 16;
-  int groups = (st->EO + pl.MG - 1) / pl.MG;
+  int groups = (B.EO + pl.MG - 1) / pl.MG;
   int RB = groups >= 2 ? 2 : 1;
   int RBG = (groups + RB - 1) / RB;
   // or "all of G_i" units, where they need fewer MFMAs per column of the batch
-  const int gi_groups = (st->EO * m->a[2] * pl.R + 15) / 16, gi_NB = (pl.SRC + 15) / 16;
+  const int gi_groups = (B.EO * m->a[2] * pl.R + 15) / 16, gi_NB = (pl.SRC + 15) / 16;
   const int gi_RB = gi_groups >= 2 ? 2 : 1, gi_RBG = (gi_groups + gi_RB - 1) / gi_RB;
   const bool gi = gi_NB <= 5 && gi_RBG * gi_RB * gi_NB < m->a[2] * RBG * RB * NB;
   if (gi) { NB = gi_NB; groups = gi_groups; RB = gi_RB; RBG = gi_RBG; }
@@ -564,12 +606,16 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   const int64_t nsplit = ((N + chunk - 1) / chunk + 3) / 4;              // workgroups per unit = partial sums
   if (nsplit > 1) {
     const size_t need = size_t(nsplit) * size_t(nnz) * sizeof(float);
-    if (st->partial_bytes < need) {
-      if (st->partial) RBGP_HIP(hipFree(st->partial));   // (waits for launches that still use it)
-      st->partial = nullptr;
-      st->partial_bytes = 0;
-      RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&st->partial), need));
-      st->partial_bytes = need;
+    if (B.partial_bytes < need) {
+      if (!B.grow) return RBGP_ETOOLARGE;
+      SddmmState *g = B.grow;
+      if (g->partial) RBGP_HIP(hipFree(g->partial));   // (waits for launches that still use it)
+      g->partial = nullptr;
+      g->partial_bytes = 0;
+      RBGP_HIP(hipMalloc(reinterpret_cast<void **>(&g->partial), need));
+      g->partial_bytes = need;
+      B.partial = g->partial;
+      B.partial_bytes = need;
     }
   }
   SddmmParams p;
@@ -601,12 +647,12 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
     if (p.x_bytes >= (int64_t(1) << 31)) return RBGP_EUNSUPPORTED;
   }
   p.dO = dO; p.I = I;
-  p.out = nsplit > 1 ? st->partial : dW;
-  p.colrows = st->colrows; p.colpos = st->colpos; p.rowtab = st->rowtab;
+  p.out = nsplit > 1 ? B.partial : dW;
+  p.colrows = B.colrows; p.colpos = B.colpos; p.rowtab = B.rowtab;
   p.N = N; p.ld_dO = ld_dO; p.ldI = ldI; p.nnz = nnz; p.chunk = chunk;
-  p.src_rows = pl.SRC; p.spos = st->spos;
+  p.src_rows = pl.SRC; p.spos = B.spos;
   p.nbt = nbt; p.halves = halves;
-  p.EO = st->EO; p.RBG = RBG; p.NSTG = pl.NSTG; p.stage_rows = pl.SRC;
+  p.EO = B.EO; p.RBG = RBG; p.NSTG = pl.NSTG; p.stage_rows = pl.SRC;
   p.tile_rows = m->c[1] * m->c[2] * m->c[3];
   p.a2 = pl.A2; p.a3 = m->a[2]; p.a4 = m->a[3]; p.R = pl.R;
   p.lgRS = 0;
@@ -615,8 +661,93 @@ int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev
   fn<<<dim3(unsigned(blocks), unsigned(nsplit)), dim3(256), 0, hs>>>(p);
   RBGP_HIP(hipGetLastError());
   if (nsplit > 1) {
-    sddmm_reduce<<<dim3(unsigned((nnz + 255) / 256)), dim3(256), 0, hs>>>(st->partial, dW, nnz, int(nsplit));
+    sddmm_reduce<<<dim3(unsigned((nnz + 255) / 256)), dim3(256), 0, hs>>>(B.partial, dW, nnz, int(nsplit));
     RBGP_HIP(hipGetLastError());
   }
   return RBGP_OK;
+}
+
+}  // namespace
+
+int rbgp_sddmm_launch(const rbgp_mask *m, void **state, const int32_t *const dev_adj[4], bool use_mfma, bool bf16,
+                      int64_t N, const void *dO, int64_t ld_dO, const void *I, int64_t ldI, float *dW, void *stream,
+                      const rbgp_conv_geometry *conv) {
+  if (conv && !use_mfma) return RBGP_EUNSUPPORTED;
+  SddmmBuffers B;
+  SddmmState *st = nullptr;
+  for (int i = 0; i < 4; ++i) B.adj[i] = dev_adj[i];
+  if (use_mfma && N > 0) {
+    st = static_cast<SddmmState *>(*state);
+    if (!st) {
+      st = new (std::nothrow) SddmmState();
+      if (!st) return RBGP_ENOMEM;
+      *state = st;
+    }
+    if (!st->colrows) {
+      int rc = build_state(m, st);
+      if (rc) return rc;
+    }
+    B.colrows = st->colrows; B.colpos = st->colpos; B.rowtab = st->rowtab; B.spos = st->spos;
+    B.EO = st->EO;
+    B.partial = st->partial; B.partial_bytes = st->partial_bytes;
+    B.grow = st;
+  }
+  return launch_core(m, B, st, use_mfma, bf16, N, dO, ld_dO, I, ldI, dW, static_cast<hipStream_t>(stream), conv);
+}
+
+int rbgp_sddmm_static_launch(const rbgp_mask *m, bool use_mfma, bool bf16, int64_t N, const void *dO, int64_t ld_dO,
+                             const void *I, int64_t ldI, float *dW, void *stream) {
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  int dev = -1;
+  RBGP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RBGP_EUNSUPPORTED;
+  StaticSlot &slot = g_static[dev];
+  if (!slot.ptr) {   // once per GPU: the address of this GPU's copy of the array
+    unsigned char *p = nullptr;
+    RBGP_HIP(hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)));
+    if (!p) return RBGP_EHIP;
+    slot.ptr = p;
+  }
+  SddmmBuffers B;
+  if (N > 0) {
+    // table area: the four adjacency lists (plain kernel) or the MFMA kernel's four tables, 16-byte aligned
+    std::vector<int32_t> all;
+    size_t off[4] = {0, 0, 0, 0};
+    try {
+      SddmmHostTables h;
+      if (use_mfma) make_host_tables(m, &h);
+      const std::vector<int32_t> *src[4] = {use_mfma ? &h.colrows : &m->adj[0], use_mfma ? &h.colpos : &m->adj[1],
+                                            use_mfma ? &h.rt : &m->adj[2], use_mfma ? &h.sp : &m->adj[3]};
+      for (int i = 0; i < 4; ++i) {
+        off[i] = all.size();
+        all.insert(all.end(), src[i]->begin(), src[i]->end());
+        all.resize((all.size() + 3) / 4 * 4, 0);
+      }
+      B.EO = h.EO;
+    } catch (const std::bad_alloc &) {
+      return RBGP_ENOMEM;
+    }
+    if (all.size() * sizeof(int32_t) > kStaticTableBytes) return RBGP_ETOOLARGE;
+    int32_t *tab = reinterpret_cast<int32_t *>(slot.ptr);
+    const uint64_t key = m->uid * 2 + (use_mfma ? 1 : 0);
+    if (slot.key != key) {
+      slot.key = 0;
+      for (size_t at = 0; at < all.size(); at += 960) {
+        ArgChunk c;
+        const int n = int(std::min<size_t>(960, all.size() - at));
+        std::copy(all.begin() + at, all.begin() + at + n, c.v);
+        table_write<<<dim3(1), dim3(256), 0, hs>>>(c, tab + at, n);
+        RBGP_HIP(hipGetLastError());
+      }
+      slot.key = key;
+    }
+    if (use_mfma) {
+      B.colrows = tab + off[0]; B.colpos = tab + off[1]; B.rowtab = tab + off[2]; B.spos = tab + off[3];
+    } else {
+      for (int i = 0; i < 4; ++i) B.adj[i] = tab + off[i];
+    }
+    B.partial = reinterpret_cast<float *>(slot.ptr + kStaticTableBytes);
+    B.partial_bytes = kStaticPartialBytes;
+  }
+  return launch_core(m, B, nullptr, use_mfma, bf16, N, dO, ld_dO, I, ldI, dW, hs, nullptr);
 }
