@@ -47,7 +47,8 @@ typedef struct rbgp_mask rbgp_mask_t; /* opaque, host memory */
  * (nearest, ties to even) when they store O; everywhere else (packing, layouts, kernel choice,
  * rbgp_sddmm, whose dW stays fp32) the two bf16 modes are the same mode, and buffers packed for
  * one serve the other.  (The paper states no precision: Section 5.) */
-typedef enum { RBGP_F32 = 0, RBGP_BF16_F32ACC = 1, RBGP_BF16 = 2 } rbgp_dtype_t;
+enum { RBGP_F32 = 0, RBGP_BF16_F32ACC = 1, RBGP_BF16 = 2 };
+typedef int rbgp_dtype_t; /* one of the three above; any other value is answered with RBGP_EINVAL */
 
 enum {
   RBGP_OK = 0,
@@ -79,7 +80,7 @@ enum {
   RBGP_KERNEL_MFMA_TILE = 4 /* bf16 modes only, never chosen by AUTO: every nonzero of G_o as a dense
                                block of W_s (zeros where the inner graphs have no edge), I staged in
                                LDS once per workgroup, 32-row MFMA.  Any inner graphs; needs
-                               |G_r.U| |G_i.U| |G_b.U| = 32 or 64 and |G_r.V| |G_i.V| |G_b.V| <= 320.
+                               |G_r.U| |G_i.U| |G_b.U| = 32 and |G_r.V| |G_i.V| |G_b.V| <= 320.
                                rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8,
                                rbgp_conv3x3 an image width that is a multiple of 8 (ESHAPE) */
 };
@@ -303,6 +304,12 @@ int rbgp_sddmm_static(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, in
 int rbgp_spmm(const rbgp_mask_t *mask, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N,
               const void *dev_packed, const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO,
               void *hip_stream);
+/* Non-finite inputs.  The sum of Section 5 runs over the kept weights of a row only, and so does
+ * RBGP_KERNEL_GENERIC: an infinity or NaN in a row of I reaches the outputs of the rows of W_s that keep
+ * a weight in that column of the mask, nothing else.  The MFMA families fill their matrix-core groups
+ * with zero weights where a stage is padded or (RBGP_KERNEL_MFMA_REG, RBGP_KERNEL_MFMA_TILE) a tile row
+ * lacks a tile, and 0 x inf is NaN: with them a non-finite I[k][n] can turn any output of COLUMN n of O
+ * (never another column) into NaN.  Finite I gives the same result on all families (to rounding). */
 
 /* Fused 3x3 convolution (stride 1, zero padding 1): O = W_s x im2col(X) without the lowered
  * input ever being stored.  (The paper feeds its kernel batched activations lowered to a

@@ -89,7 +89,9 @@ def load():
         # torch bundles its own HIP runtime (SONAME libamdhip64.so.7).  Import it first so
         # that librbgp.so binds to that copy: two HIP runtimes in one process do not share
         # the device and the second one reports "no ROCm-capable device".
-        import torch  # noqa: F401
+        # (RBGP_NO_TORCH: the host-only sanitizer run loads the library without torch in the process)
+        if not os.environ.get("RBGP_NO_TORCH"):
+            import torch  # noqa: F401
         lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)

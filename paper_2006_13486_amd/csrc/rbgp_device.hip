@@ -440,19 +440,26 @@ int ensure_device(const rbgp_mask *m) {
   }
   rbgp_device_state *dev = m->dev;
   RBGP_HIP(hipGetDevice(&dev->device));
-  for (int i = 0; i < 4; ++i) {
-    int rc = upload(m->adj[i], &dev->adj[i]);
-    if (rc) return rc;
-  }
-  if (m->plan.ok) {
+  // the state is touched only when every table is on the device (adj[0] marks "built")
+  int32_t *adj[4] = {nullptr, nullptr, nullptr, nullptr}, *rowoff = nullptr;
+  int rc = RBGP_OK;
+  for (int i = 0; i < 4 && !rc; ++i) rc = upload(m->adj[i], &adj[i]);
+  if (!rc && m->plan.ok) {
     const rbgp_mfma_plan &p = m->plan;
     std::vector<int32_t> ro(size_t(m->a[2]) * p.KS);
     for (int u3 = 0; u3 < m->a[2]; ++u3)
       for (int kk = 0; kk < p.KS; ++kk)
         ro[size_t(u3) * p.KS + kk] = m->adj[2][size_t(u3) * m->d[2] + kk / m->c[3]] * m->c[3] + kk % m->c[3];
-    int rc = upload(ro, &dev->rowoff);
-    if (rc) return rc;
+    rc = upload(ro, &rowoff);
   }
+  if (rc) {
+    for (int32_t *t : adj)
+      if (t) (void)hipFree(t);
+    if (rowoff) (void)hipFree(rowoff);
+    return rc;
+  }
+  dev->rowoff = rowoff;
+  for (int i = 3; i >= 0; --i) dev->adj[i] = adj[i];
   return RBGP_OK;
 }
 
@@ -505,12 +512,16 @@ size_t rbgp_packed_bytes(const rbgp_mask_t *m, rbgp_dtype_t dtype) {
   return size_t(packed_elems(m, resolve_kernel(m, dtype), dtype)) * elem_bytes(dtype);
 }
 
-int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
+static int pack_layout_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
   if (!m || !out || !valid_dtype(dtype)) return RBGP_EINVAL;
   std::vector<int32_t> perm;
   rbgp_build_pack_perm(m, resolve_kernel(m, dtype), bf16_in(dtype), perm);
   std::copy(perm.begin(), perm.end(), out);
   return RBGP_OK;
+}
+
+int rbgp_pack_layout(const rbgp_mask_t *m, rbgp_dtype_t dtype, int32_t *out) {
+  RBGP_GUARDED(pack_layout_impl(m, dtype, out));
 }
 
 static int pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *dev_values,
@@ -537,14 +548,24 @@ static int pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_o
   return RBGP_OK;
 }
 
-int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
+static int pack_device_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
                      void *hip_stream) {
   return pack_device(m, dtype, false, dev_values, dev_packed, hip_stream);
 }
 
-int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
+int rbgp_pack_device(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *dev_values, void *dev_packed,
+                     void *hip_stream) {
+  RBGP_GUARDED(pack_device_impl(m, dtype, dev_values, dev_packed, hip_stream));
+}
+
+static int pack_transposed_device_impl(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
                                 void *dev_packed, void *hip_stream) {
   return pack_device(mask_t, dtype, true, dev_values, dev_packed, hip_stream);
+}
+
+int rbgp_pack_transposed_device(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *dev_values,
+                                void *dev_packed, void *hip_stream) {
+  RBGP_GUARDED(pack_transposed_device_impl(mask_t, dtype, dev_values, dev_packed, hip_stream));
 }
 
 static int pack_host(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_order, const void *host_values,
@@ -571,17 +592,27 @@ static int pack_host(const rbgp_mask_t *m, rbgp_dtype_t dtype, bool original_ord
   return RBGP_OK;
 }
 
-int rbgp_pack(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+static int pack_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
               void *hip_stream) {
   return pack_host(m, dtype, false, host_values, dev_packed, hip_stream);
 }
 
-int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+int rbgp_pack(const rbgp_mask_t *m, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+              void *hip_stream) {
+  RBGP_GUARDED(pack_impl(m, dtype, host_values, dev_packed, hip_stream));
+}
+
+static int pack_transposed_impl(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
                          void *hip_stream) {
   return pack_host(mask_t, dtype, true, host_values, dev_packed, hip_stream);
 }
 
-int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+int rbgp_pack_transposed(const rbgp_mask_t *mask_t, rbgp_dtype_t dtype, const void *host_values, void *dev_packed,
+                         void *hip_stream) {
+  RBGP_GUARDED(pack_transposed_impl(mask_t, dtype, host_values, dev_packed, hip_stream));
+}
+
+static int sddmm_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
                int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
   if (!valid_dtype(dtype)) return RBGP_EINVAL;
@@ -600,7 +631,12 @@ int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, i
                            hip_stream);
 }
 
-int rbgp_sddmm_static(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+int rbgp_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+               int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
+  RBGP_GUARDED(sddmm_impl(m, dtype, M, K, N, dev_dO, ld_dO, dev_I, ldI, dev_dW, hip_stream));
+}
+
+static int sddmm_static_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
                       int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
   if (!valid_dtype(dtype)) return RBGP_EINVAL;
@@ -614,7 +650,12 @@ int rbgp_sddmm_static(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64
   return rbgp_sddmm_static_launch(m, use_mfma, bf16, N, dev_dO, ld_dO, dev_I, ldI, dev_dW, hip_stream);
 }
 
-int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,
+int rbgp_sddmm_static(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_dO,
+                      int64_t ld_dO, const void *dev_I, int64_t ldI, float *dev_dW, void *hip_stream) {
+  RBGP_GUARDED(sddmm_static_impl(m, dtype, M, K, N, dev_dO, ld_dO, dev_I, ldI, dev_dW, hip_stream));
+}
+
+static int spmm_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,
               const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
   if (!valid_dtype(dtype)) return RBGP_EINVAL;
@@ -708,7 +749,12 @@ int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, in
   return RBGP_OK;
 }
 
-int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in, int64_t images,
+int rbgp_spmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_t K, int64_t N, const void *dev_packed,
+              const void *dev_I, int64_t ldI, void *dev_O, int64_t ldO, void *hip_stream) {
+  RBGP_GUARDED(spmm_impl(m, dtype, M, K, N, dev_packed, dev_I, ldI, dev_O, ldO, hip_stream));
+}
+
+static int conv3x3_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in, int64_t images,
                  int64_t height, int64_t width, const void *dev_packed, const void *dev_X, void *dev_O, int64_t ldO,
                  void *hip_stream) {
   if (!m) return RBGP_EINVAL;
@@ -730,7 +776,13 @@ int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out,
                          N, dev_O, ldO, hip_stream, &geom);
 }
 
-int rbgp_conv3x3_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
+int rbgp_conv3x3(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in, int64_t images,
+                 int64_t height, int64_t width, const void *dev_packed, const void *dev_X, void *dev_O, int64_t ldO,
+                 void *hip_stream) {
+  RBGP_GUARDED(conv3x3_impl(m, dtype, channels_out, channels_in, images, height, width, dev_packed, dev_X, dev_O, ldO, hip_stream));
+}
+
+static int conv3x3_sddmm_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
                        int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
                        const void *dev_X, float *dev_dW, void *hip_stream) {
   if (!m) return RBGP_EINVAL;
@@ -750,6 +802,12 @@ int rbgp_conv3x3_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channel
   const rbgp_conv_geometry geom = {images, height, width};
   return rbgp_sddmm_launch(m, &m->dev->sddmm_state, m->dev->adj, true, bf16, N, dev_dO, ld_dO, dev_X, N, dev_dW,
                            hip_stream, &geom);
+}
+
+int rbgp_conv3x3_sddmm(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t channels_out, int64_t channels_in,
+                       int64_t images, int64_t height, int64_t width, const void *dev_dO, int64_t ld_dO,
+                       const void *dev_X, float *dev_dW, void *hip_stream) {
+  RBGP_GUARDED(conv3x3_sddmm_impl(m, dtype, channels_out, channels_in, images, height, width, dev_dO, ld_dO, dev_X, dev_dW, hip_stream));
 }
 
 }  // extern "C"

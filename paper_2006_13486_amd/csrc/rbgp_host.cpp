@@ -509,7 +509,7 @@ void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
   long budget = 200000;
   const int lb_tot = (TR * d1 + 1) / 2;
   struct Rec {
-    decltype(cost) &cost; std::vector<int32_t> &cur, &best; std::vector<char> &taken;
+    decltype(cost) &quad_cost; std::vector<int32_t> &cur, &best; std::vector<char> &taken;
     int TRP, nq, d1, lb_tot; int &best_max, &best_tot; long &budget;
     bool done() const { return best_max <= d1 && best_tot <= lb_tot; }
     void go(int depth, int cmax, int ctot) {
@@ -534,7 +534,7 @@ void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
                 for (int k = 0; k < 4; ++k)
                   if (k != a && k != b) h[nh++] = q[k];
                 Cand c;
-                c.mx = cost(q[a], q[b], h[0], h[1], &c.tot);
+                c.mx = quad_cost(q[a], q[b], h[0], h[1], &c.tot);
                 c.r[0] = q[a]; c.r[1] = q[b]; c.r[2] = h[0]; c.r[3] = h[1];
                 cands.push_back(c);
               }
@@ -984,7 +984,7 @@ static void co_adjacency(const rbgp_mask *m, std::vector<int32_t> coadj[4]) {
   }
 }
 
-int rbgp_transpose_order(const rbgp_mask_t *m, int32_t *out) {
+static int transpose_order_impl(const rbgp_mask_t *m, int32_t *out) {
   if (!m || !out) return RBGP_EINVAL;
   try {
     std::vector<int32_t> coadj[4];
@@ -994,6 +994,10 @@ int rbgp_transpose_order(const rbgp_mask_t *m, int32_t *out) {
     return RBGP_ENOMEM;
   }
   return RBGP_OK;
+}
+
+int rbgp_transpose_order(const rbgp_mask_t *m, int32_t *out) {
+  RBGP_GUARDED(transpose_order_impl(m, out));
 }
 
 int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
@@ -1118,10 +1122,14 @@ int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
   return RBGP_OK;
 }
 
-int rbgp_mask_original_order(const rbgp_mask_t *m, int32_t *out) {
+static int mask_original_order_impl(const rbgp_mask_t *m, int32_t *out) {
   if (!m || !out || m->from_original.empty()) return RBGP_EINVAL;
   std::copy(m->from_original.begin(), m->from_original.end(), out);
   return RBGP_OK;
+}
+
+int rbgp_mask_original_order(const rbgp_mask_t *m, int32_t *out) {
+  RBGP_GUARDED(mask_original_order_impl(m, out));
 }
 
 void rbgp_mask_free(rbgp_mask_t *mask) {
@@ -1162,7 +1170,7 @@ int rbgp_mask_spectrum(const rbgp_mask_t *m, int i, double *sigma1, double *sigm
   return RBGP_OK;
 }
 
-int rbgp_mask_columns(const rbgp_mask_t *m, int32_t *out) {
+static int mask_columns_impl(const rbgp_mask_t *m, int32_t *out) {
   if (!m || !out) return RBGP_EINVAL;
   const int32_t *A0 = m->adj[0].data(), *A1 = m->adj[1].data(), *A2 = m->adj[2].data(),
                 *A3 = m->adj[3].data();
@@ -1184,7 +1192,11 @@ int rbgp_mask_columns(const rbgp_mask_t *m, int32_t *out) {
   return RBGP_OK;
 }
 
-int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
+int rbgp_mask_columns(const rbgp_mask_t *m, int32_t *out) {
+  RBGP_GUARDED(mask_columns_impl(m, out));
+}
+
+static int mask_dense_impl(const rbgp_mask_t *m, uint8_t *out) {
   if (!m || !out) return RBGP_EINVAL;
   std::memset(out, 0, size_t(m->M) * size_t(m->K));
   std::vector<int32_t> cols(size_t(m->nnz));
@@ -1195,7 +1207,11 @@ int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
   return RBGP_OK;
 }
 
-int rbgp_mask_reg_plan(const rbgp_mask_t *m, int32_t info[16]) {
+int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
+  RBGP_GUARDED(mask_dense_impl(m, out));
+}
+
+static int mask_reg_plan_impl(const rbgp_mask_t *m, int32_t info[16]) {
   if (!m || !info) return RBGP_EINVAL;
   for (int i = 0; i < 16; ++i) info[i] = 0;
   const rbgp_reg_plan &p = m->reg;
@@ -1219,6 +1235,10 @@ int rbgp_mask_reg_plan(const rbgp_mask_t *m, int32_t info[16]) {
     }
   }
   return RBGP_OK;
+}
+
+int rbgp_mask_reg_plan(const rbgp_mask_t *m, int32_t info[16]) {
+  RBGP_GUARDED(mask_reg_plan_impl(m, info));
 }
 
 // Every (tile row, tile, stage of the tile) must be multiplied exactly once, by a stage whose base
@@ -1262,6 +1282,18 @@ int rbgp_mask_check_tables(const rbgp_mask_t *m) {
           if (c != 1) return RBGP_EINTERNAL;
       }
     }
+    // the packed buffer holds exactly the fragments the stage lists can name, plus the zero fragment; the
+    // rows of I a stage's contraction steps select lie inside the rows the stage spans
+    if (p.packed_elems != (int64_t(p.TR) * fpm * m->a[2] + 1) * p.NQ * 4 * p.RS * 4) return RBGP_EINTERNAL;
+    if (p.KCR > p.KC || p.KC > p.NO * 4 || p.NO > p.NQ * 4 || stage_rows != p.SRC) return RBGP_EINTERNAL;
+    for (int u3 = 0; u3 < m->a[2]; ++u3)
+      for (int kk = 0; kk < p.KCR; ++kk) {
+        const int st = rbgp_reg_step(m, kk);
+        if (st < 0 || st >= p.KCR) return RBGP_EINTERNAL;
+        const int v4 = st % m->c[3], j3 = (st / m->c[3]) % m->d[2], vv = st / (m->c[3] * m->d[2]);
+        const int64_t row = (int64_t(vv) * m->c[2] + m->adj[2][size_t(u3) * m->d[2] + j3]) * m->c[3] + v4;
+        if (vv >= p.VC || row < 0 || row >= p.SRC) return RBGP_EINTERNAL;
+      }
     const rbgp_reg_dual &d = m->reg_dual;
     if (d.ok) {
       std::vector<int> used(size_t(p.TR) * fpm, 0);

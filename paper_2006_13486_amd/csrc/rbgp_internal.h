@@ -4,11 +4,22 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "../../include/rbgp.h"
 
 struct rbgp_device_state;  // defined in rbgp_device.hip
+
+// No C++ exception crosses the C boundary: an entry point that can allocate host memory returns through this.
+#define RBGP_GUARDED(expr)              \
+  try {                                 \
+    return (expr);                      \
+  } catch (const std::bad_alloc &) {    \
+    return RBGP_ENOMEM;                 \
+  } catch (...) {                       \
+    return RBGP_EINVAL;                 \
+  }
 
 // MFMA_REG bf16 kernels: a stage of KC contraction steps = rbgp_bf16_blocks32(KC) blocks of 32 steps
 // plus, if rbgp_bf16_tail16(KC), one block of 16 (a remainder above 16 takes a whole block of 32)

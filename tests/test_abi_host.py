@@ -414,3 +414,70 @@ def test_conv3x3_transposed_mask_holds_the_flipped_kernel(shape):
     with pytest.raises(rb.RbgpError) as ei:
         rb.rbgp_mask_conv3x3_transpose(rb.rbgp_make_mask(wl.TINY.rows, wl.TINY.cols, wl.TINY.row_deg, 1))
     assert ei.value.code == rb.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ index tables of the register family
+def _all_workload_shapes():
+    from tests import test_gpu_parity as tp
+    shapes = [(w.rows, w.cols, w.row_deg) for w in wl.CONFIGS]
+    for layer in range(len(wl.VGG19_LAYERS)):
+        for d in (1, 2, 3, 4):
+            w = wl.vgg19_sweep_workload(layer, d, wl.F32)
+            shapes.append((w.rows, w.cols, w.row_deg))
+    for o, i in [(0, 2), (1, 1), (0, 3), (1, 2), (2, 1), (0, 4), (1, 3), (2, 2), (3, 1)]:
+        w = wl.sdmm4096_table2(o, i)
+        shapes.append((w.rows, w.cols, w.row_deg))
+    for gr, gb in [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]:
+        w = wl.sdmm4096_table3(gr, gb, 3)
+        shapes.append((w.rows, w.cols, w.row_deg))
+    shapes += list(tp.FUZZ) + list(tp.PAIRING_SHAPES)
+    return sorted(set(shapes))
+
+
+def test_index_tables_are_consistent_for_every_workload_shape():
+    """The library's own check of the tables its register kernels read -- every (tile row, tile, stage)
+    multiplied exactly once by a stage of that tile, fragment positions inside the packed buffer, rows of I
+    inside the stage -- on every mask shape of the benchmarks and GPU tests, their transposes and the masks
+    of their transposed convolutions."""
+    count = 0
+    for rows, cols, deg in _all_workload_shapes():
+        try:
+            mask = rb.rbgp_make_mask(rows, cols, deg, 77)
+        except rb.RbgpError as e:          # (a cell whose factor cannot be sampled is recorded by the sweep, not hidden)
+            assert e.code == rb.ENOTRAMANUJAN
+            continue
+        derived = [mask, rb.rbgp_mask_transpose(mask)]
+        if cols[3] == 9 and deg[3] == 9:
+            derived.append(rb.rbgp_mask_conv3x3_transpose(mask))
+        for m in derived:
+            rb.rbgp_mask_check_tables(m)
+            info = rb.rbgp_mask_reg_plan(m)
+            if info[0]:                    # the family covers the mask
+                MG, NSTG, TR, ncl, longest, total = info[0], info[1], info[3], info[4], info[5], info[6]
+                d_o = rb.rbgp_mask_factor(m, 0)[2]
+                per_row = d_o * NSTG
+                assert ncl == -(-TR // MG) and per_row <= longest <= MG * per_row
+                assert -(-TR * per_row // MG) <= total <= ncl * MG * per_row
+                if info[7]:                # tile-by-tile pairing: never more work than one stage per (tile row, tile)
+                    assert info[0] == 2 and info[7] == -(-TR // 4)
+                    assert -(-TR * per_row // 2) <= info[9] <= TR * per_row
+                    assert info[10] <= info[8] <= 2 * info[10] and info[8] >= min(TR, 2) * per_row // 2
+            count += 1
+    assert count > 150
+
+
+def test_pairing_of_the_conv5_mask_multiplies_no_zero_rows():
+    """VGG19 conv5 at density 1/8: G_o is one 2-lift of the complete graph on (8, 8) vertices, so the tile
+    rows u and u + 8 have complementary tiles (Appendix: the clone of an edge is the identity pair or the
+    crossover pair).  Fixed pairs of tile rows walk 9 or 10 tiles for 8 each; quads of two complementary
+    pairs walk 8 tiles per SIMD with all 16 rows of every MFMA group rows of the mask."""
+    w = wl.VGG19_CONV5
+    mask = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+    _, _, d_o, adj = rb.rbgp_mask_factor(mask, 0)
+    has = np.zeros((16, 16), bool)
+    for u in range(16):
+        has[u, adj[u]] = True
+    assert all((has[u] ^ has[u + 8]).all() for u in range(8))
+    info = rb.rbgp_mask_reg_plan(mask)
+    assert info[:7] == [2, 1, 72, 16, 8, 10, 76]
+    assert info[7:11] == [4, 8, 64, info[10]] and info[9] == 16 * d_o // 2

@@ -445,3 +445,27 @@ def test_masks_of_more_than_four_base_graphs(w, dtype):
     assert orc.normalised_error(dI, dI_ref, dI_den) <= gh.TOL[dtype]
     dW = gh.library_sddmm(w, lib[2], lib[1])
     assert orc.normalised_error(dW, dW_ref, dW_den) <= gh.TOL[dtype]
+
+
+def test_non_finite_input_stays_in_its_column():
+    """An infinity in one element of I: on the plain kernel it reaches exactly the rows of W_s that keep a
+    weight in that column of the mask (the sum of Section 5 runs over kept weights only); on the MFMA
+    families, whose padding multiplies zero weights by real rows of I, it may spoil other rows of the same
+    column of O, and never another column."""
+    w = replace(wl.VGG19_CONV5, rows=(4, 4, 4, 2), cols=(4, 4, 8, 9), row_deg=(2, 4, 2, 9), name="non_finite")
+    N, k_bad, n_bad = 200, 37, 77
+    vl, Il, vf, If = gh.host_inputs(w, N)
+    I_bad = Il.copy()
+    I_bad[k_bad, n_bad] = np.inf
+    mask = gh.make_mask(w)
+    touched = rb.rbgp_mask_dense(mask).reshape(w.M, w.K)[:, k_bad].astype(bool)
+    assert touched.any() and not touched.all()
+    for kernel in (GEN, MFMA, REG):
+        clean, _ = gh.library_spmm(w, vl, Il, kernel=kernel, tag="finite")
+        spoilt, _ = gh.library_spmm(w, vl, I_bad, kernel=kernel, tag="one infinity")
+        others = np.ones(N, bool)
+        others[n_bad] = False
+        assert np.array_equal(clean[:, others].view(np.uint32), spoilt[:, others].view(np.uint32))
+        assert not np.isfinite(spoilt[touched, n_bad]).any()
+        if kernel == GEN:
+            assert np.array_equal(clean[~touched, n_bad].view(np.uint32), spoilt[~touched, n_bad].view(np.uint32))
