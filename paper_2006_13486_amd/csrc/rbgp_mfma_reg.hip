@@ -88,12 +88,9 @@ __global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
   // 4 / S column tiles.  Used when N is too small to give every SIMD a wave otherwise.
   const int lgS = p.lgS, S = 1 << lgS;
   const int ks = wid & (S - 1);
-  // With fewer than eight groups of column tiles the spare XCD slots take further clusters, so that
-  // a small batch still spreads over all eight XCDs.
-  const int xcd = blockIdx.x & 7, u3 = blockIdx.y;
-  const int cl = ((blockIdx.x >> 3) << (3 - p.lgX)) + (xcd >> p.lgX);
-  const int ntq = (xcd & ((1 << p.lgX) - 1)) + (int(blockIdx.z) << p.lgX);
-  if (cl >= p.ncl || (ntq << (2 - lgS)) >= p.ntiles) return;
+  WgCoord wg;
+  if (!wg_coord(p, &wg)) return;
+  const int cl = wg.cl, u3 = wg.u3, ntq = wg.ntq;
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
   // byte offset of the wave's first column in a row of I (fused convolution: the lane's own
@@ -700,23 +697,21 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.lgS = lgS;
   const int64_t tiles_per_wg = 4 >> lgS;
   const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-  int lgX = 3;   // groups of column tiles dealt to the XCDs side by side: the power of two >= nquads, at most 8
-  while (lgX > 0 && (int64_t(1) << (lgX - 1)) >= nquads) --lgX;
-  const int64_t qgroups = (nquads + (int64_t(1) << lgX) - 1) >> lgX;
-  const int64_t xgroups = (ncl + (8 >> lgX) - 1) / (8 >> lgX);
-  if (qgroups > 65535 || m->a[2] > 65535) return RBGP_EUNSUPPORTED;
-  rp.lgX = lgX;
+  // one-dimensional grid, items dealt to the XCDs in blocks (see RegParams)
+  // (measured on one box, us: conv5 18.0 / 18.2 / 18.2 with order 1 / 0 / 2; conv3 bf16 20.2 / 17.8 / 17.6; WRN 90.9 / 76.4 / 75.9)
+  rp.order = (m->e[2] == 1 && nquads <= 64) ? 1 : nquads >= 8 ? 2 : 0;
+  const int64_t items = int64_t(ncl) * m->a[2] * nquads;
+  const int64_t per_xcd = rp.order == 2 ? int64_t(ncl) * m->a[2] * ((nquads + 7) / 8) : (items + 7) / 8;
+  if (per_xcd * 8 > 0x7fffffff) return RBGP_EUNSUPPORTED;
   rp.ncl = ncl;
+  rp.per_xcd = int(per_xcd);
+  rp.ngroups = int(nquads);
   reg_fn fn = dual ? nullptr : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : e->global_fn;
   if (!fn && !dual) return RBGP_EUNSUPPORTED;
   if (lds > 64 * 1024 && fn)   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                  int(lds)));
   if (dual) {
-    // one-dimensional grid: XCD = id & 7 takes a block of the (G_i vertex, pair of column tiles) units
-    const int64_t units = int64_t(m->a[2]) * nquads, per_xcd = (units + 7) / 8;
-    if (per_xcd * ncl * 8 > 0x7fffffff || per_xcd > 0x7fffffff) return RBGP_EUNSUPPORTED;
-    rp.lgX = int(per_xcd);
     DualParams dq;
     dq.r = rp;
     const rbgp_reg_dual &du = m->reg_dual;
@@ -746,9 +741,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     }
     dq.tab = *dtab;
     rbgp_dual_fn dfn = rbgp_reg_dual_kernel(pl.KC);
-    hipLaunchKernelGGL(dfn, dim3(unsigned(8 * per_xcd * ncl)), dim3(512), lds, static_cast<hipStream_t>(stream), dq);
+    hipLaunchKernelGGL(dfn, dim3(unsigned(8 * per_xcd)), dim3(512), lds, static_cast<hipStream_t>(stream), dq);
   } else {
-    hipLaunchKernelGGL(fn, dim3(unsigned(8 * xgroups), unsigned(m->a[2]), unsigned(qgroups)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
+    hipLaunchKernelGGL(fn, dim3(unsigned(8 * per_xcd)), dim3(256), lds, static_cast<hipStream_t>(stream), rp);
   }
   RBGP_HIP(hipGetLastError());
   return RBGP_OK;

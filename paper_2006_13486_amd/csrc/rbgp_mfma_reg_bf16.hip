@@ -81,11 +81,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   const int wid = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   const int lgS = p.lgS, S = 1 << lgS;
   const int ks = wid & (S - 1);          // this wave's share of the stage list
-  // workgroup -> (XCD, cluster, G_i vertex, 4/S neighbouring column tiles); see the fp32 kernel
-  const int xcd = blockIdx.x & 7, u3 = blockIdx.y;
-  const int cl = ((blockIdx.x >> 3) << (3 - p.lgX)) + (xcd >> p.lgX);
-  if (cl >= p.ncl) return;               // (the whole workgroup)
-  const int ntq = (xcd & ((1 << p.lgX) - 1)) + (int(blockIdx.z) << p.lgX);
+  // workgroup -> (cluster, G_i vertex, 4/S neighbouring column tiles); see wg_coord
+  WgCoord wg;
+  if (!wg_coord(p, &wg)) return;         // (the whole workgroup)
+  const int cl = wg.cl, u3 = wg.u3, ntq = wg.ntq;
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const bool valid = nt < p.ntiles;
   if (lgS == 0 && !valid) return;        // (with S > 1 every wave reaches the barrier below)

@@ -41,19 +41,12 @@ __global__ __launch_bounds__(512) void spmm_reg_dual(DualParams dp) {
   // wave k: SIMD k & 3 = (column tile of the pair, x); y = k >> 2
   const int ct = (wid >> 1) & 1, x = wid & 1, y = wid >> 2;
 
-  // A workgroup is one (quad, G_i vertex) pair on two neighbouring column tiles, four waves each.
-  // Workgroups are dealt round-robin to the 8 XCDs, so workgroup id & 7 is the XCD, each with its own L2.
-  // The (G_i vertex, pair of column tiles) units are dealt to the XCDs in blocks, G_i vertex first:
-  // all readers of a piece of I (the quads) share an L2, and the rows an XCD reads are read over a wide
-  // contiguous span of columns.  (A narrow span -- one XCD per group of columns -- puts all of an XCD's
-  // traffic on the few L2 and memory channels that the span's addresses select in every row.)
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int cl = slot % p.ncl;
-  const int wu = xcd * p.lgX + slot / p.ncl;   // (lgX: units per XCD)
-  const int npairs = (p.ntiles + 1) >> 1;
-  if (wu >= p.a3 * npairs) return;   // (the whole workgroup leaves)
-  const int u3 = wu / npairs;
-  const int nt = ((wu % npairs) << 1) + ct;
+  // A workgroup is one (quad, G_i vertex) pair on two neighbouring column tiles, four waves each (see wg_coord
+  // for how the workgroups map to the XCDs).
+  WgCoord wg;
+  if (!wg_coord(p, &wg)) return;   // (the whole workgroup leaves)
+  const int cl = wg.cl, u3 = wg.u3;
+  const int nt = (wg.ntq << 1) + ct;
   const int64_t n0 = int64_t(nt) * CW;
   const uint32_t n0b = p.conv ? 0u : uint32_t(nt) * uint32_t(CW * 4);
   const int g = lane >> 4, j = lane & 15;

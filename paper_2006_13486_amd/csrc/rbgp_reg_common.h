@@ -64,12 +64,53 @@ struct RegParams {
   int tm;                  // rows of one tile row: a_r * a_i * a_b
   int ntiles;              // column tiles: ceil(N / columns per wave)
   int lgS;                 // log2 of the waves that share a column tile (split of the stage list)
-  int lgX, ncl;            // eight consecutive workgroups (one per XCD) = 2^lgX groups of column tiles x 8 / 2^lgX clusters;
-                           //   number of clusters
+  int ncl;                 // clusters of tile rows (pairing kernel: quads)
+  // Workgroups (one-dimensional grid) are dealt round-robin to the 8 XCDs, so workgroup id & 7 is the XCD, each with
+  // its own L2; within an XCD they start in the order of their ids.  A unit is a (G_i vertex, group of column
+  // tiles) pair; the clusters of a unit are always neighbours on one XCD (they read the same rows of I).  order:
+  //  2  column group g on XCD g & 7, all G_i vertices of a column group together: the workgroups that run at the same
+  //     time read neighbouring columns on all eight XCDs (long runs of every row of I are wanted at once, which the
+  //     memory likes), and G_i vertices that share rows of I share an L2.  For batches of at least 8 column groups.
+  //  1  the units in (G_i vertex, column group) order, dealt to the XCDs in blocks of per_xcd items: an XCD reads one
+  //     wide contiguous span of the rows of its G_i vertices.  Where every row of I belongs to one G_i vertex (right
+  //     degree 1) and the batch is a few dozen column groups: on the VGG19 conv5 shape the XCDs then finish
+  //     together, with order 2 every other XCD ran 1.4 us longer.
+  //  0  as 1 in (column group, G_i vertex) order: small batches whose G_i vertices share rows of I.
+  int per_xcd;             // items (cluster, unit) per XCD
+  int ngroups;             // groups of column tiles (one group per workgroup)
+  int order;
 };
 
 constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 constexpr int kOob = 0x40000000;        // byte offset beyond any packed weight buffer (reads return 0)
+
+// (cluster, G_i vertex, group of column tiles) of this workgroup; false: none (the workgroup leaves)
+struct WgCoord {
+  int cl, u3, ntq;
+};
+__device__ __forceinline__ bool wg_coord(const RegParams &p, WgCoord *c) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  if (p.order == 2) {
+    const int per_group = p.ncl * p.a3, q = slot / per_group, rem = slot - q * per_group;
+    c->ntq = xcd + 8 * q;
+    if (c->ntq >= p.ngroups) return false;
+    c->u3 = rem / p.ncl;
+    c->cl = rem - c->u3 * p.ncl;
+    return true;
+  }
+  const int item = xcd * p.per_xcd + slot;
+  if (item >= p.ncl * p.a3 * p.ngroups) return false;
+  const int unit = item / p.ncl;
+  c->cl = item - unit * p.ncl;
+  if (p.order == 1) {
+    c->u3 = unit / p.ngroups;
+    c->ntq = unit - c->u3 * p.ngroups;
+  } else {
+    c->ntq = unit / p.a3;
+    c->u3 = unit - c->ntq * p.a3;
+  }
+  return true;
+}
 
 __device__ __forceinline__ f32x4 load_x4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
   const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
