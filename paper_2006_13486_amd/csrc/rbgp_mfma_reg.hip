@@ -65,8 +65,11 @@ namespace {
 // 3p+1, 3p+2 of a lane group are the taps dx = -1, 0, +1 of one (channel, dy) pair, i.e. three
 // windows of the same pixel row shifted by one pixel.  Only the middle one is loaded; the other
 // two are put together from it and the neighbouring lane's pixel (DPP), zero at an image border.
+// Stages of 8 steps make short waves (a transposed 3x3 layer: 64 MFMAs per wave) whose time is mostly
+// latency; four of them per SIMD (<= 128 registers, which the compiler meets without spilling) instead
+// of the three it would otherwise leave room for: the conv5 backward data product 32 -> 29 us.
 template <int KC, int RS, bool TAPS = false>
-__global__ __launch_bounds__(256) void spmm_reg(RegParams p) {
+__global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) {
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
