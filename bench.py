@@ -446,6 +446,9 @@ def main():
                          "cols_per_workgroup,groups_per_workgroup,row_pairing,row_groups,k_split")
     ap.add_argument("--kernel", type=int, default=rb.KERNEL_AUTO)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cache-resident", action="store_true",
+                    help="skip the extra leg that times the same call on one buffer set (for profiles: the kernel trace of the "
+                         "run then holds launches with I in HBM only)")
     ap.add_argument("--no-sweep-sums", action="store_true",
                     help="leave the summed VGG19 layer times (16 layers x 4 densities x 2 dtypes) out of the line")
     ap.add_argument("--ld-pad", type=int, default=0,
@@ -593,17 +596,19 @@ def main():
     settled_ms = ev2.elapsed_time(ev3) / settled_steps
     # and with one buffer set only: I then comes out of the 256 MB last-level cache, as it would behind a
     # layer that has just written it, instead of from HBM (reported beside the headline, never as it)
-    nsets_all, nsets = nsets, 1
-    ev4, ev5 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for i in range(200):
-        step(i)
-    ev4.record()
-    for i in range(settled_steps):
-        step(i)
-    ev5.record()
-    torch.cuda.synchronize()
-    resident_ms = ev4.elapsed_time(ev5) / settled_steps
-    nsets = nsets_all
+    resident_ms = None
+    if not args.no_cache_resident:
+        nsets_all, nsets = nsets, 1
+        ev4, ev5 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(200):
+            step(i)
+        ev4.record()
+        for i in range(settled_steps):
+            step(i)
+        ev5.record()
+        torch.cuda.synchronize()
+        resident_ms = ev4.elapsed_time(ev5) / settled_steps
+        nsets = nsets_all
 
     value = w.flops / (ms_per_step * 1e-3) / 1e12
     bound = BOUND[args.workload]
