@@ -77,12 +77,20 @@ enum {
   RBGP_KERNEL_MFMA = 2,     /* RBGP4 masks: I tiles staged in LDS, MFMA on the dense blocks */
   RBGP_KERNEL_MFMA_REG = 3, /* RBGP4 masks: I rows streamed into registers and reused across a
                                cluster of tile rows, 16-row MFMA on the dense blocks */
-  RBGP_KERNEL_MFMA_TILE = 4 /* bf16 modes only, never chosen by AUTO: every nonzero of G_o as a dense
+  RBGP_KERNEL_MFMA_TILE = 4,/* bf16 modes only, never chosen by AUTO: every nonzero of G_o as a dense
                                block of W_s (zeros where the inner graphs have no edge), I staged in
                                LDS once per workgroup, 32-row MFMA.  Any inner graphs; needs
                                |G_r.U| |G_i.U| |G_b.U| = 32 and |G_r.V| |G_i.V| |G_b.V| <= 320.
                                rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8,
                                rbgp_conv3x3 an image width that is a multiple of 8 (ESHAPE) */
+  RBGP_KERNEL_MFMA_REG_FILLED = 5 /* the RBGP_KERNEL_MFMA_REG kernels on the mask with G_i filled in: the
+                               packed buffer stores a zero wherever G_i has no edge, so all
+                               |G_r.U| |G_i.U| |G_b.U| rows of a tile share one column set (row repetition,
+                               Section 5, bought with multiplied zeros: |G_i.V| / d_i times the products).
+                               For masks with few rows per column set (|G_r.U| |G_b.U| <= 4, the slow rows
+                               of Table 3) and a moderately sparse G_i; AUTO takes it where it estimates
+                               it faster, never for masks whose G_b is the nine taps of a 3x3
+                               convolution (rbgp_conv3x3 does not run on it) */
 };
 
 /* tuning knobs (rbgp_mask_tune) */
@@ -365,7 +373,8 @@ int rbgp_mask_original_order(const rbgp_mask_t *derived, int32_t *out);
  * the stage lists; tile-by-tile pairing (RBGP_TUNE_ROW_PAIRING = 2; all 0 where it does not apply):
  * [7] = quads of tile rows, [8] = most stages on one SIMD (two waves), [9] = sum of the stage lists,
  * [10] = longest stage list of a wave, [11] / [12] = distinct stages of I wanted by the first / the first
- * two stages of all waves together.  [13..15] = 0. */
+ * two stages of all waves together.  [13] = longest stage list on the mask with G_i filled in
+ * (RBGP_KERNEL_MFMA_REG_FILLED; 0: not available for this mask).  [14..15] = 0. */
 int rbgp_mask_reg_plan(const rbgp_mask_t *mask, int32_t info[16]);
 
 /* Host-only self check of the index tables the RBGP_KERNEL_MFMA_REG kernels read for this mask: every

@@ -383,7 +383,45 @@ bool mfma_covers(const rbgp_mask *m) {
 // AUTO: the register-streaming family where it covers the mask (measured faster than the
 // LDS family on every VGG19 layer shape, also where several G_i vertices share a row of I),
 // else the LDS family, else GENERIC.
+// Estimated seconds per column of I: one of 1024 SIMDs at ~2.07 GHz serves 64 columns per instruction.  The
+// constants are fitted to the 4096^3 products of Tables 2 and 3 (27 masks, each on every family that covers it).
+// Register family: a wave walks the stages of its (cluster, G_i vertex) pair; a stage of KC steps costs KC 16-row
+// MFMAs of ~36 cycles (fp32) or ~10.5 cycles per step of the 32-step bf16 forms, plus what does not overlap.
+double reg_seconds(const rbgp_mask *m, bool bf16) {
+  const rbgp_reg_clusters &cl = m->reg_clusters;
+  int64_t walked = 0;
+  for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
+  const double stage = bf16 ? 150.0 + 10.5 * m->reg.KC : 110.0 + 36.0 * m->reg.KC;
+  return double(walked) * m->a[2] * stage / (64.0 * 1024.0 * 2.07e9);
+}
+// LDS-staged family (fp32 MFMA for both dtypes): a wave walks (tile, column of G_r) steps of RB * KS 4-row MFMAs,
+// ~11.5 cycles each (the LDS read that feeds it) + ~95 cycles per step.
+double lds_seconds(const rbgp_mask *m) {
+  const double steps = double(m->a[0]) * m->d[0] * m->c[1] * m->a[2];
+  return steps * (11.5 * m->plan.RB * m->plan.KS + 95.0) / (64.0 * 1024.0 * 2.07e9);
+}
+double hbm_seconds(const rbgp_mask *m) { return double(m->M + m->K) * 4.0 / 5.0e12; }
+
+int resolve_kernel_unfilled(const rbgp_mask *m, rbgp_dtype_t dtype);
+
+// AUTO, last step: the register family on the mask with G_i filled in where that is estimated faster than the
+// family chosen for the mask itself and the product is not waiting for HBM anyway.  Measured on the 4096^3
+// products of Table 3, fp32 (us): one row per column set 1538 / 848 / 833 on the register family and 2054 / 1383 /
+// 1178 on the LDS family -> 680 / 667 / 660 at densities 1/4, 1/8, 1/16; two rows 837 -> 680 at 1/4 (470 and 455 at
+// 1/8 and 1/16 stay on the register family); four rows stay (595 against 694).  bf16: also Table 2's cells with a
+// half-full G_i (G_o at 1/8: 128 -> 67 us).
 int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
+  if (m->kernel_choice == RBGP_KERNEL_MFMA_REG_FILLED) return m->filled ? RBGP_KERNEL_MFMA_REG_FILLED : RBGP_KERNEL_GENERIC;
+  const int k0 = resolve_kernel_unfilled(m, dtype);
+  if (m->kernel_choice != RBGP_KERNEL_AUTO || !m->filled) return k0;
+  if (m->c[3] == 9 && m->d[3] == 9) return k0;   // (the mask of a lowered 3x3 convolution: rbgp_conv3x3 needs its own layout)
+  if (k0 == RBGP_KERNEL_GENERIC) return RBGP_KERNEL_MFMA_REG_FILLED;
+  const bool bf16 = bf16_in(dtype);
+  const double t0 = k0 == RBGP_KERNEL_MFMA ? lds_seconds(m) : reg_seconds(m, bf16);
+  return t0 > 2.0 * hbm_seconds(m) && reg_seconds(m->filled, bf16) < t0 ? RBGP_KERNEL_MFMA_REG_FILLED : k0;
+}
+
+int resolve_kernel_unfilled(const rbgp_mask *m, rbgp_dtype_t dtype) {
   const bool reg_ok = rbgp_reg_covers(m);
   // (the tile family has bf16 kernels only: fp32 calls on such a mask take the default choice)
   if (m->kernel_choice == RBGP_KERNEL_MFMA_TILE && bf16_in(dtype) && rbgp_plan_tile(m).ok) return RBGP_KERNEL_MFMA_TILE;
@@ -399,19 +437,14 @@ int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
     // where G_o is so sparse that the tile rows of a cluster share few tiles, most of those MFMA
     // rows are padding.  That costs nothing while the product waits for HBM (WRN-40-4 group 1:
     // 25 % useful rows, still the faster family) and decides where the matrix core is the bound
-    // (the 4096^3 SDMM of Table 2 with G_o at 1/8: 29 % useful rows, 253 us against 148 us on the
-    // LDS family, which has no clusters).  Estimate both times per column of I: an MFMA of a stage
-    // step serves 64 columns and issues every ~36 cycles on one of 1024 SIMDs at ~2.07 GHz; HBM
-    // streams ~5 TB/s.
-    const rbgp_reg_clusters &cl = m->reg_clusters;
-    int64_t walked = 0;
-    for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
-    const double useful = double(m->reg.TR) * m->d[0] * m->reg.NSTG / (double(walked) * m->reg.MG);
-    const double t_mfma = double(walked) * m->a[2] * m->reg.KC * 36.0 / (64.0 * 1024.0 * 2.07e9);
-    const double t_hbm = double(m->M + m->K) * 4.0 / 5.0e12;
-    // (VGG19 layers at density 1/16 with 27-42 % useful rows and t_mfma up to 1.3 t_hbm are still faster
-    // on the register family; the SDMM above has t_mfma = 8 t_hbm)
-    return useful < 0.45 && t_mfma > 4.0 * t_hbm ? RBGP_KERNEL_MFMA : RBGP_KERNEL_MFMA_REG;
+    // (the 4096^3 SDMM of Table 2 with G_o at 1/8: 29 % useful rows, 305 us against 177 us on the
+    // LDS family, which has no clusters; with G_o complete 454 against 751).  So: the register
+    // family unless its estimated time is both well above the HBM time of the product (HBM streams
+    // ~5 TB/s) and above the LDS family's.
+    // (VGG19 layers at density 1/16 with 27-42 % useful rows and an estimate up to 1.3 x the HBM time are
+    // still faster on the register family, as is every other cell of that sweep.)
+    const double t_reg = reg_seconds(m, bf16_in(dtype));
+    return t_reg > 4.0 * hbm_seconds(m) && lds_seconds(m) < t_reg ? RBGP_KERNEL_MFMA : RBGP_KERNEL_MFMA_REG;
   }
   if (reg_ok) return RBGP_KERNEL_MFMA_REG;
   return lds_ok ? RBGP_KERNEL_MFMA : RBGP_KERNEL_GENERIC;
@@ -421,6 +454,8 @@ int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
   if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
   if (kernel == RBGP_KERNEL_MFMA_TILE) return rbgp_plan_tile(m).packed_elems;
   if (kernel == RBGP_KERNEL_MFMA_REG) return bf16_in(dtype) ? m->reg.packed_elems_bf16 : m->reg.packed_elems;
+  if (kernel == RBGP_KERNEL_MFMA_REG_FILLED)
+    return bf16_in(dtype) ? m->filled->reg.packed_elems_bf16 : m->filled->reg.packed_elems;
   return m->nnz;
 }
 
@@ -488,6 +523,7 @@ int rbgp_mask_set_kernel(rbgp_mask_t *m, int kernel) {
   if (kernel == RBGP_KERNEL_MFMA && !mfma_covers(m)) return RBGP_EUNSUPPORTED;
   if (kernel == RBGP_KERNEL_MFMA_REG && !rbgp_reg_covers(m)) return RBGP_EUNSUPPORTED;
   if (kernel == RBGP_KERNEL_MFMA_TILE && !rbgp_plan_tile(m).ok) return RBGP_EUNSUPPORTED;
+  if (kernel == RBGP_KERNEL_MFMA_REG_FILLED && !m->filled) return RBGP_EUNSUPPORTED;
   m->kernel_choice = kernel;
   return RBGP_OK;
 }
@@ -673,6 +709,13 @@ static int spmm_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_
   if (kernel == RBGP_KERNEL_MFMA_REG)
     return rbgp_reg_launch(m, &dev->reg_state, dev->tune, bf16, out_bf16, N, dev_packed, dev_I, ldI, dev_O, ldO,
                            hip_stream);
+
+  if (kernel == RBGP_KERNEL_MFMA_REG_FILLED) {   // the same kernels on the filled mask (its own tables, this mask's knobs)
+    rc = ensure_device(m->filled);
+    if (rc) return rc;
+    return rbgp_reg_launch(m->filled, &m->filled->dev->reg_state, dev->tune, bf16, out_bf16, N, dev_packed, dev_I, ldI,
+                           dev_O, ldO, hip_stream);
+  }
 
   if (kernel == RBGP_KERNEL_MFMA_TILE)
     return rbgp_tile_launch(m, &dev->tile_state, out_bf16, N, dev_packed, dev_I, ldI, dev_O, ldO, hip_stream);

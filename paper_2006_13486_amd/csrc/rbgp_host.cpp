@@ -324,6 +324,56 @@ void rbgp_plan_reg(rbgp_mask *m) {
   rbgp_reg_plan_dual(m, &m->reg_dual);
 }
 
+// The mask with G_i filled in, for RBGP_KERNEL_MFMA_REG_FILLED.  G_r (x) G_i with both complete is the complete
+// graph on their vertices, so the filled mask is G_o (x) J(a_r a_i, c_r c_i) (x) J(1, 1) (x) G_b: a four-factor mask
+// of the same family with the same row and column numbering (Kronecker ordering), every kept position of this
+// mask among its own.  Its a_r a_i a_b rows per tile row share one column set, which is what the 16-row MFMA
+// groups of the register family want; the price is a zero stored and multiplied wherever G_i has no edge.
+// Built only where that can pay: few rows per column set here (<= 4), a sparse G_i, and a filled mask the
+// register family covers.
+void rbgp_plan_filled(rbgp_mask *m) {
+  m->filled = nullptr;
+  const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
+  if (!roles || m->d[2] == m->c[2] || int64_t(m->a[1]) * m->a[3] > 4) return;
+  const int64_t ar = int64_t(m->a[1]) * m->a[2], cr = int64_t(m->c[1]) * m->c[2];
+  const int64_t rowdeg = int64_t(m->d[0]) * cr * m->c[3];
+  if (ar > (1 << 20) || cr > (1 << 20) || m->M * rowdeg >= (int64_t(1) << 31)) return;
+  rbgp_mask *t = new rbgp_mask();
+  try {
+    const int32_t a[4] = {m->a[0], int32_t(ar), 1, m->a[3]}, c[4] = {m->c[0], int32_t(cr), 1, m->c[3]};
+    for (int i = 0; i < 4; ++i) {
+      t->a[i] = a[i]; t->c[i] = c[i];
+      t->d[i] = i == 0 ? m->d[0] : c[i];
+      t->e[i] = i == 0 ? m->e[0] : a[i];
+      t->sigma1[i] = i == 0 ? m->sigma1[0] : std::sqrt(double(a[i]) * c[i]);
+      t->sigma2[i] = i == 0 ? m->sigma2[0] : 0.0;
+      t->bound[i] = i == 0 ? m->bound[0] : std::sqrt(double(t->d[i] - 1)) + std::sqrt(double(t->e[i] - 1));
+      t->status[i] = i == 0 ? m->status[0] : RBGP_SPEC_COMPLETE;
+      t->tries[i] = 0;
+    }
+    t->adj[0] = m->adj[0];
+    for (int i = 1; i < 4; ++i) {
+      t->adj[i].resize(size_t(a[i]) * c[i]);
+      for (int u = 0; u < a[i]; ++u)
+        for (int v = 0; v < c[i]; ++v) t->adj[i][size_t(u) * c[i] + v] = v;
+    }
+    t->M = m->M; t->K = m->K; t->rowdeg = rowdeg; t->coldeg = int64_t(m->e[0]) * ar * m->a[3]; t->nnz = m->M * rowdeg;
+    t->kernel_choice = RBGP_KERNEL_MFMA_REG;
+    t->uid = rbgp_next_uid();
+    t->dev = nullptr;
+    rbgp_plan_mfma(t);
+    rbgp_plan_reg(t);
+    if (!rbgp_reg_covers(t) || t->reg.packed_elems * 4 > (int64_t(1) << 30)) {
+      delete t;
+      return;
+    }
+  } catch (...) {
+    delete t;
+    throw;
+  }
+  m->filled = t;
+}
+
 // Register-streaming family: group the tile rows into clusters of U whose adjacency lists
 // overlap most (greedy: seed with the lowest free tile row, add the free row that enlarges
 // the union of tiles least; then local search, and exhaustive matching for pairs), and
@@ -437,7 +487,19 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
     members = best;
   }
   std::vector<int32_t> counts(ncl, 0);
-  std::vector<int32_t> stages(size_t(ncl) * (1 + U) * 64, -1);
+  int longest = 0;
+  for (int c = 0; c < ncl; ++c) {
+    int tiles = 0;
+    for (int v1 = 0; v1 < c1; ++v1) {
+      bool any = false;
+      for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v1];
+      tiles += any;
+    }
+    longest = std::max(longest, tiles * pl.NSTG);
+  }
+  const int TS = longest > kRegWaveStages ? 256 : 64;
+  const int stored = TS == 64 ? kRegWaveStages : kRegMaxStages;   // (the entries behind them stay -1: sentinels)
+  std::vector<int32_t> stages(size_t(ncl) * (1 + U) * TS, -1);
   for (int c = 0; c < ncl; ++c) {
     int st = 0;
     for (int v1 = 0; v1 < c1; ++v1) {
@@ -445,15 +507,15 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
       for (int k = 0; k < U; ++k) any |= members[size_t(c) * U + k] >= 0 && has[members[size_t(c) * U + k]][v1];
       if (!any) continue;
       for (int sg = 0; sg < pl.NSTG; ++sg, ++st) {
-        if (st >= 60) continue;   // does not fit the per-lane table: counted, not stored
-        stages[(size_t(c) * (1 + U)) * 64 + st] =
+        if (st >= stored) continue;   // does not fit the table: counted, not stored
+        stages[(size_t(c) * (1 + U)) * TS + st] =
             int32_t((int64_t(v1) * m->c[1] + int64_t(sg) * pl.VC) * m->c[2] * m->c[3]);
         for (int k = 0; k < U; ++k) {
           const int u1 = members[size_t(c) * U + k];
           if (u1 < 0 || !has[u1][v1]) continue;
           int j1 = 0;
           while (m->adj[0][size_t(u1 / pl.fold) * d1 + j1] != v1) ++j1;
-          stages[(size_t(c) * (1 + U) + 1 + k) * 64 + st] = j1 * pl.NSTG + sg;
+          stages[(size_t(c) * (1 + U) + 1 + k) * TS + st] = j1 * pl.NSTG + sg;
         }
       }
     }
@@ -461,6 +523,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
   }
   out->U = U;
   out->ncl = ncl;
+  out->tstride = TS;
   out->max_stages = 0;
   for (int c = 0; c < ncl; ++c) out->max_stages = std::max(out->max_stages, int(counts[c]));
   out->members.swap(members);
@@ -659,6 +722,25 @@ void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
 //           32 and at kk = 32q + 4g + e (e < 4; the rest is padding) in the block of 16:
 //           the consecutive contraction steps one lane feeds to the matrix core.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
+  if (kernel == RBGP_KERNEL_MFMA_REG_FILLED) {
+    // the register family's layout of the filled mask; a position that holds kept value (row, (j_o, v_r, v_i, v_b))
+    // of the filled mask takes this mask's value at (j_o, v_r, j_i, v_b) where v_i = adj_i[u_i][j_i], else a zero
+    const rbgp_mask *t = m->filled;
+    rbgp_build_pack_perm(t, RBGP_KERNEL_MFMA_REG, bf16, perm);
+    std::vector<int32_t> where(size_t(m->a[2]) * m->c[2], -1);   // where[u_i * c_i + v_i]: position of v_i in adj_i[u_i]
+    for (int u = 0; u < m->a[2]; ++u)
+      for (int j = 0; j < m->d[2]; ++j) where[size_t(u) * m->c[2] + m->adj[2][size_t(u) * m->d[2] + j]] = j;
+    const int64_t c2 = m->c[2], c3 = m->c[3], crf = int64_t(m->c[1]) * c2;
+    for (int32_t &s : perm) {
+      if (s < 0) continue;
+      const int64_t row = s / t->rowdeg, tt = s % t->rowdeg;
+      const int64_t v4 = tt % c3, vr = (tt / c3) % crf, j1 = tt / (c3 * crf);
+      const int64_t v2 = vr / c2, v3 = vr % c2, u3 = (row / m->a[3]) % m->a[2];
+      const int j3 = where[size_t(u3 * c2 + v3)];
+      s = j3 < 0 ? -1 : int32_t(row * m->rowdeg + ((j1 * m->c[1] + v2) * m->d[2] + j3) * c3 + v4);
+    }
+    return;
+  }
   if (kernel == RBGP_KERNEL_MFMA_TILE) {
     // [u_o][j_o][c][h][row][e]: element e = 0..7 is the weight of row `row` of the tile at tile column
     // 16c + 8h + e (the eight consecutive contraction steps one lane feeds to a 16-step MFMA); tile column
@@ -914,6 +996,7 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
   m->dev = nullptr;
   rbgp_plan_mfma(m);
   rbgp_plan_reg(m);
+  rbgp_plan_filled(m);
   *out = m;
   return RBGP_OK;
 }
@@ -1035,6 +1118,7 @@ int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
     t->dev = nullptr;
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
+    rbgp_plan_filled(t);
   } catch (const std::bad_alloc &) {
     delete t;
     return RBGP_ENOMEM;
@@ -1114,6 +1198,7 @@ int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
     t->dev = nullptr;
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
+    rbgp_plan_filled(t);
   } catch (const std::bad_alloc &) {
     delete t;
     return RBGP_ENOMEM;
@@ -1135,6 +1220,7 @@ int rbgp_mask_original_order(const rbgp_mask_t *m, int32_t *out) {
 void rbgp_mask_free(rbgp_mask_t *mask) {
   if (!mask) return;
   if (mask->dev) rbgp_device_release(mask->dev);
+  if (mask->filled) rbgp_mask_free(mask->filled);
   delete mask;
 }
 
@@ -1214,6 +1300,7 @@ int rbgp_mask_dense(const rbgp_mask_t *m, uint8_t *out) {
 static int mask_reg_plan_impl(const rbgp_mask_t *m, int32_t info[16]) {
   if (!m || !info) return RBGP_EINVAL;
   for (int i = 0; i < 16; ++i) info[i] = 0;
+  if (m->filled) info[13] = m->filled->reg_clusters.max_stages;
   const rbgp_reg_plan &p = m->reg;
   if (!p.ok) return RBGP_OK;
   info[0] = p.MG; info[1] = p.NSTG; info[2] = p.KC; info[3] = p.TR;
@@ -1246,6 +1333,25 @@ int rbgp_mask_reg_plan(const rbgp_mask_t *m, int32_t info[16]) {
 // their per-lane tables and end in sentinels.
 int rbgp_mask_check_tables(const rbgp_mask_t *m) {
   if (!m) return RBGP_EINVAL;
+  if (m->filled) {   // the filled mask has tables of its own, and its packed layout must hold every kept value once
+    const int rc = rbgp_mask_check_tables(m->filled);
+    if (rc) return rc;
+    try {
+      for (bool bf16 : {false, true}) {
+        std::vector<int32_t> perm;
+        rbgp_build_pack_perm(m, RBGP_KERNEL_MFMA_REG_FILLED, bf16, perm);
+        std::vector<char> seen(size_t(m->nnz), 0);
+        for (int32_t s : perm) {
+          if (s < -1 || s >= m->nnz) return RBGP_EINTERNAL;
+          if (s >= 0 && seen[size_t(s)]++) return RBGP_EINTERNAL;
+        }
+        for (char c : seen)
+          if (!c) return RBGP_EINTERNAL;
+      }
+    } catch (const std::bad_alloc &) {
+      return RBGP_ENOMEM;
+    }
+  }
   const rbgp_reg_plan &p = m->reg;
   if (!p.ok) return RBGP_OK;
   try {
@@ -1264,15 +1370,18 @@ int rbgp_mask_check_tables(const rbgp_mask_t *m) {
     {
       const rbgp_reg_clusters &cl = m->reg_clusters;
       std::vector<int> used(size_t(p.TR) * fpm, 0);
-      if (cl.max_stages <= 60) {
+      if (cl.max_stages <= kRegMaxStages) {
+        const int TS = cl.tstride;
+        if (TS != (cl.max_stages > kRegWaveStages ? 256 : 64)) return RBGP_EINTERNAL;
+        if (cl.stages.size() != size_t(cl.ncl) * (1 + cl.U) * TS) return RBGP_EINTERNAL;
         for (int c = 0; c < cl.ncl; ++c) {
           const int n = cl.counts[size_t(c)];
-          if (n < 0 || n > 60) return RBGP_EINTERNAL;
-          for (int st = 0; st < 64; ++st) {
-            const int32_t base = cl.stages[(size_t(c) * (1 + cl.U)) * 64 + st];
+          if (n < 0 || n > cl.max_stages) return RBGP_EINTERNAL;
+          for (int st = 0; st < TS; ++st) {
+            const int32_t base = cl.stages[(size_t(c) * (1 + cl.U)) * TS + st];
             if ((st < n) != (base >= 0)) return RBGP_EINTERNAL;
             for (int k = 0; k < cl.U; ++k) {
-              const int32_t f = cl.stages[(size_t(c) * (1 + cl.U) + 1 + k) * 64 + st];
+              const int32_t f = cl.stages[(size_t(c) * (1 + cl.U) + 1 + k) * TS + st];
               if (st >= n && f != -1) return RBGP_EINTERNAL;
               if (f >= 0 && !check_use(used, cl.members[size_t(c) * cl.U + k], f, base)) return RBGP_EINTERNAL;
             }

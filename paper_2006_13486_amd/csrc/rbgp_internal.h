@@ -71,14 +71,21 @@ struct rbgp_reg_plan {
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m);
 inline int rbgp_reg_step(const rbgp_mask *m, int kk);
 
+// Register-streaming family: a wave keeps its stage list in a lane-held table, one stage per lane, with
+// sentinels behind it (60 stages); a cluster's list may be up to four times that and is then split over
+// the waves of a workgroup (wave k takes stages k, k + S, ...).
+constexpr int kRegWaveStages = 60, kRegMaxStages = 240;
+
 // Clustering of the tile rows for the register-streaming family (host tables).
 struct rbgp_reg_clusters {
   int U = 0;                      // tile rows per cluster
   int ncl = 0;
-  int max_stages = 0;             // longest stage list (the kernels hold at most 60)
+  int max_stages = 0;             // longest stage list (a wave holds at most 60 stages, one per lane; a longer list,
+                                  //   up to 240, is split over 2 or 4 waves of the workgroup)
+  int tstride = 64;               // entries per table row: 64, or 256 where a list exceeds 60 stages
   std::vector<int32_t> members;   // [ncl][U] tile rows, -1: none
-  std::vector<int32_t> stages;    // [ncl][1+U][64]: base row of I per stage, then per member the
-                                  //   position of its weight fragment (-1: member lacks the tile)
+  std::vector<int32_t> stages;    // [ncl][1+U][tstride]: base row of I per stage, then per member the
+                                  //   position of its weight fragment (-1: member lacks the tile); -1 past the end
   std::vector<int32_t> counts;    // [ncl] stages per cluster
 };
 
@@ -125,6 +132,9 @@ struct rbgp_mask {
   rbgp_reg_clusters reg_clusters;     // clusters of reg.MG tile rows (when reg.ok)
   rbgp_reg_dual reg_dual;             // lo/hi pairing (when reg.ok, reg.MG == 2 and at most 32 tile rows)
   mutable rbgp_device_state *dev;     // lazily created device tables
+  rbgp_mask *filled = nullptr;        // RBGP_KERNEL_MFMA_REG_FILLED: the mask G_o (x) J (x) G_b with G_r and G_i
+                                      //   replaced by the complete graph on their vertices (same M, K, same row and
+                                      //   column numbering; a superset of this mask), or nullptr; owned
 };
 
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m) {
@@ -138,7 +148,7 @@ inline int rbgp_reg_step(const rbgp_mask *m, int kk) {
   return (pair / 3) * 9 + 3 * dyi + dxi;
 }
 
-enum { RBGP_NUM_KERNELS = 5 };   // one more than the largest RBGP_KERNEL_* value
+enum { RBGP_NUM_KERNELS = 6 };   // one more than the largest RBGP_KERNEL_* value
 
 // Shape of the tile kernels (rbgp_mfma_tile.hip): every nonzero of G_o is a dense TM x TK block of W_s
 // (zero where the inner graphs have no edge), multiplied in 32-row blocks by 16-step MFMAs.
@@ -197,5 +207,7 @@ void rbgp_plan_mfma(rbgp_mask *m);
 void rbgp_plan_reg(rbgp_mask *m);
 void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out);
 void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out);
+// builds m->filled where the register family covers it (called once, when the mask is made)
+void rbgp_plan_filled(rbgp_mask *m);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm);

@@ -111,20 +111,20 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
   int rrow[NO];
 #pragma unroll
   for (int o = 0; o < NO; ++o) rrow[o] = rt[o * 4];
-  const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * 64 + lane;
+  // the wave's own stages, one per lane: stage ks + lane * S of the cluster's list
+  const int TS = p.tstride;
+  const int own = ks + (lane << lgS);
+  const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * TS + (own < TS ? own : TS - 1);
   const int tb = stg[0];
   int tf[MG];
 #pragma unroll
-  for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * 64];
+  for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * TS];
   const int cnt0 = p.counts[cl];
   const int cnt = cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0;   // stages of this wave
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * MG + (lane & (MG - 1))];
-  // table lane of the wave's s-th stage; lanes past the cluster's count hold sentinels
-  auto table_lane = [&](int s) {
-    const int gs = ks + (s << lgS);
-    return gs < 63 ? gs : 63;
-  };
+  // table lane of the wave's s-th stage; lanes past the wave's count hold sentinels
+  auto table_lane = [&](int s) { return s < 63 ? s : 63; };
 
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
   // past N read whatever follows inside I (or zeros past its end): they are never stored.
@@ -398,7 +398,7 @@ const RegEntry *find_reg(int KC, int RS) {
 }
 
 struct RegTables {  // device tables of the clustering
-  int ncl = 0;
+  int ncl = 0, tstride = 64, max_stages = 0;
   int32_t *stages = nullptr, *counts = nullptr, *members = nullptr;
 };
 
@@ -433,10 +433,13 @@ void free_tables(RegTables *t) {
 }
 
 // Upload three tables; the state is touched only when all three are on the device.
-int upload_tables(int ncl, const std::vector<int32_t> &stages, const std::vector<int32_t> &counts,
-                  const std::vector<int32_t> &members, RegTables *t) {
+int upload_tables(const rbgp_reg_clusters &cl, RegTables *t) {
+  const int ncl = cl.ncl;
+  const std::vector<int32_t> &stages = cl.stages, &counts = cl.counts, &members = cl.members;
   RegTables fresh;
   fresh.ncl = ncl;
+  fresh.tstride = cl.tstride;
+  fresh.max_stages = cl.max_stages;
   int rc = upload(stages, &fresh.stages);
   if (!rc) rc = upload(counts, &fresh.counts);
   if (!rc) rc = upload(members, &fresh.members);
@@ -456,8 +459,8 @@ int build_tables(const rbgp_mask *m, int U, RegTables *t) {
     rbgp_reg_cluster(m, U, &fresh);
     cl = &fresh;
   }
-  if (cl->max_stages > 60) return RBGP_EUNSUPPORTED;   // one stage per lane plus sentinels
-  return upload_tables(cl->ncl, cl->stages, cl->counts, cl->members, t);
+  if (cl->max_stages > kRegMaxStages) return RBGP_EUNSUPPORTED;   // one stage per lane plus sentinels, four waves
+  return upload_tables(*cl, t);
 }
 
 }  // namespace
@@ -466,7 +469,7 @@ bool rbgp_reg_covers(const rbgp_mask *m) {
   const rbgp_reg_plan &p = m->reg;
   if (!p.ok) return false;
   // every cluster's stage list must fit the per-lane table
-  if (m->reg_clusters.max_stages > 60) return false;
+  if (m->reg_clusters.max_stages > kRegMaxStages) return false;
   return find_reg(p.KC, p.RS) != nullptr;
 }
 
@@ -644,6 +647,15 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     int rc = build_tables(m, G * pl.MG, tab);
     if (rc) return rc;
   }
+  if (!dual) {
+    // a stage list longer than a wave's table is split over enough waves of the workgroup
+    int need = 0;
+    while ((kRegWaveStages << need) < tab->max_stages) ++need;
+    if (need > lgS) {
+      if (tune[RBGP_TUNE_K_SPLIT]) return RBGP_EUNSUPPORTED;
+      lgS = need;
+    }
+  }
   const int ncl = dual ? m->reg_dual.nq : tab->ncl;
   const int fpm = m->d[0] * pl.NSTG;
   // LDS: partial sums of the split -- per wave the (S - 1) / S of its 4G units it does not own; lo/hi pairing:
@@ -658,6 +670,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.obf16 = out_bf16 ? 1 : 0;
   rp.rowtab = *rowtab;
   rp.stages = dual ? nullptr : tab->stages; rp.counts = dual ? nullptr : tab->counts; rp.members = dual ? nullptr : tab->members;
+  rp.tstride = tab->tstride;
   rp.N = N; rp.ldI = ldI; rp.ldO = ldO;
   rp.w_bytes = uint32_t(w_bytes);
   rp.row_bytes = uint32_t(ldI * es);

@@ -108,11 +108,14 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) rrow[8 * NK32 + t] = rt[32 * NK32 + 4 * kg + t];
   }
-  const int32_t *stg = p.stages + int64_t(cl) * (1 + U) * 64 + lane;
+  // the wave's own stages, one per lane: stage ks + lane * S of the cluster's list
+  const int TS = p.tstride;
+  const int own = ks + (lane << lgS);
+  const int32_t *stg = p.stages + int64_t(cl) * (1 + U) * TS + (own < TS ? own : TS - 1);
   const int tb = stg[0];
   int tf[U];
 #pragma unroll
-  for (int mm = 0; mm < U; ++mm) tf[mm] = stg[(1 + mm) * 64];
+  for (int mm = 0; mm < U; ++mm) tf[mm] = stg[(1 + mm) * TS];
   const int cnt = p.counts[cl];
   const int cntw = cnt > ks ? (cnt - ks + S - 1) >> lgS : 0;   // stages of this wave
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
@@ -137,10 +140,7 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
       const_cast<void *>(static_cast<const void *>(p.Wp)), 0, p.w_bytes, kRsrcFlags);
   // table lane of the wave's s-th stage; lanes past the cluster's count hold sentinels
   // (base row -1 -> a descriptor of zero extent: zeros, no memory access)
-  auto table_lane = [&](int s) {
-    const int gs = ks + (s << lgS);
-    return gs < 63 ? gs : 63;
-  };
+  auto table_lane = [&](int s) { return s < 63 ? s : 63; };
   // Once per stage (= per table lane), with vector instructions: the start and extent of the
   // stage's part of I and the offset of each tile row's weights (see the fp32 kernel); the
   // loop only reads them back.  A tile row that lacks the tile reads past the end of the

@@ -38,11 +38,13 @@ struct RegParams {
   float *O;                // fp32, or bf16 bits when obf16 is set (ldO counts elements of that type)
   int obf16;               // bf16 kernels: round the sums to bf16 when storing O
   const int32_t *rowtab;   // [a_i][NO*4]: stage-relative I row of each contraction step (padding -> 0)
-  const int32_t *stages;   // [ncl][1+MG][64]: per stage (one per lane) the base row of the stage, then per
+  const int32_t *stages;   // [ncl][1+MG][tstride]: per stage the base row of the stage, then per
                            //   cluster member j_o * NSTG + (stage within the tile), the position of its
                            //   weight fragment among the member's fragments; -1 past the end (sentinel
-                           //   stages) and when the member does not have the tile
-  const int32_t *counts;   // [ncl] stages of each cluster (<= 60)
+                           //   stages) and when the member does not have the tile.  Wave k of the S that split a
+                           //   list holds stage k + l * S in lane l.
+  int tstride;             // 64, or 256 where a list has more than 60 stages (its last entry is always a sentinel)
+  const int32_t *counts;   // [ncl] stages of each cluster (<= 60 per wave: <= 60 * S)
   const int32_t *members;  // [ncl][MG] tile rows of each cluster (-1: none)
   int64_t N, ldI, ldO;
   uint32_t w_bytes;        // extent of the packed weights (buffer descriptor)

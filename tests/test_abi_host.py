@@ -200,7 +200,8 @@ LAYOUT_SHAPES = [
 
 
 @pytest.mark.parametrize("dtype", [rb.F32, rb.BF16_F32ACC])
-@pytest.mark.parametrize("kernel", [rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG, rb.KERNEL_MFMA_TILE])
+@pytest.mark.parametrize("kernel", [rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG, rb.KERNEL_MFMA_TILE,
+                                    rb.KERNEL_MFMA_REG_FILLED])
 @pytest.mark.parametrize("shape", LAYOUT_SHAPES, ids=lambda s: "x".join(map(str, s[0])))
 def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
     """Whatever the kernel family's layout, packing is a permutation of the kept values
@@ -223,6 +224,56 @@ def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
     assert np.all(layout[layout < 0] == -1)
     if rb.rbgp_mask_kernel(mask, dtype) == rb.KERNEL_GENERIC:
         assert np.array_equal(layout, np.arange(nnz, dtype=np.int32))     # canonical order itself
+
+
+@pytest.mark.parametrize("dtype", [rb.F32, rb.BF16_F32ACC])
+@pytest.mark.parametrize("shape", [((4, 2, 8, 1), (4, 3, 8, 1), (2, 3, 4, 1)), ((2, 1, 16, 4), (2, 1, 16, 2), (2, 1, 8, 2)),
+                                   ((4, 1, 8, 3), (8, 1, 8, 1), (2, 1, 2, 1))], ids=lambda s: "x".join(map(str, s[0])))
+def test_filled_layout_is_the_register_layout_of_the_mask_with_a_complete_g_i(shape, dtype):
+    """RBGP_KERNEL_MFMA_REG_FILLED stores the mask inside the layout of G_o (x) J (x) G_b.  That mask can be made
+    through the public call with the same seed (G_o is sampled first, from the seed and its own sizes alone), so
+    its register-family layout, carried over position by position through the (row, column) each kept value sits
+    at, must be the filled layout: this mask's value where it keeps the position, a zero elsewhere."""
+    rows, cols, deg = shape
+    mask = rb.rbgp_make_mask(rows, cols, deg, 9)
+    rb.rbgp_mask_set_kernel(mask, rb.KERNEL_MFMA_REG_FILLED)
+    full = rb.rbgp_make_mask((rows[0], rows[1] * rows[2], 1, rows[3]), (cols[0], cols[1] * cols[2], 1, cols[3]),
+                             (deg[0], cols[1] * cols[2], 1, cols[3]), 9)
+    rb.rbgp_mask_set_kernel(full, rb.KERNEL_MFMA_REG)
+    dense, dense_full = rb.rbgp_mask_dense(mask).astype(bool), rb.rbgp_mask_dense(full).astype(bool)
+    assert not np.any(dense & ~dense_full)                       # a superset, same numbering
+    M, K = dense.shape
+    index = np.full((M, K), -1, dtype=np.int64)                  # canonical index of every kept position
+    index[dense] = np.arange(dense.sum())                        # (row-major over kept positions = ascending columns per row)
+    cols_full = rb.rbgp_mask_columns(full).reshape(M, -1)
+    lay_full = rb.rbgp_pack_layout(full, dtype)
+    want = np.full(lay_full.shape, -1, dtype=np.int64)
+    keep = lay_full >= 0
+    r, t = np.divmod(lay_full[keep].astype(np.int64), cols_full.shape[1])
+    want[keep] = index[r, cols_full[r, t]]
+    assert np.array_equal(rb.rbgp_pack_layout(mask, dtype), want)
+    assert rb.rbgp_packed_bytes(mask, dtype) == rb.rbgp_packed_bytes(full, dtype)
+
+
+def test_automatic_choice_on_the_masks_of_tables_2_and_3():
+    """What RBGP_KERNEL_AUTO resolves to on the paper's 4096^3 masks (host-side estimate, fitted to measurements of
+    all 27 on every family): one row per column set -> G_i filled in; G_o complete -> register family with split
+    stage lists; G_o at 1/8 -> LDS family in fp32, filled in bf16; never the LDS family in bf16."""
+    k = lambda w, dt: rb.rbgp_mask_kernel(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed), dt)
+    for d in (2, 3, 4):
+        assert k(wl.sdmm4096_table3(1, 1, d), rb.F32) == rb.KERNEL_MFMA_REG_FILLED
+    assert k(wl.sdmm4096_table3(2, 1, 3), rb.F32) == rb.KERNEL_MFMA_REG
+    assert k(wl.sdmm4096_table3(4, 1, 2), rb.F32) == rb.KERNEL_MFMA
+    assert k(wl.sdmm4096_table2(0, 2), rb.F32) == rb.KERNEL_MFMA_REG
+    assert k(wl.sdmm4096_table2(3, 1), rb.F32) == rb.KERNEL_MFMA
+    assert k(wl.sdmm4096_table2(3, 1), rb.BF16_F32ACC) == rb.KERNEL_MFMA_REG_FILLED
+    for w in [wl.sdmm4096_table3(r, b, d) for (r, b) in ((1, 1), (2, 1), (4, 1), (2, 2)) for d in (2, 3, 4)]:
+        assert k(w, rb.BF16_F32ACC) != rb.KERNEL_MFMA
+    for w in wl.CONFIGS:                       # the fixed configurations stay where they were
+        assert k(w, w.dtype) == rb.KERNEL_MFMA_REG
+    # the mask of a lowered 3x3 convolution never takes the filled family by itself (rbgp_conv3x3 reads the register layout)
+    conv = rb.rbgp_make_mask((32, 1, 16, 1), (32, 1, 8, 9), (16, 1, 2, 9), 3)
+    assert rb.rbgp_mask_reg_plan(conv)[13] > 0 and rb.rbgp_mask_kernel(conv, rb.F32) != rb.KERNEL_MFMA_REG_FILLED
 
 
 def test_the_two_bf16_modes_share_kernel_choice_and_layout():

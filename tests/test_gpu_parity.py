@@ -13,6 +13,7 @@ from tests import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 GEN, MFMA, REG = rb.KERNEL_GENERIC, rb.KERNEL_MFMA, rb.KERNEL_MFMA_REG
+FILLED = rb.KERNEL_MFMA_REG_FILLED
 
 
 # ------------------------------------------------------------------ fixed configurations, full size
@@ -241,6 +242,9 @@ def test_shapes_across_the_kernel_table(idx, dtype):
     else:
         assert idx >= 9                       # the first nine shapes are inside the LDS family's table
     gh.check_parity(w, kernel=GEN)
+    if gh.family_covers(w, FILLED):           # few rows per column set and a sparse G_i: the mask with G_i filled in
+        gh.check_parity(w, kernel=FILLED, expect_kernel=FILLED)
+        gh.check_parity(w, kernel=FILLED, tune=(0, 0, 0, 0, 0, 2), ld_pad=8, expect_kernel=FILLED)
     covered = gh.family_covers(w, REG)
     assert covered or idx not in REG_COVERED
     if covered:
@@ -249,6 +253,78 @@ def test_shapes_across_the_kernel_table(idx, dtype):
         for tune in [(0, 0, 0, 1), (0, 0, 0, 0, 0, 2)] + ([(0, 0, 0, 2)] if pairing else []) + \
                 ([(0, 64, 0, 0, 2, 1), (0, 128, 0, 0, 1, 4)] if dtype == wl.BF16 else []):
             gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
+
+
+# stage lists longer than the 60 stages one wave holds: split over 2 or 4 waves of the workgroup
+LONG_LISTS = [
+    ((4, 2, 2, 1), (128, 1, 2, 1), (64, 1, 2, 1)),     # 64 tiles per tile row (complete G_i joins G_r): 2 waves
+    ((2, 4, 1, 2), (128, 1, 1, 2), (128, 1, 1, 2)),    # complete G_o of 128 tiles: 4 waves
+    ((4, 2, 4, 2), (64, 4, 8, 9), (32, 4, 4, 9)),      # two stages of 72 steps per tile, four tile rows per cluster
+    ((8, 1, 4, 1), (64, 2, 4, 2), (16, 2, 1, 2)),      # clusters of 8 tile rows whose union exceeds one wave's table
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("idx", range(len(LONG_LISTS)))
+def test_register_family_stage_lists_beyond_one_wave(idx, dtype):
+    """Clusters that walk 61..240 stages: the register kernels split the list over the waves of a workgroup
+    whatever N is (default launch), also with the largest split asked for; the tables pass the self check."""
+    rows, cols, deg = LONG_LISTS[idx]
+    for N in (200, 1100):
+        w = wl.Workload(f"long{idx}_{dtype}", rows, cols, deg, N, dtype, 400 + idx, 500 + idx, 600 + idx, 1.0)
+        m = gh.make_mask(w)
+        rb.rbgp_mask_check_tables(m)
+        assert 60 < rb.rbgp_mask_reg_plan(m)[5] <= 240
+        gh.check_parity(w, kernel=REG, expect_kernel=REG, ld_pad=8)
+        gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 4), expect_kernel=REG)
+    if rb.rbgp_mask_reg_plan(m)[5] > 120:        # two waves cannot hold this list
+        with pytest.raises(rb.RbgpError) as e:
+            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 2), expect_kernel=REG)
+        assert e.value.code == rb.EUNSUPPORTED
+
+
+# masks with at most four rows per column set and a sparse G_i (the shapes of Table 3's slow rows, small)
+FILLED_SHAPES = [
+    ((4, 1, 16, 1), (8, 1, 8, 1), (4, 1, 4, 1)),       # R = 1: 16 rows per tile row after the fill, stages of 8 steps
+    ((2, 2, 32, 1), (4, 1, 32, 1), (2, 1, 8, 1)),      # R = 2, G_i at 1/4: 64 rows -> four 16-row groups per tile row
+    ((4, 1, 8, 4), (8, 3, 8, 2), (2, 3, 2, 2)),        # R = 4 from G_b, |G_r.V| = 3: stages of 48 steps padded to 72
+    ((2, 1, 12, 1), (64, 1, 4, 1), (64, 1, 2, 1)),     # complete G_o of 64 tiles: a stage list split over two waves
+    ((8, 1, 4, 3), (8, 1, 8, 1), (2, 1, 2, 1)),        # R = 3, 12 rows per tile row: a partial 16-row group
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("idx", range(len(FILLED_SHAPES)))
+def test_register_family_on_the_mask_with_g_i_filled_in(idx, dtype):
+    """RBGP_KERNEL_MFMA_REG_FILLED against the oracle of the ORIGINAL mask: the zeros stored where G_i has no
+    edge must change nothing; forward and transposed products, ragged N, padded leading dimension."""
+    rows, cols, deg = FILLED_SHAPES[idx]
+    w = wl.Workload(f"filled{idx}_{dtype}", rows, cols, deg, 328, dtype, 700 + idx, 800 + idx, 900 + idx, 1.0)   # (bf16: ldI % 8 == 0)
+    m = gh.make_mask(w)
+    rb.rbgp_mask_check_tables(m)
+    assert rb.rbgp_mask_reg_plan(m)[13] > 0
+    gh.check_parity(w, kernel=FILLED, expect_kernel=FILLED)
+    gh.check_parity(w, N=1096, kernel=FILLED, ld_pad=8, expect_kernel=FILLED)
+    # transposed product: the filled family where the transposed mask has one, else whatever it runs on
+    (vl, Il, dOl), f32 = gh.backward_inputs(w)
+    want_dI, den, _, _ = gh.oracle_backward(w, *f32)
+    mt = rb.rbgp_mask_transpose(m)
+    kernel = FILLED if rb.rbgp_mask_reg_plan(mt)[13] > 0 else rb.KERNEL_AUTO
+    got, used = gh.library_spmm_transposed(w, vl, dOl, kernel=kernel)
+    assert kernel == rb.KERNEL_AUTO or used == FILLED
+    assert orc.normalised_error(got, want_dI, den) <= gh.TOL[w.dtype]
+
+
+def test_filled_family_is_what_auto_takes_for_one_row_per_column_set():
+    """Table 3, G_r = G_b = (1, 1): the default launch is the filled family (both dtypes); never for the mask of a
+    lowered 3x3 convolution, never where no filled mask exists."""
+    w = wl.sdmm4096_table3(1, 1, 3)
+    m = gh.make_mask(w)
+    assert rb.rbgp_mask_kernel(m, wl.F32) == FILLED and rb.rbgp_mask_kernel(m, wl.BF16) == FILLED
+    assert rb.rbgp_mask_kernel(gh.make_mask(wl.WRN_G1), wl.F32) == REG
+    with pytest.raises(rb.RbgpError) as e:
+        rb.rbgp_mask_set_kernel(gh.make_mask(wl.VGG19_CONV5), FILLED)
+    assert e.value.code == rb.EUNSUPPORTED
 
 
 def test_activations_beyond_4_gib():
@@ -366,11 +442,14 @@ def test_sdmm4096_paper_workload_sampled():
     on the GPU, a sample of output columns checked against the oracle."""
     w = wl.sdmm4096_table2(1, 2)
     vl, Il, vf, If = gh.host_inputs(w)
-    out, used = gh.library_spmm(w, vl, Il, tag="table2")
-    assert used == MFMA
     cols = np.r_[0:64, 2000:2064, 4032:4096]
     ref, den = gh.oracle_spmm(w, vf, np.ascontiguousarray(If[:, cols]))
-    assert orc.normalised_error(out[:, cols], ref, den) <= gh.TOL[w.dtype]
+    # the default launch (register family: 128-stage lists split over the waves of a workgroup), the LDS family,
+    # and the register family on the mask with G_i filled in
+    for kernel, want in ((rb.KERNEL_AUTO, REG), (MFMA, MFMA), (FILLED, FILLED)):
+        out, used = gh.library_spmm(w, vl, Il, kernel=kernel, tag="table2")
+        assert used == want
+        assert orc.normalised_error(out[:, cols], ref, den) <= gh.TOL[w.dtype]
 
 
 # ------------------------------------------------------------------ random masks, library defaults
