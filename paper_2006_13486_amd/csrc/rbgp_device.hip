@@ -386,12 +386,14 @@ bool mfma_covers(const rbgp_mask *m) {
 // Estimated seconds per column of I: one of 1024 SIMDs at ~2.07 GHz serves 64 columns per instruction.  The
 // constants are fitted to the 4096^3 products of Tables 2 and 3 (27 masks, each on every family that covers it).
 // Register family: a wave walks the stages of its (cluster, G_i vertex) pair; a stage of KC steps costs KC 16-row
-// MFMAs of ~36 cycles (fp32) or ~10.5 cycles per step of the 32-step bf16 forms, plus what does not overlap.
+// MFMAs of ~36 cycles (fp32), or ~8 cycles per step in bf16 (the loads of the stage; its 32-step MFMAs hide behind
+// them, a second MFMA block for the remainder of a stage does not), plus what does not overlap.
 double reg_seconds(const rbgp_mask *m, bool bf16) {
   const rbgp_reg_clusters &cl = m->reg_clusters;
   int64_t walked = 0;
   for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
-  const double stage = bf16 ? 150.0 + 10.5 * m->reg.KC : 110.0 + 36.0 * m->reg.KC;
+  const int KC = m->reg.KC;
+  const double stage = bf16 ? 170.0 + 7.8 * KC + (KC > 32 && rbgp_bf16_tail16(KC) ? 100.0 : 0.0) : 110.0 + 36.0 * KC;
   return double(walked) * m->a[2] * stage / (64.0 * 1024.0 * 2.07e9);
 }
 // LDS-staged family (fp32 MFMA for both dtypes): a wave walks (tile, column of G_r) steps of RB * KS 4-row MFMAs,
@@ -407,9 +409,9 @@ int resolve_kernel_unfilled(const rbgp_mask *m, rbgp_dtype_t dtype);
 // AUTO, last step: the register family on the mask with G_i filled in where that is estimated faster than the
 // family chosen for the mask itself and the product is not waiting for HBM anyway.  Measured on the 4096^3
 // products of Table 3, fp32 (us): one row per column set 1538 / 848 / 833 on the register family and 2054 / 1383 /
-// 1178 on the LDS family -> 680 / 667 / 660 at densities 1/4, 1/8, 1/16; two rows 837 -> 680 at 1/4 (470 and 455 at
-// 1/8 and 1/16 stay on the register family); four rows stay (595 against 694).  bf16: also Table 2's cells with a
-// half-full G_i (G_o at 1/8: 128 -> 67 us).
+// 1178 on the LDS family -> 622 / 595 / 580 at densities 1/4, 1/8, 1/16; two rows 824 -> 617 at 1/4 (466 and 453 at
+// 1/8 and 1/16 stay on the register family); four rows stay (586 against 621).  bf16: also Table 2's cells with a
+// half-full G_i (G_o at 1/8: 129 -> 51 us).
 int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
   if (m->kernel_choice == RBGP_KERNEL_MFMA_REG_FILLED) return m->filled ? RBGP_KERNEL_MFMA_REG_FILLED : RBGP_KERNEL_GENERIC;
   const int k0 = resolve_kernel_unfilled(m, dtype);

@@ -306,7 +306,7 @@ void rbgp_plan_reg(rbgp_mask *m) {
   p.ok = roles && p.VC > 0 && p.R <= 16;   // (R > 16 only when |G_b.U| alone exceeds 16)
   if (p.ok) {
     p.KCR = p.VC * per_v;
-    p.KC = p.KCR <= 8 ? 8 : p.KCR <= 18 ? 18 : p.KCR <= 36 ? 36 : 72;
+    p.KC = p.KCR <= 8 ? 8 : p.KCR <= 18 ? 18 : p.KCR <= 32 ? 32 : p.KCR <= 36 ? 36 : 72;
     p.NSTG = m->c[1] / p.VC;
     p.SRC = p.VC * m->c[2] * m->c[3];
     p.RS = 2;

@@ -49,7 +49,7 @@ struct rbgp_reg_plan {
   int KT = 0;    // contraction length of one group in one tile: |G_r.V| * d_i * |G_b.V|
   int VC = 0;    // G_r columns per stage
   int KCR = 0;   // contraction length per stage: VC * d_i * |G_b.V|
-  int KC = 0;    // KCR rounded up to a stage size the kernels are built for (8, 18, 36, 72); the
+  int KC = 0;    // KCR rounded up to a stage size the kernels are built for (8, 18, 32, 36, 72); the
                  //   positions past KCR hold zero weights and read row 0 of the stage
   int NSTG = 0;  // stages per tile: |G_r.V| / VC
   int RS = 0;    // weight rows per tile row inside a 16-row MFMA group: R rounded up to 2^k

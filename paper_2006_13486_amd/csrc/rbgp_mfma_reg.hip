@@ -386,10 +386,10 @@ struct RegEntry {
   reg_fn global_fn, taps_fn;
 };
 #define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS>, taps_kernel<KC, RS>()}
-const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
-                              RBGP_R(8, 4),  RBGP_R(18, 4),  RBGP_R(36, 4),  RBGP_R(72, 4),
-                              RBGP_R(8, 8),  RBGP_R(18, 8),  RBGP_R(36, 8),  RBGP_R(72, 8),
-                              RBGP_R(8, 16), RBGP_R(18, 16), RBGP_R(36, 16), RBGP_R(72, 16)};
+const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(32, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
+                              RBGP_R(8, 4),  RBGP_R(18, 4),  RBGP_R(32, 4),  RBGP_R(36, 4),  RBGP_R(72, 4),
+                              RBGP_R(8, 8),  RBGP_R(18, 8),  RBGP_R(32, 8),  RBGP_R(36, 8),  RBGP_R(72, 8),
+                              RBGP_R(8, 16), RBGP_R(18, 16), RBGP_R(32, 16), RBGP_R(36, 16), RBGP_R(72, 16)};
 
 const RegEntry *find_reg(int KC, int RS) {
   for (const RegEntry &e : kRegTable)

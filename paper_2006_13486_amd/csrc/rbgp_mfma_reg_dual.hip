@@ -225,6 +225,7 @@ rbgp_dual_fn rbgp_reg_dual_kernel(int KC) {
   switch (KC) {
     case 8: return spmm_reg_dual<8>;
     case 18: return spmm_reg_dual<18>;
+    case 32: return spmm_reg_dual<32>;
     case 36: return spmm_reg_dual<36>;
     case 72: return spmm_reg_dual<72>;
   }
