@@ -11,6 +11,7 @@ hot-cache rate).  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+from dataclasses import replace
 import json
 import os
 import sys
@@ -149,14 +150,17 @@ def time_workload(w, args, torch, dev, steps, warmup, check_cols=0, geom=None):
 
 def sweep_cases(which, args):
     """The paper's own SDMM workloads (Tables 2 and 3) and the VGG19 layer sweep."""
-    if which == "table2":   # (sparsity of G_o, sparsity of G_i) as log2 of the inverse density
-        splits = [(0, 2), (1, 1), (0, 3), (1, 2), (2, 1), (0, 4), (1, 3), (2, 2), (3, 1)]
-        return [wl.sdmm4096_table2(o, i) for o, i in splits]
-    if which == "table3":
-        shapes = [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]
-        return [wl.sdmm4096_table3(gr, gb, d) for gr, gb in shapes for d in (2, 3, 4)]
+    tables = which in ("table2", "table3")   # (the paper's tables are fp32: their default; the VGG19 sweep runs both)
+    dts = {"f32": [wl.F32], "bf16": [wl.BF16], "both": [wl.F32, wl.BF16]}[args.sweep_dtype or ("f32" if tables else "both")]
+    if tables:
+        if which == "table2":           # (sparsity of G_o, sparsity of G_i) as log2 of the inverse density
+            splits = [(0, 2), (1, 1), (0, 3), (1, 2), (2, 1), (0, 4), (1, 3), (2, 2), (3, 1)]
+            ws = [wl.sdmm4096_table2(o, i) for o, i in splits]
+        else:
+            shapes = [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]
+            ws = [wl.sdmm4096_table3(gr, gb, d) for gr, gb in shapes for d in (2, 3, 4)]
+        return [w if dt == wl.F32 else replace(w, name=w.name + "_bf16", dtype=dt) for dt in dts for w in ws]
     dens = [int(x) for x in args.sweep_density.split(",")]
-    dts = {"f32": [wl.F32], "bf16": [wl.BF16], "both": [wl.F32, wl.BF16]}[args.sweep_dtype]
     cases = []
     for dt in dts:
         for d in dens:
@@ -473,7 +477,8 @@ def main():
     ap.add_argument("--sweep-steps", type=int, default=300)
     ap.add_argument("--sweep-check", type=int, default=32, help="output columns per case checked against the oracle (0: none)")
     ap.add_argument("--sweep-density", default="2,3", help="vgg19 sweep: log2 of the inverse densities")
-    ap.add_argument("--sweep-dtype", default="both", choices=["f32", "bf16", "both"])
+    ap.add_argument("--sweep-dtype", default=None, choices=["f32", "bf16", "both"],
+                    help="default: both for the VGG19 sweep, f32 for the tables")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run ten 64 MiB device-to-device copies and exit (reference for the FETCH_SIZE / "
                          "WRITE_SIZE counters)")
