@@ -69,7 +69,7 @@ namespace {
 // latency; four of them per SIMD (<= 128 registers, which the compiler meets without spilling) instead
 // of the three it would otherwise leave room for: the conv5 backward data product 32 -> 29 us.
 template <int KC, int RS, bool TAPS = false>
-__global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) {
+__global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
@@ -180,8 +180,11 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
                                              kRsrcFlags);
   };
 
-  f32x4 B0[NO], B1[NO];
-  f32x4 A0[NQ], A1[NQ];
+  // Register sets = stages of loads in flight.  Two for the long stages; a stage of 8 steps is 8 MFMAs (256
+  // cycles), and two of them ahead cover far less than a memory access takes: such kernels keep four.
+  constexpr int D = KC <= 8 ? 4 : 2;
+  f32x4 Bs[D][NO];
+  f32x4 As[D][NQ];
   if (!valid && lgS == 0) return;   // (with a split stage list every wave reaches the barrier below)
   // Drain every outstanding load count here: a wait for the table loads inside the loop
   // would run on every iteration and drain the prefetched stages with it.
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
   };
 
   // One stage: MFMAs of stage s from (B, A); every B slot and every weight quad is
-  // refilled for stage s + 2 right after its last use (RELOAD), so that about two stages
+  // refilled for stage s + D right after its last use (RELOAD), so that about D stages
   // of loads are in flight at any time.  Every real stage has work (the stage list is the
   // union of the cluster's tiles), so the loop body is branch-free and its wait counts
   // are exact.
@@ -239,8 +242,8 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
     int sofs = 0, av = 0;
     __amdgpu_buffer_rsrc_t rb2 = rw;
     if constexpr (RELOAD) {
-      rb2 = b_rsrc(s + 2, &sofs);
-      av = a_addr(s + 2);
+      rb2 = b_rsrc(s + D, &sofs);
+      av = a_addr(s + D);
     }
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
@@ -253,7 +256,12 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
           B[o] = load_x4(rb2, off[o], sofs);
         else if constexpr (o % 3 == 2)
           B[o - 1] = load_x4(rb2, off[o - 1], sofs);   // the pair's middle window, after its last use
-        if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
+        if constexpr (o % 4 == 3 || o == NO - 1) {
+          // (a last quad that is used in part stays whole until here: a register of it that the compiler gave to
+          // something else would have to wait for the quad's pending load, i.e. for every load in flight)
+          asm volatile("" ::"v"(A[o / 4]));
+          A[o / 4] = a_load(av, o / 4);
+        }
         __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
       }
     });
@@ -295,23 +303,42 @@ __global__ __launch_bounds__(256, (KC <= 8 ? 4 : 1)) void spmm_reg(RegParams p) 
       }
       if constexpr (o % 4 == 3 || o == NO - 1) {
         An[o / 4] = a_load(av1, o / 4);
+        asm volatile("" ::"v"(A[o / 4]));
         A[o / 4] = a_load(av2, o / 4);
       }
       __builtin_amdgcn_sched_barrier(0);
     });
   };
 
-  // Two register sets alternate; stages past the end read zeros (sentinel table lanes).
-  fill(0, B0, A0);
-  first_stage(B0, A0, B1, A1);
-  if (cnt > 1) {   // the loop is reachable only through stage 1, which keeps its wait counts exact
-    stage(1, B1, A1, std::true_type{});
-    int s = 2;
-    for (; s + 1 < cnt; s += 2) {
-      stage(s, B0, A0, std::true_type{});
-      stage(s + 1, B1, A1, std::true_type{});
+  // The register sets take turns; stages past the end read zeros (sentinel table lanes).
+  if constexpr (D == 2) {
+    f32x4(&B0)[NO] = Bs[0], (&B1)[NO] = Bs[1];
+    f32x4(&A0)[NQ] = As[0], (&A1)[NQ] = As[1];
+    fill(0, B0, A0);
+    first_stage(B0, A0, B1, A1);
+    if (cnt > 1) {   // the loop is reachable only through stage 1, which keeps its wait counts exact
+      stage(1, B1, A1, std::true_type{});
+      int s = 2;
+      for (; s + 1 < cnt; s += 2) {
+        stage(s, B0, A0, std::true_type{});
+        stage(s + 1, B1, A1, std::true_type{});
+      }
+      if (s < cnt) stage(s, B0, A0, std::false_type{});
     }
-    if (s < cnt) stage(s, B0, A0, std::false_type{});
+  } else {
+    // all D sets are requested up front; whole rounds of D stages refill as they go (branch-free: exact wait
+    // counts); the last, partial round only consumes what is already on its way
+    static_for<0, D>([&](auto kc) { fill(decltype(kc)::value, Bs[decltype(kc)::value], As[decltype(kc)::value]); });
+    int s = 0;
+    for (; s + D <= cnt; s += D)
+      static_for<0, D>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        stage(s + k, Bs[k], As[k], std::true_type{});
+      });
+    static_for<0, D>([&](auto kc) {
+      constexpr int k = decltype(kc)::value;
+      if (s + k < cnt) stage(s + k, Bs[k], As[k], std::false_type{});
+    });
   }
   __builtin_amdgcn_s_waitcnt(0);
 
