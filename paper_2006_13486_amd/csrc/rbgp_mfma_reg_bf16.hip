@@ -225,7 +225,12 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
     for (int t = 0; t < n; ++t) B[first + t] = load_raw<LW>(rb2, off[first + t], sofs);
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) A[gi][b] = load_u4(rw, av[gi], b * QB);
+    for (int gi = 0; gi < G; ++gi) {
+      // (the 16-step block uses half of its weight quad: it stays whole until here, else a register of it that
+      // the compiler gave to something else would have to wait for the quad's pending load, i.e. for every load)
+      asm volatile("" ::"v"(A[gi][b]));
+      A[gi][b] = load_u4(rw, av[gi], b * QB);
+    }
     __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
   };
 
