@@ -216,10 +216,11 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
   auto load_x = [&](int64_t elem) {
     return __builtin_bit_cast(reg, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, int(elem * ES), 0, 0));
   };
-  auto load_all = [&](reg *r, int64_t n) {
+  // (`at`: pixel(n), looked up by the caller -- ahead of time inside the loop, where a lookup right before its use
+  // would have to wait for every load in flight)
+  auto load_all = [&](reg *r, int64_t n, int64_t at) {
 #pragma unroll
     for (int i = 0; i < RB; ++i) r[i] = Op::load(p.dO, off[i] + n);
-    const int64_t at = pixel(n);
 #pragma unroll
     for (int i = RB; i < NL; ++i) {
       if constexpr (CONV) r[i] = load_x(off[i] + at);
@@ -269,8 +270,11 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
       return c < n_last ? c : n_last;
     };
     reg raw[D][NL], cur[NL], nxt[NL];
+    int64_t at_next[D];   // pixel(column(k + D)) of the step that refills set d next, requested one round earlier
 #pragma unroll
-    for (int d = 0; d < D; ++d) load_all(raw[d], column(d));
+    for (int d = 0; d < D; ++d) load_all(raw[d], column(d), pixel(column(d)));
+#pragma unroll
+    for (int d = 0; d < D; ++d) at_next[d] = pixel(column(D + d));
 #pragma unroll
     for (int i = 0; i < NL; ++i) cur[i] = Op::zero();
     for (int64_t k0 = 0; k0 <= iters; k0 += D) {
@@ -278,7 +282,9 @@ __global__ __launch_bounds__(256) void sddmm_reg(SddmmParams p) {
       for (int d = 0; d < D; ++d) {
         const int64_t k = k0 + d;
         transpose_all(nxt, raw[d]);
-        load_all(raw[d], column(k + D));
+        const int64_t at = at_next[d];
+        at_next[d] = pixel(column(k + 2 * D));
+        load_all(raw[d], column(k + D), at);
         mac_all(cur);
         const bool live = k < iters;   // nxt holds iteration k
 #pragma unroll
