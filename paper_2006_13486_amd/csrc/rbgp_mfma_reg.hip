@@ -68,9 +68,15 @@ namespace {
 // Stages of 8 steps make short waves (a transposed 3x3 layer: 64 MFMAs per wave) whose time is mostly
 // latency; four of them per SIMD (<= 128 registers, which the compiler meets without spilling) instead
 // of the three it would otherwise leave room for: the conv5 backward data product 32 -> 29 us.
-template <int KC, int RS, bool TAPS = false>
-__global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
+// NG (one tile row per group only, RS = 16): 16-row groups per wave.  Where rows of G_r moved into the tile-row
+// index, NG consecutive tile rows have the very same tiles; one wave then takes NG of them, and every loaded row
+// of I feeds NG groups of MFMAs: the rows of I cross the load path of the CU 1/NG as often (a stage of 72 steps
+// asks for 23 KB per 2304 MFMA cycles and wave, ~40 B/clk per CU with four waves, close to what the path
+// delivers), at NG times the accumulators.
+template <int KC, int RS, bool TAPS = false, int NG = 1>
+__global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
+  static_assert(NG == 1 || RS == 16, "several groups per wave: one tile row per group");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
   constexpr int NO = (KC + 3) / 4;       // load slots per stage (4 contraction steps each)
   constexpr int NQ = (NO + 3) / 4;       // weight registers per stage come as NQ 16-byte loads
@@ -93,7 +99,7 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   const int ks = wid & (S - 1);
   WgCoord wg;
   if (!wg_coord(p, &wg)) return;
-  const int cl = wg.cl, u3 = wg.u3, ntq = wg.ntq;
+  const int cl = wg.cl * NG, u3 = wg.u3, ntq = wg.ntq;   // (NG > 1: the first of the wave's NG tile rows; all share its tables)
   const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
   const int64_t n0 = int64_t(nt) * CW;
   // byte offset of the wave's first column in a row of I (fused convolution: the lane's own
@@ -184,17 +190,20 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   // cycles), and two of them ahead cover far less than a memory access takes: such kernels keep four.
   constexpr int D = KC <= 8 ? 4 : 2;
   f32x4 Bs[D][NO];
-  f32x4 As[D][NQ];
+  f32x4 As[D][NG][NQ];
   if (!valid && lgS == 0) return;   // (with a split stage list every wave reaches the barrier below)
   // Drain every outstanding load count here: a wait for the table loads inside the loop
   // would run on every iteration and drain the prefetched stages with it.
   __builtin_amdgcn_s_waitcnt(0);
 
-  f32x16 acc[4];
+  f32x16 acc[NG][4];
 #pragma unroll
-  for (int w = 0; w < 4; ++w)
+  for (int k = 0; k < NG; ++k)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[w][v] = 0.f;
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[k][w][v] = 0.f;
+  const int gstr = p.fpm * p.a3 * FB;   // NG > 1: from one tile row's weights to the next one's (same tile, same stage)
 
   // Loads are unconditional so that the wait counts are exact (sentinel stages and absent
   // tiles read zeros, see above).
@@ -237,7 +246,7 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   // of loads are in flight at any time.  Every real stage has work (the stage list is the
   // union of the cluster's tiles), so the loop body is branch-free and its wait counts
   // are exact.
-  auto stage = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NQ], auto reload) {
+  auto stage = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NG][NQ], auto reload) {
     constexpr bool RELOAD = decltype(reload)::value;
     int sofs = 0, av = 0;
     __amdgpu_buffer_rsrc_t rb2 = rw;
@@ -247,10 +256,13 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
     }
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
-      const float a = A[o / 4][o % 4];
       const f32x4 b = operand(B, oc);
 #pragma unroll
-      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[w], 0, 0, 0);
+      for (int k = 0; k < NG; ++k) {
+        const float a = A[k][o / 4][o % 4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[k][w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[k][w], 0, 0, 0);
+      }
       if constexpr (RELOAD) {
         if constexpr (!TAPS)
           B[o] = load_x4(rb2, off[o], sofs);
@@ -259,15 +271,18 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
         if constexpr (o % 4 == 3 || o == NO - 1) {
           // (a last quad that is used in part stays whole until here: a register of it that the compiler gave to
           // something else would have to wait for the quad's pending load, i.e. for every load in flight)
-          asm volatile("" ::"v"(A[o / 4]));
-          A[o / 4] = a_load(av, o / 4);
+#pragma unroll
+          for (int k = 0; k < NG; ++k) {
+            asm volatile("" ::"v"(A[k][o / 4]));
+            A[k][o / 4] = a_load(av + k * gstr, o / 4);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
       }
     });
   };
   // loads of stage s in the same order as the refills above
-  auto fill = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NQ]) {
+  auto fill = [&](int s, f32x4 (&B)[NO], f32x4 (&A)[NG][NQ]) {
     int sofs;
     const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(s, &sofs);
     const int av = a_addr(s);
@@ -277,23 +292,29 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
         B[o] = load_x4(rb2, off[o], sofs);
       else if constexpr (o % 3 == 2)
         B[o - 1] = load_x4(rb2, off[o - 1], sofs);
-      if constexpr (o % 4 == 3 || o == NO - 1) A[o / 4] = a_load(av, o / 4);
+      if constexpr (o % 4 == 3 || o == NO - 1) {
+#pragma unroll
+        for (int k = 0; k < NG; ++k) A[k][o / 4] = a_load(av + k * gstr, o / 4);
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
   };
 
   // Stage 0 starts as soon as its own data is there: the loads of stage 1 (into the second
   // register set) and the refills for stage 2 are issued between its MFMAs.
-  auto first_stage = [&](f32x4 (&B)[NO], f32x4 (&A)[NQ], f32x4 (&Bn)[NO], f32x4 (&An)[NQ]) {
+  auto first_stage = [&](f32x4 (&B)[NO], f32x4 (&A)[NG][NQ], f32x4 (&Bn)[NO], f32x4 (&An)[NG][NQ]) {
     int sofs1, sofs2;
     const __amdgpu_buffer_rsrc_t rb1 = b_rsrc(1, &sofs1), rb2 = b_rsrc(2, &sofs2);
     const int av1 = a_addr(1), av2 = a_addr(2);
     static_for<0, NO>([&](auto oc) {
       constexpr int o = decltype(oc)::value;
-      const float a = A[o / 4][o % 4];
       const f32x4 b = operand(B, oc);
 #pragma unroll
-      for (int w = 0; w < 4; ++w) acc[w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[w], 0, 0, 0);
+      for (int k = 0; k < NG; ++k) {
+        const float a = A[k][o / 4][o % 4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[k][w] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b[w], acc[k][w], 0, 0, 0);
+      }
       if constexpr (!TAPS) {
         Bn[o] = load_x4(rb1, off[o], sofs1);
         B[o] = load_x4(rb2, off[o], sofs2);
@@ -302,9 +323,12 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
         B[o - 1] = load_x4(rb2, off[o - 1], sofs2);
       }
       if constexpr (o % 4 == 3 || o == NO - 1) {
-        An[o / 4] = a_load(av1, o / 4);
-        asm volatile("" ::"v"(A[o / 4]));
-        A[o / 4] = a_load(av2, o / 4);
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+          An[k][o / 4] = a_load(av1 + k * gstr, o / 4);
+          asm volatile("" ::"v"(A[k][o / 4]));
+          A[k][o / 4] = a_load(av2 + k * gstr, o / 4);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -313,7 +337,7 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   // The register sets take turns; stages past the end read zeros (sentinel table lanes).
   if constexpr (D == 2) {
     f32x4(&B0)[NO] = Bs[0], (&B1)[NO] = Bs[1];
-    f32x4(&A0)[NQ] = As[0], (&A1)[NQ] = As[1];
+    f32x4(&A0)[NG][NQ] = As[0], (&A1)[NG][NQ] = As[1];
     fill(0, B0, A0);
     first_stage(B0, A0, B1, A1);
     if (cnt > 1) {   // the loop is reachable only through stage 1, which keeps its wait counts exact
@@ -345,15 +369,16 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Unit t of the sum holds
   // weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
   const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
-  auto unit = [&](int t) {
+  auto unit = [&](int t, int k = 0) {
     f32x4 v;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) v[w] = (acc[w][t] + acc[w][4 + t]) + (acc[w][8 + t] + acc[w][12 + t]);
+    for (int w = 0; w < 4; ++w) v[w] = (acc[k][w][t] + acc[k][w][4 + t]) + (acc[k][w][8 + t] + acc[k][w][12 + t]);
     return v;
   };
-  auto store_unit = [&](int t, f32x4 v) {
+  auto store_unit = [&](int t, f32x4 v, int k = 0) {
     const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
-    const int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
+    int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
+    if constexpr (NG > 1) u1 = u1 >= 0 ? u1 + k : u1;   // (group k is the tile row after group k - 1's)
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
     if (valid && u1 >= 0 && r < p.R) {
       const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
@@ -369,34 +394,41 @@ __global__ __launch_bounds__(256, (KC <= 8 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_r
   };
   if (lgS == 0) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) store_unit(t, unit(t));
+    for (int k = 0; k < NG; ++k)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) store_unit(t, unit(t, k), k);
   } else {
     // The S waves of a column tile each own the units t with t % S == their share.  A wave
     // leaves the units it does not own in LDS (densely: unit t of owner o sits at
-    // (t / S) * (S - 1) + o - (o > share)) and, after the barrier, adds up the ones it owns in
-    // wave order, so the result does not depend on timing.
+    // (t / S) * (S - 1) + o - (o > share); one such block per group and wave) and, after the barrier,
+    // adds up the ones it owns in wave order, so the result does not depend on timing.
     f32x4 *const red4 = reinterpret_cast<f32x4 *>(wlds);
     const int per_wave = (4 >> lgS) * (S - 1);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int o = t & (S - 1);
-      if (o != ks) red4[(wid * per_wave + (t >> lgS) * (S - 1) + o - (o > ks ? 1 : 0)) * 64 + lane] = unit(t);
-    }
+    for (int k = 0; k < NG; ++k)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int o = t & (S - 1);
+        if (o != ks)
+          red4[((k * 4 + wid) * per_wave + (t >> lgS) * (S - 1) + o - (o > ks ? 1 : 0)) * 64 + lane] = unit(t, k);
+      }
     __syncthreads();
     const int w0 = wid & ~(S - 1);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if ((t & (S - 1)) == ks) {
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        for (int k = 0; k < S; ++k) {
-          if (k == ks)
-            v += unit(t);
-          else
-            v += red4[((w0 + k) * per_wave + (t >> lgS) * (S - 1) + ks - (ks > k ? 1 : 0)) * 64 + lane];
+    for (int k = 0; k < NG; ++k)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if ((t & (S - 1)) == ks) {
+          f32x4 v = {0.f, 0.f, 0.f, 0.f};
+          for (int kk = 0; kk < S; ++kk) {
+            if (kk == ks)
+              v += unit(t, k);
+            else
+              v += red4[((k * 4 + w0 + kk) * per_wave + (t >> lgS) * (S - 1) + ks - (ks > kk ? 1 : 0)) * 64 + lane];
+          }
+          store_unit(t, v, k);
         }
-        store_unit(t, v);
       }
-    }
   }
 }
 
@@ -408,11 +440,31 @@ constexpr reg_fn taps_kernel() {   // the tap-grouped variant exists for stages 
   else
     return nullptr;
 }
+template <int KC, int RS, int NG>
+constexpr reg_fn taps_kernel_ng() {
+  if constexpr (KC % 12 == 0)
+    return spmm_reg<KC, RS, true, NG>;
+  else
+    return nullptr;
+}
 struct RegEntry {
   int KC, RS;
   reg_fn global_fn, taps_fn;
 };
 #define RBGP_R(KC, RS) {KC, RS, spmm_reg<KC, RS>, taps_kernel<KC, RS>()}
+// several 16-row groups per wave (one tile row each): two for every stage size, four for the short stages
+struct RegGroupEntry {
+  int KC, NG;
+  reg_fn global_fn, taps_fn;
+};
+#define RBGP_RG(KC, NG) {KC, NG, spmm_reg<KC, 16, false, NG>, taps_kernel_ng<KC, 16, NG>()}
+const RegGroupEntry kRegGroupTable[] = {RBGP_RG(8, 2),  RBGP_RG(18, 2), RBGP_RG(32, 2), RBGP_RG(36, 2), RBGP_RG(72, 2),
+                                        RBGP_RG(8, 4),  RBGP_RG(18, 4)};
+const RegGroupEntry *find_reg_groups(int KC, int NG) {
+  for (const RegGroupEntry &e : kRegGroupTable)
+    if (e.KC == KC && e.NG == NG) return &e;
+  return nullptr;
+}
 const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(32, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
                               RBGP_R(8, 4),  RBGP_R(18, 4),  RBGP_R(32, 4),  RBGP_R(36, 4),  RBGP_R(72, 4),
                               RBGP_R(8, 8),  RBGP_R(18, 8),  RBGP_R(32, 8),  RBGP_R(36, 8),  RBGP_R(72, 8),
@@ -683,12 +735,43 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       lgS = need;
     }
   }
-  const int ncl = dual ? m->reg_dual.nq : tab->ncl;
+  // fp32, rows of G_r moved into the tile-row index: NG of the `fold` tile rows that share their tiles per wave
+  // (see spmm_reg), as many as still leave every SIMD a wave; tuning knob RBGP_TUNE_ROW_GROUPS overrides.
+  int NGf = 1;
+  const RegGroupEntry *ge = nullptr;
+  if (!bf16 && !dual && pl.MG == 1 && pl.fold > 1) {
+    bool ident = true;   // (clusters of one tile row come in tile-row order)
+    for (int c = 0; c < m->reg_clusters.ncl && ident; ++c) ident = m->reg_clusters.members[size_t(c)] == c;
+    auto fits = [&](int ng) {
+      const RegGroupEntry *g = find_reg_groups(pl.KC, ng);
+      return ident && pl.fold % ng == 0 && g && (!taps || g->taps_fn);
+    };
+    const int tg = tune[RBGP_TUNE_ROW_GROUPS];
+    if (tg > 1) {
+      if (!fits(tg)) return RBGP_EUNSUPPORTED;
+      NGf = tg;
+    } else if (tg == 0) {
+      // (not for short waves: with several groups a SIMD holds one wave instead of up to four, and a wave of a few
+      // hundred MFMAs is mostly latency -- the conv5 backward data product, 8 stages of 8 steps: 29.6 us with one
+      // group, 39.8 / 35.3 with two / four; the density-1/2 VGG19 layers, 8-16 stages of 72 steps: 6-19 % faster with two)
+      const int64_t steps = int64_t(tab->max_stages) * pl.KC;
+      for (int ng : {4, 2})
+        if (fits(ng) && steps >= (128 * ng << lgS) && ((int64_t(tab->ncl / ng) * m->a[2] * ntiles) << lgS) >= 1024) {
+          NGf = ng;
+          break;
+        }
+    }
+    if (NGf > 1) ge = find_reg_groups(pl.KC, NGf);
+  } else if (!bf16 && tune[RBGP_TUNE_ROW_GROUPS] > 1) {
+    return RBGP_EUNSUPPORTED;
+  }
+  const int ncl = dual ? m->reg_dual.nq : tab->ncl / NGf;
   const int fpm = m->d[0] * pl.NSTG;
   // LDS: partial sums of the split -- per wave the (S - 1) / S of its 4G units it does not own; lo/hi pairing:
   // the four units of half of the eight waves
   size_t lds = dual ? size_t(16) * 1024
                     : size_t(4) * ((4 * G) >> lgS) * ((1 << lgS) - 1) * (bf16 ? NC / 4 : 1) * 1024;
+  lds *= NGf;   // (fp32 with several groups per wave: one such block per group)
 
   RegParams rp;
   rp.Wp = static_cast<const float *>(packed);
@@ -749,7 +832,11 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.ncl = ncl;
   rp.per_xcd = int(per_xcd);
   rp.ngroups = int(nquads);
-  reg_fn fn = dual ? nullptr : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW) : taps ? e->taps_fn : e->global_fn;
+  reg_fn fn = dual ? nullptr
+              : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW)
+              : ge   ? (taps ? ge->taps_fn : ge->global_fn)
+              : taps ? e->taps_fn
+                     : e->global_fn;
   if (!fn && !dual) return RBGP_EUNSUPPORTED;
   if (lds > 64 * 1024 && fn)   // (cheap host-side call; repeated because fn varies with the knobs)
     RBGP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -327,6 +327,48 @@ def test_filled_family_is_what_auto_takes_for_one_row_per_column_set():
     assert e.value.code == rb.EUNSUPPORTED
 
 
+# masks whose rows of G_r move into the tile-row index (more than 16 rows per column set): fp32 waves that take 2 or 4
+# of the tile rows that share their tiles
+ROW_GROUP_SHAPES = [
+    ((2, 8, 4, 3), (2, 2, 4, 9), (1, 2, 2, 9), (2,)),        # R = 24 -> 2 x 12, stages of 36
+    ((4, 4, 2, 9), (4, 4, 4, 2), (2, 4, 2, 2), (2, 4)),      # R = 36 -> 4 x 9 (a transposed 3x3 layer), stages of 16 in 18
+    ((2, 2, 32, 2), (4, 1, 32, 1), (2, 1, 32, 1), (2,)),     # complete G_i: 128 rows -> 8 x 16, stages of 32 (no kernel of 4 groups)
+    ((2, 4, 4, 2), (2, 2, 8, 9), (1, 2, 8, 9), (2,)),        # R = 32 -> 2 x 16, stages of 72
+    ((4, 8, 1, 8), (8, 2, 1, 9), (4, 2, 1, 9), (2, 4)),      # R = 64 -> 4 x 16, stages of 18
+]
+
+
+@pytest.mark.parametrize("idx", range(len(ROW_GROUP_SHAPES)))
+def test_fp32_register_family_row_groups_per_wave(idx):
+    """RBGP_TUNE_ROW_GROUPS on the fp32 register kernels (2 or 4 tile rows with the same tiles per wave), ragged N,
+    padded leading dimension, alone and with a split stage list; refused where the tile rows do not come in such groups."""
+    rows, cols, deg, groups = ROW_GROUP_SHAPES[idx]
+    w = wl.Workload(f"rowgroups{idx}", rows, cols, deg, 333, wl.F32, 40 + idx, 50 + idx, 60 + idx, 1.0)
+    for ng in groups:
+        gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, ng), ld_pad=3, expect_kernel=REG)
+        gh.check_parity(w, N=64, kernel=REG, tune=(0, 0, 0, 0, ng), expect_kernel=REG)
+    gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 2, 2), expect_kernel=REG)     # with a split stage list as well
+    gh.check_parity(w, N=200, kernel=REG, tune=(0, 0, 0, 0, groups[-1], 4), ld_pad=1, expect_kernel=REG)
+    if 4 not in groups:
+        with pytest.raises(rb.RbgpError) as e:
+            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 4), expect_kernel=REG)
+        assert e.value.code == rb.EUNSUPPORTED
+
+
+def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
+    # a density-1/2 VGG19 layer shape (complete G_i joins G_r: 32 rows per column set), images 8 pixels wide: tap-grouped
+    w = wl.Workload("rowgroups_conv", (4, 4, 4, 2), (4, 2, 8, 9), (2, 2, 8, 9), 0, wl.F32, 71, 72, 73, 1.0)
+    X = wl.conv_activations(w, 6, 8, 8)
+    want, den = gh.oracle_spmm(w, wl.kept_weights(w), orc.im2col_3x3(X))
+    for ng in (1, 2):
+        out = gh.library_conv3x3(w, wl.kept_weights(w), X, tune=(0, 0, 0, 0, ng), kernel=REG)
+        assert orc.normalised_error(out, want, den) <= gh.TOL[w.dtype]
+    # a mask with 8 rows per column set has no such groups
+    with pytest.raises(rb.RbgpError) as e:
+        gh.check_parity(wl.VGG19_CONV5, N=256, kernel=REG, tune=(0, 0, 0, 0, 2), expect_kernel=REG)
+    assert e.value.code == rb.EUNSUPPORTED
+
+
 def test_activations_beyond_4_gib():
     """An I of 4.6 GB (WRN shape, 2 000 037 columns, odd leading dimension): the kernels'
     32-bit offsets must only span one stage.  A sample of output columns is checked."""
