@@ -105,8 +105,12 @@ enum {
                                          the same tile (EUNSUPPORTED where that kernel does not apply: bf16,
                                          other group sizes, more than 32 tile rows, with RBGP_TUNE_K_SPLIT);
                                          default: 2 where it walks fewer tiles and N fills the chip */
-  RBGP_TUNE_ROW_GROUPS = 4,           /* MFMA_REG bf16: 16-row MFMA groups per wave, 1, 2 or 4 (each
-                                         loaded row of I is reused by all of them) */
+  RBGP_TUNE_ROW_GROUPS = 4,           /* MFMA_REG: 16-row MFMA groups per wave, 1, 2 or 4 (each loaded row of I
+                                         is reused by all of them).  bf16: any mask (larger clusters of tile
+                                         rows).  fp32: only tile rows that have the very same tiles -- masks
+                                         with more than 16 rows per column set, whose rows of G_r move into
+                                         the tile-row index -- 2 for every stage size, 4 for stages of up to
+                                         18 steps (else EUNSUPPORTED) */
   RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG: waves that share a column tile and split its
                                          nonzero tiles between them, 1, 2 or 4 (default: 1 unless N
                                          is too small to give every SIMD a wave) */
