@@ -445,6 +445,9 @@ int resolve_kernel_unfilled(const rbgp_mask *m, rbgp_dtype_t dtype) {
     // ~5 TB/s) and above the LDS family's.
     // (VGG19 layers at density 1/16 with 27-42 % useful rows and an estimate up to 1.3 x the HBM time are
     // still faster on the register family, as is every other cell of that sweep.)
+    // The mask of a lowered 3x3 convolution stays on the register family: rbgp_conv3x3 and the fused gradients read
+    // its layout (and it was the faster family on every VGG19 cell, forward and transposed).
+    if (m->c[3] == 9 && m->d[3] == 9) return RBGP_KERNEL_MFMA_REG;
     const double t_reg = reg_seconds(m, bf16_in(dtype));
     return t_reg > 4.0 * hbm_seconds(m) && lds_seconds(m) < t_reg ? RBGP_KERNEL_MFMA : RBGP_KERNEL_MFMA_REG;
   }

@@ -276,6 +276,22 @@ def test_automatic_choice_on_the_masks_of_tables_2_and_3():
     assert rb.rbgp_mask_reg_plan(conv)[13] > 0 and rb.rbgp_mask_kernel(conv, rb.F32) != rb.KERNEL_MFMA_REG_FILLED
 
 
+def test_every_vgg19_sweep_mask_runs_on_the_register_family():
+    """The masks of the VGG19 layer sweep, their transposes and the masks of their transposed convolutions resolve to
+    the register family whatever the estimates say: rbgp_conv3x3 and the fused gradients need its layout."""
+    for layer in range(1, 16):
+        for d in (1, 2, 3, 4):
+            w = wl.vgg19_sweep_workload(layer, d, wl.F32)
+            try:
+                m = rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed)
+            except rb.RbgpError as e:
+                assert e.code == rb.ENOTRAMANUJAN
+                continue
+            for mask in (m, rb.rbgp_mask_transpose(m), rb.rbgp_mask_conv3x3_transpose(m)):
+                for dt in (rb.F32, rb.BF16_F32ACC):
+                    assert rb.rbgp_mask_kernel(mask, dt) == rb.KERNEL_MFMA_REG, (w.name, dt)
+
+
 def test_the_two_bf16_modes_share_kernel_choice_and_layout():
     """RBGP_BF16 only changes how rbgp_spmm / rbgp_conv3x3 store O: packed buffers are interchangeable."""
     for rows, cols, deg in LAYOUT_SHAPES[:4]:
