@@ -393,7 +393,11 @@ double reg_seconds(const rbgp_mask *m, bool bf16) {
   int64_t walked = 0;
   for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
   const int KC = m->reg.KC;
-  const double stage = bf16 ? 170.0 + 7.8 * KC + (KC > 32 && rbgp_bf16_tail16(KC) ? 100.0 : 0.0) : 110.0 + 36.0 * KC;
+  double stage = bf16 ? 150.0 + 6.8 * KC + (KC > 32 && rbgp_bf16_tail16(KC) ? 100.0 : 0.0) : 110.0 + 36.0 * KC;
+  // tile rows with the very same tiles (rows of G_r in the tile-row index) share their loads of I: the bf16 kernels
+  // take two or four of them per wave (measured on the filled masks of Table 3: 182 / 122 / 100-111 us)
+  if (bf16 && m->reg.MG == 1 && m->reg.fold % 2 == 0)
+    stage *= m->reg.fold % 4 == 0 && cl.max_stages >= 32 && KC <= 36 ? 0.56 : 0.67;
   return double(walked) * m->a[2] * stage / (64.0 * 1024.0 * 2.07e9);
 }
 // LDS-staged family (fp32 MFMA for both dtypes): a wave walks (tile, column of G_r) steps of RB * KS 4-row MFMAs,

@@ -679,7 +679,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
         int64_t total1 = 0, total2 = 0;
         for (int32_t c : m->reg_clusters.counts) total1 += c;
         for (int32_t c : c2.counts) total2 += c;
-        st->g2_stages = (c2.max_stages > 60 || m->reg_clusters.U != pl.MG || 5 * total2 > 4 * total1) ? -2 : c2.max_stages;
+        st->g2_stages = (c2.max_stages > kRegMaxStages || m->reg_clusters.U != pl.MG || 5 * total2 > 4 * total1) ? -2 : c2.max_stages;
         st->g2_ncl = c2.ncl;
         st->g2_shared = 20 * total2 <= 11 * total1;
       }
@@ -692,6 +692,16 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
         // (and where the tile rows of a larger cluster have the same tiles -- rows of G_r moved into the tile-row
         // index -- the second group costs no extra stage at all: 12-17 % faster on the density-1/2 layers)
         if (waves2 * S2 >= 1024 && (S2 == 1 || conv || st->g2_shared || st->g2_stages / S2 >= 12)) G = 2;
+        // Four tile rows with the very same tiles (at least four of G_r's rows moved into the tile-row index, as on the
+        // filled masks of Tables 2-3): four groups per wave, where the chip stays full and the accumulators fit without
+        // spilling (stages of up to 36 steps).  4096^3 with one row per column set: 182 / 122 / 111 us with 1 / 2 / 4 groups.
+        // (stage lists of 16: 53.9 us against 51.1 with two groups -- long lists only)
+        if (G == 2 && st->g2_shared && pl.MG == 1 && pl.fold % 4 == 0 && pl.KC <= 36 && st->g2_stages >= 32) {
+          const int64_t waves4 = int64_t(pl.TR / 4) * m->a[2] * ntiles;
+          int S4 = 1;
+          while (S4 < 4 && (waves4 * S4 < 1024 || st->g2_stages > kRegWaveStages * S4)) S4 *= 2;
+          if (waves4 * S4 >= 1024 && st->g2_stages <= kRegWaveStages * S4) G = 4;
+        }
       }
     }
     const int64_t ncl = (pl.TR + G * pl.MG - 1) / (G * pl.MG);
