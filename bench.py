@@ -31,9 +31,12 @@ from paper_2006_13486_amd import workloads as wl    # noqa: E402
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 PEAK_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix (= packed vector) peak
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
-WORKLOADS = {"conv5": wl.VGG19_CONV5, "conv3": wl.VGG19_CONV3_BF16, "wrn": wl.WRN_G1, "tiny": wl.TINY}
+WORKLOADS = {"conv5": wl.VGG19_CONV5, "conv3": wl.VGG19_CONV3_BF16, "wrn": wl.WRN_G1, "tiny": wl.TINY,
+             # two of the paper's own 4096^3 products: Table 3's first row (one row per column set, 75 % sparse) and
+             # Table 2's (87.5 %, 50 %) cell at 93.75 %
+             "sdmm_r1": wl.sdmm4096_table3(1, 1, 2), "sdmm_o8": wl.sdmm4096_table2(3, 1)}
 # which roofline bounds each workload (arithmetic intensity vs the fp32 / bf16 ridge)
-BOUND = {"conv5": "mfma", "conv3": "hbm", "wrn": "hbm", "tiny": "hbm"}
+BOUND = {"conv5": "mfma", "conv3": "hbm", "wrn": "hbm", "tiny": "hbm", "sdmm_r1": "mfma", "sdmm_o8": "mfma"}
 
 
 def cpu_baseline(w, vals_f32, I_f32, out_gpu):
