@@ -3,6 +3,8 @@
 library's default launch: what `bench.py` times in its sweeps.  The inputs are drawn on the device
 (seeded); a sample of output columns goes back to the host and is compared element by element with
 the oracle's product of the same input bits (normalised error, tolerance of the dtype)."""
+from dataclasses import replace
+
 import numpy as np
 import pytest
 
@@ -77,13 +79,22 @@ def test_vgg19_sweep_cell(layer, log2_inv_density, dtype):
     _check_sampled(wl.vgg19_sweep_workload(layer, log2_inv_density, dtype))
 
 
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("gr,gb", [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)])
-def test_sdmm4096_table3_shape(gr, gb):
-    """Table 3's six (G_r, G_b) shapes at 87.5 % sparsity (G_o at 50 %)."""
-    _check_sampled(wl.sdmm4096_table3(gr, gb, 3))
+def test_sdmm4096_table3_shape(gr, gb, dtype):
+    """Table 3's six (G_r, G_b) shapes at 87.5 % sparsity (G_o at 50 %), on whatever family the library takes for
+    them (the mask itself or the mask with G_i filled in, stage lists split over the waves of a workgroup)."""
+    _check_sampled(replace(wl.sdmm4096_table3(gr, gb, 3), dtype=dtype))
 
 
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("o,i", [(0, 3), (2, 1), (3, 1)])
-def test_sdmm4096_table2_split(o, i):
+def test_sdmm4096_table2_split(o, i, dtype):
     """Table 2: all the sparsity in G_i, most of it in G_o, and G_o at 1/8."""
-    _check_sampled(wl.sdmm4096_table2(o, i))
+    _check_sampled(replace(wl.sdmm4096_table2(o, i), dtype=dtype))
+
+
+def test_sdmm4096_table3_first_row_at_every_density():
+    """One row per column set (G_r = G_b = (1, 1)): the filled family at 75, 87.5 and 93.75 %."""
+    for d in (2, 3, 4):
+        _check_sampled(wl.sdmm4096_table3(1, 1, d))
