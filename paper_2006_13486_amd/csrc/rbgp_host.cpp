@@ -994,9 +994,17 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
   m->kernel_choice = RBGP_KERNEL_AUTO;
   m->uid = rbgp_next_uid();
   m->dev = nullptr;
-  rbgp_plan_mfma(m);
-  rbgp_plan_reg(m);
-  rbgp_plan_filled(m);
+  try {   // (the plans allocate their host tables)
+    rbgp_plan_mfma(m);
+    rbgp_plan_reg(m);
+    rbgp_plan_filled(m);
+  } catch (const std::bad_alloc &) {
+    rbgp_mask_free(m);
+    return RBGP_ENOMEM;
+  } catch (...) {
+    rbgp_mask_free(m);
+    return RBGP_EINTERNAL;
+  }
   *out = m;
   return RBGP_OK;
 }
