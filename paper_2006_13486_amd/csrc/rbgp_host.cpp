@@ -498,7 +498,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out) {
     longest = std::max(longest, tiles * pl.NSTG);
   }
   const int TS = longest > kRegWaveStages ? 256 : 64;
-  const int stored = TS == 64 ? kRegWaveStages : kRegMaxStages;   // (the entries behind them stay -1: sentinels)
+  const int stored = TS;   // (entries past a list's end stay -1)
   std::vector<int32_t> stages(size_t(ncl) * (1 + U) * TS, -1);
   for (int c = 0; c < ncl; ++c) {
     int st = 0;

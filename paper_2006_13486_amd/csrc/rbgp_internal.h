@@ -71,10 +71,10 @@ struct rbgp_reg_plan {
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m);
 inline int rbgp_reg_step(const rbgp_mask *m, int kk);
 
-// Register-streaming family: a wave keeps its stage list in a lane-held table, one stage per lane, with
-// sentinels behind it (60 stages); a cluster's list may be up to four times that and is then split over
-// the waves of a workgroup (wave k takes stages k, k + S, ...).
-constexpr int kRegWaveStages = 60, kRegMaxStages = 240;
+// Register-streaming family: a wave keeps its stage list in a lane-held table, one stage per lane (64 stages;
+// reads past its count are turned into sentinels by the count); a cluster's list may be up to four times that
+// and is then split over the waves of a workgroup (wave k takes stages k, k + S, ...).
+constexpr int kRegWaveStages = 64, kRegMaxStages = 256;
 
 // Clustering of the tile rows for the register-streaming family (host tables).
 struct rbgp_reg_clusters {

@@ -126,10 +126,11 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
 #pragma unroll
   for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * TS];
   const int cnt0 = p.counts[cl];
-  const int cnt = cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0;   // stages of this wave
+  const int cnt = __builtin_amdgcn_readfirstlane(cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0);   // stages of this wave
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * MG + (lane & (MG - 1))];
-  // table lane of the wave's s-th stage; lanes past the wave's count hold sentinels
+  // table lane of the wave's s-th stage (all 64 lanes may hold stages: a stage past the wave's count is made a
+  // sentinel where it is read back -- zero extent, weights past the end of the buffer)
   auto table_lane = [&](int s) { return s < 63 ? s : 63; };
 
   // byte offset of this lane's 16 bytes in every slot, relative to the stage base.  Columns
@@ -182,8 +183,8 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
     const uint64_t base = uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_lo, tl))) |
                           (uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_hi, tl))) << 32);
     *sofs = 0;
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, __builtin_amdgcn_readlane(ib_ext, tl),
-                                             kRsrcFlags);
+    const int ext = __builtin_amdgcn_readlane(ib_ext, tl);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, s < cnt ? ext : 0, kRsrcFlags);
   };
 
   // Register sets = stages of loads in flight.  Two for the long stages; a stage of 8 steps is 8 MFMAs (256
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
       const int sv = __builtin_amdgcn_readlane(aoff[mm], tl);
       addr = mi == mm ? sv : addr;
     }
-    return addr + alane;
+    return (s < cnt ? addr : kOob) + alane;
   };
   auto a_load = [&](int addr, int q) { return load_x4(rw, addr, q * QB); };
 

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
   for (int mm = 0; mm < U; ++mm) tf[mm] = stg[(1 + mm) * TS];
   const int cnt = p.counts[cl];
-  const int cntw = cnt > ks ? (cnt - ks + S - 1) >> lgS : 0;   // stages of this wave
+  const int cntw = __builtin_amdgcn_readfirstlane(cnt > ks ? (cnt - ks + S - 1) >> lgS : 0);   // stages of this wave
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * U + (lane & (U - 1))];
 
@@ -154,21 +154,23 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
 #pragma unroll
   for (int mm = 0; mm < U; ++mm)
     aoff[mm] = (tf[mm] >= 0 && mem[mm] >= 0) ? ((mem[mm] * p.fpm + tf[mm]) * p.a3 + u3) * FB : kOob;
-  auto b_rsrc = [&](int tl, int *sofs) {
+  // (`live`: the stage is one of the wave's; all 64 table lanes may hold stages, and one past the count is made a
+  // sentinel here: zero extent, weights past the end of the buffer)
+  auto b_rsrc = [&](int tl, bool live, int *sofs) {
     const uint64_t base = uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_lo, tl))) |
                           (uint64_t(uint32_t(__builtin_amdgcn_readlane(ib_hi, tl))) << 32);
     *sofs = 0;
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, __builtin_amdgcn_readlane(ib_ext, tl),
-                                             kRsrcFlags);
+    const int ext = __builtin_amdgcn_readlane(ib_ext, tl);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, live ? ext : 0, kRsrcFlags);
   };
-  auto a_addr = [&](int tl, int gi) {
+  auto a_addr = [&](int tl, bool live, int gi) {
     int addr = 0;
 #pragma unroll
     for (int mm = 0; mm < MG; ++mm) {
       const int sv = __builtin_amdgcn_readlane(aoff[gi * MG + mm], tl);
       addr = mi == mm ? sv : addr;
     }
-    return addr + alane;
+    return (live ? addr : kOob) + alane;
   };
   __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
 
@@ -243,9 +245,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     __amdgpu_buffer_rsrc_t rb2 = rw;
     if constexpr (RELOAD) {
       const int tl = table_lane(s + 2);
-      rb2 = b_rsrc(tl, &sofs);
+      const bool live = s + 2 < cntw;
+      rb2 = b_rsrc(tl, live, &sofs);
 #pragma unroll
-      for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, gi);
+      for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, live, gi);
     }
     static_for<0, NB>([&](auto bc) {
       block(bc, B, A);
@@ -255,9 +258,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   auto fill = [&](int s, Raw<LW> (&B)[NLD], u32x4 (&A)[G][NB]) {
     int sofs, av[G];
     const int tl = table_lane(s);
-    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(tl, &sofs);
+    const bool live = s < cntw;
+    const __amdgpu_buffer_rsrc_t rb2 = b_rsrc(tl, live, &sofs);
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, gi);
+    for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, live, gi);
     static_for<0, NB>([&](auto bc) { load_block(bc, B, A, rb2, sofs, av); });
   };
 

@@ -255,32 +255,34 @@ def test_shapes_across_the_kernel_table(idx, dtype):
             gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
 
 
-# stage lists longer than the 60 stages one wave holds: split over 2 or 4 waves of the workgroup
+# stage lists as long as or longer than the 64 stages one wave holds: split over 2 or 4 waves of the workgroup
 LONG_LISTS = [
     ((4, 2, 2, 1), (128, 1, 2, 1), (64, 1, 2, 1)),     # 64 tiles per tile row (complete G_i joins G_r): 2 waves
     ((2, 4, 1, 2), (128, 1, 1, 2), (128, 1, 1, 2)),    # complete G_o of 128 tiles: 4 waves
     ((4, 2, 4, 2), (64, 4, 8, 9), (32, 4, 4, 9)),      # two stages of 72 steps per tile, four tile rows per cluster
-    ((8, 1, 4, 1), (64, 2, 4, 2), (16, 2, 1, 2)),      # clusters of 8 tile rows whose union exceeds one wave's table
+    ((8, 1, 4, 1), (64, 2, 4, 2), (16, 2, 1, 2)),      # clusters of 8 tile rows whose union fills one wave's table to the last lane
 ]
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
 @pytest.mark.parametrize("idx", range(len(LONG_LISTS)))
 def test_register_family_stage_lists_beyond_one_wave(idx, dtype):
-    """Clusters that walk 61..240 stages: the register kernels split the list over the waves of a workgroup
+    """Clusters that walk 64..256 stages: beyond 64 the register kernels split the list over the waves of a workgroup
     whatever N is (default launch), also with the largest split asked for; the tables pass the self check."""
     rows, cols, deg = LONG_LISTS[idx]
     for N in (200, 1100):
         w = wl.Workload(f"long{idx}_{dtype}", rows, cols, deg, N, dtype, 400 + idx, 500 + idx, 600 + idx, 1.0)
         m = gh.make_mask(w)
         rb.rbgp_mask_check_tables(m)
-        assert 60 < rb.rbgp_mask_reg_plan(m)[5] <= 240
+        assert 64 <= rb.rbgp_mask_reg_plan(m)[5] <= 256
         gh.check_parity(w, kernel=REG, expect_kernel=REG, ld_pad=8)
         gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 4), expect_kernel=REG)
-    if rb.rbgp_mask_reg_plan(m)[5] > 120:        # two waves cannot hold this list
+    if rb.rbgp_mask_reg_plan(m)[5] > 64:         # one wave cannot hold this list
         with pytest.raises(rb.RbgpError) as e:
-            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 2), expect_kernel=REG)
+            gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 1), expect_kernel=REG)
         assert e.value.code == rb.EUNSUPPORTED
+    else:
+        gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 0, 1), expect_kernel=REG)
 
 
 # masks with at most four rows per column set and a sparse G_i (the shapes of Table 3's slow rows, small)
