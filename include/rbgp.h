@@ -114,7 +114,11 @@ enum {
   RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG: waves that share a column tile and split its
                                          nonzero tiles between them, 1, 2 or 4 (default: 1 unless N
                                          is too small to give every SIMD a wave) */
-  RBGP_NUM_TUNE = 6
+  RBGP_TUNE_COLUMN_TILES = 6,         /* MFMA_REG fp32, stages of up to 8 contraction steps, every tile row with
+                                         the same number of tiles: column tiles (64 columns each) a wave takes
+                                         one after the other, 1, 2, 4 or 8 (EUNSUPPORTED where the stage lists of
+                                         that many tiles exceed 64 stages, for rbgp_conv3x3 and with a split) */
+  RBGP_NUM_TUNE = 7
 };
 
 /* Device tables.  A mask keeps small index tables in device memory (adjacency lists, stage lists,

@@ -73,8 +73,10 @@ namespace {
 // of I feeds NG groups of MFMAs: the rows of I cross the load path of the CU 1/NG as often (a stage of 72 steps
 // asks for 23 KB per 2304 MFMA cycles and wave, ~40 B/clk per CU with four waves, close to what the path
 // delivers), at NG times the accumulators.
-template <int KC, int RS, bool TAPS = false, int NG = 1>
-__global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
+// CTILES (stages of up to 8 steps): the variant whose waves take several column tiles one after the other.
+template <int KC, int RS, bool TAPS = false, int NG = 1, bool CTILES = false>
+__global__ __launch_bounds__(256, (KC <= 8 && NG <= 2 ? (CTILES || NG == 2 ? 2 : RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
+  static_assert(!CTILES || (KC <= 8 && !TAPS), "column tiles per wave: short stages, not the fused convolution");
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   static_assert(NG == 1 || RS == 16, "several groups per wave: one tile row per group");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
@@ -100,11 +102,16 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
   WgCoord wg;
   if (!wg_coord(p, &wg)) return;
   const int cl = wg.cl * NG, u3 = wg.u3, ntq = wg.ntq;   // (NG > 1: the first of the wave's NG tile rows; all share its tables)
-  const int nt = (ntq << (2 - lgS)) + (wid >> lgS);
+  // Register sets = stages of loads in flight.  Two for the long stages; a stage of 8 steps is 8 MFMAs (256
+  // cycles), and two of them ahead cover far less than a memory access takes: such kernels keep four.
+  constexpr int D = KC <= 8 ? 4 : 2;
+  // Short stages, every stage list of the same length: a wave takes `ct` neighbouring column tiles one after the
+  // other as ONE list of ct * (stages per tile) stages (lane l of the stage table then serves column tile
+  // l / stages-per-tile), so the tables are fetched once and the first rows of the next tile are on their way while
+  // the last stages of this one are multiplied; the sums of a tile are stored when its last stage is done.
+  const int ct = CTILES ? p.ct : 1;
+  const int nt = ((ntq << (2 - lgS)) + (wid >> lgS)) * ct;   // (the first of them)
   const int64_t n0 = int64_t(nt) * CW;
-  // byte offset of the wave's first column in a row of I (fused convolution: the lane's own
-  // column offset inside a channel of X, see `off` below)
-  const uint32_t n0b = p.conv ? 0u : uint32_t(nt) * uint32_t(CW * 4);
   const int g = lane >> 4, j = lane & 15;
   const int mi = j / RS, ri = j % RS;    // as a weight lane: member of the group, row of the member
 
@@ -119,14 +126,24 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
   for (int o = 0; o < NO; ++o) rrow[o] = rt[o * 4];
   // the wave's own stages, one per lane: stage ks + lane * S of the cluster's list
   const int TS = p.tstride;
-  const int own = ks + (lane << lgS);
+  int own = ks + (lane << lgS), ctile = 0;
+  if (CTILES) {
+    ctile = lane / p.ct_cnt;
+    own = lane - ctile * p.ct_cnt;
+  }
+  // byte offset of the first column (of the lane's table entry's tile) in a row of I (fused convolution: the
+  // lane's own column offset inside a channel of X, see `off` below)
+  const uint32_t n0b = p.conv ? 0u : uint32_t(nt + ctile) * uint32_t(CW * 4);
+  const bool tile_ok = nt + ctile < p.ntiles;
   const int32_t *stg = p.stages + int64_t(cl) * (1 + MG) * TS + (own < TS ? own : TS - 1);
   const int tb = stg[0];
   int tf[MG];
 #pragma unroll
   for (int mm = 0; mm < MG; ++mm) tf[mm] = stg[(1 + mm) * TS];
   const int cnt0 = p.counts[cl];
-  const int cnt = __builtin_amdgcn_readfirstlane(cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0);   // stages of this wave
+  const int tiles_here = p.ntiles - nt < ct ? p.ntiles - nt : ct;
+  const int cnt = __builtin_amdgcn_readfirstlane(   // stages of this wave
+      CTILES ? p.ct_cnt * (tiles_here > 0 ? tiles_here : 0) : cnt0 > ks ? (cnt0 - ks + S - 1) >> lgS : 0);
   const int rov = p.rowofs[lane & 15];   // lane-held copies, read back with bpermute in the epilogue
   const int memv = p.members[cl * MG + (lane & (MG - 1))];
   // table lane of the wave's s-th stage (all 64 lanes may hold stages: a stage past the wave's count is made a
@@ -171,7 +188,7 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
   const uint64_t i_first = reinterpret_cast<uint64_t>(p.I) + uint64_t(uint32_t(tbu)) * p.row_bytes + n0b;
   const int ib_lo = int(uint32_t(i_first)), ib_hi = int(uint32_t(i_first >> 32));
   const int rows_left = p.last_row - tbu < p.src_rows ? p.last_row - tbu : p.src_rows;
-  const int ib_ext = (tb >= 0 && valid) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
+  const int ib_ext = (tb >= 0 && tile_ok) ? int(uint32_t(rows_left) * p.row_bytes + (p.n_bytes - n0b)) : 0;
   // per-lane byte offset of each member's weights: a tile row that lacks the tile reads at an
   // offset past the weight buffer (zeros)
   int aoff[MG];
@@ -187,9 +204,6 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
     return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(base), 0, s < cnt ? ext : 0, kRsrcFlags);
   };
 
-  // Register sets = stages of loads in flight.  Two for the long stages; a stage of 8 steps is 8 MFMAs (256
-  // cycles), and two of them ahead cover far less than a memory access takes: such kernels keep four.
-  constexpr int D = KC <= 8 ? 4 : 2;
   f32x4 Bs[D][NO];
   f32x4 As[D][NG][NQ];
   if (!valid && lgS == 0) return;   // (with a split stage list every wave reaches the barrier below)
@@ -335,6 +349,45 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
     });
   };
 
+  // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Unit t of the sum holds
+  // weight row 4*(lane/16) + t of the group, lane j the columns 4j + w (of the column tile that starts at n0c).
+  auto unit = [&](int t, int k = 0) {
+    f32x4 v;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) v[w] = (acc[k][w][t] + acc[k][w][4 + t]) + (acc[k][w][8 + t] + acc[k][w][12 + t]);
+    return v;
+  };
+  // (the kernel arguments the stores need, read once: inside the store helpers they would be fetched again per unit)
+  float *const out = p.O;
+  const int64_t out_ld = p.ldO, out_n = p.N;
+  const int out_tm = p.tm, out_a4 = p.a4, out_r = p.R;
+  const bool out_aligned = (out_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0);
+  auto vec_ok_at = [&](int64_t n0c) { return out_aligned && (n0c + j * 4 + 4 <= out_n); };
+  auto store_unit = [&](int t, f32x4 v, int k, int64_t n0c, bool vec_ok) {
+    const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
+    int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
+    if constexpr (NG > 1) u1 = u1 >= 0 ? u1 + k : u1;   // (group k is the tile row after group k - 1's)
+    const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
+    if (valid && u1 >= 0 && r < out_r) {
+      const int64_t m = int64_t(u1) * out_tm + u3 * out_a4 + ro;
+      float *o = out + m * out_ld + n0c + j * 4;
+      if (vec_ok) {
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          if (n0c + j * 4 + w < out_n) o[w] = v[w];
+      }
+    }
+  };
+  auto store_tile = [&](int64_t n0c) {
+    const bool vec_ok = vec_ok_at(n0c);
+#pragma unroll
+    for (int k = 0; k < NG; ++k)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) store_unit(t, unit(t, k), k, n0c, vec_ok);
+  };
+
   // The register sets take turns; stages past the end read zeros (sentinel table lanes).
   if constexpr (D == 2) {
     f32x4(&B0)[NO] = Bs[0], (&B1)[NO] = Bs[1];
@@ -355,6 +408,31 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
     // counts); the last, partial round only consumes what is already on its way
     static_for<0, D>([&](auto kc) { fill(decltype(kc)::value, Bs[decltype(kc)::value], As[decltype(kc)::value]); });
     int s = 0;
+    if constexpr (CTILES) {
+      // several column tiles, one list: every tile has p.ct_cnt stages, a multiple of D, so a tile ends with a
+      // round; its sums are stored while the first stages of the next tile are already in flight
+      int left = p.ct_cnt;
+      int64_t n0c = n0;
+      for (; s + D <= cnt; s += D) {
+        static_for<0, D>([&](auto kc) {
+          constexpr int k = decltype(kc)::value;
+          stage(s + k, Bs[k], As[k], std::true_type{});
+        });
+        left -= D;
+        if (left == 0) {
+          store_tile(n0c);
+#pragma unroll
+          for (int k = 0; k < NG; ++k)
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) acc[k][w][v] = 0.f;
+          n0c += CW;
+          left = p.ct_cnt;
+        }
+      }
+      return;
+    }
     for (; s + D <= cnt; s += D)
       static_for<0, D>([&](auto kc) {
         constexpr int k = decltype(kc)::value;
@@ -367,37 +445,8 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
   }
   __builtin_amdgcn_s_waitcnt(0);
 
-  // epilogue: add the four blocks (contraction steps 0..3 mod 4).  Unit t of the sum holds
-  // weight row 4*(lane/16) + t of the group, lane j the columns 4j + w.
-  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
-  auto unit = [&](int t, int k = 0) {
-    f32x4 v;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) v[w] = (acc[k][w][t] + acc[k][w][4 + t]) + (acc[k][w][8 + t] + acc[k][w][12 + t]);
-    return v;
-  };
-  auto store_unit = [&](int t, f32x4 v, int k = 0) {
-    const int i16 = 4 * g + t, mm = i16 / RS, r = i16 % RS;
-    int u1 = __builtin_amdgcn_ds_bpermute(mm * 4, memv);
-    if constexpr (NG > 1) u1 = u1 >= 0 ? u1 + k : u1;   // (group k is the tile row after group k - 1's)
-    const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
-    if (valid && u1 >= 0 && r < p.R) {
-      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
-      float *o = p.O + m * p.ldO + n0 + j * 4;
-      if (vec_ok) {
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
-      } else {
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-          if (n0 + j * 4 + w < p.N) o[w] = v[w];
-      }
-    }
-  };
   if (lgS == 0) {
-#pragma unroll
-    for (int k = 0; k < NG; ++k)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) store_unit(t, unit(t, k), k);
+    store_tile(n0);
   } else {
     // The S waves of a column tile each own the units t with t % S == their share.  A wave
     // leaves the units it does not own in LDS (densely: unit t of owner o sits at
@@ -405,6 +454,7 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
     // adds up the ones it owns in wave order, so the result does not depend on timing.
     f32x4 *const red4 = reinterpret_cast<f32x4 *>(wlds);
     const int per_wave = (4 >> lgS) * (S - 1);
+    const bool vec_ok = vec_ok_at(n0);
 #pragma unroll
     for (int k = 0; k < NG; ++k)
 #pragma unroll
@@ -427,7 +477,7 @@ __global__ __launch_bounds__(256, (KC <= 8 && NG == 1 ? (RS >= 4 ? 4 : 3) : 1)) 
             else
               v += red4[((k * 4 + w0 + kk) * per_wave + (t >> lgS) * (S - 1) + ks - (ks > kk ? 1 : 0)) * 64 + lane];
           }
-          store_unit(t, v, k);
+          store_unit(t, v, k, n0, vec_ok);
         }
       }
   }
@@ -464,6 +514,20 @@ const RegGroupEntry kRegGroupTable[] = {RBGP_RG(8, 2),  RBGP_RG(18, 2), RBGP_RG(
 const RegGroupEntry *find_reg_groups(int KC, int NG) {
   for (const RegGroupEntry &e : kRegGroupTable)
     if (e.KC == KC && e.NG == NG) return &e;
+  return nullptr;
+}
+// waves that take several column tiles (stages of 8 steps): {RS, NG, kernel}
+struct RegTilesEntry {
+  int RS, NG;
+  reg_fn fn;
+};
+const RegTilesEntry kRegTilesTable[] = {{2, 1, spmm_reg<8, 2, false, 1, true>},   {4, 1, spmm_reg<8, 4, false, 1, true>},
+                                        {8, 1, spmm_reg<8, 8, false, 1, true>},   {16, 1, spmm_reg<8, 16, false, 1, true>},
+                                        {16, 2, spmm_reg<8, 16, false, 2, true>}};
+reg_fn find_reg_tiles(int KC, int RS, int NG) {
+  if (KC != 8) return nullptr;
+  for (const RegTilesEntry &e : kRegTilesTable)
+    if (e.RS == RS && e.NG == NG) return e.fn;
   return nullptr;
 }
 const RegEntry kRegTable[] = {RBGP_R(8, 2),  RBGP_R(18, 2),  RBGP_R(32, 2),  RBGP_R(36, 2),  RBGP_R(72, 2),
@@ -750,9 +814,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   // (see spmm_reg), as many as still leave every SIMD a wave; tuning knob RBGP_TUNE_ROW_GROUPS overrides.
   int NGf = 1;
   const RegGroupEntry *ge = nullptr;
+  bool ident = !bf16 && !dual && pl.MG == 1 && pl.fold > 1;   // (clusters of one tile row that come in tile-row order)
+  for (int c = 0; c < m->reg_clusters.ncl && ident; ++c) ident = m->reg_clusters.members[size_t(c)] == c;
   if (!bf16 && !dual && pl.MG == 1 && pl.fold > 1) {
-    bool ident = true;   // (clusters of one tile row come in tile-row order)
-    for (int c = 0; c < m->reg_clusters.ncl && ident; ++c) ident = m->reg_clusters.members[size_t(c)] == c;
     auto fits = [&](int ng) {
       const RegGroupEntry *g = find_reg_groups(pl.KC, ng);
       return ident && pl.fold % ng == 0 && g && (!taps || g->taps_fn);
@@ -775,6 +839,37 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (NGf > 1) ge = find_reg_groups(pl.KC, NGf);
   } else if (!bf16 && tune[RBGP_TUNE_ROW_GROUPS] > 1) {
     return RBGP_EUNSUPPORTED;
+  }
+  // fp32, stages of up to 8 steps (short waves, mostly latency): column tiles per wave (see spmm_reg); tuning knob
+  // RBGP_TUNE_COLUMN_TILES overrides.
+  int CT = 1;
+  {
+    const int tc = tune[RBGP_TUNE_COLUMN_TILES];
+    bool can = !bf16 && !dual && !conv && find_reg_tiles(pl.KC, pl.RS, NGf) && lgS == 0 && tab->max_stages > 0 && tab->max_stages % 4 == 0 &&
+               m->reg_clusters.U == pl.MG;
+    for (size_t c = 0; can && c < m->reg_clusters.counts.size(); ++c) can = m->reg_clusters.counts[c] == tab->max_stages;
+    auto fits = [&](int c) { return can && (c == 2 || c == 4 || c == 8) && tab->max_stages * c <= kRegWaveStages; };
+    auto waves = [&](int ng, int c) { return int64_t(tab->ncl / ng) * m->a[2] * ((ntiles + c - 1) / c); };
+    if (tc > 1) {
+      if (!fits(tc)) return RBGP_EUNSUPPORTED;
+      CT = tc;
+    } else if (tc == 0 && NGf == 1) {
+      // Measured on the conv5 backward data product (64 tile rows of 9 rows, 8 stages of 8 steps, 16 384 such
+      // waves), us per launch on one box: one tile per wave 31.2, four 29.6; two of the tile rows that share their
+      // tiles per wave as well (each row of dO loaded half as often; two waves per SIMD) 27.8 with four tiles, 28.8
+      // with two, 32.4 with eight.  The waves must still fill the SIMDs: three each with one row group, two with two.
+      if (tune[RBGP_TUNE_ROW_GROUPS] == 0 && ident && pl.fold % 2 == 0 && find_reg_tiles(pl.KC, pl.RS, 2) && fits(4) &&
+          waves(2, 4) >= 2048) {
+        NGf = 2;
+        CT = 4;
+      } else {
+        for (int c : {4, 2})
+          if (fits(c) && waves(1, c) >= 3072) {
+            CT = c;
+            break;
+          }
+      }
+    }
   }
   const int ncl = dual ? m->reg_dual.nq : tab->ncl / NGf;
   const int fpm = m->d[0] * pl.NSTG;
@@ -832,7 +927,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   for (int r = 0; r < 16; ++r) rp.rowofs[r] = (r / m->a[3]) * m->a[2] * m->a[3] + r % m->a[3];
   rp.ntiles = int(ntiles);
   rp.lgS = lgS;
-  const int64_t tiles_per_wg = 4 >> lgS;
+  const int64_t tiles_per_wg = (4 >> lgS) * CT;
+  rp.ct = CT;
+  rp.ct_cnt = tab->max_stages;
   const int64_t nquads = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
   // one-dimensional grid, items dealt to the XCDs in blocks (see RegParams)
   // (measured on one box, us: conv5 18.0 / 18.2 / 18.2 with order 1 / 0 / 2; conv3 bf16 20.2 / 17.8 / 17.6; WRN 90.9 / 76.4 / 75.9)
@@ -843,8 +940,9 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.ncl = ncl;
   rp.per_xcd = int(per_xcd);
   rp.ngroups = int(nquads);
-  reg_fn fn = dual ? nullptr
-              : bf16 ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW)
+  reg_fn fn = dual     ? nullptr
+              : bf16   ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW)
+              : CT > 1 ? find_reg_tiles(pl.KC, pl.RS, NGf)
               : ge   ? (taps ? ge->taps_fn : ge->global_fn)
               : taps ? e->taps_fn
                      : e->global_fn;

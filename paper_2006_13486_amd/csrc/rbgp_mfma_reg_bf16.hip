@@ -172,6 +172,11 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     }
     return (live ? addr : kOob) + alane;
   };
+  // (the kernel arguments the epilogue needs, read here with the tables: fetched after the loop, they would add
+  // scalar-load latencies to the end of every wave)
+  float *const out = p.O;
+  const int64_t out_ld = p.ldO, out_n = p.N;
+  const int out_tm = p.tm, out_a4 = p.a4, out_r = p.R, out_bf16 = p.obf16;
   __builtin_amdgcn_s_waitcnt(0);   // drain the table loads outside the loop (see the fp32 kernel)
 
   f32x4 acc[G][NC];
@@ -282,10 +287,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
   // Epilogue.  Unit (gi, t) = register t of group gi's NC accumulators: weight row
   // 4*(lane/16) + t of the group, lane j the columns NC*j + w.
   // (bf16 output: a lane's NC columns are 2 * NC bytes, stored whole when they are aligned)
-  const bool obf = p.obf16 != 0;
-  const bool vec_ok = (n0 + j * NC + NC <= p.N) &&
-                      (obf ? (p.ldO % NC == 0) && (reinterpret_cast<uintptr_t>(p.O) % (2 * NC) == 0)
-                           : (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0));
+  const bool obf = out_bf16 != 0;
+  const bool vec_ok = (n0 + j * NC + NC <= out_n) &&
+                      (obf ? (out_ld % NC == 0) && (reinterpret_cast<uintptr_t>(out) % (2 * NC) == 0)
+                           : (out_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0));
   auto unit_piece = [&](int gi, int t, int h) {
     return f32x4{acc[gi][4 * h][t], acc[gi][4 * h + 1][t], acc[gi][4 * h + 2][t], acc[gi][4 * h + 3][t]};
   };
@@ -293,10 +298,10 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     const int i16 = 4 * kg + t, mm = i16 / RS, r = i16 % RS;
     const int u1 = __builtin_amdgcn_ds_bpermute((gi * MG + mm) * 4, memv);
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
-    if (valid && u1 >= 0 && r < p.R) {
-      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
+    if (valid && u1 >= 0 && r < out_r) {
+      const int64_t m = int64_t(u1) * out_tm + u3 * out_a4 + ro;
       if (obf) {
-        uint16_t *o = reinterpret_cast<uint16_t *>(p.O) + m * p.ldO + n0 + j * NC;
+        uint16_t *o = reinterpret_cast<uint16_t *>(out) + m * out_ld + n0 + j * NC;
         if (vec_ok) {
           if constexpr (NH == 2) {
             const u32x4 w = {bf16_pair(v[0][0], v[0][1]), bf16_pair(v[0][2], v[0][3]), bf16_pair(v[1][0], v[1][1]),
@@ -311,11 +316,11 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
           for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int w = 0; w < 4; ++w)
-              if (n0 + j * NC + 4 * h + w < p.N) o[4 * h + w] = uint16_t(bf16_bits(v[h][w]));
+              if (n0 + j * NC + 4 * h + w < out_n) o[4 * h + w] = uint16_t(bf16_bits(v[h][w]));
         }
         return;
       }
-      float *o = p.O + m * p.ldO + n0 + j * NC;
+      float *o = out + m * out_ld + n0 + j * NC;
       if (vec_ok) {
 #pragma unroll
         for (int h = 0; h < NH; ++h) __builtin_nontemporal_store(v[h], reinterpret_cast<f32x4 *>(o) + h);
@@ -324,7 +329,7 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
         for (int h = 0; h < NH; ++h)
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            if (n0 + j * NC + 4 * h + w < p.N) o[4 * h + w] = v[h][w];
+            if (n0 + j * NC + 4 * h + w < out_n) o[4 * h + w] = v[h][w];
       }
     }
   };

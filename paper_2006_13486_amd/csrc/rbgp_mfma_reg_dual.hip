@@ -58,6 +58,11 @@ __global__ __launch_bounds__(512) void spmm_reg_dual(DualParams dp) {
   const i32x4 *qd = reinterpret_cast<const i32x4 *>(tab + dp.o_quads) + cl * 2;
   const i32x4 quad_rows = qd[0], quad_counts = qd[1];
   const int cmax = dp.cmax;
+  // (the kernel arguments the epilogue needs, read here with the tables: fetched after the loop, they would add
+  // scalar-load latencies to the end of every wave)
+  float *const out = p.O;
+  const int64_t out_ld = p.ldO, out_n = p.N;
+  const int out_tm = p.tm, out_a4 = p.a4, out_r = p.R;
   const i32x4 *stg = reinterpret_cast<const i32x4 *>(tab + dp.o_stages) + ((cl * 2 + x) * 2 + y) * cmax;
   const i32x4 entry = stg[lane < cmax ? lane : cmax - 1];
   // stage-relative row of I of contraction step 4 * o + g, for this lane's g
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(512) void spmm_reg_dual(DualParams dp) {
   }
   __syncthreads();
   if (x != y) return;
-  const bool vec_ok = (p.ldO % 4 == 0) && (reinterpret_cast<uintptr_t>(p.O) % 16 == 0) && (n0 + j * 4 + 4 <= p.N);
+  const bool vec_ok = (out_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0) && (n0 + j * 4 + 4 <= out_n);
   const int u1 = g < 2 ? rowL : rowH;
   // wave (0, 0): lo rows from (0, 1), hi rows from (1, 0); wave (1, 1): lo rows from (1, 0), hi rows from (0, 1)
   const int giver = g < 2 ? x : 1 - x;
@@ -205,15 +210,15 @@ __global__ __launch_bounds__(512) void spmm_reg_dual(DualParams dp) {
     const f32x4 v = mine + other;
     const int r = 4 * (g & 1) + t;
     const int ro = __builtin_amdgcn_ds_bpermute(r * 4, rov);
-    if (valid && u1 >= 0 && r < p.R) {
-      const int64_t m = int64_t(u1) * p.tm + u3 * p.a4 + ro;
-      float *o = p.O + m * p.ldO + n0 + j * 4;
+    if (valid && u1 >= 0 && r < out_r) {
+      const int64_t m = int64_t(u1) * out_tm + u3 * out_a4 + ro;
+      float *o = out + m * out_ld + n0 + j * 4;
       if (vec_ok) {
         __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (n0 + j * 4 + c < p.N) o[c] = v[c];
+          if (n0 + j * 4 + c < out_n) o[c] = v[c];
       }
     }
   }

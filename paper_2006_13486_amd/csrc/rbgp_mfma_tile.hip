@@ -108,6 +108,11 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
   // its tiles) comes from the kernel arguments when it fits them, else it is copied to LDS first
   // (reading it later must not wait for the loads in flight).
   const bool inl = p.inl_ok != 0;
+  // (the kernel arguments the epilogue needs, read here: fetched after the loop, they would add scalar-load
+  // latencies to the end of every consumer wave)
+  void *const out = p.O;
+  const int64_t out_ld = p.ldO, out_n = p.N;
+  const int out_bf16 = p.obf16;
   const int rec = p.max_stages + 4 * p.d_o;    // words per row group
   const int cnt = inl ? p.inl[p.RG * rec + rg] : p.counts[rg];
   int32_t *const tab = reinterpret_cast<int32_t *>(lds_raw);
@@ -297,16 +302,16 @@ __global__ __launch_bounds__(512) void spmm_tile_bf16(TileParams p) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int64_t n = n0 + 32 * h + n32;
-    if (n >= p.N) continue;
+    if (n >= out_n) continue;
     const int64_t m0 = int64_t(u_o) * TM + 4 * h2;
-    if (p.obf16) {
-      uint16_t *o = reinterpret_cast<uint16_t *>(p.O) + m0 * p.ldO + n;
+    if (out_bf16) {
+      uint16_t *o = reinterpret_cast<uint16_t *>(out) + m0 * out_ld + n;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * p.ldO] = uint16_t(bf16_bits(acc[h][r]));
+      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * out_ld] = uint16_t(bf16_bits(acc[h][r]));
     } else {
-      float *o = reinterpret_cast<float *>(p.O) + m0 * p.ldO + n;
+      float *o = reinterpret_cast<float *>(out) + m0 * out_ld + n;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * p.ldO] = acc[h][r];
+      for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * out_ld] = acc[h][r];
     }
   }
 }

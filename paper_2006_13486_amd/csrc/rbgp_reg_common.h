@@ -67,6 +67,8 @@ struct RegParams {
   int ntiles;              // column tiles: ceil(N / columns per wave)
   int lgS;                 // log2 of the waves that share a column tile (split of the stage list)
   int ncl;                 // clusters of tile rows (pairing kernel: quads)
+  int ct, ct_cnt;          // fp32 kernels with stages of up to 8 steps: column tiles a wave takes one after the other (1 elsewhere)
+                           //   and, when that is more than one, the stages of every cluster's list (all equal, a multiple of 4)
   // Workgroups (one-dimensional grid) are dealt round-robin to the 8 XCDs, so workgroup id & 7 is the XCD, each with
   // its own L2; within an XCD they start in the order of their ids.  A unit is a (G_i vertex, group of column
   // tiles) pair; the clusters of a unit are always neighbours on one XCD (they read the same rows of I).  order:

@@ -371,6 +371,49 @@ def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
     assert e.value.code == rb.EUNSUPPORTED
 
 
+# stages of 8 contraction steps, every stage list of the same length (a multiple of 4): waves that take several
+# column tiles one after the other.  (rows, cols, degrees, column tiles per wave to try, row groups per wave)
+COLUMN_TILE_SHAPES = [
+    ((8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4, 8), 1),    # a transposed 3x3 layer: 36 rows -> 4 x 9, lists of 4
+    ((8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4), 2),       # the same with two of the four tile rows per wave
+    ((4, 2, 2, 4), (4, 2, 4, 2), (4, 2, 2, 2), (2, 8), 1),       # 8 rows per column set, complete G_o: lists of 4
+    ((8, 2, 2, 2), (8, 1, 4, 4), (8, 1, 2, 4), (2, 4, 8), 1),    # 4 rows per column set, lists of 8
+    ((8, 1, 4, 1), (8, 2, 4, 2), (8, 2, 2, 2), (4,), 1),         # one row per column set, lists of 8
+    ((8, 4, 4, 9), (8, 3, 4, 2), (4, 3, 1, 2), (4,), 1),         # stages of 6 steps in 8
+]
+
+
+@pytest.mark.parametrize("idx", range(len(COLUMN_TILE_SHAPES)))
+def test_fp32_register_family_column_tiles_per_wave(idx):
+    """RBGP_TUNE_COLUMN_TILES: N of one tile, of several waves' worth with a ragged last tile and a last wave that has
+    fewer tiles than the others, padded leading dimension."""
+    rows, cols, deg, tiles, ng = COLUMN_TILE_SHAPES[idx]
+    w = wl.Workload(f"coltiles{idx}", rows, cols, deg, 333, wl.F32, 140 + idx, 150 + idx, 160 + idx, 1.0)
+    for ct in tiles:
+        tune = (0, 0, 0, 0, ng, 1, ct)   # (no split of the stage lists, which small N would bring)
+        gh.check_parity(w, kernel=REG, tune=tune, ld_pad=3, expect_kernel=REG)          # 6 tiles
+        gh.check_parity(w, N=64, kernel=REG, tune=tune, expect_kernel=REG)              # one tile
+        gh.check_parity(w, N=2309, kernel=REG, tune=tune, ld_pad=1, expect_kernel=REG)  # 37 tiles
+    if 8 not in tiles and rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(rows, cols, deg, w.mask_seed))[5] == 8:
+        gh.check_parity(w, N=1024, kernel=REG, tune=(0, 0, 0, 0, ng, 1, 8), expect_kernel=REG)   # 8 x 8 = the 64 table lanes
+
+
+def test_column_tiles_per_wave_refusals_and_default():
+    # stage lists of different lengths (sparse G_o, two tile rows per group), the fused convolution, a split list,
+    # stages of more than 8 steps, bf16: refused
+    ragged = wl.Workload("coltiles_ragged", (16, 2, 2, 4), (16, 2, 4, 2), (8, 2, 2, 2), 256, wl.F32, 171, 172, 173, 1.0)
+    long_steps = wl.Workload("coltiles_18", (8, 4, 4, 9), (8, 4, 4, 2), (4, 4, 2, 2), 256, wl.F32, 174, 175, 176, 1.0)
+    ok = wl.Workload("coltiles_ok", (8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), 256, wl.F32, 177, 178, 179, 1.0)
+    for w, tune in ((ragged, (0, 0, 0, 0, 0, 1, 2)), (long_steps, (0, 0, 0, 0, 0, 1, 2)), (ok, (0, 0, 0, 0, 0, 2, 2)),
+                    (ok, (0, 0, 0, 0, 0, 1, 3)), (ok, (0, 0, 0, 0, 0, 1, 32)), (replace(ok, dtype=wl.BF16), (0, 0, 0, 0, 0, 1, 2))):
+        with pytest.raises(rb.RbgpError) as e:
+            gh.check_parity(w, kernel=REG, tune=tune, expect_kernel=REG)
+        assert e.value.code == rb.EUNSUPPORTED
+    # the library's own choice on the backward data product of the headline layer (64 tile rows of 9 rows, 8 stages of
+    # 8 steps): whatever it takes, the result is the oracle's
+    gh.check_parity(ok, N=8192, kernel=rb.KERNEL_AUTO)
+
+
 def test_activations_beyond_4_gib():
     """An I of 4.6 GB (WRN shape, 2 000 037 columns, odd leading dimension): the kernels'
     32-bit offsets must only span one stage.  A sample of output columns is checked."""
