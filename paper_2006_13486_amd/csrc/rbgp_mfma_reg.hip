@@ -72,10 +72,13 @@ namespace {
 // index, NG consecutive tile rows have the very same tiles; one wave then takes NG of them, and every loaded row
 // of I feeds NG groups of MFMAs: the rows of I cross the load path of the CU 1/NG as often (a stage of 72 steps
 // asks for 23 KB per 2304 MFMA cycles and wave, ~40 B/clk per CU with four waves, close to what the path
-// delivers), at NG times the accumulators.
+// delivers), at NG times the accumulators.  Two groups with stages of up to 32 steps (36 tap-grouped) still fit two
+// waves per SIMD without spilling; the larger ones get one.
 // CTILES (stages of up to 8 steps): the variant whose waves take several column tiles one after the other.
 template <int KC, int RS, bool TAPS = false, int NG = 1, bool CTILES = false>
-__global__ __launch_bounds__(256, (KC <= 8 && NG <= 2 ? (CTILES || NG == 2 ? 2 : RS >= 4 ? 4 : 3) : 1)) void spmm_reg(RegParams p) {
+__global__ __launch_bounds__(256, (NG == 2 && (KC <= 32 || (KC == 36 && TAPS)) ? 2
+                                   : KC <= 8 && NG == 1                         ? (CTILES ? 2 : RS >= 4 ? 4 : 3)
+                                                                                : 1)) void spmm_reg(RegParams p) {
   static_assert(!CTILES || (KC <= 8 && !TAPS), "column tiles per wave: short stages, not the fused convolution");
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   static_assert(NG == 1 || RS == 16, "several groups per wave: one tile row per group");
@@ -835,6 +838,11 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
           NGf = ng;
           break;
         }
+      // (the kernels of two groups with stages of up to 32 steps fit two waves per SIMD, like those of one group or
+      // nearly so: there two groups pay from 64 steps on, while every SIMD still gets its two waves)
+      if (NGf == 1 && fits(2) && pl.KC <= 32 && !taps && steps >= (64 << lgS) &&
+          ((int64_t(tab->ncl / 2) * m->a[2] * ntiles) << lgS) >= 2048)
+        NGf = 2;
     }
     if (NGf > 1) ge = find_reg_groups(pl.KC, NGf);
   } else if (!bf16 && tune[RBGP_TUNE_ROW_GROUPS] > 1) {
@@ -853,6 +861,12 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
     if (tc > 1) {
       if (!fits(tc)) return RBGP_EUNSUPPORTED;
       CT = tc;
+    } else if (tc == 0 && NGf == 2) {
+      for (int c : {4, 2})
+        if (fits(c) && waves(2, c) >= 2048) {
+          CT = c;
+          break;
+        }
     } else if (tc == 0 && NGf == 1) {
       // Measured on the conv5 backward data product (64 tile rows of 9 rows, 8 stages of 8 steps, 16 384 such
       // waves), us per launch on one box: one tile per wave 31.2, four 29.6; two of the tile rows that share their
