@@ -12,7 +12,7 @@ import numpy as np
 F32, BF16_F32ACC, BF16 = 0, 1, 2   # BF16: as BF16_F32ACC with O stored as bf16 bits
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_MFMA, KERNEL_MFMA_REG, KERNEL_MFMA_TILE, KERNEL_MFMA_REG_FILLED = 0, 1, 2, 3, 4, 5
 TUNE_COLS_PER_LANE, TUNE_COLS_PER_WORKGROUP, TUNE_GROUPS_PER_WORKGROUP, TUNE_ROW_PAIRING = 0, 1, 2, 3
-TUNE_ROW_GROUPS, TUNE_K_SPLIT, TUNE_COLUMN_TILES = 4, 5, 6
+TUNE_ROW_GROUPS, TUNE_K_SPLIT, TUNE_COLUMN_TILES, TUNE_REGISTER_SETS = 4, 5, 6, 7
 SPEC_OK, SPEC_COMPLETE, SPEC_DEGENERATE, SPEC_PRODUCT = 0, 1, 2, 3
 OK, EINVAL, ENOMEM, ENOTRAMANUJAN, ESHAPE, EHIP, EUNSUPPORTED, EINTERNAL, ETOOLARGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 

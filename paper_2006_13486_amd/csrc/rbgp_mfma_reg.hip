@@ -75,11 +75,15 @@ namespace {
 // delivers), at NG times the accumulators.  Two groups with stages of up to 32 steps (36 tap-grouped) still fit two
 // waves per SIMD without spilling; the larger ones get one.
 // CTILES (stages of up to 8 steps): the variant whose waves take several column tiles one after the other.
-template <int KC, int RS, bool TAPS = false, int NG = 1, bool CTILES = false>
-__global__ __launch_bounds__(256, (NG == 2 && (KC <= 32 || (KC == 36 && TAPS)) ? 2
-                                   : KC <= 8 && NG == 1                         ? (CTILES ? 2 : RS >= 4 ? 4 : 3)
-                                                                                : 1)) void spmm_reg(RegParams p) {
+// LEAN (stages of 72 steps, one group): one register set instead of two -- every slot is refilled in place for the next
+// stage right after its last use -- so that two waves fit a SIMD (the two sets of the plain kernel fill the register
+// file of one).
+template <int KC, int RS, bool TAPS = false, int NG = 1, bool CTILES = false, bool LEAN = false>
+__global__ __launch_bounds__(256, (LEAN || (NG == 2 && (KC <= 32 || (KC == 36 && TAPS))) ? 2
+                                   : KC <= 8 && NG == 1                                   ? (CTILES ? 2 : RS >= 4 ? 4 : 3)
+                                                                                          : 1)) void spmm_reg(RegParams p) {
   static_assert(!CTILES || (KC <= 8 && !TAPS), "column tiles per wave: short stages, not the fused convolution");
+  static_assert(!LEAN || (KC > 8 && NG == 1 && !CTILES), "one register set: the long stages, one group");
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   static_assert(NG == 1 || RS == 16, "several groups per wave: one tile row per group");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256, (NG == 2 && (KC <= 32 || (KC == 36 && TAPS)) ?
   const int cl = wg.cl * NG, u3 = wg.u3, ntq = wg.ntq;   // (NG > 1: the first of the wave's NG tile rows; all share its tables)
   // Register sets = stages of loads in flight.  Two for the long stages; a stage of 8 steps is 8 MFMAs (256
   // cycles), and two of them ahead cover far less than a memory access takes: such kernels keep four.
-  constexpr int D = KC <= 8 ? 4 : 2;
+  constexpr int D = LEAN ? 1 : KC <= 8 ? 4 : 2;
   // Short stages, every stage list of the same length: a wave takes `ct` neighbouring column tiles one after the
   // other as ONE list of ct * (stages per tile) stages (lane l of the stage table then serves column tile
   // l / stages-per-tile), so the tables are fetched once and the first rows of the next tile are on their way while
@@ -519,6 +523,21 @@ const RegGroupEntry *find_reg_groups(int KC, int NG) {
     if (e.KC == KC && e.NG == NG) return &e;
   return nullptr;
 }
+// one register set, two waves per SIMD (stages of 72 steps): {RS, kernel}
+struct RegLeanEntry {
+  int RS;
+  reg_fn fn;
+};
+const RegLeanEntry kRegLeanTable[] = {{2, spmm_reg<72, 2, false, 1, false, true>},
+                                      {4, spmm_reg<72, 4, false, 1, false, true>},
+                                      {8, spmm_reg<72, 8, false, 1, false, true>},
+                                      {16, spmm_reg<72, 16, false, 1, false, true>}};
+reg_fn find_reg_lean(int KC, int RS) {
+  if (KC != 72) return nullptr;
+  for (const RegLeanEntry &e : kRegLeanTable)
+    if (e.RS == RS) return e.fn;
+  return nullptr;
+}
 // waves that take several column tiles (stages of 8 steps): {RS, NG, kernel}
 struct RegTilesEntry {
   int RS, NG;
@@ -885,6 +904,18 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       }
     }
   }
+  // fp32, stages of 72 steps, one group: one register set at two waves per SIMD instead of two sets at one (see
+  // spmm_reg); tuning knob RBGP_TUNE_REGISTER_SETS overrides.
+  bool lean = false;
+  {
+    const int tr = tune[RBGP_TUNE_REGISTER_SETS];
+    if (tr < 0 || tr > 2) return RBGP_EUNSUPPORTED;
+    const bool can = !bf16 && !dual && !taps && NGf == 1 && CT == 1 && find_reg_lean(pl.KC, pl.RS);
+    if (tr == 1 && !can) return RBGP_EUNSUPPORTED;
+    // (measured on the fp32 VGG19 layers at every density, batches of 512 to 131 072 columns, split lists included:
+    // 1-19 % faster than two sets in every cell, so it is the default wherever it applies)
+    lean = can && tr != 2;
+  }
   const int ncl = dual ? m->reg_dual.nq : tab->ncl / NGf;
   const int fpm = m->d[0] * pl.NSTG;
   // LDS: partial sums of the split -- per wave the (S - 1) / S of its 4G units it does not own; lo/hi pairing:
@@ -957,6 +988,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   reg_fn fn = dual     ? nullptr
               : bf16   ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW)
               : CT > 1 ? find_reg_tiles(pl.KC, pl.RS, NGf)
+              : lean   ? find_reg_lean(pl.KC, pl.RS)
               : ge   ? (taps ? ge->taps_fn : ge->global_fn)
               : taps ? e->taps_fn
                      : e->global_fn;

@@ -414,6 +414,41 @@ def test_column_tiles_per_wave_refusals_and_default():
     gh.check_parity(ok, N=8192, kernel=rb.KERNEL_AUTO)
 
 
+# stages of 72 steps with 2, 4, 8 and 16 weight rows per tile row: the kernels with one register set (two waves per SIMD)
+ONE_SET_SHAPES = [((4, 1, 4, 2), 2), ((4, 2, 4, 2), 4), ((4, 4, 4, 2), 8), ((4, 4, 4, 4), 16)]
+
+
+@pytest.mark.parametrize("idx", range(len(ONE_SET_SHAPES)))
+def test_fp32_register_family_one_register_set(idx):
+    """RBGP_TUNE_REGISTER_SETS = 1: ragged N, padded leading dimension, one column tile, a split stage list."""
+    rows, rs = ONE_SET_SHAPES[idx]
+    w = wl.Workload(f"oneset{idx}", rows, (4, 4, 4, 9), (2, 4, 2, 9), 333, wl.F32, 180 + idx, 190 + idx, 200 + idx, 1.0)
+    assert 16 // rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed))[0] == rs
+    pairing = 1 if rs == 8 else 0   # (8 rows: the fixed pairs, not the tile-by-tile pairing kernel)
+    for N, split, pad in ((333, 1, 3), (64, 0, 0), (2309, 1, 1), (200, 2, 0), (130, 4, 2)):
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, pairing, 0, split, 0, 1), ld_pad=pad, expect_kernel=REG)
+    gh.check_parity(w, N=333, kernel=REG, tune=(0, 0, 0, pairing, 0, 0, 0, 2), expect_kernel=REG)
+
+
+def test_one_register_set_on_the_headline_layer_and_refusals():
+    gh.check_parity(wl.VGG19_CONV5, N=512, kernel=REG, tune=(0, 0, 0, 1, 0, 0, 0, 1), expect_kernel=REG)
+    # the fused convolution on 4-pixel-wide images (no tap grouping): the same kernel reading the activations
+    w = wl.VGG19_CONV5
+    X = wl.conv_activations(w, 9, 4, 4)
+    want, den = gh.oracle_spmm(w, wl.kept_weights(w), orc.im2col_3x3(X))
+    for sets in (1, 2):
+        out = gh.library_conv3x3(w, wl.kept_weights(w), X, tune=(0, 0, 0, 1, 0, 0, 0, sets), kernel=REG)
+        assert orc.normalised_error(out, want, den) <= gh.TOL[w.dtype]
+    short = wl.Workload("oneset_18", (8, 4, 4, 9), (8, 4, 4, 2), (4, 4, 2, 2), 256, wl.F32, 174, 175, 176, 1.0)
+    for w, tune in ((short, (0, 0, 0, 0, 0, 0, 0, 1)),                       # stages of 18 steps
+                    (wl.VGG19_CONV5, (0, 0, 0, 2, 0, 0, 0, 1)),              # with the tile-by-tile pairing kernel
+                    (wl.VGG19_CONV5, (0, 0, 0, 1, 0, 0, 0, 3)),              # not a value of the knob
+                    (replace(wl.VGG19_CONV3_BF16, N=256), (0, 0, 0, 0, 0, 0, 0, 1))):   # bf16
+        with pytest.raises(rb.RbgpError) as e:
+            gh.check_parity(w, N=256, kernel=REG, tune=tune, expect_kernel=REG)
+        assert e.value.code == rb.EUNSUPPORTED
+
+
 def test_activations_beyond_4_gib():
     """An I of 4.6 GB (WRN shape, 2 000 037 columns, odd leading dimension): the kernels'
     32-bit offsets must only span one stage.  A sample of output columns is checked."""
