@@ -778,7 +778,10 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
         // 15-22 % on every VGG19 layer that keeps the chip full, however short the split lists)
         // (and where the tile rows of a larger cluster have the same tiles -- rows of G_r moved into the tile-row
         // index -- the second group costs no extra stage at all: 12-17 % faster on the density-1/2 layers)
-        if (waves2 * S2 >= 1024 && (S2 == 1 || conv || st->g2_shared || st->g2_stages / S2 >= 12)) G = 2;
+        // (with the one-register-set kernels of the 128-column tiles a split in two pays from six stages per wave on:
+        // VGG19 conv3 16.97 -> 16.35 us, layers 5, 6, 9-11 at density 1/4 8-9 % faster)
+        const int enough = (S2 == 2 && CW == 128) ? 6 : 12;
+        if (waves2 * S2 >= 1024 && (S2 == 1 || conv || st->g2_shared || st->g2_stages / S2 >= enough)) G = 2;
         // Four tile rows with the very same tiles (at least four of G_r's rows moved into the tile-row index, as on the
         // filled masks of Tables 2-3): four groups per wave, where the chip stays full and the accumulators fit without
         // spilling (stages of up to 36 steps).  4096^3 with one row per column set: 182 / 122 / 111 us with 1 / 2 / 4 groups.
@@ -910,10 +913,12 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   {
     const int tr = tune[RBGP_TUNE_REGISTER_SETS];
     if (tr < 0 || tr > 2) return RBGP_EUNSUPPORTED;
-    const bool can = !bf16 && !dual && !taps && NGf == 1 && CT == 1 && find_reg_lean(pl.KC, pl.RS);
+    const bool can = bf16 ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) != nullptr
+                          : !dual && !taps && NGf == 1 && CT == 1 && find_reg_lean(pl.KC, pl.RS);
     if (tr == 1 && !can) return RBGP_EUNSUPPORTED;
     // (measured on the fp32 VGG19 layers at every density, batches of 512 to 131 072 columns, split lists included:
-    // 1-19 % faster than two sets in every cell, so it is the default wherever it applies)
+    // 1-19 % faster than two sets in every cell; bf16 on 128-column tiles: 1-13 % faster in 38 of 41 cells, 2-6 %
+    // slower in three; so it is the default wherever it applies)
     lean = can && tr != 2;
   }
   const int ncl = dual ? m->reg_dual.nq : tab->ncl / NGf;
@@ -986,7 +991,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   rp.per_xcd = int(per_xcd);
   rp.ngroups = int(nquads);
   reg_fn fn = dual     ? nullptr
-              : bf16   ? rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW)
+              : bf16   ? (lean ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) : rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW))
               : CT > 1 ? find_reg_tiles(pl.KC, pl.RS, NGf)
               : lean   ? find_reg_lean(pl.KC, pl.RS)
               : ge   ? (taps ? ge->taps_fn : ge->global_fn)

@@ -61,8 +61,10 @@ __device__ __forceinline__ s16x4 as_s16x4(unsigned lo, unsigned hi) {
   return __builtin_bit_cast(s16x4, v);
 }
 
-template <int KC, int RS, int G, int CW>
-__global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
+// LEAN: one register set instead of two -- every block's rows of I and weights are refilled in place for the wave's
+// next stage right after their last use -- so that two waves fit a SIMD where the two sets fill the register file of one.
+template <int KC, int RS, int G, int CW, bool LEAN = false>
+__global__ __launch_bounds__(256, LEAN ? 2 : 1) void spmm_reg_bf16(RegParams p) {
   constexpr int NC = CW / 16;            // columns per lane: 4 or 8
   constexpr int LW = NC / 2;             // dwords per lane and row
   constexpr int NH = NC / 4;             // 16-byte pieces of a lane's output row
@@ -241,16 +243,17 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     __builtin_amdgcn_sched_barrier(0);   // keep the loads where they are: the wait counts depend on it
   };
 
-  // One stage: every block's rows of I and weights are refilled for the wave's stage s + 2
-  // right after their last use, so about two stages of loads are in flight; the loop body is
+  // One stage: every block's rows of I and weights are refilled for the wave's stage s + DIST (the number of register
+  // sets) right after their last use, so about DIST stages of loads are in flight; the loop body is
   // branch-free and its wait counts are exact.
+  constexpr int DIST = LEAN ? 1 : 2;
   auto stage = [&](int s, Raw<LW> (&B)[NLD], u32x4 (&A)[G][NB], auto reload) {
     constexpr bool RELOAD = decltype(reload)::value;
     int sofs = 0, av[G] = {};
     __amdgpu_buffer_rsrc_t rb2 = rw;
     if constexpr (RELOAD) {
-      const int tl = table_lane(s + 2);
-      const bool live = s + 2 < cntw;
+      const int tl = table_lane(s + DIST);
+      const bool live = s + DIST < cntw;
       rb2 = b_rsrc(tl, live, &sofs);
 #pragma unroll
       for (int gi = 0; gi < G; ++gi) av[gi] = a_addr(tl, live, gi);
@@ -270,11 +273,16 @@ __global__ __launch_bounds__(256) void spmm_reg_bf16(RegParams p) {
     static_for<0, NB>([&](auto bc) { load_block(bc, B, A, rb2, sofs, av); });
   };
 
-  Raw<LW> B0[NLD], B1[NLD];
-  u32x4 A0[G][NB], A1[G][NB];
-  fill(0, B0, A0);
-  fill(1, B1, A1);   // (issued before any MFMA waits: measured faster than interleaving it with stage 0)
-  {
+  if constexpr (LEAN) {
+    Raw<LW> B0[NLD];
+    u32x4 A0[G][NB];
+    fill(0, B0, A0);
+    for (int s = 0; s < cntw; ++s) stage(s, B0, A0, std::true_type{});   // (past the end: sentinels, no memory access)
+  } else {
+    Raw<LW> B0[NLD], B1[NLD];
+    u32x4 A0[G][NB], A1[G][NB];
+    fill(0, B0, A0);
+    fill(1, B1, A1);   // (issued before any MFMA waits: measured faster than interleaving it with stage 0)
     int s = 0;
     for (; s + 1 < cntw; s += 2) {
       stage(s, B0, A0, std::true_type{});
@@ -395,7 +403,18 @@ const Entry kTable[] = {RBGP_B(8, 2),  RBGP_B(18, 2),  RBGP_B(32, 2),  RBGP_B(36
                         RBGP_B(8, 8),  RBGP_B(18, 8),  RBGP_B(32, 8),  RBGP_B(36, 8),  RBGP_B(72, 8),
                         RBGP_B(8, 16), RBGP_B(18, 16), RBGP_B(32, 16), RBGP_B(36, 16), RBGP_B(72, 16)};
 
+// one register set, two waves per SIMD: the 128-column tiles whose two sets leave room for one wave only
+#define RBGP_BL(KC, RS) {KC, RS, 1, 128, spmm_reg_bf16<KC, RS, 1, 128, true>}, {KC, RS, 2, 128, spmm_reg_bf16<KC, RS, 2, 128, true>}
+const Entry kLeanTable[] = {RBGP_BL(36, 2), RBGP_BL(72, 2), RBGP_BL(36, 4),  RBGP_BL(72, 4),
+                            RBGP_BL(36, 8), RBGP_BL(72, 8), RBGP_BL(36, 16), RBGP_BL(72, 16)};
+
 }  // namespace
+
+rbgp_reg_fn rbgp_reg_bf16_lean_kernel(int KC, int RS, int G, int CW) {
+  for (const Entry &e : kLeanTable)
+    if (e.KC == KC && e.RS == RS && e.G == G && e.CW == CW) return e.fn;
+  return nullptr;
+}
 
 rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G, int CW) {
   for (const Entry &e : kTable)

@@ -147,6 +147,8 @@ typedef void (*rbgp_dual_fn)(rbgp_reg::DualParams);
 // bf16 kernel for KC contraction steps per stage, RS weight rows per tile row, G 16-row
 // groups per wave and CW (64 or 128) columns per wave; nullptr when that combination is not built.
 rbgp_reg_fn rbgp_reg_bf16_kernel(int KC, int RS, int G, int CW);
+// the same with one register set (two waves per SIMD); nullptr where that variant is not built
+rbgp_reg_fn rbgp_reg_bf16_lean_kernel(int KC, int RS, int G, int CW);
 // fp32 kernel with lo/hi pairing of the tile rows (8-row halves; tables of rbgp_reg_dual in the
 // stages / counts / members fields); nullptr when KC is not built.
 rbgp_dual_fn rbgp_reg_dual_kernel(int KC);

@@ -430,6 +430,27 @@ def test_fp32_register_family_one_register_set(idx):
     gh.check_parity(w, N=333, kernel=REG, tune=(0, 0, 0, pairing, 0, 0, 0, 2), expect_kernel=REG)
 
 
+@pytest.mark.parametrize("idx", range(len(ONE_SET_SHAPES)))
+@pytest.mark.parametrize("steps", [72, 36])
+def test_bf16_register_family_one_register_set(idx, steps):
+    """The bf16 kernels with one register set (128-column tiles, one or two row groups, stages of 72 and 36 steps):
+    ragged N, a split stage list, the bf16-output mode; 64-column tiles have no such variant."""
+    rows, rs = ONE_SET_SHAPES[idx]
+    cols, deg = ((4, 4, 4, 9), (2, 4, 2, 9)) if steps == 72 else ((4, 2, 4, 9), (2, 2, 2, 9))
+    w = wl.Workload(f"oneset_bf16_{steps}_{idx}", rows, cols, deg, 328, wl.BF16, 210 + idx, 220 + idx, 230 + idx, 1.0)
+    assert rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed))[2] == steps
+    for N, groups, split in ((328, 1, 1), (1096, 2, 1), (136, 1, 2), (2312, 2, 4), (128, 1, 0)):
+        gh.check_parity(w, N=N, kernel=REG, tune=(0, 128, 0, 0, groups, split, 0, 1), expect_kernel=REG)
+    # bf16 output: the rounding of what the fp32-output mode of the same launch stores
+    vl, Il, vf, If = gh.host_inputs(w, 328)
+    out16, _ = gh.library_spmm(w, vl, Il, REG, (0, 128, 0, 0, 1, 1, 0, 1), out_bf16=True)
+    out32, _ = gh.library_spmm(w, vl, Il, REG, (0, 128, 0, 0, 1, 1, 0, 1))
+    assert np.array_equal((out16.view(np.uint32) >> 16).astype(np.uint16), orc.f32_to_bf16_bits(out32))
+    with pytest.raises(rb.RbgpError) as e:
+        gh.check_parity(w, N=328, kernel=REG, tune=(0, 64, 0, 0, 1, 1, 0, 1), expect_kernel=REG)
+    assert e.value.code == rb.EUNSUPPORTED
+
+
 def test_one_register_set_on_the_headline_layer_and_refusals():
     gh.check_parity(wl.VGG19_CONV5, N=512, kernel=REG, tune=(0, 0, 0, 1, 0, 0, 0, 1), expect_kernel=REG)
     # the fused convolution on 4-pixel-wide images (no tap grouping): the same kernel reading the activations
@@ -443,7 +464,7 @@ def test_one_register_set_on_the_headline_layer_and_refusals():
     for w, tune in ((short, (0, 0, 0, 0, 0, 0, 0, 1)),                       # stages of 18 steps
                     (wl.VGG19_CONV5, (0, 0, 0, 2, 0, 0, 0, 1)),              # with the tile-by-tile pairing kernel
                     (wl.VGG19_CONV5, (0, 0, 0, 1, 0, 0, 0, 3)),              # not a value of the knob
-                    (replace(wl.VGG19_CONV3_BF16, N=256), (0, 0, 0, 0, 0, 0, 0, 1))):   # bf16
+                    (replace(wl.VGG19_CONV3_BF16, N=256), (0, 64, 0, 0, 0, 0, 0, 1))):   # bf16 on 64-column tiles
         with pytest.raises(rb.RbgpError) as e:
             gh.check_parity(w, N=256, kernel=REG, tune=tune, expect_kernel=REG)
         assert e.value.code == rb.EUNSUPPORTED
