@@ -119,9 +119,10 @@ enum {
                                          one after the other, 1, 2, 4 or 8 (EUNSUPPORTED where the stage lists of
                                          that many tiles exceed 64 stages, for rbgp_conv3x3 and with a split) */
   RBGP_TUNE_REGISTER_SETS = 7,        /* MFMA_REG: 2 = two register sets (two stages of loads in flight per wave),
-                                         1 = one set refilled in place, which lets two waves share a SIMD: fp32 with
-                                         stages of 72 contraction steps and one row group, bf16 on 128-column tiles
-                                         with stages of 36 or 72 steps and one or two row groups (EUNSUPPORTED
+                                         1 = one set refilled in place, which lets more waves share a SIMD: fp32 with
+                                         stages of 18 steps and more and one row group (two groups: 36 steps, or
+                                         72 on the tap-grouped fused convolution), bf16 on 128-column tiles with
+                                         stages of 36 or 72 steps and one or two row groups (EUNSUPPORTED
                                          elsewhere); default: 1 where it exists */
   RBGP_NUM_TUNE = 8
 };

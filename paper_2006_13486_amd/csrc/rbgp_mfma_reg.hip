@@ -75,15 +75,16 @@ namespace {
 // delivers), at NG times the accumulators.  Two groups with stages of up to 32 steps (36 tap-grouped) still fit two
 // waves per SIMD without spilling; the larger ones get one.
 // CTILES (stages of up to 8 steps): the variant whose waves take several column tiles one after the other.
-// LEAN (stages of 72 steps, one group): one register set instead of two -- every slot is refilled in place for the next
-// stage right after its last use -- so that two waves fit a SIMD (the two sets of the plain kernel fill the register
-// file of one).
+// LEAN (stages of 18 steps and more): one register set instead of two -- every slot is refilled in place for the next
+// stage right after its last use -- so that more waves fit a SIMD (72 steps: two instead of one; 32 and 36 steps:
+// three instead of two; 18 steps: four instead of three; two groups of 36 steps or of 72 tap-grouped ones: two
+// instead of one).
 template <int KC, int RS, bool TAPS = false, int NG = 1, bool CTILES = false, bool LEAN = false>
 __global__ __launch_bounds__(256, (LEAN || (NG == 2 && (KC <= 32 || (KC == 36 && TAPS))) ? 2
                                    : KC <= 8 && NG == 1                                   ? (CTILES ? 2 : RS >= 4 ? 4 : 3)
                                                                                           : 1)) void spmm_reg(RegParams p) {
   static_assert(!CTILES || (KC <= 8 && !TAPS), "column tiles per wave: short stages, not the fused convolution");
-  static_assert(!LEAN || (KC > 8 && NG == 1 && !CTILES), "one register set: the long stages, one group");
+  static_assert(!LEAN || (KC > 8 && !CTILES), "one register set: the long stages");
   static_assert(!TAPS || KC % 12 == 0, "tap-grouped stages are multiples of 12 steps");
   static_assert(NG == 1 || RS == 16, "several groups per wave: one tile row per group");
   constexpr int MG = 16 / RS;            // tile rows per MFMA group = cluster size
@@ -523,19 +524,25 @@ const RegGroupEntry *find_reg_groups(int KC, int NG) {
     if (e.KC == KC && e.NG == NG) return &e;
   return nullptr;
 }
-// one register set, two waves per SIMD (stages of 72 steps): {RS, kernel}
+// one register set (stages of 18 steps and more): {KC, RS, tap-grouped, NG, kernel}
 struct RegLeanEntry {
-  int RS;
+  int KC, RS;
+  bool taps;
+  int NG;
   reg_fn fn;
 };
-const RegLeanEntry kRegLeanTable[] = {{2, spmm_reg<72, 2, false, 1, false, true>},
-                                      {4, spmm_reg<72, 4, false, 1, false, true>},
-                                      {8, spmm_reg<72, 8, false, 1, false, true>},
-                                      {16, spmm_reg<72, 16, false, 1, false, true>}};
-reg_fn find_reg_lean(int KC, int RS) {
-  if (KC != 72) return nullptr;
+#define RBGP_L1(KC, RS) {KC, RS, false, 1, spmm_reg<KC, RS, false, 1, false, true>}
+#define RBGP_L1T(KC, RS) {KC, RS, true, 1, spmm_reg<KC, RS, true, 1, false, true>}
+#define RBGP_L4(KC) RBGP_L1(KC, 2), RBGP_L1(KC, 4), RBGP_L1(KC, 8), RBGP_L1(KC, 16)
+#define RBGP_L4T(KC) RBGP_L1T(KC, 2), RBGP_L1T(KC, 4), RBGP_L1T(KC, 8), RBGP_L1T(KC, 16)
+const RegLeanEntry kRegLeanTable[] = {RBGP_L4(18),  RBGP_L4(32),  RBGP_L4(36), RBGP_L4(72),
+                                      RBGP_L4T(36), RBGP_L4T(72),
+                                      {36, 16, false, 2, spmm_reg<36, 16, false, 2, false, true>},
+                                      {36, 16, true, 2, spmm_reg<36, 16, true, 2, false, true>},
+                                      {72, 16, true, 2, spmm_reg<72, 16, true, 2, false, true>}};
+reg_fn find_reg_lean(int KC, int RS, bool taps, int NG) {
   for (const RegLeanEntry &e : kRegLeanTable)
-    if (e.RS == RS) return e.fn;
+    if (e.KC == KC && e.RS == RS && e.taps == taps && e.NG == NG) return e.fn;
   return nullptr;
 }
 // waves that take several column tiles (stages of 8 steps): {RS, NG, kernel}
@@ -907,18 +914,19 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
       }
     }
   }
-  // fp32, stages of 72 steps, one group: one register set at two waves per SIMD instead of two sets at one (see
-  // spmm_reg); tuning knob RBGP_TUNE_REGISTER_SETS overrides.
+  // One register set with more waves per SIMD instead of two sets (see spmm_reg, spmm_reg_bf16) wherever that variant
+  // is built; tuning knob RBGP_TUNE_REGISTER_SETS overrides.
   bool lean = false;
   {
     const int tr = tune[RBGP_TUNE_REGISTER_SETS];
     if (tr < 0 || tr > 2) return RBGP_EUNSUPPORTED;
     const bool can = bf16 ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) != nullptr
-                          : !dual && !taps && NGf == 1 && CT == 1 && find_reg_lean(pl.KC, pl.RS);
+                          : !dual && CT == 1 && find_reg_lean(pl.KC, pl.RS, taps, NGf);
     if (tr == 1 && !can) return RBGP_EUNSUPPORTED;
     // (measured on the fp32 VGG19 layers at every density, batches of 512 to 131 072 columns, split lists included:
-    // 1-19 % faster than two sets in every cell; bf16 on 128-column tiles: 1-13 % faster in 38 of 41 cells, 2-6 %
-    // slower in three; so it is the default wherever it applies)
+    // stages of 72 steps 1-19 % faster than two sets in every cell, the shorter stages and the tap-grouped kernels
+    // 1-2 % over the forward, fused and backward sweeps (single cells up to 12 %); bf16 on 128-column tiles: 1-13 %
+    // faster in 38 of 41 cells, 2-6 % slower in three; so it is the default wherever it applies)
     lean = can && tr != 2;
   }
   const int ncl = dual ? m->reg_dual.nq : tab->ncl / NGf;
@@ -993,7 +1001,7 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   reg_fn fn = dual     ? nullptr
               : bf16   ? (lean ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) : rbgp_reg_bf16_kernel(pl.KC, pl.RS, G, CW))
               : CT > 1 ? find_reg_tiles(pl.KC, pl.RS, NGf)
-              : lean   ? find_reg_lean(pl.KC, pl.RS)
+              : lean   ? find_reg_lean(pl.KC, pl.RS, taps, NGf)
               : ge   ? (taps ? ge->taps_fn : ge->global_fn)
               : taps ? e->taps_fn
                      : e->global_fn;

@@ -350,6 +350,7 @@ def test_fp32_register_family_row_groups_per_wave(idx):
         gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, ng), ld_pad=3, expect_kernel=REG)
         gh.check_parity(w, N=64, kernel=REG, tune=(0, 0, 0, 0, ng), expect_kernel=REG)
     gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 2, 2), expect_kernel=REG)     # with a split stage list as well
+    gh.check_parity(w, kernel=REG, tune=(0, 0, 0, 0, 2, 0, 0, 2), ld_pad=1, expect_kernel=REG)   # two register sets
     gh.check_parity(w, N=200, kernel=REG, tune=(0, 0, 0, 0, groups[-1], 4), ld_pad=1, expect_kernel=REG)
     if 4 not in groups:
         with pytest.raises(rb.RbgpError) as e:
@@ -363,8 +364,9 @@ def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
     X = wl.conv_activations(w, 6, 8, 8)
     want, den = gh.oracle_spmm(w, wl.kept_weights(w), orc.im2col_3x3(X))
     for ng in (1, 2):
-        out = gh.library_conv3x3(w, wl.kept_weights(w), X, tune=(0, 0, 0, 0, ng), kernel=REG)
-        assert orc.normalised_error(out, want, den) <= gh.TOL[w.dtype]
+        for sets in (1, 2):
+            out = gh.library_conv3x3(w, wl.kept_weights(w), X, tune=(0, 0, 0, 0, ng, 0, 0, sets), kernel=REG)
+            assert orc.normalised_error(out, want, den) <= gh.TOL[w.dtype]
     # a mask with 8 rows per column set has no such groups
     with pytest.raises(rb.RbgpError) as e:
         gh.check_parity(wl.VGG19_CONV5, N=256, kernel=REG, tune=(0, 0, 0, 0, 2), expect_kernel=REG)
@@ -418,12 +420,20 @@ def test_column_tiles_per_wave_refusals_and_default():
 ONE_SET_SHAPES = [((4, 1, 4, 2), 2), ((4, 2, 4, 2), 4), ((4, 4, 4, 2), 8), ((4, 4, 4, 4), 16)]
 
 
+# stages of 72, 36, 32 and 18 steps: columns and left degrees of the factors
+ONE_SET_STAGES = {72: ((4, 4, 4, 9), (2, 4, 2, 9)), 36: ((4, 2, 4, 9), (2, 2, 2, 9)), 32: ((4, 4, 4, 4), (2, 4, 2, 4)),
+                  18: ((4, 1, 4, 9), (2, 1, 2, 9))}
+
+
 @pytest.mark.parametrize("idx", range(len(ONE_SET_SHAPES)))
-def test_fp32_register_family_one_register_set(idx):
+@pytest.mark.parametrize("steps", sorted(ONE_SET_STAGES))
+def test_fp32_register_family_one_register_set(idx, steps):
     """RBGP_TUNE_REGISTER_SETS = 1: ragged N, padded leading dimension, one column tile, a split stage list."""
     rows, rs = ONE_SET_SHAPES[idx]
-    w = wl.Workload(f"oneset{idx}", rows, (4, 4, 4, 9), (2, 4, 2, 9), 333, wl.F32, 180 + idx, 190 + idx, 200 + idx, 1.0)
-    assert 16 // rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed))[0] == rs
+    cols, deg = ONE_SET_STAGES[steps]
+    w = wl.Workload(f"oneset{steps}_{idx}", rows, cols, deg, 333, wl.F32, 180 + idx, 190 + idx, 200 + idx, 1.0)
+    plan = rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed))
+    assert 16 // plan[0] == rs and plan[2] == steps
     pairing = 1 if rs == 8 else 0   # (8 rows: the fixed pairs, not the tile-by-tile pairing kernel)
     for N, split, pad in ((333, 1, 3), (64, 0, 0), (2309, 1, 1), (200, 2, 0), (130, 4, 2)):
         gh.check_parity(w, N=N, kernel=REG, tune=(0, 0, 0, pairing, 0, split, 0, 1), ld_pad=pad, expect_kernel=REG)
@@ -460,8 +470,8 @@ def test_one_register_set_on_the_headline_layer_and_refusals():
     for sets in (1, 2):
         out = gh.library_conv3x3(w, wl.kept_weights(w), X, tune=(0, 0, 0, 1, 0, 0, 0, sets), kernel=REG)
         assert orc.normalised_error(out, want, den) <= gh.TOL[w.dtype]
-    short = wl.Workload("oneset_18", (8, 4, 4, 9), (8, 4, 4, 2), (4, 4, 2, 2), 256, wl.F32, 174, 175, 176, 1.0)
-    for w, tune in ((short, (0, 0, 0, 0, 0, 0, 0, 1)),                       # stages of 18 steps
+    short = wl.Workload("oneset_8", (8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), 256, wl.F32, 174, 175, 176, 1.0)
+    for w, tune in ((short, (0, 0, 0, 0, 0, 0, 0, 1)),                       # stages of 8 steps
                     (wl.VGG19_CONV5, (0, 0, 0, 2, 0, 0, 0, 1)),              # with the tile-by-tile pairing kernel
                     (wl.VGG19_CONV5, (0, 0, 0, 1, 0, 0, 0, 3)),              # not a value of the knob
                     (replace(wl.VGG19_CONV3_BF16, N=256), (0, 64, 0, 0, 0, 0, 0, 1))):   # bf16 on 64-column tiles
