@@ -122,8 +122,10 @@ enum {
                                          1 = one set refilled in place, which lets more waves share a SIMD: fp32 with
                                          stages of 18 steps and more and one row group (two groups: 36 steps, or
                                          72 on the tap-grouped fused convolution), bf16 on 128-column tiles with
-                                         stages of 36 or 72 steps and one or two row groups (EUNSUPPORTED
-                                         elsewhere); default: 1 where it exists */
+                                         stages of 36 or 72 steps and one or two row groups, of up to 36 steps
+                                         and four groups (one tile row each), of 18 or 32 steps and two groups
+                                         where a wave has one stage (EUNSUPPORTED elsewhere); default: 1 where
+                                         it exists */
   RBGP_NUM_TUNE = 8
 };
 

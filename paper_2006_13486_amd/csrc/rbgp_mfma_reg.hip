@@ -920,7 +920,11 @@ int rbgp_reg_launch(const rbgp_mask *m, void **state, const int *tune, bool bf16
   {
     const int tr = tune[RBGP_TUNE_REGISTER_SETS];
     if (tr < 0 || tr > 2) return RBGP_EUNSUPPORTED;
-    const bool can = bf16 ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) != nullptr
+    // (bf16, two groups of short stages: only where a wave has a single stage -- nothing to prefetch, so the second set
+    // buys nothing and the extra waves do, 27.6 -> 22.2 us on the dense first VGG19 layer; with several short stages
+    // the two sets keep more bytes in flight, 18.5 against 23.6 us on layer 2 at density 1/8)
+    const bool can = bf16 ? rbgp_reg_bf16_lean_kernel(pl.KC, pl.RS, G, CW) != nullptr &&
+                                (pl.KC > 32 || G == 4 || tab->max_stages <= (1 << lgS))
                           : !dual && CT == 1 && find_reg_lean(pl.KC, pl.RS, taps, NGf);
     if (tr == 1 && !can) return RBGP_EUNSUPPORTED;
     // (measured on the fp32 VGG19 layers at every density, batches of 512 to 131 072 columns, split lists included:

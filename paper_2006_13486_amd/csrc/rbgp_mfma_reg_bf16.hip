@@ -403,10 +403,17 @@ const Entry kTable[] = {RBGP_B(8, 2),  RBGP_B(18, 2),  RBGP_B(32, 2),  RBGP_B(36
                         RBGP_B(8, 8),  RBGP_B(18, 8),  RBGP_B(32, 8),  RBGP_B(36, 8),  RBGP_B(72, 8),
                         RBGP_B(8, 16), RBGP_B(18, 16), RBGP_B(32, 16), RBGP_B(36, 16), RBGP_B(72, 16)};
 
-// one register set, two waves per SIMD: the 128-column tiles whose two sets leave room for one wave only
+// one register set, more waves per SIMD: 128-column tiles; stages of 36 and 72 steps with one or two groups, the
+// shorter stages with two or four groups (four: one tile row per group)
 #define RBGP_BL(KC, RS) {KC, RS, 1, 128, spmm_reg_bf16<KC, RS, 1, 128, true>}, {KC, RS, 2, 128, spmm_reg_bf16<KC, RS, 2, 128, true>}
+#define RBGP_BL2(KC, RS) {KC, RS, 2, 128, spmm_reg_bf16<KC, RS, 2, 128, true>}
 const Entry kLeanTable[] = {RBGP_BL(36, 2), RBGP_BL(72, 2), RBGP_BL(36, 4),  RBGP_BL(72, 4),
-                            RBGP_BL(36, 8), RBGP_BL(72, 8), RBGP_BL(36, 16), RBGP_BL(72, 16)};
+                            RBGP_BL(36, 8), RBGP_BL(72, 8), RBGP_BL(36, 16), RBGP_BL(72, 16),
+                            RBGP_BL2(18, 2), RBGP_BL2(32, 2), RBGP_BL2(18, 4),  RBGP_BL2(32, 4),
+                            RBGP_BL2(18, 8), RBGP_BL2(32, 8), RBGP_BL2(18, 16), RBGP_BL2(32, 16),
+                            {18, 16, 4, 128, spmm_reg_bf16<18, 16, 4, 128, true>},
+                            {32, 16, 4, 128, spmm_reg_bf16<32, 16, 4, 128, true>},
+                            {36, 16, 4, 128, spmm_reg_bf16<36, 16, 4, 128, true>}};
 
 }  // namespace
 

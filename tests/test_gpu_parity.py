@@ -459,6 +459,28 @@ def test_bf16_register_family_one_register_set(idx, steps):
     with pytest.raises(rb.RbgpError) as e:
         gh.check_parity(w, N=328, kernel=REG, tune=(0, 64, 0, 0, 1, 1, 0, 1), expect_kernel=REG)
     assert e.value.code == rb.EUNSUPPORTED
+    if rs == 16:   # four groups per wave: built for stages of up to 36 steps
+        if steps == 36:
+            gh.check_parity(w, N=1096, kernel=REG, tune=(0, 128, 0, 0, 4, 1, 0, 1), expect_kernel=REG)
+        else:
+            with pytest.raises(rb.RbgpError) as e:
+                gh.check_parity(w, N=1096, kernel=REG, tune=(0, 128, 0, 0, 4, 1, 0, 1), expect_kernel=REG)
+            assert e.value.code == rb.EUNSUPPORTED
+
+
+def test_bf16_one_register_set_on_short_stages():
+    """Stages of 32 and 18 steps: with two groups only where a wave has a single stage, with four groups always."""
+    one_stage32 = wl.Workload("oneset_bf16_single32", (4, 4, 2, 2), (1, 4, 4, 2), (1, 4, 4, 2), 1096, wl.BF16, 241, 242, 243, 1.0)
+    one_stage18 = wl.Workload("oneset_bf16_single18", (4, 2, 4, 2), (1, 2, 4, 4), (1, 2, 2, 4), 1096, wl.BF16, 244, 245, 246, 1.0)
+    for w in (one_stage32, one_stage18):
+        for sets in (1, 2, 0):
+            gh.check_parity(w, kernel=REG, tune=(0, 128, 0, 0, 2, 1, 0, sets), expect_kernel=REG)
+    gh.check_parity(one_stage32, kernel=REG, tune=(0, 128, 0, 0, 4, 1, 0, 1), expect_kernel=REG)
+    several = wl.Workload("oneset_bf16_several18", (4, 4, 4, 4), (4, 1, 4, 9), (2, 1, 2, 9), 1096, wl.BF16, 247, 248, 249, 1.0)
+    gh.check_parity(several, kernel=REG, tune=(0, 128, 0, 0, 4, 1, 0, 1), expect_kernel=REG)
+    with pytest.raises(rb.RbgpError) as e:
+        gh.check_parity(several, kernel=REG, tune=(0, 128, 0, 0, 2, 1, 0, 1), expect_kernel=REG)
+    assert e.value.code == rb.EUNSUPPORTED
 
 
 def test_one_register_set_on_the_headline_layer_and_refusals():
