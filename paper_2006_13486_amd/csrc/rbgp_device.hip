@@ -398,6 +398,9 @@ double reg_seconds(const rbgp_mask *m, bool bf16) {
   // take two or four of them per wave (measured on the filled masks of Table 3: 182 / 122 / 100-111 us)
   if (bf16 && m->reg.MG == 1 && m->reg.fold % 2 == 0)
     stage *= m->reg.fold % 4 == 0 && cl.max_stages >= 32 && KC <= 36 ? 0.56 : 0.67;
+  // (fp32, the same with stages of up to 32 steps: two such tile rows per wave and two waves per SIMD keep the matrix
+  // core busy throughout -- 500-520 us for the 2 x 34.4 GFLOP of Table 3's filled masks, 32.4 cycles per MFMA)
+  if (!bf16 && m->reg.MG == 1 && m->reg.fold % 2 == 0 && KC <= 32) stage = 40.0 + 33.0 * KC;
   return double(walked) * m->a[2] * stage / (64.0 * 1024.0 * 2.07e9);
 }
 // LDS-staged family (fp32 MFMA for both dtypes): a wave walks (tile, column of G_r) steps of RB * KS 4-row MFMAs,
@@ -415,7 +418,9 @@ int resolve_kernel_unfilled(const rbgp_mask *m, rbgp_dtype_t dtype);
 // products of Table 3, fp32 (us): one row per column set 1538 / 848 / 833 on the register family and 2054 / 1383 /
 // 1178 on the LDS family -> 622 / 595 / 580 at densities 1/4, 1/8, 1/16; two rows 824 -> 617 at 1/4 (466 and 453 at
 // 1/8 and 1/16 stay on the register family); four rows stay (586 against 621).  bf16: also Table 2's cells with a
-// half-full G_i (G_o at 1/8: 129 -> 51 us).
+// half-full G_i (G_o at 1/8: 129 -> 51 us).  Since the two-group kernel of the filled masks runs two waves per SIMD
+// (500-520 us on the one-row masks) the half-full G_i cells of fp32 take it too: 517 against 542 us on the LDS
+// family with G_o at 1/2, 266 / 281 at 1/4, 142 / 150 at 1/8.
 int resolve_kernel(const rbgp_mask *m, rbgp_dtype_t dtype) {
   if (m->kernel_choice == RBGP_KERNEL_MFMA_REG_FILLED) return m->filled ? RBGP_KERNEL_MFMA_REG_FILLED : RBGP_KERNEL_GENERIC;
   const int k0 = resolve_kernel_unfilled(m, dtype);

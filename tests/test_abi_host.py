@@ -258,14 +258,17 @@ def test_filled_layout_is_the_register_layout_of_the_mask_with_a_complete_g_i(sh
 def test_automatic_choice_on_the_masks_of_tables_2_and_3():
     """What RBGP_KERNEL_AUTO resolves to on the paper's 4096^3 masks (host-side estimate, fitted to measurements of
     all 27 on every family): one row per column set -> G_i filled in; G_o complete -> register family with split
-    stage lists; G_o at 1/8 -> LDS family in fp32, filled in bf16; never the LDS family in bf16."""
+    stage lists; a half-full G_i -> filled in (517 against 542 us, 142 against 150 with G_o at 1/8); four rows per column
+    set and a sparser G_i -> LDS family in fp32; never the LDS family in bf16."""
     k = lambda w, dt: rb.rbgp_mask_kernel(rb.rbgp_make_mask(w.rows, w.cols, w.row_deg, w.mask_seed), dt)
     for d in (2, 3, 4):
         assert k(wl.sdmm4096_table3(1, 1, d), rb.F32) == rb.KERNEL_MFMA_REG_FILLED
     assert k(wl.sdmm4096_table3(2, 1, 3), rb.F32) == rb.KERNEL_MFMA_REG
-    assert k(wl.sdmm4096_table3(4, 1, 2), rb.F32) == rb.KERNEL_MFMA
+    assert k(wl.sdmm4096_table3(4, 1, 2), rb.F32) == rb.KERNEL_MFMA_REG_FILLED
+    assert k(wl.sdmm4096_table3(4, 1, 4), rb.F32) == rb.KERNEL_MFMA
     assert k(wl.sdmm4096_table2(0, 2), rb.F32) == rb.KERNEL_MFMA_REG
-    assert k(wl.sdmm4096_table2(3, 1), rb.F32) == rb.KERNEL_MFMA
+    assert k(wl.sdmm4096_table2(3, 1), rb.F32) == rb.KERNEL_MFMA_REG_FILLED
+    assert k(wl.sdmm4096_table2(2, 2), rb.F32) == rb.KERNEL_MFMA
     assert k(wl.sdmm4096_table2(3, 1), rb.BF16_F32ACC) == rb.KERNEL_MFMA_REG_FILLED
     for w in [wl.sdmm4096_table3(r, b, d) for (r, b) in ((1, 1), (2, 1), (4, 1), (2, 2)) for d in (2, 3, 4)]:
         assert k(w, rb.BF16_F32ACC) != rb.KERNEL_MFMA
