@@ -8,8 +8,8 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "librbgp.so")
-SOURCES = ["rbgp_host.cpp", "rbgp_device.hip", "rbgp_mfma_reg.hip", "rbgp_mfma_reg_bf16.hip", "rbgp_mfma_reg_dual.hip", "rbgp_sddmm.hip",
-           "rbgp_mfma_tile.hip"]
+SOURCES = ["rbgp_mfma_reg_bf16_wide.hip", "rbgp_mfma_reg_bf16.hip", "rbgp_mfma_reg_bf16_lean.hip", "rbgp_mfma_reg.hip", "rbgp_host.cpp",
+           "rbgp_device.hip", "rbgp_mfma_reg_dual.hip", "rbgp_sddmm.hip", "rbgp_mfma_tile.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

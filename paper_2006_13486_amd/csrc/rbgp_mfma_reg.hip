@@ -1,6 +1,6 @@
 // Register-streaming MFMA kernels for O = W_s x I (Section 5, "GPU
 // Implementation"): the fp32 kernel, and the launcher and device tables of both
-// dtypes (the bf16 kernel is in rbgp_mfma_reg_bf16.hip).
+// dtypes (the bf16 kernel is in rbgp_reg_bf16_kernel.h).
 //
 // Work decomposition.  One wavefront owns: a cluster of U tile rows u_o, one G_i
 // vertex u_i (so, per tile row, the R = |G_r.U|*|G_b.U| rows that share a column
