@@ -580,18 +580,25 @@ def main():
     # `--steps 20 --warmup 5` the timed region would otherwise measure the clock ramp, not the kernel).
     for i in range(args.settle):
         step(i)
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()                              # same stream as the launches (torch's current stream)
-    for i in range(args.steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kern_ms = ev0.elapsed_time(ev1) / args.steps
+
+    def timed_region():
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()                              # same stream as the launches (torch's current stream)
+        for i in range(args.steps):
+            step(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ev0.elapsed_time(ev1) / args.steps
+
+    # (set-up as well: the whole region -- warm-up, synchronisation, K steps, synchronisation -- rehearsed, untimed, so
+    # that what the process does once -- the first events, the first wait on a drained queue -- is not in the K steps)
+    for _ in range(3 if args.settle else 0):
+        timed_region()
+    wall, kern_ms = timed_region()
     ms_per_step = wall * 1e3 / args.steps
     # the same measurement over a long run (what the other objects of the line are timed with)
     settled_steps = max(args.steps, 2000)
