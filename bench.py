@@ -193,7 +193,7 @@ def run_sweep(args, torch, dev):
                       "steps": args.sweep_steps, "data": "synthetic", "cases": cases}))
 
 
-def sweep_sums(torch, dev, steps=100, warmup=50):
+def sweep_sums(torch, dev, steps=200, warmup=300):
     """All 16 VGG19 conv layers at the four densities, fp32 and bf16, through rbgp_spmm with library defaults:
     per (dtype, density) the sum of the per-layer launch times.  Inputs are generated on the device (seeded,
     ReLU(N(0,1)) as everywhere); the outputs of these cells are checked in the GPU tests, not here."""

@@ -10,9 +10,10 @@
 // touches are loaded straight from global memory into VGPRs and each loaded row
 // is used for every tile row of the cluster that has the tile: the register-level
 // reuse the paper obtains from row repetition, extended across tile rows.  No
-// LDS, no barrier in the main loop: waves are independent; loads are issued two
-// stages ahead, slot by slot, into the registers the previous MFMAs just released,
-// and the compiler's vmcnt bookkeeping provides the software pipeline.  (LDS is
+// LDS, no barrier in the main loop: waves are independent; loads are issued one
+// stage ahead (two or four in the variants with several register sets), slot by
+// slot, into the registers the previous MFMAs just released, and the compiler's
+// vmcnt bookkeeping provides the software pipeline.  (LDS is
 // used once, after the loop, when the stage list of a cluster is split over
 // several waves for small N.)
 // The same kernel serves the fused 3x3 convolution: only the addresses of the
