@@ -374,6 +374,77 @@ void rbgp_plan_filled(rbgp_mask *m) {
   m->filled = t;
 }
 
+// The same mask with part of G_b's rows moved into G_i, for RBGP_KERNEL_MFMA_REG.  Where more than 16 rows share a
+// column set (|G_r.U| |G_b.U| > 16), the plan moves rows of G_r into the tile-row index until the rest fits a 16-row
+// MFMA group; with |G_b.U| = 9 (the transpose of a lowered 3x3 convolution) that leaves 9 rows of 16.  A complete
+// G_b is a Kronecker product itself, J(a_b, c_b) = J(q, 1) (x) J(a_b / q, c_b), and G_i (x) J(q, 1) is a biregular
+// graph again (every vertex of G_i repeated q times), so
+//   G_o (x) G_r (x) G_i (x) G_b = G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(a_b / q, c_b)
+// entry for entry, with the same numbering of rows and columns and the same order of a row's kept values: another
+// four-factor mask of the family, with |G_r.U| a_b / q rows per column set.  The q that fills the MFMA group best is
+// taken (9 = 3 x 3: 12 rows of 16 with |G_r.U| = 4 instead of 9), if it beats the plan of the mask as given.  Not
+// for the mask of a lowered 3x3 convolution itself (rbgp_conv3x3 reads that mask's own layout).
+void rbgp_plan_regroup(rbgp_mask *m) {
+  m->regroup = nullptr;
+  const rbgp_reg_plan &p = m->reg;
+  if (!p.ok || p.fold <= 1 || !rbgp_reg_covers(m)) return;
+  if ((m->c[3] == 9 && m->d[3] == 9) || m->d[3] != m->c[3] || m->d[1] != m->c[1]) return;
+  for (int u = 0; u < m->a[3]; ++u)      // (a complete G_b lists its columns in order: the canonical order carries over)
+    for (int v = 0; v < m->c[3]; ++v)
+      if (m->adj[3][size_t(u) * m->c[3] + v] != v) return;
+  int best_rows = 0, best_r = p.R;
+  for (int rows = 1; rows < m->a[3]; ++rows) {   // rows of G_b kept in the last factor
+    if (m->a[3] % rows) continue;
+    int a2 = m->a[1];                            // what the plan would leave of G_r (see rbgp_plan_reg)
+    while (a2 > 1 && a2 * rows > 16) {
+      --a2;
+      while (m->a[1] % a2) --a2;
+    }
+    if (a2 * rows <= 16 && a2 * rows >= best_r + (best_rows ? 0 : 1)) {
+      best_r = a2 * rows;
+      best_rows = rows;
+    }
+  }
+  if (!best_rows) return;
+  const int q = m->a[3] / best_rows;
+  if (int64_t(m->a[2]) * q > (1 << 20)) return;
+  rbgp_mask *t = new rbgp_mask();
+  try {
+    for (int i = 0; i < 4; ++i) {
+      t->a[i] = m->a[i]; t->c[i] = m->c[i]; t->d[i] = m->d[i]; t->e[i] = m->e[i];
+      t->sigma1[i] = m->sigma1[i]; t->sigma2[i] = m->sigma2[i]; t->bound[i] = m->bound[i];
+      t->status[i] = m->status[i]; t->tries[i] = 0;
+      t->adj[i] = m->adj[i];
+    }
+    t->a[2] = m->a[2] * q; t->e[2] = m->e[2] * q;
+    t->sigma1[2] = m->sigma1[2] * std::sqrt(double(q)); t->sigma2[2] = m->sigma2[2] * std::sqrt(double(q));
+    t->a[3] = best_rows; t->e[3] = best_rows;
+    t->sigma1[3] = std::sqrt(double(best_rows) * m->c[3]);
+    t->adj[2].resize(size_t(t->a[2]) * m->d[2]);
+    for (int u = 0; u < m->a[2]; ++u)
+      for (int b = 0; b < q; ++b)
+        for (int j = 0; j < m->d[2]; ++j)
+          t->adj[2][(size_t(u) * q + b) * m->d[2] + j] = m->adj[2][size_t(u) * m->d[2] + j];
+    t->adj[3].resize(size_t(best_rows) * m->c[3]);
+    for (int u = 0; u < best_rows; ++u)
+      for (int v = 0; v < m->c[3]; ++v) t->adj[3][size_t(u) * m->c[3] + v] = v;
+    t->M = m->M; t->K = m->K; t->rowdeg = m->rowdeg; t->coldeg = m->coldeg; t->nnz = m->nnz;
+    t->kernel_choice = RBGP_KERNEL_MFMA_REG;
+    t->uid = rbgp_next_uid();
+    t->dev = nullptr;
+    rbgp_plan_mfma(t);
+    rbgp_plan_reg(t);
+    if (!rbgp_reg_covers(t) || t->reg.R <= p.R) {
+      delete t;
+      return;
+    }
+  } catch (...) {
+    delete t;
+    throw;
+  }
+  m->regroup = t;
+}
+
 // Register-streaming family: group the tile rows into clusters of U whose adjacency lists
 // overlap most (greedy: seed with the lowest free tile row, add the free row that enlarges
 // the union of tiles least; then local search, and exhaustive matching for pairs), and
@@ -722,6 +793,10 @@ void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
 //           32 and at kk = 32q + 4g + e (e < 4; the rest is padding) in the block of 16:
 //           the consecutive contraction steps one lane feeds to the matrix core.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
+  if (kernel == RBGP_KERNEL_MFMA_REG && m->regroup && !bf16) {   // fp32: the register layout of the regrouped mask
+    rbgp_build_pack_perm(m->regroup, kernel, bf16, perm);         //   (same kept values, same canonical indices)
+    return;
+  }
   if (kernel == RBGP_KERNEL_MFMA_REG_FILLED) {
     // the register family's layout of the filled mask; a position that holds kept value (row, (j_o, v_r, v_i, v_b))
     // of the filled mask takes this mask's value at (j_o, v_r, j_i, v_b) where v_i = adj_i[u_i][j_i], else a zero
@@ -998,6 +1073,7 @@ int rbgp_make_mask_k(int32_t count, const int32_t *rows, const int32_t *cols, co
     rbgp_plan_mfma(m);
     rbgp_plan_reg(m);
     rbgp_plan_filled(m);
+    rbgp_plan_regroup(m);
   } catch (const std::bad_alloc &) {
     rbgp_mask_free(m);
     return RBGP_ENOMEM;
@@ -1127,6 +1203,7 @@ int rbgp_mask_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
     rbgp_plan_filled(t);
+    rbgp_plan_regroup(t);
   } catch (const std::bad_alloc &) {
     delete t;
     return RBGP_ENOMEM;
@@ -1207,6 +1284,7 @@ int rbgp_mask_conv3x3_transpose(const rbgp_mask_t *m, rbgp_mask_t **out) {
     rbgp_plan_mfma(t);
     rbgp_plan_reg(t);
     rbgp_plan_filled(t);
+    rbgp_plan_regroup(t);
   } catch (const std::bad_alloc &) {
     delete t;
     return RBGP_ENOMEM;
@@ -1229,6 +1307,7 @@ void rbgp_mask_free(rbgp_mask_t *mask) {
   if (!mask) return;
   if (mask->dev) rbgp_device_release(mask->dev);
   if (mask->filled) rbgp_mask_free(mask->filled);
+  if (mask->regroup) rbgp_mask_free(mask->regroup);
   delete mask;
 }
 
@@ -1309,6 +1388,10 @@ static int mask_reg_plan_impl(const rbgp_mask_t *m, int32_t info[16]) {
   if (!m || !info) return RBGP_EINVAL;
   for (int i = 0; i < 16; ++i) info[i] = 0;
   if (m->filled) info[13] = m->filled->reg_clusters.max_stages;
+  if (m->regroup) {   // fp32 runs on the regrouped mask
+    info[14] = m->regroup->reg.R;
+    info[15] = m->regroup->reg.TR;
+  }
   const rbgp_reg_plan &p = m->reg;
   if (!p.ok) return RBGP_OK;
   info[0] = p.MG; info[1] = p.NSTG; info[2] = p.KC; info[3] = p.TR;
@@ -1348,6 +1431,30 @@ int rbgp_mask_check_tables(const rbgp_mask_t *m) {
       for (bool bf16 : {false, true}) {
         std::vector<int32_t> perm;
         rbgp_build_pack_perm(m, RBGP_KERNEL_MFMA_REG_FILLED, bf16, perm);
+        std::vector<char> seen(size_t(m->nnz), 0);
+        for (int32_t s : perm) {
+          if (s < -1 || s >= m->nnz) return RBGP_EINTERNAL;
+          if (s >= 0 && seen[size_t(s)]++) return RBGP_EINTERNAL;
+        }
+        for (char c : seen)
+          if (!c) return RBGP_EINTERNAL;
+      }
+    } catch (const std::bad_alloc &) {
+      return RBGP_ENOMEM;
+    }
+  }
+  if (m->regroup) {   // the regrouped mask: the same entries in the same order, its own tables, and a packed layout that
+                      //   holds every kept value of this mask once
+    if (m->regroup->M != m->M || m->regroup->K != m->K || m->regroup->nnz != m->nnz) return RBGP_EINTERNAL;
+    const int rc = rbgp_mask_check_tables(m->regroup);
+    if (rc) return rc;
+    try {
+      std::vector<int32_t> mine(size_t(m->nnz)), theirs(size_t(m->nnz));
+      if (mask_columns_impl(m, mine.data()) || mask_columns_impl(m->regroup, theirs.data()) || mine != theirs)
+        return RBGP_EINTERNAL;
+      {
+        std::vector<int32_t> perm;
+        rbgp_build_pack_perm(m, RBGP_KERNEL_MFMA_REG, false, perm);
         std::vector<char> seen(size_t(m->nnz), 0);
         for (int32_t s : perm) {
           if (s < -1 || s >= m->nnz) return RBGP_EINTERNAL;

@@ -135,6 +135,11 @@ struct rbgp_mask {
   rbgp_mask *filled = nullptr;        // RBGP_KERNEL_MFMA_REG_FILLED: the mask G_o (x) J (x) G_b with G_r and G_i
                                       //   replaced by the complete graph on their vertices (same M, K, same row and
                                       //   column numbering; a superset of this mask), or nullptr; owned
+  rbgp_mask *regroup = nullptr;       // RBGP_KERNEL_MFMA_REG, fp32, on a mask with more than 16 rows per column set: the SAME mask
+                                      //   (same entries, same canonical order of the kept values) factored as
+                                      //   G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(|G_b.U| / q, |G_b.V|), whose rows per
+                                      //   column set fill more of a 16-row MFMA group; the register family then runs on
+                                      //   it (tables, plan and packed layout are its own), or nullptr; owned
 };
 
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m) {
@@ -209,5 +214,7 @@ void rbgp_reg_cluster(const rbgp_mask *m, int U, rbgp_reg_clusters *out);
 void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out);
 // builds m->filled where the register family covers it (called once, when the mask is made)
 void rbgp_plan_filled(rbgp_mask *m);
+// builds m->regroup where that factoring uses more rows of the MFMA group (called once, when the mask is made)
+void rbgp_plan_regroup(rbgp_mask *m);
 // canonical index (m * rowdeg + t) of every packed element, -1 for padding
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm);

@@ -333,7 +333,7 @@ def test_filled_family_is_what_auto_takes_for_one_row_per_column_set():
 # of the tile rows that share their tiles
 ROW_GROUP_SHAPES = [
     ((2, 8, 4, 3), (2, 2, 4, 9), (1, 2, 2, 9), (2,)),        # R = 24 -> 2 x 12, stages of 36
-    ((4, 4, 2, 9), (4, 4, 4, 2), (2, 4, 2, 2), (2, 4)),      # R = 36 -> 4 x 9 (a transposed 3x3 layer), stages of 16 in 18
+    ((4, 4, 2, 11), (4, 4, 4, 2), (2, 4, 2, 2), (2, 4)),     # R = 44 -> 4 x 11, stages of 16 in 18
     ((2, 2, 32, 2), (4, 1, 32, 1), (2, 1, 32, 1), (2,)),     # complete G_i: 128 rows -> 8 x 16, stages of 32 (no kernel of 4 groups)
     ((2, 4, 4, 2), (2, 2, 8, 9), (1, 2, 8, 9), (2,)),        # R = 32 -> 2 x 16, stages of 72
     ((4, 8, 1, 8), (8, 2, 1, 9), (4, 2, 1, 9), (2, 4)),      # R = 64 -> 4 x 16, stages of 18
@@ -358,6 +358,35 @@ def test_fp32_register_family_row_groups_per_wave(idx):
         assert e.value.code == rb.EUNSUPPORTED
 
 
+# more than 16 rows per column set with a composite |G_b.U|: the register family runs on the same mask factored as
+# G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(|G_b.U| / q, .), whose MFMA groups are fuller.  (rows, cols, degrees, rows per
+# group before and after)
+REGROUP_SHAPES = [
+    ((4, 4, 2, 9), (4, 4, 4, 2), (2, 4, 2, 2), 9, 12),      # a transposed 3x3 layer: 36 rows, 4 x 9 -> 3 x 12
+    ((4, 8, 2, 9), (4, 2, 2, 2), (2, 2, 1, 2), 9, 12),      # 72 rows: 8 x 9 -> 6 x 12, stages of 4 steps in 8
+    ((2, 32, 1, 9), (2, 4, 2, 2), (1, 4, 2, 2), 9, 16),     # 288 rows: 32 x 9 -> 18 x 16
+    ((4, 4, 4, 12), (4, 2, 4, 3), (2, 2, 2, 3), 12, 16),    # 48 rows: 4 x 12 -> 3 x 16
+]
+
+
+@pytest.mark.parametrize("idx", range(len(REGROUP_SHAPES)))
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_register_family_on_the_regrouped_mask(idx, dtype):
+    rows, cols, deg, before, after = REGROUP_SHAPES[idx]
+    N = 333 if dtype == wl.F32 else 328
+    w = wl.Workload(f"regroup{idx}", rows, cols, deg, N, dtype, 250 + idx, 260 + idx, 270 + idx, 1.0)
+    mask = rb.rbgp_make_mask(rows, cols, deg, w.mask_seed)
+    plan = rb.rbgp_mask_reg_plan(mask)
+    assert plan[14] == after                      # rows of the MFMA group in use on the regrouped mask
+    rb.rbgp_mask_check_tables(mask)
+    gh.check_parity(w, kernel=REG, ld_pad=3 if dtype == wl.F32 else 8, expect_kernel=REG)
+    gh.check_parity(w, N=64, kernel=REG, expect_kernel=REG)
+    gh.check_parity(w, N=2312, kernel=REG, tune=(0, 0, 0, 0, 0, 1), expect_kernel=REG)
+    gh.check_parity(w, N=200, kernel=REG, tune=(0, 0, 0, 0, 0, 2), expect_kernel=REG)
+    gh.check_parity(w, kernel=rb.KERNEL_AUTO)
+    gh.check_parity(w, kernel=GEN, expect_kernel=GEN)   # the generic family runs the mask as given: same results
+
+
 def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
     # a density-1/2 VGG19 layer shape (complete G_i joins G_r: 32 rows per column set), images 8 pixels wide: tap-grouped
     w = wl.Workload("rowgroups_conv", (4, 4, 4, 2), (4, 2, 8, 9), (2, 2, 8, 9), 0, wl.F32, 71, 72, 73, 1.0)
@@ -377,7 +406,7 @@ def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
 # column tiles one after the other.  (rows, cols, degrees, column tiles per wave to try, row groups per wave)
 COLUMN_TILE_SHAPES = [
     ((8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4, 8), 1),    # a transposed 3x3 layer: 36 rows -> 4 x 9, lists of 4
-    ((8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4), 2),       # the same with two of the four tile rows per wave
+    ((8, 4, 4, 11), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4), 2),      # 44 rows -> 4 x 11: two of the four tile rows per wave
     ((4, 2, 2, 4), (4, 2, 4, 2), (4, 2, 2, 2), (2, 8), 1),       # 8 rows per column set, complete G_o: lists of 4
     ((8, 2, 2, 2), (8, 1, 4, 4), (8, 1, 2, 4), (2, 4, 8), 1),    # 4 rows per column set, lists of 8
     ((8, 1, 4, 1), (8, 2, 4, 2), (8, 2, 2, 2), (4,), 1),         # one row per column set, lists of 8
