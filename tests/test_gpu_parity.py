@@ -387,6 +387,35 @@ def test_register_family_on_the_regrouped_mask(idx, dtype):
     gh.check_parity(w, kernel=GEN, expect_kernel=GEN)   # the generic family runs the mask as given: same results
 
 
+def test_regrouped_masks_randomised():
+    """Seeded random masks with a composite |G_b.U| and up to 16 x 15 rows per column set, fp32, register family:
+    the result is the oracle's whether or not the library regroups the mask; at least a third of them are regrouped."""
+    g = np.random.Generator(np.random.PCG64(20))
+    ran = regrouped = 0
+    for it in range(60):
+        a_o, c_o = int(g.choice([2, 4, 8])), int(g.choice([2, 4, 8]))
+        d_o = int(g.choice([x for x in (1, 2, 4, 8) if x <= c_o]))
+        a_r, c_r = int(g.choice([2, 4, 8, 16])), int(g.choice([1, 2, 4]))
+        a_i, c_i = int(g.choice([1, 2, 4])), int(g.choice([1, 2, 4]))
+        d_i = int(g.choice([x for x in (1, 2, 4) if x <= c_i]))
+        a_b, c_b = int(g.choice([4, 6, 8, 9, 10, 12, 15])), int(g.choice([1, 2, 3]))
+        rows, cols, deg = (a_o, a_r, a_i, a_b), (c_o, c_r, c_i, c_b), (d_o, c_r, d_i, c_b)
+        try:
+            mask = rb.rbgp_make_mask(rows, cols, deg, 300 + it)
+        except rb.RbgpError:
+            continue                                  # (not a shape the sampler accepts)
+        plan = rb.rbgp_mask_reg_plan(mask)
+        if plan[0] == 0:
+            continue
+        rb.rbgp_mask_check_tables(mask)
+        w = wl.Workload(f"regroup_rand{it}", rows, cols, deg, int(g.choice([64, 200, 333])), wl.F32, 300 + it, 301 + it,
+                        302 + it, 1.0)
+        gh.check_parity(w, kernel=REG, ld_pad=int(g.choice([0, 3])), expect_kernel=REG)
+        ran += 1
+        regrouped += plan[14] > 0
+    assert ran >= 30 and 3 * regrouped >= ran
+
+
 def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
     # a density-1/2 VGG19 layer shape (complete G_i joins G_r: 32 rows per column set), images 8 pixels wide: tap-grouped
     w = wl.Workload("rowgroups_conv", (4, 4, 4, 2), (4, 2, 8, 9), (2, 2, 8, 9), 0, wl.F32, 71, 72, 73, 1.0)
