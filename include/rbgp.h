@@ -110,7 +110,8 @@ enum {
                                          rows).  fp32: only tile rows that have the very same tiles -- masks
                                          with more than 16 rows per column set, whose rows of G_r move into
                                          the tile-row index -- 2 for every stage size, 4 for stages of up to
-                                         18 steps (else EUNSUPPORTED) */
+                                         18 steps (else EUNSUPPORTED; a mask that fp32 runs regrouped, see
+                                         rbgp_mask_reg_plan, has the tile rows of that factoring) */
   RBGP_TUNE_K_SPLIT = 5,              /* MFMA_REG: waves that share a column tile and split its
                                          nonzero tiles between them, 1, 2 or 4 (default: 1 unless N
                                          is too small to give every SIMD a wave) */
