@@ -394,7 +394,9 @@ int rbgp_mask_original_order(const rbgp_mask_t *derived, int32_t *out);
  * (RBGP_KERNEL_MFMA_REG_FILLED; 0: not available for this mask).  Masks with more than 16 rows per column set and
  * a composite |G_b.U| (the transpose of a lowered 3x3 convolution): in fp32 the family runs on the same mask
  * factored as G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(|G_b.U| / q, |G_b.V|), which fills more of the 16 rows of an
- * MFMA group; [14] = rows of a group in use there, [15] = its tile rows (0, 0: the mask runs as given). */
+ * MFMA group; [14] = rows of a group in use there, [15] = its tile rows (0, 0: the mask runs as given).  Masks with
+ * a complete G_o run (both dtypes) with G_o (x) G_r merged into one tile column, J(a_o, 1) (x) J(a_r, c_o c_r), where
+ * that makes the stages longer and the walk cheaper; [14], [15] then describe that factoring. */
 int rbgp_mask_reg_plan(const rbgp_mask_t *mask, int32_t info[16]);
 
 /* Host-only self check of the index tables the RBGP_KERNEL_MFMA_REG kernels read for this mask: every

@@ -389,7 +389,7 @@ bool mfma_covers(const rbgp_mask *m) {
 // MFMAs of ~36 cycles (fp32), or ~8 cycles per step in bf16 (the loads of the stage; its 32-step MFMAs hide behind
 // them, a second MFMA block for the remainder of a stage does not), plus what does not overlap.
 double reg_seconds(const rbgp_mask *m, bool bf16) {
-  if (m->regroup && !bf16) m = m->regroup;   // (the fp32 kernels run on the regrouped mask)
+  if (m->regroup && (!bf16 || m->regroup_bf16)) m = m->regroup;   // (the kernels run on the regrouped mask)
   const rbgp_reg_clusters &cl = m->reg_clusters;
   int64_t walked = 0;
   for (int c = 0; c < cl.ncl; ++c) walked += cl.counts[size_t(c)];
@@ -469,7 +469,7 @@ int64_t packed_elems(const rbgp_mask *m, int kernel, rbgp_dtype_t dtype) {
   if (kernel == RBGP_KERNEL_MFMA) return m->plan.packed_elems;
   if (kernel == RBGP_KERNEL_MFMA_TILE) return rbgp_plan_tile(m).packed_elems;
   if (kernel == RBGP_KERNEL_MFMA_REG) {
-    if (bf16_in(dtype)) return m->reg.packed_elems_bf16;
+    if (bf16_in(dtype)) return m->regroup && m->regroup_bf16 ? m->regroup->reg.packed_elems_bf16 : m->reg.packed_elems_bf16;
     return m->regroup ? m->regroup->reg.packed_elems : m->reg.packed_elems;
   }
   if (kernel == RBGP_KERNEL_MFMA_REG_FILLED)
@@ -727,7 +727,7 @@ static int spmm_impl(const rbgp_mask_t *m, rbgp_dtype_t dtype, int64_t M, int64_
   // fp32: the same mask factored for fuller MFMA groups (its own tables, this mask's knobs).  Not bf16: there the
   // matrix core has room, the load path does not, and the regrouped mask has fewer tile rows that share their loads
   // (VGG19 backward data products: fp32 17-36 % faster, bf16 5-25 % slower).
-  if (kernel == RBGP_KERNEL_MFMA_REG && m->regroup && !bf16) {
+  if (kernel == RBGP_KERNEL_MFMA_REG && m->regroup && (!bf16 || m->regroup_bf16)) {
     rc = ensure_device(m->regroup);
     if (rc) return rc;
     return rbgp_reg_launch(m->regroup, &m->regroup->dev->reg_state, dev->tune, bf16, out_bf16, N, dev_packed, dev_I,

@@ -384,11 +384,21 @@ void rbgp_plan_filled(rbgp_mask *m) {
 // four-factor mask of the family, with |G_r.U| a_b / q rows per column set.  The q that fills the MFMA group best is
 // taken (9 = 3 x 3: 12 rows of 16 with |G_r.U| = 4 instead of 9), if it beats the plan of the mask as given.  Not
 // for the mask of a lowered 3x3 convolution itself (rbgp_conv3x3 reads that mask's own layout).
+//
+// The column side has the same freedom where G_o is complete: J(a_o, c_o) (x) J(a_r, c_r) = J(a_o, 1) (x) J(a_r, c_o c_r),
+// one tile column that holds all of K.  A stage is a run of columns of G_r inside a tile, so with few columns in G_r
+// the stages are short however dense the mask (Table 2's cells with a complete G_o: |G_r.V| = 1, stages of 2 to 8
+// steps padded to 8, 128 of them per wave); on the merged factoring they are 64 steps of 72.  Both dtypes.
+static bool plan_regroup_columns(rbgp_mask *m);
+
 void rbgp_plan_regroup(rbgp_mask *m) {
   m->regroup = nullptr;
+  m->regroup_bf16 = false;
   const rbgp_reg_plan &p = m->reg;
-  if (!p.ok || p.fold <= 1 || !rbgp_reg_covers(m)) return;
+  if (!p.ok || !rbgp_reg_covers(m)) return;
   if ((m->c[3] == 9 && m->d[3] == 9) || m->d[3] != m->c[3] || m->d[1] != m->c[1]) return;
+  if (plan_regroup_columns(m)) return;
+  if (p.fold <= 1) return;
   for (int u = 0; u < m->a[3]; ++u)      // (a complete G_b lists its columns in order: the canonical order carries over)
     for (int v = 0; v < m->c[3]; ++v)
       if (m->adj[3][size_t(u) * m->c[3] + v] != v) return;
@@ -443,6 +453,55 @@ void rbgp_plan_regroup(rbgp_mask *m) {
     throw;
   }
   m->regroup = t;
+}
+
+static bool plan_regroup_columns(rbgp_mask *m) {
+  const rbgp_reg_plan &p = m->reg;
+  if (m->c[0] <= 1 || m->d[0] != m->c[0] || p.KC >= 72) return false;
+  if (int64_t(m->c[0]) * m->c[1] > (1 << 20)) return false;
+  for (int i = 0; i < 2; ++i)     // (complete factors that list their columns in order: the canonical order carries over)
+    for (int u = 0; u < m->a[i]; ++u)
+      for (int v = 0; v < m->c[i]; ++v)
+        if (m->adj[i][size_t(u) * m->c[i] + v] != v) return false;
+  rbgp_mask *t = new rbgp_mask();
+  try {
+    for (int i = 0; i < 4; ++i) {
+      t->a[i] = m->a[i]; t->c[i] = m->c[i]; t->d[i] = m->d[i]; t->e[i] = m->e[i];
+      t->sigma1[i] = m->sigma1[i]; t->sigma2[i] = m->sigma2[i]; t->bound[i] = m->bound[i];
+      t->status[i] = m->status[i]; t->tries[i] = 0;
+      t->adj[i] = m->adj[i];
+    }
+    const int cr = m->c[0] * m->c[1];
+    t->c[0] = 1; t->d[0] = 1; t->e[0] = m->a[0]; t->sigma1[0] = std::sqrt(double(m->a[0])); t->sigma2[0] = 0.0;
+    t->c[1] = cr; t->d[1] = cr; t->e[1] = m->a[1]; t->sigma1[1] = std::sqrt(double(m->a[1]) * cr); t->sigma2[1] = 0.0;
+    t->adj[0].assign(size_t(m->a[0]), 0);
+    t->adj[1].resize(size_t(m->a[1]) * cr);
+    for (int u = 0; u < m->a[1]; ++u)
+      for (int v = 0; v < cr; ++v) t->adj[1][size_t(u) * cr + v] = v;
+    t->M = m->M; t->K = m->K; t->rowdeg = m->rowdeg; t->coldeg = m->coldeg; t->nnz = m->nnz;
+    t->kernel_choice = RBGP_KERNEL_MFMA_REG;
+    t->uid = rbgp_next_uid();
+    t->dev = nullptr;
+    rbgp_plan_mfma(t);
+    rbgp_plan_reg(t);
+    // taken where the stages get longer and the walk cheaper (per stage ~110 cycles + 36 per padded step, the fp32
+    // kernels' measured cost; bf16 follows the same order)
+    auto walk_cost = [](const rbgp_mask *x) {
+      int64_t n = 0;
+      for (int32_t c : x->reg_clusters.counts) n += c;
+      return n * (110 + 36 * x->reg.KC) * x->a[2];
+    };
+    if (!rbgp_reg_covers(t) || t->reg.KC <= p.KC || walk_cost(t) >= walk_cost(m)) {
+      delete t;
+      return false;
+    }
+  } catch (...) {
+    delete t;
+    throw;
+  }
+  m->regroup = t;
+  m->regroup_bf16 = true;
+  return true;
 }
 
 // Register-streaming family: group the tile rows into clusters of U whose adjacency lists
@@ -793,7 +852,7 @@ void rbgp_reg_plan_dual(const rbgp_mask *m, rbgp_reg_dual *out) {
 //           32 and at kk = 32q + 4g + e (e < 4; the rest is padding) in the block of 16:
 //           the consecutive contraction steps one lane feeds to the matrix core.
 void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector<int32_t> &perm) {
-  if (kernel == RBGP_KERNEL_MFMA_REG && m->regroup && !bf16) {   // fp32: the register layout of the regrouped mask
+  if (kernel == RBGP_KERNEL_MFMA_REG && m->regroup && (!bf16 || m->regroup_bf16)) {   // the register layout of the regrouped mask
     rbgp_build_pack_perm(m->regroup, kernel, bf16, perm);         //   (same kept values, same canonical indices)
     return;
   }
@@ -1452,9 +1511,9 @@ int rbgp_mask_check_tables(const rbgp_mask_t *m) {
       std::vector<int32_t> mine(size_t(m->nnz)), theirs(size_t(m->nnz));
       if (mask_columns_impl(m, mine.data()) || mask_columns_impl(m->regroup, theirs.data()) || mine != theirs)
         return RBGP_EINTERNAL;
-      {
+      for (bool bf16 : {false, true}) {
         std::vector<int32_t> perm;
-        rbgp_build_pack_perm(m, RBGP_KERNEL_MFMA_REG, false, perm);
+        rbgp_build_pack_perm(m, RBGP_KERNEL_MFMA_REG, bf16, perm);
         std::vector<char> seen(size_t(m->nnz), 0);
         for (int32_t s : perm) {
           if (s < -1 || s >= m->nnz) return RBGP_EINTERNAL;

@@ -139,7 +139,10 @@ struct rbgp_mask {
                                       //   (same entries, same canonical order of the kept values) factored as
                                       //   G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(|G_b.U| / q, |G_b.V|), whose rows per
                                       //   column set fill more of a 16-row MFMA group; the register family then runs on
-                                      //   it (tables, plan and packed layout are its own), or nullptr; owned
+                                      //   it (tables, plan and packed layout are its own), or nullptr; owned.  Or, where
+                                      //   G_o is complete, the same mask with G_o (x) G_r merged into one tile column
+                                      //   J(a_o, 1) (x) J(a_r, c_o c_r), whose stages are longer (then for bf16 as well)
+  bool regroup_bf16 = false;          // the bf16 kernels run on `regroup` too
 };
 
 inline bool rbgp_reg_tap_grouped(const rbgp_mask *m) {

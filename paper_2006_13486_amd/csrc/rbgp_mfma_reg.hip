@@ -551,9 +551,9 @@ struct RegTilesEntry {
   int RS, NG;
   reg_fn fn;
 };
-const RegTilesEntry kRegTilesTable[] = {{2, 1, spmm_reg<8, 2, false, 1, true>},   {4, 1, spmm_reg<8, 4, false, 1, true>},
-                                        {8, 1, spmm_reg<8, 8, false, 1, true>},   {16, 1, spmm_reg<8, 16, false, 1, true>},
-                                        {16, 2, spmm_reg<8, 16, false, 2, true>}};
+// (one tile row per group only: with several, the stage lists are of one length only where G_o is complete, and such
+// masks run with G_o (x) G_r merged, rbgp_plan_regroup, on longer stages)
+const RegTilesEntry kRegTilesTable[] = {{16, 1, spmm_reg<8, 16, false, 1, true>}, {16, 2, spmm_reg<8, 16, false, 2, true>}};
 reg_fn find_reg_tiles(int KC, int RS, int NG) {
   if (KC != 8) return nullptr;
   for (const RegTilesEntry &e : kRegTilesTable)

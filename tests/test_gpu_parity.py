@@ -258,7 +258,7 @@ def test_shapes_across_the_kernel_table(idx, dtype):
 # stage lists as long as or longer than the 64 stages one wave holds: split over 2 or 4 waves of the workgroup
 LONG_LISTS = [
     ((4, 2, 2, 1), (128, 1, 2, 1), (64, 1, 2, 1)),     # 64 tiles per tile row (complete G_i joins G_r): 2 waves
-    ((2, 4, 1, 2), (128, 1, 1, 2), (128, 1, 1, 2)),    # complete G_o of 128 tiles: 4 waves
+    ((4, 4, 1, 2), (256, 1, 1, 2), (128, 1, 1, 2)),    # G_o of 256 tile columns at 1/2, two tile rows per cluster: 3 waves
     ((4, 2, 4, 2), (64, 4, 8, 9), (32, 4, 4, 9)),      # two stages of 72 steps per tile, four tile rows per cluster
     ((8, 1, 4, 1), (64, 2, 4, 2), (16, 2, 1, 2)),      # clusters of 8 tile rows whose union fills one wave's table to the last lane
 ]
@@ -387,6 +387,34 @@ def test_register_family_on_the_regrouped_mask(idx, dtype):
     gh.check_parity(w, kernel=GEN, expect_kernel=GEN)   # the generic family runs the mask as given: same results
 
 
+# a complete G_o: the register family runs on the same mask with G_o (x) G_r merged into one tile column, whose
+# stages are longer (rows, cols, degrees, steps per stage before and after)
+MERGED_COLUMN_SHAPES = [
+    ((4, 2, 2, 4), (4, 2, 4, 2), (4, 2, 2, 2), 8, 32),          # 4 tiles of 8 steps -> one stage of 32
+    ((8, 2, 2, 2), (8, 1, 4, 4), (8, 1, 2, 4), 8, 72),          # 8 tiles of 8 steps -> one stage of 64 in 72
+    ((8, 1, 4, 1), (8, 2, 4, 2), (8, 2, 2, 2), 8, 72),          # one row per column set
+    ((2, 4, 1, 2), (128, 1, 1, 2), (128, 1, 1, 2), 8, 72),      # 128 tiles of 2 steps in 8 -> 4 stages of 64 in 72
+    ((4, 4, 8, 1), (32, 1, 8, 1), (32, 1, 2, 1), 8, 72),        # Table 2's shape with a complete G_o, small
+]
+
+
+@pytest.mark.parametrize("idx", range(len(MERGED_COLUMN_SHAPES)))
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_register_family_on_the_mask_with_merged_tile_columns(idx, dtype):
+    rows, cols, deg, before, after = MERGED_COLUMN_SHAPES[idx]
+    N = 333 if dtype == wl.F32 else 328
+    w = wl.Workload(f"merged{idx}", rows, cols, deg, N, dtype, 280 + idx, 290 + idx, 295 + idx, 1.0)
+    mask = rb.rbgp_make_mask(rows, cols, deg, w.mask_seed)
+    plan = rb.rbgp_mask_reg_plan(mask)
+    assert plan[2] == before and plan[14] > 0 and plan[15] > 0
+    rb.rbgp_mask_check_tables(mask)
+    gh.check_parity(w, kernel=REG, ld_pad=3 if dtype == wl.F32 else 8, expect_kernel=REG)
+    gh.check_parity(w, N=64 if dtype == wl.F32 else 128, kernel=REG, expect_kernel=REG)
+    gh.check_parity(w, N=2312, kernel=REG, tune=(0, 0, 0, 0, 0, 1), expect_kernel=REG)
+    gh.check_parity(w, N=200, kernel=REG, tune=(0, 0, 0, 0, 0, 2), expect_kernel=REG)
+    gh.check_parity(w, kernel=GEN, expect_kernel=GEN)
+
+
 def test_regrouped_masks_randomised():
     """Seeded random masks with a composite |G_b.U| and up to 16 x 15 rows per column set, fp32, register family:
     the result is the oracle's whether or not the library regroups the mask; at least a third of them are regrouped."""
@@ -436,9 +464,6 @@ def test_fp32_row_groups_on_the_fused_convolution_and_refusals():
 COLUMN_TILE_SHAPES = [
     ((8, 4, 4, 9), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4, 8), 1),    # a transposed 3x3 layer: 36 rows -> 4 x 9, lists of 4
     ((8, 4, 4, 11), (8, 4, 2, 2), (4, 4, 1, 2), (2, 4), 2),      # 44 rows -> 4 x 11: two of the four tile rows per wave
-    ((4, 2, 2, 4), (4, 2, 4, 2), (4, 2, 2, 2), (2, 8), 1),       # 8 rows per column set, complete G_o: lists of 4
-    ((8, 2, 2, 2), (8, 1, 4, 4), (8, 1, 2, 4), (2, 4, 8), 1),    # 4 rows per column set, lists of 8
-    ((8, 1, 4, 1), (8, 2, 4, 2), (8, 2, 2, 2), (4,), 1),         # one row per column set, lists of 8
     ((8, 4, 4, 9), (8, 3, 4, 2), (4, 3, 1, 2), (4,), 1),         # stages of 6 steps in 8
 ]
 
@@ -454,12 +479,10 @@ def test_fp32_register_family_column_tiles_per_wave(idx):
         gh.check_parity(w, kernel=REG, tune=tune, ld_pad=3, expect_kernel=REG)          # 6 tiles
         gh.check_parity(w, N=64, kernel=REG, tune=tune, expect_kernel=REG)              # one tile
         gh.check_parity(w, N=2309, kernel=REG, tune=tune, ld_pad=1, expect_kernel=REG)  # 37 tiles
-    if 8 not in tiles and rb.rbgp_mask_reg_plan(rb.rbgp_make_mask(rows, cols, deg, w.mask_seed))[5] == 8:
-        gh.check_parity(w, N=1024, kernel=REG, tune=(0, 0, 0, 0, ng, 1, 8), expect_kernel=REG)   # 8 x 8 = the 64 table lanes
 
 
 def test_column_tiles_per_wave_refusals_and_default():
-    # stage lists of different lengths (sparse G_o, two tile rows per group), the fused convolution, a split list,
+    # stage lists of different lengths (sparse G_o, two tile rows per group: no kernel of this kind), a split list,
     # stages of more than 8 steps, bf16: refused
     ragged = wl.Workload("coltiles_ragged", (16, 2, 2, 4), (16, 2, 4, 2), (8, 2, 2, 2), 256, wl.F32, 171, 172, 173, 1.0)
     long_steps = wl.Workload("coltiles_18", (8, 4, 4, 9), (8, 4, 4, 2), (4, 4, 2, 2), 256, wl.F32, 174, 175, 176, 1.0)
