@@ -83,14 +83,17 @@ enum {
                                |G_r.U| |G_i.U| |G_b.U| = 32 and |G_r.V| |G_i.V| |G_b.V| <= 320.
                                rbgp_spmm then needs dev_I 16-byte aligned and ldI a multiple of 8,
                                rbgp_conv3x3 an image width that is a multiple of 8 (ESHAPE) */
-  RBGP_KERNEL_MFMA_REG_FILLED = 5 /* the RBGP_KERNEL_MFMA_REG kernels on the mask with G_i filled in: the
-                               packed buffer stores a zero wherever G_i has no edge, so all
-                               |G_r.U| |G_i.U| |G_b.U| rows of a tile share one column set (row repetition,
-                               Section 5, bought with multiplied zeros: |G_i.V| / d_i times the products).
-                               For masks with few rows per column set (|G_r.U| |G_b.U| <= 4, the slow rows
-                               of Table 3) and a moderately sparse G_i; AUTO takes it where it estimates
-                               it faster, never for masks whose G_b is the nine taps of a 3x3
-                               convolution (rbgp_conv3x3 does not run on it) */
+  RBGP_KERNEL_MFMA_REG_FILLED = 5 /* the RBGP_KERNEL_MFMA_REG kernels on a superset of the mask, the packed buffer
+                               storing a zero wherever the mask has no entry.  Either G_i filled in: all
+                               |G_r.U| |G_i.U| |G_b.U| rows of a tile then share one column set (row repetition,
+                               Section 5, bought with |G_i.V| / d_i times the products); for masks with few
+                               rows per column set (|G_r.U| |G_b.U| <= 4, the slow rows of Table 3) and a
+                               moderately sparse G_i.  Or G_o filled in (at least a quarter full): G_o (x) G_r
+                               is then one tile column through all of K, walked in stages of up to 72 steps
+                               instead of the few one tile holds, at |G_o.V| / d_o times the products.  The
+                               library keeps the candidate it estimates cheaper; AUTO takes it where it
+                               estimates it faster than the mask as given, never for masks whose G_b is the
+                               nine taps of a 3x3 convolution (rbgp_conv3x3 does not run on it) */
 };
 
 /* tuning knobs (rbgp_mask_tune) */

@@ -331,33 +331,54 @@ void rbgp_plan_reg(rbgp_mask *m) {
 // groups of the register family want; the price is a zero stored and multiplied wherever G_i has no edge.
 // Built only where that can pay: few rows per column set here (<= 4), a sparse G_i, and a filled mask the
 // register family covers.
-void rbgp_plan_filled(rbgp_mask *m) {
-  m->filled = nullptr;
+// A second way to the same end, where G_o is at least a quarter full: G_o filled in.  The filled G_o is complete, so
+// G_o (x) G_r merges into one tile column (see rbgp_plan_regroup) and the stages become runs of up to 72 steps
+// through all of K instead of the few steps one tile holds; every tile row has that one tile, so groups of several
+// tile rows are full.  c_o / d_o times the products.  Of the two candidates the one whose walk is cheaper (per stage
+// ~110 cycles + 36 per padded step) is kept; AUTO then weighs it against the mask as given.
+static rbgp_mask *filled_twin(const rbgp_mask *m, int kind) {
   const bool roles = m->d[1] == m->c[1] && m->d[3] == m->c[3];
-  if (!roles || m->d[2] == m->c[2] || int64_t(m->a[1]) * m->a[3] > 4) return;
-  const int64_t ar = int64_t(m->a[1]) * m->a[2], cr = int64_t(m->c[1]) * m->c[2];
-  const int64_t rowdeg = int64_t(m->d[0]) * cr * m->c[3];
-  if (ar > (1 << 20) || cr > (1 << 20) || m->M * rowdeg >= (int64_t(1) << 31)) return;
+  if (!roles || (m->c[3] == 9 && m->d[3] == 9 && kind == 1)) return nullptr;
+  int32_t a[4], c[4], d[4];
+  int64_t rowdeg, coldeg;
+  if (kind == 0) {
+    if (m->d[2] == m->c[2] || int64_t(m->a[1]) * m->a[3] > 4) return nullptr;
+    const int64_t ar = int64_t(m->a[1]) * m->a[2], cr = int64_t(m->c[1]) * m->c[2];
+    if (ar > (1 << 20) || cr > (1 << 20)) return nullptr;
+    const int32_t aa[4] = {m->a[0], int32_t(ar), 1, m->a[3]}, cc[4] = {m->c[0], int32_t(cr), 1, m->c[3]};
+    for (int i = 0; i < 4; ++i) { a[i] = aa[i]; c[i] = cc[i]; d[i] = i == 0 ? m->d[0] : cc[i]; }
+    rowdeg = int64_t(m->d[0]) * cr * m->c[3];
+    coldeg = int64_t(m->e[0]) * ar * m->a[3];
+  } else {
+    if (m->d[0] == m->c[0] || int64_t(m->c[0]) > 4 * int64_t(m->d[0])) return nullptr;
+    const int64_t cr = int64_t(m->c[0]) * m->c[1];
+    if (cr > (1 << 20)) return nullptr;
+    const int32_t cc[4] = {1, int32_t(cr), m->c[2], m->c[3]};
+    for (int i = 0; i < 4; ++i) { a[i] = m->a[i]; c[i] = cc[i]; d[i] = i == 2 ? m->d[2] : cc[i]; }
+    rowdeg = cr * m->d[2] * m->c[3];
+    coldeg = int64_t(m->a[0]) * m->a[1] * m->e[2] * m->a[3];
+  }
+  if (m->M * rowdeg >= (int64_t(1) << 31)) return nullptr;
   rbgp_mask *t = new rbgp_mask();
   try {
-    const int32_t a[4] = {m->a[0], int32_t(ar), 1, m->a[3]}, c[4] = {m->c[0], int32_t(cr), 1, m->c[3]};
     for (int i = 0; i < 4; ++i) {
-      t->a[i] = a[i]; t->c[i] = c[i];
-      t->d[i] = i == 0 ? m->d[0] : c[i];
-      t->e[i] = i == 0 ? m->e[0] : a[i];
-      t->sigma1[i] = i == 0 ? m->sigma1[0] : std::sqrt(double(a[i]) * c[i]);
-      t->sigma2[i] = i == 0 ? m->sigma2[0] : 0.0;
-      t->bound[i] = i == 0 ? m->bound[0] : std::sqrt(double(t->d[i] - 1)) + std::sqrt(double(t->e[i] - 1));
-      t->status[i] = i == 0 ? m->status[0] : RBGP_SPEC_COMPLETE;
+      const bool same = kind == 0 ? i == 0 : i == 2;     // the factor the twin shares with the mask
+      t->a[i] = a[i]; t->c[i] = c[i]; t->d[i] = d[i];
+      t->e[i] = same ? m->e[i] : a[i];
+      t->sigma1[i] = same ? m->sigma1[i] : std::sqrt(double(a[i]) * c[i]);
+      t->sigma2[i] = same ? m->sigma2[i] : 0.0;
+      t->bound[i] = same ? m->bound[i] : std::sqrt(double(t->d[i] - 1)) + std::sqrt(double(t->e[i] - 1));
+      t->status[i] = same ? m->status[i] : RBGP_SPEC_COMPLETE;
       t->tries[i] = 0;
+      if (same) {
+        t->adj[i] = m->adj[i];
+      } else {
+        t->adj[i].resize(size_t(a[i]) * c[i]);
+        for (int u = 0; u < a[i]; ++u)
+          for (int v = 0; v < c[i]; ++v) t->adj[i][size_t(u) * c[i] + v] = v;
+      }
     }
-    t->adj[0] = m->adj[0];
-    for (int i = 1; i < 4; ++i) {
-      t->adj[i].resize(size_t(a[i]) * c[i]);
-      for (int u = 0; u < a[i]; ++u)
-        for (int v = 0; v < c[i]; ++v) t->adj[i][size_t(u) * c[i] + v] = v;
-    }
-    t->M = m->M; t->K = m->K; t->rowdeg = rowdeg; t->coldeg = int64_t(m->e[0]) * ar * m->a[3]; t->nnz = m->M * rowdeg;
+    t->M = m->M; t->K = m->K; t->rowdeg = rowdeg; t->coldeg = coldeg; t->nnz = m->M * rowdeg;
     t->kernel_choice = RBGP_KERNEL_MFMA_REG;
     t->uid = rbgp_next_uid();
     t->dev = nullptr;
@@ -365,13 +386,35 @@ void rbgp_plan_filled(rbgp_mask *m) {
     rbgp_plan_reg(t);
     if (!rbgp_reg_covers(t) || t->reg.packed_elems * 4 > (int64_t(1) << 30)) {
       delete t;
-      return;
+      return nullptr;
     }
   } catch (...) {
     delete t;
     throw;
   }
-  m->filled = t;
+  return t;
+}
+
+void rbgp_plan_filled(rbgp_mask *m) {
+  m->filled = nullptr;
+  m->filled_kind = 0;
+  auto walk_cost = [](const rbgp_mask *x) {
+    int64_t n = 0;
+    for (int32_t c : x->reg_clusters.counts) n += c;
+    return n * (110 + 36 * x->reg.KC) * x->a[2];
+  };
+  rbgp_mask *t0 = filled_twin(m, 0), *t1 = nullptr;
+  try {
+    t1 = filled_twin(m, 1);
+  } catch (...) {
+    delete t0;
+    throw;
+  }
+  if (t0 && t1) {
+    if (walk_cost(t1) < walk_cost(t0)) { delete t0; t0 = nullptr; } else { delete t1; t1 = nullptr; }
+  }
+  m->filled = t0 ? t0 : t1;
+  m->filled_kind = t0 ? 0 : 1;
 }
 
 // The same mask with part of G_b's rows moved into G_i, for RBGP_KERNEL_MFMA_REG.  Where more than 16 rows share a
@@ -861,6 +904,28 @@ void rbgp_build_pack_perm(const rbgp_mask *m, int kernel, bool bf16, std::vector
     // of the filled mask takes this mask's value at (j_o, v_r, j_i, v_b) where v_i = adj_i[u_i][j_i], else a zero
     const rbgp_mask *t = m->filled;
     rbgp_build_pack_perm(t, RBGP_KERNEL_MFMA_REG, bf16, perm);
+    if (m->filled_kind == 1) {
+      // G_o filled in and merged with G_r: the filled mask's kept value (row, (v_o c_r + v_r, j_i, v_b)) is this mask's
+      // value at (j_o, j_r, j_i, j_b) with v_o = adj_o[u_o][j_o] (v_r, v_b likewise), else a zero
+      std::vector<int32_t> wh[4];
+      for (int i : {0, 1, 3}) {
+        wh[i].assign(size_t(m->a[i]) * m->c[i], -1);
+        for (int u = 0; u < m->a[i]; ++u)
+          for (int j = 0; j < m->d[i]; ++j) wh[i][size_t(u) * m->c[i] + m->adj[i][size_t(u) * m->d[i] + j]] = j;
+      }
+      const int64_t c3 = m->c[3], d2 = m->d[2], c1 = m->c[1];
+      const int64_t rows_o = int64_t(m->a[1]) * m->a[2] * m->a[3], rows_r = int64_t(m->a[2]) * m->a[3];
+      for (int32_t &s : perm) {
+        if (s < 0) continue;
+        const int64_t row = s / t->rowdeg, tt = s % t->rowdeg;
+        const int64_t v4 = tt % c3, j3 = (tt / c3) % d2, vr = tt / (c3 * d2);
+        const int64_t v1 = vr / c1, v2 = vr % c1;
+        const int64_t u1 = row / rows_o, u2 = (row / rows_r) % m->a[1], u4 = row % m->a[3];
+        const int j1 = wh[0][size_t(u1 * m->c[0] + v1)], j2 = wh[1][size_t(u2 * c1 + v2)], j4 = wh[3][size_t(u4 * c3 + v4)];
+        s = j1 < 0 ? -1 : int32_t(row * m->rowdeg + ((int64_t(j1) * m->d[1] + j2) * d2 + j3) * m->d[3] + j4);
+      }
+      return;
+    }
     std::vector<int32_t> where(size_t(m->a[2]) * m->c[2], -1);   // where[u_i * c_i + v_i]: position of v_i in adj_i[u_i]
     for (int u = 0; u < m->a[2]; ++u)
       for (int j = 0; j < m->d[2]; ++j) where[size_t(u) * m->c[2] + m->adj[2][size_t(u) * m->d[2] + j]] = j;

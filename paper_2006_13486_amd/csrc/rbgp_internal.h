@@ -135,6 +135,7 @@ struct rbgp_mask {
   rbgp_mask *filled = nullptr;        // RBGP_KERNEL_MFMA_REG_FILLED: the mask G_o (x) J (x) G_b with G_r and G_i
                                       //   replaced by the complete graph on their vertices (same M, K, same row and
                                       //   column numbering; a superset of this mask), or nullptr; owned
+  int filled_kind = 0;                // 0: G_i filled in; 1: G_o filled in (and merged with G_r into one tile column)
   rbgp_mask *regroup = nullptr;       // RBGP_KERNEL_MFMA_REG, fp32, on a mask with more than 16 rows per column set: the SAME mask
                                       //   (same entries, same canonical order of the kept values) factored as
                                       //   G_o (x) G_r (x) (G_i (x) J(q, 1)) (x) J(|G_b.U| / q, |G_b.V|), whose rows per

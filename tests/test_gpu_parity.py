@@ -700,9 +700,9 @@ def test_sdmm4096_paper_workload_sampled():
     vl, Il, vf, If = gh.host_inputs(w)
     cols = np.r_[0:64, 2000:2064, 4032:4096]
     ref, den = gh.oracle_spmm(w, vf, np.ascontiguousarray(If[:, cols]))
-    # the default launch (register family: 128-stage lists split over the waves of a workgroup), the LDS family,
-    # and the register family on the mask with G_i filled in
-    for kernel, want in ((rb.KERNEL_AUTO, REG), (MFMA, MFMA), (FILLED, FILLED)):
+    # the default launch (the register family on the mask with G_o filled in and merged with G_r), the register family on
+    # the mask as given (stage lists split over the waves of a workgroup) and the LDS family
+    for kernel, want in ((rb.KERNEL_AUTO, FILLED), (REG, REG), (MFMA, MFMA), (FILLED, FILLED)):
         out, used = gh.library_spmm(w, vl, Il, kernel=kernel, tag="table2")
         assert used == want
         assert orc.normalised_error(out[:, cols], ref, den) <= gh.TOL[w.dtype]
