@@ -353,10 +353,14 @@ static rbgp_mask *filled_twin(const rbgp_mask *m, int kind) {
     if (m->d[0] == m->c[0] || int64_t(m->c[0]) > 4 * int64_t(m->d[0])) return nullptr;
     const int64_t cr = int64_t(m->c[0]) * m->c[1];
     if (cr > (1 << 20)) return nullptr;
-    const int32_t cc[4] = {1, int32_t(cr), m->c[2], m->c[3]};
-    for (int i = 0; i < 4; ++i) { a[i] = m->a[i]; c[i] = cc[i]; d[i] = i == 2 ? m->d[2] : cc[i]; }
+    // (both G_o and G_r complete now: their rows merge as well, J(a_o, 1) (x) J(a_r, c_o c_r) = J(1, 1) (x) J(a_o a_r, c_o c_r),
+    // so all a_o a_r |G_b.U| rows of a G_i vertex share one column set: full MFMA groups whatever |G_r.U| |G_b.U| is)
+    const int64_t ar = int64_t(m->a[0]) * m->a[1];
+    if (ar > (1 << 20)) return nullptr;
+    const int32_t aa[4] = {1, int32_t(ar), m->a[2], m->a[3]}, cc[4] = {1, int32_t(cr), m->c[2], m->c[3]};
+    for (int i = 0; i < 4; ++i) { a[i] = aa[i]; c[i] = cc[i]; d[i] = i == 2 ? m->d[2] : cc[i]; }
     rowdeg = cr * m->d[2] * m->c[3];
-    coldeg = int64_t(m->a[0]) * m->a[1] * m->e[2] * m->a[3];
+    coldeg = ar * m->e[2] * m->a[3];
   }
   if (m->M * rowdeg >= (int64_t(1) << 31)) return nullptr;
   rbgp_mask *t = new rbgp_mask();
@@ -501,7 +505,7 @@ void rbgp_plan_regroup(rbgp_mask *m) {
 static bool plan_regroup_columns(rbgp_mask *m) {
   const rbgp_reg_plan &p = m->reg;
   if (m->c[0] <= 1 || m->d[0] != m->c[0] || p.KC >= 72) return false;
-  if (int64_t(m->c[0]) * m->c[1] > (1 << 20)) return false;
+  if (int64_t(m->c[0]) * m->c[1] > (1 << 20) || int64_t(m->a[0]) * m->a[1] > (1 << 20)) return false;
   for (int i = 0; i < 2; ++i)     // (complete factors that list their columns in order: the canonical order carries over)
     for (int u = 0; u < m->a[i]; ++u)
       for (int v = 0; v < m->c[i]; ++v)
@@ -515,11 +519,13 @@ static bool plan_regroup_columns(rbgp_mask *m) {
       t->adj[i] = m->adj[i];
     }
     const int cr = m->c[0] * m->c[1];
-    t->c[0] = 1; t->d[0] = 1; t->e[0] = m->a[0]; t->sigma1[0] = std::sqrt(double(m->a[0])); t->sigma2[0] = 0.0;
-    t->c[1] = cr; t->d[1] = cr; t->e[1] = m->a[1]; t->sigma1[1] = std::sqrt(double(m->a[1]) * cr); t->sigma2[1] = 0.0;
-    t->adj[0].assign(size_t(m->a[0]), 0);
-    t->adj[1].resize(size_t(m->a[1]) * cr);
-    for (int u = 0; u < m->a[1]; ++u)
+    // (the rows merge too: J(a_o, 1) (x) J(a_r, c_o c_r) = J(1, 1) (x) J(a_o a_r, c_o c_r), more rows per column set)
+    const int ar = m->a[0] * m->a[1];
+    t->a[0] = 1; t->c[0] = 1; t->d[0] = 1; t->e[0] = 1; t->sigma1[0] = 1.0; t->sigma2[0] = 0.0;
+    t->a[1] = ar; t->c[1] = cr; t->d[1] = cr; t->e[1] = ar; t->sigma1[1] = std::sqrt(double(ar) * cr); t->sigma2[1] = 0.0;
+    t->adj[0].assign(1, 0);
+    t->adj[1].resize(size_t(ar) * cr);
+    for (int u = 0; u < ar; ++u)
       for (int v = 0; v < cr; ++v) t->adj[1][size_t(u) * cr + v] = v;
     t->M = m->M; t->K = m->K; t->rowdeg = m->rowdeg; t->coldeg = m->coldeg; t->nnz = m->nnz;
     t->kernel_choice = RBGP_KERNEL_MFMA_REG;

@@ -231,7 +231,7 @@ def test_pack_layout_holds_every_kept_value_exactly_once(shape, kernel, dtype):
                                    ((4, 1, 8, 3), (8, 1, 8, 1), (2, 1, 2, 1))], ids=lambda s: "x".join(map(str, s[0])))
 def test_filled_layout_is_the_register_layout_of_the_filled_mask(shape, dtype):
     """RBGP_KERNEL_MFMA_REG_FILLED stores the mask inside the layout of a superset of it: G_o (x) J (x) G_b (G_i filled
-    in) or J (x) G_i (x) G_b with G_o and G_r merged into one tile column (G_o filled in), whichever the library
+    in) or J(1,1) (x) J (x) G_i (x) G_b with G_o and G_r merged into one complete factor (G_o filled in), whichever the library
     estimates cheaper.  Both supersets can be made through the public call with the same seed (every factor is sampled
     from the seed, its position and its own sizes alone), so the register-family layout of one of them, carried over
     position by position through the (row, column) each kept value sits at, must be the filled layout: this mask's
@@ -245,7 +245,8 @@ def test_filled_layout_is_the_register_layout_of_the_filled_mask(shape, dtype):
     index[dense] = np.arange(dense.sum())                        # (row-major over kept positions = ascending columns per row)
     candidates = [((rows[0], rows[1] * rows[2], 1, rows[3]), (cols[0], cols[1] * cols[2], 1, cols[3]),
                    (deg[0], cols[1] * cols[2], 1, cols[3])),
-                  (rows, (1, cols[0] * cols[1], cols[2], cols[3]), (1, cols[0] * cols[1], deg[2], cols[3]))]
+                  ((1, rows[0] * rows[1], rows[2], rows[3]), (1, cols[0] * cols[1], cols[2], cols[3]),
+                   (1, cols[0] * cols[1], deg[2], cols[3]))]
     got, matches = rb.rbgp_pack_layout(mask, dtype), 0
     for frows, fcols, fdeg in candidates:
         full = rb.rbgp_make_mask(frows, fcols, fdeg, 9)
