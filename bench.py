@@ -34,9 +34,12 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 WORKLOADS = {"conv5": wl.VGG19_CONV5, "conv3": wl.VGG19_CONV3_BF16, "wrn": wl.WRN_G1, "tiny": wl.TINY,
              # two of the paper's own 4096^3 products: Table 3's first row (one row per column set, 75 % sparse) and
              # Table 2's (87.5 %, 50 %) cell at 93.75 %
-             "sdmm_r1": wl.sdmm4096_table3(1, 1, 2), "sdmm_o8": wl.sdmm4096_table2(3, 1)}
+             "sdmm_r1": wl.sdmm4096_table3(1, 1, 2), "sdmm_o8": wl.sdmm4096_table2(3, 1),
+             # Table 3's first row at 93.75 % (runs on the mask with G_o filled in) and Table 2's cell with a complete G_o
+             "sdmm_r1_d16": wl.sdmm4096_table3(1, 1, 4), "sdmm_o1": wl.sdmm4096_table2(0, 4)}
 # which roofline bounds each workload (arithmetic intensity vs the fp32 / bf16 ridge)
-BOUND = {"conv5": "mfma", "conv3": "hbm", "wrn": "hbm", "tiny": "hbm", "sdmm_r1": "mfma", "sdmm_o8": "mfma"}
+BOUND = {"conv5": "mfma", "conv3": "hbm", "wrn": "hbm", "tiny": "hbm", "sdmm_r1": "mfma", "sdmm_o8": "mfma",
+         "sdmm_r1_d16": "mfma", "sdmm_o1": "mfma"}
 
 
 def cpu_baseline(w, vals_f32, I_f32, out_gpu):
